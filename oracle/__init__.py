@@ -1,0 +1,153 @@
+"""Float64 CPU oracle for the Conv1D -> RG-LRU path (test infrastructure).
+
+This package wraps ``rglru_oracle.c`` (plain sequential double-precision loops
+written from Sections 2.3-2.4 and Appendix A of the Griffin/Hawk paper) with
+numpy marshalling.  It shares no code with the HIP library and imports nothing
+from it.  Only the test suite, the smoke check and the benchmark's
+``cpu_baseline`` leg may import it; the product path never does.
+
+Every function takes and returns float64 numpy arrays in the layouts given at
+the top of ``rglru_oracle.c``.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rglru_oracle.c")
+_LIB = os.path.join(_HERE, "librglru_oracle.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile the oracle with gcc (-O2, no fast-math, OpenMP for the timing leg)."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
+        return _LIB
+    tmp = _LIB + ".tmp%d" % os.getpid()
+    subprocess.check_call(
+        ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-o", tmp, _SRC, "-lm"])
+    os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.oracle_max_threads.restype = ctypes.c_int
+        _lib.oracle_set_threads(1)  # canonical parity order: one thread
+    return _lib
+
+
+def _p(a):
+    """double* for a C-contiguous float64 array, or NULL for None."""
+    if a is None:
+        return ctypes.c_void_p(0)
+    assert a.dtype == np.float64 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _f64(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.float64)
+
+
+def set_threads(n):
+    """Threads for the (batch, gate-block) loop; 1 is the canonical order."""
+    _load().oracle_set_threads(int(n))
+
+
+def max_threads():
+    return int(_load().oracle_max_threads())
+
+
+def conv1d(u, conv_w, conv_b=None, state_in=None, want_state=False):
+    """Causal separable Conv1D (Section 2.3). u [B,T,D], conv_w [K,D] lag-indexed.
+
+    state_in / returned state: [B,K-1,D] chronological (row 0 oldest).
+    """
+    u, conv_w, conv_b, state_in = _f64(u), _f64(conv_w), _f64(conv_b), _f64(state_in)
+    B, T, D = u.shape
+    K = conv_w.shape[0]
+    assert conv_w.shape == (K, D)
+    x = np.empty((B, T, D))
+    st = np.empty((B, K - 1, D)) if want_state else None
+    _load().oracle_conv1d(B, T, D, K, _p(u), _p(conv_w), _p(conv_b), _p(state_in), _p(x), _p(st))
+    return (x, st) if want_state else x
+
+
+def rglru(x, W_a, W_x, b_a, b_x, Lambda, h0=None, c=8.0, want_gates=False):
+    """RG-LRU eqs. (1)-(4) on convolved input x [B,T,D]; W [nb,bs,bs]. Returns y, hT[, gates]."""
+    x, W_a, W_x, b_a, b_x, Lambda, h0 = map(_f64, (x, W_a, W_x, b_a, b_x, Lambda, h0))
+    B, T, D = x.shape
+    nb, bs, _ = W_a.shape
+    assert nb * bs == D and W_a.shape == W_x.shape == (nb, bs, bs)
+    y = np.empty((B, T, D))
+    hT = np.empty((B, D))
+    g = [np.empty((B, T, D)) for _ in range(4)] if want_gates else [None] * 4
+    _load().oracle_rglru(B, T, D, nb, ctypes.c_double(c), _p(x), _p(W_a), _p(W_x), _p(b_a),
+                         _p(b_x), _p(Lambda), _p(h0), _p(y), _p(hT), *map(_p, g))
+    if T == 0:
+        hT[...] = 0.0 if h0 is None else h0
+    if want_gates:
+        return y, hT, dict(r=g[0], i=g[1], a=g[2], m=g[3])
+    return y, hT
+
+
+def forward(u, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b=None, h0=None, state_in=None, c=8.0):
+    """Conv1D then RG-LRU. Returns y [B,T,D], hT [B,D], state_out [B,K-1,D] (chronological)."""
+    u, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b, h0, state_in = map(
+        _f64, (u, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b, h0, state_in))
+    B, T, D = u.shape
+    nb, bs, _ = W_a.shape
+    K = conv_w.shape[0]
+    assert nb * bs == D
+    y = np.empty((B, T, D))
+    hT = np.empty((B, D))
+    st = np.empty((B, K - 1, D))
+    _load().oracle_forward(B, T, D, nb, K, ctypes.c_double(c), _p(u), _p(W_a), _p(W_x), _p(b_a),
+                           _p(b_x), _p(Lambda), _p(conv_w), _p(conv_b), _p(h0), _p(state_in),
+                           _p(y), _p(hT), _p(st))
+    if T == 0:
+        hT[...] = 0.0 if h0 is None else h0
+    return y, hT, st
+
+
+def decode_step(u_t, W_a, W_x, b_a, b_x, Lambda, conv_w, h, state, conv_b=None, c=8.0):
+    """One token per sequence. u_t [B,D]; h [B,D] and state [B,K-1,D] (chronological) are
+    float64 arrays UPDATED IN PLACE. Returns y_t [B,D]."""
+    u_t, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b = map(
+        _f64, (u_t, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b))
+    assert h.dtype == np.float64 and state.dtype == np.float64
+    B, D = u_t.shape
+    nb, bs, _ = W_a.shape
+    K = conv_w.shape[0]
+    assert state.shape == (B, K - 1, D) and h.shape == (B, D)
+    y = np.empty((B, D))
+    _load().oracle_decode_step(B, D, nb, K, ctypes.c_double(c), _p(u_t), _p(W_a), _p(W_x),
+                               _p(b_a), _p(b_x), _p(Lambda), _p(conv_w), _p(conv_b), _p(h),
+                               _p(state), _p(y))
+    return y
+
+
+def backward(u, W_a, W_x, b_a, b_x, Lambda, conv_w, dy, conv_b=None, h0=None, state_in=None,
+             dhT=None, c=8.0):
+    """Adjoint of ``forward`` for L = sum(dy*y) + sum(dhT*hT). Returns a dict of float64 grads:
+    du, dh0, dW_a, dW_x, db_a, db_x, dLambda, dconv_w, dconv_b."""
+    u, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b, h0, state_in, dy, dhT = map(
+        _f64, (u, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b, h0, state_in, dy, dhT))
+    B, T, D = u.shape
+    nb, bs, _ = W_a.shape
+    K = conv_w.shape[0]
+    out = dict(du=np.empty((B, T, D)), dh0=np.empty((B, D)), dW_a=np.empty((nb, bs, bs)),
+               dW_x=np.empty((nb, bs, bs)), db_a=np.empty(D), db_x=np.empty(D),
+               dLambda=np.empty(D), dconv_w=np.empty((K, D)), dconv_b=np.empty(D))
+    _load().oracle_backward(B, T, D, nb, K, ctypes.c_double(c), _p(u), _p(W_a), _p(W_x), _p(b_a),
+                            _p(b_x), _p(Lambda), _p(conv_w), _p(conv_b), _p(h0), _p(state_in),
+                            _p(dy), _p(dhT), _p(out["du"]), _p(out["dh0"]), _p(out["dW_a"]),
+                            _p(out["dW_x"]), _p(out["db_a"]), _p(out["db_x"]),
+                            _p(out["dLambda"]), _p(out["dconv_w"]), _p(out["dconv_b"]))
+    return out
