@@ -1,0 +1,182 @@
+/*
+ * rglru.h - C ABI of the MI355X (gfx950) library for the hot path of the Griffin/Hawk
+ * recurrent block (arxiv 2402.19427): the width-4 temporal Conv1D (Section 2.3,
+ * "Recurrent block") feeding the RG-LRU layer (Section 2.4, eqs. 1-4; log-space decay of
+ * Appendix A; block-diagonal gate weights of Section 4.1), for whole sequences, for
+ * single-token decode (Section 5, Appendix F "Cache sizes") and for the backward pass.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ * - Every tensor pointer is a DEVICE pointer owned by the caller. The library never
+ *   allocates, frees or keeps them. Struct pointers (rglru_shape, rglru_params,
+ *   rglru_param_grads) are HOST pointers, read during the call only.
+ * - Calls are asynchronous: kernels are enqueued on `stream` (a hipStream_t passed as
+ *   void*, NULL = the default stream) and the function returns without synchronising.
+ * - Scratch memory comes from the caller: `workspace` must hold at least
+ *   rglru_workspace_bytes(shape, op) bytes, 256-byte aligned; the library initialises what
+ *   it needs on `stream`. Two calls that overlap in time must not share a workspace.
+ * - Inputs are read-only. Outputs are overwritten (gradients are NOT accumulated).
+ * - Return value: RGLRU_OK, or a negative RGLRU_ERR_* code; rglru_last_error() then
+ *   describes the failure (thread-local string). Argument validation happens on the host
+ *   before anything is launched, so an error return leaves all outputs untouched.
+ *
+ * Layouts (row-major, last index fastest; "act" = shape.act_dtype, "w" = shape.w_dtype)
+ *   u, y, dy, du, x   [B][T][D]         act
+ *   W_a, W_x          [nb][bs][bs]      w     W[g][j][k]: output channel g*bs+j, input
+ *                                             channel g*bs+k; bs = D/nb (block-diagonal
+ *                                             gate matrices, Section 4.1)
+ *   b_a, b_x, Lambda  [D]               f32
+ *   conv_w            [4][D]            f32   lag-indexed: conv_w[k] multiplies u_{t-k}
+ *   conv_b            [D] or NULL       f32
+ *   h0, hT, h, dh0, dhT [B][D]          f32
+ *   conv state        [B][3][D]         act   ring buffer: the input at absolute position n
+ *                                             lives in slot n mod 3 (mathematical modulo).
+ *                                             A NULL incoming state means zero left-padding.
+ *
+ * What is computed (x_t is the Conv1D output, c = shape.c, sigma = logistic function):
+ *   x_t = sum_{k=0..3} conv_w[k] * u_{t-k} (+ conv_b)                     Section 2.3
+ *   r_t = sigma(W_a x_t + b_a),  i_t = sigma(W_x x_t + b_x)               eqs. (1), (2)
+ *   a_t = sigma(Lambda)^(c r_t)  evaluated as exp(-c softplus(-Lambda) r_t) eq. (3), App. A
+ *   h_t = a_t h_{t-1} + sqrt(1 - a_t^2) (i_t x_t),  y_t = h_t             eq. (4)
+ * (Appendix A prints softplus(+Lambda); that contradicts a = sigma(Lambda) of Section 2.4,
+ * which is what this library follows.)
+ */
+#ifndef RGLRU_H
+#define RGLRU_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes */
+#define RGLRU_OK 0
+#define RGLRU_ERR_INVALID_ARG (-1) /* NULL required pointer, non-positive size, D % nb != 0,   */
+                                   /* negative position, misaligned pointer                    */
+#define RGLRU_ERR_UNSUPPORTED (-2) /* dtype / conv width / block size with no kernel           */
+#define RGLRU_ERR_WORKSPACE (-3)   /* workspace NULL or smaller than rglru_workspace_bytes()   */
+#define RGLRU_ERR_HIP (-4)         /* a HIP runtime call or kernel launch failed               */
+
+/* element types */
+#define RGLRU_F32 0
+#define RGLRU_BF16 1
+
+/* operations, for rglru_workspace_bytes() */
+#define RGLRU_OP_CONV1D 0
+#define RGLRU_OP_FORWARD 1
+#define RGLRU_OP_DECODE 2
+#define RGLRU_OP_BACKWARD 3
+
+typedef struct rglru_shape {
+  int32_t B;          /* sequences                                  (>= 1)                 */
+  int32_t T;          /* time steps per sequence                    (>= 0; ignored by decode) */
+  int32_t D;          /* channels (D_RNN)                           (>= 1)                 */
+  int32_t num_blocks; /* gate blocks nb; D % nb == 0                (ignored by conv1d)    */
+  int32_t conv_width; /* temporal filter width; only 4 is supported                        */
+  float c;            /* exponent scale of eq. (3); the paper uses 8                       */
+  int32_t act_dtype;  /* RGLRU_F32 or RGLRU_BF16: u, y, dy, du, x, conv state              */
+  int32_t w_dtype;    /* RGLRU_F32 or RGLRU_BF16: W_a, W_x. Supported pairs:               */
+                      /* (act f32, w f32) and (act bf16, w bf16)                           */
+} rglru_shape;
+
+typedef struct rglru_params {
+  const void *W_a;     /* [nb][bs][bs] w   recurrence-gate weights, eq. (1) */
+  const void *W_x;     /* [nb][bs][bs] w   input-gate weights, eq. (2)      */
+  const float *b_a;    /* [D]                                               */
+  const float *b_x;    /* [D]                                               */
+  const float *Lambda; /* [D]              a = sigma(Lambda), Section 2.4   */
+  const float *conv_w; /* [4][D]           Section 2.3                      */
+  const float *conv_b; /* [D] or NULL                                       */
+} rglru_params;
+
+typedef struct rglru_param_grads {
+  float *dW_a;     /* [nb][bs][bs] */
+  float *dW_x;     /* [nb][bs][bs] */
+  float *db_a;     /* [D]          */
+  float *db_x;     /* [D]          */
+  float *dLambda;  /* [D]          */
+  float *dconv_w;  /* [4][D]       */
+  float *dconv_b;  /* [D] or NULL (skipped) */
+} rglru_param_grads;
+
+/*
+ * Temporal Conv1D alone (Section 2.3): x[b,t,d] = sum_k conv_w[k,d] u[b,t-k,d] (+ conv_b[d]).
+ *   u              [B][T][D] act, read.
+ *   conv_state_in  ring state holding the inputs at positions pos0-3..pos0-1, or NULL (zeros).
+ *   pos0           absolute position of u[:,0,:] (>= 0); selects the ring slots.
+ *   x_out          [B][T][D] act, written.
+ *   conv_state_out ring state after consuming the T inputs, or NULL (not produced). May alias
+ *                  conv_state_in.
+ * shape.num_blocks is ignored. T == 0 copies the state through and writes nothing else.
+ */
+int rglru_conv1d(const rglru_shape *shape, const void *u, const float *conv_w,
+                 const float *conv_b, const void *conv_state_in, int64_t pos0, void *x_out,
+                 void *conv_state_out, void *stream);
+
+/*
+ * Forward over whole sequences: Conv1D then RG-LRU (Sections 2.3-2.4, eqs. 1-4).
+ *   u              [B][T][D] act, read.
+ *   h0             [B][D] f32 state before the first step, or NULL (zeros).
+ *   conv_state_in / pos0 / conv_state_out  as in rglru_conv1d.
+ *   y              [B][T][D] act, written (y_t = h_t, rounded to act).
+ *   hT             [B][D] f32 state after the last step (unrounded), or NULL. May alias h0.
+ *   workspace      >= rglru_workspace_bytes(shape, RGLRU_OP_FORWARD) bytes.
+ * A sequence may be fed in pieces: passing hT and conv_state_out of one call as h0 and
+ * conv_state_in of the next (with pos0 advanced by T) gives the one-shot result.
+ * T == 0 copies h0 to hT and the conv state through.
+ */
+int rglru_forward(const rglru_shape *shape, const rglru_params *params, const void *u,
+                  const float *h0, const void *conv_state_in, int64_t pos0, void *y, float *hT,
+                  void *conv_state_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * One decode step (Section 5; state sizes of Appendix F): the forward equations for one new
+ * token per sequence, with both states updated in place.
+ *   u_t        [B][D] act, the new input of every sequence.
+ *   h          [B][D] f32, recurrent state: read as h_{t-1}, overwritten with h_t.
+ *   conv_state [B][3][D] act ring: slots (pos-1, pos-2, pos-3) mod 3 are read as lags 1..3,
+ *              then slot pos mod 3 is overwritten with u_t.
+ *   pos        absolute position of the new token (>= 0), one value for the whole batch.
+ *   y_t        [B][D] act, written.
+ * shape.T is ignored. No workspace is needed.
+ */
+int rglru_decode_step(const rglru_shape *shape, const rglru_params *params, const void *u_t,
+                      float *h, void *conv_state, int64_t pos, void *y_t, void *stream);
+
+/*
+ * Backward of rglru_forward for the loss L = sum(dy * y) + sum(dhT * hT): the adjoint of
+ * eqs. (1)-(4) and of the Conv1D (the paper prints no backward; it is the reverse-time scan
+ * delta_t = dy_t + a_{t+1} delta_{t+1} followed by the pointwise, block-diagonal and
+ * convolution adjoints).
+ *   u, h0, conv_state_in, pos0   the forward call's inputs.
+ *   y          [B][T][D] act, the forward call's output (supplies h_{t-1}).
+ *   dy         [B][T][D] act, upstream gradient.
+ *   dhT        [B][D] f32 gradient reaching hT, or NULL (zeros).
+ *   du         [B][T][D] act, written.
+ *   dh0        [B][D] f32, written, or NULL (skipped).
+ *   grads      parameter gradients, f32, summed over B and T, overwritten. Every pointer
+ *              except dconv_b is required. The carried-in conv state receives no gradient.
+ *   workspace  >= rglru_workspace_bytes(shape, RGLRU_OP_BACKWARD) bytes.
+ * T must be >= 1.
+ */
+int rglru_backward(const rglru_shape *shape, const rglru_params *params, const void *u,
+                   const float *h0, const void *conv_state_in, int64_t pos0, const void *y,
+                   const void *dy, const float *dhT, void *du, float *dh0,
+                   const rglru_param_grads *grads, void *workspace, size_t workspace_bytes,
+                   void *stream);
+
+/* Bytes of workspace `op` (RGLRU_OP_*) needs for `shape`; 0 if none or if shape is invalid. */
+size_t rglru_workspace_bytes(const rglru_shape *shape, int op);
+
+/* Description of the last error returned on the calling thread ("" if none). */
+const char *rglru_last_error(void);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int rglru_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RGLRU_H */

@@ -1,0 +1,24 @@
+"""MI355X-native Conv1D -> RG-LRU path of the Griffin/Hawk recurrent block.
+
+The work happens in librglru.so (hand-written HIP for gfx950, C ABI in include/rglru.h);
+`paper_2402_19427_amd.binding` is the thin ctypes layer with the same names, re-exported
+here. The binding is loaded on first use so that `python -m paper_2402_19427_amd.build` can
+run before the library exists; using any entry point without the built library raises
+ImportError (there is no fallback implementation).
+"""
+import importlib
+
+_EXPORTS = (
+    "BF16", "F32", "OK", "ERR_HIP", "ERR_INVALID_ARG", "ERR_UNSUPPORTED", "ERR_WORKSPACE",
+    "OP_BACKWARD", "OP_CONV1D", "OP_DECODE", "OP_FORWARD", "LIB_PATH", "ParamGrads", "Params",
+    "RglruError", "Shape", "make_param_grads", "make_params", "make_shape", "rglru_backward",
+    "rglru_conv1d", "rglru_decode_step", "rglru_forward", "rglru_last_error", "rglru_version",
+    "rglru_workspace_bytes",
+)
+__all__ = list(_EXPORTS)
+
+
+def __getattr__(name):
+    if name in _EXPORTS:
+        return getattr(importlib.import_module(".binding", __name__), name)
+    raise AttributeError(name)

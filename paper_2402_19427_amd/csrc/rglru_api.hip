@@ -1,0 +1,265 @@
+// C ABI of librglru: argument validation on the host, choice of kernel family, launches.
+// Nothing here touches the GPU before validation has passed, so every error path can be
+// exercised on a machine without one.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "rglru_internal.h"
+
+using namespace rglru;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+size_t act_size(const rglru_shape *s) { return s->act_dtype == RGLRU_BF16 ? 2 : 4; }
+
+constexpr int MAX_BLOCK = 2048;  // largest gate block the generic kernels stage in LDS
+
+// Checks everything about `s` that does not involve pointers. need_blocks: the op uses the
+// gate matrices. Returns RGLRU_OK or an error code with the message set.
+int check_shape(const rglru_shape *s, bool need_blocks, bool need_T, int min_T) {
+  if (!s) return fail(RGLRU_ERR_INVALID_ARG, "shape is NULL");
+  if (s->B < 1) return fail(RGLRU_ERR_INVALID_ARG, "B must be >= 1 (got %d)", s->B);
+  if (s->D < 1) return fail(RGLRU_ERR_INVALID_ARG, "D must be >= 1 (got %d)", s->D);
+  if (need_T && s->T < min_T)
+    return fail(RGLRU_ERR_INVALID_ARG, "T must be >= %d (got %d)", min_T, s->T);
+  if (!(s->c > 0.f) || !std::isfinite(s->c))
+    return fail(RGLRU_ERR_INVALID_ARG, "c must be finite and positive");
+  if (s->act_dtype != RGLRU_F32 && s->act_dtype != RGLRU_BF16)
+    return fail(RGLRU_ERR_INVALID_ARG, "unknown act_dtype %d", s->act_dtype);
+  if (s->w_dtype != RGLRU_F32 && s->w_dtype != RGLRU_BF16)
+    return fail(RGLRU_ERR_INVALID_ARG, "unknown w_dtype %d", s->w_dtype);
+  if (need_blocks) {
+    if (s->num_blocks < 1)
+      return fail(RGLRU_ERR_INVALID_ARG, "num_blocks must be >= 1 (got %d)", s->num_blocks);
+    if (s->D % s->num_blocks != 0)
+      return fail(RGLRU_ERR_INVALID_ARG, "D (%d) is not a multiple of num_blocks (%d)", s->D,
+                  s->num_blocks);
+  }
+  if (s->conv_width != 4)
+    return fail(RGLRU_ERR_UNSUPPORTED, "conv_width %d is not supported (only 4)", s->conv_width);
+  if (s->act_dtype != s->w_dtype)
+    return fail(RGLRU_ERR_UNSUPPORTED,
+                "act_dtype %d with w_dtype %d is not supported (use f32/f32 or bf16/bf16)",
+                s->act_dtype, s->w_dtype);
+  if (need_blocks && s->D / s->num_blocks > MAX_BLOCK)
+    return fail(RGLRU_ERR_UNSUPPORTED, "gate block size %d exceeds %d", s->D / s->num_blocks,
+                MAX_BLOCK);
+  if (s->B > 65535) return fail(RGLRU_ERR_UNSUPPORTED, "B %d exceeds 65535", s->B);
+  return RGLRU_OK;
+}
+
+int check_ptr(const void *p, const char *name, size_t align, bool required) {
+  if (!p) return required ? fail(RGLRU_ERR_INVALID_ARG, "%s is NULL", name) : RGLRU_OK;
+  if (!aligned(p, align))
+    return fail(RGLRU_ERR_INVALID_ARG, "%s is not %zu-byte aligned", name, align);
+  return RGLRU_OK;
+}
+
+#define CHECK(expr)               \
+  do {                            \
+    int rc_ = (expr);             \
+    if (rc_ != RGLRU_OK) return rc_; \
+  } while (0)
+
+int check_params(const rglru_shape *s, const rglru_params *p) {
+  if (!p) return fail(RGLRU_ERR_INVALID_ARG, "params is NULL");
+  const size_t ws = s->w_dtype == RGLRU_BF16 ? 2 : 4;
+  CHECK(check_ptr(p->W_a, "params.W_a", ws, true));
+  CHECK(check_ptr(p->W_x, "params.W_x", ws, true));
+  CHECK(check_ptr(p->b_a, "params.b_a", 4, true));
+  CHECK(check_ptr(p->b_x, "params.b_x", 4, true));
+  CHECK(check_ptr(p->Lambda, "params.Lambda", 4, true));
+  CHECK(check_ptr(p->conv_w, "params.conv_w", 4, true));
+  CHECK(check_ptr(p->conv_b, "params.conv_b", 4, false));
+  return RGLRU_OK;
+}
+
+int check_workspace(const void *ws, size_t have, size_t need) {
+  if (need == 0) return RGLRU_OK;
+  if (!ws) return fail(RGLRU_ERR_WORKSPACE, "workspace is NULL but %zu bytes are needed", need);
+  if (have < need)
+    return fail(RGLRU_ERR_WORKSPACE, "workspace has %zu bytes, %zu are needed", have, need);
+  if (!aligned(ws, 256)) return fail(RGLRU_ERR_INVALID_ARG, "workspace is not 256-byte aligned");
+  return RGLRU_OK;
+}
+
+int hip_fail(hipError_t e, const char *what) {
+  return fail(RGLRU_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+void fill_params(Problem &q, const rglru_shape *s, const rglru_params *p) {
+  q.B = s->B; q.T = s->T; q.D = s->D;
+  q.nb = s->num_blocks; q.bs = s->D / s->num_blocks;
+  q.c = s->c;
+  q.W_a = p->W_a; q.W_x = p->W_x;
+  q.b_a = p->b_a; q.b_x = p->b_x; q.Lambda = p->Lambda;
+  q.conv_w = p->conv_w; q.conv_b = p->conv_b;
+}
+
+size_t workspace_need(const rglru_shape *s, int op) {
+  switch (op) {
+    case RGLRU_OP_BACKWARD:
+      return backward_generic_ws_bytes(s->B, s->T, s->D, s->num_blocks);
+    default:
+      return 0;
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *rglru_last_error(void) { return g_err; }
+
+int rglru_version(void) { return 100; }
+
+size_t rglru_workspace_bytes(const rglru_shape *shape, int op) {
+  if (op < RGLRU_OP_CONV1D || op > RGLRU_OP_BACKWARD) return 0;
+  char keep[sizeof(g_err)];
+  memcpy(keep, g_err, sizeof(g_err));
+  const bool blocks = op != RGLRU_OP_CONV1D;
+  const int rc = check_shape(shape, blocks, op != RGLRU_OP_DECODE, op == RGLRU_OP_BACKWARD ? 1 : 0);
+  memcpy(g_err, keep, sizeof(g_err));  // a size query does not disturb the error string
+  if (rc != RGLRU_OK) return 0;
+  return workspace_need(shape, op);
+}
+
+int rglru_conv1d(const rglru_shape *shape, const void *u, const float *conv_w,
+                 const float *conv_b, const void *conv_state_in, int64_t pos0, void *x_out,
+                 void *conv_state_out, void *stream) {
+  CHECK(check_shape(shape, false, true, 0));
+  const size_t as = act_size(shape);
+  if (pos0 < 0) return fail(RGLRU_ERR_INVALID_ARG, "pos0 must be >= 0");
+  CHECK(check_ptr(u, "u", as, shape->T > 0));
+  CHECK(check_ptr(x_out, "x_out", as, shape->T > 0));
+  CHECK(check_ptr(conv_w, "conv_w", 4, true));
+  CHECK(check_ptr(conv_b, "conv_b", 4, false));
+  CHECK(check_ptr(conv_state_in, "conv_state_in", as, false));
+  CHECK(check_ptr(conv_state_out, "conv_state_out", as, false));
+
+  Problem q;
+  memset(&q, 0, sizeof(q));
+  q.B = shape->B; q.T = shape->T; q.D = shape->D; q.nb = 1; q.bs = shape->D;
+  q.c = shape->c; q.pos0 = pos0;
+  q.u = u; q.conv_w = conv_w; q.conv_b = conv_b;
+  q.state_in = conv_state_in; q.state_out = conv_state_out;
+  const bool bf = shape->act_dtype == RGLRU_BF16;
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t e = launch_conv1d_generic(q, bf, x_out, s);
+  if (e != hipSuccess) return hip_fail(e, "conv1d launch");
+  e = launch_state_update(q, bf, s);
+  if (e != hipSuccess) return hip_fail(e, "conv state launch");
+  g_err[0] = 0;
+  return RGLRU_OK;
+}
+
+int rglru_forward(const rglru_shape *shape, const rglru_params *params, const void *u,
+                  const float *h0, const void *conv_state_in, int64_t pos0, void *y, float *hT,
+                  void *conv_state_out, void *workspace, size_t workspace_bytes, void *stream) {
+  CHECK(check_shape(shape, true, true, 0));
+  CHECK(check_params(shape, params));
+  const size_t as = act_size(shape);
+  if (pos0 < 0) return fail(RGLRU_ERR_INVALID_ARG, "pos0 must be >= 0");
+  CHECK(check_ptr(u, "u", as, shape->T > 0));
+  CHECK(check_ptr(y, "y", as, shape->T > 0));
+  CHECK(check_ptr(h0, "h0", 4, false));
+  CHECK(check_ptr(hT, "hT", 4, false));
+  CHECK(check_ptr(conv_state_in, "conv_state_in", as, false));
+  CHECK(check_ptr(conv_state_out, "conv_state_out", as, false));
+  CHECK(check_workspace(workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_FORWARD)));
+
+  Problem q;
+  memset(&q, 0, sizeof(q));
+  fill_params(q, shape, params);
+  q.pos0 = pos0; q.u = u; q.h0 = h0; q.state_in = conv_state_in;
+  q.y = y; q.hT = hT; q.state_out = conv_state_out;
+  q.ws = workspace; q.ws_bytes = workspace_bytes;
+  const bool bf = shape->act_dtype == RGLRU_BF16;
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t e = launch_forward_generic(q, bf, s);
+  if (e != hipSuccess) return hip_fail(e, "forward launch");
+  // the new ring state is written after the last read of the incoming one (they may alias)
+  e = launch_state_update(q, bf, s);
+  if (e != hipSuccess) return hip_fail(e, "conv state launch");
+  g_err[0] = 0;
+  return RGLRU_OK;
+}
+
+int rglru_decode_step(const rglru_shape *shape, const rglru_params *params, const void *u_t,
+                      float *h, void *conv_state, int64_t pos, void *y_t, void *stream) {
+  CHECK(check_shape(shape, true, false, 0));
+  CHECK(check_params(shape, params));
+  const size_t as = act_size(shape);
+  if (pos < 0) return fail(RGLRU_ERR_INVALID_ARG, "pos must be >= 0");
+  CHECK(check_ptr(u_t, "u_t", as, true));
+  CHECK(check_ptr(h, "h", 4, true));
+  CHECK(check_ptr(conv_state, "conv_state", as, true));
+  CHECK(check_ptr(y_t, "y_t", as, true));
+
+  Problem q;
+  memset(&q, 0, sizeof(q));
+  fill_params(q, shape, params);
+  q.T = 1; q.pos0 = pos; q.u = u_t; q.hT = h; q.state_in = conv_state;
+  q.state_out = conv_state; q.y = y_t;
+  const bool bf = shape->act_dtype == RGLRU_BF16;
+  hipError_t e = launch_decode_generic(q, bf, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "decode launch");
+  g_err[0] = 0;
+  return RGLRU_OK;
+}
+
+int rglru_backward(const rglru_shape *shape, const rglru_params *params, const void *u,
+                   const float *h0, const void *conv_state_in, int64_t pos0, const void *y,
+                   const void *dy, const float *dhT, void *du, float *dh0,
+                   const rglru_param_grads *grads, void *workspace, size_t workspace_bytes,
+                   void *stream) {
+  CHECK(check_shape(shape, true, true, 1));
+  CHECK(check_params(shape, params));
+  const size_t as = act_size(shape);
+  if (pos0 < 0) return fail(RGLRU_ERR_INVALID_ARG, "pos0 must be >= 0");
+  CHECK(check_ptr(u, "u", as, true));
+  CHECK(check_ptr(y, "y", as, true));
+  CHECK(check_ptr(dy, "dy", as, true));
+  CHECK(check_ptr(du, "du", as, true));
+  CHECK(check_ptr(h0, "h0", 4, false));
+  CHECK(check_ptr(dhT, "dhT", 4, false));
+  CHECK(check_ptr(dh0, "dh0", 4, false));
+  CHECK(check_ptr(conv_state_in, "conv_state_in", as, false));
+  if (!grads) return fail(RGLRU_ERR_INVALID_ARG, "grads is NULL");
+  CHECK(check_ptr(grads->dW_a, "grads.dW_a", 4, true));
+  CHECK(check_ptr(grads->dW_x, "grads.dW_x", 4, true));
+  CHECK(check_ptr(grads->db_a, "grads.db_a", 4, true));
+  CHECK(check_ptr(grads->db_x, "grads.db_x", 4, true));
+  CHECK(check_ptr(grads->dLambda, "grads.dLambda", 4, true));
+  CHECK(check_ptr(grads->dconv_w, "grads.dconv_w", 4, true));
+  CHECK(check_ptr(grads->dconv_b, "grads.dconv_b", 4, false));
+  CHECK(check_workspace(workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_BACKWARD)));
+
+  Problem q;
+  memset(&q, 0, sizeof(q));
+  fill_params(q, shape, params);
+  q.pos0 = pos0; q.u = u; q.h0 = h0; q.state_in = conv_state_in;
+  q.y_in = y; q.dy = dy; q.dhT = dhT; q.du = du; q.dh0 = dh0; q.g = *grads;
+  q.ws = workspace; q.ws_bytes = workspace_bytes;
+  const bool bf = shape->act_dtype == RGLRU_BF16;
+  hipError_t e = launch_backward_generic(q, bf, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "backward launch");
+  g_err[0] = 0;
+  return RGLRU_OK;
+}
+
+}  // extern "C"

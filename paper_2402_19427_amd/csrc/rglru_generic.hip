@@ -1,0 +1,537 @@
+// Shape-generic kernels for the Conv1D -> RG-LRU path: any block size, fp32 or bf16 storage,
+// fp32 arithmetic with accurate math (expf / expm1f / log1pf). They serve the fp32 contract
+// (relative error 1e-5) and every shape the MFMA kernels do not cover.
+//
+// Equations: Conv1D - Section 2.3 of the Griffin/Hawk paper; gates, decay, recurrence -
+// Section 2.4 eqs. (1)-(4); log-space decay - Appendix A (with the sign that matches
+// a = sigmoid(Lambda)); decode state - Appendix F.
+#include "rglru_internal.h"
+
+namespace rglru {
+
+constexpr int GT = 8;        // rows (time steps or sequences) per tile
+constexpr int NTHREADS = 256;
+
+// largest dynamic LDS any generic kernel asks for: two [GT][bs] tiles (dgrad)
+size_t generic_lds_bytes(int bs) { return (size_t)(2 * GT) * bs * sizeof(float); }
+
+// ------------------------------------------------------------------ shared device code
+__device__ __forceinline__ float softplus_f(float z) {
+  return z > 0.f ? z + log1pf(expf(-z)) : log1pf(expf(z));
+}
+__device__ __forceinline__ float sigmoid_f(float z) { return 1.f / (1.f + expf(-z)); }
+
+struct Gates {
+  float r, i, a, m;
+};
+// eqs. (1)-(3): neg_cs = -c * softplus(-Lambda) = c * log sigmoid(Lambda)
+__device__ __forceinline__ Gates gate_math(float p, float q, float neg_cs) {
+  Gates g;
+  g.r = sigmoid_f(p);
+  g.i = sigmoid_f(q);
+  const float la = neg_cs * g.r;
+  g.a = expf(la);
+  g.m = sqrtf(-expm1f(2.f * la));  // sqrt(1 - a^2) without cancellation
+  return g;
+}
+
+// input of sequence b at time t (t may be negative: carried state, else zero padding)
+template <typename AT>
+__device__ __forceinline__ float input_at(const Problem &p, int b, int t, int d) {
+  if (t >= 0) return ldf((const AT *)p.u, ((size_t)b * p.T + t) * p.D + d);
+  if (!p.state_in) return 0.f;
+  return ldf((const AT *)p.state_in, ((size_t)b * 3 + ring_slot(p.pos0 + t)) * p.D + d);
+}
+
+// Conv1D output x[b,t,d] (Section 2.3), lag-indexed taps
+template <typename AT>
+__device__ __forceinline__ float conv_at(const Problem &p, int b, int t, int d) {
+  float acc = p.conv_b ? p.conv_b[d] : 0.f;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) acc = fmaf(p.conv_w[(size_t)k * p.D + d], input_at<AT>(p, b, t - k, d), acc);
+  return acc;
+}
+
+// p[tt], q[tt] = b + W[g][j][:] . xs[tt][:] for the GT rows of an LDS tile xs[GT][bs]
+template <typename AT>
+__device__ __forceinline__ void gate_rows(const Problem &p, int g, int j, const float *xs,
+                                          float *pa, float *qa) {
+  const int bs = p.bs, d = g * bs + j;
+  const AT *wa = (const AT *)p.W_a + ((size_t)g * bs + j) * bs;
+  const AT *wx = (const AT *)p.W_x + ((size_t)g * bs + j) * bs;
+#pragma unroll
+  for (int tt = 0; tt < GT; ++tt) {
+    pa[tt] = p.b_a[d];
+    qa[tt] = p.b_x[d];
+  }
+  for (int k = 0; k < bs; ++k) {
+    const float a = ldf(wa, k), x = ldf(wx, k);
+#pragma unroll
+    for (int tt = 0; tt < GT; ++tt) {
+      const float v = xs[tt * bs + k];
+      pa[tt] = fmaf(a, v, pa[tt]);
+      qa[tt] = fmaf(x, v, qa[tt]);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------ Conv1D alone
+template <typename AT>
+__global__ void __launch_bounds__(NTHREADS) conv1d_kernel(Problem p, AT *x_out) {
+  const size_t n = (size_t)p.B * p.T * p.D;
+  for (size_t idx = (size_t)blockIdx.x * NTHREADS + threadIdx.x; idx < n;
+       idx += (size_t)gridDim.x * NTHREADS) {
+    const int d = (int)(idx % p.D);
+    const size_t bt = idx / p.D;
+    const int t = (int)(bt % p.T), b = (int)(bt / p.T);
+    stf(x_out, idx, conv_at<AT>(p, b, t, d));
+  }
+}
+
+// Ring state after the T inputs: slots of the new inputs are overwritten, the others are
+// carried from state_in (or zero). One thread per (b, slot, d).
+template <typename AT>
+__global__ void __launch_bounds__(NTHREADS) state_update_kernel(Problem p) {
+  const size_t n = (size_t)p.B * 3 * p.D;
+  for (size_t idx = (size_t)blockIdx.x * NTHREADS + threadIdx.x; idx < n;
+       idx += (size_t)gridDim.x * NTHREADS) {
+    const int d = (int)(idx % p.D);
+    const int slot = (int)((idx / p.D) % 3), b = (int)(idx / ((size_t)3 * p.D));
+    // newest position that maps to this slot among pos0+T-3 .. pos0+T-1
+    const long long end = p.pos0 + p.T;
+    long long npos = end - 1 - ring_slot(end - 1 - slot);
+    float v;
+    if (npos >= p.pos0)
+      v = ldf((const AT *)p.u, ((size_t)b * p.T + (size_t)(npos - p.pos0)) * p.D + d);
+    else
+      v = p.state_in ? ldf((const AT *)p.state_in, idx) : 0.f;
+    stf((AT *)p.state_out, idx, v);
+  }
+}
+
+// --------------------------------------------------------------------------- forward
+// One workgroup per (gate block, sequence), walking the sequence in tiles of GT steps:
+// Conv1D into LDS, gate dot products per output channel, then the recurrence with the state
+// kept per channel in LDS.
+template <typename AT>
+__global__ void __launch_bounds__(NTHREADS) forward_kernel(Problem p) {
+  extern __shared__ float smem[];
+  const int g = blockIdx.x, b = blockIdx.y, bs = p.bs, tid = threadIdx.x;
+  float *xs = smem, *hc = smem + GT * bs;
+  for (int j = tid; j < bs; j += NTHREADS)
+    hc[j] = p.h0 ? p.h0[(size_t)b * p.D + g * bs + j] : 0.f;
+  for (int t0 = 0; t0 < p.T; t0 += GT) {
+    const int nt = min(GT, p.T - t0);
+    __syncthreads();
+    for (int idx = tid; idx < GT * bs; idx += NTHREADS) {
+      const int tt = idx / bs, j = idx - tt * bs;
+      xs[idx] = tt < nt ? conv_at<AT>(p, b, t0 + tt, g * bs + j) : 0.f;
+    }
+    __syncthreads();
+    for (int j = tid; j < bs; j += NTHREADS) {
+      const int d = g * bs + j;
+      float pa[GT], qa[GT];
+      gate_rows<AT>(p, g, j, xs, pa, qa);
+      const float neg_cs = -p.c * softplus_f(-p.Lambda[d]);
+      float h = hc[j];
+#pragma unroll
+      for (int tt = 0; tt < GT; ++tt) {
+        if (tt < nt) {
+          const Gates gt = gate_math(pa[tt], qa[tt], neg_cs);
+          h = fmaf(gt.a, h, gt.m * (gt.i * xs[tt * bs + j]));  // eq. (4)
+          stf((AT *)p.y, ((size_t)b * p.T + t0 + tt) * p.D + d, h);
+        }
+      }
+      hc[j] = h;
+    }
+  }
+  __syncthreads();
+  if (p.hT)
+    for (int j = tid; j < bs; j += NTHREADS) p.hT[(size_t)b * p.D + g * bs + j] = hc[j];
+}
+
+// ---------------------------------------------------------------------------- decode
+// One workgroup per (gate block, tile of GT sequences); T == 1, states updated in place.
+// The ring slot of the new token is written by the workgroup that owns the channels, after
+// all of its reads of the state.
+template <typename AT>
+__global__ void __launch_bounds__(NTHREADS) decode_kernel(Problem p) {
+  extern __shared__ float smem[];
+  const int g = blockIdx.x, b0 = blockIdx.y * GT, bs = p.bs, tid = threadIdx.x;
+  const int nbat = min(GT, p.B - b0);
+  float *xs = smem;
+  AT *state = (AT *)p.state_out;  // in-place ring
+  for (int idx = tid; idx < GT * bs; idx += NTHREADS) {
+    const int tt = idx / bs, j = idx - tt * bs, d = g * bs + j;
+    float acc = 0.f;
+    if (tt < nbat) {
+      const int b = b0 + tt;
+      acc = p.conv_b ? p.conv_b[d] : 0.f;
+      acc = fmaf(p.conv_w[d], ldf((const AT *)p.u, (size_t)b * p.D + d), acc);
+#pragma unroll
+      for (int k = 1; k < 4; ++k)
+        acc = fmaf(p.conv_w[(size_t)k * p.D + d],
+                   ldf(state, ((size_t)b * 3 + ring_slot(p.pos0 - k)) * p.D + d), acc);
+    }
+    xs[idx] = acc;
+  }
+  __syncthreads();
+  const int wslot = ring_slot(p.pos0);
+  for (int j = tid; j < bs; j += NTHREADS) {
+    const int d = g * bs + j;
+    float pa[GT], qa[GT];
+    gate_rows<AT>(p, g, j, xs, pa, qa);
+    const float neg_cs = -p.c * softplus_f(-p.Lambda[d]);
+#pragma unroll
+    for (int tt = 0; tt < GT; ++tt) {
+      if (tt < nbat) {
+        const size_t o = (size_t)(b0 + tt) * p.D + d;
+        const Gates gt = gate_math(pa[tt], qa[tt], neg_cs);
+        const float h = fmaf(gt.a, p.hT[o], gt.m * (gt.i * xs[tt * bs + j]));
+        p.hT[o] = h;
+        stf((AT *)p.y, o, h);
+        state[((size_t)(b0 + tt) * 3 + wslot) * p.D + d] = ((const AT *)p.u)[o];
+      }
+    }
+  }
+}
+
+// --------------------------------------------------------------------------- backward
+// Workspace layout (floats): x[N] dp[N] dq[N] dx[N] | partA[B][3][D] | partC[nchunk][5][D]
+struct BwdWs {
+  float *x, *dp, *dq, *dx, *partA, *partC;
+  int tchunk, nchunk;
+};
+constexpr int CONV_TCHUNK = 256;
+
+static size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+static BwdWs carve_bwd_ws(void *ws, int B, int T, int D) {
+  BwdWs w;
+  const size_t N = (size_t)B * T * D;
+  char *base = (char *)ws;
+  size_t off = 0;
+  w.x = (float *)(base + off); off += align256(N * 4);
+  w.dp = (float *)(base + off); off += align256(N * 4);
+  w.dq = (float *)(base + off); off += align256(N * 4);
+  w.dx = (float *)(base + off); off += align256(N * 4);
+  w.partA = (float *)(base + off); off += align256((size_t)B * 3 * D * 4);
+  w.tchunk = CONV_TCHUNK;
+  w.nchunk = B * ((T + CONV_TCHUNK - 1) / CONV_TCHUNK);
+  w.partC = (float *)(base + off);
+  return w;
+}
+
+size_t backward_generic_ws_bytes(int B, int T, int D, int nb) {
+  (void)nb;
+  const size_t N = (size_t)B * T * D;
+  const size_t nchunk = (size_t)B * ((T + CONV_TCHUNK - 1) / CONV_TCHUNK);
+  return 4 * align256(N * 4) + align256((size_t)B * 3 * D * 4) + align256(nchunk * 5 * D * 4);
+}
+
+// Pass 1: one workgroup per (gate block, sequence), walking the sequence backwards in tiles:
+// recompute x and the gates, run delta_t = dy_t + a_{t+1} delta_{t+1}, form the pointwise
+// adjoints, and store x, dp, dq and the direct part of dx for the later contractions.
+template <typename AT>
+__global__ void __launch_bounds__(NTHREADS) bwd_pointwise_kernel(Problem p, BwdWs w) {
+  extern __shared__ float smem[];
+  const int g = blockIdx.x, b = blockIdx.y, bs = p.bs, tid = threadIdx.x;
+  float *xs = smem;                 // [GT][bs]
+  float *carry = smem + GT * bs;    // [bs]  a_{t+1} * delta_{t+1}
+  float *sums = carry + bs;         // [3][bs] running db_a, db_x, dLambda of this sequence
+  for (int j = tid; j < bs; j += NTHREADS) {
+    carry[j] = p.dhT ? p.dhT[(size_t)b * p.D + g * bs + j] : 0.f;
+    sums[j] = sums[bs + j] = sums[2 * bs + j] = 0.f;
+  }
+  const int ntile = (p.T + GT - 1) / GT;
+  for (int tile = ntile - 1; tile >= 0; --tile) {
+    const int t0 = tile * GT, nt = min(GT, p.T - t0);
+    __syncthreads();
+    for (int idx = tid; idx < GT * bs; idx += NTHREADS) {
+      const int tt = idx / bs, j = idx - tt * bs;
+      xs[idx] = tt < nt ? conv_at<AT>(p, b, t0 + tt, g * bs + j) : 0.f;
+    }
+    __syncthreads();
+    for (int j = tid; j < bs; j += NTHREADS) {
+      const int d = g * bs + j;
+      float pa[GT], qa[GT];
+      gate_rows<AT>(p, g, j, xs, pa, qa);
+      const float neg_cs = -p.c * softplus_f(-p.Lambda[d]);
+      const float lam_scale = p.c * (1.f - sigmoid_f(p.Lambda[d]));
+      float cy = carry[j], s_ba = 0.f, s_bx = 0.f, s_lam = 0.f;
+#pragma unroll
+      for (int tt = GT - 1; tt >= 0; --tt) {
+        if (tt < nt) {
+          const int t = t0 + tt;
+          const size_t o = ((size_t)b * p.T + t) * p.D + d;
+          const Gates gt = gate_math(pa[tt], qa[tt], neg_cs);
+          const float x = xs[tt * bs + j];
+          const float delta = ldf((const AT *)p.dy, o) + cy;
+          const float hprev = t > 0 ? ldf((const AT *)p.y_in, o - p.D)
+                                    : (p.h0 ? p.h0[(size_t)b * p.D + d] : 0.f);
+          const float gin = gt.i * x;
+          // d m / d a = -a / m; the term vanishes with the gate in the limit m -> 0
+          const float corr = gt.m > 0.f ? gt.a * gin / gt.m : 0.f;
+          const float dla = delta * gt.a * (hprev - corr);
+          const float dg = delta * gt.m;
+          const float di = dg * x;
+          const float dr = neg_cs * dla;
+          const float dpv = dr * gt.r * (1.f - gt.r);
+          const float dqv = di * gt.i * (1.f - gt.i);
+          s_lam = fmaf(dla * gt.r, lam_scale, s_lam);
+          s_ba += dpv;
+          s_bx += dqv;
+          w.x[o] = x;
+          w.dp[o] = dpv;
+          w.dq[o] = dqv;
+          w.dx[o] = dg * gt.i;
+          cy = gt.a * delta;
+        }
+      }
+      carry[j] = cy;
+      sums[j] += s_ba;
+      sums[bs + j] += s_bx;
+      sums[2 * bs + j] += s_lam;
+    }
+  }
+  __syncthreads();
+  for (int j = tid; j < bs; j += NTHREADS) {
+    const int d = g * bs + j;
+    if (p.dh0) p.dh0[(size_t)b * p.D + d] = carry[j];
+    w.partA[((size_t)b * 3 + 0) * p.D + d] = sums[j];
+    w.partA[((size_t)b * 3 + 1) * p.D + d] = sums[bs + j];
+    w.partA[((size_t)b * 3 + 2) * p.D + d] = sums[2 * bs + j];
+  }
+}
+
+// Pass 2: dx[t][k] += sum_j W_a[g][j][k] dp[t][j] + W_x[g][j][k] dq[t][j]
+template <typename AT>
+__global__ void __launch_bounds__(NTHREADS) bwd_dgrad_kernel(Problem p, BwdWs w) {
+  extern __shared__ float smem[];
+  const int g = blockIdx.x, b = blockIdx.y, t0 = blockIdx.z * GT, bs = p.bs, tid = threadIdx.x;
+  const int nt = min(GT, p.T - t0);
+  float *dps = smem, *dqs = smem + GT * bs;  // [GT][bs] each
+  for (int idx = tid; idx < GT * bs; idx += NTHREADS) {
+    const int tt = idx / bs, j = idx - tt * bs;
+    const size_t o = ((size_t)b * p.T + t0 + tt) * p.D + g * bs + j;
+    dps[idx] = tt < nt ? w.dp[o] : 0.f;
+    dqs[idx] = tt < nt ? w.dq[o] : 0.f;
+  }
+  __syncthreads();
+  const AT *Wa = (const AT *)p.W_a + (size_t)g * bs * bs;
+  const AT *Wx = (const AT *)p.W_x + (size_t)g * bs * bs;
+  for (int k = tid; k < bs; k += NTHREADS) {
+    float acc[GT];
+#pragma unroll
+    for (int tt = 0; tt < GT; ++tt)
+      acc[tt] = tt < nt ? w.dx[((size_t)b * p.T + t0 + tt) * p.D + g * bs + k] : 0.f;
+    for (int j = 0; j < bs; ++j) {
+      const float wa = ldf(Wa, (size_t)j * bs + k), wx = ldf(Wx, (size_t)j * bs + k);
+#pragma unroll
+      for (int tt = 0; tt < GT; ++tt)
+        acc[tt] = fmaf(wa, dps[tt * bs + j], fmaf(wx, dqs[tt * bs + j], acc[tt]));
+    }
+#pragma unroll
+    for (int tt = 0; tt < GT; ++tt)
+      if (tt < nt) w.dx[((size_t)b * p.T + t0 + tt) * p.D + g * bs + k] = acc[tt];
+  }
+}
+
+// Pass 3a: du[b,t,d] = sum_k conv_w[k][d] dx[b,t+k,d]
+template <typename AT>
+__global__ void __launch_bounds__(NTHREADS) bwd_conv_input_kernel(Problem p, BwdWs w) {
+  const size_t n = (size_t)p.B * p.T * p.D;
+  for (size_t idx = (size_t)blockIdx.x * NTHREADS + threadIdx.x; idx < n;
+       idx += (size_t)gridDim.x * NTHREADS) {
+    const int d = (int)(idx % p.D);
+    const int t = (int)((idx / p.D) % p.T);
+    float acc = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (t + k < p.T) acc = fmaf(p.conv_w[(size_t)k * p.D + d], w.dx[idx + (size_t)k * p.D], acc);
+    stf((AT *)p.du, idx, acc);
+  }
+}
+
+// Pass 3b: per (sequence, time chunk) partial sums of dconv_w[k][d] = sum dx_t u_{t-k} and
+// dconv_b[d] = sum dx_t
+template <typename AT>
+__global__ void __launch_bounds__(NTHREADS) bwd_conv_weight_kernel(Problem p, BwdWs w) {
+  const int d = blockIdx.x * NTHREADS + threadIdx.x;
+  if (d >= p.D) return;
+  const int nct = (p.T + w.tchunk - 1) / w.tchunk;
+  const int b = blockIdx.y / nct, c = blockIdx.y % nct;
+  const int t0 = c * w.tchunk, t1 = min(p.T, t0 + w.tchunk);
+  float s[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+  float u1 = input_at<AT>(p, b, t0 - 1, d), u2 = input_at<AT>(p, b, t0 - 2, d),
+        u3 = input_at<AT>(p, b, t0 - 3, d);
+  for (int t = t0; t < t1; ++t) {
+    const size_t o = ((size_t)b * p.T + t) * p.D + d;
+    const float dx = w.dx[o], u0 = ldf((const AT *)p.u, o);
+    s[0] = fmaf(dx, u0, s[0]);
+    s[1] = fmaf(dx, u1, s[1]);
+    s[2] = fmaf(dx, u2, s[2]);
+    s[3] = fmaf(dx, u3, s[3]);
+    s[4] += dx;
+    u3 = u2; u2 = u1; u1 = u0;
+  }
+#pragma unroll
+  for (int k = 0; k < 5; ++k) w.partC[((size_t)blockIdx.y * 5 + k) * p.D + d] = s[k];
+}
+
+// out.p[r][d] = sum_q part[q][r][d] for r < rows, in a fixed order (deterministic)
+struct RowOuts {
+  float *p[5];
+};
+__global__ void __launch_bounds__(NTHREADS) reduce_parts_kernel(const float *part, int nparts,
+                                                                int rows, int D, RowOuts out) {
+  const int d = blockIdx.x * NTHREADS + threadIdx.x, r = blockIdx.y;
+  if (d >= D || !out.p[r]) return;
+  float s = 0.f;
+  for (int q = 0; q < nparts; ++q) s += part[((size_t)q * rows + r) * D + d];
+  out.p[r][d] = s;
+}
+
+// Pass 4: dW_a[g][j][k] = sum_{b,t} dp[b,t,j] x[b,t,k], dW_x likewise with dq. One workgroup
+// per 32x32 output tile of one block, 16x16 threads with 2x2 outputs each, rows streamed
+// through LDS 32 at a time.
+__global__ void __launch_bounds__(NTHREADS) bwd_wgrad_kernel(Problem p, BwdWs w) {
+  __shared__ float xs[32][33], ps[32][33], qs[32][33];
+  const int g = blockIdx.x, j0 = blockIdx.y * 32, k0 = blockIdx.z * 32, bs = p.bs;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  float aa[2][2] = {{0.f, 0.f}, {0.f, 0.f}}, ax[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
+  const size_t rows = (size_t)p.B * p.T;
+  for (size_t r0 = 0; r0 < rows; r0 += 32) {
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < 32 * 32; idx += NTHREADS) {
+      const int rr = idx >> 5, cc = idx & 31;
+      const size_t row = r0 + rr;
+      const bool okr = row < rows;
+      const size_t base = row * p.D + (size_t)g * bs;
+      xs[rr][cc] = (okr && k0 + cc < bs) ? w.x[base + k0 + cc] : 0.f;
+      ps[rr][cc] = (okr && j0 + cc < bs) ? w.dp[base + j0 + cc] : 0.f;
+      qs[rr][cc] = (okr && j0 + cc < bs) ? w.dq[base + j0 + cc] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll 8
+    for (int rr = 0; rr < 32; ++rr) {
+      const float x0 = xs[rr][tx], x1 = xs[rr][tx + 16];
+      const float p0 = ps[rr][ty], p1 = ps[rr][ty + 16];
+      const float q0 = qs[rr][ty], q1 = qs[rr][ty + 16];
+      aa[0][0] = fmaf(p0, x0, aa[0][0]); aa[0][1] = fmaf(p0, x1, aa[0][1]);
+      aa[1][0] = fmaf(p1, x0, aa[1][0]); aa[1][1] = fmaf(p1, x1, aa[1][1]);
+      ax[0][0] = fmaf(q0, x0, ax[0][0]); ax[0][1] = fmaf(q0, x1, ax[0][1]);
+      ax[1][0] = fmaf(q1, x0, ax[1][0]); ax[1][1] = fmaf(q1, x1, ax[1][1]);
+    }
+  }
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      const int j = j0 + ty + 16 * a, k = k0 + tx + 16 * c;
+      if (j < bs && k < bs) {
+        p.g.dW_a[((size_t)g * bs + j) * bs + k] = aa[a][c];
+        p.g.dW_x[((size_t)g * bs + j) * bs + k] = ax[a][c];
+      }
+    }
+}
+
+// ------------------------------------------------------------------------- launchers
+static int grid_1d(size_t n) {
+  size_t blocks = (n + NTHREADS - 1) / NTHREADS;
+  return (int)(blocks < 1 ? 1 : (blocks > 65536 ? 65536 : blocks));
+}
+
+template <typename K>
+static hipError_t allow_lds(K kernel, size_t bytes) {
+  if (bytes <= 48 * 1024) return hipSuccess;
+  return hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)bytes);
+}
+
+hipError_t launch_conv1d_generic(const Problem &p, bool bf, void *x_out, hipStream_t s) {
+  const size_t n = (size_t)p.B * p.T * p.D;
+  if (n == 0) return hipSuccess;
+  if (bf)
+    hipLaunchKernelGGL(conv1d_kernel<bf16>, dim3(grid_1d(n)), dim3(NTHREADS), 0, s, p, (bf16 *)x_out);
+  else
+    hipLaunchKernelGGL(conv1d_kernel<float>, dim3(grid_1d(n)), dim3(NTHREADS), 0, s, p, (float *)x_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_state_update(const Problem &p, bool bf, hipStream_t s) {
+  if (!p.state_out) return hipSuccess;
+  const size_t n = (size_t)p.B * 3 * p.D;
+  if (bf)
+    hipLaunchKernelGGL(state_update_kernel<bf16>, dim3(grid_1d(n)), dim3(NTHREADS), 0, s, p);
+  else
+    hipLaunchKernelGGL(state_update_kernel<float>, dim3(grid_1d(n)), dim3(NTHREADS), 0, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_forward_generic(const Problem &p, bool bf, hipStream_t s) {
+  const size_t lds = generic_lds_bytes(p.bs);
+  hipError_t e = bf ? allow_lds(forward_kernel<bf16>, lds) : allow_lds(forward_kernel<float>, lds);
+  if (e != hipSuccess) return e;
+  const dim3 grid(p.nb, p.B);
+  if (bf)
+    hipLaunchKernelGGL(forward_kernel<bf16>, grid, dim3(NTHREADS), lds, s, p);
+  else
+    hipLaunchKernelGGL(forward_kernel<float>, grid, dim3(NTHREADS), lds, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_generic(const Problem &p, bool bf, hipStream_t s) {
+  const size_t lds = generic_lds_bytes(p.bs);
+  hipError_t e = bf ? allow_lds(decode_kernel<bf16>, lds) : allow_lds(decode_kernel<float>, lds);
+  if (e != hipSuccess) return e;
+  const dim3 grid(p.nb, (p.B + GT - 1) / GT);
+  if (bf)
+    hipLaunchKernelGGL(decode_kernel<bf16>, grid, dim3(NTHREADS), lds, s, p);
+  else
+    hipLaunchKernelGGL(decode_kernel<float>, grid, dim3(NTHREADS), lds, s, p);
+  return hipGetLastError();
+}
+
+template <typename AT>
+static hipError_t backward_generic_t(const Problem &p, hipStream_t s) {
+  const BwdWs w = carve_bwd_ws(p.ws, p.B, p.T, p.D);
+  const size_t lds = generic_lds_bytes(p.bs);
+  hipError_t e = allow_lds(bwd_pointwise_kernel<AT>, lds);
+  if (e != hipSuccess) return e;
+  e = allow_lds(bwd_dgrad_kernel<AT>, lds);
+  if (e != hipSuccess) return e;
+  const size_t n = (size_t)p.B * p.T * p.D;
+  const int dblocks = (p.D + NTHREADS - 1) / NTHREADS;
+
+  hipLaunchKernelGGL(bwd_pointwise_kernel<AT>, dim3(p.nb, p.B), dim3(NTHREADS), lds, s, p, w);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  const RowOuts gate_outs = {{p.g.db_a, p.g.db_x, p.g.dLambda, nullptr, nullptr}};
+  hipLaunchKernelGGL(reduce_parts_kernel, dim3(dblocks, 3), dim3(NTHREADS), 0, s, w.partA, p.B, 3,
+                     p.D, gate_outs);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  // dgrad: time tiles in gridDim.z (<= 65535), sequences in y
+  const int ntile = (p.T + GT - 1) / GT;
+  if (ntile > 65535 || p.B > 65535) return hipErrorInvalidConfiguration;
+  hipLaunchKernelGGL(bwd_dgrad_kernel<AT>, dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds, s, p, w);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(bwd_conv_input_kernel<AT>, dim3(grid_1d(n)), dim3(NTHREADS), 0, s, p, w);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (w.nchunk > 65535) return hipErrorInvalidConfiguration;
+  hipLaunchKernelGGL(bwd_conv_weight_kernel<AT>, dim3(dblocks, w.nchunk), dim3(NTHREADS), 0, s, p, w);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  const RowOuts conv_outs = {{p.g.dconv_w, p.g.dconv_w + p.D, p.g.dconv_w + 2 * (size_t)p.D,
+                              p.g.dconv_w + 3 * (size_t)p.D, p.g.dconv_b}};
+  hipLaunchKernelGGL(reduce_parts_kernel, dim3(dblocks, 5), dim3(NTHREADS), 0, s, w.partC, w.nchunk,
+                     5, p.D, conv_outs);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  const int tiles = (p.bs + 31) / 32;
+  hipLaunchKernelGGL(bwd_wgrad_kernel, dim3(p.nb, tiles, tiles), dim3(NTHREADS), 0, s, p, w);
+  return hipGetLastError();
+}
+
+hipError_t launch_backward_generic(const Problem &p, bool bf, hipStream_t s) {
+  return bf ? backward_generic_t<bf16>(p, s) : backward_generic_t<float>(p, s);
+}
+
+}  // namespace rglru

@@ -1,0 +1,68 @@
+// Internal declarations shared by the translation units of librglru (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "rglru.h"
+
+namespace rglru {
+
+// bfloat16 storage type: raw bits; arithmetic always happens in fp32.
+struct bf16 {
+  unsigned short v;
+};
+
+__device__ __forceinline__ float ldf(const float *p, size_t i) { return p[i]; }
+__device__ __forceinline__ float ldf(const bf16 *p, size_t i) {
+  return __uint_as_float(((unsigned)p[i].v) << 16);
+}
+// round-to-nearest-even, NaN kept quiet
+__device__ __forceinline__ unsigned short f32_to_bf16_bits(float f) {
+  unsigned u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (unsigned short)(u >> 16);
+}
+__device__ __forceinline__ void stf(float *p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void stf(bf16 *p, size_t i, float v) { p[i].v = f32_to_bf16_bits(v); }
+
+// mathematical n mod 3 for the conv ring buffer (n may be negative)
+__host__ __device__ __forceinline__ int ring_slot(long long n) {
+  int r = (int)(n % 3);
+  return r < 0 ? r + 3 : r;
+}
+
+// Everything a kernel needs to know about one call. Pointers are device pointers.
+struct Problem {
+  int B, T, D, nb, bs;
+  float c;
+  long long pos0;
+  const void *u;
+  const void *W_a, *W_x;
+  const float *b_a, *b_x, *Lambda, *conv_w, *conv_b;
+  const float *h0;
+  const void *state_in;
+  void *y;
+  float *hT;
+  void *state_out;
+  // backward only
+  const void *y_in, *dy;
+  const float *dhT;
+  void *du;
+  float *dh0;
+  rglru_param_grads g;
+  void *ws;
+  size_t ws_bytes;
+};
+
+// Launchers. Each returns hipSuccess or the launch error. `bf` selects bf16 act+weights.
+hipError_t launch_conv1d_generic(const Problem &p, bool bf, void *x_out, hipStream_t s);
+hipError_t launch_state_update(const Problem &p, bool bf, hipStream_t s);
+hipError_t launch_forward_generic(const Problem &p, bool bf, hipStream_t s);
+hipError_t launch_decode_generic(const Problem &p, bool bf, hipStream_t s);
+hipError_t launch_backward_generic(const Problem &p, bool bf, hipStream_t s);
+size_t backward_generic_ws_bytes(int B, int T, int D, int nb);
+size_t generic_lds_bytes(int bs);
+
+}  // namespace rglru

@@ -1,0 +1,114 @@
+"""Convenience layer for tests, smoke and the benchmark: moves numpy inputs into device
+memory with torch (used for allocation and streams only) and calls the C ABI through the
+ctypes binding. It performs no arithmetic of the method.
+"""
+import numpy as np
+import torch
+
+from . import binding as R
+
+
+def _bits_to_bf16_tensor(a_f32, device):
+    """float32 numpy values that are exactly representable in bf16 -> torch.bfloat16 tensor."""
+    bits = (np.ascontiguousarray(a_f32, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    return torch.from_numpy(bits.view(np.int16)).to(device).view(torch.bfloat16)
+
+
+def to_device(a, act, device="cuda:0"):
+    """numpy float32 -> device tensor stored as `act` ("f32" | "bf16"); None passes through."""
+    if a is None:
+        return None
+    if act == "bf16":
+        return _bits_to_bf16_tensor(a, device)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+
+
+def to_host(t):
+    return None if t is None else t.detach().float().cpu().numpy()
+
+
+class DeviceProblem:
+    """Device copies of one workload's parameters plus the shape/params structs."""
+
+    def __init__(self, inp, B, T, D, nb, act, device="cuda:0", c=8.0):
+        self.B, self.T, self.D, self.nb, self.act, self.device = B, T, D, nb, act, device
+        self.dt = R.BF16 if act == "bf16" else R.F32
+        self.tdtype = torch.bfloat16 if act == "bf16" else torch.float32
+        self.c = c
+        self.W_a = to_device(inp["W_a"], act, device)
+        self.W_x = to_device(inp["W_x"], act, device)
+        self.b_a = to_device(inp["b_a"], "f32", device)
+        self.b_x = to_device(inp["b_x"], "f32", device)
+        self.Lambda = to_device(inp["Lambda"], "f32", device)
+        self.conv_w = to_device(inp["conv_w"], "f32", device)
+        self.conv_b = to_device(inp.get("conv_b"), "f32", device)
+        self.params = R.make_params(self.W_a, self.W_x, self.b_a, self.b_x, self.Lambda,
+                                    self.conv_w, self.conv_b)
+        self._ws = {}
+
+    def shape(self, T=None, B=None):
+        return R.make_shape(self.B if B is None else B, self.T if T is None else T, self.D,
+                            self.nb, self.dt, c=self.c)
+
+    def workspace(self, shape, op):
+        n = R.rglru_workspace_bytes(shape, op)
+        key = (op, n)
+        if key not in self._ws:
+            self._ws[key] = torch.empty(max(n, 256), dtype=torch.uint8, device=self.device)
+        return self._ws[key], n
+
+    def empty_act(self, *shape):
+        return torch.empty(*shape, dtype=self.tdtype, device=self.device)
+
+    def empty_f32(self, *shape):
+        return torch.empty(*shape, dtype=torch.float32, device=self.device)
+
+    # ---- one-call helpers (allocate outputs, call the library, leave results on device)
+    def conv1d(self, u, state_in=None, pos0=0, want_state=True):
+        B, T, D = u.shape
+        sh = self.shape(T=T, B=B)
+        x = self.empty_act(B, T, D)
+        st = self.empty_act(B, 3, D) if want_state else None
+        R.rglru_conv1d(sh, u, self.conv_w, self.conv_b, state_in, pos0, x, st)
+        return x, st
+
+    def forward(self, u, h0=None, state_in=None, pos0=0, want_state=True, stream=None):
+        B, T, D = u.shape
+        sh = self.shape(T=T, B=B)
+        ws, n = self.workspace(sh, R.OP_FORWARD)
+        y = self.empty_act(B, T, D)
+        hT = self.empty_f32(B, D)
+        st = self.empty_act(B, 3, D) if want_state else None
+        R.rglru_forward(sh, self.params, u, h0, state_in, pos0, y, hT, st, ws, n, stream)
+        return y, hT, st
+
+    def decode_step(self, u_t, h, conv_state, pos, stream=None):
+        B, D = u_t.shape
+        sh = self.shape(T=1, B=B)
+        y = self.empty_act(B, D)
+        R.rglru_decode_step(sh, self.params, u_t, h, conv_state, pos, y, stream)
+        return y
+
+    def alloc_grads(self):
+        bs = self.D // self.nb
+        g = dict(dW_a=self.empty_f32(self.nb, bs, bs), dW_x=self.empty_f32(self.nb, bs, bs),
+                 db_a=self.empty_f32(self.D), db_x=self.empty_f32(self.D),
+                 dLambda=self.empty_f32(self.D), dconv_w=self.empty_f32(4, self.D),
+                 dconv_b=self.empty_f32(self.D))
+        return g
+
+    def backward(self, u, y, dy, h0=None, state_in=None, pos0=0, dhT=None, grads=None,
+                 stream=None):
+        B, T, D = u.shape
+        sh = self.shape(T=T, B=B)
+        ws, n = self.workspace(sh, R.OP_BACKWARD)
+        du = self.empty_act(B, T, D)
+        dh0 = self.empty_f32(B, D)
+        g = grads if grads is not None else self.alloc_grads()
+        pg = R.make_param_grads(g["dW_a"], g["dW_x"], g["db_a"], g["db_x"], g["dLambda"],
+                                g["dconv_w"], g["dconv_b"])
+        R.rglru_backward(sh, self.params, u, h0, state_in, pos0, y, dy, dhT, du, dh0, pg, ws, n,
+                         stream)
+        out = dict(g)
+        out["du"], out["dh0"] = du, dh0
+        return out

@@ -1,0 +1,142 @@
+"""Host-side checks that need no GPU: the shared library loads, exports every function the
+public header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+import paper_2402_19427_amd as R  # noqa: E402
+
+FAKE = 0x1000  # a non-NULL, 256-byte aligned address that is never dereferenced on error paths
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "rglru.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rglru_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"rglru_conv1d", "rglru_forward", "rglru_decode_step", "rglru_backward",
+            "rglru_workspace_bytes", "rglru_last_error", "rglru_version"} <= set(names)
+    lib = ctypes.CDLL(R.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert R.rglru_version() >= 100
+
+
+def test_binding_exposes_the_same_names():
+    for n in declared_functions():
+        assert callable(getattr(R, n)), n
+
+
+def params():
+    return R.make_params(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)
+
+
+def fwd(shape, p=None, u=FAKE, y=FAKE, ws=None, ws_bytes=0, pos0=0, h0=None):
+    R.rglru_forward(shape, p or params(), u, h0, None, pos0, y, None, None, ws, ws_bytes)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(B=0), R.ERR_INVALID_ARG),
+    (dict(D=0), R.ERR_INVALID_ARG),
+    (dict(T=-1), R.ERR_INVALID_ARG),
+    (dict(num_blocks=0), R.ERR_INVALID_ARG),
+    (dict(num_blocks=3), R.ERR_INVALID_ARG),            # 16 % 3 != 0
+    (dict(c=0.0), R.ERR_INVALID_ARG),
+    (dict(act_dtype=7), R.ERR_INVALID_ARG),
+    (dict(conv_width=3), R.ERR_UNSUPPORTED),
+    (dict(conv_width=0), R.ERR_UNSUPPORTED),
+    (dict(act_dtype=R.BF16, w_dtype=R.F32), R.ERR_UNSUPPORTED),
+    (dict(D=4096 * 4, num_blocks=1), R.ERR_UNSUPPORTED),  # block larger than the LDS tile
+    (dict(B=70000), R.ERR_UNSUPPORTED),
+])
+def test_forward_rejects_bad_shapes(kw, code):
+    base = dict(B=2, T=8, D=16, num_blocks=2, act_dtype=R.F32)
+    base.update(kw)
+    with pytest.raises(R.RglruError) as e:
+        fwd(R.make_shape(**base))
+    assert e.value.code == code
+    assert R.rglru_last_error() != ""
+
+
+def test_null_and_misaligned_pointers():
+    s = R.make_shape(2, 8, 16, 2, R.F32)
+    with pytest.raises(R.RglruError) as e:
+        fwd(s, u=None)
+    assert e.value.code == R.ERR_INVALID_ARG and "u is NULL" in str(e.value)
+    with pytest.raises(R.RglruError) as e:
+        fwd(s, y=None)
+    assert e.value.code == R.ERR_INVALID_ARG
+    with pytest.raises(R.RglruError) as e:
+        fwd(s, u=FAKE + 2)
+    assert e.value.code == R.ERR_INVALID_ARG and "aligned" in str(e.value)
+    with pytest.raises(R.RglruError) as e:
+        fwd(s, p=R.make_params(None, FAKE, FAKE, FAKE, FAKE, FAKE))
+    assert e.value.code == R.ERR_INVALID_ARG and "W_a" in str(e.value)
+    with pytest.raises(R.RglruError) as e:
+        fwd(s, pos0=-1)
+    assert e.value.code == R.ERR_INVALID_ARG
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_forward(s, None, FAKE, None, None, 0, FAKE, None, None, None, 0)
+    assert e.value.code == R.ERR_INVALID_ARG
+
+
+def test_decode_and_conv_validation():
+    s = R.make_shape(2, 1, 16, 2, R.BF16)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_decode_step(s, params(), FAKE, None, FAKE, 0, FAKE)
+    assert e.value.code == R.ERR_INVALID_ARG and "h is NULL" in str(e.value)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_decode_step(s, params(), FAKE, FAKE, FAKE, -5, FAKE)
+    assert e.value.code == R.ERR_INVALID_ARG
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_conv1d(s, FAKE, None, None, None, 0, FAKE, None)
+    assert e.value.code == R.ERR_INVALID_ARG and "conv_w" in str(e.value)
+    # conv1d ignores num_blocks
+    s2 = R.make_shape(2, 4, 16, 5, R.BF16)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_conv1d(s2, None, FAKE, None, None, 0, FAKE, None)
+    assert "u is NULL" in str(e.value)
+
+
+def test_backward_validation_and_workspace():
+    s = R.make_shape(2, 8, 16, 2, R.F32)
+    need = R.rglru_workspace_bytes(s, R.OP_BACKWARD)
+    assert need > 0 and need % 256 == 0
+    g = R.make_param_grads(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)
+    args = (s, params(), FAKE, None, None, 0, FAKE, FAKE, None, FAKE, None, g)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_backward(*args, None, 0)
+    assert e.value.code == R.ERR_WORKSPACE
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_backward(*args, FAKE, need - 1)
+    assert e.value.code == R.ERR_WORKSPACE
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_backward(*args, FAKE + 64, need)
+    assert e.value.code == R.ERR_INVALID_ARG
+    g2 = R.make_param_grads(FAKE, FAKE, None, FAKE, FAKE, FAKE)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_backward(s, params(), FAKE, None, None, 0, FAKE, FAKE, None, FAKE, None, g2,
+                         FAKE, need)
+    assert e.value.code == R.ERR_INVALID_ARG and "db_a" in str(e.value)
+    s0 = R.make_shape(2, 0, 16, 2, R.F32)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_backward(s0, params(), FAKE, None, None, 0, FAKE, FAKE, None, FAKE, None, g,
+                         FAKE, 1 << 20)
+    assert e.value.code == R.ERR_INVALID_ARG
+
+
+def test_workspace_query_is_zero_for_invalid_shapes_and_keeps_error_string():
+    bad = R.make_shape(2, 8, 16, 3, R.F32)
+    with pytest.raises(R.RglruError):
+        fwd(bad)
+    msg = R.rglru_last_error()
+    assert R.rglru_workspace_bytes(bad, R.OP_FORWARD) == 0
+    assert R.rglru_workspace_bytes(bad, 99) == 0
+    assert R.rglru_last_error() == msg

@@ -1,0 +1,232 @@
+"""GPU parity: the HIP library, called through its C ABI, against the float64 oracle on the
+same seeded inputs, element by element.
+
+Tolerances (relative error with an rms floor, rglru_inputs.rel_err):
+  fp32 storage  : 1e-5
+  bf16 storage  : 2e-2   (bf16 in / fp32 state and accumulation)
+Bit-exact where the work is a copy (conv ring state).
+"""
+import numpy as np
+import pytest
+
+import oracle
+import rglru_inputs as gen
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+# parameter gradients are long sums of rounded products; the bf16 bar applies to each tensor
+GRAD_TOL = {"f32": 2e-5, "bf16": 2e-2}
+
+
+def runner():
+    import paper_2402_19427_amd.runner as rn
+    return rn
+
+
+def f64(inp):
+    return {k: (None if v is None else np.asarray(v, np.float64)) for k, v in inp.items()}
+
+
+def oracle_forward(inp, h0=None, state=None):
+    q = f64(inp)
+    return oracle.forward(q["u"], q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"],
+                          q["conv_w"], conv_b=q.get("conv_b"), h0=h0, state_in=state)
+
+
+SHAPES = [
+    # B, T, D, nb, act            what it exercises
+    (1, 256, 256, 4, "f32"),     # workload C0
+    (2, 37, 96, 3, "f32"),       # ragged T, bs = 32
+    (3, 5, 40, 5, "f32"),        # bs = 8, fewer steps than one tile
+    (1, 1, 16, 1, "f32"),        # single step, single dense block
+    (2, 130, 512, 2, "bf16"),    # bs = 256: the tuned block size, ragged T
+    (2, 70, 320, 2, "bf16"),     # bs = 160: the paper's 16 blocks at width 2560
+    (1, 9, 24, 24, "bf16"),      # nb = D: per-channel gates
+    (2, 300, 600, 2, "bf16"),    # bs = 300 > workgroup size
+]
+
+
+@pytest.mark.parametrize("B,T,D,nb,act", SHAPES)
+@pytest.mark.parametrize("full", [False, True])
+def test_forward_matches_oracle(B, T, D, nb, act, full):
+    rn = runner()
+    inp = gen.make_inputs(B, T, D, nb, act=act, seed=B * 1000 + T + D, h0=full, state=full,
+                          bias=full)
+    pos0 = 5 if full else 0
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    u = rn.to_device(inp["u"], act)
+    h0 = rn.to_device(inp["h0"], "f32")
+    ring = None
+    if full:
+        ring = rn.to_device(gen.ring_from_chrono(inp["state"], pos0), act)
+    y, hT, st = dp.forward(u, h0=h0, state_in=ring, pos0=pos0)
+    y_ref, hT_ref, st_ref = oracle_forward(inp, h0=inp["h0"], state=inp["state"])
+    assert gen.rel_err(rn.to_host(y), y_ref) < TOL[act]
+    assert gen.rel_err(rn.to_host(hT), hT_ref) < (1e-5 if act == "f32" else 2e-3)
+    np.testing.assert_array_equal(gen.chrono_from_ring(rn.to_host(st), pos0 + T), st_ref)
+
+
+@pytest.mark.parametrize("act", ["f32", "bf16"])
+def test_forward_in_pieces_equals_one_shot_and_states_may_alias(act):
+    rn = runner()
+    B, T, D, nb = 2, 45, 64, 2
+    inp = gen.make_inputs(B, T, D, nb, act=act, seed=77, h0=True)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    u = rn.to_device(inp["u"], act)
+    y_ref, hT_ref, st_ref = oracle_forward(inp, h0=inp["h0"])
+    h = rn.to_device(inp["h0"], "f32")
+    state = None
+    import paper_2402_19427_amd as R
+    ys = []
+    pos = 0
+    for T1 in (1, 2, 13, 29):   # pieces shorter than the filter, then longer ones
+        piece = u[:, pos:pos + T1].contiguous()
+        sh = dp.shape(T=T1)
+        ws, n = dp.workspace(sh, R.OP_FORWARD)
+        y = dp.empty_act(B, T1, D)
+        st_out = state if state is not None else dp.empty_act(B, 3, D)
+        R.rglru_forward(sh, dp.params, piece, h, state, pos, y, h, st_out, ws, n)  # in place
+        state = st_out
+        ys.append(rn.to_host(y))
+        pos += T1
+    assert pos == T
+    assert gen.rel_err(np.concatenate(ys, axis=1), y_ref) < TOL[act]
+    assert gen.rel_err(rn.to_host(h), hT_ref) < (1e-5 if act == "f32" else 2e-3)
+    np.testing.assert_array_equal(gen.chrono_from_ring(rn.to_host(state), T), st_ref)
+
+
+def test_forward_zero_length_passes_states_through():
+    rn = runner()
+    B, D, nb = 2, 32, 2
+    inp = gen.make_inputs(B, 4, D, nb, act="bf16", seed=5, h0=True, state=True)
+    dp = rn.DeviceProblem(inp, B, 0, D, nb, "bf16")
+    u = dp.empty_act(B, 0, D)
+    ring = rn.to_device(gen.ring_from_chrono(inp["state"], 7), "bf16")
+    y, hT, st = dp.forward(u, h0=rn.to_device(inp["h0"], "f32"), state_in=ring, pos0=7)
+    np.testing.assert_array_equal(rn.to_host(hT), inp["h0"])
+    np.testing.assert_array_equal(rn.to_host(st), rn.to_host(ring))
+
+
+@pytest.mark.parametrize("B,T,D,act", [(2, 50, 96, "f32"), (3, 2, 40, "bf16"), (1, 700, 512, "bf16")])
+@pytest.mark.parametrize("full", [False, True])
+def test_conv1d_matches_oracle(B, T, D, act, full):
+    rn = runner()
+    inp = gen.make_inputs(B, T, D, 1, act=act, seed=T + D, state=full, bias=full)
+    pos0 = 4 if full else 0
+    dp = rn.DeviceProblem(inp, B, T, D, 1, act)
+    ring = rn.to_device(gen.ring_from_chrono(inp["state"], pos0), act) if full else None
+    x, st = dp.conv1d(rn.to_device(inp["u"], act), state_in=ring, pos0=pos0)
+    q = f64(inp)
+    x_ref, st_ref = oracle.conv1d(q["u"], q["conv_w"], conv_b=q.get("conv_b"),
+                                  state_in=q["state"], want_state=True)
+    assert gen.rel_err(rn.to_host(x), x_ref) < (1e-6 if act == "f32" else 5e-3)
+    np.testing.assert_array_equal(gen.chrono_from_ring(rn.to_host(st), pos0 + T), st_ref)
+
+
+@pytest.mark.parametrize("B,D,nb,act", [(5, 64, 2, "f32"), (19, 512, 2, "bf16"), (3, 320, 2, "bf16"),
+                                        (64, 1024, 4, "bf16")])
+def test_decode_steps_match_oracle_and_wrap_the_ring(B, D, nb, act):
+    rn = runner()
+    nsteps = 7
+    inp = gen.make_inputs(B, 1, D, nb, act=act, seed=B + D, h0=True, state=True,
+                          decode_tokens=nsteps, bias=True)
+    dp = rn.DeviceProblem(inp, B, 1, D, nb, act)
+    pos = 11
+    h = rn.to_device(inp["h0"], "f32")
+    ring = rn.to_device(gen.ring_from_chrono(inp["state"], pos), act)
+    q = f64(inp)
+    h_ref, st_ref = q["h0"].copy(), q["state"].copy()
+    for s in range(nsteps):
+        y = dp.decode_step(rn.to_device(inp["u_dec"][s], act), h, ring, pos + s)
+        y_ref = oracle.decode_step(q["u_dec"][s], q["W_a"], q["W_x"], q["b_a"], q["b_x"],
+                                   q["Lambda"], q["conv_w"], h_ref, st_ref, conv_b=q["conv_b"])
+        assert gen.rel_err(rn.to_host(y), y_ref) < TOL[act], s
+        assert gen.rel_err(rn.to_host(h), h_ref) < (1e-5 if act == "f32" else 2e-3), s
+        np.testing.assert_array_equal(gen.chrono_from_ring(rn.to_host(ring), pos + s + 1), st_ref)
+
+
+def test_decode_continues_a_forward_call():
+    rn = runner()
+    B, T, D, nb, act = 4, 21, 512, 2, "bf16"
+    inp = gen.make_inputs(B, T + 1, D, nb, act=act, seed=9)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    u = rn.to_device(inp["u"], act)
+    _, hT, st = dp.forward(u[:, :T].contiguous())
+    y_last = dp.decode_step(u[:, T].contiguous(), hT, st, T)
+    y_ref, hT_ref, _ = oracle_forward(inp)
+    assert gen.rel_err(rn.to_host(y_last), y_ref[:, T]) < TOL[act]
+    assert gen.rel_err(rn.to_host(hT), hT_ref) < 2e-3
+
+
+BWD_SHAPES = [
+    (2, 19, 64, 2, "f32"),
+    (1, 256, 256, 4, "f32"),
+    (3, 3, 40, 5, "f32"),
+    (2, 1, 16, 1, "f32"),
+    (2, 75, 512, 2, "bf16"),
+    (2, 33, 320, 2, "bf16"),
+    (1, 270, 600, 2, "bf16"),
+]
+
+
+@pytest.mark.parametrize("B,T,D,nb,act", BWD_SHAPES)
+@pytest.mark.parametrize("full", [False, True])
+def test_backward_matches_oracle(B, T, D, nb, act, full):
+    rn = runner()
+    inp = gen.make_inputs(B, T, D, nb, act=act, seed=31 * B + T + D, h0=full, state=full,
+                          bias=full, dy=True)
+    pos0 = 2 if full else 0
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    u = rn.to_device(inp["u"], act)
+    h0 = rn.to_device(inp["h0"], "f32")
+    ring = rn.to_device(gen.ring_from_chrono(inp["state"], pos0), act) if full else None
+    dhT = rn.to_device(inp["dhT"], "f32") if full else None
+    y, _, _ = dp.forward(u, h0=h0, state_in=ring, pos0=pos0, want_state=False)
+    out = dp.backward(u, y, rn.to_device(inp["dy"], act), h0=h0, state_in=ring, pos0=pos0,
+                      dhT=dhT)
+    q = f64(inp)
+    ref = oracle.backward(q["u"], q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"],
+                          q["conv_w"], q["dy"], conv_b=q.get("conv_b"), h0=q["h0"],
+                          state_in=q["state"], dhT=q["dhT"] if full else None)
+    for k in ("du", "dh0", "dW_a", "dW_x", "db_a", "db_x", "dLambda", "dconv_w", "dconv_b"):
+        err = gen.rel_err(rn.to_host(out[k]), ref[k])
+        assert err < GRAD_TOL[act], (k, err)
+
+
+def test_backward_optional_outputs_can_be_skipped():
+    rn = runner()
+    import paper_2402_19427_amd as R
+    B, T, D, nb, act = 2, 12, 32, 2, "f32"
+    inp = gen.make_inputs(B, T, D, nb, act=act, seed=3, dy=True)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    u = rn.to_device(inp["u"], act)
+    y, _, _ = dp.forward(u, want_state=False)
+    full = dp.backward(u, y, rn.to_device(inp["dy"], act))
+    g = dp.alloc_grads()
+    pg = R.make_param_grads(g["dW_a"], g["dW_x"], g["db_a"], g["db_x"], g["dLambda"],
+                            g["dconv_w"], None)
+    sh = dp.shape()
+    ws, n = dp.workspace(sh, R.OP_BACKWARD)
+    du = dp.empty_act(B, T, D)
+    R.rglru_backward(sh, dp.params, u, None, None, 0, y, rn.to_device(inp["dy"], act), None, du,
+                     None, pg, ws, n)
+    np.testing.assert_array_equal(rn.to_host(du), rn.to_host(full["du"]))
+    np.testing.assert_array_equal(rn.to_host(g["dW_a"]), rn.to_host(full["dW_a"]))
+
+
+def test_results_are_deterministic_run_to_run():
+    rn = runner()
+    B, T, D, nb, act = 2, 200, 512, 2, "bf16"
+    inp = gen.make_inputs(B, T, D, nb, act=act, seed=8, h0=True, dy=True)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    u = rn.to_device(inp["u"], act)
+    h0 = rn.to_device(inp["h0"], "f32")
+    outs = []
+    for _ in range(3):
+        y, hT, _ = dp.forward(u, h0=h0)
+        g = dp.backward(u, y, rn.to_device(inp["dy"], act), h0=h0)
+        outs.append((rn.to_host(y), rn.to_host(hT), rn.to_host(g["du"]), rn.to_host(g["dW_a"])))
+    for o in outs[1:]:
+        for a, b in zip(outs[0], o):
+            np.testing.assert_array_equal(a, b)
