@@ -42,6 +42,10 @@ def _load():
         raise ImportError(
             "%s is missing: build it with `python -m paper_2402_19427_amd.build` "
             "(there is no fallback implementation)" % LIB_PATH)
+    # torch ships its own HIP runtime; it has to be in the process before librglru is
+    # loaded so that the library binds to that same runtime (one runtime, one set of devices
+    # and streams) instead of pulling in a second copy from /opt/rocm.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, i64, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
     sp, pp, gp = ctypes.POINTER(Shape), ctypes.POINTER(Params), ctypes.POINTER(ParamGrads)

@@ -257,7 +257,8 @@ __global__ void __launch_bounds__(NTHREADS) bwd_pointwise_kernel(Problem p, BwdW
       float pa[GT], qa[GT];
       gate_rows<AT>(p, g, j, xs, pa, qa);
       const float neg_cs = -p.c * softplus_f(-p.Lambda[d]);
-      const float lam_scale = p.c * (1.f - sigmoid_f(p.Lambda[d]));
+      // 1 - sigmoid(Lambda) = sigmoid(-Lambda), evaluated without cancellation
+      const float lam_scale = p.c * sigmoid_f(-p.Lambda[d]);
       float cy = carry[j], s_ba = 0.f, s_bx = 0.f, s_lam = 0.f;
 #pragma unroll
       for (int tt = GT - 1; tt >= 0; --tt) {
