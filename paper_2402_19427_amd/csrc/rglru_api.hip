@@ -114,6 +114,10 @@ size_t workspace_need(const rglru_shape *s, int op) {
   switch (op) {
     case RGLRU_OP_BACKWARD:
       return backward_generic_ws_bytes(s->B, s->T, s->D, s->num_blocks);
+    case RGLRU_OP_FORWARD:
+      if (s->act_dtype == RGLRU_BF16 && s->D / s->num_blocks == 256 && s->T >= 1)
+        return forward_mfma_ws_bytes(s->B, s->T, s->D, s->num_blocks);
+      return 0;
     default:
       return 0;
   }
@@ -190,7 +194,8 @@ int rglru_forward(const rglru_shape *shape, const rglru_params *params, const vo
   q.ws = workspace; q.ws_bytes = workspace_bytes;
   const bool bf = shape->act_dtype == RGLRU_BF16;
   hipStream_t s = (hipStream_t)stream;
-  hipError_t e = launch_forward_generic(q, bf, s);
+  hipError_t e = forward_mfma_supported(q, bf) ? launch_forward_mfma(q, s)
+                                              : launch_forward_generic(q, bf, s);
   if (e != hipSuccess) return hip_fail(e, "forward launch");
   // the new ring state is written after the last read of the incoming one (they may alias)
   e = launch_state_update(q, bf, s);

@@ -65,4 +65,9 @@ hipError_t launch_backward_generic(const Problem &p, bool bf, hipStream_t s);
 size_t backward_generic_ws_bytes(int B, int T, int D, int nb);
 size_t generic_lds_bytes(int bs);
 
+// MFMA forward (bf16 storage, gate blocks of 256)
+bool forward_mfma_supported(const Problem &p, bool bf);
+size_t forward_mfma_ws_bytes(int B, int T, int D, int nb);
+hipError_t launch_forward_mfma(const Problem &p, hipStream_t s);
+
 }  // namespace rglru
