@@ -194,11 +194,16 @@ int rglru_forward(const rglru_shape *shape, const rglru_params *params, const vo
   q.ws = workspace; q.ws_bytes = workspace_bytes;
   const bool bf = shape->act_dtype == RGLRU_BF16;
   hipStream_t s = (hipStream_t)stream;
-  hipError_t e = forward_mfma_supported(q, bf) ? launch_forward_mfma(q, s)
-                                              : launch_forward_generic(q, bf, s);
-  if (e != hipSuccess) return hip_fail(e, "forward launch");
-  // the new ring state is written after the last read of the incoming one (they may alias)
-  e = launch_state_update(q, bf, s);
+  hipError_t e;
+  if (forward_mfma_supported(q, bf)) {
+    e = launch_forward_mfma(q, s);  // writes the new ring state itself
+    if (e != hipSuccess) return hip_fail(e, "forward launch");
+  } else {
+    e = launch_forward_generic(q, bf, s);
+    if (e != hipSuccess) return hip_fail(e, "forward launch");
+    // the new ring state is written after the last read of the incoming one (they may alias)
+    e = launch_state_update(q, bf, s);
+  }
   if (e != hipSuccess) return hip_fail(e, "conv state launch");
   g_err[0] = 0;
   return RGLRU_OK;

@@ -8,9 +8,12 @@
 //   gates, a_t, sqrt(1-a_t^2) (eqs. 1-3, Appendix A) and the scan (eq. 4) in registers: every
 //     lane runs 16 consecutive steps of one channel, the two lane halves are combined with
 //     the affine composition (a2,b2)o(a1,b1) = (a2 a1, a2 b1 + b2)
-//   carries between the time slices of one sequence travel through 8-byte records in global
-//     memory (value + tag in one atomic word): each tile first publishes its own aggregate,
-//     then looks back over its predecessors until it meets an inclusive state.
+//   when a sequence is sliced in time (tile t belongs to workgroup t mod G), every tile
+//     publishes its aggregate (prod a, local end state) as tagged 8-byte records; a workgroup
+//     carries its own state from its previous tile across the G-1 tiles in between by reading
+//     their aggregates. Aggregates do not depend on incoming states, so no workgroup ever
+//     waits on a chain; the outputs of a tile are finished one iteration late, from the (a_t, b_t)
+//     pairs parked in LDS, so that the records it needs are long since visible.
 //
 // Scaling trick: the Conv1D taps are multiplied by log2(e), so the MFMA delivers
 // log2(e)*(Wx+b) and v_exp_f32 (a base-2 exponential) needs no extra multiply; the input gate
@@ -27,19 +30,23 @@ constexpr int NTHR = NWAVE * 64;
 constexpr int TT = 32;           // time steps per tile
 constexpr int XS = BS + 8;       // LDS row stride in bf16 elements (528 B: conflict-free b128 reads)
 constexpr float LOG2E = 1.4426950408889634f;
+constexpr int XS_BYTES = 2 * TT * XS * 2;          // two x tiles
+constexpr int CONST_BYTES = 64 * 32 + 128 * 48;      // selection operands + Conv1D taps per lane
+constexpr int HOLD_BYTES = NWAVE * 64 * 32 * 4;     // local scan of one tile, per lane 32 floats
+constexpr int SPIN_LIMIT = 1 << 22;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned long long u64;
-
-constexpr unsigned TAG_AGG = 1, TAG_INCL = 2;
-constexpr int SPIN_LIMIT = 1 << 22;
 
 struct FwdArgs {
   Problem p;
   int G;         // time slices (workgroups) per (sequence, block)
   int ntile;     // tiles per sequence
-  int R;         // record ring depth per unit (multiple of G)
+  int R;         // record ring depth per unit
   u64 *rec;      // [unit][R][2][256] records (A then H), zeroed before launch; NULL if G == 1
   int *err;      // set to 1 if a bounded wait expired
   int swizzle;   // remap block ids so that neighbouring time slices share an XCD
@@ -47,15 +54,15 @@ struct FwdArgs {
 
 __device__ __forceinline__ float bf_lo(unsigned v) { return __uint_as_float(v << 16); }
 __device__ __forceinline__ float bf_hi(unsigned v) { return __uint_as_float(v & 0xffff0000u); }
-__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
-  return (unsigned)f32_to_bf16_bits(lo) | ((unsigned)f32_to_bf16_bits(hi) << 16);
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {  // v_cvt_pk_bf16_f32
+  const f32x2 v = {lo, hi};
+  const bf16x2 b = __builtin_convertvector(v, bf16x2);
+  return *(const unsigned *)&b;
 }
 
-__device__ __forceinline__ u64 make_rec(float v, unsigned tag) {
-  return ((u64)tag << 32) | (u64)__float_as_uint(v);
-}
 __device__ __forceinline__ void publish(u64 *slot, float v, unsigned tag) {
-  __hip_atomic_store(slot, make_rec(v, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const u64 r = ((u64)tag << 32) | (u64)__float_as_uint(v);
+  __hip_atomic_store(slot, r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ u64 peek(const u64 *slot) {
   return __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -74,27 +81,34 @@ __device__ __forceinline__ void gate_fast(float pp, float qq, float xx, float kd
   b = (m * il) * xx;
 }
 
-__global__ void __launch_bounds__(256) zero_words_kernel(u64 *p, size_t n) {
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256)
-    p[i] = 0;
+__global__ void __launch_bounds__(256) zero_words_kernel(uint4 *p, size_t n16) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n16) p[i] = make_uint4(0, 0, 0, 0);
 }
 
-template <bool MULTI>
+// GMAX = 1: one workgroup per (sequence, block); GMAX = 4 / 8: 2..4 / 5..8 time slices
+template <int GMAX>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 fwd_mfma_kernel(FwdArgs a) {
-  __shared__ __attribute__((aligned(16))) unsigned short xs[2][TT * XS];
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned short *xs = (unsigned short *)smem;                   // [2][TT][XS]
+  bf16x8 *sel_lds = (bf16x8 *)(smem + XS_BYTES);                 // [2][64] selection operands
+  f32x4 *cw_lds = (f32x4 *)(smem + XS_BYTES + 64 * 32);          // [3][128] Conv1D taps and bias
+  float *hold = (float *)(smem + XS_BYTES + CONST_BYTES);        // [wave][8][64] float4
   const Problem &p = a.p;
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, hf = lane >> 5, j = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, j = lane & 31;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int G = GMAX == 1 ? 1 : a.G;
 
   int bid = blockIdx.x;
-  if (a.swizzle) {  // consecutive logical ids on the same XCD (ids are dealt round-robin to 8)
+  if (GMAX > 1 && a.swizzle) {  // consecutive logical ids on one XCD (ids are dealt round-robin to 8)
     const int per = gridDim.x >> 3;
     bid = (bid & 7) * per + (bid >> 3);
   }
-  const int unit = bid / a.G, w = bid - unit * a.G;
+  const int unit = bid / G, w = bid - unit * G;
   const int b = unit / p.nb, g = unit - b * p.nb;
   const int D = p.D, T = p.T;
-  const int ch = wv * 32 + j;            // channel inside the block owned by this lane
+  const int ch = wv * 32 + j;  // channel inside the block owned by this lane
   const int d = g * BS + ch;
 
   // ---- gate weights of this wave's 32 output channels, resident in registers
@@ -109,11 +123,16 @@ fwd_mfma_kernel(FwdArgs a) {
     }
   }
   // selection matrices that copy this wave's 32 columns of the tile into accumulator layout
-  bf16x8 sel0, sel1;
+  // (the same for every wave; parked in LDS to keep registers for the weights)
+  if (tid < 64) {
+    bf16x8 sel0, sel1;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    sel0[e] = (__bf16)((hf * 8 + e == j) ? 1.0f : 0.0f);
-    sel1[e] = (__bf16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
+    for (int e = 0; e < 8; ++e) {
+      sel0[e] = (__bf16)((hf * 8 + e == j) ? 1.0f : 0.0f);
+      sel1[e] = (__bf16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
+    }
+    sel_lds[lane] = sel0;
+    sel_lds[64 + lane] = sel1;
   }
   const float bias_p = p.b_a[d] * LOG2E, bias_q = p.b_x[d] * LOG2E;
   float kd;  // -c * softplus(-Lambda) * log2(e)
@@ -124,60 +143,156 @@ fwd_mfma_kernel(FwdArgs a) {
   }
 
   // ---- Conv1D assignment: channel pair c2, rows 8*rg .. 8*rg+7 of the tile
-  const int c2 = tid & 127, rg = tid >> 7;
+  const int c2 = tid & 127;
+  const int rg = __builtin_amdgcn_readfirstlane(tid >> 7);
   const int dc = g * BS + 2 * c2;
-  float cw[4][2], cb[2];
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    cw[k][0] = p.conv_w[(size_t)k * D + dc] * LOG2E;
-    cw[k][1] = p.conv_w[(size_t)k * D + dc + 1] * LOG2E;
+  if (tid < 128) {  // taps (scaled by log2 e) and bias of the channel pair, parked in LDS
+    f32x4 t0v, t1v, t2v;
+    t0v[0] = p.conv_w[dc] * LOG2E;                  t0v[1] = p.conv_w[dc + 1] * LOG2E;
+    t0v[2] = p.conv_w[(size_t)D + dc] * LOG2E;      t0v[3] = p.conv_w[(size_t)D + dc + 1] * LOG2E;
+    t1v[0] = p.conv_w[(size_t)2 * D + dc] * LOG2E;  t1v[1] = p.conv_w[(size_t)2 * D + dc + 1] * LOG2E;
+    t1v[2] = p.conv_w[(size_t)3 * D + dc] * LOG2E;  t1v[3] = p.conv_w[(size_t)3 * D + dc + 1] * LOG2E;
+    t2v[0] = p.conv_b ? p.conv_b[dc] * LOG2E : 0.f;
+    t2v[1] = p.conv_b ? p.conv_b[dc + 1] * LOG2E : 0.f;
+    t2v[2] = t2v[3] = 0.f;
+    cw_lds[c2] = t0v;
+    cw_lds[128 + c2] = t1v;
+    cw_lds[256 + c2] = t2v;
   }
-  cb[0] = p.conv_b ? p.conv_b[dc] * LOG2E : 0.f;
-  cb[1] = p.conv_b ? p.conv_b[dc + 1] * LOG2E : 0.f;
-  const unsigned *u32 = (const unsigned *)((const unsigned short *)p.u + (size_t)b * T * D + dc);
+
+  // buffer descriptors over this sequence: scalar row offsets, per-lane channel offsets
+  const unsigned seq_bytes = (unsigned)((size_t)T * D * 2);
+  const unsigned row_bytes = (unsigned)D * 2;
+  const __amdgpu_buffer_rsrc_t u_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void *)((const unsigned short *)p.u + (size_t)b * T * D), 0, seq_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void *)((unsigned short *)p.y + (size_t)b * T * D), 0, seq_bytes, 0x00020000);
+  const unsigned u_voff = (unsigned)dc * 2;
+  const unsigned y_voff = (unsigned)d * 2 + (unsigned)hf * 16 * row_bytes;
   const unsigned *st32 =
       p.state_in ? (const unsigned *)((const unsigned short *)p.state_in + (size_t)b * 3 * D + dc) : nullptr;
 
-  auto conv_tile = [&](int t0, int buf) {
-    // inputs t0+8rg-3 .. t0+8rg+7 of the channel pair
-    unsigned raw[11];
+  unsigned raw[11];  // inputs t0+8rg-3 .. t0+8rg+7 of the channel pair
+  auto load_rows = [&](int t0) {
+    const int tb = t0 + 8 * rg - 3;
+    if (tb >= 0 && tb + 11 <= T) {
 #pragma unroll
-    for (int n = 0; n < 11; ++n) {
-      const int t = t0 + 8 * rg - 3 + n;
-      unsigned v = 0;
-      if (t >= 0) {
-        if (t < T) v = u32[(size_t)t * (D / 2)];
-      } else if (st32) {
-        v = st32[(size_t)ring_slot(p.pos0 + t) * (D / 2)];
+      for (int n = 0; n < 11; ++n)
+        raw[n] = __builtin_amdgcn_raw_buffer_load_b32(u_rsrc, u_voff, (unsigned)(tb + n) * row_bytes, 0);
+    } else {  // first or last rows of the sequence (uniform over the wave)
+#pragma unroll
+      for (int n = 0; n < 11; ++n) {
+        const int t = tb + n;
+        unsigned v = 0;
+        if (t >= 0) {
+          if (t < T) v = __builtin_amdgcn_raw_buffer_load_b32(u_rsrc, u_voff, (unsigned)t * row_bytes, 0);
+        } else if (st32) {
+          v = st32[(size_t)ring_slot(p.pos0 + t) * (D / 2)];
+        }
+        raw[n] = v;
       }
-      raw[n] = v;
     }
+  };
+  unsigned short *xw = xs + (8 * rg) * XS + 2 * c2;
+  auto conv_rows = [&](int buf) {
+    const f32x4 w01 = cw_lds[c2], w23 = cw_lds[128 + c2], bb = cw_lds[256 + c2];
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
-      float x0 = cb[0], x1 = cb[1];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        x0 = fmaf(cw[k][0], bf_lo(raw[r + 3 - k]), x0);
-        x1 = fmaf(cw[k][1], bf_hi(raw[r + 3 - k]), x1);
-      }
-      const int t = t0 + 8 * rg + r;
-      const unsigned packed = t < T ? pack_bf16(x0, x1) : 0u;
-      *(unsigned *)&xs[buf][(8 * rg + r) * XS + 2 * c2] = packed;
+      float x0 = bb[0], x1 = bb[1];
+      x0 = fmaf(w01[0], bf_lo(raw[r + 3]), x0); x1 = fmaf(w01[1], bf_hi(raw[r + 3]), x1);
+      x0 = fmaf(w01[2], bf_lo(raw[r + 2]), x0); x1 = fmaf(w01[3], bf_hi(raw[r + 2]), x1);
+      x0 = fmaf(w23[0], bf_lo(raw[r + 1]), x0); x1 = fmaf(w23[1], bf_hi(raw[r + 1]), x1);
+      x0 = fmaf(w23[2], bf_lo(raw[r]), x0);     x1 = fmaf(w23[3], bf_hi(raw[r]), x1);
+      *(unsigned *)(xw + buf * (TT * XS) + r * XS) = pack_bf16(x0, x1);
     }
   };
 
   // A-operand row of this lane: accumulator register r of lane half hf must be time hf*16+r
   const int arow = ((j >> 2) & 1) * 16 + (j >> 3) * 4 + (j & 3);
+  const unsigned short *arow_base = xs + arow * XS + hf * 8;
+  f32x4 *hold_mine = (f32x4 *)hold + (size_t)wv * 8 * 64 + lane;
 
-  float carry = (!MULTI && p.h0) ? p.h0[(size_t)b * D + d] : 0.f;  // state entering the next tile
-  unsigned short *yb = (unsigned short *)p.y + (size_t)b * T * D + d;
+  u64 *ring = GMAX > 1 ? a.rec + (size_t)unit * a.R * 2 * BS + ch : nullptr;
+  float carry = p.h0 ? p.h0[(size_t)b * D + d] : 0.f;  // state after this workgroup's previous tile
+  int spins = 0;
+
+  // four consecutive steps (quarter q) of this lane's run: h <- a h + b, y = h (eq. 4)
+  auto run_quarter = [&](int t0, int q, const f32x4 &av, const f32x4 &bv, float &h) {
+    const unsigned so = (unsigned)(t0 + 4 * q) * row_bytes;
+    const float h0v = fmaf(av[0], h, bv[0]), h1v = fmaf(av[1], h0v, bv[1]);
+    const float h2v = fmaf(av[2], h1v, bv[2]), h3v = fmaf(av[3], h2v, bv[3]);
+    h = h3v;
+    const unsigned p0 = pack_bf16(h0v, h1v), p1 = pack_bf16(h2v, h3v);
+    if (T - t0 >= TT) {
+      __builtin_amdgcn_raw_buffer_store_b16((short)(p0 & 0xffff), y_rsrc, y_voff, so, 0);
+      __builtin_amdgcn_raw_buffer_store_b16((short)(p0 >> 16), y_rsrc, y_voff, so + row_bytes, 0);
+      __builtin_amdgcn_raw_buffer_store_b16((short)(p1 & 0xffff), y_rsrc, y_voff, so + 2 * row_bytes, 0);
+      __builtin_amdgcn_raw_buffer_store_b16((short)(p1 >> 16), y_rsrc, y_voff, so + 3 * row_bytes, 0);
+    } else {
+      const int nvalid = T - t0 - hf * 16 - 4 * q;  // steps of this quarter inside the sequence
+      if (0 < nvalid) __builtin_amdgcn_raw_buffer_store_b16((short)(p0 & 0xffff), y_rsrc, y_voff, so, 0);
+      if (1 < nvalid) __builtin_amdgcn_raw_buffer_store_b16((short)(p0 >> 16), y_rsrc, y_voff, so + row_bytes, 0);
+      if (2 < nvalid) __builtin_amdgcn_raw_buffer_store_b16((short)(p1 & 0xffff), y_rsrc, y_voff, so + 2 * row_bytes, 0);
+      if (3 < nvalid) __builtin_amdgcn_raw_buffer_store_b16((short)(p1 >> 16), y_rsrc, y_voff, so + 3 * row_bytes, 0);
+    }
+  };
+
+  // state of the held tile (its local scan sits in LDS until the next iteration)
+  int held = -1;
+  float hA_lo = 1.f, hH_lo = 0.f, hA_t = 1.f, hH_t = 0.f;  // aggregates of the tile parked in LDS
+  u64 recA[GMAX > 1 ? GMAX - 1 : 1], recH[GMAX > 1 ? GMAX - 1 : 1];
+
+  auto fetch_records = [&](int t) {  // aggregates of the G-1 tiles before tile t
+#pragma unroll
+    for (int s = 0; s < GMAX - 1; ++s) {
+      const int k = t - (G - 1) + s;
+      if (s < G - 1 && k >= 0) {
+        const u64 *slot = ring + (size_t)(k % a.R) * 2 * BS;
+        recA[s] = peek(slot);
+        recH[s] = peek(slot + BS);
+      }
+    }
+  };
+  // finish tile t: carry the state across the tiles of the other slices, write y
+  auto resolve = [&](int t) {
+    float h = carry;
+#pragma unroll
+    for (int s = 0; s < GMAX - 1; ++s) {
+      const int k = t - (G - 1) + s;
+      if (s < G - 1 && k >= 0) {
+        const u64 *slot = ring + (size_t)(k % a.R) * 2 * BS;
+        const unsigned want = (unsigned)(k + 1);
+        while ((unsigned)(recA[s] >> 32) != want && spins < SPIN_LIMIT) {
+          ++spins;
+          __builtin_amdgcn_s_sleep(1);
+          recA[s] = peek(slot);
+        }
+        while ((unsigned)(recH[s] >> 32) != want && spins < SPIN_LIMIT) {
+          ++spins;
+          __builtin_amdgcn_s_sleep(1);
+          recH[s] = peek(slot + BS);
+        }
+        h = fmaf(__uint_as_float((unsigned)recA[s]), h, __uint_as_float((unsigned)recH[s]));
+      }
+    }
+    float hrun = hf ? fmaf(hA_lo, h, hH_lo) : h;  // state entering this lane's run
+#pragma unroll
+    for (int q = 0; q < 4; ++q) run_quarter(t * TT, q, hold_mine[q * 64], hold_mine[(q + 4) * 64], hrun);
+    carry = fmaf(hA_t, h, hH_t);
+  };
 
   int tile = w;
-  if (tile < a.ntile) conv_tile(tile * TT, 0);
+  if (tile < a.ntile) load_rows(tile * TT);
+  __syncthreads();  // the constants parked in LDS are visible to every wave
+  if (tile < a.ntile) conv_rows(0);
   __syncthreads();
 
-  for (int it = 0; tile < a.ntile; tile += a.G, ++it) {
+  for (int it = 0; tile < a.ntile; tile += G, ++it) {
     const int buf = it & 1, t0 = tile * TT;
+    const int next = tile + G;
+    if (next < a.ntile) load_rows(next * TT);       // lands while this tile is computed
+    if (GMAX > 1 && held >= 0) fetch_records(held);
+
     // ---- gate pre-activations on the matrix cores
     f32x16 accp, accq, accx;
 #pragma unroll
@@ -186,124 +301,116 @@ fwd_mfma_kernel(FwdArgs a) {
       accq[r] = bias_q;
       accx[r] = 0.f;
     }
-    const unsigned short *arow_ptr = &xs[buf][arow * XS + hf * 8];
+    const unsigned short *ap = arow_base + buf * (TT * XS);
+    {
+      bf16x8 a0 = *(const bf16x8 *)(ap), a1 = *(const bf16x8 *)(ap + 16);
 #pragma unroll
-    for (int ks = 0; ks < 16; ++ks) {
-      const bf16x8 av = *(const bf16x8 *)(arow_ptr + ks * 16);
-      accp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, wa[ks], accp, 0, 0, 0);
-      accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, wx[ks], accq, 0, 0, 0);
+      for (int ks = 0; ks < 16; ++ks) {
+        const bf16x8 a2 = *(const bf16x8 *)(ap + ((ks + 2) & 15) * 16);  // two steps ahead
+        accp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wa[ks], accp, 0, 0, 0);
+        accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wx[ks], accq, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        a0 = a1;
+        a1 = a2;
+      }
     }
     {
-      const bf16x8 a0 = *(const bf16x8 *)(arow_ptr + (2 * wv) * 16);
-      const bf16x8 a1 = *(const bf16x8 *)(arow_ptr + (2 * wv + 1) * 16);
-      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, sel0, accx, 0, 0, 0);
-      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, sel1, accx, 0, 0, 0);
+      const bf16x8 s0 = *(const bf16x8 *)(ap + (2 * wv) * 16);
+      const bf16x8 s1 = *(const bf16x8 *)(ap + (2 * wv + 1) * 16);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(s0, sel_lds[lane], accx, 0, 0, 0);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(s1, sel_lds[64 + lane], accx, 0, 0, 0);
     }
 
-    // ---- gates and the 16-step scan of this lane (zero incoming state)
-    const int nvalid = min(TT, T - t0) - hf * 16;  // valid steps of this lane's run (may be <= 0)
-    float hl[16], pr[16];
+    // ---- the tile parked in LDS one iteration ago can be finished now
+    if (GMAX > 1 && held >= 0) resolve(held);
+
+    // ---- gates (eqs. 1-3); the (a_t, b_t) pairs go to LDS, the lane keeps the aggregate of
+    // its 16-step run: prun = prod a, hrun = end state for a zero incoming state
     float hrun = 0.f, prun = 1.f;
     if (T - t0 >= TT) {  // full tile (uniform over the workgroup)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float av, bv;
-        gate_fast(accp[r], accq[r], accx[r], kd, av, bv);
-        hrun = fmaf(av, hrun, bv);
-        prun *= av;
-        hl[r] = hrun;
-        pr[r] = prun;
+      for (int q = 0; q < 4; ++q) {
+        f32x4 aq, bq;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float av, bv;
+          gate_fast(accp[4 * q + e], accq[4 * q + e], accx[4 * q + e], kd, av, bv);
+          hrun = fmaf(av, hrun, bv);
+          prun *= av;
+          aq[e] = av;
+          bq[e] = bv;
+        }
+        hold_mine[q * 64] = aq;
+        hold_mine[(q + 4) * 64] = bq;
       }
     } else {
+      const int nvalid = T - t0 - hf * 16;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float av, bv;
-        gate_fast(accp[r], accq[r], accx[r], kd, av, bv);
-        if (r >= nvalid) {  // steps past the end of the sequence leave the state untouched
-          av = 1.f;
-          bv = 0.f;
+      for (int q = 0; q < 4; ++q) {
+        f32x4 aq, bq;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float av, bv;
+          gate_fast(accp[4 * q + e], accq[4 * q + e], accx[4 * q + e], kd, av, bv);
+          if (4 * q + e >= nvalid) {  // steps past the end of the sequence leave the state untouched
+            av = 1.f;
+            bv = 0.f;
+          }
+          hrun = fmaf(av, hrun, bv);
+          prun *= av;
+          aq[e] = av;
+          bq[e] = bv;
         }
-        hrun = fmaf(av, hrun, bv);
-        prun *= av;
-        hl[r] = hrun;
-        pr[r] = prun;
+        hold_mine[q * 64] = aq;
+        hold_mine[(q + 4) * 64] = bq;
       }
     }
     // ---- combine the two lane halves: lower half = steps 0..15, upper = 16..31
-    const float oA = __shfl_xor(prun, 32), oH = __shfl_xor(hrun, 32);
-    const float A_lo = hf ? oA : prun, H_lo = hf ? oH : hrun;
-    const float A_up = hf ? prun : oA, H_up = hf ? hrun : oH;
-    const float A_tile = A_lo * A_up, H_tile = fmaf(A_up, H_lo, H_up);
-
-    float h_in;
-    if (MULTI) {
-      u64 *ring = a.rec + (size_t)unit * a.R * 2 * BS;
-      u64 *mine = ring + (size_t)(tile % a.R) * 2 * BS;
-      const unsigned tagbase = (unsigned)(tile + 1) << 2;
-      // publish the aggregate: lower half writes A, upper half writes H
-      publish(mine + hf * BS + ch, hf ? H_tile : A_tile, tagbase | TAG_AGG);
-      // look back
-      float accA = 1.f, accH = 0.f;
-      int k = tile - 1;
-      int spins = 0;
-      bool found = false;
-      while (k >= 0 && !found) {
-        const u64 *slot = ring + (size_t)(k % a.R) * 2 * BS;
-        const unsigned want = (unsigned)(k + 1) << 2;
-        u64 rh = peek(slot + BS + ch);
-        while (((unsigned)(rh >> 32) & ~3u) != want) {
-          if (++spins > SPIN_LIMIT) break;
-          __builtin_amdgcn_s_sleep(2);
-          rh = peek(slot + BS + ch);
-        }
-        if (spins > SPIN_LIMIT) break;
-        const float hv = __uint_as_float((unsigned)rh);
-        if (((unsigned)(rh >> 32) & 3u) == TAG_INCL) {
-          accH = fmaf(accA, hv, accH);
-          found = true;
-        } else {
-          u64 ra = peek(slot + ch);
-          while (((unsigned)(ra >> 32) & ~3u) != want) {
-            if (++spins > SPIN_LIMIT) break;
-            __builtin_amdgcn_s_sleep(2);
-            ra = peek(slot + ch);
-          }
-          if (spins > SPIN_LIMIT) break;
-          accH = fmaf(accA, hv, accH);
-          accA *= __uint_as_float((unsigned)ra);
-          --k;
-        }
-      }
-      if (spins > SPIN_LIMIT) *a.err = 1;
-      if (!found) {  // reached the start of the sequence
-        const float h0v = p.h0 ? p.h0[(size_t)b * D + d] : 0.f;
-        accH = fmaf(accA, h0v, accH);
-      }
-      h_in = accH;
-      const float h_end = fmaf(A_tile, h_in, H_tile);
-      if (hf) publish(mine + BS + ch, h_end, tagbase | TAG_INCL);
-      carry = h_end;
-    } else {
-      h_in = carry;
-      carry = fmaf(A_tile, h_in, H_tile);
+    {
+      const float oA = __shfl_xor(prun, 32), oH = __shfl_xor(hrun, 32);
+      hA_lo = hf ? oA : prun;
+      hH_lo = hf ? oH : hrun;
+      const float A_up = hf ? prun : oA, H_up = hf ? hrun : oH;
+      hA_t = hA_lo * A_up;
+      hH_t = fmaf(A_up, hH_lo, H_up);
     }
-
-    // ---- outputs: y_t = local state + (product of a up to t) * state entering the run
-    const float hin_seg = hf ? fmaf(A_lo, h_in, H_lo) : h_in;
-    unsigned short *yrow = yb + (size_t)(t0 + hf * 16) * D;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      if (r < nvalid) yrow[(size_t)r * D] = f32_to_bf16_bits(fmaf(pr[r], hin_seg, hl[r]));
+    if (GMAX > 1) {
+      // publish the aggregate: lower half writes A, upper half writes H
+      publish(ring + (size_t)(tile % a.R) * 2 * BS + hf * BS, hf ? hH_t : hA_t, (unsigned)(tile + 1));
+      held = tile;
+    } else {
+      resolve(tile);
     }
 
     // ---- next tile of this workgroup into the other LDS buffer
-    const int next = tile + a.G;
-    if (next < a.ntile) conv_tile(next * TT, buf ^ 1);
+    if (next < a.ntile) conv_rows(buf ^ 1);
     __syncthreads();
   }
+  if (GMAX > 1 && held >= 0) {
+    fetch_records(held);
+    resolve(held);
+    if (spins >= SPIN_LIMIT) *a.err = 1;
+  }
 
-  // the workgroup that ran the last tile owns the final state
-  if (p.hT && (a.ntile - 1) % a.G == w && hf == 0) p.hT[(size_t)b * D + d] = carry;
+  // the workgroup that ran the last tile owns the final states
+  if ((a.ntile - 1) % G == w) {
+    if (p.hT && hf == 0) p.hT[(size_t)b * D + d] = carry;
+    if (p.state_out && tid < 128) {
+      // ring slots of the last three inputs; older slots are carried over (Appendix F state)
+      unsigned *so32 = (unsigned *)((unsigned short *)p.state_out + (size_t)b * 3 * D + dc);
+      const long long end = p.pos0 + T;
+#pragma unroll
+      for (int slot = 0; slot < 3; ++slot) {
+        const long long npos = end - 1 - ring_slot(end - 1 - slot);
+        unsigned v = 0;
+        if (npos >= p.pos0)
+          v = __builtin_amdgcn_raw_buffer_load_b32(u_rsrc, u_voff, (unsigned)(npos - p.pos0) * row_bytes, 0);
+        else if (st32)
+          v = st32[(size_t)slot * (D / 2)];
+        so32[(size_t)slot * (D / 2)] = v;
+      }
+    }
+  }
 }
 
 }  // namespace
@@ -324,17 +431,19 @@ static int num_cu() {
 }
 
 bool forward_mfma_supported(const Problem &p, bool bf) {
-  return bf && p.bs == BS && p.T >= 1 && ((uintptr_t)p.W_a % 16 == 0) &&
-         ((uintptr_t)p.W_x % 16 == 0) && ((uintptr_t)p.u % 4 == 0) &&
-         (!p.state_in || (uintptr_t)p.state_in % 4 == 0);
+  return bf && p.bs == BS && p.T >= 1 && (size_t)p.T * p.D * 2 < ((size_t)1 << 32) &&
+         ((uintptr_t)p.W_a % 16 == 0) && ((uintptr_t)p.W_x % 16 == 0) && ((uintptr_t)p.u % 4 == 0) &&
+         (!p.state_in || (uintptr_t)p.state_in % 4 == 0) &&
+         (!p.state_out || (uintptr_t)p.state_out % 4 == 0);
 }
 
-// time slices per (sequence, block): as many as keep every workgroup resident at once
+// time slices per (sequence, block): as many as keep every workgroup resident at once, at
+// most 8 (every tile reads the aggregates of the G-1 tiles before it)
 static int pick_slices(int units, int ntile, int ncu) {
   int G = ncu / units;
   if (G < 1) G = 1;
   if (G > ntile) G = ntile;
-  if (G > 32) G = 32;
+  if (G > 8) G = 8;
   return G;
 }
 
@@ -344,8 +453,22 @@ size_t forward_mfma_ws_bytes(int B, int T, int D, int nb) {
   const int units = B * nb, ntile = (T + TT - 1) / TT;
   const int G = pick_slices(units, ntile, 256);
   if (G == 1) return 0;
-  const size_t R = 4 * (size_t)G;
+  const size_t R = 8 * (size_t)G;
   return 256 + (size_t)units * R * 2 * BS * sizeof(u64);
+}
+
+template <int GMAX>
+static hipError_t launch_t(const FwdArgs &a, int grid, size_t lds, hipStream_t s) {
+  static bool configured = false;  // the kernel asks for more than the default LDS limit
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void *)fwd_mfma_kernel<GMAX>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       XS_BYTES + CONST_BYTES + HOLD_BYTES);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  hipLaunchKernelGGL(fwd_mfma_kernel<GMAX>, dim3(grid), dim3(NTHR), lds, s, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_forward_mfma(const Problem &p, hipStream_t s) {
@@ -356,23 +479,23 @@ hipError_t launch_forward_mfma(const Problem &p, hipStream_t s) {
   int ncu = num_cu();
   if (ncu > 256) ncu = 256;  // the workspace is sized for at most 256 resident workgroups
   a.G = pick_slices(units, a.ntile, ncu);
-  a.R = 4 * a.G;
+  a.R = 8 * a.G;
   const int grid = units * a.G;
   a.swizzle = (a.G > 1 && grid % 8 == 0) ? 1 : 0;
   if (a.G == 1) {
     a.rec = nullptr;
     a.err = nullptr;
-    hipLaunchKernelGGL(fwd_mfma_kernel<false>, dim3(grid), dim3(NTHR), 0, s, a);
-    return hipGetLastError();
+    return launch_t<1>(a, grid, XS_BYTES + CONST_BYTES + HOLD_BYTES, s);
   }
   a.err = (int *)p.ws;
   a.rec = (u64 *)((char *)p.ws + 256);
-  const size_t nwords = 32 + (size_t)units * a.R * 2 * BS;
-  hipLaunchKernelGGL(zero_words_kernel, dim3(256), dim3(256), 0, s, (u64 *)p.ws, nwords);
+  const size_t n16 = (256 + (size_t)units * a.R * 2 * BS * sizeof(u64)) / 16;
+  hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s,
+                     (uint4 *)p.ws, n16);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(fwd_mfma_kernel<true>, dim3(grid), dim3(NTHR), 0, s, a);
-  return hipGetLastError();
+  return a.G <= 4 ? launch_t<4>(a, grid, XS_BYTES + CONST_BYTES + HOLD_BYTES, s)
+                  : launch_t<8>(a, grid, XS_BYTES + CONST_BYTES + HOLD_BYTES, s);
 }
 
 }  // namespace rglru
