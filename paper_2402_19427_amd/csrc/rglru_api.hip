@@ -113,6 +113,9 @@ void fill_params(Problem &q, const rglru_shape *s, const rglru_params *p) {
 size_t workspace_need(const rglru_shape *s, int op) {
   switch (op) {
     case RGLRU_OP_BACKWARD:
+      if (s->act_dtype == RGLRU_BF16 && s->D / s->num_blocks == 256 &&
+          (size_t)s->T * s->D * 4 < ((size_t)1 << 32))
+        return backward_mfma_ws_bytes(s->B, s->T, s->D, s->num_blocks);
       return backward_generic_ws_bytes(s->B, s->T, s->D, s->num_blocks);
     case RGLRU_OP_FORWARD:
       if (s->act_dtype == RGLRU_BF16 && s->D / s->num_blocks == 256 && s->T >= 1)
@@ -266,7 +269,15 @@ int rglru_backward(const rglru_shape *shape, const rglru_params *params, const v
   q.y_in = y; q.dy = dy; q.dhT = dhT; q.du = du; q.dh0 = dh0; q.g = *grads;
   q.ws = workspace; q.ws_bytes = workspace_bytes;
   const bool bf = shape->act_dtype == RGLRU_BF16;
-  hipError_t e = launch_backward_generic(q, bf, (hipStream_t)stream);
+  hipError_t e;
+  if (backward_mfma_supported(q, bf)) {
+    e = launch_backward_mfma(q, (hipStream_t)stream);
+  } else {
+    // pointers too loosely aligned for the MFMA kernels: the generic kernels need more scratch
+    CHECK(check_workspace(workspace, workspace_bytes,
+                          backward_generic_ws_bytes(shape->B, shape->T, shape->D, shape->num_blocks)));
+    e = launch_backward_generic(q, bf, (hipStream_t)stream);
+  }
   if (e != hipSuccess) return hip_fail(e, "backward launch");
   g_err[0] = 0;
   return RGLRU_OK;

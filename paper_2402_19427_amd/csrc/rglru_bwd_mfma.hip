@@ -1,0 +1,979 @@
+// Backward for bf16 storage and gate blocks of 256 channels (gfx950), in three kernels:
+//
+//  1. bwd_gates_kernel - walks each (sequence, gate block) backwards in tiles of 32 steps:
+//     recomputes the Conv1D and the gates (same MFMA layout as the forward kernel), runs the
+//     reverse scan eps_t = a_t (dy_t + eps_{t+1}) (so that delta_t = dy_t + eps_{t+1}) and forms
+//     the pointwise adjoints of Section 2.4 eqs. (1)-(4):
+//        dla_t = delta_t (h_t - g_t / m_t)      g = i x, m = sqrt(1 - a^2)
+//                (equal to delta a (h_{t-1} - a g / m) because a h_{t-1} = h_t - m g and
+//                 a^2 + m^2 = 1; it needs y_t only, never h0)
+//        dp_t  = -c softplus(-Lambda) dla_t r_t (1 - r_t)
+//        dq_t  = delta_t m_t g_t (1 - i_t)
+//        dxd_t = delta_t m_t i_t                 (the part of dx that bypasses the gates)
+//     and writes x, dp, dq, dxd (bf16) plus per-channel sums for db_a, db_x, dLambda.
+//     Time slices of one sequence exchange tile aggregates (prod a, local eps) as tagged 8-byte
+//     records; a first sweep over the tile computes a_t and the aggregate, a second sweep the
+//     adjoints once the incoming eps is known.
+//  2. bwd_dgrad_kernel - dx = dxd + dp W_a + dq W_x, the products on the matrix cores (transposed weights
+//     resident in registers), then the Conv1D adjoint: du_t = sum_k w_k dx_{t+k},
+//     dconv_w[k] = sum dx_t u_{t-k}, dconv_b = sum dx_t.
+//  3. bwd_wgrad_kernel - dW_a = dp^T x, dW_x = dq^T x with the time axis as the contraction.
+#include "rglru_mfma.h"
+
+namespace rglru {
+
+using namespace mfma;
+
+namespace {
+
+constexpr float LN2 = 0.6931471805599453f;
+constexpr int TS = TT + 8;                       // row stride (bf16) of the [channel][time] tiles
+constexpr int TR_BYTES = BS * TS * 2;            // one transposed tile
+// LDS of the gates kernel: x tiles (high, low) | constants | dy^T | y^T | r_t of the tile
+constexpr int G_OFF_CONST = XS_BYTES;
+constexpr int G_OFF_DYT = G_OFF_CONST + CONST_BYTES;
+constexpr int G_OFF_YT = G_OFF_DYT + TR_BYTES;
+constexpr int G_OFF_HOLD = G_OFF_YT + TR_BYTES;
+constexpr int G_LDS = G_OFF_HOLD + HOLD_BYTES / 2;
+
+struct BwdArgs {
+  Problem p;
+  int G, ntile, R;
+  u64 *rec;
+  int *err;
+  int swizzle;
+  unsigned short *xo, *xlo, *dpo, *dqo;  // bf16 [B][T][D]: log2(e)*x (high part, low part), dp, dq
+  float *dxo;                             // f32 [B][T][D]: dxd (kept in fp32: du sums four taps of it
+                                          // with cancellation)
+  float *part;                            // [B*G][3][D]: sums for db_a, db_x, dLambda
+};
+
+// packs the low halves (sel = 0) or high halves (sel = 1) of two dwords of bf16 pairs
+__device__ __forceinline__ unsigned pick_halves(unsigned lo_src, unsigned hi_src, int sel) {
+  return sel ? __builtin_amdgcn_perm(hi_src, lo_src, 0x07060302u)   // hi16(hi_src) : hi16(lo_src)
+             : __builtin_amdgcn_perm(hi_src, lo_src, 0x05040100u);  // lo16(hi_src) : lo16(lo_src)
+}
+
+template <int GMAX>
+__global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
+bwd_gates_kernel(BwdArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned short *xs = (unsigned short *)smem;
+  bf16x8 *sel_lds = (bf16x8 *)(smem + G_OFF_CONST);
+  f32x4 *cw_lds = (f32x4 *)(smem + G_OFF_CONST + 64 * 32);
+  unsigned short *dyT = (unsigned short *)(smem + G_OFF_DYT);
+  unsigned short *yT = (unsigned short *)(smem + G_OFF_YT);
+  float *hold = (float *)(smem + G_OFF_HOLD);
+  const Problem &p = a.p;
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, j = lane & 31;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int G = GMAX == 1 ? 1 : a.G;
+
+  int bid = blockIdx.x;
+  if (GMAX > 1 && a.swizzle) {
+    const int per = gridDim.x >> 3;
+    bid = (bid & 7) * per + (bid >> 3);
+  }
+  const int unit = bid / G, w = bid - unit * G;
+  const int b = unit / p.nb, g = unit - b * p.nb;
+  const int D = p.D, T = p.T;
+  const int ch = wv * 32 + j;
+  const int d = g * BS + ch;
+
+  bf16x8 wa[16], wx[16];
+  {
+    const bf16x8 *pa = (const bf16x8 *)((const unsigned short *)p.W_a + ((size_t)g * BS + ch) * BS + hf * 8);
+    const bf16x8 *px = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) {
+      wa[ks] = pa[ks * 2];
+      wx[ks] = px[ks * 2];
+    }
+  }
+  if (tid < 64) {
+    bf16x8 sel0, sel1;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      sel0[e] = (__bf16)((hf * 8 + e == j) ? 1.0f : 0.0f);
+      sel1[e] = (__bf16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
+    }
+    sel_lds[lane] = sel0;
+    sel_lds[64 + lane] = sel1;
+  }
+  const float bias_p = p.b_a[d] * LOG2E, bias_q = p.b_x[d] * LOG2E;
+  float kd, kd_ln, lam_scale;
+  {
+    const float z = -p.Lambda[d];
+    const float sp = z > 0.f ? z + log1pf(expf(-z)) : log1pf(expf(z));  // softplus(-Lambda)
+    kd_ln = -p.c * sp;
+    kd = kd_ln * LOG2E;
+    lam_scale = p.c / (1.f + expf(-z));  // c * sigmoid(-Lambda) = c * (1 - sigmoid(Lambda))
+  }
+
+  const int c2 = tid & 127;
+  const int rg = __builtin_amdgcn_readfirstlane(tid >> 7);
+  const int dc = g * BS + 2 * c2;
+  if (tid < 128) {
+    f32x4 t0v, t1v, t2v;
+    t0v[0] = p.conv_w[dc] * LOG2E;                  t0v[1] = p.conv_w[dc + 1] * LOG2E;
+    t0v[2] = p.conv_w[(size_t)D + dc] * LOG2E;      t0v[3] = p.conv_w[(size_t)D + dc + 1] * LOG2E;
+    t1v[0] = p.conv_w[(size_t)2 * D + dc] * LOG2E;  t1v[1] = p.conv_w[(size_t)2 * D + dc + 1] * LOG2E;
+    t1v[2] = p.conv_w[(size_t)3 * D + dc] * LOG2E;  t1v[3] = p.conv_w[(size_t)3 * D + dc + 1] * LOG2E;
+    t2v[0] = p.conv_b ? p.conv_b[dc] * LOG2E : 0.f;
+    t2v[1] = p.conv_b ? p.conv_b[dc + 1] * LOG2E : 0.f;
+    t2v[2] = t2v[3] = 0.f;
+    cw_lds[c2] = t0v;
+    cw_lds[128 + c2] = t1v;
+    cw_lds[256 + c2] = t2v;
+  }
+
+  const unsigned seq_bytes = (unsigned)((size_t)T * D * 2);
+  const unsigned row_bytes = (unsigned)D * 2;
+  const size_t seq_off = (size_t)b * T * D;
+  auto rsrc = [&](const void *base) {
+    return __builtin_amdgcn_make_buffer_rsrc(uniform_ptr((const unsigned short *)base + seq_off), 0,
+                                             seq_bytes, 0x00020000);
+  };
+  const __amdgpu_buffer_rsrc_t u_rsrc = rsrc(p.u), y_rsrc = rsrc(p.y_in), dy_rsrc = rsrc(p.dy);
+  const __amdgpu_buffer_rsrc_t xo_rsrc = rsrc(a.xo), xl_rsrc = rsrc(a.xlo), dp_rsrc = rsrc(a.dpo),
+                               dq_rsrc = rsrc(a.dqo);
+  const __amdgpu_buffer_rsrc_t dx_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_ptr(a.dxo + seq_off), 0, 2 * seq_bytes, 0x00020000);
+  const unsigned c_voff = (unsigned)dc * 2;                                   // channel pair
+  const unsigned o_voff = (unsigned)d * 2 + (unsigned)hf * 16 * row_bytes;    // channel, lane half
+  const unsigned *st32 =
+      p.state_in ? (const unsigned *)((const unsigned short *)p.state_in + (size_t)b * 3 * D + dc) : nullptr;
+
+  unsigned raw[11];
+  auto load_rows = [&](int t0) {
+    const int tb = t0 + 8 * rg - 3;
+    if (tb >= 0 && tb + 11 <= T) {
+#pragma unroll
+      for (int n = 0; n < 11; ++n)
+        raw[n] = __builtin_amdgcn_raw_buffer_load_b32(u_rsrc, c_voff, (unsigned)(tb + n) * row_bytes, 0);
+    } else {
+#pragma unroll
+      for (int n = 0; n < 11; ++n) {
+        const int t = tb + n;
+        unsigned v = 0;
+        if (t >= 0) {
+          if (t < T) v = __builtin_amdgcn_raw_buffer_load_b32(u_rsrc, c_voff, (unsigned)t * row_bytes, 0);
+        } else if (st32) {
+          v = st32[(size_t)ring_slot(p.pos0 + t) * (D / 2)];
+        }
+        raw[n] = v;
+      }
+    }
+  };
+  unsigned short *xw = xs + (8 * rg) * XS + 2 * c2;
+  // Conv1D rows of tile t0 into LDS buffer `buf` and into the x workspace
+  auto conv_rows = [&](int t0, int buf) {
+    const f32x4 w01 = cw_lds[c2], w23 = cw_lds[128 + c2], bb = cw_lds[256 + c2];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      float x0 = bb[0], x1 = bb[1];
+      x0 = fmaf(w01[0], bf_lo(raw[r + 3]), x0); x1 = fmaf(w01[1], bf_hi(raw[r + 3]), x1);
+      x0 = fmaf(w01[2], bf_lo(raw[r + 2]), x0); x1 = fmaf(w01[3], bf_hi(raw[r + 2]), x1);
+      x0 = fmaf(w23[0], bf_lo(raw[r + 1]), x0); x1 = fmaf(w23[1], bf_hi(raw[r + 1]), x1);
+      x0 = fmaf(w23[2], bf_lo(raw[r]), x0);     x1 = fmaf(w23[3], bf_hi(raw[r]), x1);
+      unsigned hi_pk, lo_pk;
+      split_bf16(x0, x1, hi_pk, lo_pk);
+      *(unsigned *)(xw + buf * (2 * XT_ELEMS) + r * XS) = hi_pk;
+      *(unsigned *)(xw + buf * (2 * XT_ELEMS) + XT_ELEMS + r * XS) = lo_pk;
+      const int t = t0 + 8 * rg + r;
+      if (t < T) {
+        __builtin_amdgcn_raw_buffer_store_b32(hi_pk, xo_rsrc, c_voff, (unsigned)t * row_bytes, 0);
+        __builtin_amdgcn_raw_buffer_store_b32(lo_pk, xl_rsrc, c_voff, (unsigned)t * row_bytes, 0);
+      }
+    }
+  };
+  // dy and y rows 8*rg..8*rg+7 of tile t0 for the channel pair (zero past the sequence end)
+  unsigned rdy[8], ry[8];
+  auto load_dy_y = [&](int t0) {
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const int t = t0 + 8 * rg + r;
+      unsigned v0 = 0, v1 = 0;
+      if (t < T) {
+        v0 = __builtin_amdgcn_raw_buffer_load_b32(dy_rsrc, c_voff, (unsigned)t * row_bytes, 0);
+        v1 = __builtin_amdgcn_raw_buffer_load_b32(y_rsrc, c_voff, (unsigned)t * row_bytes, 0);
+      }
+      rdy[r] = v0;
+      ry[r] = v1;
+    }
+  };
+  // transposed [channel][time] copies: 8 consecutive steps of one channel are 16 contiguous bytes
+  auto park_dy_y = [&]() {
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      uint4 vd, vy;
+      vd.x = pick_halves(rdy[0], rdy[1], c); vd.y = pick_halves(rdy[2], rdy[3], c);
+      vd.z = pick_halves(rdy[4], rdy[5], c); vd.w = pick_halves(rdy[6], rdy[7], c);
+      vy.x = pick_halves(ry[0], ry[1], c);   vy.y = pick_halves(ry[2], ry[3], c);
+      vy.z = pick_halves(ry[4], ry[5], c);   vy.w = pick_halves(ry[6], ry[7], c);
+      *(uint4 *)(dyT + (2 * c2 + c) * TS + 8 * rg) = vd;
+      *(uint4 *)(yT + (2 * c2 + c) * TS + 8 * rg) = vy;
+    }
+  };
+
+  const int arow = ((j >> 2) & 1) * 16 + (j >> 3) * 4 + (j & 3);
+  const unsigned short *arow_base = xs + arow * XS + hf * 8;
+  f32x4 *hold_mine = (f32x4 *)hold + (size_t)wv * 4 * 64 + lane;
+  const uint4 *dyT_mine = (const uint4 *)(dyT + ch * TS + hf * 16);
+  const uint4 *yT_mine = (const uint4 *)(yT + ch * TS + hf * 16);
+
+  u64 *ring = GMAX > 1 ? a.rec + (size_t)unit * a.R * 2 * BS + ch : nullptr;
+  float carry = p.dhT ? p.dhT[(size_t)b * D + d] : 0.f;  // eps entering this workgroup's next tile
+  float s_ba = 0.f, s_bx = 0.f, s_lam = 0.f;
+  int spins = 0;
+
+  // tiles are walked from the end of the sequence: this workgroup owns ntile-1-w, -G, ...
+  int tile = a.ntile - 1 - w;
+  if (tile >= 0) load_rows(tile * TT);
+  __syncthreads();
+  if (tile >= 0) conv_rows(tile * TT, 0);
+  __syncthreads();
+
+  for (int it = 0; tile >= 0; tile -= G, ++it) {
+    const int buf = it & 1, t0 = tile * TT;
+    const int next = tile - G;
+    if (next >= 0) load_rows(next * TT);
+    load_dy_y(t0);
+
+    // ---- gate pre-activations on the matrix cores
+    f32x16 accp, accq, accx;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      accp[r] = bias_p;
+      accq[r] = bias_q;
+      accx[r] = 0.f;
+    }
+    const unsigned short *ap = arow_base + buf * (2 * XT_ELEMS);
+    {
+      bf16x8 a0 = *(const bf16x8 *)(ap), a1 = *(const bf16x8 *)(ap + 16);
+#pragma unroll
+      for (int ks = 0; ks < 16; ++ks) {
+        const bf16x8 a2 = *(const bf16x8 *)(ap + ((ks + 2) & 15) * 16);
+        accp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wa[ks], accp, 0, 0, 0);
+        accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wx[ks], accq, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        a0 = a1;
+        a1 = a2;
+      }
+    }
+    {
+      const bf16x8 s0 = *(const bf16x8 *)(ap + (2 * wv) * 16);
+      const bf16x8 s1 = *(const bf16x8 *)(ap + (2 * wv + 1) * 16);
+      const bf16x8 l0 = *(const bf16x8 *)(ap + XT_ELEMS + (2 * wv) * 16);
+      const bf16x8 l1 = *(const bf16x8 *)(ap + XT_ELEMS + (2 * wv + 1) * 16);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(s0, sel_lds[lane], accx, 0, 0, 0);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(s1, sel_lds[64 + lane], accx, 0, 0, 0);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(l0, sel_lds[lane], accx, 0, 0, 0);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(l1, sel_lds[64 + lane], accx, 0, 0, 0);
+    }
+    park_dy_y();
+    __syncthreads();
+
+    // ---- first sweep (latest step first): r_t, a_t into LDS, aggregate of this lane's run:
+    // eps_out = prun * eps_in + erun
+    const int nvalid = T - t0 - hf * 16;  // steps of this lane's run inside the sequence
+    float erun = 0.f, prun = 1.f;
+#pragma unroll
+    for (int q = 3; q >= 0; --q) {
+      const uint4 dq4 = dyT_mine[q >> 1];
+      const unsigned d01 = (q & 1) ? dq4.z : dq4.x, d23 = (q & 1) ? dq4.w : dq4.y;
+      const float dyv[4] = {bf_lo(d01), bf_hi(d01), bf_lo(d23), bf_hi(d23)};
+      f32x4 rq;
+#pragma unroll
+      for (int e = 3; e >= 0; --e) {
+        const float ep = __builtin_amdgcn_exp2f(-accp[4 * q + e]);
+        const float rv = __builtin_amdgcn_rcpf(1.f + ep);
+        float av = __builtin_amdgcn_exp2f(kd * rv);
+        if (4 * q + e >= nvalid) av = 1.f;  // past the end: eps passes through (dy is zero there)
+        erun = av * (dyv[e] + erun);
+        prun *= av;
+        rq[e] = rv;
+      }
+      hold_mine[q * 64] = rq;
+    }
+    // ---- combine the lane halves; the upper half (later steps) is applied first
+    const float oA = __shfl_xor(prun, 32), oE = __shfl_xor(erun, 32);
+    const float A_up = hf ? prun : oA, E_up = hf ? erun : oE;
+    const float A_lo = hf ? oA : prun, E_lo = hf ? oE : erun;
+    const float A_t = A_lo * A_up, E_t = fmaf(A_lo, E_up, E_lo);
+
+    float e_in = carry;
+    if (GMAX > 1) {
+      publish(ring + (size_t)(tile % a.R) * 2 * BS + hf * BS, hf ? E_t : A_t, (unsigned)(tile + 1));
+      // eps entering this tile: own state after tile+G carried across tiles tile+G-1 .. tile+1
+#pragma unroll
+      for (int s = GMAX - 2; s >= 0; --s) {
+        const int k = tile + 1 + s;
+        if (s < G - 1 && k < a.ntile) {
+          const u64 *slot = ring + (size_t)(k % a.R) * 2 * BS;
+          const unsigned want = (unsigned)(k + 1);
+          u64 ra = peek(slot), re = peek(slot + BS);
+          while ((unsigned)(ra >> 32) != want && spins < SPIN_LIMIT) {
+            ++spins;
+            __builtin_amdgcn_s_sleep(1);
+            ra = peek(slot);
+          }
+          while ((unsigned)(re >> 32) != want && spins < SPIN_LIMIT) {
+            ++spins;
+            __builtin_amdgcn_s_sleep(1);
+            re = peek(slot + BS);
+          }
+          e_in = fmaf(__uint_as_float((unsigned)ra), e_in, __uint_as_float((unsigned)re));
+        }
+      }
+    }
+    carry = fmaf(A_t, e_in, E_t);
+
+    // ---- second sweep: adjoints with the true eps, latest step first
+    float erev = hf ? e_in : fmaf(A_up, e_in, E_up);  // eps_{t+1} for the last step of this run
+    const unsigned so = (unsigned)t0 * row_bytes;
+#pragma unroll
+    for (int q = 3; q >= 0; --q) {
+      const uint4 dq4 = dyT_mine[q >> 1], yq4 = yT_mine[q >> 1];
+      const unsigned d01 = (q & 1) ? dq4.z : dq4.x, d23 = (q & 1) ? dq4.w : dq4.y;
+      const unsigned y01 = (q & 1) ? yq4.z : yq4.x, y23 = (q & 1) ? yq4.w : yq4.y;
+      const float dyv[4] = {bf_lo(d01), bf_hi(d01), bf_lo(d23), bf_hi(d23)};
+      const float yv[4] = {bf_lo(y01), bf_hi(y01), bf_lo(y23), bf_hi(y23)};
+      const f32x4 rq = hold_mine[q * 64];
+      float dpv[4], dqv[4], dxv[4];
+#pragma unroll
+      for (int e = 3; e >= 0; --e) {
+        const float rv = rq[e];
+        const float av = __builtin_amdgcn_exp2f(kd * rv);
+        const bool ok = 4 * q + e < nvalid;
+        const float delta = ok ? dyv[e] + erev : 0.f;
+        const float m2 = fmaxf(fmaf(-av, av, 1.f), 1e-30f);
+        const float rs = __builtin_amdgcn_rsqf(m2);       // 1 / m
+        const float m = m2 * rs;
+        const float eq = __builtin_amdgcn_exp2f(-accq[4 * q + e]);
+        const float iv = __builtin_amdgcn_rcpf(1.f + eq);
+        const float gin = iv * (accx[4 * q + e] * LN2);   // i_t x_t
+        const float dla = delta * fmaf(-gin, rs, yv[e]);  // delta (h_t - g/m)
+        const float dg = delta * m;
+        dxv[e] = dg * iv;
+        dqv[e] = dg * gin * (1.f - iv);
+        dpv[e] = (kd_ln * dla) * fmaf(-rv, rv, rv);
+        s_lam = fmaf(dla, rv, s_lam);
+        s_ba += dpv[e];
+        s_bx += dqv[e];
+        erev = ok ? av * delta : erev;
+      }
+      const unsigned soq = so + (unsigned)(4 * q) * row_bytes;
+      const unsigned p0 = pack_bf16(dpv[0], dpv[1]), p1 = pack_bf16(dpv[2], dpv[3]);
+      const unsigned q0 = pack_bf16(dqv[0], dqv[1]), q1 = pack_bf16(dqv[2], dqv[3]);
+      const int nv = nvalid - 4 * q;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (e < nv) {
+          const unsigned pp = e < 2 ? p0 : p1, qq = e < 2 ? q0 : q1;
+          const short sp = (short)((e & 1) ? (pp >> 16) : (pp & 0xffff));
+          const short sq = (short)((e & 1) ? (qq >> 16) : (qq & 0xffff));
+          __builtin_amdgcn_raw_buffer_store_b16(sp, dp_rsrc, o_voff, soq + e * row_bytes, 0);
+          __builtin_amdgcn_raw_buffer_store_b16(sq, dq_rsrc, o_voff, soq + e * row_bytes, 0);
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(dxv[e]), dx_rsrc, 2 * o_voff,
+                                                2 * (soq + e * row_bytes), 0);
+        }
+      }
+    }
+
+    if (next >= 0) conv_rows(next * TT, buf ^ 1);
+    __syncthreads();
+  }
+  if (GMAX > 1 && spins >= SPIN_LIMIT) *a.err = 1;
+
+  // per-channel sums of this workgroup (both lane halves hold the same channel)
+  s_ba += __shfl_xor(s_ba, 32);
+  s_bx += __shfl_xor(s_bx, 32);
+  s_lam += __shfl_xor(s_lam, 32);
+  if (hf == 0) {
+    float *pp = a.part + ((size_t)(b * G + w) * 3) * D + d;
+    pp[0] = s_ba;
+    pp[D] = s_bx;
+    pp[2 * (size_t)D] = s_lam * lam_scale;
+    // the workgroup that ran tile 0 holds eps_0 = dL/dh0
+    if (p.dh0 && (a.ntile - 1 - w) % G == 0) p.dh0[(size_t)b * D + d] = carry;
+  }
+}
+
+
+// ------------------------------------------------------------------------------ dgrad
+// A tile: [32 steps][dp 256 | dq 256] bf16, row stride 520 elements (1040 B)
+constexpr int AS = 2 * BS + 8;
+constexpr int D_A_BYTES = 2 * TT * AS * 2;           // two A tiles
+constexpr int US_ROWS = TT + 3;                      // u rows t0-3 .. t0+31
+constexpr int D_OFF_SEL = D_A_BYTES;
+constexpr int D_OFF_U = D_OFF_SEL + 64 * 32;
+constexpr int D_LDS = D_OFF_U + US_ROWS * XS * 2;
+
+struct DgradArgs {
+  Problem p;
+  int C, ntile;                            // contiguous time chunks per unit, tiles per sequence
+  const unsigned short *dpo, *dqo;         // bf16 [B][T][D]
+  const float *dxo;                        // f32 [B][T][D]
+  const unsigned short *wta, *wtx;         // transposed gate weights [nb][in k][out j], bf16
+  float *part;                             // [B*C][5][D]: dconv_w[0..3], dconv_b partial sums
+};
+
+__global__ void __launch_bounds__(256) transpose_weights_kernel(const unsigned short *W,
+                                                                unsigned short *WT, int nmat) {
+  __shared__ unsigned short tile[32][33];
+  const int m = blockIdx.z, bx = blockIdx.x * 32, by = blockIdx.y * 32;
+  if (m >= nmat) return;
+  const unsigned short *src = W + (size_t)m * BS * BS;
+  unsigned short *dst = WT + (size_t)m * BS * BS;
+  for (int i = threadIdx.x; i < 32 * 32; i += 256) {
+    const int r = i >> 5, c = i & 31;
+    tile[r][c] = src[(size_t)(by + r) * BS + bx + c];
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 32 * 32; i += 256) {
+    const int r = i >> 5, c = i & 31;
+    dst[(size_t)(bx + r) * BS + by + c] = tile[c][r];
+  }
+}
+
+__global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
+bwd_dgrad_kernel(DgradArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned short *as = (unsigned short *)smem;                       // [2][TT][AS]
+  bf16x8 *sel_lds = (bf16x8 *)(smem + D_OFF_SEL);
+  unsigned short *us = (unsigned short *)(smem + D_OFF_U);           // [35][XS]
+  const Problem &p = a.p;
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, j = lane & 31;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int unit = blockIdx.x / a.C, c = blockIdx.x - unit * a.C;
+  const int b = unit / p.nb, g = unit - b * p.nb;
+  const int D = p.D, T = p.T;
+  const int ch = wv * 32 + j;   // input channel (column of the gate matrices) owned by this lane
+  const int d = g * BS + ch;
+
+  // transposed weights of this wave's 32 columns: B operand rows are output channels
+  bf16x8 wa[16], wx[16];
+  {
+    const bf16x8 *pa = (const bf16x8 *)(a.wta + ((size_t)g * BS + ch) * BS + hf * 8);
+    const bf16x8 *px = (const bf16x8 *)(a.wtx + ((size_t)g * BS + ch) * BS + hf * 8);
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) {
+      wa[ks] = pa[ks * 2];
+      wx[ks] = px[ks * 2];
+    }
+  }
+  if (tid < 64) {
+    bf16x8 sel0, sel1;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      sel0[e] = (__bf16)((hf * 8 + e == j) ? 1.0f : 0.0f);
+      sel1[e] = (__bf16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
+    }
+    sel_lds[lane] = sel0;
+    sel_lds[64 + lane] = sel1;
+  }
+  float cw[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) cw[k] = p.conv_w[(size_t)k * D + d];
+
+  const unsigned seq_bytes = (unsigned)((size_t)T * D * 2);
+  const unsigned row_bytes = (unsigned)D * 2;
+  const size_t seq_off = (size_t)b * T * D;
+  auto rsrc = [&](const void *base) {
+    return __builtin_amdgcn_make_buffer_rsrc(uniform_ptr((const unsigned short *)base + seq_off), 0,
+                                             seq_bytes, 0x00020000);
+  };
+  const __amdgpu_buffer_rsrc_t u_rsrc = rsrc(p.u), du_rsrc = rsrc(p.du);
+  const __amdgpu_buffer_rsrc_t dp_rsrc = rsrc(a.dpo), dq_rsrc = rsrc(a.dqo);
+  const __amdgpu_buffer_rsrc_t dx_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_ptr(a.dxo + seq_off), 0, 2 * seq_bytes, 0x00020000);
+  const unsigned o_voff = (unsigned)d * 2 + (unsigned)hf * 16 * row_bytes;
+
+  // loaders: 16 bytes (8 channels) per thread; a 512-byte row is covered by 32 threads
+  const int lc = tid & 31, lr = tid >> 5;               // channel group, row 0..15
+  const unsigned l_voff = (unsigned)(g * BS + 8 * lc) * 2;
+  uint4 ra[4];                                          // rows lr, lr+16 of dp, dq
+  auto load_a = [&](int t0) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int t = t0 + lr + 16 * h;
+      uint4 z = make_uint4(0, 0, 0, 0);
+      ra[h] = ra[2 + h] = z;
+      if (t < T) {
+        const unsigned so = (unsigned)t * row_bytes;
+        ra[h] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(dp_rsrc, l_voff, so, 0));
+        ra[2 + h] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(dq_rsrc, l_voff, so, 0));
+      }
+    }
+  };
+  auto park_a = [&](int buf) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      unsigned short *row = as + buf * (TT * AS) + (lr + 16 * h) * AS + 8 * lc;
+      *(uint4 *)(row) = ra[h];
+      *(uint4 *)(row + BS) = ra[2 + h];
+    }
+  };
+  // dxd of this lane's run (channel d, 16 consecutive steps), fp32, zero past the sequence end
+  float dxd[16];
+  auto load_dxd = [&](int t0) {
+    const int nvalid = T - t0 - hf * 16;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      dxd[r] = 0.f;
+      if (r < nvalid)
+        dxd[r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+            dx_rsrc, 2 * o_voff, 2 * (unsigned)(t0 + r) * row_bytes, 0));
+    }
+  };
+  // u rows t0-3 .. t0+31 (35 rows): rows lr, lr+16 and (for lr < 3) lr+32
+  const unsigned *st32 =
+      p.state_in ? (const unsigned *)((const unsigned short *)p.state_in + (size_t)b * 3 * D + g * BS + 8 * lc)
+                 : nullptr;
+  uint4 ru[3];
+  auto load_u = [&](int t0) {
+#pragma unroll
+    for (int h = 0; h < 3; ++h) {
+      const int rho = lr + 16 * h, t = t0 - 3 + rho;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (rho < US_ROWS) {
+        if (t >= 0) {
+          if (t < T) v = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(u_rsrc, l_voff, (unsigned)t * row_bytes, 0));
+        } else if (st32) {
+          v = *(const uint4 *)(st32 + (size_t)ring_slot(p.pos0 + t) * (D / 2));
+        }
+      }
+      ru[h] = v;
+    }
+  };
+  auto park_u = [&]() {
+#pragma unroll
+    for (int h = 0; h < 3; ++h) {
+      const int rho = lr + 16 * h;
+      if (rho < US_ROWS) *(uint4 *)(us + rho * XS + 8 * lc) = ru[h];
+    }
+  };
+
+  const int arow = ((j >> 2) & 1) * 16 + (j >> 3) * 4 + (j & 3);
+  const unsigned short *arow_base = as + arow * AS + hf * 8;
+  const unsigned short *urow_base = us + (arow + 3) * XS + (2 * wv) * 16 + hf * 8;
+
+  // this workgroup's tiles [lo, hi), walked backwards; tile hi (if any) only supplies the
+  // three dx rows that the Conv1D adjoint of tile hi-1 reaches into
+  const int per = (a.ntile + a.C - 1) / a.C;
+  const int lo = c * per, hi = min(a.ntile, lo + per);
+  float sw[4] = {0.f, 0.f, 0.f, 0.f}, sb = 0.f;
+  float nx0 = 0.f, nx1 = 0.f, nx2 = 0.f;  // dx at the first three steps of the next tile (upper half lanes)
+  if (lo < hi) {
+    int tile = hi < a.ntile ? hi : hi - 1;
+    load_a(tile * TT);
+    __syncthreads();
+    park_a(0);
+    __syncthreads();
+    for (int it = 0; tile >= lo; --tile, ++it) {
+      const int buf = it & 1, t0 = tile * TT;
+      const bool halo = tile == hi;
+      if (tile > lo) load_a((tile - 1) * TT);
+      if (!halo) load_u(t0);
+      load_dxd(t0);
+
+      f32x16 acc0, acc1;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc0[r] = acc1[r] = 0.f;
+      const unsigned short *ap = arow_base + buf * (TT * AS);
+      {
+        bf16x8 a0 = *(const bf16x8 *)(ap), a1 = *(const bf16x8 *)(ap + BS);
+#pragma unroll
+        for (int ks = 0; ks < 16; ++ks) {
+          const bf16x8 n0 = *(const bf16x8 *)(ap + ((ks + 1) & 15) * 16);
+          const bf16x8 n1 = *(const bf16x8 *)(ap + BS + ((ks + 1) & 15) * 16);
+          acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wa[ks], acc0, 0, 0, 0);
+          acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, wx[ks], acc1, 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          a0 = n0;
+          a1 = n1;
+        }
+      }
+      float dx[19];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dx[r] = dxd[r] + (acc0[r] + acc1[r]);
+      // steps 16..18 of this lane's run: the other half's first three (lower lanes) or the
+      // next tile's first three (upper lanes)
+      const float s0v = __shfl_xor(dx[0], 32), s1v = __shfl_xor(dx[1], 32), s2v = __shfl_xor(dx[2], 32);
+      dx[16] = hf ? nx0 : s0v;
+      dx[17] = hf ? nx1 : s1v;
+      dx[18] = hf ? nx2 : s2v;
+      nx0 = s0v; nx1 = s1v; nx2 = s2v;
+
+      if (!halo) {
+        park_u();
+        __syncthreads();
+        // Conv1D adjoint towards the input
+        const unsigned so = (unsigned)t0 * row_bytes;
+        const int nvalid = T - t0 - hf * 16;
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+          float v0 = cw[0] * dx[r], v1 = cw[0] * dx[r + 1];
+#pragma unroll
+          for (int k = 1; k < 4; ++k) {
+            v0 = fmaf(cw[k], dx[r + k], v0);
+            v1 = fmaf(cw[k], dx[r + 1 + k], v1);
+          }
+          const unsigned pk = pack_bf16(v0, v1);
+          if (r < nvalid)
+            __builtin_amdgcn_raw_buffer_store_b16((short)(pk & 0xffff), du_rsrc, o_voff, so + r * row_bytes, 0);
+          if (r + 1 < nvalid)
+            __builtin_amdgcn_raw_buffer_store_b16((short)(pk >> 16), du_rsrc, o_voff, so + (r + 1) * row_bytes, 0);
+        }
+        // Conv1D adjoint towards the taps: u_{t-k} in accumulator layout by selection
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          f32x16 au;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) au[r] = 0.f;
+          const unsigned short *up = urow_base - k * XS;
+          au = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(up), sel_lds[lane], au, 0, 0, 0);
+          au = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(up + 16), sel_lds[64 + lane], au, 0, 0, 0);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sw[k] = fmaf(dx[r], au[r], sw[k]);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sb += dx[r];
+      }
+      if (tile > lo) park_a(buf ^ 1);
+      __syncthreads();
+    }
+  }
+  // partial sums of this workgroup
+#pragma unroll
+  for (int k = 0; k < 4; ++k) sw[k] += __shfl_xor(sw[k], 32);
+  sb += __shfl_xor(sb, 32);
+  if (hf == 0) {
+    float *pp = a.part + ((size_t)(b * a.C + c) * 5) * D + d;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) pp[(size_t)k * D] = sw[k];
+    pp[(size_t)4 * D] = sb;
+  }
+}
+
+
+// ------------------------------------------------------------------------------ wgrad
+// One workgroup accumulates a 256 x 256 block dW[gate][g] over a slice of the B*T rows.
+// Wave (mw, nw) owns output rows 64*mw.. (2 blocks of 32) and columns 128*nw.. (4 blocks).
+// Both operands arrive as [time][channel] tiles; a selection MFMA turns a 32-channel column
+// block into (channel, 16 consecutive steps) registers, which packed to bf16 are exactly the
+// A / B fragments of a product that contracts over time.
+constexpr int W_TILE = TT * XS * 2;          // one [32][264] bf16 tile
+constexpr int W_OFF_SEL = 6 * W_TILE;        // two buffers x (dp|dq tile, x high tile, x low tile)
+constexpr int W_LDS = W_OFF_SEL + 64 * 32;
+
+struct WgradArgs {
+  int nb, S, D;
+  long long rows;                           // B*T
+  const unsigned short *dpo, *dqo, *xo, *xlo;  // bf16 [rows][D]
+  float *part;                              // [S][2][nb][256][256]
+};
+
+__global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
+bwd_wgrad_kernel(WgradArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16x8 *sel_lds = (bf16x8 *)(smem + W_OFF_SEL);
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, j = lane & 31;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int mw = wv >> 1, nw = wv & 1;
+  // block id -> (slice s, gate, block g); the two gates of a (g, s) pair are neighbours so
+  // that they find the shared x tile in the same L2
+  const int s = blockIdx.x / (2 * a.nb), rem = blockIdx.x - s * 2 * a.nb;
+  const int g = rem >> 1, gate = rem & 1;
+  const unsigned short *src = gate ? a.dqo : a.dpo;
+
+  if (tid < 64) {
+    bf16x8 sel0, sel1;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      sel0[e] = (__bf16)((hf * 8 + e == j) ? 1.0f : 0.0f);
+      sel1[e] = (__bf16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
+    }
+    sel_lds[lane] = sel0;
+    sel_lds[64 + lane] = sel1;
+  }
+
+  // rows of this slice, in steps of 32
+  const long long nstep_all = (a.rows + TT - 1) / TT;
+  const long long per = (nstep_all + a.S - 1) / a.S;
+  const long long st_lo = (long long)s * per, st_hi = st_lo + per < nstep_all ? st_lo + per : nstep_all;
+
+  // loaders: 16 bytes per thread, rows lr and lr+16 of both tiles
+  const int lc = tid & 31, lr = tid >> 5;
+  const unsigned short *gsrc = src + (size_t)g * BS + 8 * lc;
+  const unsigned short *gx = a.xo + (size_t)g * BS + 8 * lc;
+  const unsigned short *gxl = a.xlo + (size_t)g * BS + 8 * lc;
+  uint4 rl[6];
+  auto load_tiles = [&](long long step) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const long long row = step * TT + lr + 16 * h;
+      uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0, v2 = v0;
+      if (row < a.rows) {
+        v0 = *(const uint4 *)(gsrc + (size_t)row * a.D);
+        v1 = *(const uint4 *)(gx + (size_t)row * a.D);
+        v2 = *(const uint4 *)(gxl + (size_t)row * a.D);
+      }
+      rl[h] = v0;
+      rl[2 + h] = v1;
+      rl[4 + h] = v2;
+    }
+  };
+  auto park_tiles = [&](int buf) {
+    unsigned short *t0p = (unsigned short *)(smem + (size_t)buf * 3 * W_TILE);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      *(uint4 *)(t0p + (lr + 16 * h) * XS + 8 * lc) = rl[h];
+      *(uint4 *)(t0p + TT * XS + (lr + 16 * h) * XS + 8 * lc) = rl[2 + h];
+      *(uint4 *)(t0p + 2 * TT * XS + (lr + 16 * h) * XS + 8 * lc) = rl[4 + h];
+    }
+  };
+
+  const int arow = ((j >> 2) & 1) * 16 + (j >> 3) * 4 + (j & 3);
+  const int a_off = arow * XS + hf * 8;
+
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int m = 0; m < 2; ++m)
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
+
+  if (st_lo < st_hi) {
+    load_tiles(st_lo);
+    __syncthreads();
+    park_tiles(0);
+    __syncthreads();
+    int it = 0;
+    for (long long step = st_lo; step < st_hi; ++step, ++it) {
+      const int buf = it & 1;
+      if (step + 1 < st_hi) load_tiles(step + 1);
+      const unsigned short *tg = (const unsigned short *)(smem + (size_t)buf * 3 * W_TILE) + a_off;
+      const unsigned short *tx = tg + TT * XS, *txl = tg + 2 * TT * XS;
+      const bf16x8 sl0 = sel_lds[lane], sl1 = sel_lds[64 + lane];
+      // fragments: column block c of a tile -> two K-steps of 8 consecutive time steps per lane
+      auto fragments = [&](const unsigned short *tile, int cblk, bf16x8 &f0, bf16x8 &f1) {
+        f32x16 t;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t[r] = 0.f;
+        t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(tile + cblk * 32), sl0, t, 0, 0, 0);
+        t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(tile + cblk * 32 + 16), sl1, t, 0, 0, 0);
+        unsigned pk[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pk[e] = pack_bf16(t[2 * e], t[2 * e + 1]);
+        uint4 lo4 = make_uint4(pk[0], pk[1], pk[2], pk[3]), hi4 = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+        f0 = __builtin_bit_cast(bf16x8, lo4);
+        f1 = __builtin_bit_cast(bf16x8, hi4);
+      };
+      bf16x8 fa[2][2];
+#pragma unroll
+      for (int m = 0; m < 2; ++m) fragments(tg, 2 * mw + m, fa[m][0], fa[m][1]);
+#pragma unroll
+      for (int n = 0; n < 4; ++n) {
+        bf16x8 fb0, fb1, fl0, fl1;  // x = high + low, both bf16
+        fragments(tx, 4 * nw + n, fb0, fb1);
+        fragments(txl, 4 * nw + n, fl0, fl1);
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+          acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m][0], fb0, acc[m][n], 0, 0, 0);
+          acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m][1], fb1, acc[m][n], 0, 0, 0);
+          acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m][0], fl0, acc[m][n], 0, 0, 0);
+          acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m][1], fl1, acc[m][n], 0, 0, 0);
+        }
+      }
+      if (step + 1 < st_hi) park_tiles(buf ^ 1);
+      __syncthreads();
+    }
+  }
+  // dW = ln(2) * sum (the x tiles carry the factor log2 e); rows of the accumulator are
+  // output channels j, columns are input channels k
+  float *out = a.part + (((size_t)s * 2 + gate) * a.nb + g) * BS * BS;
+#pragma unroll
+  for (int m = 0; m < 2; ++m)
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = 64 * mw + 32 * m + 8 * (r >> 2) + 4 * hf + (r & 3);
+        const int col = 128 * nw + 32 * n + j;
+        out[(size_t)row * BS + col] = acc[m][n][r] * LN2;
+      }
+}
+
+// dW[gate][g][j][k] = sum over slices, in a fixed order
+__global__ void __launch_bounds__(256) reduce_wgrad_kernel(const float *part, int S, size_t per_gate,
+                                                           float *dWa, float *dWx) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= 2 * per_gate) return;
+  float sum = 0.f;
+  for (int s = 0; s < S; ++s) sum += part[(size_t)s * 2 * per_gate + i];
+  if (i < per_gate)
+    dWa[i] = sum;
+  else
+    dWx[i - per_gate] = sum;
+}
+
+// out[r][d] = sum_q part[q][r][d]
+struct RowOuts5 {
+  float *p[5];
+};
+__global__ void __launch_bounds__(256) reduce_rows_kernel(const float *part, int nparts, int rows,
+                                                          int D, RowOuts5 out) {
+  const int d = blockIdx.x * 256 + threadIdx.x, r = blockIdx.y;
+  if (d >= D || !out.p[r]) return;
+  float s = 0.f;
+  for (int q = 0; q < nparts; ++q) s += part[((size_t)q * rows + r) * D + d];
+  out.p[r][d] = s;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------ host side
+namespace {
+
+size_t al256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+struct BwdPlan {
+  int units, ntile, G, R, C, S;
+  size_t off_x, off_xl, off_dp, off_dq, off_dx, off_wta, off_wtx, off_rec, off_partA, off_partC, off_partW, total;
+};
+
+BwdPlan plan_backward(int B, int T, int D, int nb, int ncu) {
+  BwdPlan q;
+  q.units = B * nb;
+  q.ntile = (T + TT - 1) / TT;
+  q.G = pick_slices(q.units, q.ntile, ncu);
+  q.R = 8 * q.G;
+  q.C = ncu / q.units;
+  if (q.C < 1) q.C = 1;
+  if (q.C > q.ntile) q.C = q.ntile;
+  // wgrad: 2*nb blocks per slice; enough slices to cover the device, each at least 8 steps
+  const long long steps = ((long long)B * T + TT - 1) / TT;
+  long long S = ncu / (2 * nb);
+  if (S < 1) S = 1;
+  if (S > steps / 8) S = steps / 8 > 0 ? steps / 8 : 1;
+  q.S = (int)S;
+  const size_t N2 = al256((size_t)B * T * D * 2), wbytes = al256((size_t)nb * BS * BS * 2);
+  size_t off = 0;
+  q.off_x = off; off += N2;
+  q.off_xl = off; off += N2;
+  q.off_dp = off; off += N2;
+  q.off_dq = off; off += N2;
+  q.off_dx = off; off += 2 * N2;
+  q.off_wta = off; off += wbytes;
+  q.off_wtx = off; off += wbytes;
+  q.off_rec = off; off += al256(256 + (size_t)q.units * q.R * 2 * BS * sizeof(u64));
+  q.off_partA = off; off += al256((size_t)B * q.G * 3 * D * 4);
+  q.off_partC = off; off += al256((size_t)B * q.C * 5 * D * 4);
+  q.off_partW = off; off += al256((size_t)q.S * 2 * nb * BS * BS * 4);
+  q.total = off;
+  return q;
+}
+
+}  // namespace
+
+bool backward_mfma_supported(const Problem &p, bool bf) {
+  auto al = [](const void *q, size_t n) { return ((uintptr_t)q % n) == 0; };
+  return bf && p.bs == BS && p.T >= 1 && (size_t)p.T * p.D * 4 < ((size_t)1 << 32) &&
+         al(p.W_a, 16) && al(p.W_x, 16) && al(p.u, 16) && al(p.y_in, 4) && al(p.dy, 4) &&
+         al(p.du, 2) && (!p.state_in || al(p.state_in, 16));
+}
+
+size_t backward_mfma_ws_bytes(int B, int T, int D, int nb) {
+  // sized for 256 compute units so that the answer does not depend on the device
+  return plan_backward(B, T, D, nb, 256).total;
+}
+
+template <typename K>
+static hipError_t big_lds(K kernel, int bytes) {
+  return hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
+  int ncu = num_cu();
+  if (ncu > 256) ncu = 256;
+  const BwdPlan q = plan_backward(p.B, p.T, p.D, p.nb, ncu);
+  char *ws = (char *)p.ws;
+  hipError_t e;
+  static bool configured = false;
+  if (!configured) {
+    if ((e = big_lds(bwd_gates_kernel<1>, G_LDS)) != hipSuccess) return e;
+    if ((e = big_lds(bwd_gates_kernel<4>, G_LDS)) != hipSuccess) return e;
+    if ((e = big_lds(bwd_gates_kernel<8>, G_LDS)) != hipSuccess) return e;
+    if ((e = big_lds(bwd_dgrad_kernel, D_LDS)) != hipSuccess) return e;
+    if ((e = big_lds(bwd_wgrad_kernel, W_LDS)) != hipSuccess) return e;
+    configured = true;
+  }
+  unsigned short *wta = (unsigned short *)(ws + q.off_wta), *wtx = (unsigned short *)(ws + q.off_wtx);
+  hipLaunchKernelGGL(transpose_weights_kernel, dim3(BS / 32, BS / 32, p.nb), dim3(256), 0, s,
+                     (const unsigned short *)p.W_a, wta, p.nb);
+  hipLaunchKernelGGL(transpose_weights_kernel, dim3(BS / 32, BS / 32, p.nb), dim3(256), 0, s,
+                     (const unsigned short *)p.W_x, wtx, p.nb);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+
+  // 1. gates, reverse scan, pointwise adjoints
+  BwdArgs a;
+  a.p = p;
+  a.G = q.G; a.ntile = q.ntile; a.R = q.R;
+  a.err = (int *)(ws + q.off_rec);
+  a.rec = (u64 *)(ws + q.off_rec + 256);
+  a.xo = (unsigned short *)(ws + q.off_x);
+  a.xlo = (unsigned short *)(ws + q.off_xl);
+  a.dpo = (unsigned short *)(ws + q.off_dp);
+  a.dqo = (unsigned short *)(ws + q.off_dq);
+  a.dxo = (float *)(ws + q.off_dx);
+  a.part = (float *)(ws + q.off_partA);
+  const int grid = q.units * q.G;
+  a.swizzle = (q.G > 1 && grid % 8 == 0) ? 1 : 0;
+  if (q.G == 1) {
+    hipLaunchKernelGGL(bwd_gates_kernel<1>, dim3(grid), dim3(NTHR), G_LDS, s, a);
+  } else {
+    if ((e = launch_zero(ws + q.off_rec, 256 + (size_t)q.units * q.R * 2 * BS * sizeof(u64), s)) != hipSuccess)
+      return e;
+    if (q.G <= 4)
+      hipLaunchKernelGGL(bwd_gates_kernel<4>, dim3(grid), dim3(NTHR), G_LDS, s, a);
+    else
+      hipLaunchKernelGGL(bwd_gates_kernel<8>, dim3(grid), dim3(NTHR), G_LDS, s, a);
+  }
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  const int dblocks = (p.D + 255) / 256;
+  const RowOuts5 gate_outs = {{p.g.db_a, p.g.db_x, p.g.dLambda, nullptr, nullptr}};
+  hipLaunchKernelGGL(reduce_rows_kernel, dim3(dblocks, 3), dim3(256), 0, s, (const float *)a.part,
+                     p.B * q.G, 3, p.D, gate_outs);
+
+  // 2. dgrad and Conv1D adjoint
+  DgradArgs dg;
+  dg.p = p;
+  dg.C = q.C; dg.ntile = q.ntile;
+  dg.dpo = a.dpo; dg.dqo = a.dqo; dg.dxo = a.dxo;
+  dg.wta = wta; dg.wtx = wtx;
+  dg.part = (float *)(ws + q.off_partC);
+  hipLaunchKernelGGL(bwd_dgrad_kernel, dim3(q.units * q.C), dim3(NTHR), D_LDS, s, dg);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  const RowOuts5 conv_outs = {{p.g.dconv_w, p.g.dconv_w + p.D, p.g.dconv_w + 2 * (size_t)p.D,
+                               p.g.dconv_w + 3 * (size_t)p.D, p.g.dconv_b}};
+  hipLaunchKernelGGL(reduce_rows_kernel, dim3(dblocks, 5), dim3(256), 0, s, (const float *)dg.part,
+                     p.B * q.C, 5, p.D, conv_outs);
+
+  // 3. wgrad
+  WgradArgs wg;
+  wg.nb = p.nb; wg.S = q.S; wg.D = p.D;
+  wg.rows = (long long)p.B * p.T;
+  wg.dpo = a.dpo; wg.dqo = a.dqo; wg.xo = a.xo; wg.xlo = a.xlo;
+  wg.part = (float *)(ws + q.off_partW);
+  hipLaunchKernelGGL(bwd_wgrad_kernel, dim3(q.S * 2 * p.nb), dim3(NTHR), W_LDS, s, wg);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  const size_t per_gate = (size_t)p.nb * BS * BS;
+  hipLaunchKernelGGL(reduce_wgrad_kernel, dim3((unsigned)((2 * per_gate + 255) / 256)), dim3(256), 0, s,
+                     (const float *)wg.part, q.S, per_gate, p.g.dW_a, p.g.dW_x);
+  return hipGetLastError();
+}
+
+}  // namespace rglru

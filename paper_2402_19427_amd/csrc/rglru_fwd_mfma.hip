@@ -2,7 +2,8 @@
 //
 // One workgroup of 8 waves owns one (sequence, gate block) pair - or one of G interleaved
 // time slices of it - and walks it in tiles of 32 steps:
-//   Conv1D (Section 2.3) in fp32 -> bf16 tile in LDS
+//   Conv1D (Section 2.3) in fp32 -> tile in LDS as bf16 high part + bf16 low part; the gate
+//     products read the high part, the recurrence input x_t is rebuilt from both
 //   gate pre-activations W_a x, W_x x (eqs. 1-2) with v_mfma_f32_32x32x16_bf16; each wave keeps
 //     its 32 output channels of both gate matrices in registers for the whole kernel
 //   gates, a_t, sqrt(1-a_t^2) (eqs. 1-3, Appendix A) and the scan (eq. 4) in registers: every
@@ -18,29 +19,13 @@
 // Scaling trick: the Conv1D taps are multiplied by log2(e), so the MFMA delivers
 // log2(e)*(Wx+b) and v_exp_f32 (a base-2 exponential) needs no extra multiply; the input gate
 // is evaluated as ln(2)*sigmoid, which cancels the factor carried by x.
-#include "rglru_internal.h"
+#include "rglru_mfma.h"
 
 namespace rglru {
 
+using namespace mfma;
+
 namespace {
-
-constexpr int BS = 256;          // gate block size this kernel is built for
-constexpr int NWAVE = 8;         // waves per workgroup, 32 output channels each
-constexpr int NTHR = NWAVE * 64;
-constexpr int TT = 32;           // time steps per tile
-constexpr int XS = BS + 8;       // LDS row stride in bf16 elements (528 B: conflict-free b128 reads)
-constexpr float LOG2E = 1.4426950408889634f;
-constexpr int XS_BYTES = 2 * TT * XS * 2;          // two x tiles
-constexpr int CONST_BYTES = 64 * 32 + 128 * 48;      // selection operands + Conv1D taps per lane
-constexpr int HOLD_BYTES = NWAVE * 64 * 32 * 4;     // local scan of one tile, per lane 32 floats
-constexpr int SPIN_LIMIT = 1 << 22;
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned long long u64;
 
 struct FwdArgs {
   Problem p;
@@ -51,22 +36,6 @@ struct FwdArgs {
   int *err;      // set to 1 if a bounded wait expired
   int swizzle;   // remap block ids so that neighbouring time slices share an XCD
 };
-
-__device__ __forceinline__ float bf_lo(unsigned v) { return __uint_as_float(v << 16); }
-__device__ __forceinline__ float bf_hi(unsigned v) { return __uint_as_float(v & 0xffff0000u); }
-__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {  // v_cvt_pk_bf16_f32
-  const f32x2 v = {lo, hi};
-  const bf16x2 b = __builtin_convertvector(v, bf16x2);
-  return *(const unsigned *)&b;
-}
-
-__device__ __forceinline__ void publish(u64 *slot, float v, unsigned tag) {
-  const u64 r = ((u64)tag << 32) | (u64)__float_as_uint(v);
-  __hip_atomic_store(slot, r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ u64 peek(const u64 *slot) {
-  return __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 // eqs. (1)-(3) with base-2 exponentials; pp, qq, xx carry a factor log2(e).
 // Returns a_t and b_t = sqrt(1-a_t^2) * i_t * x_t.
@@ -91,7 +60,7 @@ template <int GMAX>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 fwd_mfma_kernel(FwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  unsigned short *xs = (unsigned short *)smem;                   // [2][TT][XS]
+  unsigned short *xs = (unsigned short *)smem;                   // [2 buffers][high, low][TT][XS]
   bf16x8 *sel_lds = (bf16x8 *)(smem + XS_BYTES);                 // [2][64] selection operands
   f32x4 *cw_lds = (f32x4 *)(smem + XS_BYTES + 64 * 32);          // [3][128] Conv1D taps and bias
   float *hold = (float *)(smem + XS_BYTES + CONST_BYTES);        // [wave][8][64] float4
@@ -164,9 +133,9 @@ fwd_mfma_kernel(FwdArgs a) {
   const unsigned seq_bytes = (unsigned)((size_t)T * D * 2);
   const unsigned row_bytes = (unsigned)D * 2;
   const __amdgpu_buffer_rsrc_t u_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      (void *)((const unsigned short *)p.u + (size_t)b * T * D), 0, seq_bytes, 0x00020000);
+      uniform_ptr((const unsigned short *)p.u + (size_t)b * T * D), 0, seq_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      (void *)((unsigned short *)p.y + (size_t)b * T * D), 0, seq_bytes, 0x00020000);
+      uniform_ptr((unsigned short *)p.y + (size_t)b * T * D), 0, seq_bytes, 0x00020000);
   const unsigned u_voff = (unsigned)dc * 2;
   const unsigned y_voff = (unsigned)d * 2 + (unsigned)hf * 16 * row_bytes;
   const unsigned *st32 =
@@ -203,7 +172,10 @@ fwd_mfma_kernel(FwdArgs a) {
       x0 = fmaf(w01[2], bf_lo(raw[r + 2]), x0); x1 = fmaf(w01[3], bf_hi(raw[r + 2]), x1);
       x0 = fmaf(w23[0], bf_lo(raw[r + 1]), x0); x1 = fmaf(w23[1], bf_hi(raw[r + 1]), x1);
       x0 = fmaf(w23[2], bf_lo(raw[r]), x0);     x1 = fmaf(w23[3], bf_hi(raw[r]), x1);
-      *(unsigned *)(xw + buf * (TT * XS) + r * XS) = pack_bf16(x0, x1);
+      unsigned hi_pk, lo_pk;
+      split_bf16(x0, x1, hi_pk, lo_pk);
+      *(unsigned *)(xw + buf * (2 * XT_ELEMS) + r * XS) = hi_pk;
+      *(unsigned *)(xw + buf * (2 * XT_ELEMS) + XT_ELEMS + r * XS) = lo_pk;
     }
   };
 
@@ -301,7 +273,7 @@ fwd_mfma_kernel(FwdArgs a) {
       accq[r] = bias_q;
       accx[r] = 0.f;
     }
-    const unsigned short *ap = arow_base + buf * (TT * XS);
+    const unsigned short *ap = arow_base + buf * (2 * XT_ELEMS);
     {
       bf16x8 a0 = *(const bf16x8 *)(ap), a1 = *(const bf16x8 *)(ap + 16);
 #pragma unroll
@@ -317,8 +289,12 @@ fwd_mfma_kernel(FwdArgs a) {
     {
       const bf16x8 s0 = *(const bf16x8 *)(ap + (2 * wv) * 16);
       const bf16x8 s1 = *(const bf16x8 *)(ap + (2 * wv + 1) * 16);
+      const bf16x8 l0 = *(const bf16x8 *)(ap + XT_ELEMS + (2 * wv) * 16);
+      const bf16x8 l1 = *(const bf16x8 *)(ap + XT_ELEMS + (2 * wv + 1) * 16);
       accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(s0, sel_lds[lane], accx, 0, 0, 0);
       accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(s1, sel_lds[64 + lane], accx, 0, 0, 0);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(l0, sel_lds[lane], accx, 0, 0, 0);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(l1, sel_lds[64 + lane], accx, 0, 0, 0);
     }
 
     // ---- the tile parked in LDS one iteration ago can be finished now
@@ -418,7 +394,7 @@ fwd_mfma_kernel(FwdArgs a) {
 // ------------------------------------------------------------------------------ host side
 static int g_num_cu = 0;
 
-static int num_cu() {
+int mfma::num_cu() {
   if (g_num_cu == 0) {
     int dev = 0, n = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
@@ -430,6 +406,13 @@ static int num_cu() {
   return g_num_cu;
 }
 
+hipError_t mfma::launch_zero(void *ptr, size_t bytes, hipStream_t s) {
+  const size_t n16 = bytes / 16;
+  hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s,
+                     (uint4 *)ptr, n16);
+  return hipGetLastError();
+}
+
 bool forward_mfma_supported(const Problem &p, bool bf) {
   return bf && p.bs == BS && p.T >= 1 && (size_t)p.T * p.D * 2 < ((size_t)1 << 32) &&
          ((uintptr_t)p.W_a % 16 == 0) && ((uintptr_t)p.W_x % 16 == 0) && ((uintptr_t)p.u % 4 == 0) &&
@@ -439,7 +422,7 @@ bool forward_mfma_supported(const Problem &p, bool bf) {
 
 // time slices per (sequence, block): as many as keep every workgroup resident at once, at
 // most 8 (every tile reads the aggregates of the G-1 tiles before it)
-static int pick_slices(int units, int ntile, int ncu) {
+int mfma::pick_slices(int units, int ntile, int ncu) {
   int G = ncu / units;
   if (G < 1) G = 1;
   if (G > ntile) G = ntile;
@@ -489,10 +472,7 @@ hipError_t launch_forward_mfma(const Problem &p, hipStream_t s) {
   }
   a.err = (int *)p.ws;
   a.rec = (u64 *)((char *)p.ws + 256);
-  const size_t n16 = (256 + (size_t)units * a.R * 2 * BS * sizeof(u64)) / 16;
-  hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s,
-                     (uint4 *)p.ws, n16);
-  hipError_t e = hipGetLastError();
+  hipError_t e = launch_zero(p.ws, 256 + (size_t)units * a.R * 2 * BS * sizeof(u64), s);
   if (e != hipSuccess) return e;
   return a.G <= 4 ? launch_t<4>(a, grid, XS_BYTES + CONST_BYTES + HOLD_BYTES, s)
                   : launch_t<8>(a, grid, XS_BYTES + CONST_BYTES + HOLD_BYTES, s);

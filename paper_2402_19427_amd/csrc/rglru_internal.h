@@ -70,4 +70,9 @@ bool forward_mfma_supported(const Problem &p, bool bf);
 size_t forward_mfma_ws_bytes(int B, int T, int D, int nb);
 hipError_t launch_forward_mfma(const Problem &p, hipStream_t s);
 
+// MFMA backward (bf16 storage, gate blocks of 256)
+bool backward_mfma_supported(const Problem &p, bool bf);
+size_t backward_mfma_ws_bytes(int B, int T, int D, int nb);
+hipError_t launch_backward_mfma(const Problem &p, hipStream_t s);
+
 }  // namespace rglru

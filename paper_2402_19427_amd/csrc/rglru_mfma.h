@@ -1,0 +1,62 @@
+// Device helpers shared by the MFMA kernels (bf16 storage, gate blocks of 256 channels).
+#pragma once
+#include "rglru_internal.h"
+
+namespace rglru {
+namespace mfma {
+
+constexpr int BS = 256;          // gate block size this kernel is built for
+constexpr int NWAVE = 8;         // waves per workgroup, 32 output channels each
+constexpr int NTHR = NWAVE * 64;
+constexpr int TT = 32;           // time steps per tile
+constexpr int XS = BS + 8;       // LDS row stride in bf16 elements (528 B: conflict-free b128 reads)
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr int XT_ELEMS = TT * XS;                   // one [32][264] bf16 tile
+constexpr int XS_BYTES = 4 * XT_ELEMS * 2;          // two buffers x (high part, low part) of the x tile
+constexpr int CONST_BYTES = 64 * 32 + 128 * 48;      // selection operands + Conv1D taps per lane
+constexpr int HOLD_BYTES = NWAVE * 64 * 32 * 4;     // local scan of one tile, per lane 32 floats
+constexpr int SPIN_LIMIT = 1 << 22;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned long long u64;
+
+__device__ __forceinline__ float bf_lo(unsigned v) { return __uint_as_float(v << 16); }
+__device__ __forceinline__ float bf_hi(unsigned v) { return __uint_as_float(v & 0xffff0000u); }
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {  // v_cvt_pk_bf16_f32
+  const f32x2 v = {lo, hi};
+  const bf16x2 b = __builtin_convertvector(v, bf16x2);
+  return *(const unsigned *)&b;
+}
+// x = high + low with both parts in bf16 (16 mantissa bits in total): packs two values
+__device__ __forceinline__ void split_bf16(float x0, float x1, unsigned &hi_pk, unsigned &lo_pk) {
+  hi_pk = pack_bf16(x0, x1);
+  lo_pk = pack_bf16(x0 - bf_lo(hi_pk), x1 - bf_hi(hi_pk));
+}
+
+// 64-bit address made provably wave-uniform (kept in scalar registers), for buffer descriptors
+__device__ __forceinline__ void *uniform_ptr(const void *q) {
+  const u64 v = (u64)q;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return (void *)(((u64)hi << 32) | lo);
+}
+
+__device__ __forceinline__ void publish(u64 *slot, float v, unsigned tag) {
+  const u64 r = ((u64)tag << 32) | (u64)__float_as_uint(v);
+  __hip_atomic_store(slot, r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ u64 peek(const u64 *slot) {
+  return __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// host side (defined with the forward kernel)
+int num_cu();                                    // compute units of the current device
+int pick_slices(int units, int ntile, int ncu);  // time slices per (sequence, block)
+hipError_t launch_zero(void *ptr, size_t bytes, hipStream_t s);  // bytes % 16 == 0
+
+}  // namespace mfma
+}  // namespace rglru

@@ -172,6 +172,11 @@ BWD_SHAPES = [
     (2, 75, 512, 2, "bf16"),
     (2, 33, 320, 2, "bf16"),
     (1, 270, 600, 2, "bf16"),
+    (1, 1, 256, 1, "bf16"),       # MFMA path, single step
+    (2, 31, 256, 1, "bf16"),      # MFMA path, one partial tile
+    (1, 700, 256, 1, "bf16"),     # MFMA path, one unit in 8 time slices
+    (33, 70, 1024, 4, "bf16"),    # MFMA path, 132 units, no slicing
+    (8, 300, 2048, 8, "bf16"),    # MFMA path, 64 units x 4 slices
 ]
 
 
@@ -191,6 +196,7 @@ def test_backward_matches_oracle(B, T, D, nb, act, full):
     out = dp.backward(u, y, rn.to_device(inp["dy"], act), h0=h0, state_in=ring, pos0=pos0,
                       dhT=dhT)
     q = f64(inp)
+    oracle.set_threads(8 if q["u"].size > (1 << 20) else 1)
     ref = oracle.backward(q["u"], q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"],
                           q["conv_w"], q["dy"], conv_b=q.get("conv_b"), h0=q["h0"],
                           state_in=q["state"], dhT=q["dhT"] if full else None)
