@@ -27,6 +27,8 @@ using namespace mfma;
 
 namespace {
 
+constexpr int FWD_LDS = XS_BYTES + CONST_BYTES + HOLD_BYTES + NWAVE * OTILE_BYTES;
+
 struct FwdArgs {
   Problem p;
   int G;         // time slices (workgroups) per (sequence, block)
@@ -41,6 +43,11 @@ struct FwdArgs {
 // Returns a_t and b_t = sqrt(1-a_t^2) * i_t * x_t.
 __device__ __forceinline__ void gate_fast(float pp, float qq, float xx, float kd, float &a,
                                           float &b) {
+#ifdef RGLRU_EXP_NOGATE
+  a = 0.99f + 1e-9f * pp;
+  b = xx + 1e-9f * qq + kd * 0.f;
+  return;
+#endif
   const float ep = __builtin_amdgcn_exp2f(-pp);
   const float r = __builtin_amdgcn_rcpf(1.f + ep);
   a = __builtin_amdgcn_exp2f(kd * r);
@@ -67,6 +74,8 @@ fwd_mfma_kernel(FwdArgs a) {
   const Problem &p = a.p;
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, j = lane & 31;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // this wave's staging tile for the y rows it produces
+  unsigned short *otile = (unsigned short *)(smem + XS_BYTES + CONST_BYTES + HOLD_BYTES) + wv * (OTILE_BYTES / 2);
   const int G = GMAX == 1 ? 1 : a.G;
 
   int bid = blockIdx.x;
@@ -137,7 +146,6 @@ fwd_mfma_kernel(FwdArgs a) {
   const __amdgpu_buffer_rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       uniform_ptr((unsigned short *)p.y + (size_t)b * T * D), 0, seq_bytes, 0x00020000);
   const unsigned u_voff = (unsigned)dc * 2;
-  const unsigned y_voff = (unsigned)d * 2 + (unsigned)hf * 16 * row_bytes;
   const unsigned *st32 =
       p.state_in ? (const unsigned *)((const unsigned short *)p.state_in + (size_t)b * 3 * D + dc) : nullptr;
 
@@ -168,6 +176,15 @@ fwd_mfma_kernel(FwdArgs a) {
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
       float x0 = bb[0], x1 = bb[1];
+#ifdef RGLRU_EXP_NOCONV
+      x0 += __uint_as_float(raw[r]); x1 += __uint_as_float(raw[r + 3]);
+      {
+        unsigned hi_pk = __float_as_uint(x0), lo_pk = __float_as_uint(x1);
+        *(unsigned *)(xw + buf * (2 * XT_ELEMS) + r * XS) = hi_pk;
+        *(unsigned *)(xw + buf * (2 * XT_ELEMS) + XT_ELEMS + r * XS) = lo_pk;
+      }
+      continue;
+#endif
       x0 = fmaf(w01[0], bf_lo(raw[r + 3]), x0); x1 = fmaf(w01[1], bf_hi(raw[r + 3]), x1);
       x0 = fmaf(w01[2], bf_lo(raw[r + 2]), x0); x1 = fmaf(w01[3], bf_hi(raw[r + 2]), x1);
       x0 = fmaf(w23[0], bf_lo(raw[r + 1]), x0); x1 = fmaf(w23[1], bf_hi(raw[r + 1]), x1);
@@ -188,26 +205,22 @@ fwd_mfma_kernel(FwdArgs a) {
   float carry = p.h0 ? p.h0[(size_t)b * D + d] : 0.f;  // state after this workgroup's previous tile
   int spins = 0;
 
-  // four consecutive steps (quarter q) of this lane's run: h <- a h + b, y = h (eq. 4)
-  auto run_quarter = [&](int t0, int q, const f32x4 &av, const f32x4 &bv, float &h) {
-    const unsigned so = (unsigned)(t0 + 4 * q) * row_bytes;
+  // four consecutive steps (quarter q) of this lane's run: h <- a h + b, y = h (eq. 4); the
+  // bf16 results go to the wave's staging tile at (row = step, column = channel)
+  unsigned short *ot_mine = otile + (hf * 16) * OT + j;
+  auto run_quarter = [&](int q, const f32x4 &av, const f32x4 &bv, float &h) {
     const float h0v = fmaf(av[0], h, bv[0]), h1v = fmaf(av[1], h0v, bv[1]);
     const float h2v = fmaf(av[2], h1v, bv[2]), h3v = fmaf(av[3], h2v, bv[3]);
     h = h3v;
     const unsigned p0 = pack_bf16(h0v, h1v), p1 = pack_bf16(h2v, h3v);
-    if (T - t0 >= TT) {
-      __builtin_amdgcn_raw_buffer_store_b16((short)(p0 & 0xffff), y_rsrc, y_voff, so, 0);
-      __builtin_amdgcn_raw_buffer_store_b16((short)(p0 >> 16), y_rsrc, y_voff, so + row_bytes, 0);
-      __builtin_amdgcn_raw_buffer_store_b16((short)(p1 & 0xffff), y_rsrc, y_voff, so + 2 * row_bytes, 0);
-      __builtin_amdgcn_raw_buffer_store_b16((short)(p1 >> 16), y_rsrc, y_voff, so + 3 * row_bytes, 0);
-    } else {
-      const int nvalid = T - t0 - hf * 16 - 4 * q;  // steps of this quarter inside the sequence
-      if (0 < nvalid) __builtin_amdgcn_raw_buffer_store_b16((short)(p0 & 0xffff), y_rsrc, y_voff, so, 0);
-      if (1 < nvalid) __builtin_amdgcn_raw_buffer_store_b16((short)(p0 >> 16), y_rsrc, y_voff, so + row_bytes, 0);
-      if (2 < nvalid) __builtin_amdgcn_raw_buffer_store_b16((short)(p1 & 0xffff), y_rsrc, y_voff, so + 2 * row_bytes, 0);
-      if (3 < nvalid) __builtin_amdgcn_raw_buffer_store_b16((short)(p1 >> 16), y_rsrc, y_voff, so + 3 * row_bytes, 0);
-    }
+    unsigned short *o = ot_mine + (4 * q) * OT;
+    o[0] = (unsigned short)(p0 & 0xffff);
+    o[OT] = (unsigned short)(p0 >> 16);
+    o[2 * OT] = (unsigned short)(p1 & 0xffff);
+    o[3 * OT] = (unsigned short)(p1 >> 16);
   };
+  // 16-byte stores of the staged tile: lane l owns 8 channels of rows l/4 and l/4+16
+  const unsigned yw_voff = (unsigned)(g * BS + wv * 32 + (lane & 3) * 8) * 2 + (unsigned)(lane >> 2) * row_bytes;
 
   // state of the held tile (its local scan sits in LDS until the next iteration)
   int held = -1;
@@ -249,7 +262,10 @@ fwd_mfma_kernel(FwdArgs a) {
     }
     float hrun = hf ? fmaf(hA_lo, h, hH_lo) : h;  // state entering this lane's run
 #pragma unroll
-    for (int q = 0; q < 4; ++q) run_quarter(t * TT, q, hold_mine[q * 64], hold_mine[(q + 4) * 64], hrun);
+    for (int q = 0; q < 4; ++q) run_quarter(q, hold_mine[q * 64], hold_mine[(q + 4) * 64], hrun);
+#ifndef RGLRU_EXP_NOSTORE
+    store_staged_tile(otile, lane, y_rsrc, yw_voff, (unsigned)(t * TT) * row_bytes, row_bytes, T - t * TT);
+#endif
     carry = fmaf(hA_t, h, hH_t);
   };
 
@@ -276,8 +292,13 @@ fwd_mfma_kernel(FwdArgs a) {
     const unsigned short *ap = arow_base + buf * (2 * XT_ELEMS);
     {
       bf16x8 a0 = *(const bf16x8 *)(ap), a1 = *(const bf16x8 *)(ap + 16);
+#ifdef RGLRU_EXP_NOGEMM
+#pragma unroll 1
+      for (int ks = 0; ks < 1; ++ks) {
+#else
 #pragma unroll
       for (int ks = 0; ks < 16; ++ks) {
+#endif
         const bf16x8 a2 = *(const bf16x8 *)(ap + ((ks + 2) & 15) * 16);  // two steps ahead
         accp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wa[ks], accp, 0, 0, 0);
         accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wx[ks], accq, 0, 0, 0);
@@ -350,6 +371,10 @@ fwd_mfma_kernel(FwdArgs a) {
       hA_t = hA_lo * A_up;
       hH_t = fmaf(A_up, hH_lo, H_up);
     }
+#ifdef RGLRU_EXP_NORESOLVE
+    if (hrun == 12345.f) resolve(tile);
+    carry += hA_t;
+#else
     if (GMAX > 1) {
       // publish the aggregate: lower half writes A, upper half writes H
       publish(ring + (size_t)(tile % a.R) * 2 * BS + hf * BS, hf ? hH_t : hA_t, (unsigned)(tile + 1));
@@ -357,6 +382,7 @@ fwd_mfma_kernel(FwdArgs a) {
     } else {
       resolve(tile);
     }
+#endif
 
     // ---- next tile of this workgroup into the other LDS buffer
     if (next < a.ntile) conv_rows(buf ^ 1);
@@ -416,6 +442,7 @@ hipError_t mfma::launch_zero(void *ptr, size_t bytes, hipStream_t s) {
 bool forward_mfma_supported(const Problem &p, bool bf) {
   return bf && p.bs == BS && p.T >= 1 && (size_t)p.T * p.D * 2 < ((size_t)1 << 32) &&
          ((uintptr_t)p.W_a % 16 == 0) && ((uintptr_t)p.W_x % 16 == 0) && ((uintptr_t)p.u % 4 == 0) &&
+         ((uintptr_t)p.y % 16 == 0) &&
          (!p.state_in || (uintptr_t)p.state_in % 4 == 0) &&
          (!p.state_out || (uintptr_t)p.state_out % 4 == 0);
 }
@@ -446,7 +473,7 @@ static hipError_t launch_t(const FwdArgs &a, int grid, size_t lds, hipStream_t s
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void *)fwd_mfma_kernel<GMAX>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       XS_BYTES + CONST_BYTES + HOLD_BYTES);
+                                       FWD_LDS);
     if (e != hipSuccess) return e;
     configured = true;
   }
@@ -468,14 +495,14 @@ hipError_t launch_forward_mfma(const Problem &p, hipStream_t s) {
   if (a.G == 1) {
     a.rec = nullptr;
     a.err = nullptr;
-    return launch_t<1>(a, grid, XS_BYTES + CONST_BYTES + HOLD_BYTES, s);
+    return launch_t<1>(a, grid, FWD_LDS, s);
   }
   a.err = (int *)p.ws;
   a.rec = (u64 *)((char *)p.ws + 256);
   hipError_t e = launch_zero(p.ws, 256 + (size_t)units * a.R * 2 * BS * sizeof(u64), s);
   if (e != hipSuccess) return e;
-  return a.G <= 4 ? launch_t<4>(a, grid, XS_BYTES + CONST_BYTES + HOLD_BYTES, s)
-                  : launch_t<8>(a, grid, XS_BYTES + CONST_BYTES + HOLD_BYTES, s);
+  return a.G <= 4 ? launch_t<4>(a, grid, FWD_LDS, s)
+                  : launch_t<8>(a, grid, FWD_LDS, s);
 }
 
 }  // namespace rglru

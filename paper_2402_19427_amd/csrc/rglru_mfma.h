@@ -15,6 +15,8 @@ constexpr int XT_ELEMS = TT * XS;                   // one [32][264] bf16 tile
 constexpr int XS_BYTES = 4 * XT_ELEMS * 2;          // two buffers x (high part, low part) of the x tile
 constexpr int CONST_BYTES = 64 * 32 + 128 * 48;      // selection operands + Conv1D taps per lane
 constexpr int HOLD_BYTES = NWAVE * 64 * 32 * 4;     // local scan of one tile, per lane 32 floats
+constexpr int OT = 40;                              // row stride (bf16) of a wave's output staging tile
+constexpr int OTILE_BYTES = TT * OT * 2;            // [32 steps][32 channels] bf16 per wave
 constexpr int SPIN_LIMIT = 1 << 22;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -51,6 +53,24 @@ __device__ __forceinline__ void publish(u64 *slot, float v, unsigned tag) {
 }
 __device__ __forceinline__ u64 peek(const u64 *slot) {
   return __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// A wave's [32 steps][32 channels] bf16 tile, staged in LDS by the lanes that own (channel,
+// 16 consecutive steps), leaves as 16-byte stores: lane l writes 8 channels of row l/4 (and of
+// row l/4 + 16), so 4 lanes cover the wave's 64 contiguous bytes of a row.
+//   ot      this wave's staging tile
+//   voff    byte offset of (row l/4, channel group l%4) of this lane inside the sequence
+//   soff    byte offset of the tile's first row
+//   nrows   rows of the tile inside the sequence (>= 32 for a full tile)
+__device__ __forceinline__ void store_staged_tile(const unsigned short *ot, int lane,
+                                                  __amdgpu_buffer_rsrc_t rsrc, unsigned voff,
+                                                  unsigned soff, unsigned row_bytes, int nrows) {
+  const int row = lane >> 2, chunk = lane & 3;
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v0 = *(const u32x4 *)(ot + row * OT + chunk * 8);
+  const u32x4 v1 = *(const u32x4 *)(ot + (row + 16) * OT + chunk * 8);
+  if (row < nrows) __builtin_amdgcn_raw_buffer_store_b128(v0, rsrc, voff, soff, 0);
+  if (row + 16 < nrows) __builtin_amdgcn_raw_buffer_store_b128(v1, rsrc, voff, soff + 16 * row_bytes, 0);
 }
 
 // host side (defined with the forward kernel)
