@@ -23,18 +23,40 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
 
 
 def algorithmic_costs(B, T, D, nb):
-    """Bytes each entry point must move (every input read once, every output written once,
-    intermediates never touching HBM) and the gate-contraction FLOPs it must execute."""
+    """Per kernel: the bytes of the METHOD's own inputs and outputs that the kernel touches
+    (each read or written once; tensors that exist only because the backward is split into
+    three kernels are not algorithmic traffic) and the gate-contraction FLOPs it executes."""
     bs = D // nb
     N = B * T * D
-    w_bytes = 2 * nb * bs * bs * 2                     # both gate matrices, bf16
-    vec = 8 * D * 4                                     # b_a, b_x, Lambda, conv_w, conv_b-sized slack
-    fwd = dict(bytes=4 * N + w_bytes + vec + 4 * B * D + 6 * B * D,   # u in, y out, hT, conv state
-               flops=4 * bs * N)                        # two [T x bs] x [bs x bs] products
-    dec = dict(bytes=(2 + 6 + 2 + 4 + 4 + 2) * B * D + w_bytes + vec, flops=4 * bs * B * D)
-    bwd = dict(bytes=8 * N + w_bytes + vec + 2 * nb * bs * bs * 4 + 8 * B * D,  # u,y,dy in; du out; dW
-               flops=12 * bs * N)                       # gate recompute + dgrad + wgrad
-    return fwd, dec, bwd
+    w_bytes = 2 * nb * bs * bs * 2                      # both gate matrices, bf16
+    vec = 8 * D * 4                                      # b_a, b_x, Lambda, conv_w, conv_b
+    gemm = 4 * bs * N                                    # two [rows x bs] x [bs x bs] products
+    return {
+        # u in, y out, weights, hT and conv state out
+        "fwd_mfma_kernel": dict(bytes=4 * N + w_bytes + vec + 10 * B * D, flops=gemm),
+        # u_t, 3 ring slots read + 1 written, h read + written, y_t, weights
+        "decode_mfma_kernel": dict(bytes=(2 + 6 + 2 + 4 + 4 + 2) * B * D + w_bytes + vec,
+                                   flops=4 * bs * B * D),
+        # u, y, dy in (gate recompute + reverse scan + pointwise adjoints)
+        "bwd_gates_kernel": dict(bytes=6 * N + w_bytes + vec + 8 * B * D, flops=gemm),
+        # u in (for dconv_w), du out
+        "bwd_dgrad_kernel": dict(bytes=4 * N + w_bytes + vec, flops=gemm),
+        # dW_a, dW_x out (fp32)
+        "bwd_wgrad_kernel": dict(bytes=2 * nb * bs * bs * 4, flops=gemm),
+    }
+
+
+def read_traffic(workload):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), taken from
+    the committed summary profiles/hbm_traffic_<workload>.txt (lines `kernel: bytes`)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            if line.startswith("traffic_bytes "):
+                _, name, val = line.split()
+                out[name] = float(val)
+    return out
 
 
 def cpu_baseline(w, seconds_hint=20.0):
@@ -43,7 +65,7 @@ def cpu_baseline(w, seconds_hint=20.0):
     import numpy as np
     import oracle
     import rglru_inputs as gen
-    B_s, T_s = 2, min(w.T, 2048)
+    B_s, T_s = 4, min(w.T, 2048)
     inp = gen.make_inputs(B_s, T_s + 1, w.D, w.nb, act=w.act, seed=w.seed, dy=True)
     q = {k: (None if v is None else np.asarray(v, np.float64)) for k, v in inp.items()}
     par = (q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"], q["conv_w"])
@@ -102,54 +124,54 @@ def main():
     g = dp.alloc_grads()
     pg = R.make_param_grads(g["dW_a"], g["dW_x"], g["db_a"], g["db_x"], g["dLambda"],
                             g["dconv_w"], g["dconv_b"])
-    stream = torch.cuda.current_stream()
-    sh_ptr = stream.cuda_stream
+    sh_ptr = torch.cuda.current_stream().cuda_stream
 
-    def step(ev=None):
-        if ev:
-            ev[0].record(stream)
+    def step():
         R.rglru_forward(sh, dp.params, u, h0, None, 0, y, hT, st, ws_f, n_f, sh_ptr)
-        if ev:
-            ev[1].record(stream)
         R.rglru_decode_step(sh1, dp.params, u_next, hT, st, T, y1, sh_ptr)
-        if ev:
-            ev[2].record(stream)
         R.rglru_backward(sh, dp.params, u, h0, None, 0, y, dy, None, du, dh0, pg, ws_b, n_b, sh_ptr)
-        if ev:
-            ev[3].record(stream)
 
     for _ in range(args.warmup):
         step()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     torch.cuda.synchronize()
+    # every kernel launch of the timed region is bracketed by HIP events on its own stream
+    R.rglru_timing_enable(True)
     t0 = time.perf_counter()
     for k in range(args.steps):
-        step(events[k])
+        step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    R.rglru_timing_enable(False)
 
-    ms = [[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in events]
-    avg = [float(np.mean([m[i] for m in ms])) for i in range(3)]   # fwd, decode, bwd (ms)
+    per_kernel = {}
+    for i in range(R.rglru_timing_count()):
+        name, ms = R.rglru_timing_get(i)
+        tot, cnt = per_kernel.get(name, (0.0, 0))
+        per_kernel[name] = (tot + ms, cnt + 1)
     tokens = B * T + B
     ms_per_step = 1e3 * elapsed / args.steps
-    fwd_c, dec_c, bwd_c = algorithmic_costs(B, T, D, nb)
+    costs = algorithmic_costs(B, T, D, nb)
+    traffic = read_traffic(w.name)
 
-    def roof(name, cost, t_ms):
+    def roof(name, t_ms):
+        cost = costs[name]
         t_hbm = cost["bytes"] / (HBM_PEAK_GBS * 1e9)
         t_mfma = cost["flops"] / (MFMA_BF16_PEAK_TFLOPS * 1e12)
         if t_hbm >= t_mfma:
             ach = cost["bytes"] / (t_ms * 1e-3) / 1e9
             return {"kernel": name, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                    "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": traffic.get(name),
                     "algorithmic_bytes": cost["bytes"], "avg_ms": t_ms}
         ach = cost["flops"] / (t_ms * 1e-3) / 1e12
         return {"kernel": name, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic.get(name),
                 "algorithmic_flops": cost["flops"], "avg_ms": t_ms}
 
-    roofs = [roof("rglru_forward", fwd_c, avg[0]), roof("rglru_decode_step", dec_c, avg[1]),
-             roof("rglru_backward", bwd_c, avg[2])]
-    dominant = max(range(3), key=lambda i: avg[i])
+    kernels = {n: {"avg_ms": tot / cnt, "launches_per_step": cnt / args.steps,
+                   "ms_per_step": tot / args.steps} for n, (tot, cnt) in per_kernel.items()}
+    dominant = max((n for n in kernels if n in costs), key=lambda n: kernels[n]["ms_per_step"])
+    roofs = [roof(n, kernels[n]["avg_ms"]) for n in costs if n in kernels]
+    alg_step_bytes = 12 * B * T * D   # method-level: forward 4 B/element + backward 8 B/element
 
     out = {
         "metric": "RG-LRU block tokens/sec and achieved HBM GB/s (% of MI355X peak)",
@@ -163,9 +185,11 @@ def main():
         "config": {"workload": "%s: B=%d T=%d D=%d nb=%d %s, forward + 1 decode step + backward"
                                % (w.name, B, T, D, nb, w.act),
                    "global_batch": B, "seq_len": T},
-        "roofline": roofs[dominant],
-        "entry_points": roofs,
-        "hbm_gbs_step": (fwd_c["bytes"] + dec_c["bytes"] + bwd_c["bytes"]) / (elapsed / args.steps) / 1e9,
+        "roofline": roof(dominant, kernels[dominant]["avg_ms"]),
+        "kernel_rooflines": roofs,
+        "kernels": kernels,
+        "hbm_gbs_step": alg_step_bytes / (elapsed / args.steps) / 1e9,
+        "hbm_frac_step": alg_step_bytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)

@@ -173,6 +173,19 @@ size_t rglru_workspace_bytes(const rglru_shape *shape, int op);
 /* Description of the last error returned on the calling thread ("" if none). */
 const char *rglru_last_error(void);
 
+/*
+ * Kernel timing for benchmarks (not part of the method). While enabled on the calling thread,
+ * every kernel an entry point launches is bracketed by two HIP events recorded on that call's
+ * stream; the library owns the events. rglru_timing_count() is the number of kernels recorded
+ * since the last rglru_timing_enable(1) (at most 8192; later launches are not recorded).
+ * rglru_timing_get() returns the name of record `index` (a static string) and, once the caller
+ * has synchronised the stream, the kernel's duration in milliseconds in *ms.
+ * Returns RGLRU_OK, RGLRU_ERR_INVALID_ARG (bad index / NULL) or RGLRU_ERR_HIP.
+ */
+int rglru_timing_enable(int enable);
+int rglru_timing_count(void);
+int rglru_timing_get(int index, const char **name, float *ms);
+
 /* Library version: major * 10000 + minor * 100 + patch. */
 int rglru_version(void);
 

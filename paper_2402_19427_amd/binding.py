@@ -57,6 +57,9 @@ def _load():
     lib.rglru_workspace_bytes.restype = sz
     lib.rglru_last_error.restype = ctypes.c_char_p
     lib.rglru_version.restype = ctypes.c_int
+    lib.rglru_timing_enable.argtypes = [ctypes.c_int]
+    lib.rglru_timing_get.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p),
+                                     ctypes.POINTER(ctypes.c_float)]
     for f in (lib.rglru_conv1d, lib.rglru_forward, lib.rglru_decode_step, lib.rglru_backward):
         f.restype = ctypes.c_int
     return lib
@@ -113,6 +116,21 @@ def rglru_version():
 
 def rglru_last_error():
     return _lib.rglru_last_error().decode()
+
+
+def rglru_timing_enable(enable):
+    _check(_lib.rglru_timing_enable(1 if enable else 0))
+
+
+def rglru_timing_count():
+    return int(_lib.rglru_timing_count())
+
+
+def rglru_timing_get(index):
+    """(kernel name, milliseconds) of timing record `index`; synchronise the stream first."""
+    name, ms = ctypes.c_char_p(), ctypes.c_float()
+    _check(_lib.rglru_timing_get(index, ctypes.byref(name), ctypes.byref(ms)))
+    return name.value.decode(), float(ms.value)
 
 
 def rglru_workspace_bytes(shape, op):

@@ -128,7 +128,53 @@ size_t workspace_need(const rglru_shape *s, int op) {
 
 }  // namespace
 
+// ---- benchmark timing
+namespace {
+constexpr int MAX_TIMED = 8192;
+struct TimedRecord {
+  const char *name;
+  hipEvent_t start, stop;
+};
+thread_local bool g_timing = false;
+thread_local int g_ntimed = 0;
+thread_local TimedRecord *g_timed = nullptr;   // events are created once and reused
+thread_local int g_events_made = 0;
+}  // namespace
+
+rglru::KernelTimer::KernelTimer(const char *name, hipStream_t stream) : s(stream), slot(-1) {
+  if (!g_timing || g_ntimed >= MAX_TIMED) return;
+  if (!g_timed) g_timed = new TimedRecord[MAX_TIMED];
+  if (g_ntimed >= g_events_made) {
+    if (hipEventCreate(&g_timed[g_ntimed].start) != hipSuccess) return;
+    if (hipEventCreate(&g_timed[g_ntimed].stop) != hipSuccess) return;
+    g_events_made = g_ntimed + 1;
+  }
+  slot = g_ntimed++;
+  g_timed[slot].name = name;
+  (void)hipEventRecord(g_timed[slot].start, s);
+}
+rglru::KernelTimer::~KernelTimer() {
+  if (slot >= 0) (void)hipEventRecord(g_timed[slot].stop, s);
+}
+
 extern "C" {
+
+int rglru_timing_enable(int enable) {
+  g_timing = enable != 0;
+  if (g_timing) g_ntimed = 0;
+  return RGLRU_OK;
+}
+
+int rglru_timing_count(void) { return g_ntimed; }
+
+int rglru_timing_get(int index, const char **name, float *ms) {
+  if (index < 0 || index >= g_ntimed || !name || !ms)
+    return fail(RGLRU_ERR_INVALID_ARG, "timing record %d does not exist", index);
+  *name = g_timed[index].name;
+  hipError_t e = hipEventElapsedTime(ms, g_timed[index].start, g_timed[index].stop);
+  if (e != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+  return RGLRU_OK;
+}
 
 const char *rglru_last_error(void) { return g_err; }
 
@@ -229,7 +275,8 @@ int rglru_decode_step(const rglru_shape *shape, const rglru_params *params, cons
   q.T = 1; q.pos0 = pos; q.u = u_t; q.hT = h; q.state_in = conv_state;
   q.state_out = conv_state; q.y = y_t;
   const bool bf = shape->act_dtype == RGLRU_BF16;
-  hipError_t e = launch_decode_generic(q, bf, (hipStream_t)stream);
+  hipError_t e = decode_mfma_supported(q, bf) ? launch_decode_mfma(q, (hipStream_t)stream)
+                                             : launch_decode_generic(q, bf, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "decode launch");
   g_err[0] = 0;
   return RGLRU_OK;

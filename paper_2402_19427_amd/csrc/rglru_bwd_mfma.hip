@@ -912,10 +912,16 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
     configured = true;
   }
   unsigned short *wta = (unsigned short *)(ws + q.off_wta), *wtx = (unsigned short *)(ws + q.off_wtx);
-  hipLaunchKernelGGL(transpose_weights_kernel, dim3(BS / 32, BS / 32, p.nb), dim3(256), 0, s,
-                     (const unsigned short *)p.W_a, wta, p.nb);
-  hipLaunchKernelGGL(transpose_weights_kernel, dim3(BS / 32, BS / 32, p.nb), dim3(256), 0, s,
-                     (const unsigned short *)p.W_x, wtx, p.nb);
+  {
+    KernelTimer kt("transpose_weights_kernel", s);
+    hipLaunchKernelGGL(transpose_weights_kernel, dim3(BS / 32, BS / 32, p.nb), dim3(256), 0, s,
+                       (const unsigned short *)p.W_a, wta, p.nb);
+  }
+  {
+    KernelTimer kt("transpose_weights_kernel", s);
+    hipLaunchKernelGGL(transpose_weights_kernel, dim3(BS / 32, BS / 32, p.nb), dim3(256), 0, s,
+                       (const unsigned short *)p.W_x, wtx, p.nb);
+  }
   if ((e = hipGetLastError()) != hipSuccess) return e;
 
   // 1. gates, reverse scan, pointwise adjoints
@@ -932,12 +938,14 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   a.part = (float *)(ws + q.off_partA);
   const int grid = q.units * q.G;
   a.swizzle = (q.G > 1 && grid % 8 == 0) ? 1 : 0;
-  if (q.G == 1) {
-    hipLaunchKernelGGL(bwd_gates_kernel<1>, dim3(grid), dim3(NTHR), G_LDS, s, a);
-  } else {
-    if ((e = launch_zero(ws + q.off_rec, 256 + (size_t)q.units * q.R * 2 * BS * sizeof(u64), s)) != hipSuccess)
-      return e;
-    if (q.G <= 4)
+  if (q.G > 1 &&
+      (e = launch_zero(ws + q.off_rec, 256 + (size_t)q.units * q.R * 2 * BS * sizeof(u64), s)) != hipSuccess)
+    return e;
+  {
+    KernelTimer kt("bwd_gates_kernel", s);
+    if (q.G == 1)
+      hipLaunchKernelGGL(bwd_gates_kernel<1>, dim3(grid), dim3(NTHR), G_LDS, s, a);
+    else if (q.G <= 4)
       hipLaunchKernelGGL(bwd_gates_kernel<4>, dim3(grid), dim3(NTHR), G_LDS, s, a);
     else
       hipLaunchKernelGGL(bwd_gates_kernel<8>, dim3(grid), dim3(NTHR), G_LDS, s, a);
@@ -945,8 +953,11 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const int dblocks = (p.D + 255) / 256;
   const RowOuts5 gate_outs = {{p.g.db_a, p.g.db_x, p.g.dLambda, nullptr, nullptr}};
-  hipLaunchKernelGGL(reduce_rows_kernel, dim3(dblocks, 3), dim3(256), 0, s, (const float *)a.part,
-                     p.B * q.G, 3, p.D, gate_outs);
+  {
+    KernelTimer kt("reduce_rows_kernel", s);
+    hipLaunchKernelGGL(reduce_rows_kernel, dim3(dblocks, 3), dim3(256), 0, s, (const float *)a.part,
+                       p.B * q.G, 3, p.D, gate_outs);
+  }
 
   // 2. dgrad and Conv1D adjoint
   DgradArgs dg;
@@ -955,12 +966,18 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   dg.dpo = a.dpo; dg.dqo = a.dqo; dg.dxo = a.dxo;
   dg.wta = wta; dg.wtx = wtx;
   dg.part = (float *)(ws + q.off_partC);
-  hipLaunchKernelGGL(bwd_dgrad_kernel, dim3(q.units * q.C), dim3(NTHR), D_LDS, s, dg);
+  {
+    KernelTimer kt("bwd_dgrad_kernel", s);
+    hipLaunchKernelGGL(bwd_dgrad_kernel, dim3(q.units * q.C), dim3(NTHR), D_LDS, s, dg);
+  }
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const RowOuts5 conv_outs = {{p.g.dconv_w, p.g.dconv_w + p.D, p.g.dconv_w + 2 * (size_t)p.D,
                                p.g.dconv_w + 3 * (size_t)p.D, p.g.dconv_b}};
-  hipLaunchKernelGGL(reduce_rows_kernel, dim3(dblocks, 5), dim3(256), 0, s, (const float *)dg.part,
-                     p.B * q.C, 5, p.D, conv_outs);
+  {
+    KernelTimer kt("reduce_rows_kernel", s);
+    hipLaunchKernelGGL(reduce_rows_kernel, dim3(dblocks, 5), dim3(256), 0, s, (const float *)dg.part,
+                       p.B * q.C, 5, p.D, conv_outs);
+  }
 
   // 3. wgrad
   WgradArgs wg;
@@ -968,11 +985,17 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   wg.rows = (long long)p.B * p.T;
   wg.dpo = a.dpo; wg.dqo = a.dqo; wg.xo = a.xo; wg.xlo = a.xlo;
   wg.part = (float *)(ws + q.off_partW);
-  hipLaunchKernelGGL(bwd_wgrad_kernel, dim3(q.S * 2 * p.nb), dim3(NTHR), W_LDS, s, wg);
+  {
+    KernelTimer kt("bwd_wgrad_kernel", s);
+    hipLaunchKernelGGL(bwd_wgrad_kernel, dim3(q.S * 2 * p.nb), dim3(NTHR), W_LDS, s, wg);
+  }
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const size_t per_gate = (size_t)p.nb * BS * BS;
-  hipLaunchKernelGGL(reduce_wgrad_kernel, dim3((unsigned)((2 * per_gate + 255) / 256)), dim3(256), 0, s,
-                     (const float *)wg.part, q.S, per_gate, p.g.dW_a, p.g.dW_x);
+  {
+    KernelTimer kt("reduce_wgrad_kernel", s);
+    hipLaunchKernelGGL(reduce_wgrad_kernel, dim3((unsigned)((2 * per_gate + 255) / 256)), dim3(256), 0, s,
+                       (const float *)wg.part, q.S, per_gate, p.g.dW_a, p.g.dW_x);
+  }
   return hipGetLastError();
 }
 

@@ -415,6 +415,129 @@ fwd_mfma_kernel(FwdArgs a) {
   }
 }
 
+
+// ------------------------------------------------------------------------------ decode
+// One decode step (Section 5; states of Appendix F) for a tile of 32 sequences and one gate
+// block: the rows of the MFMA tile are sequences instead of time steps. The ring slot of the
+// new token is the slot of the lag-3 input, which the same thread has just read.
+constexpr int DEC_LDS = 2 * XT_ELEMS * 2 + 64 * 32;   // x tile (high, low) + selection operands
+
+struct DecArgs {
+  Problem p;   // u = u_t [B][D], hT = h [B][D] (in place), state_out = ring (in place), y = y_t
+};
+
+__global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
+decode_mfma_kernel(DecArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned short *xs = (unsigned short *)smem;                       // [high, low][32][XS]
+  bf16x8 *sel_lds = (bf16x8 *)(smem + 2 * XT_ELEMS * 2);
+  const Problem &p = a.p;
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, j = lane & 31;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = blockIdx.x, b0 = blockIdx.y * TT;
+  const int D = p.D, B = p.B;
+  const int ch = wv * 32 + j, d = g * BS + ch;
+
+  bf16x8 wa[16], wx[16];
+  {
+    const bf16x8 *pa = (const bf16x8 *)((const unsigned short *)p.W_a + ((size_t)g * BS + ch) * BS + hf * 8);
+    const bf16x8 *px = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) {
+      wa[ks] = pa[ks * 2];
+      wx[ks] = px[ks * 2];
+    }
+  }
+  if (tid < 64) {
+    bf16x8 sel0, sel1;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      sel0[e] = (__bf16)((hf * 8 + e == j) ? 1.0f : 0.0f);
+      sel1[e] = (__bf16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
+    }
+    sel_lds[lane] = sel0;
+    sel_lds[64 + lane] = sel1;
+  }
+
+  // ---- Conv1D over the ring for rows (sequences) 8*rg .. 8*rg+7, channel pair c2
+  {
+    const int c2 = tid & 127, rg = tid >> 7, dc = g * BS + 2 * c2;
+    float cw[4][2], cb[2];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      cw[k][0] = p.conv_w[(size_t)k * D + dc] * LOG2E;
+      cw[k][1] = p.conv_w[(size_t)k * D + dc + 1] * LOG2E;
+    }
+    cb[0] = p.conv_b ? p.conv_b[dc] * LOG2E : 0.f;
+    cb[1] = p.conv_b ? p.conv_b[dc + 1] * LOG2E : 0.f;
+    const int s1 = ring_slot(p.pos0 - 1), s2 = ring_slot(p.pos0 - 2), s3 = ring_slot(p.pos0 - 3);
+    unsigned short *ring = (unsigned short *)p.state_out;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const int b = b0 + 8 * rg + r;
+      unsigned hi_pk = 0, lo_pk = 0;
+      if (b < B) {
+        const unsigned u0 = *(const unsigned *)((const unsigned short *)p.u + (size_t)b * D + dc);
+        unsigned *st = (unsigned *)(ring + (size_t)b * 3 * D + dc);
+        const unsigned u1 = st[(size_t)s1 * (D / 2)], u2 = st[(size_t)s2 * (D / 2)], u3 = st[(size_t)s3 * (D / 2)];
+        float x0 = cb[0], x1 = cb[1];
+        x0 = fmaf(cw[0][0], bf_lo(u0), x0); x1 = fmaf(cw[0][1], bf_hi(u0), x1);
+        x0 = fmaf(cw[1][0], bf_lo(u1), x0); x1 = fmaf(cw[1][1], bf_hi(u1), x1);
+        x0 = fmaf(cw[2][0], bf_lo(u2), x0); x1 = fmaf(cw[2][1], bf_hi(u2), x1);
+        x0 = fmaf(cw[3][0], bf_lo(u3), x0); x1 = fmaf(cw[3][1], bf_hi(u3), x1);
+        split_bf16(x0, x1, hi_pk, lo_pk);
+        st[(size_t)s3 * (D / 2)] = u0;  // slot pos mod 3 == slot (pos-3) mod 3
+      }
+      *(unsigned *)(xs + (8 * rg + r) * XS + 2 * c2) = hi_pk;
+      *(unsigned *)(xs + XT_ELEMS + (8 * rg + r) * XS + 2 * c2) = lo_pk;
+    }
+  }
+  __syncthreads();
+
+  const float bias_p = p.b_a[d] * LOG2E, bias_q = p.b_x[d] * LOG2E;
+  float kd;
+  {
+    const float z = -p.Lambda[d];
+    const float sp = z > 0.f ? z + log1pf(expf(-z)) : log1pf(expf(z));
+    kd = -p.c * sp * LOG2E;
+  }
+  const int arow = ((j >> 2) & 1) * 16 + (j >> 3) * 4 + (j & 3);
+  const unsigned short *ap = xs + arow * XS + hf * 8;
+  f32x16 accp, accq, accx;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    accp[r] = bias_p;
+    accq[r] = bias_q;
+    accx[r] = 0.f;
+  }
+#pragma unroll
+  for (int ks = 0; ks < 16; ++ks) {
+    const bf16x8 av = *(const bf16x8 *)(ap + ks * 16);
+    accp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, wa[ks], accp, 0, 0, 0);
+    accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, wx[ks], accq, 0, 0, 0);
+  }
+  accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ap + (2 * wv) * 16), sel_lds[lane], accx, 0, 0, 0);
+  accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ap + (2 * wv + 1) * 16), sel_lds[64 + lane], accx, 0, 0, 0);
+  accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ap + XT_ELEMS + (2 * wv) * 16), sel_lds[lane], accx, 0, 0, 0);
+  accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ap + XT_ELEMS + (2 * wv + 1) * 16), sel_lds[64 + lane], accx, 0, 0, 0);
+
+  // ---- eq. (4) for the 16 sequences of this lane's run
+  float *h = p.hT;
+  unsigned short *y = (unsigned short *)p.y;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int b = b0 + hf * 16 + r;
+    if (b < B) {
+      const size_t o = (size_t)b * D + d;
+      float av, bv;
+      gate_fast(accp[r], accq[r], accx[r], kd, av, bv);
+      const float hn = fmaf(av, h[o], bv);
+      h[o] = hn;
+      y[o] = (unsigned short)(pack_bf16(hn, 0.f) & 0xffff);
+    }
+  }
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------------------ host side
@@ -434,6 +557,7 @@ int mfma::num_cu() {
 
 hipError_t mfma::launch_zero(void *ptr, size_t bytes, hipStream_t s) {
   const size_t n16 = bytes / 16;
+  KernelTimer kt("zero_words_kernel", s);
   hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s,
                      (uint4 *)ptr, n16);
   return hipGetLastError();
@@ -477,6 +601,7 @@ static hipError_t launch_t(const FwdArgs &a, int grid, size_t lds, hipStream_t s
     if (e != hipSuccess) return e;
     configured = true;
   }
+  KernelTimer kt("fwd_mfma_kernel", s);
   hipLaunchKernelGGL(fwd_mfma_kernel<GMAX>, dim3(grid), dim3(NTHR), lds, s, a);
   return hipGetLastError();
 }
@@ -503,6 +628,19 @@ hipError_t launch_forward_mfma(const Problem &p, hipStream_t s) {
   if (e != hipSuccess) return e;
   return a.G <= 4 ? launch_t<4>(a, grid, FWD_LDS, s)
                   : launch_t<8>(a, grid, FWD_LDS, s);
+}
+
+bool decode_mfma_supported(const Problem &p, bool bf) {
+  return bf && p.bs == BS && ((uintptr_t)p.W_a % 16 == 0) && ((uintptr_t)p.W_x % 16 == 0) &&
+         ((uintptr_t)p.u % 4 == 0) && ((uintptr_t)p.state_out % 4 == 0);
+}
+
+hipError_t launch_decode_mfma(const Problem &p, hipStream_t s) {
+  DecArgs a;
+  a.p = p;
+  KernelTimer kt("decode_mfma_kernel", s);
+  hipLaunchKernelGGL(decode_mfma_kernel, dim3(p.nb, (p.B + TT - 1) / TT), dim3(NTHR), DEC_LDS, s, a);
+  return hipGetLastError();
 }
 
 }  // namespace rglru

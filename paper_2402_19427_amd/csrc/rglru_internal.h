@@ -56,6 +56,15 @@ struct Problem {
   size_t ws_bytes;
 };
 
+// Benchmark timing: brackets a kernel launch with HIP events when timing is enabled on this
+// thread (see rglru_timing_enable in rglru.h). Usage: { KernelTimer t("name", stream); launch; }
+struct KernelTimer {
+  hipStream_t s;
+  int slot;
+  KernelTimer(const char *name, hipStream_t stream);
+  ~KernelTimer();
+};
+
 // Launchers. Each returns hipSuccess or the launch error. `bf` selects bf16 act+weights.
 hipError_t launch_conv1d_generic(const Problem &p, bool bf, void *x_out, hipStream_t s);
 hipError_t launch_state_update(const Problem &p, bool bf, hipStream_t s);
@@ -69,6 +78,10 @@ size_t generic_lds_bytes(int bs);
 bool forward_mfma_supported(const Problem &p, bool bf);
 size_t forward_mfma_ws_bytes(int B, int T, int D, int nb);
 hipError_t launch_forward_mfma(const Problem &p, hipStream_t s);
+
+// MFMA decode step (bf16 storage, gate blocks of 256)
+bool decode_mfma_supported(const Problem &p, bool bf);
+hipError_t launch_decode_mfma(const Problem &p, hipStream_t s);
 
 // MFMA backward (bf16 storage, gate blocks of 256)
 bool backward_mfma_supported(const Problem &p, bool bf);
