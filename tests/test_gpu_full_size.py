@@ -1,0 +1,139 @@
+"""Parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+
+The oracle cannot run a whole workload in seconds, so outputs are checked on sampled
+(sequence, gate block) pairs: the path is independent across sequences and across gate blocks
+(depthwise Conv1D, block-diagonal gates, diagonal recurrence), so the oracle evaluates one pair
+as a problem of its own (B = 1, nb = 1, D = bs) from the same inputs. Parameter gradients sum
+over sequences, so for a sampled block every sequence is run through the oracle.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import rglru_inputs as gen
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2   # bf16 storage, fp32 state and accumulation
+
+
+def block_params(inp, g, bs):
+    sl = slice(g * bs, (g + 1) * bs)
+    f = lambda a: np.asarray(a, np.float64)
+    return sl, (f(inp["W_a"][g:g + 1]), f(inp["W_x"][g:g + 1]), f(inp["b_a"][sl]), f(inp["b_x"][sl]),
+                f(inp["Lambda"][sl]), f(inp["conv_w"][:, sl]))
+
+
+def run_forward_full(name, pairs):
+    import paper_2402_19427_amd.runner as rn
+    w = gen.CONFIGS[name]
+    inp = gen.make_workload(name, dy=False)
+    dp = rn.DeviceProblem(inp, w.B, w.T, w.D, w.nb, w.act)
+    u = rn.to_device(inp["u"], w.act)
+    h0 = rn.to_device(inp["h0"], "f32")
+    y, hT, st = dp.forward(u, h0=h0)
+    y_h, hT_h, st_h = rn.to_host(y), rn.to_host(hT), rn.to_host(st)
+    del y, u
+    oracle.set_threads(1)
+    for b, g in pairs:
+        sl, par = block_params(inp, g, w.bs)
+        h0_u = None if inp["h0"] is None else np.asarray(inp["h0"][b:b + 1, sl], np.float64)
+        y_ref, hT_ref, st_ref = oracle.forward(np.asarray(inp["u"][b:b + 1, :, sl], np.float64), *par,
+                                               h0=h0_u)
+        assert gen.rel_err(y_h[b:b + 1, :, sl], y_ref) < TOL, (name, b, g)
+        assert gen.rel_err(hT_h[b:b + 1, sl], hT_ref) < TOL, (name, b, g)
+        np.testing.assert_array_equal(gen.chrono_from_ring(st_h[b:b + 1, :, sl], w.T), st_ref)
+    # a property that holds for every element: the outputs are finite
+    assert np.isfinite(y_h).all() and np.isfinite(hT_h).all()
+
+
+def test_c1_training_shaped_forward_full_size():
+    run_forward_full("C1", [(0, 0), (3, 7), (7, 9)])
+
+
+def test_c2_long_sequence_forward_full_size():
+    # one sequence of 32768 steps with a random initial state: every tile boundary and every
+    # time slice of the carry exchange lies on the path to the last outputs
+    run_forward_full("C2", [(0, 0), (0, 9)])
+
+
+def test_c4_forward_and_backward_full_size():
+    import paper_2402_19427_amd.runner as rn
+    w = gen.CONFIGS["C4"]
+    inp = gen.make_workload("C4")
+    dp = rn.DeviceProblem(inp, w.B, w.T, w.D, w.nb, w.act)
+    u = rn.to_device(inp["u"], w.act)
+    dy = rn.to_device(inp["dy"], w.act)
+    y, hT, _ = dp.forward(u, want_state=False)
+    out = dp.backward(u, y, dy)
+    y_h, du_h, dh0_h = rn.to_host(y), rn.to_host(out["du"]), rn.to_host(out["dh0"])
+    small = {k: rn.to_host(out[k]) for k in ("dW_a", "dW_x", "db_a", "db_x", "dLambda", "dconv_w",
+                                             "dconv_b")}
+    del y, u, dy, out
+    g = 5   # every sequence of one gate block: parameter gradients sum over the batch
+    sl, par = block_params(inp, g, w.bs)
+    acc = None
+    oracle.set_threads(1)
+    for b in range(w.B):
+        ub = np.asarray(inp["u"][b:b + 1, :, sl], np.float64)
+        dyb = np.asarray(inp["dy"][b:b + 1, :, sl], np.float64)
+        ref = oracle.backward(ub, *par, dyb)
+        if b in (0, 9):
+            y_ref, _, _ = oracle.forward(ub, *par)
+            assert gen.rel_err(y_h[b:b + 1, :, sl], y_ref) < TOL, b
+        assert gen.rel_err(du_h[b:b + 1, :, sl], ref["du"]) < TOL, b
+        assert gen.rel_err(dh0_h[b:b + 1, sl], ref["dh0"]) < TOL, b
+        if acc is None:
+            acc = {k: ref[k].copy() for k in small}
+        else:
+            for k in small:
+                acc[k] += ref[k]
+    assert gen.rel_err(small["dW_a"][g], acc["dW_a"][0]) < TOL
+    assert gen.rel_err(small["dW_x"][g], acc["dW_x"][0]) < TOL
+    for k in ("db_a", "db_x", "dLambda", "dconv_b"):
+        assert gen.rel_err(small[k][sl], acc[k]) < TOL, k
+    assert gen.rel_err(small["dconv_w"][:, sl], acc["dconv_w"]) < TOL
+    assert np.isfinite(du_h).all() and all(np.isfinite(v).all() for v in small.values())
+
+
+def test_c3_batched_decode_full_size():
+    import paper_2402_19427_amd.runner as rn
+    w = gen.CONFIGS["C3"]
+    inp = gen.make_workload("C3")
+    dp = rn.DeviceProblem(inp, w.B, 1, w.D, w.nb, w.act)
+    pos0 = 4096
+    h = rn.to_device(inp["h0"], "f32")
+    ring = rn.to_device(gen.ring_from_chrono(inp["state"], pos0), w.act)
+    toks = [rn.to_device(inp["u_dec"][i], w.act) for i in range(8)]
+    blocks = (0, 11)
+    refs = {}
+    for g in blocks:
+        sl, par = block_params(inp, g, w.bs)
+        refs[g] = (sl, par, np.asarray(inp["h0"][:, sl], np.float64).copy(),
+                   np.asarray(inp["state"][:, :, sl], np.float64).copy())
+    for s in range(64):
+        y = dp.decode_step(toks[s % 8], h, ring, pos0 + s)
+        check = s < 4 or s == 63
+        if check:
+            y_h, h_h, ring_h = rn.to_host(y), rn.to_host(h), rn.to_host(ring)
+        for g in blocks:
+            sl, par, h_ref, st_ref = refs[g]
+            y_ref = oracle.decode_step(np.asarray(inp["u_dec"][s % 8][:, sl], np.float64), *par,
+                                       h_ref, st_ref)
+            if check:
+                assert gen.rel_err(y_h[:, sl], y_ref) < TOL, (s, g)
+                assert gen.rel_err(h_h[:, sl], h_ref) < TOL, (s, g)
+                np.testing.assert_array_equal(
+                    gen.chrono_from_ring(ring_h[:, :, sl], pos0 + s + 1), st_ref)
+
+
+def test_c0_tiny_fp32_full_size():
+    import paper_2402_19427_amd.runner as rn
+    w = gen.CONFIGS["C0"]
+    inp = gen.make_workload("C0")
+    dp = rn.DeviceProblem(inp, w.B, w.T, w.D, w.nb, w.act)
+    y, hT, _ = dp.forward(rn.to_device(inp["u"], w.act))
+    q = {k: (None if v is None else np.asarray(v, np.float64)) for k, v in inp.items()}
+    y_ref, hT_ref, _ = oracle.forward(q["u"], q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"],
+                                      q["conv_w"])
+    assert gen.rel_err(rn.to_host(y), y_ref) < 1e-5
+    assert gen.rel_err(rn.to_host(hT), hT_ref) < 1e-5
