@@ -87,6 +87,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy, the reference that scales the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
@@ -131,6 +134,12 @@ def main():
         R.rglru_decode_step(sh1, dp.params, u_next, hT, st, T, y1, sh_ptr)
         R.rglru_backward(sh, dp.params, u, h0, None, 0, y, dy, None, du, dh0, pg, ws_b, n_b, sh_ptr)
 
+    if args.calibration_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)   # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

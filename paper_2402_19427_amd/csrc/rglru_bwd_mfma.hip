@@ -40,6 +40,7 @@ struct BwdArgs {
   Problem p;
   int G, ntile, R;
   u64 *rec;
+  unsigned *flags;                        // [unit][R][8 waves]: tile + 1 once a wave's records are out
   int *err;
   int swizzle;
   unsigned short *xo, *xlo, *dpo, *dqo;  // bf16 [B][T][D]: log2(e)*x (high part, low part), dp, dq
@@ -80,15 +81,18 @@ bwd_gates_kernel(BwdArgs a) {
   const int ch = wv * 32 + j;
   const int d = g * BS + ch;
 
-  bf16x8 wa[16], wx[16];
+  // gate weights of this wave's 32 output channels: all of W_a and the first NRES K-steps of W_x
+  // stay in registers; the rest of W_x is re-read from L2 every tile (the register file cannot
+  // hold everything this kernel needs, and L2 is a far better spill space than scratch)
+  constexpr int NRES = 4;
+  bf16x8 wa[16], wx[NRES];
+  const bf16x8 *pxs = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
   {
     const bf16x8 *pa = (const bf16x8 *)((const unsigned short *)p.W_a + ((size_t)g * BS + ch) * BS + hf * 8);
-    const bf16x8 *px = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
 #pragma unroll
-    for (int ks = 0; ks < 16; ++ks) {
-      wa[ks] = pa[ks * 2];
-      wx[ks] = px[ks * 2];
-    }
+    for (int ks = 0; ks < 16; ++ks) wa[ks] = pa[ks * 2];
+#pragma unroll
+    for (int ks = 0; ks < NRES; ++ks) wx[ks] = pxs[ks * 2];
   }
   if (tid < 64) {
     bf16x8 sel0, sel1;
@@ -223,6 +227,7 @@ bwd_gates_kernel(BwdArgs a) {
   const uint4 *yT_mine = (const uint4 *)(yT + ch * TS + hf * 16);
 
   u64 *ring = GMAX > 1 ? a.rec + (size_t)unit * a.R * 2 * BS + ch : nullptr;
+  unsigned *flag_ring = GMAX > 1 ? a.flags + (size_t)unit * a.R * NWAVE + wv : nullptr;
   float carry = p.dhT ? p.dhT[(size_t)b * D + d] : 0.f;  // eps entering this workgroup's next tile
   float s_ba = 0.f, s_bx = 0.f, s_lam = 0.f;
   int spins = 0;
@@ -237,7 +242,6 @@ bwd_gates_kernel(BwdArgs a) {
   for (int it = 0; tile >= 0; tile -= G, ++it) {
     const int buf = it & 1, t0 = tile * TT;
     const int next = tile - G;
-    if (next >= 0) load_rows(next * TT);
     load_dy_y(t0);
 
     // ---- gate pre-activations on the matrix cores
@@ -251,11 +255,18 @@ bwd_gates_kernel(BwdArgs a) {
     const unsigned short *ap = arow_base + buf * (2 * XT_ELEMS);
     {
       bf16x8 a0 = *(const bf16x8 *)(ap), a1 = *(const bf16x8 *)(ap + 16);
+      bf16x8 s0 = pxs[NRES * 2], s1 = pxs[(NRES + 1) * 2];   // streamed W_x fragments, two ahead
 #pragma unroll
       for (int ks = 0; ks < 16; ++ks) {
         const bf16x8 a2 = *(const bf16x8 *)(ap + ((ks + 2) & 15) * 16);
         accp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wa[ks], accp, 0, 0, 0);
-        accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wx[ks], accq, 0, 0, 0);
+        if (ks < NRES) {
+          accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wx[ks], accq, 0, 0, 0);
+        } else {
+          accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, s0, accq, 0, 0, 0);
+          s0 = s1;
+          if (ks + 2 < 16) s1 = pxs[(ks + 2) * 2];
+        }
         __builtin_amdgcn_sched_barrier(0);
         a0 = a1;
         a1 = a2;
@@ -272,6 +283,7 @@ bwd_gates_kernel(BwdArgs a) {
       accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(l1, sel_lds[64 + lane], accx, 0, 0, 0);
     }
     park_dy_y();
+    if (next >= 0) load_rows(next * TT);  // consumed by conv_rows at the end of the iteration
     __syncthreads();
 
     // ---- first sweep (latest step first): r_t, a_t into LDS, aggregate of this lane's run:
@@ -305,6 +317,11 @@ bwd_gates_kernel(BwdArgs a) {
     float e_in = carry;
     if (GMAX > 1) {
       publish(ring + (size_t)(tile % a.R) * 2 * BS + hf * BS, hf ? E_t : A_t, (unsigned)(tile + 1));
+      // once this wave's records have left, raise its flag: waiting waves poll one word
+      // instead of hammering the records
+      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+      __hip_atomic_store(flag_ring + (size_t)(tile % a.R) * NWAVE, (unsigned)(tile + 1), __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
       // eps entering this tile: own state after tile+G carried across tiles tile+G-1 .. tile+1
 #pragma unroll
       for (int s = GMAX - 2; s >= 0; --s) {
@@ -312,6 +329,12 @@ bwd_gates_kernel(BwdArgs a) {
         if (s < G - 1 && k < a.ntile) {
           const u64 *slot = ring + (size_t)(k % a.R) * 2 * BS;
           const unsigned want = (unsigned)(k + 1);
+          const unsigned *fl = flag_ring + (size_t)(k % a.R) * NWAVE;
+          while (__hip_atomic_load(fl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != want &&
+                 spins < SPIN_LIMIT) {
+            ++spins;
+            __builtin_amdgcn_s_sleep(2);
+          }
           u64 ra = peek(slot), re = peek(slot + BS);
           while ((unsigned)(ra >> 32) != want && spins < SPIN_LIMIT) {
             ++spins;
@@ -362,6 +385,7 @@ bwd_gates_kernel(BwdArgs a) {
         s_ba += dpv[e];
         s_bx += dqv[e];
         erev = ok ? av * delta : erev;
+        __builtin_amdgcn_sched_barrier(0);  // one element at a time: registers are scarce here
       }
       const unsigned soq = so + (unsigned)(4 * q) * row_bytes;
       const unsigned p0 = pack_bf16(dpv[0], dpv[1]), p1 = pack_bf16(dpv[2], dpv[3]);
@@ -869,7 +893,7 @@ BwdPlan plan_backward(int B, int T, int D, int nb, int ncu) {
   q.off_dx = off; off += 2 * N2;
   q.off_wta = off; off += wbytes;
   q.off_wtx = off; off += wbytes;
-  q.off_rec = off; off += al256(256 + (size_t)q.units * q.R * 2 * BS * sizeof(u64));
+  q.off_rec = off; off += al256(256 + (size_t)q.units * q.R * (2 * BS * sizeof(u64) + NWAVE * 4));
   q.off_partA = off; off += al256((size_t)B * q.G * 3 * D * 4);
   q.off_partC = off; off += al256((size_t)B * q.C * 5 * D * 4);
   q.off_partW = off; off += al256((size_t)q.S * 2 * nb * BS * BS * 4);
@@ -930,6 +954,7 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   a.G = q.G; a.ntile = q.ntile; a.R = q.R;
   a.err = (int *)(ws + q.off_rec);
   a.rec = (u64 *)(ws + q.off_rec + 256);
+  a.flags = (unsigned *)(ws + q.off_rec + 256 + (size_t)q.units * q.R * 2 * BS * sizeof(u64));
   a.xo = (unsigned short *)(ws + q.off_x);
   a.xlo = (unsigned short *)(ws + q.off_xl);
   a.dpo = (unsigned short *)(ws + q.off_dp);
@@ -939,7 +964,7 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   const int grid = q.units * q.G;
   a.swizzle = (q.G > 1 && grid % 8 == 0) ? 1 : 0;
   if (q.G > 1 &&
-      (e = launch_zero(ws + q.off_rec, 256 + (size_t)q.units * q.R * 2 * BS * sizeof(u64), s)) != hipSuccess)
+      (e = launch_zero(ws + q.off_rec, 256 + (size_t)q.units * q.R * (2 * BS * sizeof(u64) + NWAVE * 4), s)) != hipSuccess)
     return e;
   {
     KernelTimer kt("bwd_gates_kernel", s);

@@ -90,15 +90,18 @@ fwd_mfma_kernel(FwdArgs a) {
   const int d = g * BS + ch;
 
   // ---- gate weights of this wave's 32 output channels, resident in registers
-  bf16x8 wa[16], wx[16];
+  // (when the sequence is sliced in time the kernel needs more registers for the carry
+  // exchange; the last K-steps of W_x are then re-read from L2 every tile - a far better spill
+  // space than scratch memory)
+  constexpr int NRES = GMAX == 1 ? 16 : (GMAX == 4 ? 8 : 4);
+  bf16x8 wa[16], wx[NRES];
+  const bf16x8 *pxs = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
   {
     const bf16x8 *pa = (const bf16x8 *)((const unsigned short *)p.W_a + ((size_t)g * BS + ch) * BS + hf * 8);
-    const bf16x8 *px = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
 #pragma unroll
-    for (int ks = 0; ks < 16; ++ks) {
-      wa[ks] = pa[ks * 2];
-      wx[ks] = px[ks * 2];
-    }
+    for (int ks = 0; ks < 16; ++ks) wa[ks] = pa[ks * 2];
+#pragma unroll
+    for (int ks = 0; ks < NRES; ++ks) wx[ks] = pxs[ks * 2];
   }
   // selection matrices that copy this wave's 32 columns of the tile into accumulator layout
   // (the same for every wave; parked in LDS to keep registers for the weights)
@@ -292,6 +295,11 @@ fwd_mfma_kernel(FwdArgs a) {
     const unsigned short *ap = arow_base + buf * (2 * XT_ELEMS);
     {
       bf16x8 a0 = *(const bf16x8 *)(ap), a1 = *(const bf16x8 *)(ap + 16);
+      bf16x8 st0 = a0, st1 = a0;  // streamed W_x fragments, two K-steps ahead
+      if (NRES < 16) {
+        st0 = pxs[NRES * 2];
+        st1 = pxs[(NRES + 1 < 16 ? NRES + 1 : 15) * 2];
+      }
 #ifdef RGLRU_EXP_NOGEMM
 #pragma unroll 1
       for (int ks = 0; ks < 1; ++ks) {
@@ -301,7 +309,13 @@ fwd_mfma_kernel(FwdArgs a) {
 #endif
         const bf16x8 a2 = *(const bf16x8 *)(ap + ((ks + 2) & 15) * 16);  // two steps ahead
         accp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wa[ks], accp, 0, 0, 0);
-        accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wx[ks], accq, 0, 0, 0);
+        if (ks < NRES) {
+          accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wx[ks], accq, 0, 0, 0);
+        } else {
+          accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, st0, accq, 0, 0, 0);
+          st0 = st1;
+          if (ks + 2 < 16) st1 = pxs[(ks + 2) * 2];
+        }
         __builtin_amdgcn_sched_barrier(0);
         a0 = a1;
         a1 = a2;
