@@ -426,13 +426,16 @@ bwd_gates_kernel(BwdArgs a) {
 
 
 // ------------------------------------------------------------------------------ dgrad
-// A tile: [32 steps][dp 256 | dq 256] bf16, row stride 520 elements (1040 B)
-constexpr int AS = 2 * BS + 8;
-constexpr int D_A_BYTES = 2 * TT * AS * 2;           // two A tiles
+// A tile: 32 steps x (dp 256 | dq 256) bf16, filled by direct-to-LDS loads (layout below);
+// two of them, two u tiles of 35 rows, and the selection fragments.
+constexpr int AS = 2 * BS + 8;                       // slot stride in elements (1040 B)
+constexpr int D_A_TILE = TT * AS * 2;                // one A tile: 16 dp slots, then 16 dq slots
+constexpr int D_A_BYTES = 2 * D_A_TILE;              // two A tiles
 constexpr int US_ROWS = TT + 3;                      // u rows t0-3 .. t0+31
 constexpr int D_OFF_SEL = D_A_BYTES;
 constexpr int D_OFF_U = D_OFF_SEL + 64 * 32;
-constexpr int D_LDS = D_OFF_U + US_ROWS * XS * 2;
+constexpr int D_U_TILE = US_ROWS * XS * 2;
+constexpr int D_LDS = D_OFF_U + 2 * D_U_TILE;
 
 struct DgradArgs {
   Problem p;
@@ -443,13 +446,15 @@ struct DgradArgs {
   float *part;                             // [B*C][5][D]: dconv_w[0..3], dconv_b partial sums
 };
 
-__global__ void __launch_bounds__(256) transpose_weights_kernel(const unsigned short *W,
-                                                                unsigned short *WT, int nmat) {
+__global__ void __launch_bounds__(256) transpose_weights_kernel(const unsigned short *Wa,
+                                                                const unsigned short *Wx,
+                                                                unsigned short *WTa,
+                                                                unsigned short *WTx, int nmat) {
   __shared__ unsigned short tile[32][33];
-  const int m = blockIdx.z, bx = blockIdx.x * 32, by = blockIdx.y * 32;
-  if (m >= nmat) return;
-  const unsigned short *src = W + (size_t)m * BS * BS;
-  unsigned short *dst = WT + (size_t)m * BS * BS;
+  const int m = blockIdx.z % nmat, which = blockIdx.z / nmat;
+  const int bx = blockIdx.x * 32, by = blockIdx.y * 32;
+  const unsigned short *src = (which ? Wx : Wa) + (size_t)m * BS * BS;
+  unsigned short *dst = (which ? WTx : WTa) + (size_t)m * BS * BS;
   for (int i = threadIdx.x; i < 32 * 32; i += 256) {
     const int r = i >> 5, c = i & 31;
     tile[r][c] = src[(size_t)(by + r) * BS + bx + c];
@@ -464,9 +469,9 @@ __global__ void __launch_bounds__(256) transpose_weights_kernel(const unsigned s
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 bwd_dgrad_kernel(DgradArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  unsigned short *as = (unsigned short *)smem;                       // [2][TT][AS]
+  unsigned short *as = (unsigned short *)smem;                       // [2] A tiles
   bf16x8 *sel_lds = (bf16x8 *)(smem + D_OFF_SEL);
-  unsigned short *us = (unsigned short *)(smem + D_OFF_U);           // [35][XS]
+  unsigned short *us = (unsigned short *)(smem + D_OFF_U);           // [2][35][XS]
   const Problem &p = a.p;
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, j = lane & 31;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -514,29 +519,20 @@ bwd_dgrad_kernel(DgradArgs a) {
       uniform_ptr(a.dxo + seq_off), 0, 2 * seq_bytes, 0x00020000);
   const unsigned o_voff = (unsigned)d * 2 + (unsigned)hf * 16 * row_bytes;
 
-  // loaders: 16 bytes (8 channels) per thread; a 512-byte row is covered by 32 threads
-  const int lc = tid & 31, lr = tid >> 5;               // channel group, row 0..15
-  const unsigned l_voff = (unsigned)(g * BS + 8 * lc) * 2;
-  uint4 ra[4];                                          // rows lr, lr+16 of dp, dq
-  auto load_a = [&](int t0) {
+  // A tiles go from global memory straight into LDS, 16 bytes per lane: one instruction lays
+  // 1024 contiguous bytes, the 256 channels of row r (lanes 0-31) and of row r+8 (lanes 32-63)
+  // of one array. Slot s = (r & 7) + 8 (r >> 4) holds that pair; rows r and r+8 never meet in
+  // one 16-lane group of the fragment reads, so the 1040-byte slot stride keeps them apart in
+  // the banks. Rows past the end of the sequence are out of the buffer's range and read as zero.
+  const unsigned a_voff = (unsigned)(g * BS + 8 * (lane & 31)) * 2 + (unsigned)(lane >> 5) * 8 * row_bytes;
+  auto load_a = [&](int buf, int t0) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int t = t0 + lr + 16 * h;
-      uint4 z = make_uint4(0, 0, 0, 0);
-      ra[h] = ra[2 + h] = z;
-      if (t < T) {
-        const unsigned so = (unsigned)t * row_bytes;
-        ra[h] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(dp_rsrc, l_voff, so, 0));
-        ra[2 + h] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(dq_rsrc, l_voff, so, 0));
-      }
-    }
-  };
-  auto park_a = [&](int buf) {
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      unsigned short *row = as + buf * (TT * AS) + (lr + 16 * h) * AS + 8 * lc;
-      *(uint4 *)(row) = ra[h];
-      *(uint4 *)(row + BS) = ra[2 + h];
+    for (int i = 0; i < 2; ++i) {
+      const int sl = wv * 2 + i, r0 = (sl & 7) + (sl >> 3) * 16;
+      const unsigned so = (unsigned)(t0 + r0) * row_bytes;
+      unsigned char *dst = smem + buf * D_A_TILE + sl * (AS * 2);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(dp_rsrc, (__attribute__((address_space(3))) void *)dst, 16, a_voff, so, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(dq_rsrc, (__attribute__((address_space(3))) void *)(dst + D_A_TILE / 2), 16, a_voff, so, 0, 0);
     }
   };
   // dxd of this lane's run (channel d, 16 consecutive steps), fp32, zero past the sequence end
@@ -551,7 +547,10 @@ bwd_dgrad_kernel(DgradArgs a) {
             dx_rsrc, 2 * o_voff, 2 * (unsigned)(t0 + r) * row_bytes, 0));
     }
   };
-  // u rows t0-3 .. t0+31 (35 rows): rows lr, lr+16 and (for lr < 3) lr+32
+  // u rows t0-3 .. t0+31 (35 rows), 16 bytes (8 channels) per thread: rows lr, lr+16 and
+  // (for lr < 3) lr+32
+  const int lc = tid & 31, lr = tid >> 5;
+  const unsigned u_voff = (unsigned)(g * BS + 8 * lc) * 2;
   const unsigned *st32 =
       p.state_in ? (const unsigned *)((const unsigned short *)p.state_in + (size_t)b * 3 * D + g * BS + 8 * lc)
                  : nullptr;
@@ -563,7 +562,7 @@ bwd_dgrad_kernel(DgradArgs a) {
       uint4 v = make_uint4(0, 0, 0, 0);
       if (rho < US_ROWS) {
         if (t >= 0) {
-          if (t < T) v = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(u_rsrc, l_voff, (unsigned)t * row_bytes, 0));
+          if (t < T) v = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(u_rsrc, u_voff, (unsigned)t * row_bytes, 0));
         } else if (st32) {
           v = *(const uint4 *)(st32 + (size_t)ring_slot(p.pos0 + t) * (D / 2));
         }
@@ -571,16 +570,16 @@ bwd_dgrad_kernel(DgradArgs a) {
       ru[h] = v;
     }
   };
-  auto park_u = [&]() {
+  auto park_u = [&](int ub) {
 #pragma unroll
     for (int h = 0; h < 3; ++h) {
       const int rho = lr + 16 * h;
-      if (rho < US_ROWS) *(uint4 *)(us + rho * XS + 8 * lc) = ru[h];
+      if (rho < US_ROWS) *(uint4 *)(us + ub * (D_U_TILE / 2) + rho * XS + 8 * lc) = ru[h];
     }
   };
 
   const int arow = ((j >> 2) & 1) * 16 + (j >> 3) * 4 + (j & 3);
-  const unsigned short *arow_base = as + arow * AS + hf * 8;
+  const unsigned short *arow_base = as + ((arow & 7) + (arow >> 4) * 8) * AS + ((arow >> 3) & 1) * BS + hf * 8;
   const unsigned short *urow_base = us + (arow + 3) * XS + (2 * wv) * 16 + hf * 8;
 
   // this workgroup's tiles [lo, hi), walked backwards; tile hi (if any) only supplies the
@@ -590,28 +589,33 @@ bwd_dgrad_kernel(DgradArgs a) {
   float sw[4] = {0.f, 0.f, 0.f, 0.f}, sb = 0.f;
   float nx0 = 0.f, nx1 = 0.f, nx2 = 0.f;  // dx at the first three steps of the next tile (upper half lanes)
   if (lo < hi) {
+    // One barrier per tile. Everything a tile needs from memory is requested a whole iteration
+    // ahead, right after the barrier of the tile before it: the A tile two tiles on (into the
+    // buffer whose last readers have just passed that barrier), dxd and u of the next tile (into
+    // the registers just consumed). The barrier's wait for outstanding loads therefore finds
+    // them done. The u tile is double-buffered so that the taps' sums of one tile may still read
+    // it while the next tile is parked.
     int tile = hi < a.ntile ? hi : hi - 1;
-    load_a(tile * TT);
-    __syncthreads();
-    park_a(0);
+    load_a(0, tile * TT);
+    if (tile > lo) load_a(1, (tile - 1) * TT);
+    load_dxd(tile * TT);
+    if (tile != hi) load_u(tile * TT);
     __syncthreads();
     for (int it = 0; tile >= lo; --tile, ++it) {
       const int buf = it & 1, t0 = tile * TT;
       const bool halo = tile == hi;
-      if (tile > lo) load_a((tile - 1) * TT);
-      if (!halo) load_u(t0);
-      load_dxd(t0);
 
       f32x16 acc0, acc1;
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc0[r] = acc1[r] = 0.f;
-      const unsigned short *ap = arow_base + buf * (TT * AS);
+      const unsigned short *ap = arow_base + buf * (D_A_TILE / 2);
       {
-        bf16x8 a0 = *(const bf16x8 *)(ap), a1 = *(const bf16x8 *)(ap + BS);
+        constexpr int DQ = D_A_TILE / 4;   // dq slots, in elements
+        bf16x8 a0 = *(const bf16x8 *)(ap), a1 = *(const bf16x8 *)(ap + DQ);
 #pragma unroll
         for (int ks = 0; ks < 16; ++ks) {
           const bf16x8 n0 = *(const bf16x8 *)(ap + ((ks + 1) & 15) * 16);
-          const bf16x8 n1 = *(const bf16x8 *)(ap + BS + ((ks + 1) & 15) * 16);
+          const bf16x8 n1 = *(const bf16x8 *)(ap + DQ + ((ks + 1) & 15) * 16);
           acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wa[ks], acc0, 0, 0, 0);
           acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, wx[ks], acc1, 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
@@ -629,10 +633,14 @@ bwd_dgrad_kernel(DgradArgs a) {
       dx[17] = hf ? nx1 : s1v;
       dx[18] = hf ? nx2 : s2v;
       nx0 = s0v; nx1 = s1v; nx2 = s2v;
-
+      if (!halo) park_u(buf);
+      __syncthreads();
+      if (tile - 2 >= lo) load_a(buf, t0 - 2 * TT);
+      if (tile > lo) {
+        load_dxd(t0 - TT);
+        load_u(t0 - TT);
+      }
       if (!halo) {
-        park_u();
-        __syncthreads();
         // Conv1D adjoint towards the input
         const unsigned so = (unsigned)t0 * row_bytes;
         const int nvalid = T - t0 - hf * 16;
@@ -656,7 +664,7 @@ bwd_dgrad_kernel(DgradArgs a) {
           f32x16 au;
 #pragma unroll
           for (int r = 0; r < 16; ++r) au[r] = 0.f;
-          const unsigned short *up = urow_base - k * XS;
+          const unsigned short *up = urow_base + buf * (D_U_TILE / 2) - k * XS;
           au = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(up), sel_lds[lane], au, 0, 0, 0);
           au = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(up + 16), sel_lds[64 + lane], au, 0, 0, 0);
 #pragma unroll
@@ -665,8 +673,6 @@ bwd_dgrad_kernel(DgradArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) sb += dx[r];
       }
-      if (tile > lo) park_a(buf ^ 1);
-      __syncthreads();
     }
   }
   // partial sums of this workgroup
@@ -938,13 +944,8 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   unsigned short *wta = (unsigned short *)(ws + q.off_wta), *wtx = (unsigned short *)(ws + q.off_wtx);
   {
     KernelTimer kt("transpose_weights_kernel", s);
-    hipLaunchKernelGGL(transpose_weights_kernel, dim3(BS / 32, BS / 32, p.nb), dim3(256), 0, s,
-                       (const unsigned short *)p.W_a, wta, p.nb);
-  }
-  {
-    KernelTimer kt("transpose_weights_kernel", s);
-    hipLaunchKernelGGL(transpose_weights_kernel, dim3(BS / 32, BS / 32, p.nb), dim3(256), 0, s,
-                       (const unsigned short *)p.W_x, wtx, p.nb);
+    hipLaunchKernelGGL(transpose_weights_kernel, dim3(BS / 32, BS / 32, 2 * p.nb), dim3(256), 0, s,
+                       (const unsigned short *)p.W_a, (const unsigned short *)p.W_x, wta, wtx, p.nb);
   }
   if ((e = hipGetLastError()) != hipSuccess) return e;
 

@@ -21,6 +21,8 @@
 // is evaluated as ln(2)*sigmoid, which cancels the factor carried by x.
 #include "rglru_mfma.h"
 
+#include <type_traits>
+
 namespace rglru {
 
 using namespace mfma;
@@ -28,6 +30,23 @@ using namespace mfma;
 namespace {
 
 constexpr int FWD_LDS = XS_BYTES + CONST_BYTES + HOLD_BYTES + NWAVE * OTILE_BYTES;
+
+// Optional phase timestamps for tuning builds (compiled out otherwise): wave `wv` of workgroup
+// `wg` records the shader clock at up to 8 points of each of its first 32 iterations.
+#ifndef RGLRU_ROTATE
+#define RGLRU_ROTATE 1
+#endif
+#ifdef RGLRU_TRACE
+__device__ unsigned long long g_trace[512 * 8 * 32 * 8];
+#define RGLRU_TR(k) tr[k] = __builtin_amdgcn_s_memtime()
+#define RGLRU_TR_FLUSH(wg, wv, it)                                                              \
+  if (lane == 0 && (it) < 32 && (wg) < 512) {                                                    \
+    for (int k_ = 0; k_ < 8; ++k_) g_trace[((((wg) * 8 + (wv)) * 32 + (it)) << 3) + k_] = tr[k_]; \
+  }
+#else
+#define RGLRU_TR(k)
+#define RGLRU_TR_FLUSH(wg, wv, it)
+#endif
 
 struct FwdArgs {
   Problem p;
@@ -93,7 +112,10 @@ fwd_mfma_kernel(FwdArgs a) {
   // (when the sequence is sliced in time the kernel needs more registers for the carry
   // exchange; the last K-steps of W_x are then re-read from L2 every tile - a far better spill
   // space than scratch memory)
-  constexpr int NRES = GMAX == 1 ? 16 : (GMAX == 4 ? 8 : 4);
+#ifndef RGLRU_NRES4
+#define RGLRU_NRES4 8
+#endif
+  constexpr int NRES = GMAX == 1 ? 16 : (GMAX == 4 ? RGLRU_NRES4 : 4);
   bf16x8 wa[16], wx[NRES];
   const bf16x8 *pxs = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
   {
@@ -153,7 +175,7 @@ fwd_mfma_kernel(FwdArgs a) {
       p.state_in ? (const unsigned *)((const unsigned short *)p.state_in + (size_t)b * 3 * D + dc) : nullptr;
 
   unsigned raw[11];  // inputs t0+8rg-3 .. t0+8rg+7 of the channel pair
-  auto load_rows = [&](int t0) {
+  auto load_rows = [&](int t0) __attribute__((always_inline)) {
     const int tb = t0 + 8 * rg - 3;
     if (tb >= 0 && tb + 11 <= T) {
 #pragma unroll
@@ -174,7 +196,7 @@ fwd_mfma_kernel(FwdArgs a) {
     }
   };
   unsigned short *xw = xs + (8 * rg) * XS + 2 * c2;
-  auto conv_rows = [&](int buf) {
+  auto conv_rows = [&](int buf) __attribute__((always_inline)) {
     const f32x4 w01 = cw_lds[c2], w23 = cw_lds[128 + c2], bb = cw_lds[256 + c2];
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
@@ -211,7 +233,7 @@ fwd_mfma_kernel(FwdArgs a) {
   // four consecutive steps (quarter q) of this lane's run: h <- a h + b, y = h (eq. 4); the
   // bf16 results go to the wave's staging tile at (row = step, column = channel)
   unsigned short *ot_mine = otile + (hf * 16) * OT + j;
-  auto run_quarter = [&](int q, const f32x4 &av, const f32x4 &bv, float &h) {
+  auto run_quarter = [&](int q, const f32x4 &av, const f32x4 &bv, float &h) __attribute__((always_inline)) {
     const float h0v = fmaf(av[0], h, bv[0]), h1v = fmaf(av[1], h0v, bv[1]);
     const float h2v = fmaf(av[2], h1v, bv[2]), h3v = fmaf(av[3], h2v, bv[3]);
     h = h3v;
@@ -230,7 +252,7 @@ fwd_mfma_kernel(FwdArgs a) {
   float hA_lo = 1.f, hH_lo = 0.f, hA_t = 1.f, hH_t = 0.f;  // aggregates of the tile parked in LDS
   u64 recA[GMAX > 1 ? GMAX - 1 : 1], recH[GMAX > 1 ? GMAX - 1 : 1];
 
-  auto fetch_records = [&](int t) {  // aggregates of the G-1 tiles before tile t
+  auto fetch_records = [&](int t) __attribute__((always_inline)) {  // aggregates of the G-1 tiles before tile t
 #pragma unroll
     for (int s = 0; s < GMAX - 1; ++s) {
       const int k = t - (G - 1) + s;
@@ -242,7 +264,7 @@ fwd_mfma_kernel(FwdArgs a) {
     }
   };
   // finish tile t: carry the state across the tiles of the other slices, write y
-  auto resolve = [&](int t) {
+  auto resolve = [&](int t) __attribute__((always_inline)) {
     float h = carry;
 #pragma unroll
     for (int s = 0; s < GMAX - 1; ++s) {
@@ -272,20 +294,13 @@ fwd_mfma_kernel(FwdArgs a) {
     carry = fmaf(hA_t, h, hH_t);
   };
 
-  int tile = w;
-  if (tile < a.ntile) load_rows(tile * TT);
-  __syncthreads();  // the constants parked in LDS are visible to every wave
-  if (tile < a.ntile) conv_rows(0);
-  __syncthreads();
-
-  for (int it = 0; tile < a.ntile; tile += G, ++it) {
-    const int buf = it & 1, t0 = tile * TT;
-    const int next = tile + G;
-    if (next < a.ntile) load_rows(next * TT);       // lands while this tile is computed
-    if (GMAX > 1 && held >= 0) fetch_records(held);
-
-    // ---- gate pre-activations on the matrix cores
-    f32x16 accp, accq, accx;
+#ifdef RGLRU_TRACE
+  unsigned long long tr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#endif
+  // ---- gate pre-activations of the tile in LDS buffer `buf` on the matrix cores, and the
+  // tile's own columns (high + low part) moved into accumulator layout by selection
+  f32x16 accp, accq, accx;
+  auto gemm = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       accp[r] = bias_p;
@@ -309,9 +324,15 @@ fwd_mfma_kernel(FwdArgs a) {
 #endif
         const bf16x8 a2 = *(const bf16x8 *)(ap + ((ks + 2) & 15) * 16);  // two steps ahead
         accp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wa[ks], accp, 0, 0, 0);
+#ifdef RGLRU_EXP_NOSTREAM
+        if (true) {
+          accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wx[ks % NRES], accq, 0, 0, 0);
+        } else {
+#else
         if (ks < NRES) {
           accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wx[ks], accq, 0, 0, 0);
         } else {
+#endif
           accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, st0, accq, 0, 0, 0);
           st0 = st1;
           if (ks + 2 < 16) st1 = pxs[(ks + 2) * 2];
@@ -331,11 +352,16 @@ fwd_mfma_kernel(FwdArgs a) {
       accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(l0, sel_lds[lane], accx, 0, 0, 0);
       accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(l1, sel_lds[64 + lane], accx, 0, 0, 0);
     }
+  };
 
-    // ---- the tile parked in LDS one iteration ago can be finished now
+  // ---- everything after the products for tile `tl`, whose pre-activations sit in the
+  // accumulators: finish the tile parked one step earlier, gates, aggregates, publication
+  auto pointwise = [&](int tl) __attribute__((always_inline)) {
+    const int t0 = tl * TT;
     if (GMAX > 1 && held >= 0) resolve(held);
+    RGLRU_TR(2);
 
-    // ---- gates (eqs. 1-3); the (a_t, b_t) pairs go to LDS, the lane keeps the aggregate of
+    // gates (eqs. 1-3); the (a_t, b_t) pairs go to LDS, the lane keeps the aggregate of
     // its 16-step run: prun = prod a, hrun = end state for a zero incoming state
     float hrun = 0.f, prun = 1.f;
     if (T - t0 >= TT) {  // full tile (uniform over the workgroup)
@@ -376,7 +402,8 @@ fwd_mfma_kernel(FwdArgs a) {
         hold_mine[(q + 4) * 64] = bq;
       }
     }
-    // ---- combine the two lane halves: lower half = steps 0..15, upper = 16..31
+    // combine the two lane halves: lower half = steps 0..15, upper = 16..31
+    RGLRU_TR(3);
     {
       const float oA = __shfl_xor(prun, 32), oH = __shfl_xor(hrun, 32);
       hA_lo = hf ? oA : prun;
@@ -386,22 +413,67 @@ fwd_mfma_kernel(FwdArgs a) {
       hH_t = fmaf(A_up, hH_lo, H_up);
     }
 #ifdef RGLRU_EXP_NORESOLVE
-    if (hrun == 12345.f) resolve(tile);
+    if (hrun == 12345.f) resolve(tl);
     carry += hA_t;
 #else
     if (GMAX > 1) {
       // publish the aggregate: lower half writes A, upper half writes H
-      publish(ring + (size_t)(tile % a.R) * 2 * BS + hf * BS, hf ? hH_t : hA_t, (unsigned)(tile + 1));
-      held = tile;
+      publish(ring + (size_t)(tl % a.R) * 2 * BS + hf * BS, hf ? hH_t : hA_t, (unsigned)(tl + 1));
+      held = tl;
     } else {
-      resolve(tile);
+      resolve(tl);
     }
 #endif
+  };
 
-    // ---- next tile of this workgroup into the other LDS buffer
-    if (next < a.ntile) conv_rows(buf ^ 1);
-    __syncthreads();
-  }
+  // The two waves that share a SIMD run half a step apart: waves 0-3 multiply first and then do
+  // the pointwise work of the same tile, waves 4-7 do the pointwise work of their previous tile
+  // first and multiply afterwards, keeping the accumulators across the barrier. Matrix and
+  // vector phases of the pair then overlap instead of colliding.
+  const bool late = RGLRU_ROTATE && wv >= NWAVE / 2;
+
+  int tile = w;
+  if (tile < a.ntile) load_rows(tile * TT);
+  __syncthreads();  // the constants parked in LDS are visible to every wave
+  if (tile < a.ntile) conv_rows(0);
+  __syncthreads();
+
+  // (two copies of the loop, one per order, so that the accumulators are live across the
+  // barrier only where they have to be; both execute the same number of barriers)
+  auto run = [&](auto late_c) __attribute__((always_inline)) {
+    constexpr bool LATE = decltype(late_c)::value;
+    int it = 0;
+    for (; tile < a.ntile; tile += G, ++it) {
+      const int buf = it & 1;
+      const int next = tile + G;
+      RGLRU_TR(0);
+      if (GMAX > 1 && held >= 0) fetch_records(held);
+      if (!LATE) {
+        if (next < a.ntile) load_rows(next * TT);     // lands while this tile is computed
+        gemm(buf);
+        RGLRU_TR(1);
+        pointwise(tile);
+      } else {
+        RGLRU_TR(1);
+        if (it > 0) pointwise(tile - G);
+        if (next < a.ntile) load_rows(next * TT);     // lands during the products
+        gemm(buf);
+      }
+      // next tile of this workgroup into the other LDS buffer
+      RGLRU_TR(4);
+      if (next < a.ntile) conv_rows(buf ^ 1);
+      RGLRU_TR(5);
+      __syncthreads();
+      RGLRU_TR(6);
+      RGLRU_TR_FLUSH((int)blockIdx.x, wv, it);
+    }
+    if (LATE && it > 0) {
+      if (GMAX > 1 && held >= 0) fetch_records(held);
+      pointwise(tile - G);
+    }
+  };
+  if (late) run(std::true_type{});
+  else run(std::false_type{});
   if (GMAX > 1 && held >= 0) {
     fetch_records(held);
     resolve(held);
@@ -656,5 +728,11 @@ hipError_t launch_decode_mfma(const Problem &p, hipStream_t s) {
   hipLaunchKernelGGL(decode_mfma_kernel, dim3(p.nb, (p.B + TT - 1) / TT), dim3(NTHR), DEC_LDS, s, a);
   return hipGetLastError();
 }
+
+#ifdef RGLRU_TRACE
+extern "C" int rglru_trace_read(unsigned long long *dst, size_t n) {
+  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_trace), n * sizeof(unsigned long long));
+}
+#endif
 
 }  // namespace rglru
