@@ -180,9 +180,13 @@ const char *rglru_last_error(void);
  * since the last rglru_timing_enable(1) (at most 8192; later launches are not recorded).
  * rglru_timing_get() returns the name of record `index` (a static string) and, once the caller
  * has synchronised the stream, the kernel's duration in milliseconds in *ms.
- * Returns RGLRU_OK, RGLRU_ERR_INVALID_ARG (bad index / NULL) or RGLRU_ERR_HIP.
+ * rglru_timing_select(name) restricts the bracketing to the kernels of that name (NULL or ""
+ * = every kernel again): two event records per launch are not free, and a run that only needs
+ * one kernel's duration should not pay for all of them.
+ * Returns RGLRU_OK, RGLRU_ERR_INVALID_ARG (bad index / NULL / name too long) or RGLRU_ERR_HIP.
  */
 int rglru_timing_enable(int enable);
+int rglru_timing_select(const char *kernel_name);
 int rglru_timing_count(void);
 int rglru_timing_get(int index, const char **name, float *ms);
 

@@ -13,7 +13,7 @@ _EXPORTS = (
     "OP_BACKWARD", "OP_CONV1D", "OP_DECODE", "OP_FORWARD", "LIB_PATH", "ParamGrads", "Params",
     "RglruError", "Shape", "make_param_grads", "make_params", "make_shape", "rglru_backward",
     "rglru_conv1d", "rglru_decode_step", "rglru_forward", "rglru_last_error", "rglru_version",
-    "rglru_workspace_bytes", "rglru_timing_enable", "rglru_timing_count", "rglru_timing_get",
+    "rglru_workspace_bytes", "rglru_timing_enable", "rglru_timing_select", "rglru_timing_count", "rglru_timing_get",
 )
 __all__ = list(_EXPORTS)
 

@@ -58,6 +58,7 @@ def _load():
     lib.rglru_last_error.restype = ctypes.c_char_p
     lib.rglru_version.restype = ctypes.c_int
     lib.rglru_timing_enable.argtypes = [ctypes.c_int]
+    lib.rglru_timing_select.argtypes = [ctypes.c_char_p]
     lib.rglru_timing_get.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p),
                                      ctypes.POINTER(ctypes.c_float)]
     for f in (lib.rglru_conv1d, lib.rglru_forward, lib.rglru_decode_step, lib.rglru_backward):
@@ -120,6 +121,11 @@ def rglru_last_error():
 
 def rglru_timing_enable(enable):
     _check(_lib.rglru_timing_enable(1 if enable else 0))
+
+
+def rglru_timing_select(kernel_name):
+    """Time only the kernels of this name (None: all kernels)."""
+    _check(_lib.rglru_timing_select(kernel_name.encode() if kernel_name else None))
 
 
 def rglru_timing_count():

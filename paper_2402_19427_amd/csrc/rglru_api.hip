@@ -139,10 +139,12 @@ thread_local bool g_timing = false;
 thread_local int g_ntimed = 0;
 thread_local TimedRecord *g_timed = nullptr;   // events are created once and reused
 thread_local int g_events_made = 0;
+thread_local char g_only[64] = "";             // if not empty: the only kernel name that is timed
 }  // namespace
 
 rglru::KernelTimer::KernelTimer(const char *name, hipStream_t stream) : s(stream), slot(-1) {
   if (!g_timing || g_ntimed >= MAX_TIMED) return;
+  if (g_only[0] && strcmp(g_only, name) != 0) return;
   if (!g_timed) g_timed = new TimedRecord[MAX_TIMED];
   if (g_ntimed >= g_events_made) {
     if (hipEventCreate(&g_timed[g_ntimed].start) != hipSuccess) return;
@@ -162,6 +164,13 @@ extern "C" {
 int rglru_timing_enable(int enable) {
   g_timing = enable != 0;
   if (g_timing) g_ntimed = 0;
+  return RGLRU_OK;
+}
+
+int rglru_timing_select(const char *kernel_name) {
+  if (kernel_name && strlen(kernel_name) >= sizeof(g_only))
+    return fail(RGLRU_ERR_INVALID_ARG, "kernel name longer than %zu characters", sizeof(g_only) - 1);
+  snprintf(g_only, sizeof(g_only), "%s", kernel_name ? kernel_name : "");
   return RGLRU_OK;
 }
 

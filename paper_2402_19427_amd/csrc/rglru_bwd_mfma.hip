@@ -10,7 +10,7 @@
 //        dp_t  = -c softplus(-Lambda) dla_t r_t (1 - r_t)
 //        dq_t  = delta_t m_t g_t (1 - i_t)
 //        dxd_t = delta_t m_t i_t                 (the part of dx that bypasses the gates)
-//     and writes x, dp, dq, dxd (bf16) plus per-channel sums for db_a, db_x, dLambda.
+//     and writes dp, dq (bf16), dxd (fp32) plus per-channel sums for db_a, db_x, dLambda.
 //     Time slices of one sequence exchange tile aggregates (prod a, local eps) as tagged 8-byte
 //     records; a first sweep over the tile computes a_t and the aggregate, a second sweep the
 //     adjoints once the incoming eps is known.
@@ -36,14 +36,34 @@ constexpr int G_OFF_YT = G_OFF_DYT + TR_BYTES;
 constexpr int G_OFF_HOLD = G_OFF_YT + TR_BYTES;
 constexpr int G_LDS = G_OFF_HOLD + HOLD_BYTES / 2;
 
+// Optional phase timestamps for tuning builds (compiled out otherwise)
+#ifdef RGLRU_TRACE
+__device__ unsigned long long g_trace_bwd[512 * 8 * 32 * 8];
+#define RGLRU_TR(k) tr[k] = __builtin_amdgcn_s_memtime()
+#define RGLRU_TR_FLUSH(wg, wv, it)                                                                  \
+  if (lane == 0 && (it) < 32 && (wg) < 512) {                                                        \
+    for (int k_ = 0; k_ < 8; ++k_) g_trace_bwd[((((wg) * 8 + (wv)) * 32 + (it)) << 3) + k_] = tr[k_]; \
+  }
+#else
+#define RGLRU_TR(k)
+#define RGLRU_TR_FLUSH(wg, wv, it)
+#endif
+#if defined(RGLRU_TRACE) && defined(RGLRU_TRACE_WGRAD)
+#define RGLRU_TRW(k) RGLRU_TR(k)
+#define RGLRU_TRW_FLUSH(wg, wv, it) RGLRU_TR_FLUSH(wg, wv, it)
+#else
+#define RGLRU_TRW(k)
+#define RGLRU_TRW_FLUSH(wg, wv, it)
+#endif
+
 struct BwdArgs {
   Problem p;
   int G, ntile, R;
   u64 *rec;
-  unsigned *flags;                        // [unit][R][8 waves]: tile + 1 once a wave's records are out
   int *err;
   int swizzle;
-  unsigned short *xo, *xlo, *dpo, *dqo;  // bf16 [B][T][D]: log2(e)*x (high part, low part), dp, dq
+  const unsigned short *wxf;              // W_x in fragment order (prep_kernel)
+  unsigned short *dpo, *dqo;              // bf16 [B][T][D]: dp, dq
   float *dxo;                             // f32 [B][T][D]: dxd (kept in fp32: du sums four taps of it
                                           // with cancellation)
   float *part;                            // [B*G][3][D]: sums for db_a, db_x, dLambda
@@ -86,13 +106,15 @@ bwd_gates_kernel(BwdArgs a) {
   // hold everything this kernel needs, and L2 is a far better spill space than scratch)
   constexpr int NRES = 4;
   bf16x8 wa[16], wx[NRES];
-  const bf16x8 *pxs = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
+  // fragment ks of this lane when streamed: pxs[ks * 64] (W_x in fragment order)
+  const bf16x8 *pxs = (const bf16x8 *)a.wxf + (size_t)(g * NWAVE + wv) * 16 * 64 + lane;
   {
     const bf16x8 *pa = (const bf16x8 *)((const unsigned short *)p.W_a + ((size_t)g * BS + ch) * BS + hf * 8);
+    const bf16x8 *px = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
 #pragma unroll
     for (int ks = 0; ks < 16; ++ks) wa[ks] = pa[ks * 2];
 #pragma unroll
-    for (int ks = 0; ks < NRES; ++ks) wx[ks] = pxs[ks * 2];
+    for (int ks = 0; ks < NRES; ++ks) wx[ks] = px[ks * 2];
   }
   if (tid < 64) {
     bf16x8 sel0, sel1;
@@ -139,8 +161,7 @@ bwd_gates_kernel(BwdArgs a) {
                                              seq_bytes, 0x00020000);
   };
   const __amdgpu_buffer_rsrc_t u_rsrc = rsrc(p.u), y_rsrc = rsrc(p.y_in), dy_rsrc = rsrc(p.dy);
-  const __amdgpu_buffer_rsrc_t xo_rsrc = rsrc(a.xo), xl_rsrc = rsrc(a.xlo), dp_rsrc = rsrc(a.dpo),
-                               dq_rsrc = rsrc(a.dqo);
+  const __amdgpu_buffer_rsrc_t dp_rsrc = rsrc(a.dpo), dq_rsrc = rsrc(a.dqo);
   const __amdgpu_buffer_rsrc_t dx_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       uniform_ptr(a.dxo + seq_off), 0, 2 * seq_bytes, 0x00020000);
   const unsigned c_voff = (unsigned)dc * 2;                                   // channel pair
@@ -170,8 +191,8 @@ bwd_gates_kernel(BwdArgs a) {
     }
   };
   unsigned short *xw = xs + (8 * rg) * XS + 2 * c2;
-  // Conv1D rows of tile t0 into LDS buffer `buf` and into the x workspace
-  auto conv_rows = [&](int t0, int buf) {
+  // Conv1D rows of this workgroup's next tile into LDS buffer `buf`
+  auto conv_rows = [&](int buf) {
     const f32x4 w01 = cw_lds[c2], w23 = cw_lds[128 + c2], bb = cw_lds[256 + c2];
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
@@ -184,11 +205,6 @@ bwd_gates_kernel(BwdArgs a) {
       split_bf16(x0, x1, hi_pk, lo_pk);
       *(unsigned *)(xw + buf * (2 * XT_ELEMS) + r * XS) = hi_pk;
       *(unsigned *)(xw + buf * (2 * XT_ELEMS) + XT_ELEMS + r * XS) = lo_pk;
-      const int t = t0 + 8 * rg + r;
-      if (t < T) {
-        __builtin_amdgcn_raw_buffer_store_b32(hi_pk, xo_rsrc, c_voff, (unsigned)t * row_bytes, 0);
-        __builtin_amdgcn_raw_buffer_store_b32(lo_pk, xl_rsrc, c_voff, (unsigned)t * row_bytes, 0);
-      }
     }
   };
   // dy and y rows 8*rg..8*rg+7 of tile t0 for the channel pair (zero past the sequence end)
@@ -227,7 +243,6 @@ bwd_gates_kernel(BwdArgs a) {
   const uint4 *yT_mine = (const uint4 *)(yT + ch * TS + hf * 16);
 
   u64 *ring = GMAX > 1 ? a.rec + (size_t)unit * a.R * 2 * BS + ch : nullptr;
-  unsigned *flag_ring = GMAX > 1 ? a.flags + (size_t)unit * a.R * NWAVE + wv : nullptr;
   float carry = p.dhT ? p.dhT[(size_t)b * D + d] : 0.f;  // eps entering this workgroup's next tile
   float s_ba = 0.f, s_bx = 0.f, s_lam = 0.f;
   int spins = 0;
@@ -236,13 +251,17 @@ bwd_gates_kernel(BwdArgs a) {
   int tile = a.ntile - 1 - w;
   if (tile >= 0) load_rows(tile * TT);
   __syncthreads();
-  if (tile >= 0) conv_rows(tile * TT, 0);
+  if (tile >= 0) conv_rows(0);
+  if (tile >= 0) load_dy_y(tile * TT);
   __syncthreads();
 
   for (int it = 0; tile >= 0; tile -= G, ++it) {
     const int buf = it & 1, t0 = tile * TT;
     const int next = tile - G;
-    load_dy_y(t0);
+#ifdef RGLRU_TRACE
+    unsigned long long tr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#endif
+    RGLRU_TR(0);
 
     // ---- gate pre-activations on the matrix cores
     f32x16 accp, accq, accx;
@@ -255,7 +274,7 @@ bwd_gates_kernel(BwdArgs a) {
     const unsigned short *ap = arow_base + buf * (2 * XT_ELEMS);
     {
       bf16x8 a0 = *(const bf16x8 *)(ap), a1 = *(const bf16x8 *)(ap + 16);
-      bf16x8 s0 = pxs[NRES * 2], s1 = pxs[(NRES + 1) * 2];   // streamed W_x fragments, two ahead
+      bf16x8 s0 = pxs[NRES * 64], s1 = pxs[(NRES + 1) * 64];   // streamed W_x fragments, two ahead
 #pragma unroll
       for (int ks = 0; ks < 16; ++ks) {
         const bf16x8 a2 = *(const bf16x8 *)(ap + ((ks + 2) & 15) * 16);
@@ -265,7 +284,7 @@ bwd_gates_kernel(BwdArgs a) {
         } else {
           accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, s0, accq, 0, 0, 0);
           s0 = s1;
-          if (ks + 2 < 16) s1 = pxs[(ks + 2) * 2];
+          if (ks + 2 < 16) s1 = pxs[(ks + 2) * 64];
         }
         __builtin_amdgcn_sched_barrier(0);
         a0 = a1;
@@ -284,7 +303,9 @@ bwd_gates_kernel(BwdArgs a) {
     }
     park_dy_y();
     if (next >= 0) load_rows(next * TT);  // consumed by conv_rows at the end of the iteration
+    RGLRU_TR(1);
     __syncthreads();
+    RGLRU_TR(2);
 
     // ---- first sweep (latest step first): r_t, a_t into LDS, aggregate of this lane's run:
     // eps_out = prun * eps_in + erun
@@ -315,42 +336,47 @@ bwd_gates_kernel(BwdArgs a) {
     const float A_t = A_lo * A_up, E_t = fmaf(A_lo, E_up, E_lo);
 
     float e_in = carry;
+    RGLRU_TR(3);
     if (GMAX > 1) {
       publish(ring + (size_t)(tile % a.R) * 2 * BS + hf * BS, hf ? E_t : A_t, (unsigned)(tile + 1));
-      // once this wave's records have left, raise its flag: waiting waves poll one word
-      // instead of hammering the records
-      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-      __hip_atomic_store(flag_ring + (size_t)(tile % a.R) * NWAVE, (unsigned)(tile + 1), __ATOMIC_RELAXED,
-                         __HIP_MEMORY_SCOPE_AGENT);
-      // eps entering this tile: own state after tile+G carried across tiles tile+G-1 .. tile+1
+      // eps entering this tile: own state after tile+G carried across tiles tile+G-1 .. tile+1.
+      // Their aggregates are requested two tiles at a time (one round trip per pair instead of
+      // two per tile); a tag that is not there yet is simply read again.
 #pragma unroll
-      for (int s = GMAX - 2; s >= 0; --s) {
-        const int k = tile + 1 + s;
-        if (s < G - 1 && k < a.ntile) {
-          const u64 *slot = ring + (size_t)(k % a.R) * 2 * BS;
-          const unsigned want = (unsigned)(k + 1);
-          const unsigned *fl = flag_ring + (size_t)(k % a.R) * NWAVE;
-          while (__hip_atomic_load(fl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != want &&
-                 spins < SPIN_LIMIT) {
-            ++spins;
-            __builtin_amdgcn_s_sleep(2);
+      for (int s0 = GMAX - 2; s0 >= 0; s0 -= 2) {
+        u64 recA[2], recE[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const int s = s0 - i, k = tile + 1 + s;
+          if (s >= 0 && s < G - 1 && k < a.ntile) {
+            const u64 *slot = ring + (size_t)(k % a.R) * 2 * BS;
+            recA[i] = peek(slot);
+            recE[i] = peek(slot + BS);
           }
-          u64 ra = peek(slot), re = peek(slot + BS);
-          while ((unsigned)(ra >> 32) != want && spins < SPIN_LIMIT) {
-            ++spins;
-            __builtin_amdgcn_s_sleep(1);
-            ra = peek(slot);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const int s = s0 - i, k = tile + 1 + s;
+          if (s >= 0 && s < G - 1 && k < a.ntile) {
+            const u64 *slot = ring + (size_t)(k % a.R) * 2 * BS;
+            const unsigned want = (unsigned)(k + 1);
+            while ((unsigned)(recA[i] >> 32) != want && spins < SPIN_LIMIT) {
+              ++spins;
+              __builtin_amdgcn_s_sleep(2);
+              recA[i] = peek(slot);
+            }
+            while ((unsigned)(recE[i] >> 32) != want && spins < SPIN_LIMIT) {
+              ++spins;
+              __builtin_amdgcn_s_sleep(2);
+              recE[i] = peek(slot + BS);
+            }
+            e_in = fmaf(__uint_as_float((unsigned)recA[i]), e_in, __uint_as_float((unsigned)recE[i]));
           }
-          while ((unsigned)(re >> 32) != want && spins < SPIN_LIMIT) {
-            ++spins;
-            __builtin_amdgcn_s_sleep(1);
-            re = peek(slot + BS);
-          }
-          e_in = fmaf(__uint_as_float((unsigned)ra), e_in, __uint_as_float((unsigned)re));
         }
       }
     }
     carry = fmaf(A_t, e_in, E_t);
+    RGLRU_TR(5);
 
     // ---- second sweep: adjoints with the true eps, latest step first
     float erev = hf ? e_in : fmaf(A_up, e_in, E_up);  // eps_{t+1} for the last step of this run
@@ -405,8 +431,16 @@ bwd_gates_kernel(BwdArgs a) {
       }
     }
 
-    if (next >= 0) conv_rows(next * TT, buf ^ 1);
+    RGLRU_TR(6);
+    if (next >= 0) {
+      conv_rows(buf ^ 1);
+      // dy and y of the next tile: requested before the barrier, so that part of the trip to HBM
+      // is over when the streamed weight fragments of the next product queue up behind it
+      load_dy_y(next * TT);
+    }
     __syncthreads();
+    RGLRU_TR(7);
+    RGLRU_TR_FLUSH((int)blockIdx.x, wv, it);
   }
   if (GMAX > 1 && spins >= SPIN_LIMIT) *a.err = 1;
 
@@ -691,17 +725,28 @@ bwd_dgrad_kernel(DgradArgs a) {
 // ------------------------------------------------------------------------------ wgrad
 // One workgroup accumulates a 256 x 256 block dW[gate][g] over a slice of the B*T rows.
 // Wave (mw, nw) owns output rows 64*mw.. (2 blocks of 32) and columns 128*nw.. (4 blocks).
-// Both operands arrive as [time][channel] tiles; a selection MFMA turns a 32-channel column
-// block into (channel, 16 consecutive steps) registers, which packed to bf16 are exactly the
-// A / B fragments of a product that contracts over time.
-constexpr int W_TILE = TT * XS * 2;          // one [32][264] bf16 tile
-constexpr int W_OFF_SEL = 6 * W_TILE;        // two buffers x (dp|dq tile, x high tile, x low tile)
-constexpr int W_LDS = W_OFF_SEL + 64 * 32;
+// The product contracts over time, so a fragment is 8 consecutive steps of one channel.
+// x is rebuilt here from u with the Conv1D of Section 2.3 (cheaper than a round trip of x
+// through HBM): a thread produces 8 consecutive steps of a channel pair, splits them into a
+// bf16 high and low part and lays them into [channel][time] tiles, where a fragment is one
+// 16-byte read. dp (or dq) arrives as the [time][channel] rows the gates kernel wrote; a
+// selection MFMA turns a 32-channel column block of it into (channel, 16 consecutive steps)
+// registers, which packed to bf16 are the fragments of the other operand.
+constexpr int W_TILE = TT * XS * 2;          // dp or dq: one [32 steps][264] bf16 tile
+constexpr int W_XT = BS * TS * 2;            // x part: one [256 channels][40] bf16 tile, time fastest
+constexpr int W_BUF = W_TILE + 2 * W_XT;     // one buffer: dp|dq tile, x high part, x low part
+constexpr int W_OFF_SEL = 2 * W_BUF;
+constexpr int W_OFF_CW = W_OFF_SEL + 64 * 32;
+constexpr int W_LDS = W_OFF_CW + 128 * 48;   // Conv1D taps and bias per channel pair
 
 struct WgradArgs {
-  int nb, S, D;
+  int nb, S, D, T;
   long long rows;                           // B*T
-  const unsigned short *dpo, *dqo, *xo, *xlo;  // bf16 [rows][D]
+  long long pos0;
+  const unsigned short *dpo, *dqo;          // bf16 [rows][D]
+  const unsigned short *u;                  // bf16 [rows][D]
+  const unsigned short *state_in;           // bf16 [B][3][D] ring, or NULL
+  const float *conv_w, *conv_b;             // [4][D], [D] or NULL
   float *part;                              // [S][2][nb][256][256]
 };
 
@@ -709,14 +754,19 @@ __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)
 bwd_wgrad_kernel(WgradArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16x8 *sel_lds = (bf16x8 *)(smem + W_OFF_SEL);
+  f32x4 *cw_lds = (f32x4 *)(smem + W_OFF_CW);
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, j = lane & 31;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int mw = wv >> 1, nw = wv & 1;
-  // block id -> (slice s, gate, block g); the two gates of a (g, s) pair are neighbours so
-  // that they find the shared x tile in the same L2
-  const int s = blockIdx.x / (2 * a.nb), rem = blockIdx.x - s * 2 * a.nb;
-  const int g = rem >> 1, gate = rem & 1;
+  // block id -> (slice s, gate, block g). Consecutive ids are dealt to the 8 XCDs in turn, so
+  // the two gates of a (g, s) pair get ids 8 apart: same XCD, started together, and the u rows
+  // one of them fetches are found in that XCD's L2 by the other.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int gate = slot & 1, pair = (slot >> 1) * 8 + xcd;
+  if (pair >= a.S * a.nb) return;
+  const int s = pair / a.nb, g = pair - s * a.nb;
   const unsigned short *src = gate ? a.dqo : a.dpo;
+  const int D = a.D, T = a.T;
 
   if (tid < 64) {
     bf16x8 sel0, sel1;
@@ -728,41 +778,125 @@ bwd_wgrad_kernel(WgradArgs a) {
     sel_lds[lane] = sel0;
     sel_lds[64 + lane] = sel1;
   }
+  // Conv1D assignment: channel pair c2, rows 8*rg .. 8*rg+7 of the tile
+  const int c2 = tid & 127;
+  const int rg = __builtin_amdgcn_readfirstlane(tid >> 7);
+  const int dc = g * BS + 2 * c2;
+  if (tid < 128) {
+    f32x4 t0v, t1v, t2v;
+    t0v[0] = a.conv_w[dc];                  t0v[1] = a.conv_w[dc + 1];
+    t0v[2] = a.conv_w[(size_t)D + dc];      t0v[3] = a.conv_w[(size_t)D + dc + 1];
+    t1v[0] = a.conv_w[(size_t)2 * D + dc];  t1v[1] = a.conv_w[(size_t)2 * D + dc + 1];
+    t1v[2] = a.conv_w[(size_t)3 * D + dc];  t1v[3] = a.conv_w[(size_t)3 * D + dc + 1];
+    t2v[0] = a.conv_b ? a.conv_b[dc] : 0.f;
+    t2v[1] = a.conv_b ? a.conv_b[dc + 1] : 0.f;
+    t2v[2] = t2v[3] = 0.f;
+    cw_lds[c2] = t0v;
+    cw_lds[128 + c2] = t1v;
+    cw_lds[256 + c2] = t2v;
+  }
 
   // rows of this slice, in steps of 32
   const long long nstep_all = (a.rows + TT - 1) / TT;
   const long long per = (nstep_all + a.S - 1) / a.S;
   const long long st_lo = (long long)s * per, st_hi = st_lo + per < nstep_all ? st_lo + per : nstep_all;
 
-  // loaders: 16 bytes per thread, rows lr and lr+16 of both tiles
+  // dp / dq loader: 16 bytes per thread, rows lr and lr+16 of the tile
   const int lc = tid & 31, lr = tid >> 5;
   const unsigned short *gsrc = src + (size_t)g * BS + 8 * lc;
-  const unsigned short *gx = a.xo + (size_t)g * BS + 8 * lc;
-  const unsigned short *gxl = a.xlo + (size_t)g * BS + 8 * lc;
-  uint4 rl[6];
-  auto load_tiles = [&](long long step) {
+  uint4 rl[2];
+  // u rows of the channel pair. A tile of the flattened [B*T] rows may straddle sequences, so
+  // every input is addressed through its own (sequence, step): in(row, lag) is u[row - lag]
+  // while that stays inside the row's sequence, else the carried-in Conv1D state or zero.
+  const unsigned *u32 = (const unsigned *)(a.u + dc);
+  const unsigned *st32 = a.state_in ? (const unsigned *)(a.state_in + dc) : nullptr;
+  auto input_at = [&](long long b, int t) -> unsigned {   // pair of inputs at step t (may be < 0)
+    if (t >= 0) return u32[(size_t)(b * T + t) * (D / 2)];
+    if (st32) return st32[((size_t)b * 3 + ring_slot(a.pos0 + t)) * (D / 2)];
+    return 0u;
+  };
+  unsigned raw[11];   // inputs of rows r0-3 .. r0+7, r0 = first of this thread's 8 rows
+  int slow = 0;       // this thread's rows of the tile being prepared are not one plain window
+  // (sequence, step) of this thread's first row in the tile the next load_tiles call fetches;
+  // the calls walk consecutive tiles, so it advances without a division
+  long long nb_ = (st_lo * TT + 8 * rg) / T;
+  int nt_ = (int)(st_lo * TT + 8 * rg - nb_ * T);
+  auto load_tiles = [&](long long step) __attribute__((always_inline)) {
+    const long long r0 = step * TT + 8 * rg;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const long long row = step * TT + lr + 16 * h;
-      uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0, v2 = v0;
-      if (row < a.rows) {
-        v0 = *(const uint4 *)(gsrc + (size_t)row * a.D);
-        v1 = *(const uint4 *)(gx + (size_t)row * a.D);
-        v2 = *(const uint4 *)(gxl + (size_t)row * a.D);
-      }
-      rl[h] = v0;
-      rl[2 + h] = v1;
-      rl[4 + h] = v2;
+      rl[h] = make_uint4(0, 0, 0, 0);
+      if (row < a.rows) rl[h] = *(const uint4 *)(gsrc + (size_t)row * D);
+    }
+    slow = !(nt_ >= 3 && nt_ + 8 <= T && r0 + 8 <= a.rows);
+    if (!slow) {
+      const unsigned *base = u32 + (size_t)(r0 - 3) * (D / 2);
+#pragma unroll
+      for (int n = 0; n < 11; ++n) raw[n] = base[(unsigned)n * (unsigned)(D / 2)];
+    }
+    nt_ += TT;
+    while (nt_ >= T) {
+      nt_ -= T;
+      ++nb_;
     }
   };
-  auto park_tiles = [&](int buf) {
-    unsigned short *t0p = (unsigned short *)(smem + (size_t)buf * 3 * W_TILE);
+  // dp / dq rows and the rebuilt x of the requested tile into LDS buffer `buf`
+  auto park_tiles = [&](long long step, int buf) __attribute__((always_inline)) {
+    unsigned short *t0p = (unsigned short *)(smem + (size_t)buf * W_BUF);
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      *(uint4 *)(t0p + (lr + 16 * h) * XS + 8 * lc) = rl[h];
-      *(uint4 *)(t0p + TT * XS + (lr + 16 * h) * XS + 8 * lc) = rl[2 + h];
-      *(uint4 *)(t0p + 2 * TT * XS + (lr + 16 * h) * XS + 8 * lc) = rl[4 + h];
+    for (int h = 0; h < 2; ++h) *(uint4 *)(t0p + (lr + 16 * h) * XS + 8 * lc) = rl[h];
+    const f32x4 w01 = cw_lds[c2], w23 = cw_lds[128 + c2], bb = cw_lds[256 + c2];
+    float xa[8], xb[8];   // 8 consecutive steps of the two channels
+    if (!slow) {
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        float x0 = bb[0], x1 = bb[1];
+        x0 = fmaf(w01[0], bf_lo(raw[r + 3]), x0); x1 = fmaf(w01[1], bf_hi(raw[r + 3]), x1);
+        x0 = fmaf(w01[2], bf_lo(raw[r + 2]), x0); x1 = fmaf(w01[3], bf_hi(raw[r + 2]), x1);
+        x0 = fmaf(w23[0], bf_lo(raw[r + 1]), x0); x1 = fmaf(w23[1], bf_hi(raw[r + 1]), x1);
+        x0 = fmaf(w23[2], bf_lo(raw[r]), x0);     x1 = fmaf(w23[3], bf_hi(raw[r]), x1);
+        xa[r] = x0;
+        xb[r] = x1;
+      }
+    } else {  // first rows of a sequence, a tile across two sequences, or the ragged end
+      const long long r0 = step * TT + 8 * rg;
+#pragma unroll 1
+      for (int r = 0; r < 8; ++r) {
+        const long long row = r0 + r;
+        float x0 = 0.f, x1 = 0.f;
+        if (row < a.rows) {
+          const long long b = row / T;
+          const int t = (int)(row - b * T);
+          const unsigned i0 = input_at(b, t), i1 = input_at(b, t - 1), i2 = input_at(b, t - 2),
+                         i3 = input_at(b, t - 3);
+          x0 = bb[0]; x1 = bb[1];
+          x0 = fmaf(w01[0], bf_lo(i0), x0); x1 = fmaf(w01[1], bf_hi(i0), x1);
+          x0 = fmaf(w01[2], bf_lo(i1), x0); x1 = fmaf(w01[3], bf_hi(i1), x1);
+          x0 = fmaf(w23[0], bf_lo(i2), x0); x1 = fmaf(w23[1], bf_hi(i2), x1);
+          x0 = fmaf(w23[2], bf_lo(i3), x0); x1 = fmaf(w23[3], bf_hi(i3), x1);
+        }
+        // (a dynamic index into xa / xb would put them in scratch memory)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          if (q == r) {
+            xa[q] = x0;
+            xb[q] = x1;
+          }
+        }
+      }
     }
+    uint4 ah, al, bh, bl;
+    split_bf16(xa[0], xa[1], ah.x, al.x); split_bf16(xa[2], xa[3], ah.y, al.y);
+    split_bf16(xa[4], xa[5], ah.z, al.z); split_bf16(xa[6], xa[7], ah.w, al.w);
+    split_bf16(xb[0], xb[1], bh.x, bl.x); split_bf16(xb[2], xb[3], bh.y, bl.y);
+    split_bf16(xb[4], xb[5], bh.z, bl.z); split_bf16(xb[6], xb[7], bh.w, bl.w);
+    unsigned short *xh = (unsigned short *)(smem + (size_t)buf * W_BUF + W_TILE) + (2 * c2) * TS + 8 * rg;
+    unsigned short *xl = xh + BS * TS;
+    *(uint4 *)(xh) = ah;
+    *(uint4 *)(xh + TS) = bh;
+    *(uint4 *)(xl) = al;
+    *(uint4 *)(xl + TS) = bl;
   };
 
   const int arow = ((j >> 2) & 1) * 16 + (j >> 3) * 4 + (j & 3);
@@ -776,54 +910,93 @@ bwd_wgrad_kernel(WgradArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
 
+  // products of the tile in LDS buffer `buf`
+  auto products = [&](int buf) __attribute__((always_inline)) {
+    const unsigned short *tg = (const unsigned short *)(smem + (size_t)buf * W_BUF) + a_off;
+    const unsigned short *xh = (const unsigned short *)(smem + (size_t)buf * W_BUF + W_TILE) +
+                               (4 * nw * 32 + j) * TS + 16 * hf;
+    const unsigned short *xl = xh + BS * TS;
+    const bf16x8 sl0 = sel_lds[lane], sl1 = sel_lds[64 + lane];
+    // dp / dq fragments: column block c of the tile -> two K-steps of 8 consecutive steps per lane
+    bf16x8 fa[2][2];
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+      const unsigned short *tile = tg + (2 * mw + m) * 32;
+      f32x16 t;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) t[r] = 0.f;
+      t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(tile), sl0, t, 0, 0, 0);
+      t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(tile + 16), sl1, t, 0, 0, 0);
+      unsigned pk[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pk[e] = pack_bf16(t[2 * e], t[2 * e + 1]);
+      uint4 lo4 = make_uint4(pk[0], pk[1], pk[2], pk[3]), hi4 = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+      fa[m][0] = __builtin_bit_cast(bf16x8, lo4);
+      fa[m][1] = __builtin_bit_cast(bf16x8, hi4);
+    }
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+      // x = high + low, both bf16; as in the dp / dq fragments, lane half hf holds steps
+      // 16 hf .. 16 hf + 7 in the first K-step and the following 8 in the second
+      const bf16x8 fb0 = *(const bf16x8 *)(xh + n * 32 * TS), fb1 = *(const bf16x8 *)(xh + n * 32 * TS + 8);
+      const bf16x8 fl0 = *(const bf16x8 *)(xl + n * 32 * TS), fl1 = *(const bf16x8 *)(xl + n * 32 * TS + 8);
+      acc[0][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][0], fb0, acc[0][n], 0, 0, 0);
+      acc[1][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][0], fb0, acc[1][n], 0, 0, 0);
+      acc[0][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][1], fb1, acc[0][n], 0, 0, 0);
+      acc[1][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][1], fb1, acc[1][n], 0, 0, 0);
+      acc[0][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][0], fl0, acc[0][n], 0, 0, 0);
+      acc[1][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][0], fl0, acc[1][n], 0, 0, 0);
+      acc[0][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][1], fl1, acc[0][n], 0, 0, 0);
+      acc[1][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][1], fl1, acc[1][n], 0, 0, 0);
+    }
+  };
+
+  // The two waves that share a SIMD work half a step apart: waves 0-3 multiply and then
+  // prepare the next tile, waves 4-7 prepare first and multiply afterwards (their inputs are
+  // requested one step earlier), so that matrix and vector phases of the pair overlap. Both
+  // orders read buffer `buf` and write the other one between the same two barriers.
+  const bool late = wv >= NWAVE / 2;
   if (st_lo < st_hi) {
     load_tiles(st_lo);
-    __syncthreads();
-    park_tiles(0);
+    __syncthreads();   // the taps parked in LDS are visible
+    park_tiles(st_lo, 0);
+    if (late && st_lo + 1 < st_hi) load_tiles(st_lo + 1);
     __syncthreads();
     int it = 0;
-    for (long long step = st_lo; step < st_hi; ++step, ++it) {
-      const int buf = it & 1;
-      if (step + 1 < st_hi) load_tiles(step + 1);
-      const unsigned short *tg = (const unsigned short *)(smem + (size_t)buf * 3 * W_TILE) + a_off;
-      const unsigned short *tx = tg + TT * XS, *txl = tg + 2 * TT * XS;
-      const bf16x8 sl0 = sel_lds[lane], sl1 = sel_lds[64 + lane];
-      // fragments: column block c of a tile -> two K-steps of 8 consecutive time steps per lane
-      auto fragments = [&](const unsigned short *tile, int cblk, bf16x8 &f0, bf16x8 &f1) {
-        f32x16 t;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) t[r] = 0.f;
-        t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(tile + cblk * 32), sl0, t, 0, 0, 0);
-        t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(tile + cblk * 32 + 16), sl1, t, 0, 0, 0);
-        unsigned pk[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) pk[e] = pack_bf16(t[2 * e], t[2 * e + 1]);
-        uint4 lo4 = make_uint4(pk[0], pk[1], pk[2], pk[3]), hi4 = make_uint4(pk[4], pk[5], pk[6], pk[7]);
-        f0 = __builtin_bit_cast(bf16x8, lo4);
-        f1 = __builtin_bit_cast(bf16x8, hi4);
-      };
-      bf16x8 fa[2][2];
-#pragma unroll
-      for (int m = 0; m < 2; ++m) fragments(tg, 2 * mw + m, fa[m][0], fa[m][1]);
-#pragma unroll
-      for (int n = 0; n < 4; ++n) {
-        bf16x8 fb0, fb1, fl0, fl1;  // x = high + low, both bf16
-        fragments(tx, 4 * nw + n, fb0, fb1);
-        fragments(txl, 4 * nw + n, fl0, fl1);
-#pragma unroll
-        for (int m = 0; m < 2; ++m) {
-          acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m][0], fb0, acc[m][n], 0, 0, 0);
-          acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m][1], fb1, acc[m][n], 0, 0, 0);
-          acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m][0], fl0, acc[m][n], 0, 0, 0);
-          acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m][1], fl1, acc[m][n], 0, 0, 0);
-        }
+#if defined(RGLRU_TRACE) && defined(RGLRU_TRACE_WGRAD)
+    unsigned long long tr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#endif
+    if (!late) {
+      for (long long step = st_lo; step < st_hi; ++step, ++it) {
+        const int buf = it & 1;
+        RGLRU_TRW(0);
+        if (step + 1 < st_hi) load_tiles(step + 1);
+        RGLRU_TRW(1);
+        products(buf);
+        RGLRU_TRW(2);
+        if (step + 1 < st_hi) park_tiles(step + 1, buf ^ 1);
+        RGLRU_TRW(3);
+        __syncthreads();
+        RGLRU_TRW(4);
+        RGLRU_TRW_FLUSH((int)blockIdx.x, wv, it);
       }
-      if (step + 1 < st_hi) park_tiles(buf ^ 1);
-      __syncthreads();
+    } else {
+      for (long long step = st_lo; step < st_hi; ++step, ++it) {
+        const int buf = it & 1;
+        RGLRU_TRW(0);
+        if (step + 1 < st_hi) park_tiles(step + 1, buf ^ 1);
+        RGLRU_TRW(1);
+        if (step + 2 < st_hi) load_tiles(step + 2);
+        RGLRU_TRW(2);
+        products(buf);
+        RGLRU_TRW(3);
+        __syncthreads();
+        RGLRU_TRW(4);
+        RGLRU_TRW_FLUSH((int)blockIdx.x, wv, it);
+      }
     }
   }
-  // dW = ln(2) * sum (the x tiles carry the factor log2 e); rows of the accumulator are
-  // output channels j, columns are input channels k
+  // rows of the accumulator are output channels j, columns are input channels k
   float *out = a.part + (((size_t)s * 2 + gate) * a.nb + g) * BS * BS;
 #pragma unroll
   for (int m = 0; m < 2; ++m)
@@ -833,7 +1006,7 @@ bwd_wgrad_kernel(WgradArgs a) {
       for (int r = 0; r < 16; ++r) {
         const int row = 64 * mw + 32 * m + 8 * (r >> 2) + 4 * hf + (r & 3);
         const int col = 128 * nw + 32 * n + j;
-        out[(size_t)row * BS + col] = acc[m][n][r] * LN2;
+        out[(size_t)row * BS + col] = acc[m][n][r];
       }
 }
 
@@ -872,7 +1045,7 @@ size_t al256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 struct BwdPlan {
   int units, ntile, G, R, C, S;
-  size_t off_x, off_xl, off_dp, off_dq, off_dx, off_wta, off_wtx, off_rec, off_partA, off_partC, off_partW, total;
+  size_t off_dp, off_dq, off_dx, off_wta, off_wtx, off_wxf, off_rec, off_partA, off_partC, off_partW, total;
 };
 
 BwdPlan plan_backward(int B, int T, int D, int nb, int ncu) {
@@ -892,14 +1065,13 @@ BwdPlan plan_backward(int B, int T, int D, int nb, int ncu) {
   q.S = (int)S;
   const size_t N2 = al256((size_t)B * T * D * 2), wbytes = al256((size_t)nb * BS * BS * 2);
   size_t off = 0;
-  q.off_x = off; off += N2;
-  q.off_xl = off; off += N2;
   q.off_dp = off; off += N2;
   q.off_dq = off; off += N2;
   q.off_dx = off; off += 2 * N2;
   q.off_wta = off; off += wbytes;
   q.off_wtx = off; off += wbytes;
-  q.off_rec = off; off += al256(256 + (size_t)q.units * q.R * (2 * BS * sizeof(u64) + NWAVE * 4));
+  q.off_wxf = off; off += wbytes;
+  q.off_rec = off; off += al256(256 + (size_t)q.units * q.R * 2 * BS * sizeof(u64));
   q.off_partA = off; off += al256((size_t)B * q.G * 3 * D * 4);
   q.off_partC = off; off += al256((size_t)B * q.C * 5 * D * 4);
   q.off_partW = off; off += al256((size_t)q.S * 2 * nb * BS * BS * 4);
@@ -955,18 +1127,16 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   a.G = q.G; a.ntile = q.ntile; a.R = q.R;
   a.err = (int *)(ws + q.off_rec);
   a.rec = (u64 *)(ws + q.off_rec + 256);
-  a.flags = (unsigned *)(ws + q.off_rec + 256 + (size_t)q.units * q.R * 2 * BS * sizeof(u64));
-  a.xo = (unsigned short *)(ws + q.off_x);
-  a.xlo = (unsigned short *)(ws + q.off_xl);
   a.dpo = (unsigned short *)(ws + q.off_dp);
   a.dqo = (unsigned short *)(ws + q.off_dq);
   a.dxo = (float *)(ws + q.off_dx);
   a.part = (float *)(ws + q.off_partA);
   const int grid = q.units * q.G;
   a.swizzle = (q.G > 1 && grid % 8 == 0) ? 1 : 0;
-  if (q.G > 1 &&
-      (e = launch_zero(ws + q.off_rec, 256 + (size_t)q.units * q.R * (2 * BS * sizeof(u64) + NWAVE * 4), s)) != hipSuccess)
-    return e;
+  a.wxf = (const unsigned short *)(ws + q.off_wxf);
+  // the records only exist (and need clearing) when sequences are sliced in time
+  const size_t clear = q.G > 1 ? 256 + (size_t)q.units * q.R * 2 * BS * sizeof(u64) : 0;
+  if ((e = launch_prep(ws + q.off_rec, clear, p.W_x, ws + q.off_wxf, p.nb, s)) != hipSuccess) return e;
   {
     KernelTimer kt("bwd_gates_kernel", s);
     if (q.G == 1)
@@ -1007,13 +1177,17 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
 
   // 3. wgrad
   WgradArgs wg;
-  wg.nb = p.nb; wg.S = q.S; wg.D = p.D;
+  wg.nb = p.nb; wg.S = q.S; wg.D = p.D; wg.T = p.T;
   wg.rows = (long long)p.B * p.T;
-  wg.dpo = a.dpo; wg.dqo = a.dqo; wg.xo = a.xo; wg.xlo = a.xlo;
+  wg.pos0 = p.pos0;
+  wg.dpo = a.dpo; wg.dqo = a.dqo;
+  wg.u = (const unsigned short *)p.u;
+  wg.state_in = (const unsigned short *)p.state_in;
+  wg.conv_w = p.conv_w; wg.conv_b = p.conv_b;
   wg.part = (float *)(ws + q.off_partW);
   {
     KernelTimer kt("bwd_wgrad_kernel", s);
-    hipLaunchKernelGGL(bwd_wgrad_kernel, dim3(q.S * 2 * p.nb), dim3(NTHR), W_LDS, s, wg);
+    hipLaunchKernelGGL(bwd_wgrad_kernel, dim3((q.S * 2 * p.nb + 15) / 16 * 16), dim3(NTHR), W_LDS, s, wg);
   }
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const size_t per_gate = (size_t)p.nb * BS * BS;
@@ -1024,5 +1198,11 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   }
   return hipGetLastError();
 }
+
+#ifdef RGLRU_TRACE
+extern "C" int rglru_trace_read_bwd(unsigned long long *dst, size_t n) {
+  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_trace_bwd), n * sizeof(unsigned long long));
+}
+#endif
 
 }  // namespace rglru
