@@ -164,8 +164,10 @@ bwd_gates_kernel(BwdArgs a) {
   const __amdgpu_buffer_rsrc_t dp_rsrc = rsrc(a.dpo), dq_rsrc = rsrc(a.dqo);
   const __amdgpu_buffer_rsrc_t dx_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       uniform_ptr(a.dxo + seq_off), 0, 2 * seq_bytes, 0x00020000);
+  const unsigned dx_voff = ((unsigned)d * 2 + (unsigned)hf * 16 * row_bytes) * 2;  // channel, lane half
   const unsigned c_voff = (unsigned)dc * 2;                                   // channel pair
-  const unsigned o_voff = (unsigned)d * 2 + (unsigned)hf * 16 * row_bytes;    // channel, lane half
+  // 16-byte stores of a staged tile: lane l owns 8 channels of rows l/4 and l/4+16
+  const unsigned st_voff = (unsigned)(g * BS + wv * 32 + (lane & 3) * 8) * 2 + (unsigned)(lane >> 2) * row_bytes;
   const unsigned *st32 =
       p.state_in ? (const unsigned *)((const unsigned short *)p.state_in + (size_t)b * 3 * D + dc) : nullptr;
 
@@ -175,14 +177,14 @@ bwd_gates_kernel(BwdArgs a) {
     if (tb >= 0 && tb + 11 <= T) {
 #pragma unroll
       for (int n = 0; n < 11; ++n)
-        raw[n] = __builtin_amdgcn_raw_buffer_load_b32(u_rsrc, c_voff, (unsigned)(tb + n) * row_bytes, 0);
+        raw[n] = __builtin_amdgcn_raw_buffer_load_b32(u_rsrc, c_voff, (unsigned)(tb + n) * row_bytes, RGLRU_NT);
     } else {
 #pragma unroll
       for (int n = 0; n < 11; ++n) {
         const int t = tb + n;
         unsigned v = 0;
         if (t >= 0) {
-          if (t < T) v = __builtin_amdgcn_raw_buffer_load_b32(u_rsrc, c_voff, (unsigned)t * row_bytes, 0);
+          if (t < T) v = __builtin_amdgcn_raw_buffer_load_b32(u_rsrc, c_voff, (unsigned)t * row_bytes, RGLRU_NT);
         } else if (st32) {
           v = st32[(size_t)ring_slot(p.pos0 + t) * (D / 2)];
         }
@@ -215,8 +217,8 @@ bwd_gates_kernel(BwdArgs a) {
       const int t = t0 + 8 * rg + r;
       unsigned v0 = 0, v1 = 0;
       if (t < T) {
-        v0 = __builtin_amdgcn_raw_buffer_load_b32(dy_rsrc, c_voff, (unsigned)t * row_bytes, 0);
-        v1 = __builtin_amdgcn_raw_buffer_load_b32(y_rsrc, c_voff, (unsigned)t * row_bytes, 0);
+        v0 = __builtin_amdgcn_raw_buffer_load_b32(dy_rsrc, c_voff, (unsigned)t * row_bytes, RGLRU_NT);
+        v1 = __builtin_amdgcn_raw_buffer_load_b32(y_rsrc, c_voff, (unsigned)t * row_bytes, RGLRU_NT);
       }
       rdy[r] = v0;
       ry[r] = v1;
@@ -301,6 +303,7 @@ bwd_gates_kernel(BwdArgs a) {
       accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(l0, sel_lds[lane], accx, 0, 0, 0);
       accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(l1, sel_lds[64 + lane], accx, 0, 0, 0);
     }
+    RGLRU_TR(4);
     park_dy_y();
     if (next >= 0) load_rows(next * TT);  // consumed by conv_rows at the end of the iteration
     RGLRU_TR(1);
@@ -381,6 +384,10 @@ bwd_gates_kernel(BwdArgs a) {
     // ---- second sweep: adjoints with the true eps, latest step first
     float erev = hf ? e_in : fmaf(A_up, e_in, E_up);  // eps_{t+1} for the last step of this run
     const unsigned so = (unsigned)t0 * row_bytes;
+    // staging for the dp / dq columns: the x tile of this step is no longer read by anyone
+    // (every wave has passed the barrier after the products), 4 KB of it per wave
+    unsigned short *stage = xs + buf * (2 * XT_ELEMS) + wv * (2 * 32 * 32);
+    unsigned short *stage_mine = stage + (hf * 16) * 32 + j;
 #pragma unroll
     for (int q = 3; q >= 0; --q) {
       const uint4 dq4 = dyT_mine[q >> 1], yq4 = yT_mine[q >> 1];
@@ -413,23 +420,26 @@ bwd_gates_kernel(BwdArgs a) {
         erev = ok ? av * delta : erev;
         __builtin_amdgcn_sched_barrier(0);  // one element at a time: registers are scarce here
       }
-      const unsigned soq = so + (unsigned)(4 * q) * row_bytes;
-      const unsigned p0 = pack_bf16(dpv[0], dpv[1]), p1 = pack_bf16(dpv[2], dpv[3]);
-      const unsigned q0 = pack_bf16(dqv[0], dqv[1]), q1 = pack_bf16(dqv[2], dqv[3]);
-      const int nv = nvalid - 4 * q;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        if (e < nv) {
-          const unsigned pp = e < 2 ? p0 : p1, qq = e < 2 ? q0 : q1;
-          const short sp = (short)((e & 1) ? (pp >> 16) : (pp & 0xffff));
-          const short sq = (short)((e & 1) ? (qq >> 16) : (qq & 0xffff));
-          __builtin_amdgcn_raw_buffer_store_b16(sp, dp_rsrc, o_voff, soq + e * row_bytes, 0);
-          __builtin_amdgcn_raw_buffer_store_b16(sq, dq_rsrc, o_voff, soq + e * row_bytes, 0);
-          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(dxv[e]), dx_rsrc, 2 * o_voff,
-                                                2 * (soq + e * row_bytes), 0);
-        }
+      // dp, dq: columns of this wave's two [32 steps][32 channels] staging tiles
+      {
+        const unsigned p0 = pack_bf16(dpv[0], dpv[1]), p1 = pack_bf16(dpv[2], dpv[3]);
+        const unsigned q0 = pack_bf16(dqv[0], dqv[1]), q1 = pack_bf16(dqv[2], dqv[3]);
+        unsigned short *sp = stage_mine + (4 * q) * 32, *sq = sp + 32 * 32;
+        sp[0] = (unsigned short)(p0 & 0xffff); sp[32] = (unsigned short)(p0 >> 16);
+        sp[64] = (unsigned short)(p1 & 0xffff); sp[96] = (unsigned short)(p1 >> 16);
+        sq[0] = (unsigned short)(q0 & 0xffff); sq[32] = (unsigned short)(q0 >> 16);
+        sq[64] = (unsigned short)(q1 & 0xffff); sq[96] = (unsigned short)(q1 >> 16);
       }
+      // dxd (fp32): one 128-byte piece of a row per lane half and step
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (4 * q + e < nvalid)
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(dxv[e]), dx_rsrc, dx_voff,
+                                                2 * (so + (unsigned)(4 * q + e) * row_bytes), RGLRU_NT);
     }
+    // the staged dp / dq tiles leave as 16-byte stores (rows past the end of the sequence are skipped)
+    store_staged_tile_s<32, RGLRU_NT>(stage, lane, dp_rsrc, st_voff, so, row_bytes, T - t0);
+    store_staged_tile_s<32, RGLRU_NT>(stage + 32 * 32, lane, dq_rsrc, st_voff, so, row_bytes, T - t0);
 
     RGLRU_TR(6);
     if (next >= 0) {
@@ -461,7 +471,10 @@ bwd_gates_kernel(BwdArgs a) {
 
 // ------------------------------------------------------------------------------ dgrad
 // A tile: 32 steps x (dp 256 | dq 256) bf16, filled by direct-to-LDS loads (layout below);
-// two of them, two u tiles of 35 rows, and the selection fragments.
+// two of them, two u tiles of 35 rows, the selection fragments, and a staging tile per wave that
+// turns the du columns into 16-byte stores. Few, wide memory instructions matter here: a
+// compute unit issues roughly one vector memory instruction per 8 cycles, whatever its width
+// (as long as the lanes of one instruction touch few cache lines).
 constexpr int AS = 2 * BS + 8;                       // slot stride in elements (1040 B)
 constexpr int D_A_TILE = TT * AS * 2;                // one A tile: 16 dp slots, then 16 dq slots
 constexpr int D_A_BYTES = 2 * D_A_TILE;              // two A tiles
@@ -469,7 +482,8 @@ constexpr int US_ROWS = TT + 3;                      // u rows t0-3 .. t0+31
 constexpr int D_OFF_SEL = D_A_BYTES;
 constexpr int D_OFF_U = D_OFF_SEL + 64 * 32;
 constexpr int D_U_TILE = US_ROWS * XS * 2;
-constexpr int D_LDS = D_OFF_U + 2 * D_U_TILE;
+constexpr int D_OFF_OT = D_OFF_U + 2 * D_U_TILE;     // per wave: du staging tile [32][OT] bf16
+constexpr int D_LDS = D_OFF_OT + NWAVE * OTILE_BYTES;
 
 struct DgradArgs {
   Problem p;
@@ -480,23 +494,44 @@ struct DgradArgs {
   float *part;                             // [B*C][5][D]: dconv_w[0..3], dconv_b partial sums
 };
 
-__global__ void __launch_bounds__(256) transpose_weights_kernel(const unsigned short *Wa,
-                                                                const unsigned short *Wx,
-                                                                unsigned short *WTa,
-                                                                unsigned short *WTx, int nmat) {
+// Preparation pass of the backward: the first 128 nb blocks transpose W_a and W_x in 32 x 32
+// tiles for the dgrad kernel; the others clear the record rings and copy W_x into MFMA
+// fragment order, [block][wave][K-step][lane][8], so that the gates kernel re-reads the K-steps
+// it cannot keep in registers as contiguous 1 KB pieces.
+struct PrepArgs {
+  const unsigned short *Wa, *Wx;
+  unsigned short *WTa, *WTx;
+  uint4 *wxf;
+  uint4 *zero;
+  size_t n16;   // 16-byte words to clear
+  int nb;
+};
+__global__ void __launch_bounds__(256) bwd_prep_kernel(PrepArgs a) {
   __shared__ unsigned short tile[32][33];
-  const int m = blockIdx.z % nmat, which = blockIdx.z / nmat;
-  const int bx = blockIdx.x * 32, by = blockIdx.y * 32;
-  const unsigned short *src = (which ? Wx : Wa) + (size_t)m * BS * BS;
-  unsigned short *dst = (which ? WTx : WTa) + (size_t)m * BS * BS;
-  for (int i = threadIdx.x; i < 32 * 32; i += 256) {
-    const int r = i >> 5, c = i & 31;
-    tile[r][c] = src[(size_t)(by + r) * BS + bx + c];
+  const int nT = 128 * a.nb;
+  if ((int)blockIdx.x < nT) {
+    const int t = blockIdx.x & 63, mz = blockIdx.x >> 6;
+    const int m = mz % a.nb, which = mz / a.nb;
+    const int bx = (t & 7) * 32, by = (t >> 3) * 32;
+    const unsigned short *src = (which ? a.Wx : a.Wa) + (size_t)m * BS * BS;
+    unsigned short *dst = (which ? a.WTx : a.WTa) + (size_t)m * BS * BS;
+    for (int i = threadIdx.x; i < 32 * 32; i += 256) {
+      const int r = i >> 5, c = i & 31;
+      tile[r][c] = src[(size_t)(by + r) * BS + bx + c];
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 32 * 32; i += 256) {
+      const int r = i >> 5, c = i & 31;
+      dst[(size_t)(bx + r) * BS + by + c] = tile[c][r];
+    }
+    return;
   }
-  __syncthreads();
-  for (int i = threadIdx.x; i < 32 * 32; i += 256) {
-    const int r = i >> 5, c = i & 31;
-    dst[(size_t)(bx + r) * BS + by + c] = tile[c][r];
+  const size_t i = (size_t)(blockIdx.x - nT) * 256 + threadIdx.x;
+  if (i < a.n16) a.zero[i] = make_uint4(0, 0, 0, 0);
+  if (i < (size_t)a.nb * BS * BS / 8) {
+    const int lane = (int)(i & 63), ks = (int)((i >> 6) & 15), wv = (int)((i >> 10) & 7), g = (int)(i >> 13);
+    const int hf = lane >> 5, j = lane & 31;
+    a.wxf[i] = ((const uint4 *)a.Wx)[((size_t)g * BS + wv * 32 + j) * (BS / 8) + ks * 2 + hf];
   }
 }
 
@@ -549,9 +584,10 @@ bwd_dgrad_kernel(DgradArgs a) {
   };
   const __amdgpu_buffer_rsrc_t u_rsrc = rsrc(p.u), du_rsrc = rsrc(p.du);
   const __amdgpu_buffer_rsrc_t dp_rsrc = rsrc(a.dpo), dq_rsrc = rsrc(a.dqo);
-  const __amdgpu_buffer_rsrc_t dx_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      uniform_ptr(a.dxo + seq_off), 0, 2 * seq_bytes, 0x00020000);
-  const unsigned o_voff = (unsigned)d * 2 + (unsigned)hf * 16 * row_bytes;
+  // this wave's du staging tile; lane l stores 8 channels of rows l/4 and l/4 + 16
+  unsigned short *otile = (unsigned short *)(smem + D_OFF_OT) + wv * (OTILE_BYTES / 2);
+  unsigned short *ot_mine = otile + (hf * 16) * OT + j;
+  const unsigned du_voff = (unsigned)(g * BS + wv * 32 + (lane & 3) * 8) * 2 + (unsigned)(lane >> 2) * row_bytes;
 
   // A tiles go from global memory straight into LDS, 16 bytes per lane: one instruction lays
   // 1024 contiguous bytes, the 256 channels of row r (lanes 0-31) and of row r+8 (lanes 32-63)
@@ -565,11 +601,14 @@ bwd_dgrad_kernel(DgradArgs a) {
       const int sl = wv * 2 + i, r0 = (sl & 7) + (sl >> 3) * 16;
       const unsigned so = (unsigned)(t0 + r0) * row_bytes;
       unsigned char *dst = smem + buf * D_A_TILE + sl * (AS * 2);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(dp_rsrc, (__attribute__((address_space(3))) void *)dst, 16, a_voff, so, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(dq_rsrc, (__attribute__((address_space(3))) void *)(dst + D_A_TILE / 2), 16, a_voff, so, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(dp_rsrc, (__attribute__((address_space(3))) void *)dst, 16, a_voff, so, 0, RGLRU_NT);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(dq_rsrc, (__attribute__((address_space(3))) void *)(dst + D_A_TILE / 2), 16, a_voff, so, 0, RGLRU_NT);
     }
   };
   // dxd of this lane's run (channel d, 16 consecutive steps), fp32, zero past the sequence end
+  const __amdgpu_buffer_rsrc_t dx_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_ptr(a.dxo + seq_off), 0, 2 * seq_bytes, 0x00020000);
+  const unsigned dx_voff = ((unsigned)d * 2 + (unsigned)hf * 16 * row_bytes) * 2;
   float dxd[16];
   auto load_dxd = [&](int t0) {
     const int nvalid = T - t0 - hf * 16;
@@ -578,7 +617,7 @@ bwd_dgrad_kernel(DgradArgs a) {
       dxd[r] = 0.f;
       if (r < nvalid)
         dxd[r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
-            dx_rsrc, 2 * o_voff, 2 * (unsigned)(t0 + r) * row_bytes, 0));
+            dx_rsrc, dx_voff, 2 * (unsigned)(t0 + r) * row_bytes, RGLRU_NT));
     }
   };
   // u rows t0-3 .. t0+31 (35 rows), 16 bytes (8 channels) per thread: rows lr, lr+16 and
@@ -596,7 +635,7 @@ bwd_dgrad_kernel(DgradArgs a) {
       uint4 v = make_uint4(0, 0, 0, 0);
       if (rho < US_ROWS) {
         if (t >= 0) {
-          if (t < T) v = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(u_rsrc, u_voff, (unsigned)t * row_bytes, 0));
+          if (t < T) v = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(u_rsrc, u_voff, (unsigned)t * row_bytes, RGLRU_NT));
         } else if (st32) {
           v = *(const uint4 *)(st32 + (size_t)ring_slot(p.pos0 + t) * (D / 2));
         }
@@ -675,9 +714,8 @@ bwd_dgrad_kernel(DgradArgs a) {
         load_u(t0 - TT);
       }
       if (!halo) {
-        // Conv1D adjoint towards the input
-        const unsigned so = (unsigned)t0 * row_bytes;
-        const int nvalid = T - t0 - hf * 16;
+        // Conv1D adjoint towards the input; the wave's [32 steps][32 channels] results leave
+        // through its staging tile as 16-byte stores
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
           float v0 = cw[0] * dx[r], v1 = cw[0] * dx[r + 1];
@@ -687,11 +725,10 @@ bwd_dgrad_kernel(DgradArgs a) {
             v1 = fmaf(cw[k], dx[r + 1 + k], v1);
           }
           const unsigned pk = pack_bf16(v0, v1);
-          if (r < nvalid)
-            __builtin_amdgcn_raw_buffer_store_b16((short)(pk & 0xffff), du_rsrc, o_voff, so + r * row_bytes, 0);
-          if (r + 1 < nvalid)
-            __builtin_amdgcn_raw_buffer_store_b16((short)(pk >> 16), du_rsrc, o_voff, so + (r + 1) * row_bytes, 0);
+          ot_mine[r * OT] = (unsigned short)(pk & 0xffff);
+          ot_mine[(r + 1) * OT] = (unsigned short)(pk >> 16);
         }
+        store_staged_tile_s<OT, RGLRU_NT>(otile, lane, du_rsrc, du_voff, (unsigned)t0 * row_bytes, row_bytes, T - t0);
         // Conv1D adjoint towards the taps: u_{t-k} in accumulator layout by selection
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -827,13 +864,18 @@ bwd_wgrad_kernel(WgradArgs a) {
     for (int h = 0; h < 2; ++h) {
       const long long row = step * TT + lr + 16 * h;
       rl[h] = make_uint4(0, 0, 0, 0);
-      if (row < a.rows) rl[h] = *(const uint4 *)(gsrc + (size_t)row * D);
+      if (row < a.rows) {
+        typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+        const u32x4 *q4 = (const u32x4 *)(gsrc + (size_t)row * D);
+        const u32x4 v = RGLRU_NT ? __builtin_nontemporal_load(q4) : *q4;
+        rl[h] = make_uint4(v[0], v[1], v[2], v[3]);
+      }
     }
     slow = !(nt_ >= 3 && nt_ + 8 <= T && r0 + 8 <= a.rows);
     if (!slow) {
       const unsigned *base = u32 + (size_t)(r0 - 3) * (D / 2);
 #pragma unroll
-      for (int n = 0; n < 11; ++n) raw[n] = base[(unsigned)n * (unsigned)(D / 2)];
+      for (int n = 0; n < 11; ++n) raw[n] = base[(unsigned)n * (unsigned)(D / 2)];  // shared with the other gate's workgroup through L2
     }
     nt_ += TT;
     while (nt_ >= T) {
@@ -1010,30 +1052,43 @@ bwd_wgrad_kernel(WgradArgs a) {
       }
 }
 
-// dW[gate][g][j][k] = sum over slices, in a fixed order
-__global__ void __launch_bounds__(256) reduce_wgrad_kernel(const float *part, int S, size_t per_gate,
-                                                           float *dWa, float *dWx) {
-  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= 2 * per_gate) return;
-  float sum = 0.f;
-  for (int s = 0; s < S; ++s) sum += part[(size_t)s * 2 * per_gate + i];
-  if (i < per_gate)
-    dWa[i] = sum;
-  else
-    dWx[i - per_gate] = sum;
-}
-
-// out[r][d] = sum_q part[q][r][d]
-struct RowOuts5 {
-  float *p[5];
+// Final pass: every partial sum of the three kernels is added up in a fixed order.
+//   blocks [0, nW):  dW[gate][g][j][k] = sum over the S slices of the wgrad kernel
+//   then 3 rows x D: db_a, db_x, dLambda from the gates kernel's B*G partial rows
+//   then 5 rows x D: dconv_w[0..3], dconv_b from the dgrad kernel's B*C partial rows
+struct FinishArgs {
+  const float *partW, *partA, *partC;
+  int S, nA, nC, D;
+  size_t per_gate;
+  float *dWa, *dWx;
+  float *rowsA[3];
+  float *rowsC[5];
 };
-__global__ void __launch_bounds__(256) reduce_rows_kernel(const float *part, int nparts, int rows,
-                                                          int D, RowOuts5 out) {
-  const int d = blockIdx.x * 256 + threadIdx.x, r = blockIdx.y;
-  if (d >= D || !out.p[r]) return;
+__global__ void __launch_bounds__(256) bwd_finish_kernel(FinishArgs a) {
+  const int nW = (int)((2 * a.per_gate + 255) / 256), dblocks = (a.D + 255) / 256;
+  int blk = blockIdx.x;
+  if (blk < nW) {
+    const size_t i = (size_t)blk * 256 + threadIdx.x;
+    if (i >= 2 * a.per_gate) return;
+    float sum = 0.f;
+    for (int s = 0; s < a.S; ++s) sum += a.partW[(size_t)s * 2 * a.per_gate + i];
+    if (i < a.per_gate)
+      a.dWa[i] = sum;
+    else
+      a.dWx[i - a.per_gate] = sum;
+    return;
+  }
+  blk -= nW;
+  const int r = blk / dblocks, d = (blk - r * dblocks) * 256 + threadIdx.x;
+  if (d >= a.D) return;
+  const bool gates = r < 3;
+  const int rr = gates ? r : r - 3, rows = gates ? 3 : 5, n = gates ? a.nA : a.nC;
+  const float *part = gates ? a.partA : a.partC;
+  float *out = gates ? a.rowsA[rr] : a.rowsC[rr];
+  if (!out) return;
   float s = 0.f;
-  for (int q = 0; q < nparts; ++q) s += part[((size_t)q * rows + r) * D + d];
-  out.p[r][d] = s;
+  for (int q = 0; q < n; ++q) s += part[((size_t)q * rows + rr) * a.D + d];
+  out[d] = s;
 }
 
 }  // namespace
@@ -1114,12 +1169,6 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
     configured = true;
   }
   unsigned short *wta = (unsigned short *)(ws + q.off_wta), *wtx = (unsigned short *)(ws + q.off_wtx);
-  {
-    KernelTimer kt("transpose_weights_kernel", s);
-    hipLaunchKernelGGL(transpose_weights_kernel, dim3(BS / 32, BS / 32, 2 * p.nb), dim3(256), 0, s,
-                       (const unsigned short *)p.W_a, (const unsigned short *)p.W_x, wta, wtx, p.nb);
-  }
-  if ((e = hipGetLastError()) != hipSuccess) return e;
 
   // 1. gates, reverse scan, pointwise adjoints
   BwdArgs a;
@@ -1136,7 +1185,19 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   a.wxf = (const unsigned short *)(ws + q.off_wxf);
   // the records only exist (and need clearing) when sequences are sliced in time
   const size_t clear = q.G > 1 ? 256 + (size_t)q.units * q.R * 2 * BS * sizeof(u64) : 0;
-  if ((e = launch_prep(ws + q.off_rec, clear, p.W_x, ws + q.off_wxf, p.nb, s)) != hipSuccess) return e;
+  {
+    PrepArgs pa;
+    pa.Wa = (const unsigned short *)p.W_a; pa.Wx = (const unsigned short *)p.W_x;
+    pa.WTa = wta; pa.WTx = wtx;
+    pa.wxf = (uint4 *)(ws + q.off_wxf);
+    pa.zero = (uint4 *)(ws + q.off_rec);
+    pa.n16 = clear / 16;
+    pa.nb = p.nb;
+    const size_t nfrag = (size_t)p.nb * BS * BS / 8, n = pa.n16 > nfrag ? pa.n16 : nfrag;
+    KernelTimer kt("bwd_prep_kernel", s);
+    hipLaunchKernelGGL(bwd_prep_kernel, dim3((unsigned)(128 * p.nb + (n + 255) / 256)), dim3(256), 0, s, pa);
+  }
+  if ((e = hipGetLastError()) != hipSuccess) return e;
   {
     KernelTimer kt("bwd_gates_kernel", s);
     if (q.G == 1)
@@ -1147,13 +1208,6 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
       hipLaunchKernelGGL(bwd_gates_kernel<8>, dim3(grid), dim3(NTHR), G_LDS, s, a);
   }
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  const int dblocks = (p.D + 255) / 256;
-  const RowOuts5 gate_outs = {{p.g.db_a, p.g.db_x, p.g.dLambda, nullptr, nullptr}};
-  {
-    KernelTimer kt("reduce_rows_kernel", s);
-    hipLaunchKernelGGL(reduce_rows_kernel, dim3(dblocks, 3), dim3(256), 0, s, (const float *)a.part,
-                       p.B * q.G, 3, p.D, gate_outs);
-  }
 
   // 2. dgrad and Conv1D adjoint
   DgradArgs dg;
@@ -1167,13 +1221,6 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
     hipLaunchKernelGGL(bwd_dgrad_kernel, dim3(q.units * q.C), dim3(NTHR), D_LDS, s, dg);
   }
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  const RowOuts5 conv_outs = {{p.g.dconv_w, p.g.dconv_w + p.D, p.g.dconv_w + 2 * (size_t)p.D,
-                               p.g.dconv_w + 3 * (size_t)p.D, p.g.dconv_b}};
-  {
-    KernelTimer kt("reduce_rows_kernel", s);
-    hipLaunchKernelGGL(reduce_rows_kernel, dim3(dblocks, 5), dim3(256), 0, s, (const float *)dg.part,
-                       p.B * q.C, 5, p.D, conv_outs);
-  }
 
   // 3. wgrad
   WgradArgs wg;
@@ -1190,11 +1237,19 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
     hipLaunchKernelGGL(bwd_wgrad_kernel, dim3((q.S * 2 * p.nb + 15) / 16 * 16), dim3(NTHR), W_LDS, s, wg);
   }
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  const size_t per_gate = (size_t)p.nb * BS * BS;
+  // 4. all partial sums
+  FinishArgs fa;
+  fa.partW = wg.part; fa.partA = a.part; fa.partC = dg.part;
+  fa.S = q.S; fa.nA = p.B * q.G; fa.nC = p.B * q.C; fa.D = p.D;
+  fa.per_gate = (size_t)p.nb * BS * BS;
+  fa.dWa = p.g.dW_a; fa.dWx = p.g.dW_x;
+  fa.rowsA[0] = p.g.db_a; fa.rowsA[1] = p.g.db_x; fa.rowsA[2] = p.g.dLambda;
+  for (int k = 0; k < 4; ++k) fa.rowsC[k] = p.g.dconv_w + (size_t)k * p.D;
+  fa.rowsC[4] = p.g.dconv_b;
   {
-    KernelTimer kt("reduce_wgrad_kernel", s);
-    hipLaunchKernelGGL(reduce_wgrad_kernel, dim3((unsigned)((2 * per_gate + 255) / 256)), dim3(256), 0, s,
-                       (const float *)wg.part, q.S, per_gate, p.g.dW_a, p.g.dW_x);
+    const unsigned nW = (unsigned)((2 * fa.per_gate + 255) / 256), dblocks = (unsigned)((p.D + 255) / 256);
+    KernelTimer kt("bwd_finish_kernel", s);
+    hipLaunchKernelGGL(bwd_finish_kernel, dim3(nW + 8 * dblocks), dim3(256), 0, s, fa);
   }
   return hipGetLastError();
 }

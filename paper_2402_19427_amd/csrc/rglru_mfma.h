@@ -62,15 +62,27 @@ __device__ __forceinline__ u64 peek(const u64 *slot) {
 //   voff    byte offset of (row l/4, channel group l%4) of this lane inside the sequence
 //   soff    byte offset of the tile's first row
 //   nrows   rows of the tile inside the sequence (>= 32 for a full tile)
+// Cache policy of the big once-through streams (bit 1 of a buffer instruction's auxiliary
+// operand = non-temporal): they should not push the re-read weight fragments out of L2.
+#ifndef RGLRU_NT
+#define RGLRU_NT 2
+#endif
+
+template <int STRIDE, int AUX = 0>
+__device__ __forceinline__ void store_staged_tile_s(const unsigned short *ot, int lane,
+                                                    __amdgpu_buffer_rsrc_t rsrc, unsigned voff,
+                                                    unsigned soff, unsigned row_bytes, int nrows) {
+  const int row = lane >> 2, chunk = lane & 3;
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v0 = *(const u32x4 *)(ot + row * STRIDE + chunk * 8);
+  const u32x4 v1 = *(const u32x4 *)(ot + (row + 16) * STRIDE + chunk * 8);
+  if (row < nrows) __builtin_amdgcn_raw_buffer_store_b128(v0, rsrc, voff, soff, AUX);
+  if (row + 16 < nrows) __builtin_amdgcn_raw_buffer_store_b128(v1, rsrc, voff, soff + 16 * row_bytes, AUX);
+}
 __device__ __forceinline__ void store_staged_tile(const unsigned short *ot, int lane,
                                                   __amdgpu_buffer_rsrc_t rsrc, unsigned voff,
                                                   unsigned soff, unsigned row_bytes, int nrows) {
-  const int row = lane >> 2, chunk = lane & 3;
-  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-  const u32x4 v0 = *(const u32x4 *)(ot + row * OT + chunk * 8);
-  const u32x4 v1 = *(const u32x4 *)(ot + (row + 16) * OT + chunk * 8);
-  if (row < nrows) __builtin_amdgcn_raw_buffer_store_b128(v0, rsrc, voff, soff, 0);
-  if (row + 16 < nrows) __builtin_amdgcn_raw_buffer_store_b128(v1, rsrc, voff, soff + 16 * row_bytes, 0);
+  store_staged_tile_s<OT>(ot, lane, rsrc, voff, soff, row_bytes, nrows);
 }
 
 // host side (defined with the forward kernel)
