@@ -441,7 +441,8 @@ fwd_mfma_kernel(FwdArgs a) {
   // the pointwise work of the same tile, waves 4-7 do the pointwise work of their previous tile
   // first and multiply afterwards, keeping the accumulators across the barrier. Matrix and
   // vector phases of the pair then overlap instead of colliding.
-  const bool late = RGLRU_ROTATE && wv >= NWAVE / 2;
+  // (without time slices every weight is resident and the plain order is the faster one)
+  const bool late = RGLRU_ROTATE && GMAX > 1 && wv >= NWAVE / 2;
 
   int tile = w;
   if (tile < a.ntile) load_rows(tile * TT);
@@ -458,11 +459,13 @@ fwd_mfma_kernel(FwdArgs a) {
       const int buf = it & 1;
       const int next = tile + G;
       RGLRU_TR(0);
-      if (GMAX > 1 && held >= 0) fetch_records(held);
       if (!LATE) {
-        if (next < a.ntile) load_rows(next * TT);     // lands while this tile is computed
+        // rows of the next tile: where W_x fragments are streamed, after them (loads return in
+        // order, and these are trips to HBM); they land during the pointwise work
+        if (NRES == 16 && next < a.ntile) load_rows(next * TT);
         gemm(buf);
         RGLRU_TR(1);
+        if (NRES < 16 && next < a.ntile) load_rows(next * TT);
         pointwise(tile);
       } else {
         RGLRU_TR(1);
@@ -473,15 +476,16 @@ fwd_mfma_kernel(FwdArgs a) {
       // next tile of this workgroup into the other LDS buffer
       RGLRU_TR(4);
       if (next < a.ntile) conv_rows(buf ^ 1);
+      // aggregates the parked tile will need: requested here, a whole step before their use and
+      // clear of the streamed weight fragments (loads return in order); the other slices
+      // published them earlier in this step
+      if (GMAX > 1 && held >= 0) fetch_records(held);
       RGLRU_TR(5);
       __syncthreads();
       RGLRU_TR(6);
       RGLRU_TR_FLUSH((int)blockIdx.x, wv, it);
     }
-    if (LATE && it > 0) {
-      if (GMAX > 1 && held >= 0) fetch_records(held);
-      pointwise(tile - G);
-    }
+    if (LATE && it > 0) pointwise(tile - G);
   };
   if (late) run(std::true_type{});
   else run(std::false_type{});
