@@ -126,7 +126,11 @@ fwd_mfma_kernel(FwdArgs a) {
 #ifndef RGLRU_NRES4
 #define RGLRU_NRES4 8
 #endif
+#ifndef RGLRU_FWD_PF
+#define RGLRU_FWD_PF 2
+#endif
   constexpr int NRES = GMAX == 1 ? 16 : (GMAX == 4 ? RGLRU_NRES4 : 4);
+  constexpr int PF = RGLRU_FWD_PF;
   bf16x8 wa[16], wx[NRES];
   const bf16x8 *pxs = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
   {
@@ -321,10 +325,12 @@ fwd_mfma_kernel(FwdArgs a) {
     const unsigned short *ap = arow_base + buf * (2 * XT_ELEMS);
     {
       bf16x8 a0 = *(const bf16x8 *)(ap), a1 = *(const bf16x8 *)(ap + 16);
-      bf16x8 st0 = a0, st1 = a0;  // streamed W_x fragments, two K-steps ahead
+      // streamed W_x fragments: a ring of PF, all requested up front (the resident K-steps
+      // come first, so the ring has that long to fill)
+      bf16x8 st[PF];
       if (NRES < 16) {
-        st0 = pxs[NRES * 2];
-        st1 = pxs[(NRES + 1 < 16 ? NRES + 1 : 15) * 2];
+#pragma unroll
+        for (int i = 0; i < PF; ++i) st[i] = pxs[(NRES + i < 16 ? NRES + i : 15) * 2];
       }
 #ifdef RGLRU_EXP_NOGEMM
 #pragma unroll 1
@@ -344,9 +350,8 @@ fwd_mfma_kernel(FwdArgs a) {
           accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wx[ks], accq, 0, 0, 0);
         } else {
 #endif
-          accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, st0, accq, 0, 0, 0);
-          st0 = st1;
-          if (ks + 2 < 16) st1 = pxs[(ks + 2) * 2];
+          accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, st[(ks - NRES) % PF], accq, 0, 0, 0);
+          if (ks + PF < 16) st[(ks - NRES) % PF] = pxs[(ks + PF) * 2];
         }
         __builtin_amdgcn_sched_barrier(0);
         a0 = a1;
