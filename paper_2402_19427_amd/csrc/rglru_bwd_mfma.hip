@@ -858,24 +858,33 @@ bwd_wgrad_kernel(WgradArgs a) {
   // the calls walk consecutive tiles, so it advances without a division
   long long nb_ = (st_lo * TT + 8 * rg) / T;
   int nt_ = (int)(st_lo * TT + 8 * rg - nb_ * T);
+  // Both fetches go through buffer descriptors made per tile (the flattened row index does not
+  // fit a 32-bit byte offset for large batches): scalar row offsets, one per-lane column offset,
+  // rows past the end of the tensor read as zero.
+  const unsigned row_bytes = (unsigned)D * 2;
+  const unsigned t_voff = (unsigned)(g * BS + 8 * lc) * 2 + (unsigned)lr * row_bytes;   // dp / dq rows lr, lr+16
+  const unsigned u_voff = (unsigned)dc * 2;                                           // channel pair
   auto load_tiles = [&](long long step) __attribute__((always_inline)) {
     const long long r0 = step * TT + 8 * rg;
+    {
+      const long long first = step * TT, left = a.rows - first;
+      const unsigned nrows = left < TT ? (unsigned)left : (unsigned)TT;
+      const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+          uniform_ptr(src + (size_t)first * D), 0, nrows * row_bytes, 0x00020000);
+      typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const long long row = step * TT + lr + 16 * h;
-      rl[h] = make_uint4(0, 0, 0, 0);
-      if (row < a.rows) {
-        typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-        const u32x4 *q4 = (const u32x4 *)(gsrc + (size_t)row * D);
-        const u32x4 v = RGLRU_NT ? __builtin_nontemporal_load(q4) : *q4;
+      for (int h = 0; h < 2; ++h) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, t_voff, (unsigned)(16 * h) * row_bytes, RGLRU_NT);
         rl[h] = make_uint4(v[0], v[1], v[2], v[3]);
       }
     }
     slow = !(nt_ >= 3 && nt_ + 8 <= T && r0 + 8 <= a.rows);
     if (!slow) {
-      const unsigned *base = u32 + (size_t)(r0 - 3) * (D / 2);
+      // (cached normally: the other gate's workgroup of this slice finds these rows in L2)
+      const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(
+          uniform_ptr(a.u + (size_t)(r0 - 3) * D), 0, 11 * row_bytes, 0x00020000);
 #pragma unroll
-      for (int n = 0; n < 11; ++n) raw[n] = base[(unsigned)n * (unsigned)(D / 2)];  // shared with the other gate's workgroup through L2
+      for (int n = 0; n < 11; ++n) raw[n] = __builtin_amdgcn_raw_buffer_load_b32(ru, u_voff, (unsigned)n * row_bytes, 0);
     }
     nt_ += TT;
     while (nt_ >= T) {
