@@ -33,9 +33,6 @@ constexpr int FWD_LDS = XS_BYTES + CONST_BYTES + HOLD_BYTES + NWAVE * OTILE_BYTE
 
 // Optional phase timestamps for tuning builds (compiled out otherwise): wave `wv` of workgroup
 // `wg` records the shader clock at up to 8 points of each of its first 32 iterations.
-#ifndef RGLRU_ROTATE
-#define RGLRU_ROTATE 1
-#endif
 #ifdef RGLRU_TRACE
 __device__ unsigned long long g_trace[512 * 8 * 32 * 8];
 #define RGLRU_TR(k) tr[k] = __builtin_amdgcn_s_memtime()
@@ -62,11 +59,6 @@ struct FwdArgs {
 // Returns a_t and b_t = sqrt(1-a_t^2) * i_t * x_t.
 __device__ __forceinline__ void gate_fast(float pp, float qq, float xx, float kd, float &a,
                                           float &b) {
-#ifdef RGLRU_EXP_NOGATE
-  a = 0.99f + 1e-9f * pp;
-  b = xx + 1e-9f * qq + kd * 0.f;
-  return;
-#endif
   const float ep = __builtin_amdgcn_exp2f(-pp);
   const float r = __builtin_amdgcn_rcpf(1.f + ep);
   a = __builtin_amdgcn_exp2f(kd * r);
@@ -123,14 +115,8 @@ fwd_mfma_kernel(FwdArgs a) {
   // (when the sequence is sliced in time the kernel needs more registers for the carry
   // exchange; the last K-steps of W_x are then re-read from L2 every tile - a far better spill
   // space than scratch memory)
-#ifndef RGLRU_NRES4
-#define RGLRU_NRES4 8
-#endif
-#ifndef RGLRU_FWD_PF
-#define RGLRU_FWD_PF 2
-#endif
-  constexpr int NRES = GMAX == 1 ? 16 : (GMAX == 4 ? RGLRU_NRES4 : 4);
-  constexpr int PF = RGLRU_FWD_PF;
+  constexpr int NRES = GMAX == 1 ? 16 : (GMAX == 4 ? 8 : 4);
+  constexpr int PF = 2;   // streamed fragments in flight (deeper rings measured no better)
   bf16x8 wa[16], wx[NRES];
   const bf16x8 *pxs = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
   {
@@ -216,15 +202,6 @@ fwd_mfma_kernel(FwdArgs a) {
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
       float x0 = bb[0], x1 = bb[1];
-#ifdef RGLRU_EXP_NOCONV
-      x0 += __uint_as_float(raw[r]); x1 += __uint_as_float(raw[r + 3]);
-      {
-        unsigned hi_pk = __float_as_uint(x0), lo_pk = __float_as_uint(x1);
-        *(unsigned *)(xw + buf * (2 * XT_ELEMS) + r * XS) = hi_pk;
-        *(unsigned *)(xw + buf * (2 * XT_ELEMS) + XT_ELEMS + r * XS) = lo_pk;
-      }
-      continue;
-#endif
       x0 = fmaf(w01[0], bf_lo(raw[r + 3]), x0); x1 = fmaf(w01[1], bf_hi(raw[r + 3]), x1);
       x0 = fmaf(w01[2], bf_lo(raw[r + 2]), x0); x1 = fmaf(w01[3], bf_hi(raw[r + 2]), x1);
       x0 = fmaf(w23[0], bf_lo(raw[r + 1]), x0); x1 = fmaf(w23[1], bf_hi(raw[r + 1]), x1);
@@ -303,9 +280,7 @@ fwd_mfma_kernel(FwdArgs a) {
     float hrun = hf ? fmaf(hA_lo, h, hH_lo) : h;  // state entering this lane's run
 #pragma unroll
     for (int q = 0; q < 4; ++q) run_quarter(q, hold_mine[q * 64], hold_mine[(q + 4) * 64], hrun);
-#ifndef RGLRU_EXP_NOSTORE
     store_staged_tile(otile, lane, y_rsrc, yw_voff, (unsigned)(t * TT) * row_bytes, row_bytes, T - t * TT);
-#endif
     carry = fmaf(hA_t, h, hH_t);
   };
 
@@ -332,24 +307,13 @@ fwd_mfma_kernel(FwdArgs a) {
 #pragma unroll
         for (int i = 0; i < PF; ++i) st[i] = pxs[(NRES + i < 16 ? NRES + i : 15) * 2];
       }
-#ifdef RGLRU_EXP_NOGEMM
-#pragma unroll 1
-      for (int ks = 0; ks < 1; ++ks) {
-#else
 #pragma unroll
       for (int ks = 0; ks < 16; ++ks) {
-#endif
         const bf16x8 a2 = *(const bf16x8 *)(ap + ((ks + 2) & 15) * 16);  // two steps ahead
         accp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wa[ks], accp, 0, 0, 0);
-#ifdef RGLRU_EXP_NOSTREAM
-        if (true) {
-          accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wx[ks % NRES], accq, 0, 0, 0);
-        } else {
-#else
         if (ks < NRES) {
           accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wx[ks], accq, 0, 0, 0);
         } else {
-#endif
           accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, st[(ks - NRES) % PF], accq, 0, 0, 0);
           if (ks + PF < 16) st[(ks - NRES) % PF] = pxs[(ks + PF) * 2];
         }
@@ -428,10 +392,6 @@ fwd_mfma_kernel(FwdArgs a) {
       hA_t = hA_lo * A_up;
       hH_t = fmaf(A_up, hH_lo, H_up);
     }
-#ifdef RGLRU_EXP_NORESOLVE
-    if (hrun == 12345.f) resolve(tl);
-    carry += hA_t;
-#else
     if (GMAX > 1) {
       // publish the aggregate: lower half writes A, upper half writes H
       publish(ring + (size_t)(tl % a.R) * 2 * BS + hf * BS, hf ? hH_t : hA_t, (unsigned)(tl + 1));
@@ -439,7 +399,6 @@ fwd_mfma_kernel(FwdArgs a) {
     } else {
       resolve(tl);
     }
-#endif
   };
 
   // The two waves that share a SIMD run half a step apart: waves 0-3 multiply first and then do
@@ -447,7 +406,7 @@ fwd_mfma_kernel(FwdArgs a) {
   // first and multiply afterwards, keeping the accumulators across the barrier. Matrix and
   // vector phases of the pair then overlap instead of colliding.
   // (without time slices every weight is resident and the plain order is the faster one)
-  const bool late = RGLRU_ROTATE && GMAX > 1 && wv >= NWAVE / 2;
+  const bool late = GMAX > 1 && wv >= NWAVE / 2;
 
   int tile = w;
   if (tile < a.ntile) load_rows(tile * TT);
