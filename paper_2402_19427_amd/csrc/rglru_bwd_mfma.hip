@@ -29,12 +29,16 @@ namespace {
 constexpr float LN2 = 0.6931471805599453f;
 constexpr int TS = TT + 8;                       // row stride (bf16) of the [channel][time] tiles
 constexpr int TR_BYTES = BS * TS * 2;            // one transposed tile
-// LDS of the gates kernel: x tiles (high, low) | constants | dy^T | y^T | r_t of the tile
-constexpr int G_OFF_CONST = XS_BYTES;
+// LDS of the gates kernel: x tile (high, low) | constants | dy^T | y^T | r_t of the tile |
+// W_x fragments
+constexpr int G_NRES = 4;                        // K-steps of W_x resident in registers
+constexpr int G_NLDS = 5;                        // further K-steps of W_x resident in LDS
+constexpr int G_OFF_CONST = XS_BYTES / 2;        // one x buffer: the kernel has two barriers per tile
 constexpr int G_OFF_DYT = G_OFF_CONST + CONST_BYTES;
 constexpr int G_OFF_YT = G_OFF_DYT + TR_BYTES;
 constexpr int G_OFF_HOLD = G_OFF_YT + TR_BYTES;
-constexpr int G_LDS = G_OFF_HOLD + HOLD_BYTES / 2;
+constexpr int G_OFF_WX = G_OFF_HOLD + HOLD_BYTES / 2;
+constexpr int G_LDS = G_OFF_WX + G_NLDS * NWAVE * 64 * 16;
 
 // Optional phase timestamps for tuning builds (compiled out otherwise)
 #ifdef RGLRU_TRACE
@@ -102,12 +106,14 @@ bwd_gates_kernel(BwdArgs a) {
   const int d = g * BS + ch;
 
   // gate weights of this wave's 32 output channels: all of W_a and the first NRES K-steps of W_x
-  // stay in registers; the rest of W_x is re-read from L2 every tile (the register file cannot
-  // hold everything this kernel needs, and L2 is a far better spill space than scratch)
-  constexpr int NRES = 4;
+  // stay in registers, the next NLDS K-steps of W_x in LDS, and the rest is re-read from L2
+  // every tile as contiguous 1 KB fragments (the register file cannot hold everything this
+  // kernel needs, and L2 is a far better spill space than scratch)
+  constexpr int NRES = G_NRES, NLDS = G_NLDS;
   bf16x8 wa[16], wx[NRES];
   // fragment ks of this lane when streamed: pxs[ks * 64] (W_x in fragment order)
   const bf16x8 *pxs = (const bf16x8 *)a.wxf + (size_t)(g * NWAVE + wv) * 16 * 64 + lane;
+  bf16x8 *wxl = (bf16x8 *)(smem + G_OFF_WX) + (size_t)wv * NLDS * 64 + lane;   // [K-step][lane]
   {
     const bf16x8 *pa = (const bf16x8 *)((const unsigned short *)p.W_a + ((size_t)g * BS + ch) * BS + hf * 8);
     const bf16x8 *px = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
@@ -115,6 +121,8 @@ bwd_gates_kernel(BwdArgs a) {
     for (int ks = 0; ks < 16; ++ks) wa[ks] = pa[ks * 2];
 #pragma unroll
     for (int ks = 0; ks < NRES; ++ks) wx[ks] = px[ks * 2];
+#pragma unroll
+    for (int i = 0; i < NLDS; ++i) wxl[i * 64] = px[(NRES + i) * 2];   // read back by the same lane only
   }
   if (tid < 64) {
     bf16x8 sel0, sel1;
@@ -166,8 +174,7 @@ bwd_gates_kernel(BwdArgs a) {
       uniform_ptr(a.dxo + seq_off), 0, 2 * seq_bytes, 0x00020000);
   const unsigned dx_voff = ((unsigned)d * 2 + (unsigned)hf * 16 * row_bytes) * 2;  // channel, lane half
   const unsigned c_voff = (unsigned)dc * 2;                                   // channel pair
-  // 16-byte stores of a staged tile: lane l owns 8 channels of rows l/4 and l/4+16
-  const unsigned st_voff = (unsigned)(g * BS + wv * 32 + (lane & 3) * 8) * 2 + (unsigned)(lane >> 2) * row_bytes;
+  const unsigned o_voff = (unsigned)d * 2 + (unsigned)hf * 16 * row_bytes;    // channel, lane half
   const unsigned *st32 =
       p.state_in ? (const unsigned *)((const unsigned short *)p.state_in + (size_t)b * 3 * D + dc) : nullptr;
 
@@ -193,8 +200,8 @@ bwd_gates_kernel(BwdArgs a) {
     }
   };
   unsigned short *xw = xs + (8 * rg) * XS + 2 * c2;
-  // Conv1D rows of this workgroup's next tile into LDS buffer `buf`
-  auto conv_rows = [&](int buf) {
+  // Conv1D rows of this workgroup's next tile into the x tile
+  auto conv_rows = [&]() {
     const f32x4 w01 = cw_lds[c2], w23 = cw_lds[128 + c2], bb = cw_lds[256 + c2];
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
@@ -205,8 +212,8 @@ bwd_gates_kernel(BwdArgs a) {
       x0 = fmaf(w23[2], bf_lo(raw[r]), x0);     x1 = fmaf(w23[3], bf_hi(raw[r]), x1);
       unsigned hi_pk, lo_pk;
       split_bf16(x0, x1, hi_pk, lo_pk);
-      *(unsigned *)(xw + buf * (2 * XT_ELEMS) + r * XS) = hi_pk;
-      *(unsigned *)(xw + buf * (2 * XT_ELEMS) + XT_ELEMS + r * XS) = lo_pk;
+      *(unsigned *)(xw + r * XS) = hi_pk;
+      *(unsigned *)(xw + XT_ELEMS + r * XS) = lo_pk;
     }
   };
   // dy and y rows 8*rg..8*rg+7 of tile t0 for the channel pair (zero past the sequence end)
@@ -253,12 +260,12 @@ bwd_gates_kernel(BwdArgs a) {
   int tile = a.ntile - 1 - w;
   if (tile >= 0) load_rows(tile * TT);
   __syncthreads();
-  if (tile >= 0) conv_rows(0);
+  if (tile >= 0) conv_rows();
   if (tile >= 0) load_dy_y(tile * TT);
   __syncthreads();
 
   for (int it = 0; tile >= 0; tile -= G, ++it) {
-    const int buf = it & 1, t0 = tile * TT;
+    const int t0 = tile * TT;
     const int next = tile - G;
 #ifdef RGLRU_TRACE
     unsigned long long tr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -273,16 +280,21 @@ bwd_gates_kernel(BwdArgs a) {
       accq[r] = bias_q;
       accx[r] = 0.f;
     }
-    const unsigned short *ap = arow_base + buf * (2 * XT_ELEMS);
+    const unsigned short *ap = arow_base;
     {
       bf16x8 a0 = *(const bf16x8 *)(ap), a1 = *(const bf16x8 *)(ap + 16);
-      bf16x8 s0 = pxs[NRES * 64], s1 = pxs[(NRES + 1) * 64];   // streamed W_x fragments, two ahead
+      constexpr int NS = NRES + NLDS;                            // first streamed K-step
+      bf16x8 s0 = pxs[NS * 64], s1 = pxs[(NS + 1) * 64];         // streamed W_x fragments, two in flight
+      bf16x8 l0 = wxl[0];                                        // LDS-resident fragment, one ahead
 #pragma unroll
       for (int ks = 0; ks < 16; ++ks) {
         const bf16x8 a2 = *(const bf16x8 *)(ap + ((ks + 2) & 15) * 16);
         accp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wa[ks], accp, 0, 0, 0);
         if (ks < NRES) {
           accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wx[ks], accq, 0, 0, 0);
+        } else if (ks < NS) {
+          accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, l0, accq, 0, 0, 0);
+          if (ks + 1 < NS) l0 = wxl[(ks + 1 - NRES) * 64];
         } else {
           accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, s0, accq, 0, 0, 0);
           s0 = s1;
@@ -384,10 +396,6 @@ bwd_gates_kernel(BwdArgs a) {
     // ---- second sweep: adjoints with the true eps, latest step first
     float erev = hf ? e_in : fmaf(A_up, e_in, E_up);  // eps_{t+1} for the last step of this run
     const unsigned so = (unsigned)t0 * row_bytes;
-    // staging for the dp / dq columns: the x tile of this step is no longer read by anyone
-    // (every wave has passed the barrier after the products), 4 KB of it per wave
-    unsigned short *stage = xs + buf * (2 * XT_ELEMS) + wv * (2 * 32 * 32);
-    unsigned short *stage_mine = stage + (hf * 16) * 32 + j;
 #pragma unroll
     for (int q = 3; q >= 0; --q) {
       const uint4 dq4 = dyT_mine[q >> 1], yq4 = yT_mine[q >> 1];
@@ -420,15 +428,22 @@ bwd_gates_kernel(BwdArgs a) {
         erev = ok ? av * delta : erev;
         __builtin_amdgcn_sched_barrier(0);  // one element at a time: registers are scarce here
       }
-      // dp, dq: columns of this wave's two [32 steps][32 channels] staging tiles
+      // dp, dq (bf16): one 64-byte piece of a row per lane half and step
       {
         const unsigned p0 = pack_bf16(dpv[0], dpv[1]), p1 = pack_bf16(dpv[2], dpv[3]);
         const unsigned q0 = pack_bf16(dqv[0], dqv[1]), q1 = pack_bf16(dqv[2], dqv[3]);
-        unsigned short *sp = stage_mine + (4 * q) * 32, *sq = sp + 32 * 32;
-        sp[0] = (unsigned short)(p0 & 0xffff); sp[32] = (unsigned short)(p0 >> 16);
-        sp[64] = (unsigned short)(p1 & 0xffff); sp[96] = (unsigned short)(p1 >> 16);
-        sq[0] = (unsigned short)(q0 & 0xffff); sq[32] = (unsigned short)(q0 >> 16);
-        sq[64] = (unsigned short)(q1 & 0xffff); sq[96] = (unsigned short)(q1 >> 16);
+        const unsigned soq = so + (unsigned)(4 * q) * row_bytes;
+        const int nv = nvalid - 4 * q;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (e < nv) {
+            const unsigned pp = e < 2 ? p0 : p1, qq = e < 2 ? q0 : q1;
+            const short sp = (short)((e & 1) ? (pp >> 16) : (pp & 0xffff));
+            const short sq = (short)((e & 1) ? (qq >> 16) : (qq & 0xffff));
+            __builtin_amdgcn_raw_buffer_store_b16(sp, dp_rsrc, o_voff, soq + e * row_bytes, RGLRU_NT);
+            __builtin_amdgcn_raw_buffer_store_b16(sq, dq_rsrc, o_voff, soq + e * row_bytes, RGLRU_NT);
+          }
+        }
       }
       // dxd (fp32): one 128-byte piece of a row per lane half and step
 #pragma unroll
@@ -437,13 +452,10 @@ bwd_gates_kernel(BwdArgs a) {
           __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(dxv[e]), dx_rsrc, dx_voff,
                                                 2 * (so + (unsigned)(4 * q + e) * row_bytes), RGLRU_NT);
     }
-    // the staged dp / dq tiles leave as 16-byte stores (rows past the end of the sequence are skipped)
-    store_staged_tile_s<32, RGLRU_NT>(stage, lane, dp_rsrc, st_voff, so, row_bytes, T - t0);
-    store_staged_tile_s<32, RGLRU_NT>(stage + 32 * 32, lane, dq_rsrc, st_voff, so, row_bytes, T - t0);
 
     RGLRU_TR(6);
     if (next >= 0) {
-      conv_rows(buf ^ 1);
+      conv_rows();
       // dy and y of the next tile: requested before the barrier, so that part of the trip to HBM
       // is over when the streamed weight fragments of the next product queue up behind it
       load_dy_y(next * TT);
