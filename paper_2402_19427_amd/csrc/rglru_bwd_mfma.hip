@@ -52,6 +52,13 @@ __device__ unsigned long long g_trace_bwd[512 * 8 * 32 * 8];
 #define RGLRU_TR(k)
 #define RGLRU_TR_FLUSH(wg, wv, it)
 #endif
+#if defined(RGLRU_TRACE) && defined(RGLRU_TRACE_DGRAD)
+#define RGLRU_TRD(k) RGLRU_TR(k)
+#define RGLRU_TRD_FLUSH(wg, wv, it) RGLRU_TR_FLUSH(wg, wv, it)
+#else
+#define RGLRU_TRD(k)
+#define RGLRU_TRD_FLUSH(wg, wv, it)
+#endif
 #if defined(RGLRU_TRACE) && defined(RGLRU_TRACE_WGRAD)
 #define RGLRU_TRW(k) RGLRU_TR(k)
 #define RGLRU_TRW_FLUSH(wg, wv, it) RGLRU_TR_FLUSH(wg, wv, it)
@@ -218,17 +225,14 @@ bwd_gates_kernel(BwdArgs a) {
   };
   // dy and y rows 8*rg..8*rg+7 of tile t0 for the channel pair (zero past the sequence end)
   unsigned rdy[8], ry[8];
+  // (no branch around the loads: rows past the end of the sequence are out of the descriptors'
+  // range and read as zero; a conditional load would make the compiler wait for it on the spot)
   auto load_dy_y = [&](int t0) {
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
-      const int t = t0 + 8 * rg + r;
-      unsigned v0 = 0, v1 = 0;
-      if (t < T) {
-        v0 = __builtin_amdgcn_raw_buffer_load_b32(dy_rsrc, c_voff, (unsigned)t * row_bytes, RGLRU_NT);
-        v1 = __builtin_amdgcn_raw_buffer_load_b32(y_rsrc, c_voff, (unsigned)t * row_bytes, RGLRU_NT);
-      }
-      rdy[r] = v0;
-      ry[r] = v1;
+      const unsigned so = (unsigned)(t0 + 8 * rg + r) * row_bytes;
+      rdy[r] = __builtin_amdgcn_raw_buffer_load_b32(dy_rsrc, c_voff, so, RGLRU_NT);
+      ry[r] = __builtin_amdgcn_raw_buffer_load_b32(y_rsrc, c_voff, so, RGLRU_NT);
     }
   };
   // transposed [channel][time] copies: 8 consecutive steps of one channel are 16 contiguous bytes
@@ -622,15 +626,12 @@ bwd_dgrad_kernel(DgradArgs a) {
       uniform_ptr(a.dxo + seq_off), 0, 2 * seq_bytes, 0x00020000);
   const unsigned dx_voff = ((unsigned)d * 2 + (unsigned)hf * 16 * row_bytes) * 2;
   float dxd[16];
-  auto load_dxd = [&](int t0) {
-    const int nvalid = T - t0 - hf * 16;
+  // (no branches around these loads, see load_u below; `ok` false pushes them all out of range)
+  auto load_dxd = [&](int t0, bool ok) {
+    const unsigned vo = ok ? dx_voff : 0x80000000u;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      dxd[r] = 0.f;
-      if (r < nvalid)
-        dxd[r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
-            dx_rsrc, dx_voff, 2 * (unsigned)(t0 + r) * row_bytes, RGLRU_NT));
-    }
+    for (int r = 0; r < 16; ++r)
+      dxd[r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(dx_rsrc, vo, 2 * (unsigned)(t0 + r) * row_bytes, RGLRU_NT));
   };
   // u rows t0-3 .. t0+31 (35 rows), 16 bytes (8 channels) per thread: rows lr, lr+16 and
   // (for lr < 3) lr+32
@@ -640,19 +641,34 @@ bwd_dgrad_kernel(DgradArgs a) {
       p.state_in ? (const unsigned *)((const unsigned short *)p.state_in + (size_t)b * 3 * D + g * BS + 8 * lc)
                  : nullptr;
   uint4 ru[3];
-  auto load_u = [&](int t0) {
+  // No branches around the loads: a loaded value that meets a zero in a phi makes the compiler
+  // wait for it on the spot, and that wait drains every outstanding load (a trip to HBM, three
+  // times per tile). Rows past the end of the sequence and the row slots past 35 are pushed
+  // out of the descriptor's range instead and read as zero; only the tile at t = 0, whose first
+  // three rows come from the carried-in state, takes the branchy path.
+  auto load_u = [&](int t0, bool ok) {
+    if (t0 > 0 || !ok) {
+      const unsigned so = ok ? (unsigned)(t0 - 3) * row_bytes : 0u;
 #pragma unroll
-    for (int h = 0; h < 3; ++h) {
-      const int rho = lr + 16 * h, t = t0 - 3 + rho;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (rho < US_ROWS) {
-        if (t >= 0) {
-          if (t < T) v = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(u_rsrc, u_voff, (unsigned)t * row_bytes, RGLRU_NT));
-        } else if (st32) {
-          v = *(const uint4 *)(st32 + (size_t)ring_slot(p.pos0 + t) * (D / 2));
-        }
+      for (int h = 0; h < 3; ++h) {
+        const int rho = lr + 16 * h;
+        const unsigned vo = (ok && rho < US_ROWS) ? u_voff + (unsigned)rho * row_bytes : 0x80000000u;
+        ru[h] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(u_rsrc, vo, so, RGLRU_NT));
       }
-      ru[h] = v;
+    } else {
+#pragma unroll
+      for (int h = 0; h < 3; ++h) {
+        const int rho = lr + 16 * h, t = t0 - 3 + rho;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (rho < US_ROWS) {
+          if (t >= 0) {
+            if (t < T) v = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(u_rsrc, u_voff, (unsigned)t * row_bytes, RGLRU_NT));
+          } else if (st32) {
+            v = *(const uint4 *)(st32 + (size_t)ring_slot(p.pos0 + t) * (D / 2));
+          }
+        }
+        ru[h] = v;
+      }
     }
   };
   auto park_u = [&](int ub) {
@@ -683,12 +699,16 @@ bwd_dgrad_kernel(DgradArgs a) {
     int tile = hi < a.ntile ? hi : hi - 1;
     load_a(0, tile * TT);
     if (tile > lo) load_a(1, (tile - 1) * TT);
-    load_dxd(tile * TT);
-    if (tile != hi) load_u(tile * TT);
+    load_dxd(tile * TT, true);
+    load_u(tile * TT, tile != hi);
     __syncthreads();
+#if defined(RGLRU_TRACE) && defined(RGLRU_TRACE_DGRAD)
+    unsigned long long tr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#endif
     for (int it = 0; tile >= lo; --tile, ++it) {
       const int buf = it & 1, t0 = tile * TT;
       const bool halo = tile == hi;
+      RGLRU_TRD(0);
 
       f32x16 acc0, acc1;
 #pragma unroll
@@ -708,6 +728,7 @@ bwd_dgrad_kernel(DgradArgs a) {
           a1 = n1;
         }
       }
+      RGLRU_TRD(1);
       float dx[19];
 #pragma unroll
       for (int r = 0; r < 16; ++r) dx[r] = dxd[r] + (acc0[r] + acc1[r]);
@@ -719,12 +740,13 @@ bwd_dgrad_kernel(DgradArgs a) {
       dx[18] = hf ? nx2 : s2v;
       nx0 = s0v; nx1 = s1v; nx2 = s2v;
       if (!halo) park_u(buf);
+      RGLRU_TRD(2);
       __syncthreads();
+      RGLRU_TRD(3);
       if (tile - 2 >= lo) load_a(buf, t0 - 2 * TT);
-      if (tile > lo) {
-        load_dxd(t0 - TT);
-        load_u(t0 - TT);
-      }
+      load_dxd(t0 - TT, tile > lo);   // (nothing left to fetch after the last tile: out of range, zeros)
+      load_u(t0 - TT, tile > lo);
+      RGLRU_TRD(4);
       if (!halo) {
         // Conv1D adjoint towards the input; the wave's [32 steps][32 channels] results leave
         // through its staging tile as 16-byte stores
@@ -756,6 +778,8 @@ bwd_dgrad_kernel(DgradArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) sb += dx[r];
       }
+      RGLRU_TRD(5);
+      RGLRU_TRD_FLUSH((int)blockIdx.x, wv, it);
     }
   }
   // partial sums of this workgroup
