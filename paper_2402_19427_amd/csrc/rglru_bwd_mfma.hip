@@ -430,7 +430,6 @@ bwd_gates_kernel(BwdArgs a) {
         s_ba += dpv[e];
         s_bx += dqv[e];
         erev = ok ? av * delta : erev;
-        __builtin_amdgcn_sched_barrier(0);  // one element at a time: registers are scarce here
       }
       // dp, dq (bf16): one 64-byte piece of a row per lane half and step
       {
