@@ -112,10 +112,10 @@ fwd_mfma_kernel(FwdArgs a) {
   const int d = g * BS + ch;
 
   // ---- gate weights of this wave's 32 output channels, resident in registers
-  // (when the sequence is sliced in time the kernel needs more registers for the carry
-  // exchange; the last K-steps of W_x are then re-read from L2 every tile - a far better spill
-  // space than scratch memory)
-  constexpr int NRES = GMAX == 1 ? 16 : (GMAX == 4 ? 8 : 4);
+  // (the late waves keep their accumulators across the barrier, and a sequence sliced in time
+  // needs registers for the carry exchange as well: the last K-steps of W_x are re-read from L2
+  // every tile - a far better spill space than scratch memory)
+  constexpr int NRES = GMAX == 1 ? 13 : (GMAX == 4 ? 8 : 4);
   constexpr int PF = 2;   // streamed fragments in flight (deeper rings measured no better)
   bf16x8 wa[16], wx[NRES];
   const bf16x8 *pxs = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
@@ -405,8 +405,7 @@ fwd_mfma_kernel(FwdArgs a) {
   // the pointwise work of the same tile, waves 4-7 do the pointwise work of their previous tile
   // first and multiply afterwards, keeping the accumulators across the barrier. Matrix and
   // vector phases of the pair then overlap instead of colliding.
-  // (without time slices every weight is resident and the plain order is the faster one)
-  const bool late = GMAX > 1 && wv >= NWAVE / 2;
+    const bool late = wv >= NWAVE / 2;
 
   int tile = w;
   if (tile < a.ntile) load_rows(tile * TT);
@@ -424,12 +423,11 @@ fwd_mfma_kernel(FwdArgs a) {
       const int next = tile + G;
       RGLRU_TR(0);
       if (!LATE) {
-        // rows of the next tile: where W_x fragments are streamed, after them (loads return in
-        // order, and these are trips to HBM); they land during the pointwise work
-        if (NRES == 16 && next < a.ntile) load_rows(next * TT);
+        // rows of the next tile: after the streamed W_x fragments (loads return in order, and
+        // these are trips to HBM); they land during the pointwise work
         gemm(buf);
         RGLRU_TR(1);
-        if (NRES < 16 && next < a.ntile) load_rows(next * TT);
+        if (next < a.ntile) load_rows(next * TT);
         pointwise(tile);
       } else {
         RGLRU_TR(1);
