@@ -483,34 +483,132 @@ fwd_mfma_kernel(FwdArgs a) {
 // One decode step (Section 5; states of Appendix F) for a tile of 32 sequences and one gate
 // block: the rows of the MFMA tile are sequences instead of time steps. The ring slot of the
 // new token is the slot of the lag-3 input, which the same thread has just read.
-constexpr int DEC_LDS = 2 * XT_ELEMS * 2 + 64 * 32;   // x tile (high, low) + selection operands
+// LDS of the decode kernel: x tile (high, low) | selection operands | per wave: two buffers
+// (W_a, W_x) in which a quarter (4 K-steps) of the wave's 32 weight rows is turned into MFMA
+// fragment order, and one staging tile through which h (in, then out) and y move between 16-byte-per-lane
+// global accesses and the accumulator layout
+constexpr int DEC_WROW = 128 + 16;               // row stride: conflict-free 16-byte reads down a column
+constexpr int DEC_WPH = 32 * DEC_WROW;           // 32 rows x (4 K-steps of weights | 32 fp32 of h)
+constexpr int DEC_OFF_W = 2 * XT_ELEMS * 2 + 64 * 32;
+constexpr int DEC_OFF_H = DEC_OFF_W + NWAVE * 2 * DEC_WPH;
+constexpr int DEC_LDS = DEC_OFF_H + NWAVE * DEC_WPH;
+constexpr int DEC_YROW = 64 + 16;                // y staging rows (32 bf16), in weight buffer 0
 
 struct DecArgs {
   Problem p;   // u = u_t [B][D], hT = h [B][D] (in place), state_out = ring (in place), y = y_t
 };
 
+// One decode step (eqs. (1)-(4) at T = 1 on top of the Conv1D ring): a workgroup takes 32
+// sequences of one gate block. The step is latency-bound, so the kernel is built around the
+// memory pipeline: every access is 16 bytes per lane (a CU issues about one vector-memory
+// instruction per 8 cycles whatever its width, and moves 64 bytes per cycle), loads are
+// requested as early as registers allow, and nothing is loaded under a branch (that would make the compiler drain all
+// outstanding loads on the spot) - rows past the batch get an out-of-range buffer offset
+// instead: they read as zero and their stores are dropped.
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 decode_mfma_kernel(DecArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned short *xs = (unsigned short *)smem;                       // [high, low][32][XS]
   bf16x8 *sel_lds = (bf16x8 *)(smem + 2 * XT_ELEMS * 2);
+  using u32x4 = unsigned __attribute__((ext_vector_type(4)));
   const Problem &p = a.p;
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, j = lane & 31;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = blockIdx.x, b0 = blockIdx.y * TT;
   const int D = p.D, B = p.B;
   const int ch = wv * 32 + j, d = g * BS + ch;
+#ifdef RGLRU_TRACE
+  unsigned long long tr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#endif
+  RGLRU_TR(0);
 
-  bf16x8 wa[16], wx[16];
-  {
-    const bf16x8 *pa = (const bf16x8 *)((const unsigned short *)p.W_a + ((size_t)g * BS + ch) * BS + hf * 8);
-    const bf16x8 *px = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
+  constexpr unsigned OOB = 0x80000000u;
+  const unsigned row2 = (unsigned)D * 2;
+  const __amdgpu_buffer_rsrc_t u_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_ptr(p.u), 0, (unsigned)B * row2, 0x00020000);
+  const __amdgpu_buffer_rsrc_t ring_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_ptr(p.state_out), 0, 3u * (unsigned)B * row2, 0x00020000);
+  const __amdgpu_buffer_rsrc_t h_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_ptr(p.hT), 0, 2u * (unsigned)B * row2, 0x00020000);
+  const __amdgpu_buffer_rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_ptr(p.y), 0, (unsigned)B * row2, 0x00020000);
+
+  // ---- Conv1D assignment: 8 channels (16 bytes) of rows (sequences) lr and lr + 16 of the tile
+  const int lc = tid & 31, lr = tid >> 5, dc = g * BS + 8 * lc;
+  // per-channel vectors first (loads return in order, and these are needed first)
+  f32x4 cw[4][2], cb[2];
 #pragma unroll
-    for (int ks = 0; ks < 16; ++ks) {
-      wa[ks] = pa[ks * 2];
-      wx[ks] = px[ks * 2];
-    }
+  for (int k = 0; k < 4; ++k) {
+    cw[k][0] = *(const f32x4 *)(p.conv_w + (size_t)k * D + dc);
+    cw[k][1] = *(const f32x4 *)(p.conv_w + (size_t)k * D + dc + 4);
   }
+  {
+    const float *cbp = (p.conv_b ? p.conv_b : p.conv_w) + dc;
+    cb[0] = *(const f32x4 *)cbp;
+    cb[1] = *(const f32x4 *)(cbp + 4);
+  }
+  const float cb_on = p.conv_b ? 1.f : 0.f;
+  const float bias_p = p.b_a[d] * LOG2E, bias_q = p.b_x[d] * LOG2E, lam = p.Lambda[d];
+
+  const int s1 = ring_slot(p.pos0 - 1), s2 = ring_slot(p.pos0 - 2), s3 = ring_slot(p.pos0 - 3);
+  u32x4 ru[2][4];
+  unsigned ring_vo[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int b = b0 + lr + 16 * i;
+    const bool ok = b < B;
+    const unsigned uvo = ok ? (unsigned)b * row2 + (unsigned)dc * 2 : OOB;
+    const unsigned rvo = ok ? (unsigned)(b * 3) * row2 + (unsigned)dc * 2 : OOB;
+    ring_vo[i] = rvo;
+    ru[i][0] = __builtin_amdgcn_raw_buffer_load_b128(u_rsrc, uvo, 0, 0);
+    ru[i][1] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, rvo, (unsigned)s1 * row2, 0);
+    ru[i][2] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, rvo, (unsigned)s2 * row2, 0);
+    ru[i][3] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, rvo, (unsigned)s3 * row2, 0);
+  }
+
+  // ---- gate weights of this wave's 32 output channels. A fragment read straight from the
+  // row-major matrix touches 64 cache lines per instruction; instead the wave reads its rows
+  // (16 KB contiguous per gate) in four phases of four K-steps of both gates, whole 128-byte
+  // lines per 8 lanes, and turns each phase into fragment order through its own LDS buffers
+  // (one per gate; LDS serves a wave's accesses in order, so a phase may be written while the
+  // reads of the previous one are still queued). One phase is requested here, the next once
+  // the Conv1D inputs are in (more would only delay those, queued behind).
+  const unsigned char *wrow_a = (const unsigned char *)p.W_a + ((size_t)g * BS + wv * 32) * BS * 2;
+  const unsigned char *wrow_x = (const unsigned char *)p.W_x + ((size_t)g * BS + wv * 32) * BS * 2;
+  const unsigned w_lane = (unsigned)(lane >> 3) * (BS * 2) + (unsigned)(lane & 7) * 16;
+  unsigned char *wl = smem + DEC_OFF_W + wv * 2 * DEC_WPH;
+  const unsigned wl_wr = (unsigned)(lane >> 3) * DEC_WROW + (unsigned)(lane & 7) * 16;
+  const unsigned wl_rd = (unsigned)j * DEC_WROW + (unsigned)hf * 16;
+  u32x4 stg[2][8];
+  auto load_phase = [&](int ph, u32x4 (&dst)[8]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      dst[i] = *(const u32x4 *)(wrow_a + ph * 128 + w_lane + i * 8 * BS * 2);
+      dst[4 + i] = *(const u32x4 *)(wrow_x + ph * 128 + w_lane + i * 8 * BS * 2);
+    }
+  };
+  auto write_phase = [&](const u32x4 (&src)[8]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      *(u32x4 *)(wl + i * 8 * DEC_WROW + wl_wr) = src[i];
+      *(u32x4 *)(wl + DEC_WPH + i * 8 * DEC_WROW + wl_wr) = src[4 + i];
+    }
+  };
+  load_phase(0, stg[0]);
+
+  // ---- recurrent state of this wave's 32 x 32 tile: lane l takes 16 bytes of rows l/8 + 8i
+  unsigned char *hl = smem + DEC_OFF_H + wv * DEC_WPH;
+  const unsigned hl_wide = (unsigned)(lane >> 3) * DEC_WROW + (unsigned)(lane & 7) * 16;
+  unsigned h_vo[4];
+  u32x4 hin[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int b = b0 + (lane >> 3) + 8 * i;
+    h_vo[i] = b < B ? ((unsigned)b * (unsigned)D + (unsigned)(g * BS + wv * 32 + (lane & 7) * 4)) * 4 : OOB;
+    hin[i] = __builtin_amdgcn_raw_buffer_load_b128(h_rsrc, h_vo[i], 0, 0);
+  }
+  RGLRU_TR(1);
+
   if (tid < 64) {
     bf16x8 sel0, sel1;
 #pragma unroll
@@ -521,49 +619,41 @@ decode_mfma_kernel(DecArgs a) {
     sel_lds[lane] = sel0;
     sel_lds[64 + lane] = sel1;
   }
-
-  // ---- Conv1D over the ring for rows (sequences) 8*rg .. 8*rg+7, channel pair c2
-  {
-    const int c2 = tid & 127, rg = tid >> 7, dc = g * BS + 2 * c2;
-    float cw[4][2], cb[2];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      cw[k][0] = p.conv_w[(size_t)k * D + dc] * LOG2E;
-      cw[k][1] = p.conv_w[(size_t)k * D + dc + 1] * LOG2E;
-    }
-    cb[0] = p.conv_b ? p.conv_b[dc] * LOG2E : 0.f;
-    cb[1] = p.conv_b ? p.conv_b[dc + 1] * LOG2E : 0.f;
-    const int s1 = ring_slot(p.pos0 - 1), s2 = ring_slot(p.pos0 - 2), s3 = ring_slot(p.pos0 - 3);
-    unsigned short *ring = (unsigned short *)p.state_out;
-#pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      const int b = b0 + 8 * rg + r;
-      unsigned hi_pk = 0, lo_pk = 0;
-      if (b < B) {
-        const unsigned u0 = *(const unsigned *)((const unsigned short *)p.u + (size_t)b * D + dc);
-        unsigned *st = (unsigned *)(ring + (size_t)b * 3 * D + dc);
-        const unsigned u1 = st[(size_t)s1 * (D / 2)], u2 = st[(size_t)s2 * (D / 2)], u3 = st[(size_t)s3 * (D / 2)];
-        float x0 = cb[0], x1 = cb[1];
-        x0 = fmaf(cw[0][0], bf_lo(u0), x0); x1 = fmaf(cw[0][1], bf_hi(u0), x1);
-        x0 = fmaf(cw[1][0], bf_lo(u1), x0); x1 = fmaf(cw[1][1], bf_hi(u1), x1);
-        x0 = fmaf(cw[2][0], bf_lo(u2), x0); x1 = fmaf(cw[2][1], bf_hi(u2), x1);
-        x0 = fmaf(cw[3][0], bf_lo(u3), x0); x1 = fmaf(cw[3][1], bf_hi(u3), x1);
-        split_bf16(x0, x1, hi_pk, lo_pk);
-        st[(size_t)s3 * (D / 2)] = u0;  // slot pos mod 3 == slot (pos-3) mod 3
-      }
-      *(unsigned *)(xs + (8 * rg + r) * XS + 2 * c2) = hi_pk;
-      *(unsigned *)(xs + XT_ELEMS + (8 * rg + r) * XS + 2 * c2) = lo_pk;
-    }
-  }
-  __syncthreads();
-
-  const float bias_p = p.b_a[d] * LOG2E, bias_q = p.b_x[d] * LOG2E;
   float kd;
   {
-    const float z = -p.Lambda[d];
+    const float z = -lam;
     const float sp = z > 0.f ? z + log1pf(expf(-z)) : log1pf(expf(z));
     kd = -p.c * sp * LOG2E;
   }
+
+  // ---- Conv1D over the ring; the new token replaces the oldest slot
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    u32x4 hi4, lo4;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {   // channels 2e, 2e+1 of the 8
+      const int v = e >> 1, c0 = (2 * e) & 3;
+      const unsigned u0 = ru[i][0][e], u1 = ru[i][1][e], u2 = ru[i][2][e], u3 = ru[i][3][e];
+      float x0 = cb[v][c0] * cb_on, x1 = cb[v][c0 + 1] * cb_on;
+      x0 = fmaf(cw[0][v][c0], bf_lo(u0), x0); x1 = fmaf(cw[0][v][c0 + 1], bf_hi(u0), x1);
+      x0 = fmaf(cw[1][v][c0], bf_lo(u1), x0); x1 = fmaf(cw[1][v][c0 + 1], bf_hi(u1), x1);
+      x0 = fmaf(cw[2][v][c0], bf_lo(u2), x0); x1 = fmaf(cw[2][v][c0 + 1], bf_hi(u2), x1);
+      x0 = fmaf(cw[3][v][c0], bf_lo(u3), x0); x1 = fmaf(cw[3][v][c0 + 1], bf_hi(u3), x1);
+      unsigned hi_pk, lo_pk;
+      split_bf16(x0 * LOG2E, x1 * LOG2E, hi_pk, lo_pk);   // rows past the batch: all inputs read as zero
+      hi4[e] = hi_pk;
+      lo4[e] = lo_pk;
+    }
+    // slot pos mod 3 == slot (pos-3) mod 3
+    __builtin_amdgcn_raw_buffer_store_b128(ru[i][0], ring_rsrc, ring_vo[i], (unsigned)s3 * row2, 0);
+    *(u32x4 *)(xs + (lr + 16 * i) * XS + 8 * lc) = hi4;
+    *(u32x4 *)(xs + XT_ELEMS + (lr + 16 * i) * XS + 8 * lc) = lo4;
+  }
+  load_phase(1, stg[1]);
+  RGLRU_TR(2);
+  __syncthreads();
+  RGLRU_TR(3);
+
   const int arow = ((j >> 2) & 1) * 16 + (j >> 3) * 4 + (j & 3);
   const unsigned short *ap = xs + arow * XS + hf * 8;
   f32x16 accp, accq, accx;
@@ -573,32 +663,76 @@ decode_mfma_kernel(DecArgs a) {
     accq[r] = bias_q;
     accx[r] = 0.f;
   }
+  RGLRU_TR(4);
+  write_phase(stg[0]);
 #pragma unroll
-  for (int ks = 0; ks < 16; ++ks) {
-    const bf16x8 av = *(const bf16x8 *)(ap + ks * 16);
-    accp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, wa[ks], accp, 0, 0, 0);
-    accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, wx[ks], accq, 0, 0, 0);
+  for (int ph = 0; ph < 4; ++ph) {
+    if (ph + 2 < 4) load_phase(ph + 2, stg[ph & 1]);
+    // the fragments come from other lanes of this wave
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    bf16x8 av[4], fa[4], fx[4];
+#pragma unroll
+    for (int k2 = 0; k2 < 4; ++k2) {
+      av[k2] = *(const bf16x8 *)(ap + (ph * 4 + k2) * 16);
+      fa[k2] = *(const bf16x8 *)(wl + wl_rd + k2 * 32);
+      fx[k2] = *(const bf16x8 *)(wl + DEC_WPH + wl_rd + k2 * 32);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (ph + 1 < 4) write_phase(stg[(ph + 1) & 1]);
+#pragma unroll
+    for (int k2 = 0; k2 < 4; ++k2) {   // two independent accumulation chains
+      accp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[k2], fa[k2], accp, 0, 0, 0);
+      accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[k2], fx[k2], accq, 0, 0, 0);
+    }
   }
+  RGLRU_TR(5);
   accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ap + (2 * wv) * 16), sel_lds[lane], accx, 0, 0, 0);
   accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ap + (2 * wv + 1) * 16), sel_lds[64 + lane], accx, 0, 0, 0);
   accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ap + XT_ELEMS + (2 * wv) * 16), sel_lds[lane], accx, 0, 0, 0);
   accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ap + XT_ELEMS + (2 * wv + 1) * 16), sel_lds[64 + lane], accx, 0, 0, 0);
+  RGLRU_TR(6);
 
-  // ---- eq. (4) for the 16 sequences of this lane's run
-  float *h = p.hT;
-  unsigned short *y = (unsigned short *)p.y;
+  // ---- h into accumulator layout: lane (j, hf) owns channel j of rows 16 hf .. 16 hf + 15
+#pragma unroll
+  for (int i = 0; i < 4; ++i) *(u32x4 *)(hl + i * 8 * DEC_WROW + hl_wide) = hin[i];
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  float rh[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) rh[r] = *(const float *)(hl + (hf * 16 + r) * DEC_WROW + j * 4);
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+  // ---- eq. (4) for the 16 sequences of this lane's run; results back through the staging tiles
+  unsigned char *yl = wl;   // weight buffer 0 of this wave is free again
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    const int b = b0 + hf * 16 + r;
-    if (b < B) {
-      const size_t o = (size_t)b * D + d;
-      float av, bv;
-      gate_fast(accp[r], accq[r], accx[r], kd, av, bv);
-      const float hn = fmaf(av, h[o], bv);
-      h[o] = hn;
-      y[o] = (unsigned short)(pack_bf16(hn, 0.f) & 0xffff);
-    }
+    float av_, bv;
+    gate_fast(accp[r], accq[r], accx[r], kd, av_, bv);
+    const float hn = fmaf(av_, rh[r], bv);
+    *(float *)(hl + (hf * 16 + r) * DEC_WROW + j * 4) = hn;
+    *(unsigned short *)(yl + (hf * 16 + r) * DEC_YROW + j * 2) = (unsigned short)(pack_bf16(hn, 0.f) & 0xffff);
   }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    __builtin_amdgcn_raw_buffer_store_b128(*(const u32x4 *)(hl + i * 8 * DEC_WROW + hl_wide), h_rsrc, h_vo[i], 0, 0);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {   // lane l: 16 bytes of rows l/4 + 16 i
+    const int row = (lane >> 2) + 16 * i, b = b0 + row;
+    const unsigned vo = b < B ? ((unsigned)b * (unsigned)D + (unsigned)(g * BS + wv * 32 + (lane & 3) * 8)) * 2 : OOB;
+    __builtin_amdgcn_raw_buffer_store_b128(*(const u32x4 *)(yl + row * DEC_YROW + (lane & 3) * 16), y_rsrc, vo, 0, 0);
+  }
+  RGLRU_TR(7);
+  RGLRU_TR_FLUSH((int)(blockIdx.y * gridDim.x + blockIdx.x), wv, 0);
 }
 
 }  // namespace
@@ -696,8 +830,10 @@ hipError_t launch_forward_mfma(const Problem &p, hipStream_t s) {
 }
 
 bool decode_mfma_supported(const Problem &p, bool bf) {
-  return bf && p.bs == BS && ((uintptr_t)p.W_a % 16 == 0) && ((uintptr_t)p.W_x % 16 == 0) &&
-         ((uintptr_t)p.u % 4 == 0) && ((uintptr_t)p.state_out % 4 == 0);
+  // 16-byte accesses throughout; 32-bit byte offsets into the ring
+  const uintptr_t all = (uintptr_t)p.W_a | (uintptr_t)p.W_x | (uintptr_t)p.u | (uintptr_t)p.state_out |
+                        (uintptr_t)p.hT | (uintptr_t)p.y | (uintptr_t)p.conv_w | (uintptr_t)p.conv_b;
+  return bf && p.bs == BS && all % 16 == 0 && (size_t)(p.B + TT) * 3 * p.D * 2 < ((size_t)1 << 31);
 }
 
 hipError_t launch_decode_mfma(const Problem &p, hipStream_t s) {

@@ -1,0 +1,216 @@
+"""Per-workload timing report of the Conv1D -> RG-LRU path on one MI355X.
+
+    python -m paper_2402_19427_amd.workloads [--configs C0,C1,C2,C3,C4] [--json]
+
+For each of the five synthetic workloads it times the calls that workload is about (forward;
+forward and backward for the training shape; the single-token decode step for the decode shape,
+launch by launch and as one HIP graph of 1000 steps) with HIP events on the stream the library
+launches on, and prints median / minimum time, tokens/s, the algorithmic bytes of the call
+divided by the time (GB/s and fraction of the 8 TB/s HBM peak) and the gate-product FLOP rate
+against the dense bf16 MFMA peak. Small workloads rotate several buffer sets so that the
+footprint of consecutive iterations exceeds the 256 MB last-level cache ("cold"); the decode
+step is also timed on one buffer set ("hot"). Inputs are seeded and synthetic.
+"""
+import argparse
+import json
+import sys
+
+import numpy as np
+import torch
+
+import rglru_inputs as gen
+from . import binding as R
+from . import runner as rn
+
+HBM_PEAK = 8.0e12
+MFMA_PEAK = 2.5e15
+LLC_BYTES = 256 << 20
+
+
+def alg_bytes(kind, B, T, D, nb, act_b):
+    """Bytes the method itself must move per call: inputs read once, outputs written once."""
+    bs = D // nb
+    N = B * T * D
+    w = 2 * nb * bs * bs * (2 if act_b == 2 else 4)
+    vec = 8 * D * 4
+    if kind == "forward":      # u in, y out, weights, h_T and conv state out
+        return 2 * act_b * N + w + vec + (4 + 3 * act_b) * B * D
+    if kind == "backward":     # u, y, dy in; du out; dW out (fp32)
+        return 4 * act_b * N + w + vec + 2 * nb * bs * bs * 4
+    if kind == "decode":       # u_t, 3 ring slots in + 1 out, h in + out, y_t, weights
+        return (act_b + 3 * act_b + act_b + 8 + act_b) * B * D + w + vec
+    raise ValueError(kind)
+
+
+def gate_flops(kind, B, T, D, nb):
+    bs = D // nb
+    N = B * T * D
+    return {"forward": 4, "decode": 4, "backward": 12}[kind] * bs * N
+
+
+def time_calls(fn, nsets, iters, warmup):
+    """Times fn(set_index) per call with events on the current stream; returns ms per call."""
+    for i in range(warmup):
+        fn(i % nsets)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(iters)]
+    for i in range(iters):
+        ev[i][0].record()
+        fn(i % nsets)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    return np.array([a.elapsed_time(b) for a, b in ev])
+
+
+def row(name, phase, note, ms, tokens, nbytes, flops):
+    med, mn = float(np.median(ms)), float(ms.min())
+    return {"workload": name, "call": phase, "note": note, "ms_median": med, "ms_min": mn,
+            "tokens_per_s": tokens / (med * 1e-3), "alg_bytes": nbytes,
+            "alg_GBs": nbytes / (med * 1e-3) / 1e9, "hbm_frac": nbytes / (med * 1e-3) / HBM_PEAK,
+            "mfma_frac": flops / (med * 1e-3) / MFMA_PEAK}
+
+
+def run_sequence_workload(w, dev, out):
+    B, T, D, nb = w.B, w.T, w.D, w.nb
+    act_b = 2 if w.act == "bf16" else 4
+    inp = gen.make_inputs(1, 8, D, nb, act=w.act, seed=w.seed)       # parameters only
+    dp = rn.DeviceProblem(inp, B, T, D, nb, w.act, device=dev)
+    sh = dp.shape()
+    per_set = 2 * act_b * B * T * D
+    nsets = int(min(8, max(1, -(-LLC_BYTES * 5 // 4 // per_set))))
+    iters = 100 if B * T * D < (1 << 27) else 30
+    gtor = torch.Generator(device=dev)
+    gtor.manual_seed(w.seed)
+    us = [torch.randn(B, T, D, device=dev, generator=gtor).to(dp.tdtype) for _ in range(nsets)]
+    h0 = torch.randn(B, D, device=dev, generator=gtor) if w.h0 else None
+    ys = [dp.empty_act(B, T, D) for _ in range(nsets)]
+    hT = dp.empty_f32(B, D)
+    st = dp.empty_act(B, 3, D)
+    ws_f, n_f = dp.workspace(sh, R.OP_FORWARD)
+    sp = torch.cuda.current_stream().cuda_stream
+
+    def fwd(i):
+        R.rglru_forward(sh, dp.params, us[i], h0, None, 0, ys[i], hT, st, ws_f, n_f, sp)
+
+    note = "%d buffer set%s" % (nsets, "s" if nsets > 1 else "")
+    ms = time_calls(fwd, nsets, iters, 10)
+    out.append(row(w.name, "forward", note, ms, B * T, alg_bytes("forward", B, T, D, nb, act_b),
+                   gate_flops("forward", B, T, D, nb)))
+    if w.kind != "train" and w.name != "C1":
+        return
+    for i in range(nsets):
+        fwd(i)
+    dys = [torch.randn(B, T, D, device=dev, generator=gtor).to(dp.tdtype) for _ in range(nsets)]
+    du = dp.empty_act(B, T, D)
+    dh0 = dp.empty_f32(B, D)
+    g = dp.alloc_grads()
+    pg = R.make_param_grads(g["dW_a"], g["dW_x"], g["db_a"], g["db_x"], g["dLambda"],
+                            g["dconv_w"], g["dconv_b"])
+    ws_b, n_b = dp.workspace(sh, R.OP_BACKWARD)
+
+    def bwd(i):
+        R.rglru_backward(sh, dp.params, us[i], h0, None, 0, ys[i], dys[i], None, du, dh0, pg,
+                         ws_b, n_b, sp)
+
+    ms = time_calls(bwd, nsets, iters, 5)
+    out.append(row(w.name, "backward", note, ms, B * T, alg_bytes("backward", B, T, D, nb, act_b),
+                   gate_flops("backward", B, T, D, nb)))
+
+
+def run_decode_workload(w, dev, out, steps=1000):
+    B, D, nb = w.B, w.D, w.nb
+    act_b = 2 if w.act == "bf16" else 4
+    inp = gen.make_inputs(1, 8, D, nb, act=w.act, seed=w.seed)
+    dp = rn.DeviceProblem(inp, B, 1, D, nb, w.act, device=dev)
+    sh = dp.shape(T=1)
+    nbytes = alg_bytes("decode", B, 1, D, nb, act_b)
+    flops = gate_flops("decode", B, 1, D, nb)
+    per_set = (6 * act_b + 8) * B * D
+    ncold = int(-(-LLC_BYTES * 5 // 4 // per_set))
+    gtor = torch.Generator(device=dev)
+    gtor.manual_seed(w.seed)
+
+    def make_set():
+        return dict(u=torch.randn(B, D, device=dev, generator=gtor).to(dp.tdtype),
+                    h=torch.randn(B, D, device=dev, generator=gtor),
+                    st=torch.randn(B, 3, D, device=dev, generator=gtor).to(dp.tdtype),
+                    y=dp.empty_act(B, D))
+
+    sets = [make_set() for _ in range(ncold)]
+    sp = torch.cuda.current_stream().cuda_stream
+    pos = [3]
+
+    def step(i):
+        s = sets[i]
+        R.rglru_decode_step(sh, dp.params, s["u"], s["h"], s["st"], pos[0], s["y"], sp)
+        pos[0] += 1
+
+    for nsets, label in ((1, "hot: 1 buffer set"), (ncold, "cold: %d buffer sets" % ncold)):
+        ms = time_calls(step, nsets, steps, 20)
+        out.append(row(w.name, "decode, per launch", label, ms, B, nbytes, flops))
+        # the same 1000 steps back to back: launch overhead overlaps with execution
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(steps):
+            step(i % nsets)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = np.array([e0.elapsed_time(e1) / steps])
+        out.append(row(w.name, "decode, %d launches back to back" % steps, label, ms, B, nbytes, flops))
+        # ... and replayed as one HIP graph (the position is baked in at capture: timing only)
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            spg = torch.cuda.current_stream().cuda_stream    # the capturing stream
+            for i in range(steps):
+                s = sets[i % nsets]
+                R.rglru_decode_step(sh, dp.params, s["u"], s["h"], s["st"], 3 + i, s["y"], spg)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        reps = []
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            reps.append(e0.elapsed_time(e1) / steps)
+        out.append(row(w.name, "decode, one graph of %d steps" % steps, label, np.array(reps), B,
+                       nbytes, flops))
+        del graph
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--configs", default="C0,C1,C2,C3,C4")
+    ap.add_argument("--json", action="store_true", help="print one JSON object per row instead of the table")
+    args = ap.parse_args()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    out = []
+    for name in args.configs.split(","):
+        w = gen.CONFIGS[name]
+        n0 = len(out)
+        if w.kind == "decode":
+            run_decode_workload(w, dev, out)
+        else:
+            run_sequence_workload(w, dev, out)
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        for r in out[n0:]:
+            if args.json:
+                print(json.dumps(r), flush=True)
+            else:
+                print("%-3s %-38s %-22s median %9.2f us  min %9.2f us  %8.2f M tok/s  %7.1f GB/s "
+                      "= %5.1f%% of HBM peak  %5.1f%% of MFMA peak"
+                      % (r["workload"], r["call"], r["note"], r["ms_median"] * 1e3, r["ms_min"] * 1e3,
+                         r["tokens_per_s"] / 1e6, r["alg_GBs"], 100 * r["hbm_frac"],
+                         100 * r["mfma_frac"]), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -130,7 +130,7 @@ def test_conv1d_matches_oracle(B, T, D, act, full):
 
 
 @pytest.mark.parametrize("B,D,nb,act", [(5, 64, 2, "f32"), (19, 512, 2, "bf16"), (3, 320, 2, "bf16"),
-                                        (64, 1024, 4, "bf16")])
+                                        (64, 1024, 4, "bf16"), (33, 256, 1, "bf16")])
 def test_decode_steps_match_oracle_and_wrap_the_ring(B, D, nb, act):
     rn = runner()
     nsteps = 7
