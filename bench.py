@@ -85,7 +85,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C1")
+    ap.add_argument("--workload", default="C1", choices=["C1", "C2", "C4"],
+                    help="bf16 sequence workload to run the whole path on (default: C1, the one the "
+                         "metric is quoted on); per-call timings of all five workloads, C0 and the "
+                         "C3 decode loop included: python -m paper_2402_19427_amd.workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy, the reference that scales the "
