@@ -1021,27 +1021,33 @@ bwd_wgrad_kernel(WgradArgs a) {
       fa[m][1] = __builtin_bit_cast(bf16x8, hi4);
     }
 #pragma unroll
-    for (int n = 0; n < 4; ++n) {
+    for (int n = 0; n < 4; n += 2) {
       // x = high + low, both bf16; as in the dp / dq fragments, lane half hf holds steps
       // 16 hf .. 16 hf + 7 in the first K-step and the following 8 in the second
-      const bf16x8 fb0 = *(const bf16x8 *)(xh + n * 32 * TS), fb1 = *(const bf16x8 *)(xh + n * 32 * TS + 8);
-      const bf16x8 fl0 = *(const bf16x8 *)(xl + n * 32 * TS), fl1 = *(const bf16x8 *)(xl + n * 32 * TS + 8);
-      acc[0][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][0], fb0, acc[0][n], 0, 0, 0);
-      acc[1][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][0], fb0, acc[1][n], 0, 0, 0);
-      acc[0][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][1], fb1, acc[0][n], 0, 0, 0);
-      acc[1][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][1], fb1, acc[1][n], 0, 0, 0);
-      acc[0][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][0], fl0, acc[0][n], 0, 0, 0);
-      acc[1][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][0], fl0, acc[1][n], 0, 0, 0);
-      acc[0][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][1], fl1, acc[0][n], 0, 0, 0);
-      acc[1][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][1], fl1, acc[1][n], 0, 0, 0);
+      bf16x8 fb[2][4];   // [column block][high K0, high K1, low K0, low K1]
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        fb[i][0] = *(const bf16x8 *)(xh + (n + i) * 32 * TS);
+        fb[i][1] = *(const bf16x8 *)(xh + (n + i) * 32 * TS + 8);
+        fb[i][2] = *(const bf16x8 *)(xl + (n + i) * 32 * TS);
+        fb[i][3] = *(const bf16x8 *)(xl + (n + i) * 32 * TS + 8);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {   // four independent accumulators per round: no product waits for its predecessor
+        acc[0][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][q & 1], fb[0][q], acc[0][n], 0, 0, 0);
+        acc[1][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][q & 1], fb[0][q], acc[1][n], 0, 0, 0);
+        acc[0][n + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][q & 1], fb[1][q], acc[0][n + 1], 0, 0, 0);
+        acc[1][n + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][q & 1], fb[1][q], acc[1][n + 1], 0, 0, 0);
+      }
     }
   };
 
-  // The two waves that share a SIMD work half a step apart: waves 0-3 multiply and then
-  // prepare the next tile, waves 4-7 prepare first and multiply afterwards (their inputs are
+  // The two waves that share a SIMD work half a step apart: waves 4-7 multiply and then
+  // prepare the next tile, waves 0-3 prepare first and multiply afterwards (their inputs are
   // requested one step earlier), so that matrix and vector phases of the pair overlap. Both
-  // orders read buffer `buf` and write the other one between the same two barriers.
-  const bool late = wv >= NWAVE / 2;
+  // orders read buffer `buf` and write the other one between the same two barriers. (The SIMD
+  // serves its older wave first; the late order is the longer chain, so waves 0-3 get it.)
+  const bool late = wv < NWAVE / 2;
   if (st_lo < st_hi) {
     load_tiles(st_lo);
     __syncthreads();   // the taps parked in LDS are visible

@@ -401,11 +401,12 @@ fwd_mfma_kernel(FwdArgs a) {
     }
   };
 
-  // The two waves that share a SIMD run half a step apart: waves 0-3 multiply first and then do
-  // the pointwise work of the same tile, waves 4-7 do the pointwise work of their previous tile
+  // The two waves that share a SIMD run half a step apart: waves 4-7 multiply first and then do
+  // the pointwise work of the same tile, waves 0-3 do the pointwise work of their previous tile
   // first and multiply afterwards, keeping the accumulators across the barrier. Matrix and
-  // vector phases of the pair then overlap instead of colliding.
-    const bool late = wv >= NWAVE / 2;
+  // vector phases of the pair then overlap instead of colliding. (The SIMD serves its older
+  // wave first; the late order is the longer chain, so waves 0-3 get it.)
+  const bool late = wv < NWAVE / 2;
 
   int tile = w;
   if (tile < a.ntile) load_rows(tile * TT);
