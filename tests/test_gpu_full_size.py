@@ -56,30 +56,43 @@ def test_c2_long_sequence_forward_full_size():
     run_forward_full("C2", [(0, 0), (0, 9)])
 
 
-def test_c4_forward_and_backward_full_size():
+def run_train_full(name, g, y_rows, decode=False):
+    """forward (+ one decode step continuing it) + backward at the workload's full size; every
+    sequence of gate block g goes through the oracle (parameter gradients sum over the batch)."""
     import paper_2402_19427_amd.runner as rn
-    w = gen.CONFIGS["C4"]
-    inp = gen.make_workload("C4")
-    dp = rn.DeviceProblem(inp, w.B, w.T, w.D, w.nb, w.act)
-    u = rn.to_device(inp["u"], w.act)
-    dy = rn.to_device(inp["dy"], w.act)
-    y, hT, _ = dp.forward(u, want_state=False)
+    w = gen.CONFIGS[name]
+    inp = gen.make_inputs(w.B, w.T + 1, w.D, w.nb, act=w.act, seed=w.seed, dy=True)
+    T = w.T
+    dp = rn.DeviceProblem(inp, w.B, T, w.D, w.nb, w.act)
+    u_all = rn.to_device(inp["u"], w.act)
+    u = u_all[:, :T].contiguous()
+    dy = rn.to_device(inp["dy"][:, :T], w.act)
+    y, hT, st = dp.forward(u)
+    y1_h = hT1_h = None
+    if decode:
+        hT1 = hT.clone()
+        y1_h = rn.to_host(dp.decode_step(u_all[:, T].contiguous(), hT1, st, T))
+        hT1_h = rn.to_host(hT1)
     out = dp.backward(u, y, dy)
     y_h, du_h, dh0_h = rn.to_host(y), rn.to_host(out["du"]), rn.to_host(out["dh0"])
     small = {k: rn.to_host(out[k]) for k in ("dW_a", "dW_x", "db_a", "db_x", "dLambda", "dconv_w",
                                              "dconv_b")}
-    del y, u, dy, out
-    g = 5   # every sequence of one gate block: parameter gradients sum over the batch
+    del y, u, dy, out, u_all
     sl, par = block_params(inp, g, w.bs)
     acc = None
     oracle.set_threads(1)
     for b in range(w.B):
-        ub = np.asarray(inp["u"][b:b + 1, :, sl], np.float64)
-        dyb = np.asarray(inp["dy"][b:b + 1, :, sl], np.float64)
+        ub = np.asarray(inp["u"][b:b + 1, :T, sl], np.float64)
+        dyb = np.asarray(inp["dy"][b:b + 1, :T, sl], np.float64)
         ref = oracle.backward(ub, *par, dyb)
-        if b in (0, 9):
-            y_ref, _, _ = oracle.forward(ub, *par)
+        if b in y_rows:
+            y_ref, hT_ref, st_ref = oracle.forward(ub, *par)
             assert gen.rel_err(y_h[b:b + 1, :, sl], y_ref) < TOL, b
+            if decode:
+                y1_ref = oracle.decode_step(np.asarray(inp["u"][b:b + 1, T, sl], np.float64), *par,
+                                            hT_ref, st_ref)
+                assert gen.rel_err(y1_h[b:b + 1, sl], y1_ref) < TOL, b
+                assert gen.rel_err(hT1_h[b:b + 1, sl], hT_ref) < TOL, b   # updated in place
         assert gen.rel_err(du_h[b:b + 1, :, sl], ref["du"]) < TOL, b
         assert gen.rel_err(dh0_h[b:b + 1, sl], ref["dh0"]) < TOL, b
         if acc is None:
@@ -93,6 +106,16 @@ def test_c4_forward_and_backward_full_size():
         assert gen.rel_err(small[k][sl], acc[k]) < TOL, k
     assert gen.rel_err(small["dconv_w"][:, sl], acc["dconv_w"]) < TOL
     assert np.isfinite(du_h).all() and all(np.isfinite(v).all() for v in small.values())
+
+
+def test_c4_forward_and_backward_full_size():
+    run_train_full("C4", 5, (0, 9))
+
+
+def test_c1_whole_step_as_benchmarked():
+    # the step bench.py times: forward, one decode step continuing it, backward (3 time slices
+    # per (sequence, block) at this size)
+    run_train_full("C1", 3, (0, 6), decode=True)
 
 
 def test_c3_batched_decode_full_size():
