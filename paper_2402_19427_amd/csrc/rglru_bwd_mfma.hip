@@ -10,7 +10,8 @@
 //        dp_t  = -c softplus(-Lambda) dla_t r_t (1 - r_t)
 //        dq_t  = delta_t m_t g_t (1 - i_t)
 //        dxd_t = delta_t m_t i_t                 (the part of dx that bypasses the gates)
-//     and writes dp, dq (bf16), dxd (fp32) plus per-channel sums for db_a, db_x, dLambda.
+//     and writes dp, dq (bf16), dxd (24 bits: sign, exponent, 15 mantissa bits; four steps of a
+//     channel packed in 12 bytes) plus per-channel sums for db_a, db_x, dLambda.
 //     Time slices of one sequence exchange tile aggregates (prod a, local eps) as tagged 8-byte
 //     records; a first sweep over the tile computes a_t and the aggregate, a second sweep the
 //     adjoints once the incoming eps is known.
@@ -27,6 +28,7 @@ using namespace mfma;
 namespace {
 
 constexpr float LN2 = 0.6931471805599453f;
+typedef unsigned u32x3 __attribute__((ext_vector_type(3)));
 constexpr int TS = TT + 8;                       // row stride (bf16) of the [channel][time] tiles
 constexpr int TR_BYTES = BS * TS * 2;            // one transposed tile
 // LDS of the gates kernel: x tile (high, low) | constants | dy^T | y^T | r_t of the tile |
@@ -75,7 +77,7 @@ struct BwdArgs {
   int swizzle;
   const unsigned short *wxf;              // W_x in fragment order (prep_kernel)
   unsigned short *dpo, *dqo;              // bf16 [B][T][D]: dp, dq
-  float *dxo;                             // f32 [B][T][D]: dxd (kept in fp32: du sums four taps of it
+  unsigned char *dxo;                     // dxd, 24 bits per value (bf16 would break du: it sums four taps of it
                                           // with cancellation)
   float *part;                            // [B*G][3][D]: sums for db_a, db_x, dLambda
 };
@@ -177,9 +179,11 @@ bwd_gates_kernel(BwdArgs a) {
   };
   const __amdgpu_buffer_rsrc_t u_rsrc = rsrc(p.u), y_rsrc = rsrc(p.y_in), dy_rsrc = rsrc(p.dy);
   const __amdgpu_buffer_rsrc_t dp_rsrc = rsrc(a.dpo), dq_rsrc = rsrc(a.dqo);
+  // dxd: [group of 4 steps][channel][12 bytes], four values of 24 bits (top three bytes of fp32)
+  const unsigned grp_bytes = (unsigned)D * 12, ngrp = (unsigned)(T + 3) / 4;
   const __amdgpu_buffer_rsrc_t dx_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      uniform_ptr(a.dxo + seq_off), 0, 2 * seq_bytes, 0x00020000);
-  const unsigned dx_voff = ((unsigned)d * 2 + (unsigned)hf * 16 * row_bytes) * 2;  // channel, lane half
+      uniform_ptr(a.dxo + (size_t)b * ngrp * grp_bytes), 0, ngrp * grp_bytes, 0x00020000);
+  const unsigned dx_voff = (unsigned)d * 12 + (unsigned)hf * 4 * grp_bytes;  // channel, lane half
   const unsigned c_voff = (unsigned)dc * 2;                                   // channel pair
   const unsigned o_voff = (unsigned)d * 2 + (unsigned)hf * 16 * row_bytes;    // channel, lane half
   const unsigned *st32 =
@@ -448,12 +452,17 @@ bwd_gates_kernel(BwdArgs a) {
           }
         }
       }
-      // dxd (fp32): one 128-byte piece of a row per lane half and step
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if (4 * q + e < nvalid)
-          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(dxv[e]), dx_rsrc, dx_voff,
-                                                2 * (so + (unsigned)(4 * q + e) * row_bytes), RGLRU_NT);
+      // dxd: the four steps as 24-bit values (zero past the end of the sequence), 12 bytes per
+      // lane, 384 contiguous bytes per lane half
+      if (4 * q < nvalid) {
+        const unsigned r0 = __float_as_uint(dxv[0]) + 0x80u, r1 = __float_as_uint(dxv[1]) + 0x80u;
+        const unsigned r2 = __float_as_uint(dxv[2]) + 0x80u, r3 = __float_as_uint(dxv[3]) + 0x80u;
+        u32x3 w;
+        w[0] = __builtin_amdgcn_perm(r1, r0, 0x05030201u);
+        w[1] = __builtin_amdgcn_perm(r2, r1, 0x06050302u);
+        w[2] = __builtin_amdgcn_perm(r3, r2, 0x07060503u);
+        __builtin_amdgcn_raw_buffer_store_b96(w, dx_rsrc, dx_voff, (unsigned)(t0 / 4 + q) * grp_bytes, RGLRU_NT);
+      }
     }
 
     RGLRU_TR(6);
@@ -504,7 +513,7 @@ struct DgradArgs {
   Problem p;
   int C, ntile;                            // contiguous time chunks per unit, tiles per sequence
   const unsigned short *dpo, *dqo;         // bf16 [B][T][D]
-  const float *dxo;                        // f32 [B][T][D]
+  const unsigned char *dxo;                // dxd [B][ceil(T/4)][D][12 bytes]
   const unsigned short *wta, *wtx;         // transposed gate weights [nb][in k][out j], bf16
   float *part;                             // [B*C][5][D]: dconv_w[0..3], dconv_b partial sums
 };
@@ -620,17 +629,29 @@ bwd_dgrad_kernel(DgradArgs a) {
       __builtin_amdgcn_raw_ptr_buffer_load_lds(dq_rsrc, (__attribute__((address_space(3))) void *)(dst + D_A_TILE / 2), 16, a_voff, so, 0, RGLRU_NT);
     }
   };
-  // dxd of this lane's run (channel d, 16 consecutive steps), fp32, zero past the sequence end
+  // dxd of this lane's run (channel d, 16 consecutive steps): four groups of four 24-bit
+  // values, 12 bytes each; groups past the end of the sequence are out of range and read as zero
+  const unsigned grp_bytes = (unsigned)D * 12, ngrp = (unsigned)(T + 3) / 4;
   const __amdgpu_buffer_rsrc_t dx_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      uniform_ptr(a.dxo + seq_off), 0, 2 * seq_bytes, 0x00020000);
-  const unsigned dx_voff = ((unsigned)d * 2 + (unsigned)hf * 16 * row_bytes) * 2;
-  float dxd[16];
+      uniform_ptr(a.dxo + (size_t)b * ngrp * grp_bytes), 0, ngrp * grp_bytes, 0x00020000);
+  const unsigned dx_voff = (unsigned)d * 12 + (unsigned)hf * 4 * grp_bytes;
+  u32x3 dxw[4];
   // (no branches around these loads, see load_u below; `ok` false pushes them all out of range)
   auto load_dxd = [&](int t0, bool ok) {
     const unsigned vo = ok ? dx_voff : 0x80000000u;
+    const unsigned so = ok ? (unsigned)(t0 / 4) * grp_bytes : 0u;
 #pragma unroll
-    for (int r = 0; r < 16; ++r)
-      dxd[r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(dx_rsrc, vo, 2 * (unsigned)(t0 + r) * row_bytes, RGLRU_NT));
+    for (int q = 0; q < 4; ++q)
+      dxw[q] = __builtin_amdgcn_raw_buffer_load_b96(dx_rsrc, vo, so + (unsigned)q * grp_bytes, RGLRU_NT);
+  };
+  auto dxd_at = [&](int r) __attribute__((always_inline)) {   // step r of the run, back in fp32
+    const u32x3 w = dxw[r >> 2];
+    const int e = r & 3;
+    const unsigned bits = e == 0 ? __builtin_amdgcn_perm(0u, w[0], 0x0201000cu)
+                        : e == 1 ? __builtin_amdgcn_perm(w[1], w[0], 0x0504030cu)
+                        : e == 2 ? __builtin_amdgcn_perm(w[2], w[1], 0x0403020cu)
+                                 : (w[2] & 0xffffff00u);
+    return __uint_as_float(bits);
   };
   // u rows t0-3 .. t0+31 (35 rows), 16 bytes (8 channels) per thread: rows lr, lr+16 and
   // (for lr < 3) lr+32
@@ -730,7 +751,7 @@ bwd_dgrad_kernel(DgradArgs a) {
       RGLRU_TRD(1);
       float dx[19];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dx[r] = dxd[r] + (acc0[r] + acc1[r]);
+      for (int r = 0; r < 16; ++r) dx[r] = dxd_at(r) + (acc0[r] + acc1[r]);
       // steps 16..18 of this lane's run: the other half's first three (lower lanes) or the
       // next tile's first three (upper lanes)
       const float s0v = __shfl_xor(dx[0], 32), s1v = __shfl_xor(dx[1], 32), s2v = __shfl_xor(dx[2], 32);
@@ -1172,7 +1193,7 @@ BwdPlan plan_backward(int B, int T, int D, int nb, int ncu) {
   size_t off = 0;
   q.off_dp = off; off += N2;
   q.off_dq = off; off += N2;
-  q.off_dx = off; off += 2 * N2;
+  q.off_dx = off; off += al256((size_t)B * ((T + 3) / 4) * D * 12);
   q.off_wta = off; off += wbytes;
   q.off_wtx = off; off += wbytes;
   q.off_wxf = off; off += wbytes;
@@ -1228,7 +1249,7 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   a.rec = (u64 *)(ws + q.off_rec + 256);
   a.dpo = (unsigned short *)(ws + q.off_dp);
   a.dqo = (unsigned short *)(ws + q.off_dq);
-  a.dxo = (float *)(ws + q.off_dx);
+  a.dxo = (unsigned char *)(ws + q.off_dx);
   a.part = (float *)(ws + q.off_partA);
   const int grid = q.units * q.G;
   a.swizzle = (q.G > 1 && grid % 8 == 0) ? 1 : 0;
