@@ -75,7 +75,7 @@ struct BwdArgs {
   u64 *rec;
   int *err;
   int swizzle;
-  const unsigned short *wxf;              // W_x in fragment order (prep_kernel)
+  const unsigned short *wxf;              // W_x in fragment order (bwd_prep_kernel)
   unsigned short *dpo, *dqo;              // bf16 [B][T][D]: dp, dq
   unsigned char *dxo;                     // dxd, 24 bits per value (bf16 would break du: it sums four taps of it
                                           // with cancellation)

@@ -68,20 +68,11 @@ __device__ __forceinline__ void gate_fast(float pp, float qq, float xx, float kd
   b = (m * il) * xx;
 }
 
-// Preparation pass of the sliced kernels: clears the record rings and copies W_x into fragment
-// order, [block][wave][K-step][lane][8], so that the K-steps a kernel cannot keep in registers
-// are re-read each tile as contiguous 1 KB pieces (in the row-major matrix one fragment touches
-// 64 different cache lines).
-__global__ void __launch_bounds__(256) prep_kernel(uint4 *zero, size_t n16, const uint4 *Wx,
-                                                   uint4 *wxf, int nfrag) {
+// Preparation pass of the sliced forward kernel: clears the record rings (a fill kernel rather
+// than a memset, so that a caller may capture the call in a HIP graph).
+__global__ void __launch_bounds__(256) prep_kernel(uint4 *zero, size_t n16) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n16) zero[i] = make_uint4(0, 0, 0, 0);
-  if (i < (size_t)nfrag) {
-    const int lane = (int)(i & 63), ks = (int)((i >> 6) & 15), wv = (int)((i >> 10) & 7), g = (int)(i >> 13);
-    const int hf = lane >> 5, j = lane & 31;
-    // 16-byte units: a row of the matrix is 32 of them
-    wxf[i] = Wx[((size_t)g * BS + wv * 32 + j) * (BS / 8) + ks * 2 + hf];
-  }
 }
 
 // GMAX = 1: one workgroup per (sequence, block); GMAX = 4 / 8: 2..4 / 5..8 time slices
@@ -753,13 +744,10 @@ int mfma::num_cu() {
   return g_num_cu;
 }
 
-hipError_t mfma::launch_prep(void *zero, size_t zero_bytes, const void *Wx, void *wxf, int nb,
-                             hipStream_t s) {
-  const size_t n16 = zero_bytes / 16, nfrag = (size_t)nb * BS * BS / 8;
-  const size_t n = n16 > nfrag ? n16 : nfrag;
+hipError_t mfma::launch_prep(void *zero, size_t zero_bytes, hipStream_t s) {
+  const size_t n16 = zero_bytes / 16;
   KernelTimer kt("prep_kernel", s);
-  hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (uint4 *)zero,
-                     n16, (const uint4 *)Wx, (uint4 *)wxf, (int)nfrag);
+  hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s, (uint4 *)zero, n16);
   return hipGetLastError();
 }
 
@@ -824,7 +812,7 @@ hipError_t launch_forward_mfma(const Problem &p, hipStream_t s) {
   }
   a.err = (int *)p.ws;
   a.rec = (u64 *)((char *)p.ws + 256);
-  hipError_t e = launch_prep(p.ws, 256 + (size_t)units * a.R * 2 * BS * sizeof(u64), nullptr, nullptr, 0, s);
+  hipError_t e = launch_prep(p.ws, 256 + (size_t)units * a.R * 2 * BS * sizeof(u64), s);
   if (e != hipSuccess) return e;
   return a.G <= 4 ? launch_t<4>(a, grid, FWD_LDS, s)
                   : launch_t<8>(a, grid, FWD_LDS, s);

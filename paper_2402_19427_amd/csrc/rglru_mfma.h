@@ -88,9 +88,8 @@ __device__ __forceinline__ void store_staged_tile(const unsigned short *ot, int 
 // host side (defined with the forward kernel)
 int num_cu();                                    // compute units of the current device
 int pick_slices(int units, int ntile, int ncu);  // time slices per (sequence, block)
-// clears zero_bytes (% 16 == 0) at `zero` and writes W_x [nb][256][256] bf16 in MFMA fragment
-// order to `wxf` (same size), in one launch
-hipError_t launch_prep(void *zero, size_t zero_bytes, const void *Wx, void *wxf, int nb, hipStream_t s);
+// clears zero_bytes (% 16 == 0) at `zero` with a fill kernel
+hipError_t launch_prep(void *zero, size_t zero_bytes, hipStream_t s);
 
 }  // namespace mfma
 }  // namespace rglru

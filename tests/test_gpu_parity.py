@@ -241,3 +241,48 @@ def test_results_are_deterministic_run_to_run():
     for o in outs[1:]:
         for a, b in zip(outs[0], o):
             np.testing.assert_array_equal(a, b)
+
+
+def test_whole_step_replays_as_a_hip_graph():
+    """forward + decode step + backward captured into one HIP graph (the library launches fill
+    kernels, never memsets, and allocates nothing): every replay, with eager work and
+    synchronisations in between, gives the bits of the eager run."""
+    import torch
+    import paper_2402_19427_amd as R
+    rn = runner()
+    B, T, D, nb, act = 8, 300, 2048, 8, "bf16"   # 64 units x 4 time slices: records cross workgroups
+    inp = gen.make_inputs(B, T + 1, D, nb, act=act, seed=21, dy=True)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    u_all = rn.to_device(inp["u"], act)
+    u, u_next = u_all[:, :T].contiguous(), u_all[:, T].contiguous()
+    dy = rn.to_device(inp["dy"][:, :T], act)
+    sh, sh1 = dp.shape(), dp.shape(T=1)
+    ws_f, n_f = dp.workspace(sh, R.OP_FORWARD)
+    ws_b, n_b = dp.workspace(sh, R.OP_BACKWARD)
+    y, hT, st = dp.empty_act(B, T, D), dp.empty_f32(B, D), dp.empty_act(B, 3, D)
+    y1, du, dh0 = dp.empty_act(B, D), dp.empty_act(B, T, D), dp.empty_f32(B, D)
+    g = dp.alloc_grads()
+    pg = R.make_param_grads(g["dW_a"], g["dW_x"], g["db_a"], g["db_x"], g["dLambda"],
+                            g["dconv_w"], g["dconv_b"])
+    outs = dict(y=y, hT=hT, st=st, y1=y1, du=du, dh0=dh0, **g)
+
+    def step(stream):
+        R.rglru_forward(sh, dp.params, u, None, None, 0, y, hT, st, ws_f, n_f, stream)
+        R.rglru_backward(sh, dp.params, u, None, None, 0, y, dy, None, du, dh0, pg, ws_b, n_b, stream)
+        R.rglru_decode_step(sh1, dp.params, u_next, hT, st, T, y1, stream)   # updates hT, st in place
+
+    step(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    eager = {k: v.clone() for k, v in outs.items()}
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(torch.cuda.current_stream().cuda_stream)   # the capturing stream
+    for rep in range(3):
+        for v in outs.values():
+            v.fill_(7.0)                                 # eager work between the replays
+        ws_f.fill_(rep + 1)                              # stale records must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, v in outs.items():
+            assert torch.equal(v, eager[k]), (rep, k)
