@@ -1178,7 +1178,7 @@ BwdPlan plan_backward(int B, int T, int D, int nb, int ncu) {
   BwdPlan q;
   q.units = B * nb;
   q.ntile = (T + TT - 1) / TT;
-  q.G = pick_slices(q.units, q.ntile, ncu);
+  q.G = pick_slices(q.units, q.ntile, ncu, 8);
   q.R = 8 * q.G;
   q.C = ncu / q.units;
   if (q.C < 1) q.C = 1;

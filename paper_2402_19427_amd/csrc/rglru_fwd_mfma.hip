@@ -75,7 +75,9 @@ __global__ void __launch_bounds__(256) prep_kernel(uint4 *zero, size_t n16) {
   if (i < n16) zero[i] = make_uint4(0, 0, 0, 0);
 }
 
-// GMAX = 1: one workgroup per (sequence, block); GMAX = 4 / 8: 2..4 / 5..8 time slices
+constexpr int FWD_MAX_SLICES = 16;
+
+// GMAX = 1: one workgroup per (sequence, block); GMAX = 4 / 8 / 16: 2..4 / 5..8 / 9..16 time slices
 template <int GMAX>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 fwd_mfma_kernel(FwdArgs a) {
@@ -106,9 +108,9 @@ fwd_mfma_kernel(FwdArgs a) {
   // (the late waves keep their accumulators across the barrier, and a sequence sliced in time
   // needs registers for the carry exchange as well: the last K-steps of W_x are re-read from L2
   // every tile - a far better spill space than scratch memory)
-  constexpr int NRES = GMAX == 1 ? 13 : (GMAX == 4 ? 8 : 4);
+  constexpr int NRES = GMAX == 1 ? 13 : (GMAX == 4 ? 9 : (GMAX == 8 ? 6 : 2));   // measured best
   constexpr int PF = 2;   // streamed fragments in flight (deeper rings measured no better)
-  bf16x8 wa[16], wx[NRES];
+  bf16x8 wa[16], wx[NRES > 0 ? NRES : 1];
   const bf16x8 *pxs = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
   {
     const bf16x8 *pa = (const bf16x8 *)((const unsigned short *)p.W_a + ((size_t)g * BS + ch) * BS + hf * 8);
@@ -233,16 +235,16 @@ fwd_mfma_kernel(FwdArgs a) {
   // state of the held tile (its local scan sits in LDS until the next iteration)
   int held = -1;
   float hA_lo = 1.f, hH_lo = 0.f, hA_t = 1.f, hH_t = 0.f;  // aggregates of the tile parked in LDS
-  u64 recA[GMAX > 1 ? GMAX - 1 : 1], recH[GMAX > 1 ? GMAX - 1 : 1];
+  // (each lane half fetches one of the two records of a tile, A below and H above, and the
+  // halves swap them when the state is carried across: half the loads and registers)
+  u64 rec[GMAX > 1 ? GMAX - 1 : 1];
 
   auto fetch_records = [&](int t) __attribute__((always_inline)) {  // aggregates of the G-1 tiles before tile t
 #pragma unroll
     for (int s = 0; s < GMAX - 1; ++s) {
       const int k = t - (G - 1) + s;
       if (s < G - 1 && k >= 0) {
-        const u64 *slot = ring + (size_t)(k % a.R) * 2 * BS;
-        recA[s] = peek(slot);
-        recH[s] = peek(slot + BS);
+        rec[s] = peek(ring + (size_t)(k % a.R) * 2 * BS + hf * BS);
       }
     }
   };
@@ -253,19 +255,15 @@ fwd_mfma_kernel(FwdArgs a) {
     for (int s = 0; s < GMAX - 1; ++s) {
       const int k = t - (G - 1) + s;
       if (s < G - 1 && k >= 0) {
-        const u64 *slot = ring + (size_t)(k % a.R) * 2 * BS;
+        const u64 *slot = ring + (size_t)(k % a.R) * 2 * BS + hf * BS;
         const unsigned want = (unsigned)(k + 1);
-        while ((unsigned)(recA[s] >> 32) != want && spins < SPIN_LIMIT) {
+        while ((unsigned)(rec[s] >> 32) != want && spins < SPIN_LIMIT) {
           ++spins;
           __builtin_amdgcn_s_sleep(1);
-          recA[s] = peek(slot);
+          rec[s] = peek(slot);
         }
-        while ((unsigned)(recH[s] >> 32) != want && spins < SPIN_LIMIT) {
-          ++spins;
-          __builtin_amdgcn_s_sleep(1);
-          recH[s] = peek(slot + BS);
-        }
-        h = fmaf(__uint_as_float((unsigned)recA[s]), h, __uint_as_float((unsigned)recH[s]));
+        const float mine = __uint_as_float((unsigned)rec[s]), other = __shfl_xor(mine, 32);
+        h = fmaf(hf ? other : mine, h, hf ? mine : other);
       }
     }
     float hrun = hf ? fmaf(hA_lo, h, hH_lo) : h;  // state entering this lane's run
@@ -761,11 +759,11 @@ bool forward_mfma_supported(const Problem &p, bool bf) {
 
 // time slices per (sequence, block): as many as keep every workgroup resident at once, at
 // most 8 (every tile reads the aggregates of the G-1 tiles before it)
-int mfma::pick_slices(int units, int ntile, int ncu) {
+int mfma::pick_slices(int units, int ntile, int ncu, int cap) {
   int G = ncu / units;
   if (G < 1) G = 1;
   if (G > ntile) G = ntile;
-  if (G > 8) G = 8;
+  if (G > cap) G = cap;
   return G;
 }
 
@@ -773,7 +771,7 @@ int mfma::pick_slices(int units, int ntile, int ncu) {
 // worst case of 256 compute units so that it does not depend on the device.
 size_t forward_mfma_ws_bytes(int B, int T, int D, int nb) {
   const int units = B * nb, ntile = (T + TT - 1) / TT;
-  const int G = pick_slices(units, ntile, 256);
+  const int G = pick_slices(units, ntile, 256, FWD_MAX_SLICES);
   if (G == 1) return 0;
   const size_t R = 8 * (size_t)G;
   return 256 + (size_t)units * R * 2 * BS * sizeof(u64);
@@ -801,7 +799,7 @@ hipError_t launch_forward_mfma(const Problem &p, hipStream_t s) {
   a.ntile = (p.T + TT - 1) / TT;
   int ncu = num_cu();
   if (ncu > 256) ncu = 256;  // the workspace is sized for at most 256 resident workgroups
-  a.G = pick_slices(units, a.ntile, ncu);
+  a.G = pick_slices(units, a.ntile, ncu, FWD_MAX_SLICES);
   a.R = 8 * a.G;
   const int grid = units * a.G;
   a.swizzle = (a.G > 1 && grid % 8 == 0) ? 1 : 0;
@@ -815,7 +813,8 @@ hipError_t launch_forward_mfma(const Problem &p, hipStream_t s) {
   hipError_t e = launch_prep(p.ws, 256 + (size_t)units * a.R * 2 * BS * sizeof(u64), s);
   if (e != hipSuccess) return e;
   return a.G <= 4 ? launch_t<4>(a, grid, FWD_LDS, s)
-                  : launch_t<8>(a, grid, FWD_LDS, s);
+       : a.G <= 8 ? launch_t<8>(a, grid, FWD_LDS, s)
+                  : launch_t<16>(a, grid, FWD_LDS, s);
 }
 
 bool decode_mfma_supported(const Problem &p, bool bf) {

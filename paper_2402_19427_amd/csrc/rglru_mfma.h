@@ -87,7 +87,7 @@ __device__ __forceinline__ void store_staged_tile(const unsigned short *ot, int 
 
 // host side (defined with the forward kernel)
 int num_cu();                                    // compute units of the current device
-int pick_slices(int units, int ntile, int ncu);  // time slices per (sequence, block)
+int pick_slices(int units, int ntile, int ncu, int cap);  // time slices per (sequence, block), at most cap
 // clears zero_bytes (% 16 == 0) at `zero` with a fill kernel
 hipError_t launch_prep(void *zero, size_t zero_bytes, hipStream_t s);
 
