@@ -363,37 +363,31 @@ bwd_gates_kernel(BwdArgs a) {
     if (GMAX > 1) {
       publish(ring + (size_t)(tile % a.R) * 2 * BS + hf * BS, hf ? E_t : A_t, (unsigned)(tile + 1));
       // eps entering this tile: own state after tile+G carried across tiles tile+G-1 .. tile+1.
-      // Their aggregates are requested two tiles at a time (one round trip per pair instead of
-      // two per tile); a tag that is not there yet is simply read again.
+      // Each lane half fetches one of a tile's two records (A below, E above; the halves swap
+      // them afterwards), four tiles per round trip; a tag that is not there yet is simply
+      // read again.
+      constexpr int NB = 4;
 #pragma unroll
-      for (int s0 = GMAX - 2; s0 >= 0; s0 -= 2) {
-        u64 recA[2], recE[2];
+      for (int s0 = GMAX - 2; s0 >= 0; s0 -= NB) {
+        u64 rec[NB];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NB; ++i) {
           const int s = s0 - i, k = tile + 1 + s;
-          if (s >= 0 && s < G - 1 && k < a.ntile) {
-            const u64 *slot = ring + (size_t)(k % a.R) * 2 * BS;
-            recA[i] = peek(slot);
-            recE[i] = peek(slot + BS);
-          }
+          if (s >= 0 && s < G - 1 && k < a.ntile) rec[i] = peek(ring + (size_t)(k % a.R) * 2 * BS + hf * BS);
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NB; ++i) {
           const int s = s0 - i, k = tile + 1 + s;
           if (s >= 0 && s < G - 1 && k < a.ntile) {
-            const u64 *slot = ring + (size_t)(k % a.R) * 2 * BS;
+            const u64 *slot = ring + (size_t)(k % a.R) * 2 * BS + hf * BS;
             const unsigned want = (unsigned)(k + 1);
-            while ((unsigned)(recA[i] >> 32) != want && spins < SPIN_LIMIT) {
+            while ((unsigned)(rec[i] >> 32) != want && spins < SPIN_LIMIT) {
               ++spins;
               __builtin_amdgcn_s_sleep(2);
-              recA[i] = peek(slot);
+              rec[i] = peek(slot);
             }
-            while ((unsigned)(recE[i] >> 32) != want && spins < SPIN_LIMIT) {
-              ++spins;
-              __builtin_amdgcn_s_sleep(2);
-              recE[i] = peek(slot + BS);
-            }
-            e_in = fmaf(__uint_as_float((unsigned)recA[i]), e_in, __uint_as_float((unsigned)recE[i]));
+            const float mine = __uint_as_float((unsigned)rec[i]), other = __shfl_xor(mine, 32);
+            e_in = fmaf(hf ? other : mine, e_in, hf ? mine : other);
           }
         }
       }
