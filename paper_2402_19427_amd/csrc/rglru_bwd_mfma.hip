@@ -33,7 +33,7 @@ constexpr int TS = TT + 8;                       // row stride (bf16) of the [ch
 constexpr int TR_BYTES = BS * TS * 2;            // one transposed tile
 // LDS of the gates kernel: x tile (high, low) | constants | dy^T | y^T | r_t of the tile |
 // W_x fragments
-constexpr int G_NRES = 4;                        // K-steps of W_x resident in registers
+constexpr int G_NRES = 4;                        // K-steps of W_x resident in registers (5 without time slices)
 constexpr int G_NLDS = 5;                        // further K-steps of W_x resident in LDS
 constexpr int G_OFF_CONST = XS_BYTES / 2;        // one x buffer: the kernel has two barriers per tile
 constexpr int G_OFF_DYT = G_OFF_CONST + CONST_BYTES;
@@ -118,7 +118,7 @@ bwd_gates_kernel(BwdArgs a) {
   // stay in registers, the next NLDS K-steps of W_x in LDS, and the rest is re-read from L2
   // every tile as contiguous 1 KB fragments (the register file cannot hold everything this
   // kernel needs, and L2 is a far better spill space than scratch)
-  constexpr int NRES = G_NRES, NLDS = G_NLDS;
+  constexpr int NRES = GMAX == 1 ? G_NRES + 1 : G_NRES, NLDS = G_NLDS;
   bf16x8 wa[16], wx[NRES];
   // fragment ks of this lane when streamed: pxs[ks * 64] (W_x in fragment order)
   const bf16x8 *pxs = (const bf16x8 *)a.wxf + (size_t)(g * NWAVE + wv) * 16 * 64 + lane;
