@@ -1172,7 +1172,7 @@ BwdPlan plan_backward(int B, int T, int D, int nb, int ncu) {
   BwdPlan q;
   q.units = B * nb;
   q.ntile = (T + TT - 1) / TT;
-  q.G = pick_slices(q.units, q.ntile, ncu, 8);
+  q.G = pick_slices(q.units, q.ntile, ncu, 16);
   q.R = 8 * q.G;
   q.C = ncu / q.units;
   if (q.C < 1) q.C = 1;
@@ -1229,6 +1229,7 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
     if ((e = big_lds(bwd_gates_kernel<1>, G_LDS)) != hipSuccess) return e;
     if ((e = big_lds(bwd_gates_kernel<4>, G_LDS)) != hipSuccess) return e;
     if ((e = big_lds(bwd_gates_kernel<8>, G_LDS)) != hipSuccess) return e;
+    if ((e = big_lds(bwd_gates_kernel<16>, G_LDS)) != hipSuccess) return e;
     if ((e = big_lds(bwd_dgrad_kernel, D_LDS)) != hipSuccess) return e;
     if ((e = big_lds(bwd_wgrad_kernel, W_LDS)) != hipSuccess) return e;
     configured = true;
@@ -1269,8 +1270,10 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
       hipLaunchKernelGGL(bwd_gates_kernel<1>, dim3(grid), dim3(NTHR), G_LDS, s, a);
     else if (q.G <= 4)
       hipLaunchKernelGGL(bwd_gates_kernel<4>, dim3(grid), dim3(NTHR), G_LDS, s, a);
-    else
+    else if (q.G <= 8)
       hipLaunchKernelGGL(bwd_gates_kernel<8>, dim3(grid), dim3(NTHR), G_LDS, s, a);
+    else
+      hipLaunchKernelGGL(bwd_gates_kernel<16>, dim3(grid), dim3(NTHR), G_LDS, s, a);
   }
   if ((e = hipGetLastError()) != hipSuccess) return e;
 

@@ -46,7 +46,7 @@ SHAPES = [
     (1, 9, 24, 24, "bf16"),      # nb = D: per-channel gates
     (2, 300, 600, 2, "bf16"),    # bs = 300 > workgroup size
     (1, 1, 256, 1, "bf16"),      # MFMA path, one step
-    (1, 1500, 256, 1, "bf16"),   # MFMA path, one unit sliced 32 ways in time
+    (1, 1500, 256, 1, "bf16"),   # MFMA path, one unit in 16 time slices
     (33, 70, 1024, 4, "bf16"),   # MFMA path, 132 units: one workgroup per unit, no slicing
     (8, 600, 2048, 8, "bf16"),   # MFMA path, 64 units x 4 slices, record ring wraps (19 tiles > 16)
 ]
@@ -174,7 +174,7 @@ BWD_SHAPES = [
     (1, 270, 600, 2, "bf16"),
     (1, 1, 256, 1, "bf16"),       # MFMA path, single step
     (2, 31, 256, 1, "bf16"),      # MFMA path, one partial tile
-    (1, 700, 256, 1, "bf16"),     # MFMA path, one unit in 8 time slices
+    (1, 700, 256, 1, "bf16"),     # MFMA path, one unit in 16 time slices
     (33, 70, 1024, 4, "bf16"),    # MFMA path, 132 units, no slicing
     (8, 300, 2048, 8, "bf16"),    # MFMA path, 64 units x 4 slices
 ]
