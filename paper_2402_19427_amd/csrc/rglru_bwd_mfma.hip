@@ -1018,6 +1018,19 @@ bwd_wgrad_kernel(WgradArgs a) {
                                (4 * nw * 32 + j) * TS + 16 * hf;
     const unsigned short *xl = xh + BS * TS;
     const bf16x8 sl0 = sel_lds[lane], sl1 = sel_lds[64 + lane];
+    // x fragments (x = high + low, both bf16; as in the dp / dq fragments, lane half hf holds
+    // steps 16 hf .. 16 hf + 7 in the first K-step and the following 8 in the second), in the
+    // order of their use: f = 8 r + 2 q + i is column block 2 r + i, part q (high K0, high K1,
+    // low K0, low K1). LDS latency is several products long, so the reads run six fragments
+    // ahead of the products: the first six are requested before the dp / dq fragments are built.
+    auto xfrag = [&](int f) __attribute__((always_inline)) {
+      const int r = f >> 3, q = (f >> 1) & 3, i = f & 1;
+      return *(const bf16x8 *)((q < 2 ? xh : xl) + (2 * r + i) * 32 * TS + (q & 1) * 8);
+    };
+    bf16x8 w[16];
+#pragma unroll
+    for (int f = 0; f < 6; ++f) w[f] = xfrag(f);
+    __builtin_amdgcn_sched_barrier(0);
     // dp / dq fragments: column block c of the tile -> two K-steps of 8 consecutive steps per lane
     bf16x8 fa[2][2];
 #pragma unroll
@@ -1035,26 +1048,24 @@ bwd_wgrad_kernel(WgradArgs a) {
       fa[m][0] = __builtin_bit_cast(bf16x8, lo4);
       fa[m][1] = __builtin_bit_cast(bf16x8, hi4);
     }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int n = 0; n < 4; n += 2) {
-      // x = high + low, both bf16; as in the dp / dq fragments, lane half hf holds steps
-      // 16 hf .. 16 hf + 7 in the first K-step and the following 8 in the second
-      bf16x8 fb[2][4];   // [column block][high K0, high K1, low K0, low K1]
+    for (int f = 6; f < 16; ++f) w[f] = xfrag(f);
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        fb[i][0] = *(const bf16x8 *)(xh + (n + i) * 32 * TS);
-        fb[i][1] = *(const bf16x8 *)(xh + (n + i) * 32 * TS + 8);
-        fb[i][2] = *(const bf16x8 *)(xl + (n + i) * 32 * TS);
-        fb[i][3] = *(const bf16x8 *)(xl + (n + i) * 32 * TS + 8);
-      }
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {   // four independent accumulators per round: no product waits for its predecessor
-        acc[0][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][q & 1], fb[0][q], acc[0][n], 0, 0, 0);
-        acc[1][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][q & 1], fb[0][q], acc[1][n], 0, 0, 0);
-        acc[0][n + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][q & 1], fb[1][q], acc[0][n + 1], 0, 0, 0);
-        acc[1][n + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][q & 1], fb[1][q], acc[1][n + 1], 0, 0, 0);
-      }
+    for (int pr = 0; pr < 8; ++pr) {   // four independent accumulators per round: no product waits for its predecessor
+      const int r = pr >> 2, q = pr & 3;
+      acc[0][2 * r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][q & 1], w[2 * pr], acc[0][2 * r], 0, 0, 0);
+      acc[1][2 * r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][q & 1], w[2 * pr], acc[1][2 * r], 0, 0, 0);
+      acc[0][2 * r + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][q & 1], w[2 * pr + 1], acc[0][2 * r + 1], 0, 0, 0);
+      acc[1][2 * r + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][q & 1], w[2 * pr + 1], acc[1][2 * r + 1], 0, 0, 0);
     }
+    // issue order: four products, then the next two reads
+#pragma unroll
+    for (int pr = 0; pr < 8; ++pr) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      if (pr < 5) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
   };
 
   // The two waves that share a SIMD work half a step apart: waves 4-7 multiply and then
