@@ -659,9 +659,7 @@ decode_mfma_kernel(DecArgs a) {
   for (int ph = 0; ph < 4; ++ph) {
     if (ph + 2 < 4) load_phase(ph + 2, stg[ph & 1]);
     // the fragments come from other lanes of this wave
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    wave_lds_fence();
     bf16x8 av[4], fa[4], fx[4];
 #pragma unroll
     for (int k2 = 0; k2 < 4; ++k2) {
@@ -669,9 +667,7 @@ decode_mfma_kernel(DecArgs a) {
       fa[k2] = *(const bf16x8 *)(wl + wl_rd + k2 * 32);
       fx[k2] = *(const bf16x8 *)(wl + DEC_WPH + wl_rd + k2 * 32);
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    wave_lds_fence();
     if (ph + 1 < 4) write_phase(stg[(ph + 1) & 1]);
 #pragma unroll
     for (int k2 = 0; k2 < 4; ++k2) {   // two independent accumulation chains
@@ -689,15 +685,11 @@ decode_mfma_kernel(DecArgs a) {
   // ---- h into accumulator layout: lane (j, hf) owns channel j of rows 16 hf .. 16 hf + 15
 #pragma unroll
   for (int i = 0; i < 4; ++i) *(u32x4 *)(hl + i * 8 * DEC_WROW + hl_wide) = hin[i];
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  wave_lds_fence();
   float rh[16];
 #pragma unroll
   for (int r = 0; r < 16; ++r) rh[r] = *(const float *)(hl + (hf * 16 + r) * DEC_WROW + j * 4);
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  wave_lds_fence();
 
   // ---- eq. (4) for the 16 sequences of this lane's run; results back through the staging tiles
   unsigned char *yl = wl;   // weight buffer 0 of this wave is free again
@@ -709,9 +701,7 @@ decode_mfma_kernel(DecArgs a) {
     *(float *)(hl + (hf * 16 + r) * DEC_WROW + j * 4) = hn;
     *(unsigned short *)(yl + (hf * 16 + r) * DEC_YROW + j * 2) = (unsigned short)(pack_bf16(hn, 0.f) & 0xffff);
   }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  wave_lds_fence();
 #pragma unroll
   for (int i = 0; i < 4; ++i)
     __builtin_amdgcn_raw_buffer_store_b128(*(const u32x4 *)(hl + i * 8 * DEC_WROW + hl_wide), h_rsrc, h_vo[i], 0, 0);

@@ -68,6 +68,15 @@ __device__ __forceinline__ u64 peek(const u64 *slot) {
 #define RGLRU_NT 2
 #endif
 
+// Orders a wave's own LDS accesses where lanes exchange data through a wave-private buffer:
+// LDS serves the accesses of one wave in order, so no instruction is needed, only the
+// compiler must not move them across this point.
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <int STRIDE, int AUX = 0>
 __device__ __forceinline__ void store_staged_tile_s(const unsigned short *ot, int lane,
                                                     __amdgpu_buffer_rsrc_t rsrc, unsigned voff,
