@@ -12,6 +12,8 @@
  *   rglru_param_grads) are HOST pointers, read during the call only.
  * - Calls are asynchronous: kernels are enqueued on `stream` (a hipStream_t passed as
  *   void*, NULL = the default stream) and the function returns without synchronising.
+ *   A call enqueues kernels only (no memsets, copies, allocations or waits), so calls may be
+ *   recorded into a HIP graph by capturing the stream (with rglru_timing_enable(0)).
  * - Scratch memory comes from the caller: `workspace` must hold at least
  *   rglru_workspace_bytes(shape, op) bytes, 256-byte aligned; the library initialises what
  *   it needs on `stream`. Two calls that overlap in time must not share a workspace.
