@@ -97,6 +97,20 @@ def rglru(x, W_a, W_x, b_a, b_x, Lambda, h0=None, c=8.0, want_gates=False):
     return y, hT
 
 
+def scan(a, g, h0=None, a_is_log=False, normalize=True):
+    """Eq. (4) alone as a linear scan (Section 4.2): h_t = a_t h_{t-1} + m_t g_t with
+    m_t = sqrt(1 - a_t^2) (normalize) or 1. ``a`` holds a_t, or log a_t when a_is_log.
+    a, g [B,T,D]; h0 [B,D] or None. Returns h [B,T,D], hT [B,D]."""
+    a, g, h0 = map(_f64, (a, g, h0))
+    B, T, D = a.shape
+    assert g.shape == (B, T, D) and (h0 is None or h0.shape == (B, D))
+    h = np.empty((B, T, D))
+    hT = np.empty((B, D))
+    _load().oracle_scan(B, T, D, int(bool(a_is_log)), int(bool(normalize)), _p(a), _p(g), _p(h0),
+                        _p(h), _p(hT))
+    return h, hT
+
+
 def forward(u, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b=None, h0=None, state_in=None, c=8.0):
     """Conv1D then RG-LRU. Returns y [B,T,D], hT [B,D], state_out [B,K-1,D] (chronological)."""
     u, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b, h0, state_in = map(

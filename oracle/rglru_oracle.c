@@ -14,6 +14,8 @@
  *   - RG-LRU: Section 2.4, eqs. (1)-(4), a = sigmoid(Lambda), c = 8,
  *     y_t = h_t; Appendix A for evaluating a_t in log space.
  *   - Block-diagonal gate weights: Section 4.1 "Recurrent Block".
+ *   - Eq. (4) alone as a linear scan over given a_t (or log a_t) and gated
+ *     inputs: Section 4.2 "A custom linear scan", Appendix A.3 "Scan runtimes".
  *   - Backward: not printed in the paper; it is the adjoint of the forward
  *     equations, derived by hand (see oracle_backward below) and pinned by
  *     finite differences in the test suite.
@@ -166,6 +168,35 @@ void oracle_rglru(int B, int T, int D, int nb, double c, const double *x,
         }
         if (hT) hT[(size_t)b * D + d] = h;
       }
+    }
+  }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Eq. (4) alone, as a linear scan over given sequences (Section 4.2, "A     */
+/* custom linear scan"; the operation timed in Appendix A.3, "Scan           */
+/* runtimes"): per element the decay a_t - or log a_t, the form Appendix A   */
+/* evaluates it in - and the gated input g_t = i_t x_t.                      */
+/*   h_t = a_t h_{t-1} + m_t g_t,  m_t = sqrt(1 - a_t^2) (normalize != 0)    */
+/*                                 m_t = 1               (normalize == 0)    */
+/* a, g, h: [B][T][D]; h0, hT: [B][D] (h0 NULL = zeros, hT NULL = skipped).  */
+/* ------------------------------------------------------------------------ */
+void oracle_scan(int B, int T, int D, int a_is_log, int normalize,
+                 const double *a, const double *g, const double *h0,
+                 double *h, double *hT) {
+  for (int b = 0; b < B; ++b) {
+    for (int d = 0; d < D; ++d) {
+      double s = h0 ? h0[(size_t)b * D + d] : 0.0;
+      for (int t = 0; t < T; ++t) {
+        const size_t o = ((size_t)b * T + t) * D + d;
+        const double av = a_is_log ? exp(a[o]) : a[o];
+        double m = 1.0;
+        if (normalize)
+          m = a_is_log ? sqrt(-expm1(2.0 * a[o])) : sqrt(1.0 - av * av);
+        s = av * s + m * g[o];
+        h[o] = s;
+      }
+      if (hT) hT[(size_t)b * D + d] = s;
     }
   }
 }

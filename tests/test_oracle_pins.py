@@ -392,3 +392,80 @@ def test_oracle_threads_do_not_change_results():
         oracle.set_threads(1)
     np.testing.assert_array_equal(y1, y4)
     np.testing.assert_array_equal(h1, h4)
+
+
+# ------------------------------------------------------------------ eq. (4) as a linear scan
+def _scan_inputs(B, T, D, seed):
+    rng = np.random.default_rng(seed)
+    a = rng.uniform(0.5, 0.999, size=(B, T, D))
+    g = rng.standard_normal((B, T, D))
+    h0 = rng.standard_normal((B, D))
+    return a, g, h0
+
+
+def test_scan_special_cases_are_cumsum_and_cumprod():
+    a, g, h0 = _scan_inputs(2, 40, 5, 0)
+    # a = 1 without the input scale: a running sum on top of h0 (library routine)
+    h, hT = oracle.scan(np.ones_like(a), g, h0, normalize=False)
+    np.testing.assert_allclose(h, h0[:, None, :] + np.cumsum(g, axis=1), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(hT, h[:, -1], rtol=0, atol=0)
+    # zero input: pure decay by the running product of a_t
+    h, _ = oracle.scan(a, np.zeros_like(g), h0)
+    np.testing.assert_allclose(h, h0[:, None, :] * np.cumprod(a, axis=1), rtol=1e-12)
+    # no h0 means a zero initial state
+    h_a, _ = oracle.scan(a, g, None)
+    h_b, _ = oracle.scan(a, g, np.zeros_like(h0))
+    np.testing.assert_array_equal(h_a, h_b)
+
+
+def test_scan_constant_inputs_closed_form():
+    # h_t = alpha^(t+1) h0 + sqrt(1 - alpha^2) beta (1 - alpha^(t+1)) / (1 - alpha)
+    alpha, beta, T = 0.9, 0.7, 60
+    a = np.full((1, T, 3), alpha)
+    g = np.full((1, T, 3), beta)
+    h0 = np.array([[0.0, 1.5, -2.0]])
+    h, hT = oracle.scan(a, g, h0)
+    k = np.arange(1, T + 1)[None, :, None]
+    want = alpha ** k * h0[:, None, :] + np.sqrt(1 - alpha ** 2) * beta * (1 - alpha ** k) / (1 - alpha)
+    np.testing.assert_allclose(h, want, rtol=1e-12)
+    # the same without the input scale
+    h, _ = oracle.scan(a, g, h0, normalize=False)
+    np.testing.assert_allclose(h, alpha ** k * h0[:, None, :] + beta * (1 - alpha ** k) / (1 - alpha), rtol=1e-12)
+
+
+@pytest.mark.parametrize("normalize", [True, False])
+def test_scan_equals_unrolled_sum(normalize):
+    a, g, h0 = _scan_inputs(1, 7, 2, 3)
+    h, _ = oracle.scan(a, g, h0, normalize=normalize)
+    for t in range(7):
+        for d in range(2):
+            tot = h0[0, d] * np.prod(a[0, :t + 1, d])
+            for s in range(t + 1):
+                m = np.sqrt(1 - a[0, s, d] ** 2) if normalize else 1.0
+                tot += np.prod(a[0, s + 1:t + 1, d]) * m * g[0, s, d]
+            assert abs(h[0, t, d] - tot) < 1e-12
+
+
+def test_scan_log_form_equals_direct_form_and_keeps_precision_near_one():
+    a, g, h0 = _scan_inputs(2, 30, 4, 4)
+    h_dir, _ = oracle.scan(a, g, h0)
+    h_log, _ = oracle.scan(np.log(a), g, h0, a_is_log=True)
+    np.testing.assert_allclose(h_log, h_dir, rtol=1e-12, atol=1e-13)
+    # log a = -eps: sqrt(1 - a^2) = sqrt(2 eps) (1 - eps/2 + O(eps^2)), which 1 - a*a cannot resolve
+    eps = 1e-13
+    h, _ = oracle.scan(np.full((1, 1, 1), -eps), np.ones((1, 1, 1)), None, a_is_log=True)
+    assert abs(h[0, 0, 0] / (np.sqrt(2 * eps) * (1 - eps / 2)) - 1) < 1e-12
+
+
+def test_scan_on_the_layer_s_own_gates_reproduces_the_layer():
+    inp = gen.make_inputs(2, 25, 32, 4, act="f32", seed=5, h0=True)
+    q = {k: (None if v is None else np.asarray(v, np.float64)) for k, v in inp.items()}
+    x = oracle.conv1d(q["u"], q["conv_w"])
+    y, hT, gates = oracle.rglru(x, q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"], h0=q["h0"],
+                                want_gates=True)
+    h, hT2 = oracle.scan(gates["a"], gates["i"] * x, q["h0"])
+    np.testing.assert_allclose(h, y, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(hT2, hT, rtol=1e-11, atol=1e-13)
+    # and the scale it applies is the layer's sqrt(1 - a^2)
+    h3, _ = oracle.scan(gates["a"], gates["m"] * gates["i"] * x, q["h0"], normalize=False)
+    np.testing.assert_allclose(h3, y, rtol=1e-11, atol=1e-13)
