@@ -70,6 +70,7 @@ extern "C" {
 #define RGLRU_OP_FORWARD 1
 #define RGLRU_OP_DECODE 2
 #define RGLRU_OP_BACKWARD 3
+#define RGLRU_OP_SCAN 4
 
 typedef struct rglru_shape {
   int32_t B;          /* sequences                                  (>= 1)                 */
@@ -116,6 +117,28 @@ typedef struct rglru_param_grads {
 int rglru_conv1d(const rglru_shape *shape, const void *u, const float *conv_w,
                  const float *conv_b, const void *conv_state_in, int64_t pos0, void *x_out,
                  void *conv_state_out, void *stream);
+
+/* flags of rglru_scan() */
+#define RGLRU_SCAN_LOG_A 1u          /* `a` holds log a_t (<= 0) instead of a_t            */
+#define RGLRU_SCAN_NO_INPUT_SCALE 2u /* h_t = a_t h_{t-1} + g_t, without sqrt(1 - a_t^2)   */
+
+/*
+ * Eq. (4) alone, as a linear scan over given sequences (Section 4.2, "A custom linear scan";
+ * the operation whose runtimes Appendix A.3 reports for batch 8, width 1024):
+ *     h_t = a_t h_{t-1} + sqrt(1 - a_t^2) g_t,   h_{-1} = h0
+ *   a      [B][T][D] act, read: the decay a_t in [0, 1]; with RGLRU_SCAN_LOG_A its logarithm,
+ *          the form Appendix A evaluates it in (then sqrt(1 - a_t^2) = sqrt(-expm1(2 log a_t))).
+ *   g      [B][T][D] act, read: the gated input i_t x_t.
+ *   h0     [B][D] f32 or NULL (zeros).
+ *   h      [B][T][D] act, written; must not overlap a or g.
+ *   hT     [B][D] f32 or NULL (not produced): the state after the last step.
+ *   workspace: rglru_workspace_bytes(shape, RGLRU_OP_SCAN) bytes.
+ * The state is carried in fp32 whatever the storage type. Of `shape`, only B, T (>= 0), D and
+ * act_dtype are used (the other fields must still be valid). T == 0 writes hT = h0 only.
+ */
+int rglru_scan(const rglru_shape *shape, const void *a, const void *g, const float *h0,
+               unsigned flags, void *h, float *hT, void *workspace, size_t workspace_bytes,
+               void *stream);
 
 /*
  * Forward over whole sequences: Conv1D then RG-LRU (Sections 2.3-2.4, eqs. 1-4).

@@ -12,7 +12,8 @@ LIB_PATH = os.environ.get("RGLRU_LIB", os.path.join(_PKG, "librglru.so"))
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 F32, BF16 = 0, 1
-OP_CONV1D, OP_FORWARD, OP_DECODE, OP_BACKWARD = 0, 1, 2, 3
+OP_CONV1D, OP_FORWARD, OP_DECODE, OP_BACKWARD, OP_SCAN = 0, 1, 2, 3, 4
+SCAN_LOG_A, SCAN_NO_INPUT_SCALE = 1, 2
 
 
 class Shape(ctypes.Structure):
@@ -53,6 +54,7 @@ def _load():
     lib.rglru_forward.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp, vp, vp, sz, vp]
     lib.rglru_decode_step.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp]
     lib.rglru_backward.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp, vp, vp, vp, gp, vp, sz, vp]
+    lib.rglru_scan.argtypes = [sp, vp, vp, vp, ctypes.c_uint, vp, vp, vp, sz, vp]
     lib.rglru_workspace_bytes.argtypes = [sp, ctypes.c_int]
     lib.rglru_workspace_bytes.restype = sz
     lib.rglru_last_error.restype = ctypes.c_char_p
@@ -61,7 +63,8 @@ def _load():
     lib.rglru_timing_select.argtypes = [ctypes.c_char_p]
     lib.rglru_timing_get.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p),
                                      ctypes.POINTER(ctypes.c_float)]
-    for f in (lib.rglru_conv1d, lib.rglru_forward, lib.rglru_decode_step, lib.rglru_backward):
+    for f in (lib.rglru_conv1d, lib.rglru_forward, lib.rglru_decode_step, lib.rglru_backward,
+              lib.rglru_scan):
         f.restype = ctypes.c_int
     return lib
 
@@ -169,3 +172,8 @@ def rglru_backward(shape, params, u, h0, conv_state_in, pos0, y, dy, dhT, du, dh
                                _addr(conv_state_in), pos0, _addr(y), _addr(dy), _addr(dhT),
                                _addr(du), _addr(dh0), _ref(grads), _addr(workspace),
                                workspace_bytes, _stream(stream)))
+
+
+def rglru_scan(shape, a, g, h0, flags, h, hT, workspace, workspace_bytes, stream=None):
+    _check(_lib.rglru_scan(_ref(shape), _addr(a), _addr(g), _addr(h0), flags, _addr(h), _addr(hT),
+                           _addr(workspace), workspace_bytes, _stream(stream)))

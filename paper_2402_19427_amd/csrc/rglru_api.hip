@@ -117,6 +117,10 @@ size_t workspace_need(const rglru_shape *s, int op) {
           (size_t)s->T * s->D * 4 < ((size_t)1 << 32))
         return backward_mfma_ws_bytes(s->B, s->T, s->D, s->num_blocks);
       return backward_generic_ws_bytes(s->B, s->T, s->D, s->num_blocks);
+    case RGLRU_OP_SCAN:
+      if (s->act_dtype == RGLRU_BF16 && s->D % 256 == 0 && s->T >= 1)
+        return scan_tiled_ws_bytes(s->B, s->T, s->D);
+      return 0;
     case RGLRU_OP_FORWARD:
       if (s->act_dtype == RGLRU_BF16 && s->D / s->num_blocks == 256 && s->T >= 1)
         return forward_mfma_ws_bytes(s->B, s->T, s->D, s->num_blocks);
@@ -190,10 +194,10 @@ const char *rglru_last_error(void) { return g_err; }
 int rglru_version(void) { return 100; }
 
 size_t rglru_workspace_bytes(const rglru_shape *shape, int op) {
-  if (op < RGLRU_OP_CONV1D || op > RGLRU_OP_BACKWARD) return 0;
+  if (op < RGLRU_OP_CONV1D || op > RGLRU_OP_SCAN) return 0;
   char keep[sizeof(g_err)];
   memcpy(keep, g_err, sizeof(g_err));
-  const bool blocks = op != RGLRU_OP_CONV1D;
+  const bool blocks = op != RGLRU_OP_CONV1D && op != RGLRU_OP_SCAN;
   const int rc = check_shape(shape, blocks, op != RGLRU_OP_DECODE, op == RGLRU_OP_BACKWARD ? 1 : 0);
   memcpy(g_err, keep, sizeof(g_err));  // a size query does not disturb the error string
   if (rc != RGLRU_OK) return 0;
@@ -263,6 +267,33 @@ int rglru_forward(const rglru_shape *shape, const rglru_params *params, const vo
     e = launch_state_update(q, bf, s);
   }
   if (e != hipSuccess) return hip_fail(e, "conv state launch");
+  g_err[0] = 0;
+  return RGLRU_OK;
+}
+
+int rglru_scan(const rglru_shape *shape, const void *a, const void *g, const float *h0,
+               unsigned flags, void *h, float *hT, void *workspace, size_t workspace_bytes,
+               void *stream) {
+  CHECK(check_shape(shape, false, true, 0));
+  if (flags & ~(RGLRU_SCAN_LOG_A | RGLRU_SCAN_NO_INPUT_SCALE))
+    return fail(RGLRU_ERR_INVALID_ARG, "unknown scan flags 0x%x", flags);
+  const size_t as = act_size(shape);
+  CHECK(check_ptr(a, "a", as, shape->T > 0));
+  CHECK(check_ptr(g, "g", as, shape->T > 0));
+  CHECK(check_ptr(h, "h", as, shape->T > 0));
+  CHECK(check_ptr(h0, "h0", 4, false));
+  CHECK(check_ptr(hT, "hT", 4, false));
+  CHECK(check_workspace(workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_SCAN)));
+
+  ScanProblem q;
+  memset(&q, 0, sizeof(q));
+  q.B = shape->B; q.T = shape->T; q.D = shape->D; q.flags = flags;
+  q.a = a; q.g = g; q.h0 = h0; q.h = h; q.hT = hT;
+  q.ws = workspace; q.ws_bytes = workspace_bytes;
+  const bool bf = shape->act_dtype == RGLRU_BF16;
+  hipStream_t s = (hipStream_t)stream;
+  const hipError_t e = scan_tiled_supported(q, bf) ? launch_scan_tiled(q, s) : launch_scan_generic(q, bf, s);
+  if (e != hipSuccess) return hip_fail(e, "scan launch");
   g_err[0] = 0;
   return RGLRU_OK;
 }

@@ -56,6 +56,18 @@ struct Problem {
   size_t ws_bytes;
 };
 
+// One rglru_scan call.
+struct ScanProblem {
+  int B, T, D;
+  unsigned flags;
+  const void *a, *g;
+  const float *h0;
+  void *h;
+  float *hT;
+  void *ws;
+  size_t ws_bytes;
+};
+
 // Benchmark timing: brackets a kernel launch with HIP events when timing is enabled on this
 // thread (see rglru_timing_enable in rglru.h). Usage: { KernelTimer t("name", stream); launch; }
 struct KernelTimer {
@@ -87,5 +99,11 @@ hipError_t launch_decode_mfma(const Problem &p, hipStream_t s);
 bool backward_mfma_supported(const Problem &p, bool bf);
 size_t backward_mfma_ws_bytes(int B, int T, int D, int nb);
 hipError_t launch_backward_mfma(const Problem &p, hipStream_t s);
+
+// Linear scan of eq. (4): any shape and storage type / bf16 storage with D % 256 == 0
+hipError_t launch_scan_generic(const ScanProblem &p, bool bf, hipStream_t s);
+bool scan_tiled_supported(const ScanProblem &p, bool bf);
+size_t scan_tiled_ws_bytes(int B, int T, int D);
+hipError_t launch_scan_tiled(const ScanProblem &p, hipStream_t s);
 
 }  // namespace rglru

@@ -112,3 +112,16 @@ class DeviceProblem:
         out = dict(g)
         out["du"], out["dh0"] = du, dh0
         return out
+
+
+def scan(a, g, h0=None, flags=0, act="bf16", device="cuda:0", stream=None):
+    """rglru_scan on device tensors a, g [B,T,D] (dtype of `act`); returns h, hT."""
+    B, T, D = a.shape
+    dt = R.BF16 if act == "bf16" else R.F32
+    sh = R.make_shape(B, T, D, 1, dt)
+    n = R.rglru_workspace_bytes(sh, R.OP_SCAN)
+    ws = torch.empty(max(n, 256), dtype=torch.uint8, device=device)
+    h = torch.empty_like(a)
+    hT = torch.empty(B, D, dtype=torch.float32, device=device)
+    R.rglru_scan(sh, a, g, h0, flags, h, hT, ws, n, stream)
+    return h, hT

@@ -122,6 +122,22 @@ def make_inputs(B, T, D, nb, act="bf16", seed=0, h0=False, dy=False, state=False
     return out
 
 
+def make_scan_inputs(B, T, D, act="bf16", seed=0, log_a=False, h0=True):
+    """Seeded inputs of the scan-only entry point: decays distributed like the layer's own
+    (a base decay per channel with base^8 ~ U[0.9, 0.999], raised to a per-element power in
+    (0, 8)), stored as a_t or as log a_t; gated inputs ~ N(0, 1); h0 ~ N(0, 1).
+    Returns a dict of float32 arrays, a / g exactly representable in dtype `act`."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    base = rng.uniform(0.9, 0.999, size=D) ** (1.0 / C_CONST)
+    power = C_CONST * rng.uniform(0.0, 1.0, size=(B, T, D))
+    log_decay = power * np.log(base)
+    a = log_decay if log_a else np.exp(log_decay)
+    out = {"a": round_to_act(a.astype(np.float32), act),
+           "g": round_to_act(rng.standard_normal((B, T, D), dtype=np.float32), act),
+           "h0": rng.standard_normal((B, D), dtype=np.float32) if h0 else None}
+    return out
+
+
 def make_workload(name, **override):
     """Inputs of one of the named workloads C0..C4 (sizes may be overridden for sampling)."""
     w = CONFIGS[name]

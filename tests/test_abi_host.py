@@ -140,3 +140,28 @@ def test_workspace_query_is_zero_for_invalid_shapes_and_keeps_error_string():
     assert R.rglru_workspace_bytes(bad, R.OP_FORWARD) == 0
     assert R.rglru_workspace_bytes(bad, 99) == 0
     assert R.rglru_last_error() == msg
+
+
+def test_scan_validation():
+    s = R.make_shape(2, 8, 16, 5, R.BF16)     # num_blocks is not used by the scan
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_scan(s, None, FAKE, None, 0, FAKE, None, None, 0)
+    assert e.value.code == R.ERR_INVALID_ARG and "a is NULL" in str(e.value)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_scan(s, FAKE, FAKE, None, 0, None, None, None, 0)
+    assert e.value.code == R.ERR_INVALID_ARG and "h is NULL" in str(e.value)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_scan(s, FAKE, FAKE, None, 8, FAKE, None, None, 0)
+    assert e.value.code == R.ERR_INVALID_ARG and "flags" in str(e.value)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_scan(s, FAKE + 1, FAKE, None, 0, FAKE, None, None, 0)
+    assert e.value.code == R.ERR_INVALID_ARG and "aligned" in str(e.value)
+    # the tiled kernel needs a workspace when sequences are cut into time slices
+    big = R.make_shape(8, 4096, 1024, 1, R.BF16)
+    need = R.rglru_workspace_bytes(big, R.OP_SCAN)
+    assert need % 256 == 0
+    if need:
+        with pytest.raises(R.RglruError) as e:
+            R.rglru_scan(big, FAKE, FAKE, None, 0, FAKE, None, None, 0)
+        assert e.value.code == R.ERR_WORKSPACE
+    assert R.rglru_workspace_bytes(R.make_shape(8, 4096, 1000, 1, R.F32), R.OP_SCAN) == 0

@@ -286,3 +286,53 @@ def test_whole_step_replays_as_a_hip_graph():
         torch.cuda.synchronize()
         for k, v in outs.items():
             assert torch.equal(v, eager[k]), (rep, k)
+
+
+SCAN_SHAPES = [
+    # B, T, D, act
+    (2, 37, 96, "f32"),          # generic kernel, ragged everything
+    (1, 1, 8, "f32"),
+    (3, 50, 40, "bf16"),         # generic kernel: width not a multiple of 256
+    (2, 100, 256, "bf16"),       # tiled kernel, ragged last tile
+    (1, 1, 256, "bf16"),
+    (1, 3000, 256, "bf16"),      # one unit in 16 time slices
+    (8, 1024, 1024, "bf16"),     # the shape the paper times (Appendix A.3), shortest length
+    (40, 70, 2048, "bf16"),      # 320 units: no time slices
+]
+
+
+@pytest.mark.parametrize("B,T,D,act", SCAN_SHAPES)
+@pytest.mark.parametrize("log_a,scale", [(False, True), (True, True), (False, False)])
+def test_scan_matches_oracle(B, T, D, act, log_a, scale):
+    import paper_2402_19427_amd as R
+    rn = runner()
+    inp = gen.make_scan_inputs(B, T, D, act=act, seed=B + T + D, log_a=log_a)
+    flags = (R.SCAN_LOG_A if log_a else 0) | (0 if scale else R.SCAN_NO_INPUT_SCALE)
+    h, hT = rn.scan(rn.to_device(inp["a"], act), rn.to_device(inp["g"], act),
+                    rn.to_device(inp["h0"], "f32"), flags=flags, act=act)
+    oracle.set_threads(1)
+    h_ref, hT_ref = oracle.scan(inp["a"], inp["g"], inp["h0"], a_is_log=log_a, normalize=scale)
+    assert gen.rel_err(rn.to_host(h), h_ref) < TOL[act]
+    assert gen.rel_err(rn.to_host(hT), hT_ref) < (1e-5 if act == "f32" else 1e-4)   # hT is fp32
+
+
+def test_scan_without_h0_and_without_hT_and_empty():
+    import torch
+    import paper_2402_19427_amd as R
+    rn = runner()
+    inp = gen.make_scan_inputs(2, 45, 512, act="bf16", seed=3, h0=False)
+    a, g = rn.to_device(inp["a"], "bf16"), rn.to_device(inp["g"], "bf16")
+    h, hT = rn.scan(a, g, None)
+    h_ref, hT_ref = oracle.scan(inp["a"], inp["g"], None)
+    assert gen.rel_err(rn.to_host(h), h_ref) < TOL["bf16"]
+    sh = R.make_shape(2, 45, 512, 1, R.BF16)
+    n = R.rglru_workspace_bytes(sh, R.OP_SCAN)
+    ws = torch.empty(max(n, 256), dtype=torch.uint8, device="cuda:0")
+    h2 = torch.empty_like(a)
+    R.rglru_scan(sh, a, g, None, 0, h2, None, ws, n)        # no hT asked for
+    assert torch.equal(h2, h)
+    # T == 0: the state passes through
+    h0 = torch.randn(2, 512, device="cuda:0")
+    hT0 = torch.empty_like(h0)
+    R.rglru_scan(R.make_shape(2, 0, 512, 1, R.BF16), None, None, h0, 0, None, hT0, None, 0)
+    assert torch.equal(hT0, h0)
