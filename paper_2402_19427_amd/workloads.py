@@ -1,6 +1,6 @@
 """Per-workload timing report of the Conv1D -> RG-LRU path on one MI355X.
 
-    python -m paper_2402_19427_amd.workloads [--configs C0,C1,C2,C3,C4] [--json]
+    python -m paper_2402_19427_amd.workloads [--configs C0,C1,C2,C3,C4,SCAN] [--json]
 
 For each of the five synthetic workloads it times the calls that workload is about (forward;
 forward and backward for the training shape; the single-token decode step for the decode shape,
@@ -9,7 +9,9 @@ launches on, and prints median / minimum time, tokens/s, the algorithmic bytes o
 divided by the time (GB/s and fraction of the 8 TB/s HBM peak) and the gate-product FLOP rate
 against the dense bf16 MFMA peak. Small workloads rotate several buffer sets so that the
 footprint of consecutive iterations exceeds the 256 MB last-level cache ("cold"); the decode
-step is also timed on one buffer set ("hot"). Inputs are seeded and synthetic.
+step is also timed on one buffer set ("hot"). SCAN is the scan-only entry point (eq. 4 over
+given decays and gated inputs) at the shape the paper times it: batch 8, width 1024, a sweep of
+sequence lengths. Inputs are seeded and synthetic.
 """
 import argparse
 import json
@@ -183,18 +185,57 @@ def run_decode_workload(w, dev, out, steps=1000):
         del graph
 
 
+def run_scan_workload(dev, out, lengths=(1024, 4096, 16384, 65536)):
+    """rglru_scan at batch 8, width 1024 (Appendix A.3), bf16 storage: a_t and g_t read, h_t
+    written, 6 bytes per element; the state lives on chip."""
+    B, D = 8, 1024
+    gtor = torch.Generator(device=dev)
+    gtor.manual_seed(7)
+    for T in lengths:
+        per_set = 3 * 2 * B * T * D
+        nsets = int(min(8, max(1, -(-LLC_BYTES * 5 // 4 // per_set))))
+        sh = R.make_shape(B, T, D, 1, R.BF16)
+        n = R.rglru_workspace_bytes(sh, R.OP_SCAN)
+        ws = torch.empty(max(n, 256), dtype=torch.uint8, device=dev)
+        sets = []
+        for _ in range(nsets):
+            # decays distributed like the layer's: base^8 ~ U[0.9, 0.999], power 8 r with r ~ U(0, 1)
+            base = torch.empty(D, device=dev).uniform_(0.9, 0.999, generator=gtor) ** 0.125
+            la = torch.rand(B, T, D, device=dev, generator=gtor) * 8.0 * torch.log(base)
+            sets.append(dict(a=torch.exp(la).to(torch.bfloat16), la=la.to(torch.bfloat16),
+                             g=torch.randn(B, T, D, device=dev, generator=gtor).to(torch.bfloat16),
+                             h=torch.empty(B, T, D, dtype=torch.bfloat16, device=dev)))
+            del la
+        h0 = torch.randn(B, D, device=dev, generator=gtor)
+        hT = torch.empty(B, D, device=dev)
+        sp = torch.cuda.current_stream().cuda_stream
+        nbytes = per_set + 8 * B * D
+        note = "%d buffer set%s" % (nsets, "s" if nsets > 1 else "")
+        iters = 100 if T <= 16384 else 30
+        for key, flags, label in (("a", 0, "scan T=%d" % T), ("la", R.SCAN_LOG_A, "scan T=%d, log a_t" % T)):
+            def call(i):
+                st = sets[i]
+                R.rglru_scan(sh, st[key], st["g"], h0, flags, st["h"], hT, ws, n, sp)
+            ms = time_calls(call, nsets, iters, 10)
+            out.append(row("SCAN", label, note, ms, B * T, nbytes, 0))
+        del sets
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--configs", default="C0,C1,C2,C3,C4")
+    ap.add_argument("--configs", default="C0,C1,C2,C3,C4,SCAN")
     ap.add_argument("--json", action="store_true", help="print one JSON object per row instead of the table")
     args = ap.parse_args()
     dev = "cuda:0"
     torch.cuda.set_device(0)
     out = []
     for name in args.configs.split(","):
-        w = gen.CONFIGS[name]
         n0 = len(out)
-        if w.kind == "decode":
+        w = gen.CONFIGS.get(name)
+        if name == "SCAN":
+            run_scan_workload(dev, out)
+        elif w.kind == "decode":
             run_decode_workload(w, dev, out)
         else:
             run_sequence_workload(w, dev, out)
