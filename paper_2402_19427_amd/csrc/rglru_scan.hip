@@ -180,11 +180,12 @@ scan_tiled_kernel(ScanArgs a) {
   unsigned short *ot_mine = otile + (hf * 16) * OT + j;
   const unsigned hw_voff = (unsigned)(cg * BS + wv * 32 + (lane & 3) * 8) * 2 + (unsigned)(lane >> 2) * row_bytes;
 
-  // the tile whose local scan is complete but whose incoming state is not known yet: its
-  // (a_t, b_t) pairs and aggregates stay in registers for one iteration
+  // The tile whose local scan is complete but whose incoming state is not known yet keeps its
+  // (a_t, b_t) pairs and aggregates in registers for one iteration, while the next tile's are
+  // computed into the other set: [parity of the iteration]
   int held = -1;
-  float ha[16], hb[16];
-  float hA_lo = 1.f, hH_lo = 0.f, hA_t = 1.f, hH_t = 0.f;
+  float ha[2][16], hb[2][16];
+  float agg[2][4];   // A and H of the lower lane half's run, A and H of the whole tile
   u64 rec[GMAX > 1 ? GMAX - 1 : 1];   // one record per lane half (A below, H above)
 
   auto fetch_records = [&](int t) __attribute__((always_inline)) {
@@ -194,8 +195,9 @@ scan_tiled_kernel(ScanArgs a) {
       if (s < G - 1 && k >= 0) rec[s] = peek(ring + (size_t)(k % a.R) * 2 * BS + hf * BS);
     }
   };
-  // finish tile t: carry the state across the tiles of the other slices, write h
-  auto resolve = [&](int t) __attribute__((always_inline)) {
+  // finish tile t (register set P): carry the state across the tiles of the other slices, write h
+  auto resolve = [&](int t, auto par_c) __attribute__((always_inline)) {
+    constexpr int P = decltype(par_c)::value;
     float h = carry;
 #pragma unroll
     for (int s = 0; s < GMAX - 1; ++s) {
@@ -212,11 +214,11 @@ scan_tiled_kernel(ScanArgs a) {
         h = fmaf(hf ? other : mine, h, hf ? mine : other);
       }
     }
-    float hrun = hf ? fmaf(hA_lo, h, hH_lo) : h;  // state entering this lane's run
+    float hrun = hf ? fmaf(agg[P][0], h, agg[P][1]) : h;  // state entering this lane's run
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const float h0v = fmaf(ha[4 * q], hrun, hb[4 * q]), h1v = fmaf(ha[4 * q + 1], h0v, hb[4 * q + 1]);
-      const float h2v = fmaf(ha[4 * q + 2], h1v, hb[4 * q + 2]), h3v = fmaf(ha[4 * q + 3], h2v, hb[4 * q + 3]);
+      const float h0v = fmaf(ha[P][4 * q], hrun, hb[P][4 * q]), h1v = fmaf(ha[P][4 * q + 1], h0v, hb[P][4 * q + 1]);
+      const float h2v = fmaf(ha[P][4 * q + 2], h1v, hb[P][4 * q + 2]), h3v = fmaf(ha[P][4 * q + 3], h2v, hb[P][4 * q + 3]);
       hrun = h3v;
       const unsigned p0 = pack_bf16(h0v, h1v), p1 = pack_bf16(h2v, h3v);
       unsigned short *o = ot_mine + (4 * q) * OT;
@@ -229,14 +231,15 @@ scan_tiled_kernel(ScanArgs a) {
     store_staged_tile_s<OT, RGLRU_NT>(otile, lane, h_rsrc, hw_voff, (unsigned)(t * TT) * row_bytes, row_bytes,
                                       T - t * TT);
     wave_lds_fence();
-    carry = fmaf(hA_t, h, hH_t);
+    carry = fmaf(agg[P][2], h, agg[P][3]);
   };
 
-  // one tile: PAR is the parity of the iteration (register set and LDS buffer of the tile)
+  // one tile: PAR is the parity of the iteration (register sets and LDS buffer of the tile)
   auto step = [&](int tile, auto par_c) __attribute__((always_inline)) {
     constexpr int PAR = decltype(par_c)::value;
     const int t0 = tile * TT;
     // rows two tiles ahead into the register set this tile has left; records of the held tile
+    // (they land while this tile is scanned)
     if (tile + 2 * G < a.ntile) load_tile((tile + 2 * G) * TT, ra[PAR], rg[PAR]);
     if (GMAX > 1 && held >= 0) fetch_records(held);
     // the wave's 32 columns of a_t and g_t into accumulator layout
@@ -251,8 +254,6 @@ scan_tiled_kernel(ScanArgs a) {
       acca = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ta + 16), s1, acca, 0, 0, 0);
       accg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ta + SC_TILE / 2 + 16), s1, accg, 0, 0, 0);
     }
-    // finish the tile parked one iteration ago (its records were requested above)
-    if (GMAX > 1 && held >= 0) resolve(held);
     // local scan of this lane's 16-step run: prun = prod a, hrun = end state from zero
     float hrun = 0.f, prun = 1.f;
     const int nvalid = T - t0 - hf * 16;
@@ -266,22 +267,25 @@ scan_tiled_kernel(ScanArgs a) {
       }
       hrun = fmaf(av, hrun, bv);
       prun *= av;
-      ha[r] = av;
-      hb[r] = bv;
+      ha[PAR][r] = av;
+      hb[PAR][r] = bv;
     }
     {  // combine the two lane halves: lower half = steps 0..15, upper = 16..31
       const float oA = __shfl_xor(prun, 32), oH = __shfl_xor(hrun, 32);
-      hA_lo = hf ? oA : prun;
-      hH_lo = hf ? oH : hrun;
+      agg[PAR][0] = hf ? oA : prun;
+      agg[PAR][1] = hf ? oH : hrun;
       const float A_up = hf ? prun : oA, H_up = hf ? hrun : oH;
-      hA_t = hA_lo * A_up;
-      hH_t = fmaf(A_up, hH_lo, H_up);
+      agg[PAR][2] = agg[PAR][0] * A_up;
+      agg[PAR][3] = fmaf(A_up, agg[PAR][1], H_up);
     }
     if (GMAX > 1) {
-      publish(ring + (size_t)(tile % a.R) * 2 * BS + hf * BS, hf ? hH_t : hA_t, (unsigned)(tile + 1));
+      // the other slices wait for this aggregate, not for the outputs: publish first, then
+      // finish the tile parked one iteration ago
+      publish(ring + (size_t)(tile % a.R) * 2 * BS + hf * BS, hf ? agg[PAR][3] : agg[PAR][2], (unsigned)(tile + 1));
+      if (held >= 0) resolve(held, std::integral_constant<int, PAR ^ 1>{});
       held = tile;
     } else {
-      resolve(tile);
+      resolve(tile, par_c);
     }
     // rows of the next tile (requested one iteration ago) into the other LDS buffer
     if (tile + G < a.ntile) park_tile(PAR ^ 1, ra[PAR ^ 1], rg[PAR ^ 1]);
@@ -293,13 +297,19 @@ scan_tiled_kernel(ScanArgs a) {
   if (tile + G < a.ntile) load_tile((tile + G) * TT, ra[1], rg[1]);
   if (tile < a.ntile) park_tile(0, ra[0], rg[0]);
   __syncthreads();
+  int last_par = 0;
   for (; tile < a.ntile; tile += 2 * G) {
     step(tile, std::integral_constant<int, 0>{});
-    if (tile + G < a.ntile) step(tile + G, std::integral_constant<int, 1>{});
+    last_par = 0;
+    if (tile + G < a.ntile) {
+      step(tile + G, std::integral_constant<int, 1>{});
+      last_par = 1;
+    }
   }
   if (GMAX > 1 && held >= 0) {
     fetch_records(held);
-    resolve(held);
+    if (last_par) resolve(held, std::integral_constant<int, 1>{});
+    else resolve(held, std::integral_constant<int, 0>{});
     if (spins >= SPIN_LIMIT) *a.err = 1;
   }
   // the workgroup that ran the last tile owns the final state

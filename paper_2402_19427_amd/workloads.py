@@ -225,6 +225,7 @@ def run_scan_workload(dev, out, lengths=(1024, 4096, 16384, 65536)):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--configs", default="C0,C1,C2,C3,C4,SCAN")
+    ap.add_argument("--scan-lengths", default="1024,4096,16384,65536")
     ap.add_argument("--json", action="store_true", help="print one JSON object per row instead of the table")
     args = ap.parse_args()
     dev = "cuda:0"
@@ -234,7 +235,7 @@ def main():
         n0 = len(out)
         w = gen.CONFIGS.get(name)
         if name == "SCAN":
-            run_scan_workload(dev, out)
+            run_scan_workload(dev, out, tuple(int(x) for x in args.scan_lengths.split(",")))
         elif w.kind == "decode":
             run_decode_workload(w, dev, out)
         else:
