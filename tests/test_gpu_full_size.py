@@ -160,3 +160,28 @@ def test_c0_tiny_fp32_full_size():
                                       q["conv_w"])
     assert gen.rel_err(rn.to_host(y), y_ref) < 1e-5
     assert gen.rel_err(rn.to_host(hT), hT_ref) < 1e-5
+
+
+def test_scan_at_the_paper_s_measurement_shape_full_size():
+    """rglru_scan at batch 8, width 1024, 65536 steps (the longest length of the timing sweep):
+    channels are independent, so the oracle runs on a sample of them."""
+    import torch
+    import paper_2402_19427_amd as R
+    import paper_2402_19427_amd.runner as rn
+    B, T, D = 8, 65536, 1024
+    rng = np.random.Generator(np.random.PCG64(77))
+    base = rng.uniform(0.9, 0.999, size=D) ** 0.125
+    la = (8.0 * rng.uniform(0.0, 1.0, size=(B, T, D)).astype(np.float32) * np.log(base).astype(np.float32))
+    la = gen.round_to_act(la, "bf16")                       # log a_t as stored
+    g = gen.round_to_act(rng.standard_normal((B, T, D), dtype=np.float32), "bf16")
+    h0 = rng.standard_normal((B, D), dtype=np.float32)
+    h, hT = rn.scan(rn.to_device(la, "bf16"), rn.to_device(g, "bf16"), rn.to_device(h0, "f32"),
+                    flags=R.SCAN_LOG_A)
+    h_h, hT_h = rn.to_host(h), rn.to_host(hT)
+    del h
+    torch.cuda.empty_cache()
+    ch = np.arange(5, D, 37)                                 # 28 channels across all four groups
+    h_ref, hT_ref = oracle.scan(la[:, :, ch], g[:, :, ch], h0[:, ch], a_is_log=True)
+    assert gen.rel_err(h_h[:, :, ch], h_ref) < TOL
+    assert gen.rel_err(hT_h[:, ch], hT_ref) < 1e-4
+    assert np.isfinite(h_h).all()
