@@ -228,7 +228,8 @@ scan_tiled_kernel(ScanArgs a) {
       o[3 * OT] = (unsigned short)(p1 >> 16);
     }
     wave_lds_fence();
-    store_staged_tile_s<OT, RGLRU_NT>(otile, lane, h_rsrc, hw_voff, (unsigned)(t * TT) * row_bytes, row_bytes,
+    // (inputs are read non-temporally, outputs written through the cache: measured best)
+    store_staged_tile_s<OT, 0>(otile, lane, h_rsrc, hw_voff, (unsigned)(t * TT) * row_bytes, row_bytes,
                                       T - t * TT);
     wave_lds_fence();
     carry = fmaf(agg[P][2], h, agg[P][3]);
