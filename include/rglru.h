@@ -60,6 +60,7 @@ extern "C" {
 #define RGLRU_ERR_UNSUPPORTED (-2) /* dtype / conv width / block size with no kernel           */
 #define RGLRU_ERR_WORKSPACE (-3)   /* workspace NULL or smaller than rglru_workspace_bytes()   */
 #define RGLRU_ERR_HIP (-4)         /* a HIP runtime call or kernel launch failed               */
+#define RGLRU_ERR_TIMEOUT (-5)     /* rglru_workspace_status(): a bounded wait expired         */
 
 /* element types */
 #define RGLRU_F32 0
@@ -194,6 +195,18 @@ int rglru_backward(const rglru_shape *shape, const rglru_params *params, const v
 
 /* Bytes of workspace `op` (RGLRU_OP_*) needs for `shape`; 0 if none or if shape is invalid. */
 size_t rglru_workspace_bytes(const rglru_shape *shape, int op);
+
+/*
+ * Health check of a finished call (for tests and debugging: it synchronises). When sequences
+ * are cut into time slices, the workgroups of a launch hand carries to each other through
+ * records in `workspace`. Every wait on such a record is bounded; a wait that expires - it
+ * would mean that the workgroups of the launch were not all resident at once, which the launch
+ * sizes rule out - sets a flag in the workspace instead of hanging, and the outputs of that
+ * call are invalid. This function waits for `stream`, reads the flag left by the last call of
+ * `op` (RGLRU_OP_FORWARD, _BACKWARD or _SCAN) that ran with this `shape` and `workspace`, and
+ * returns RGLRU_OK or RGLRU_ERR_TIMEOUT (or RGLRU_ERR_INVALID_ARG / RGLRU_ERR_HIP).
+ */
+int rglru_workspace_status(const rglru_shape *shape, int op, const void *workspace, void *stream);
 
 /* Description of the last error returned on the calling thread ("" if none). */
 const char *rglru_last_error(void);

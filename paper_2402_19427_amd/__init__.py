@@ -9,7 +9,7 @@ ImportError (there is no fallback implementation).
 import importlib
 
 _EXPORTS = (
-    "BF16", "F32", "OK", "ERR_HIP", "ERR_INVALID_ARG", "ERR_UNSUPPORTED", "ERR_WORKSPACE",
+    "BF16", "F32", "OK", "ERR_HIP", "ERR_TIMEOUT", "rglru_workspace_status", "ERR_INVALID_ARG", "ERR_UNSUPPORTED", "ERR_WORKSPACE",
     "OP_BACKWARD", "OP_CONV1D", "OP_DECODE", "OP_FORWARD", "OP_SCAN", "SCAN_LOG_A",
     "SCAN_NO_INPUT_SCALE", "rglru_scan", "LIB_PATH", "ParamGrads", "Params",
     "RglruError", "Shape", "make_param_grads", "make_params", "make_shape", "rglru_backward",

@@ -10,7 +10,7 @@ import os
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("RGLRU_LIB", os.path.join(_PKG, "librglru.so"))
 
-OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_TIMEOUT = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
 OP_CONV1D, OP_FORWARD, OP_DECODE, OP_BACKWARD, OP_SCAN = 0, 1, 2, 3, 4
 SCAN_LOG_A, SCAN_NO_INPUT_SCALE = 1, 2
@@ -55,6 +55,8 @@ def _load():
     lib.rglru_decode_step.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp]
     lib.rglru_backward.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp, vp, vp, vp, gp, vp, sz, vp]
     lib.rglru_scan.argtypes = [sp, vp, vp, vp, ctypes.c_uint, vp, vp, vp, sz, vp]
+    lib.rglru_workspace_status.argtypes = [sp, ctypes.c_int, vp, vp]
+    lib.rglru_workspace_status.restype = ctypes.c_int
     lib.rglru_workspace_bytes.argtypes = [sp, ctypes.c_int]
     lib.rglru_workspace_bytes.restype = sz
     lib.rglru_last_error.restype = ctypes.c_char_p
@@ -177,3 +179,8 @@ def rglru_backward(shape, params, u, h0, conv_state_in, pos0, y, dy, dhT, du, dh
 def rglru_scan(shape, a, g, h0, flags, h, hT, workspace, workspace_bytes, stream=None):
     _check(_lib.rglru_scan(_ref(shape), _addr(a), _addr(g), _addr(h0), flags, _addr(h), _addr(hT),
                            _addr(workspace), workspace_bytes, _stream(stream)))
+
+
+def rglru_workspace_status(shape, op, workspace, stream=None):
+    """Waits for the stream and raises RglruError(ERR_TIMEOUT) if a bounded wait expired."""
+    _check(_lib.rglru_workspace_status(_ref(shape), op, _addr(workspace), _stream(stream)))

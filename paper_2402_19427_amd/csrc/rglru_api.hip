@@ -204,6 +204,31 @@ size_t rglru_workspace_bytes(const rglru_shape *shape, int op) {
   return workspace_need(shape, op);
 }
 
+int rglru_workspace_status(const rglru_shape *shape, int op, const void *workspace, void *stream) {
+  if (op != RGLRU_OP_FORWARD && op != RGLRU_OP_BACKWARD && op != RGLRU_OP_SCAN)
+    return fail(RGLRU_ERR_INVALID_ARG, "op %d has no workspace status", op);
+  CHECK(check_shape(shape, op != RGLRU_OP_SCAN, true, op == RGLRU_OP_BACKWARD ? 1 : 0));
+  const size_t need = workspace_need(shape, op);
+  hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+  if (need == 0) return RGLRU_OK;   // no time slices, no waits
+  if (!workspace) return fail(RGLRU_ERR_INVALID_ARG, "workspace is NULL");
+  size_t off = 0;   // forward and scan keep the flag in the first word
+  if (op == RGLRU_OP_BACKWARD) {
+    if (!(shape->act_dtype == RGLRU_BF16 && shape->D / shape->num_blocks == 256 &&
+          (size_t)shape->T * shape->D * 4 < ((size_t)1 << 32)))
+      return RGLRU_OK;              // the generic kernels do not wait on each other
+    off = backward_mfma_flag_offset(shape->B, shape->T, shape->D, shape->num_blocks);
+  }
+  int flag = 0;
+  e = hipMemcpy(&flag, (const char *)workspace + off, sizeof(flag), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hip_fail(e, "hipMemcpy");
+  if (flag != 0)
+    return fail(RGLRU_ERR_TIMEOUT, "a bounded wait between workgroups expired: the outputs of the call are invalid");
+  g_err[0] = 0;
+  return RGLRU_OK;
+}
+
 int rglru_conv1d(const rglru_shape *shape, const void *u, const float *conv_w,
                  const float *conv_b, const void *conv_state_in, int64_t pos0, void *x_out,
                  void *conv_state_out, void *stream) {

@@ -1224,6 +1224,12 @@ size_t backward_mfma_ws_bytes(int B, int T, int D, int nb) {
   return plan_backward(B, T, D, nb, 256).total;
 }
 
+size_t backward_mfma_flag_offset(int B, int T, int D, int nb) {
+  int ncu = num_cu();
+  if (ncu > 256) ncu = 256;
+  return plan_backward(B, T, D, nb, ncu).off_rec;   // the plan the launch uses
+}
+
 template <typename K>
 static hipError_t big_lds(K kernel, int bytes) {
   return hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);

@@ -165,3 +165,13 @@ def test_scan_validation():
             R.rglru_scan(big, FAKE, FAKE, None, 0, FAKE, None, None, 0)
         assert e.value.code == R.ERR_WORKSPACE
     assert R.rglru_workspace_bytes(R.make_shape(8, 4096, 1000, 1, R.F32), R.OP_SCAN) == 0
+
+
+def test_workspace_status_validation():
+    s = R.make_shape(2, 8, 16, 2, R.F32)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_workspace_status(s, R.OP_DECODE, FAKE)
+    assert e.value.code == R.ERR_INVALID_ARG
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_workspace_status(None, R.OP_FORWARD, FAKE)
+    assert e.value.code == R.ERR_INVALID_ARG

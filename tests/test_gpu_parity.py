@@ -336,3 +336,37 @@ def test_scan_without_h0_and_without_hT_and_empty():
     hT0 = torch.empty_like(h0)
     R.rglru_scan(R.make_shape(2, 0, 512, 1, R.BF16), None, None, h0, 0, None, hT0, None, 0)
     assert torch.equal(hT0, h0)
+
+
+def test_workspace_status_reports_an_expired_wait():
+    """After sliced calls the health check is clean; a flag planted from the host (no kernel
+    misbehaves for this) is reported as a timeout."""
+    import torch
+    import paper_2402_19427_amd as R
+    rn = runner()
+    B, T, D, nb = 1, 700, 256, 1          # one unit in 16 time slices: records cross workgroups
+    inp = gen.make_inputs(B, T, D, nb, act="bf16", seed=4, dy=True)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, "bf16")
+    u, dy = rn.to_device(inp["u"], "bf16"), rn.to_device(inp["dy"], "bf16")
+    y, _, _ = dp.forward(u)
+    dp.backward(u, y, dy)
+    sh = dp.shape()
+    for op in (R.OP_FORWARD, R.OP_BACKWARD):
+        ws, n = dp.workspace(sh, op)
+        assert n > 0
+        R.rglru_workspace_status(sh, op, ws)          # raises on a timeout
+    # scan
+    si = gen.make_scan_inputs(1, 3000, 256, act="bf16", seed=1)
+    a, g = rn.to_device(si["a"], "bf16"), rn.to_device(si["g"], "bf16")
+    ssh = R.make_shape(1, 3000, 256, 1, R.BF16)
+    n = R.rglru_workspace_bytes(ssh, R.OP_SCAN)
+    ws = torch.empty(n, dtype=torch.uint8, device="cuda:0")
+    h = torch.empty_like(a)
+    R.rglru_scan(ssh, a, g, None, 0, h, None, ws, n)
+    R.rglru_workspace_status(ssh, R.OP_SCAN, ws)
+    ws[:4] = torch.tensor([1, 0, 0, 0], dtype=torch.uint8, device="cuda:0")   # plant the flag
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_workspace_status(ssh, R.OP_SCAN, ws)
+    assert e.value.code == R.ERR_TIMEOUT
+    # shapes that run without time slices have nothing to report
+    R.rglru_workspace_status(R.make_shape(40, 70, 2048, 8, R.BF16), R.OP_FORWARD, None)
