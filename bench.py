@@ -181,6 +181,9 @@ def main():
     R.rglru_timing_enable(False)
     R.rglru_timing_select(None)
     dom_tot, dom_cnt = timed_kernels()[dominant]
+    # no bounded wait between workgroups expired during the run (raises otherwise)
+    R.rglru_workspace_status(sh, R.OP_FORWARD, ws_f)
+    R.rglru_workspace_status(sh, R.OP_BACKWARD, ws_b)
     dominant_ms = dom_tot / dom_cnt
 
     tokens = B * T + B
