@@ -111,6 +111,60 @@ def scan(a, g, h0=None, a_is_log=False, normalize=True):
     return h, hT
 
 
+def gelu(z, approx=False):
+    """GeLU(z) = z Phi(z) (Section 2.3's non-linearity); approx selects the tanh form."""
+    lib = _load()
+    lib.oracle_gelu.restype = ctypes.c_double
+    z = np.asarray(z, dtype=np.float64)
+    return np.array([lib.oracle_gelu(ctypes.c_double(v), int(bool(approx))) for v in z.ravel()]
+                    ).reshape(z.shape)
+
+
+def gelu_grad(z, approx=False):
+    lib = _load()
+    lib.oracle_gelu_grad.restype = ctypes.c_double
+    z = np.asarray(z, dtype=np.float64)
+    return np.array([lib.oracle_gelu_grad(ctypes.c_double(v), int(bool(approx)))
+                     for v in z.ravel()]).reshape(z.shape)
+
+
+def merge(y, branch, approx=False):
+    """The recurrent block's merge (Section 2.3): out = y * GeLU(branch), element by element."""
+    y, branch = _f64(y), _f64(branch)
+    assert y.shape == branch.shape
+    out = np.empty(y.shape)
+    _load().oracle_merge(ctypes.c_size_t(y.size), int(bool(approx)), _p(y), _p(branch), _p(out))
+    return out
+
+
+def merge_backward(y, branch, dout, approx=False):
+    """Adjoint of ``merge``: returns dy, dbranch."""
+    y, branch, dout = _f64(y), _f64(branch), _f64(dout)
+    assert y.shape == branch.shape == dout.shape
+    dy, dbranch = np.empty(y.shape), np.empty(y.shape)
+    _load().oracle_merge_backward(ctypes.c_size_t(y.size), int(bool(approx)), _p(y), _p(branch),
+                                  _p(dout), _p(dy), _p(dbranch))
+    return dy, dbranch
+
+
+def forward_merge(u, branch, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b=None, h0=None,
+                  state_in=None, c=8.0, approx=False):
+    """Conv1D -> RG-LRU -> merge with the other branch. Returns out, y, hT, state_out."""
+    y, hT, st = forward(u, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b, h0, state_in, c)
+    return merge(y, branch, approx), y, hT, st
+
+
+def backward_merge(u, branch, W_a, W_x, b_a, b_x, Lambda, conv_w, dout, conv_b=None, h0=None,
+                   state_in=None, dhT=None, c=8.0, approx=False):
+    """Adjoint of ``forward_merge`` for L = sum(dout*out) + sum(dhT*hT): the dict of
+    ``backward`` plus ``dbranch``."""
+    y, _, _ = forward(u, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b, h0, state_in, c)
+    dy, dbranch = merge_backward(y, branch, dout, approx)
+    out = backward(u, W_a, W_x, b_a, b_x, Lambda, conv_w, dy, conv_b, h0, state_in, dhT, c)
+    out["dbranch"] = dbranch
+    return out
+
+
 def forward(u, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b=None, h0=None, state_in=None, c=8.0):
     """Conv1D then RG-LRU. Returns y [B,T,D], hT [B,D], state_out [B,K-1,D] (chronological)."""
     u, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b, h0, state_in = map(

@@ -16,6 +16,8 @@
  *   - Block-diagonal gate weights: Section 4.1 "Recurrent Block".
  *   - Eq. (4) alone as a linear scan over given a_t (or log a_t) and gated
  *     inputs: Section 4.2 "A custom linear scan", Appendix A.3 "Scan runtimes".
+ *   - The block's merge, out = y * GeLU(other branch): Section 2.3 "Recurrent
+ *     block".
  *   - Backward: not printed in the paper; it is the adjoint of the forward
  *     equations, derived by hand (see oracle_backward below) and pinned by
  *     finite differences in the test suite.
@@ -28,6 +30,8 @@
  *     u_{t-k}), inputs before the start of the sequence come from a carried
  *     state when one is given and are zero otherwise; bias is optional.
  *   - x_t in eqs. (1)-(4) is the convolution output.
+ *   - GeLU is the exact z*Phi(z) of the cited reference unless the caller
+ *     selects that reference's tanh form; the paper does not say which.
  *   - h_{-1} = h0 if given, else 0; the sqrt(1-a^2) factor applies at t = 0
  *     like at any other step.
  *
@@ -53,6 +57,8 @@
 #ifdef _OPENMP
 #include <omp.h>
 #endif
+
+static const double PI = 3.14159265358979323846;
 
 static double sigmoid(double z) { return 1.0 / (1.0 + exp(-z)); }
 
@@ -198,6 +204,50 @@ void oracle_scan(int B, int T, int D, int a_is_log, int normalize,
       }
       if (hT) hT[(size_t)b * D + d] = s;
     }
+  }
+}
+
+/* ------------------------------------------------------------------------ */
+/* The recurrent block's merge (Section 2.3, "Recurrent block"): the output  */
+/* of the RG-LRU branch is multiplied element by element with GeLU of the    */
+/* other branch.  GeLU(z) = z * Phi(z) with Phi the standard normal CDF (the */
+/* definition of the cited reference); approx != 0 selects that reference's  */
+/* tanh form, 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))).               */
+/* ------------------------------------------------------------------------ */
+double oracle_gelu(double z, int approx) {
+  if (approx) {
+    const double k = sqrt(2.0 / PI) * (z + 0.044715 * z * z * z);
+    return 0.5 * z * (1.0 + tanh(k));
+  }
+  return 0.5 * z * (1.0 + erf(z / sqrt(2.0)));
+}
+
+/* d GeLU / dz: Phi(z) + z phi(z), or the derivative of the tanh form */
+double oracle_gelu_grad(double z, int approx) {
+  if (approx) {
+    const double s = sqrt(2.0 / PI);
+    const double th = tanh(s * (z + 0.044715 * z * z * z));
+    return 0.5 * (1.0 + th) +
+           0.5 * z * (1.0 - th * th) * s * (1.0 + 3.0 * 0.044715 * z * z);
+  }
+  return 0.5 * (1.0 + erf(z / sqrt(2.0))) +
+         z * exp(-0.5 * z * z) / sqrt(2.0 * PI);
+}
+
+/* out = y * GeLU(branch), n elements */
+void oracle_merge(size_t n, int approx, const double *y, const double *branch,
+                  double *out) {
+  for (size_t i = 0; i < n; ++i) out[i] = y[i] * oracle_gelu(branch[i], approx);
+}
+
+/* adjoint of oracle_merge: dy = dout * GeLU(branch),                        */
+/* dbranch = dout * y * GeLU'(branch)                                        */
+void oracle_merge_backward(size_t n, int approx, const double *y,
+                           const double *branch, const double *dout,
+                           double *dy, double *dbranch) {
+  for (size_t i = 0; i < n; ++i) {
+    dy[i] = dout[i] * oracle_gelu(branch[i], approx);
+    dbranch[i] = dout[i] * y[i] * oracle_gelu_grad(branch[i], approx);
   }
 }
 

@@ -469,3 +469,77 @@ def test_scan_on_the_layer_s_own_gates_reproduces_the_layer():
     # and the scale it applies is the layer's sqrt(1 - a^2)
     h3, _ = oracle.scan(gates["a"], gates["m"] * gates["i"] * x, q["h0"], normalize=False)
     np.testing.assert_allclose(h3, y, rtol=1e-11, atol=1e-13)
+
+
+# ------------------------------------------------------------------ the block's merge (Section 2.3)
+def test_gelu_is_z_times_the_normal_cdf():
+    from scipy.stats import norm
+    z = np.linspace(-8, 8, 801)
+    np.testing.assert_allclose(oracle.gelu(z), z * norm.cdf(z), rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(oracle.gelu_grad(z), norm.cdf(z) + z * norm.pdf(z), rtol=1e-13, atol=1e-15)
+    # table values of Phi: Phi(1) = 0.841344746..., Phi(2) = 0.977249868..., Phi(0.5) = 0.691462461...
+    np.testing.assert_allclose(oracle.gelu(np.array([0.0, 1.0, -1.0, 2.0, 0.5])),
+                               [0.0, 0.8413447460685429, -0.15865525393145707, 1.9544997361036416,
+                                0.34573123063700656], rtol=1e-14, atol=0)
+    assert oracle.gelu_grad(np.array([0.0]))[0] == 0.5
+    for approx in (False, True):      # z Phi(z) - (-z) Phi(-z) = z for either form
+        np.testing.assert_allclose(oracle.gelu(z, approx) - oracle.gelu(-z, approx), z, rtol=0, atol=1e-14)
+
+
+def test_gelu_tanh_form_stays_within_its_known_distance_of_the_exact_form():
+    z = np.linspace(-8, 8, 3201)
+    dev = np.abs(oracle.gelu(z, True) - oracle.gelu(z)).max()
+    assert 4.6e-4 < dev < 4.8e-4            # 4.73e-4 near |z| = 2.7; a wrong constant leaves this band
+    for approx in (False, True):
+        e = 1e-6
+        fd = (oracle.gelu(z + e, approx) - oracle.gelu(z - e, approx)) / (2 * e)
+        np.testing.assert_allclose(oracle.gelu_grad(z, approx), fd, rtol=0, atol=2e-9)
+
+
+@pytest.mark.parametrize("approx", [False, True])
+def test_merge_and_its_adjoint(approx):
+    rng = np.random.default_rng(11)
+    y, br, dout = (rng.standard_normal((2, 9, 6)) for _ in range(3))
+    out = oracle.merge(y, br, approx)
+    np.testing.assert_allclose(out, y * oracle.gelu(br, approx), rtol=0, atol=0)
+    dy, dbr = oracle.merge_backward(y, br, dout, approx)
+    e = 1e-6
+    for idx in [(0, 0, 0), (1, 8, 5), (0, 4, 3)]:
+        for which, got in (("y", dy), ("br", dbr)):
+            yp, ym, bp, bm = y.copy(), y.copy(), br.copy(), br.copy()
+            if which == "y":
+                yp[idx] += e
+                ym[idx] -= e
+            else:
+                bp[idx] += e
+                bm[idx] -= e
+            fd = (np.sum(dout * oracle.merge(yp, bp, approx)) - np.sum(dout * oracle.merge(ym, bm, approx))) / (2 * e)
+            assert abs(got[idx] - fd) < 1e-8
+
+
+def test_backward_merge_matches_finite_differences_through_the_whole_path():
+    inp = gen.make_inputs(2, 11, 16, 2, act="f32", seed=21, h0=True)
+    q = {k: (None if v is None else np.asarray(v, np.float64)) for k, v in inp.items()}
+    rng = np.random.default_rng(22)
+    br = rng.standard_normal(q["u"].shape)
+    dout = rng.standard_normal(q["u"].shape)
+    args = (q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"], q["conv_w"])
+
+    def loss(u, b):
+        return np.sum(dout * oracle.forward_merge(u, b, *args, h0=q["h0"])[0])
+
+    g = oracle.backward_merge(q["u"], br, *args, dout, h0=q["h0"])
+    e = 1e-6
+    for idx in [(0, 0, 0), (1, 10, 15), (0, 5, 7)]:
+        up, um = q["u"].copy(), q["u"].copy()
+        up[idx] += e
+        um[idx] -= e
+        assert abs(g["du"][idx] - (loss(up, br) - loss(um, br)) / (2 * e)) < 1e-7
+        bp, bm = br.copy(), br.copy()
+        bp[idx] += e
+        bm[idx] -= e
+        assert abs(g["dbranch"][idx] - (loss(q["u"], bp) - loss(q["u"], bm)) / (2 * e)) < 1e-7
+    # a branch of large positive values is the identity: GeLU(z) -> z, so out = y * z
+    big = np.full_like(br, 40.0)
+    out, y, _, _ = oracle.forward_merge(q["u"], big, *args, h0=q["h0"])
+    np.testing.assert_allclose(out, 40.0 * y, rtol=1e-14)
