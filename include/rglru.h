@@ -72,6 +72,8 @@ extern "C" {
 #define RGLRU_OP_DECODE 2
 #define RGLRU_OP_BACKWARD 3
 #define RGLRU_OP_SCAN 4
+#define RGLRU_OP_FORWARD_MERGE 5
+#define RGLRU_OP_BACKWARD_MERGE 6
 
 typedef struct rglru_shape {
   int32_t B;          /* sequences                                  (>= 1)                 */
@@ -193,6 +195,45 @@ int rglru_backward(const rglru_shape *shape, const rglru_params *params, const v
                    const rglru_param_grads *grads, void *workspace, size_t workspace_bytes,
                    void *stream);
 
+/* flags of the merge calls */
+#define RGLRU_MERGE_GELU_TANH 1u /* GeLU in its tanh form instead of z * Phi(z)             */
+
+/*
+ * Forward with the recurrent block's merge as its epilogue (Section 2.3, "Recurrent block":
+ * the RG-LRU branch is multiplied element by element with GeLU of the block's other branch):
+ *   out_t = y_t * GeLU(branch_t),   y = rglru_forward(u, ...).
+ * GeLU(z) = z * Phi(z), Phi the standard normal CDF; RGLRU_MERGE_GELU_TANH selects
+ * 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))). The product is formed from the unrounded
+ * fp32 h_t and rounded once to act.
+ *   branch     [B][T][D] act, read: the other branch before its non-linearity.
+ *   out        [B][T][D] act, written. May alias branch.
+ *   y          [B][T][D] act, written as by rglru_forward, or NULL (skipped). Training keeps
+ *              it for rglru_backward_merge; inference passes NULL and saves its write.
+ *   the other arguments, the workspace (RGLRU_OP_FORWARD_MERGE) and T == 0: as rglru_forward.
+ */
+int rglru_forward_merge(const rglru_shape *shape, const rglru_params *params, const void *u,
+                        const void *branch, const float *h0, const void *conv_state_in,
+                        int64_t pos0, unsigned flags, void *out, void *y, float *hT,
+                        void *conv_state_out, void *workspace, size_t workspace_bytes,
+                        void *stream);
+
+/*
+ * Backward of rglru_forward_merge for the loss L = sum(dout * out) + sum(dhT * hT): the
+ * adjoint of the merge, dy = dout * GeLU(branch) and dbranch = dout * y * GeLU'(branch),
+ * followed by rglru_backward on dy (dy is rounded to act in between, as it would be between
+ * two separate calls).
+ *   branch, y  [B][T][D] act: the forward call's input and its saved y.
+ *   dout       [B][T][D] act, upstream gradient of out.
+ *   dbranch    [B][T][D] act, written. May alias dout or branch.
+ *   the other arguments: as rglru_backward; workspace: RGLRU_OP_BACKWARD_MERGE.
+ */
+int rglru_backward_merge(const rglru_shape *shape, const rglru_params *params, const void *u,
+                         const void *branch, const float *h0, const void *conv_state_in,
+                         int64_t pos0, unsigned flags, const void *y, const void *dout,
+                         const float *dhT, void *du, void *dbranch, float *dh0,
+                         const rglru_param_grads *grads, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
 /* Bytes of workspace `op` (RGLRU_OP_*) needs for `shape`; 0 if none or if shape is invalid. */
 size_t rglru_workspace_bytes(const rglru_shape *shape, int op);
 
@@ -203,7 +244,7 @@ size_t rglru_workspace_bytes(const rglru_shape *shape, int op);
  * would mean that the workgroups of the launch were not all resident at once, which the launch
  * sizes rule out - sets a flag in the workspace instead of hanging, and the outputs of that
  * call are invalid. This function waits for `stream`, reads the flag left by the last call of
- * `op` (RGLRU_OP_FORWARD, _BACKWARD or _SCAN) that ran with this `shape` and `workspace`, and
+ * `op` (RGLRU_OP_FORWARD, _BACKWARD, _SCAN or a _MERGE variant) that ran with this `shape` and `workspace`, and
  * returns RGLRU_OK or RGLRU_ERR_TIMEOUT (or RGLRU_ERR_INVALID_ARG / RGLRU_ERR_HIP).
  */
 int rglru_workspace_status(const rglru_shape *shape, int op, const void *workspace, void *stream);

@@ -13,6 +13,8 @@ LIB_PATH = os.environ.get("RGLRU_LIB", os.path.join(_PKG, "librglru.so"))
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_TIMEOUT = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
 OP_CONV1D, OP_FORWARD, OP_DECODE, OP_BACKWARD, OP_SCAN = 0, 1, 2, 3, 4
+OP_FORWARD_MERGE, OP_BACKWARD_MERGE = 5, 6
+MERGE_GELU_TANH = 1
 SCAN_LOG_A, SCAN_NO_INPUT_SCALE = 1, 2
 
 
@@ -54,6 +56,9 @@ def _load():
     lib.rglru_forward.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp, vp, vp, sz, vp]
     lib.rglru_decode_step.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp]
     lib.rglru_backward.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp, vp, vp, vp, gp, vp, sz, vp]
+    lib.rglru_forward_merge.argtypes = [sp, pp, vp, vp, vp, vp, i64, ctypes.c_uint, vp, vp, vp, vp, vp, sz, vp]
+    lib.rglru_backward_merge.argtypes = [sp, pp, vp, vp, vp, vp, i64, ctypes.c_uint, vp, vp, vp, vp, vp, vp,
+                                         gp, vp, sz, vp]
     lib.rglru_scan.argtypes = [sp, vp, vp, vp, ctypes.c_uint, vp, vp, vp, sz, vp]
     lib.rglru_workspace_status.argtypes = [sp, ctypes.c_int, vp, vp]
     lib.rglru_workspace_status.restype = ctypes.c_int
@@ -174,6 +179,23 @@ def rglru_backward(shape, params, u, h0, conv_state_in, pos0, y, dy, dhT, du, dh
                                _addr(conv_state_in), pos0, _addr(y), _addr(dy), _addr(dhT),
                                _addr(du), _addr(dh0), _ref(grads), _addr(workspace),
                                workspace_bytes, _stream(stream)))
+
+
+def rglru_forward_merge(shape, params, u, branch, h0, conv_state_in, pos0, flags, out, y, hT,
+                        conv_state_out, workspace, workspace_bytes, stream=None):
+    _check(_lib.rglru_forward_merge(_ref(shape), _ref(params), _addr(u), _addr(branch), _addr(h0),
+                                    _addr(conv_state_in), pos0, flags, _addr(out), _addr(y),
+                                    _addr(hT), _addr(conv_state_out), _addr(workspace),
+                                    workspace_bytes, _stream(stream)))
+
+
+def rglru_backward_merge(shape, params, u, branch, h0, conv_state_in, pos0, flags, y, dout, dhT, du,
+                         dbranch, dh0, grads, workspace, workspace_bytes, stream=None):
+    _check(_lib.rglru_backward_merge(_ref(shape), _ref(params), _addr(u), _addr(branch), _addr(h0),
+                                     _addr(conv_state_in), pos0, flags, _addr(y), _addr(dout),
+                                     _addr(dhT), _addr(du), _addr(dbranch), _addr(dh0),
+                                     _ref(grads), _addr(workspace), workspace_bytes,
+                                     _stream(stream)))
 
 
 def rglru_scan(shape, a, g, h0, flags, h, hT, workspace, workspace_bytes, stream=None):

@@ -110,6 +110,11 @@ void fill_params(Problem &q, const rglru_shape *s, const rglru_params *p) {
   q.conv_w = p->conv_w; q.conv_b = p->conv_b;
 }
 
+size_t merge_dy_bytes(const rglru_shape *s) {
+  const size_t n = (size_t)s->B * s->T * s->D * (s->act_dtype == RGLRU_BF16 ? 2 : 4);
+  return (n + 255) & ~(size_t)255;
+}
+
 size_t workspace_need(const rglru_shape *s, int op) {
   switch (op) {
     case RGLRU_OP_BACKWARD:
@@ -121,6 +126,9 @@ size_t workspace_need(const rglru_shape *s, int op) {
       if (s->act_dtype == RGLRU_BF16 && s->D % 256 == 0 && s->T >= 1)
         return scan_tiled_ws_bytes(s->B, s->T, s->D);
       return 0;
+    case RGLRU_OP_BACKWARD_MERGE:   // dy between the merge adjoint and the backward, then the backward's own
+      return merge_dy_bytes(s) + workspace_need(s, RGLRU_OP_BACKWARD);
+    case RGLRU_OP_FORWARD_MERGE:
     case RGLRU_OP_FORWARD:
       if (s->act_dtype == RGLRU_BF16 && s->D / s->num_blocks == 256 && s->T >= 1)
         return forward_mfma_ws_bytes(s->B, s->T, s->D, s->num_blocks);
@@ -163,6 +171,37 @@ rglru::KernelTimer::~KernelTimer() {
   if (slot >= 0) (void)hipEventRecord(g_timed[slot].stop, s);
 }
 
+namespace {
+int backward_checks(const rglru_shape *shape, const rglru_params *params, const void *u,
+                    const float *h0, const void *conv_state_in, int64_t pos0, const void *y,
+                    const void *dy, const float *dhT, void *du, float *dh0,
+                    const rglru_param_grads *grads, void *workspace, size_t workspace_bytes) {
+  CHECK(check_shape(shape, true, true, 1));
+  CHECK(check_params(shape, params));
+  const size_t as = act_size(shape);
+  if (pos0 < 0) return fail(RGLRU_ERR_INVALID_ARG, "pos0 must be >= 0");
+  CHECK(check_ptr(u, "u", as, true));
+  CHECK(check_ptr(y, "y", as, true));
+  CHECK(check_ptr(dy, "dy", as, true));
+  CHECK(check_ptr(du, "du", as, true));
+  CHECK(check_ptr(h0, "h0", 4, false));
+  CHECK(check_ptr(dhT, "dhT", 4, false));
+  CHECK(check_ptr(dh0, "dh0", 4, false));
+  CHECK(check_ptr(conv_state_in, "conv_state_in", as, false));
+  if (!grads) return fail(RGLRU_ERR_INVALID_ARG, "grads is NULL");
+  CHECK(check_ptr(grads->dW_a, "grads.dW_a", 4, true));
+  CHECK(check_ptr(grads->dW_x, "grads.dW_x", 4, true));
+  CHECK(check_ptr(grads->db_a, "grads.db_a", 4, true));
+  CHECK(check_ptr(grads->db_x, "grads.db_x", 4, true));
+  CHECK(check_ptr(grads->dLambda, "grads.dLambda", 4, true));
+  CHECK(check_ptr(grads->dconv_w, "grads.dconv_w", 4, true));
+  CHECK(check_ptr(grads->dconv_b, "grads.dconv_b", 4, false));
+  CHECK(check_workspace(workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_BACKWARD)));
+
+  return RGLRU_OK;
+}
+}  // namespace
+
 extern "C" {
 
 int rglru_timing_enable(int enable) {
@@ -194,31 +233,35 @@ const char *rglru_last_error(void) { return g_err; }
 int rglru_version(void) { return 100; }
 
 size_t rglru_workspace_bytes(const rglru_shape *shape, int op) {
-  if (op < RGLRU_OP_CONV1D || op > RGLRU_OP_SCAN) return 0;
+  if (op < RGLRU_OP_CONV1D || op > RGLRU_OP_BACKWARD_MERGE) return 0;
   char keep[sizeof(g_err)];
   memcpy(keep, g_err, sizeof(g_err));
   const bool blocks = op != RGLRU_OP_CONV1D && op != RGLRU_OP_SCAN;
-  const int rc = check_shape(shape, blocks, op != RGLRU_OP_DECODE, op == RGLRU_OP_BACKWARD ? 1 : 0);
+  const bool bwd = op == RGLRU_OP_BACKWARD || op == RGLRU_OP_BACKWARD_MERGE;
+  const int rc = check_shape(shape, blocks, op != RGLRU_OP_DECODE, bwd ? 1 : 0);
   memcpy(g_err, keep, sizeof(g_err));  // a size query does not disturb the error string
   if (rc != RGLRU_OK) return 0;
   return workspace_need(shape, op);
 }
 
 int rglru_workspace_status(const rglru_shape *shape, int op, const void *workspace, void *stream) {
-  if (op != RGLRU_OP_FORWARD && op != RGLRU_OP_BACKWARD && op != RGLRU_OP_SCAN)
+  if (op != RGLRU_OP_FORWARD && op != RGLRU_OP_BACKWARD && op != RGLRU_OP_SCAN &&
+      op != RGLRU_OP_FORWARD_MERGE && op != RGLRU_OP_BACKWARD_MERGE)
     return fail(RGLRU_ERR_INVALID_ARG, "op %d has no workspace status", op);
-  CHECK(check_shape(shape, op != RGLRU_OP_SCAN, true, op == RGLRU_OP_BACKWARD ? 1 : 0));
+  const bool bwd = op == RGLRU_OP_BACKWARD || op == RGLRU_OP_BACKWARD_MERGE;
+  CHECK(check_shape(shape, op != RGLRU_OP_SCAN, true, bwd ? 1 : 0));
   const size_t need = workspace_need(shape, op);
   hipError_t e = hipStreamSynchronize((hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
   if (need == 0) return RGLRU_OK;   // no time slices, no waits
   if (!workspace) return fail(RGLRU_ERR_INVALID_ARG, "workspace is NULL");
   size_t off = 0;   // forward and scan keep the flag in the first word
-  if (op == RGLRU_OP_BACKWARD) {
+  if (bwd) {
     if (!(shape->act_dtype == RGLRU_BF16 && shape->D / shape->num_blocks == 256 &&
           (size_t)shape->T * shape->D * 4 < ((size_t)1 << 32)))
       return RGLRU_OK;              // the generic kernels do not wait on each other
     off = backward_mfma_flag_offset(shape->B, shape->T, shape->D, shape->num_blocks);
+    if (op == RGLRU_OP_BACKWARD_MERGE) off += merge_dy_bytes(shape);
   }
   int flag = 0;
   e = hipMemcpy(&flag, (const char *)workspace + off, sizeof(flag), hipMemcpyDeviceToHost);
@@ -352,28 +395,8 @@ int rglru_backward(const rglru_shape *shape, const rglru_params *params, const v
                    const void *dy, const float *dhT, void *du, float *dh0,
                    const rglru_param_grads *grads, void *workspace, size_t workspace_bytes,
                    void *stream) {
-  CHECK(check_shape(shape, true, true, 1));
-  CHECK(check_params(shape, params));
-  const size_t as = act_size(shape);
-  if (pos0 < 0) return fail(RGLRU_ERR_INVALID_ARG, "pos0 must be >= 0");
-  CHECK(check_ptr(u, "u", as, true));
-  CHECK(check_ptr(y, "y", as, true));
-  CHECK(check_ptr(dy, "dy", as, true));
-  CHECK(check_ptr(du, "du", as, true));
-  CHECK(check_ptr(h0, "h0", 4, false));
-  CHECK(check_ptr(dhT, "dhT", 4, false));
-  CHECK(check_ptr(dh0, "dh0", 4, false));
-  CHECK(check_ptr(conv_state_in, "conv_state_in", as, false));
-  if (!grads) return fail(RGLRU_ERR_INVALID_ARG, "grads is NULL");
-  CHECK(check_ptr(grads->dW_a, "grads.dW_a", 4, true));
-  CHECK(check_ptr(grads->dW_x, "grads.dW_x", 4, true));
-  CHECK(check_ptr(grads->db_a, "grads.db_a", 4, true));
-  CHECK(check_ptr(grads->db_x, "grads.db_x", 4, true));
-  CHECK(check_ptr(grads->dLambda, "grads.dLambda", 4, true));
-  CHECK(check_ptr(grads->dconv_w, "grads.dconv_w", 4, true));
-  CHECK(check_ptr(grads->dconv_b, "grads.dconv_b", 4, false));
-  CHECK(check_workspace(workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_BACKWARD)));
-
+  CHECK(backward_checks(shape, params, u, h0, conv_state_in, pos0, y, dy, dhT, du, dh0, grads, workspace,
+                        workspace_bytes));
   Problem q;
   memset(&q, 0, sizeof(q));
   fill_params(q, shape, params);
@@ -393,6 +416,87 @@ int rglru_backward(const rglru_shape *shape, const rglru_params *params, const v
   if (e != hipSuccess) return hip_fail(e, "backward launch");
   g_err[0] = 0;
   return RGLRU_OK;
+}
+
+int rglru_forward_merge(const rglru_shape *shape, const rglru_params *params, const void *u,
+                        const void *branch, const float *h0, const void *conv_state_in,
+                        int64_t pos0, unsigned flags, void *out, void *y, float *hT,
+                        void *conv_state_out, void *workspace, size_t workspace_bytes,
+                        void *stream) {
+  CHECK(check_shape(shape, true, true, 0));
+  CHECK(check_params(shape, params));
+  if (flags & ~RGLRU_MERGE_GELU_TANH) return fail(RGLRU_ERR_INVALID_ARG, "unknown merge flags 0x%x", flags);
+  const size_t as = act_size(shape);
+  if (pos0 < 0) return fail(RGLRU_ERR_INVALID_ARG, "pos0 must be >= 0");
+  CHECK(check_ptr(u, "u", as, shape->T > 0));
+  CHECK(check_ptr(branch, "branch", as, shape->T > 0));
+  CHECK(check_ptr(out, "out", as, shape->T > 0));
+  CHECK(check_ptr(y, "y", as, false));
+  CHECK(check_ptr(h0, "h0", 4, false));
+  CHECK(check_ptr(hT, "hT", 4, false));
+  CHECK(check_ptr(conv_state_in, "conv_state_in", as, false));
+  CHECK(check_ptr(conv_state_out, "conv_state_out", as, false));
+  CHECK(check_workspace(workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_FORWARD_MERGE)));
+  if (shape->T > 0 && (out == y || out == branch || out == u))
+    return fail(RGLRU_ERR_INVALID_ARG, "out must not alias y, branch or u");
+
+  Problem q;
+  memset(&q, 0, sizeof(q));
+  fill_params(q, shape, params);
+  q.pos0 = pos0; q.u = u; q.h0 = h0; q.state_in = conv_state_in;
+  q.hT = hT; q.state_out = conv_state_out;
+  q.ws = workspace; q.ws_bytes = workspace_bytes;
+  const bool bf = shape->act_dtype == RGLRU_BF16;
+  const bool tanh_form = (flags & RGLRU_MERGE_GELU_TANH) != 0;
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t e;
+  // without the fused epilogue: y goes to its own buffer, or through `out` when it is not kept
+  q.y = y ? y : out;
+  if (forward_mfma_supported(q, bf)) {
+    e = launch_forward_mfma(q, s);
+    if (e != hipSuccess) return hip_fail(e, "forward launch");
+  } else {
+    e = launch_forward_generic(q, bf, s);
+    if (e != hipSuccess) return hip_fail(e, "forward launch");
+    e = launch_state_update(q, bf, s);
+    if (e != hipSuccess) return hip_fail(e, "conv state launch");
+  }
+  e = launch_merge_forward(q.y, branch, out, (size_t)shape->B * shape->T * shape->D, bf, tanh_form, s);
+  if (e != hipSuccess) return hip_fail(e, "merge launch");
+  g_err[0] = 0;
+  return RGLRU_OK;
+}
+
+int rglru_backward_merge(const rglru_shape *shape, const rglru_params *params, const void *u,
+                         const void *branch, const float *h0, const void *conv_state_in,
+                         int64_t pos0, unsigned flags, const void *y, const void *dout,
+                         const float *dhT, void *du, void *dbranch, float *dh0,
+                         const rglru_param_grads *grads, void *workspace,
+                         size_t workspace_bytes, void *stream) {
+  CHECK(check_shape(shape, true, true, 1));
+  if (flags & ~RGLRU_MERGE_GELU_TANH) return fail(RGLRU_ERR_INVALID_ARG, "unknown merge flags 0x%x", flags);
+  const size_t as = act_size(shape);
+  CHECK(check_ptr(branch, "branch", as, true));
+  CHECK(check_ptr(y, "y", as, true));
+  CHECK(check_ptr(dout, "dout", as, true));
+  CHECK(check_ptr(dbranch, "dbranch", as, true));
+  CHECK(check_workspace(workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_BACKWARD_MERGE)));
+  if (dbranch == y || dbranch == u || dbranch == du)
+    return fail(RGLRU_ERR_INVALID_ARG, "dbranch must not alias y, u or du");
+  // the rest of the arguments are checked by rglru_backward before anything is launched:
+  // a dry run of its checks first, so that a bad argument leaves every output untouched
+  const size_t dyb = merge_dy_bytes(shape);
+  void *dy = workspace;
+  void *rest = (char *)workspace + dyb;
+  CHECK(backward_checks(shape, params, u, h0, conv_state_in, pos0, y, dy, dhT, du, dh0, grads, rest,
+                        workspace_bytes - dyb));
+  const bool bf = shape->act_dtype == RGLRU_BF16;
+  hipError_t e = launch_merge_backward(y, branch, dout, dy, dbranch,
+                                       (size_t)shape->B * shape->T * shape->D, bf,
+                                       (flags & RGLRU_MERGE_GELU_TANH) != 0, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "merge launch");
+  return rglru_backward(shape, params, u, h0, conv_state_in, pos0, y, dy, dhT, du, dh0, grads, rest,
+                        workspace_bytes - dyb, stream);
 }
 
 }  // extern "C"

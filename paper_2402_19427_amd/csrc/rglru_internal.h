@@ -54,6 +54,10 @@ struct Problem {
   rglru_param_grads g;
   void *ws;
   size_t ws_bytes;
+  // merge epilogue (forward): out = y * GeLU(branch) goes to `out`, y itself to `y` if not null
+  int merge;            // 0 none, 1 GeLU = z Phi(z), 2 tanh form
+  const void *branch;
+  void *out;
 };
 
 // One rglru_scan call.
@@ -106,5 +110,14 @@ hipError_t launch_scan_generic(const ScanProblem &p, bool bf, hipStream_t s);
 bool scan_tiled_supported(const ScanProblem &p, bool bf);
 size_t scan_tiled_ws_bytes(int B, int T, int D);
 hipError_t launch_scan_tiled(const ScanProblem &p, hipStream_t s);
+
+
+// The recurrent block's merge as kernels of its own (any shape and storage type)
+//   forward:  out = y * GeLU(branch), n elements; out may alias y or branch
+//   backward: dy = dout * GeLU(branch), dbranch = dout * y * GeLU'(branch)
+hipError_t launch_merge_forward(const void *y, const void *branch, void *out, size_t n, bool bf,
+                                bool tanh_form, hipStream_t s);
+hipError_t launch_merge_backward(const void *y, const void *branch, const void *dout, void *dy,
+                                 void *dbranch, size_t n, bool bf, bool tanh_form, hipStream_t s);
 
 }  // namespace rglru

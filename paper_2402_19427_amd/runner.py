@@ -82,6 +82,19 @@ class DeviceProblem:
         R.rglru_forward(sh, self.params, u, h0, state_in, pos0, y, hT, st, ws, n, stream)
         return y, hT, st
 
+    def forward_merge(self, u, branch, h0=None, state_in=None, pos0=0, flags=0, keep_y=True,
+                      stream=None):
+        B, T, D = u.shape
+        sh = self.shape(T=T, B=B)
+        ws, n = self.workspace(sh, R.OP_FORWARD_MERGE)
+        out = self.empty_act(B, T, D)
+        y = self.empty_act(B, T, D) if keep_y else None
+        hT = self.empty_f32(B, D)
+        st = self.empty_act(B, 3, D)
+        R.rglru_forward_merge(sh, self.params, u, branch, h0, state_in, pos0, flags, out, y, hT, st,
+                              ws, n, stream)
+        return out, y, hT, st
+
     def decode_step(self, u_t, h, conv_state, pos, stream=None):
         B, D = u_t.shape
         sh = self.shape(T=1, B=B)
@@ -111,6 +124,24 @@ class DeviceProblem:
                          stream)
         out = dict(g)
         out["du"], out["dh0"] = du, dh0
+        return out
+
+
+    def backward_merge(self, u, branch, y, dout, h0=None, state_in=None, pos0=0, dhT=None, flags=0,
+                       grads=None, stream=None):
+        B, T, D = u.shape
+        sh = self.shape(T=T, B=B)
+        ws, n = self.workspace(sh, R.OP_BACKWARD_MERGE)
+        du = self.empty_act(B, T, D)
+        dbranch = self.empty_act(B, T, D)
+        dh0 = self.empty_f32(B, D)
+        g = grads if grads is not None else self.alloc_grads()
+        pg = R.make_param_grads(g["dW_a"], g["dW_x"], g["db_a"], g["db_x"], g["dLambda"],
+                                g["dconv_w"], g["dconv_b"])
+        R.rglru_backward_merge(sh, self.params, u, branch, h0, state_in, pos0, flags, y, dout, dhT,
+                               du, dbranch, dh0, pg, ws, n, stream)
+        out = dict(g)
+        out["du"], out["dbranch"], out["dh0"] = du, dbranch, dh0
         return out
 
 

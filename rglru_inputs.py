@@ -138,6 +138,14 @@ def make_scan_inputs(B, T, D, act="bf16", seed=0, log_a=False, h0=True):
     return out
 
 
+def make_branch(B, T, D, act="bf16", seed=0):
+    """Seeded stand-in for the recurrent block's second branch before its GeLU (the output of a
+    linear layer on a normalised input): N(0, 1) values, exactly representable in `act`.
+    Returns float32 [B,T,D]."""
+    rng = np.random.Generator(np.random.PCG64(seed + 7919))
+    return round_to_act(rng.standard_normal((B, T, D), dtype=np.float32), act)
+
+
 def make_workload(name, **override):
     """Inputs of one of the named workloads C0..C4 (sizes may be overridden for sampling)."""
     w = CONFIGS[name]

@@ -175,3 +175,36 @@ def test_workspace_status_validation():
     with pytest.raises(R.RglruError) as e:
         R.rglru_workspace_status(None, R.OP_FORWARD, FAKE)
     assert e.value.code == R.ERR_INVALID_ARG
+
+
+def test_merge_calls_validation_and_workspace():
+    s = R.make_shape(2, 8, 16, 2, R.BF16)
+    OUT, Y = FAKE + 4096, FAKE + 8192
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_forward_merge(s, params(), FAKE, None, None, None, 0, 0, OUT, None, None, None, None, 0)
+    assert e.value.code == R.ERR_INVALID_ARG and "branch is NULL" in str(e.value)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_forward_merge(s, params(), FAKE, FAKE, None, None, 0, 2, OUT, None, None, None, None, 0)
+    assert e.value.code == R.ERR_INVALID_ARG and "flags" in str(e.value)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_forward_merge(s, params(), FAKE, Y, None, None, 0, 0, Y, None, None, None, None, 0)
+    assert e.value.code == R.ERR_INVALID_ARG and "alias" in str(e.value)
+    # the backward needs room for dy on top of the plain backward's workspace
+    plain = R.rglru_workspace_bytes(s, R.OP_BACKWARD)
+    need = R.rglru_workspace_bytes(s, R.OP_BACKWARD_MERGE)
+    assert need == plain + 2 * 8 * 16 * 2 and need % 256 == 0
+    assert R.rglru_workspace_bytes(s, R.OP_FORWARD_MERGE) == R.rglru_workspace_bytes(s, R.OP_FORWARD)
+    g = R.make_param_grads(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)
+    args = (s, params(), FAKE, FAKE, None, None, 0, 0, Y, FAKE, None, OUT, FAKE + 12288, None, g)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_backward_merge(*args, FAKE, need - 1)
+    assert e.value.code == R.ERR_WORKSPACE
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_backward_merge(s, params(), FAKE, FAKE, None, None, 0, 0, Y, FAKE, None, OUT, None, None, g,
+                               FAKE, need)
+    assert e.value.code == R.ERR_INVALID_ARG and "dbranch is NULL" in str(e.value)
+    g2 = R.make_param_grads(FAKE, FAKE, None, FAKE, FAKE, FAKE)
+    with pytest.raises(R.RglruError) as e:   # found by the plain backward's checks, before any launch
+        R.rglru_backward_merge(s, params(), FAKE, FAKE, None, None, 0, 0, Y, FAKE, None, OUT, FAKE + 12288,
+                               None, g2, FAKE, need)
+    assert e.value.code == R.ERR_INVALID_ARG and "db_a" in str(e.value)

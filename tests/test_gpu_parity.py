@@ -370,3 +370,88 @@ def test_workspace_status_reports_an_expired_wait():
     assert e.value.code == R.ERR_TIMEOUT
     # shapes that run without time slices have nothing to report
     R.rglru_workspace_status(R.make_shape(40, 70, 2048, 8, R.BF16), R.OP_FORWARD, None)
+
+
+# ------------------------------------------------------------------ the block's merge as epilogue
+MERGE_SHAPES = [
+    (2, 37, 96, 3, "f32"),       # generic kernels, ragged T
+    (1, 9, 24, 24, "bf16"),      # generic kernels, element count not a multiple of 8... (216)
+    (3, 5, 40, 5, "f32"),
+    (2, 130, 512, 2, "bf16"),    # MFMA path, ragged T
+    (33, 70, 1024, 4, "bf16"),   # MFMA path, one workgroup per unit
+    (8, 600, 2048, 8, "bf16"),   # MFMA path, time slices
+]
+
+
+@pytest.mark.parametrize("B,T,D,nb,act", MERGE_SHAPES)
+@pytest.mark.parametrize("tanh_form", [False, True])
+@pytest.mark.parametrize("keep_y", [False, True])
+def test_forward_merge_matches_oracle(B, T, D, nb, act, tanh_form, keep_y):
+    import paper_2402_19427_amd as R
+    rn = runner()
+    inp = gen.make_inputs(B, T, D, nb, act=act, seed=3 * B + T + D, h0=True, bias=True)
+    br = gen.make_branch(B, T, D, act=act, seed=T)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    out, y, hT, st = dp.forward_merge(rn.to_device(inp["u"], act), rn.to_device(br, act),
+                                      h0=rn.to_device(inp["h0"], "f32"),
+                                      flags=R.MERGE_GELU_TANH if tanh_form else 0, keep_y=keep_y)
+    q = f64(inp)
+    out_ref, y_ref, hT_ref, st_ref = oracle.forward_merge(
+        q["u"], br, q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"], q["conv_w"],
+        conv_b=q.get("conv_b"), h0=q["h0"], approx=tanh_form)
+    assert gen.rel_err(rn.to_host(out), out_ref) < TOL[act]
+    assert gen.rel_err(rn.to_host(hT), hT_ref) < TOL[act]
+    if keep_y:
+        assert gen.rel_err(rn.to_host(y), y_ref) < TOL[act]
+    np.testing.assert_array_equal(gen.chrono_from_ring(rn.to_host(st), T), st_ref)
+
+
+@pytest.mark.parametrize("B,T,D,nb,act", [(2, 37, 96, 3, "f32"), (1, 9, 24, 24, "bf16"),
+                                          (2, 130, 512, 2, "bf16"), (8, 600, 2048, 8, "bf16")])
+@pytest.mark.parametrize("tanh_form", [False, True])
+def test_backward_merge_matches_oracle(B, T, D, nb, act, tanh_form):
+    import paper_2402_19427_amd as R
+    rn = runner()
+    inp = gen.make_inputs(B, T, D, nb, act=act, seed=5 * B + T + D, h0=True, dy=True, bias=True)
+    br = gen.make_branch(B, T, D, act=act, seed=T + 1)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    flags = R.MERGE_GELU_TANH if tanh_form else 0
+    u, brd, h0 = rn.to_device(inp["u"], act), rn.to_device(br, act), rn.to_device(inp["h0"], "f32")
+    out, y, hT, st = dp.forward_merge(u, brd, h0=h0, flags=flags)
+    dhT = rn.to_device(inp["dhT"], "f32")
+    g = dp.backward_merge(u, brd, y, rn.to_device(inp["dy"], act), h0=h0, dhT=dhT, flags=flags)
+    q = f64(inp)
+    # the call is defined as the merge adjoint followed by the backward, with dy stored in the
+    # activation type in between: the oracle is composed the same way (in bf16 that one rounding
+    # alone moves single elements of dW_a by more than the bar, measured on the oracle)
+    args = (q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"], q["conv_w"])
+    y_ref, _, _ = oracle.forward(q["u"], *args, conv_b=q.get("conv_b"), h0=q["h0"])
+    dy_ref, dbr_ref = oracle.merge_backward(y_ref, br, q["dy"], approx=tanh_form)
+    dy_ref = gen.round_to_act(dy_ref.astype(np.float32), act).astype(np.float64)
+    ref = oracle.backward(q["u"], *args, dy_ref, conv_b=q.get("conv_b"), h0=q["h0"], dhT=q["dhT"])
+    ref["dbranch"] = dbr_ref
+    for k in ("du", "dbranch", "dh0"):
+        assert gen.rel_err(rn.to_host(g[k]), ref[k]) < TOL[act], k
+    for k in ("dW_a", "dW_x", "db_a", "db_x", "dLambda", "dconv_w", "dconv_b"):
+        assert gen.rel_err(rn.to_host(g[k]), ref[k]) < GRAD_TOL[act], k
+    sh = dp.shape()
+    ws, _ = dp.workspace(sh, R.OP_BACKWARD_MERGE)
+    R.rglru_workspace_status(sh, R.OP_BACKWARD_MERGE, ws)
+
+
+def test_merge_calls_reject_bad_arguments():
+    import paper_2402_19427_amd as R
+    rn = runner()
+    B, T, D, nb = 1, 4, 32, 2
+    inp = gen.make_inputs(B, T, D, nb, act="bf16", seed=1)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, "bf16")
+    u = rn.to_device(inp["u"], "bf16")
+    sh = dp.shape()
+    ws, n = dp.workspace(sh, R.OP_FORWARD_MERGE)
+    out = dp.empty_act(B, T, D)
+    with pytest.raises(R.RglruError):       # out aliases branch
+        R.rglru_forward_merge(sh, dp.params, u, out, None, None, 0, 0, out, None, None, None, ws, n)
+    with pytest.raises(R.RglruError):       # unknown flag
+        R.rglru_forward_merge(sh, dp.params, u, u, None, None, 0, 8, out, None, None, None, ws, n)
+    with pytest.raises(R.RglruError):       # branch missing
+        R.rglru_forward_merge(sh, dp.params, u, None, None, None, 0, 0, out, None, None, None, ws, n)
