@@ -197,6 +197,9 @@ int rglru_backward(const rglru_shape *shape, const rglru_params *params, const v
 
 /* flags of the merge calls */
 #define RGLRU_MERGE_GELU_TANH 1u /* GeLU in its tanh form instead of z * Phi(z)             */
+#define RGLRU_MERGE_SEPARATE 2u  /* forward: run the merge as a kernel of its own after the  */
+                                 /* recurrence instead of as its epilogue (same results up  */
+                                 /* to rounding; for measurements)                          */
 
 /*
  * Forward with the recurrent block's merge as its epilogue (Section 2.3, "Recurrent block":
@@ -216,6 +219,16 @@ int rglru_forward_merge(const rglru_shape *shape, const rglru_params *params, co
                         int64_t pos0, unsigned flags, void *out, void *y, float *hT,
                         void *conv_state_out, void *workspace, size_t workspace_bytes,
                         void *stream);
+
+/*
+ * One decode step with the merge as its epilogue: rglru_decode_step, then
+ * out_t = y_t * GeLU(branch_t) is what is written (RGLRU_MERGE_SEPARATE is not accepted).
+ *   branch_t   [B][D] act, read.
+ *   out_t      [B][D] act, written. Must not alias branch_t or u_t.
+ */
+int rglru_decode_step_merge(const rglru_shape *shape, const rglru_params *params, const void *u_t,
+                            const void *branch_t, float *h, void *conv_state, int64_t pos,
+                            unsigned flags, void *out_t, void *stream);
 
 /*
  * Backward of rglru_forward_merge for the loss L = sum(dout * out) + sum(dhT * hT): the

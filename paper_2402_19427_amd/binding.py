@@ -14,7 +14,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_TIMEOUT = 0, -
 F32, BF16 = 0, 1
 OP_CONV1D, OP_FORWARD, OP_DECODE, OP_BACKWARD, OP_SCAN = 0, 1, 2, 3, 4
 OP_FORWARD_MERGE, OP_BACKWARD_MERGE = 5, 6
-MERGE_GELU_TANH = 1
+MERGE_GELU_TANH, MERGE_SEPARATE = 1, 2
 SCAN_LOG_A, SCAN_NO_INPUT_SCALE = 1, 2
 
 
@@ -59,6 +59,7 @@ def _load():
     lib.rglru_forward_merge.argtypes = [sp, pp, vp, vp, vp, vp, i64, ctypes.c_uint, vp, vp, vp, vp, vp, sz, vp]
     lib.rglru_backward_merge.argtypes = [sp, pp, vp, vp, vp, vp, i64, ctypes.c_uint, vp, vp, vp, vp, vp, vp,
                                          gp, vp, sz, vp]
+    lib.rglru_decode_step_merge.argtypes = [sp, pp, vp, vp, vp, vp, i64, ctypes.c_uint, vp, vp]
     lib.rglru_scan.argtypes = [sp, vp, vp, vp, ctypes.c_uint, vp, vp, vp, sz, vp]
     lib.rglru_workspace_status.argtypes = [sp, ctypes.c_int, vp, vp]
     lib.rglru_workspace_status.restype = ctypes.c_int
@@ -187,6 +188,13 @@ def rglru_forward_merge(shape, params, u, branch, h0, conv_state_in, pos0, flags
                                     _addr(conv_state_in), pos0, flags, _addr(out), _addr(y),
                                     _addr(hT), _addr(conv_state_out), _addr(workspace),
                                     workspace_bytes, _stream(stream)))
+
+
+def rglru_decode_step_merge(shape, params, u_t, branch_t, h, conv_state, pos, flags, out_t,
+                            stream=None):
+    _check(_lib.rglru_decode_step_merge(_ref(shape), _ref(params), _addr(u_t), _addr(branch_t),
+                                        _addr(h), _addr(conv_state), pos, flags, _addr(out_t),
+                                        _stream(stream)))
 
 
 def rglru_backward_merge(shape, params, u, branch, h0, conv_state_in, pos0, flags, y, dout, dhT, du,

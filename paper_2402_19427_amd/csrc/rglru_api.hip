@@ -425,7 +425,8 @@ int rglru_forward_merge(const rglru_shape *shape, const rglru_params *params, co
                         void *stream) {
   CHECK(check_shape(shape, true, true, 0));
   CHECK(check_params(shape, params));
-  if (flags & ~RGLRU_MERGE_GELU_TANH) return fail(RGLRU_ERR_INVALID_ARG, "unknown merge flags 0x%x", flags);
+  if (flags & ~(RGLRU_MERGE_GELU_TANH | RGLRU_MERGE_SEPARATE))
+    return fail(RGLRU_ERR_INVALID_ARG, "unknown merge flags 0x%x", flags);
   const size_t as = act_size(shape);
   if (pos0 < 0) return fail(RGLRU_ERR_INVALID_ARG, "pos0 must be >= 0");
   CHECK(check_ptr(u, "u", as, shape->T > 0));
@@ -450,7 +451,15 @@ int rglru_forward_merge(const rglru_shape *shape, const rglru_params *params, co
   const bool tanh_form = (flags & RGLRU_MERGE_GELU_TANH) != 0;
   hipStream_t s = (hipStream_t)stream;
   hipError_t e;
+  q.merge = tanh_form ? 2 : 1; q.branch = branch; q.out = out; q.y = y;
+  if (!(flags & RGLRU_MERGE_SEPARATE) && forward_mfma_supported(q, bf)) {   // the merge is the kernel's epilogue
+    e = launch_forward_mfma(q, s);
+    if (e != hipSuccess) return hip_fail(e, "forward launch");
+    g_err[0] = 0;
+    return RGLRU_OK;
+  }
   // without the fused epilogue: y goes to its own buffer, or through `out` when it is not kept
+  q.merge = 0;
   q.y = y ? y : out;
   if (forward_mfma_supported(q, bf)) {
     e = launch_forward_mfma(q, s);
@@ -463,6 +472,46 @@ int rglru_forward_merge(const rglru_shape *shape, const rglru_params *params, co
   }
   e = launch_merge_forward(q.y, branch, out, (size_t)shape->B * shape->T * shape->D, bf, tanh_form, s);
   if (e != hipSuccess) return hip_fail(e, "merge launch");
+  g_err[0] = 0;
+  return RGLRU_OK;
+}
+
+int rglru_decode_step_merge(const rglru_shape *shape, const rglru_params *params, const void *u_t,
+                            const void *branch_t, float *h, void *conv_state, int64_t pos,
+                            unsigned flags, void *out_t, void *stream) {
+  CHECK(check_shape(shape, true, false, 0));
+  CHECK(check_params(shape, params));
+  if (flags & ~RGLRU_MERGE_GELU_TANH) return fail(RGLRU_ERR_INVALID_ARG, "unknown merge flags 0x%x", flags);
+  const size_t as = act_size(shape);
+  if (pos < 0) return fail(RGLRU_ERR_INVALID_ARG, "pos must be >= 0");
+  CHECK(check_ptr(u_t, "u_t", as, true));
+  CHECK(check_ptr(branch_t, "branch_t", as, true));
+  CHECK(check_ptr(h, "h", 4, true));
+  CHECK(check_ptr(conv_state, "conv_state", as, true));
+  CHECK(check_ptr(out_t, "out_t", as, true));
+  if (out_t == branch_t || out_t == u_t)
+    return fail(RGLRU_ERR_INVALID_ARG, "out_t must not alias branch_t or u_t");
+
+  Problem q;
+  memset(&q, 0, sizeof(q));
+  fill_params(q, shape, params);
+  q.T = 1; q.pos0 = pos; q.u = u_t; q.hT = h; q.state_in = conv_state;
+  q.state_out = conv_state; q.y = out_t;
+  const bool bf = shape->act_dtype == RGLRU_BF16;
+  const bool tanh_form = (flags & RGLRU_MERGE_GELU_TANH) != 0;
+  hipStream_t s = (hipStream_t)stream;
+  q.merge = tanh_form ? 2 : 1; q.branch = branch_t;
+  hipError_t e;
+  if (decode_mfma_supported(q, bf)) {
+    e = launch_decode_mfma(q, s);
+    if (e != hipSuccess) return hip_fail(e, "decode launch");
+  } else {
+    q.merge = 0;
+    e = launch_decode_generic(q, bf, s);
+    if (e != hipSuccess) return hip_fail(e, "decode launch");
+    e = launch_merge_forward(out_t, branch_t, out_t, (size_t)shape->B * shape->D, bf, tanh_form, s);
+    if (e != hipSuccess) return hip_fail(e, "merge launch");
+  }
   g_err[0] = 0;
   return RGLRU_OK;
 }

@@ -19,6 +19,7 @@
 // Scaling trick: the Conv1D taps are multiplied by log2(e), so the MFMA delivers
 // log2(e)*(Wx+b) and v_exp_f32 (a base-2 exponential) needs no extra multiply; the input gate
 // is evaluated as ln(2)*sigmoid, which cancels the factor carried by x.
+#include "rglru_gelu.h"
 #include "rglru_mfma.h"
 
 #include <type_traits>
@@ -77,8 +78,23 @@ __global__ void __launch_bounds__(256) prep_kernel(uint4 *zero, size_t n16) {
 
 constexpr int FWD_MAX_SLICES = 16;
 
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// eight values of y (bf16 pairs) times GeLU of eight values of the block's other branch
+template <int MERGE>
+__device__ __forceinline__ u32x4 merge8(const u32x4 yv, const u32x4 bv) {
+  u32x4 o;
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+    o[k] = pack_bf16(bf_lo(yv[k]) * gelu<MERGE == 2, true>(bf_lo(bv[k])),
+                     bf_hi(yv[k]) * gelu<MERGE == 2, true>(bf_hi(bv[k])));
+  return o;
+}
+
 // GMAX = 1: one workgroup per (sequence, block); GMAX = 4 / 8 / 16: 2..4 / 5..8 / 9..16 time slices
-template <int GMAX>
+// MERGE = 0: y is the output; 1 / 2: the recurrent block's merge (Section 2.3) as epilogue,
+// out = y * GeLU(branch) with GeLU = z Phi(z) / its tanh form, y itself written only if asked for
+template <int GMAX, int MERGE>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 fwd_mfma_kernel(FwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -108,7 +124,9 @@ fwd_mfma_kernel(FwdArgs a) {
   // (the late waves keep their accumulators across the barrier, and a sequence sliced in time
   // needs registers for the carry exchange as well: the last K-steps of W_x are re-read from L2
   // every tile - a far better spill space than scratch memory)
-  constexpr int NRES = GMAX == 1 ? 13 : (GMAX == 4 ? 9 : (GMAX == 8 ? 6 : 2));   // measured best
+  // (the merge epilogue holds eight more registers: the tile's rows of the other branch)
+  constexpr int NRES_PLAIN = GMAX == 1 ? 13 : (GMAX == 4 ? 9 : (GMAX == 8 ? 6 : 2));   // measured best
+  constexpr int NRES = MERGE == 0 ? NRES_PLAIN : (NRES_PLAIN >= 2 ? NRES_PLAIN - 2 : 0);
   constexpr int PF = 2;   // streamed fragments in flight (deeper rings measured no better)
   bf16x8 wa[16], wx[NRES > 0 ? NRES : 1];
   const bf16x8 *pxs = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
@@ -162,8 +180,13 @@ fwd_mfma_kernel(FwdArgs a) {
   const unsigned row_bytes = (unsigned)D * 2;
   const __amdgpu_buffer_rsrc_t u_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       uniform_ptr((const unsigned short *)p.u + (size_t)b * T * D), 0, seq_bytes, 0x00020000);
+  // (a y that is not asked for gets an empty range: its stores are dropped)
   const __amdgpu_buffer_rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      uniform_ptr((unsigned short *)p.y + (size_t)b * T * D), 0, seq_bytes, 0x00020000);
+      uniform_ptr((unsigned short *)p.y + (size_t)b * T * D), 0, p.y ? seq_bytes : 0u, 0x00020000);
+  const __amdgpu_buffer_rsrc_t br_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_ptr((const unsigned short *)(MERGE ? p.branch : p.u) + (size_t)b * T * D), 0, seq_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t out_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_ptr((unsigned short *)(MERGE ? p.out : p.y) + (size_t)b * T * D), 0, seq_bytes, 0x00020000);
   const unsigned u_voff = (unsigned)dc * 2;
   const unsigned *st32 =
       p.state_in ? (const unsigned *)((const unsigned short *)p.state_in + (size_t)b * 3 * D + dc) : nullptr;
@@ -188,6 +211,16 @@ fwd_mfma_kernel(FwdArgs a) {
         raw[n] = v;
       }
     }
+  };
+  // the same for a tile after the first, free of branches (a load under a branch makes every
+  // later wait on an older load a wait for all loads): no row lies before the sequence start,
+  // and the row offset is part of the per-lane offset, which the descriptor's range check
+  // covers - rows past the end of the sequence read as zero
+  auto load_rows_inner = [&](int t0) __attribute__((always_inline)) {
+    const unsigned base = u_voff + (unsigned)(t0 + 8 * rg - 3) * row_bytes;
+#pragma unroll
+    for (int n = 0; n < 11; ++n)
+      raw[n] = __builtin_amdgcn_raw_buffer_load_b32(u_rsrc, base + (unsigned)n * row_bytes, 0, 0);
   };
   unsigned short *xw = xs + (8 * rg) * XS + 2 * c2;
   auto conv_rows = [&](int buf) __attribute__((always_inline)) {
@@ -249,6 +282,17 @@ fwd_mfma_kernel(FwdArgs a) {
     }
   };
   // finish tile t: carry the state across the tiles of the other slices, write y
+  // the rows of the other branch that this lane merges into tile t: requested a whole step
+  // before the tile is finished (rows outside the sequence are outside the descriptor's range
+  // and read as zero, so any t may be asked for)
+  u32x4 bq0 = {0, 0, 0, 0}, bq1 = {0, 0, 0, 0};
+  auto fetch_branch = [&](int t) __attribute__((always_inline)) {
+    if (MERGE) {
+      const unsigned vo = yw_voff + (unsigned)(t * TT) * row_bytes;
+      bq0 = __builtin_amdgcn_raw_buffer_load_b128(br_rsrc, vo, 0, RGLRU_NT);
+      bq1 = __builtin_amdgcn_raw_buffer_load_b128(br_rsrc, vo + 16 * row_bytes, 0, RGLRU_NT);
+    }
+  };
   auto resolve = [&](int t) __attribute__((always_inline)) {
     float h = carry;
 #pragma unroll
@@ -269,7 +313,23 @@ fwd_mfma_kernel(FwdArgs a) {
     float hrun = hf ? fmaf(hA_lo, h, hH_lo) : h;  // state entering this lane's run
 #pragma unroll
     for (int q = 0; q < 4; ++q) run_quarter(q, hold_mine[q * 64], hold_mine[(q + 4) * 64], hrun);
-    store_staged_tile(otile, lane, y_rsrc, yw_voff, (unsigned)(t * TT) * row_bytes, row_bytes, T - t * TT);
+    if (MERGE) {
+      const int row = lane >> 2, chunk = lane & 3, nrows = T - t * TT;
+      const unsigned soff = (unsigned)(t * TT) * row_bytes;
+      const u32x4 v0 = *(const u32x4 *)(otile + row * OT + chunk * 8);
+      const u32x4 v1 = *(const u32x4 *)(otile + (row + 16) * OT + chunk * 8);
+      const u32x4 o0 = merge8<MERGE>(v0, bq0), o1 = merge8<MERGE>(v1, bq1);
+      if (row < nrows) {
+        __builtin_amdgcn_raw_buffer_store_b128(v0, y_rsrc, yw_voff, soff, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(o0, out_rsrc, yw_voff, soff, 0);
+      }
+      if (row + 16 < nrows) {
+        __builtin_amdgcn_raw_buffer_store_b128(v1, y_rsrc, yw_voff, soff + 16 * row_bytes, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(o1, out_rsrc, yw_voff, soff + 16 * row_bytes, 0);
+      }
+    } else {
+      store_staged_tile(otile, lane, y_rsrc, yw_voff, (unsigned)(t * TT) * row_bytes, row_bytes, T - t * TT);
+    }
     carry = fmaf(hA_t, h, hH_t);
   };
 
@@ -417,12 +477,14 @@ fwd_mfma_kernel(FwdArgs a) {
         // these are trips to HBM); they land during the pointwise work
         gemm(buf);
         RGLRU_TR(1);
-        if (next < a.ntile) load_rows(next * TT);
+        load_rows_inner(next * TT);
         pointwise(tile);
+        fetch_branch(GMAX > 1 ? held : next);   // for the tile that is finished next
       } else {
         RGLRU_TR(1);
         if (it > 0) pointwise(tile - G);
-        if (next < a.ntile) load_rows(next * TT);     // lands during the products
+        fetch_branch(GMAX > 1 ? held : tile);
+        load_rows_inner(next * TT);                   // lands during the products
         gemm(buf);
       }
       // next tile of this workgroup into the other LDS buffer
@@ -437,8 +499,12 @@ fwd_mfma_kernel(FwdArgs a) {
       RGLRU_TR(6);
       RGLRU_TR_FLUSH((int)blockIdx.x, wv, it);
     }
-    if (LATE && it > 0) pointwise(tile - G);
+    if (LATE && it > 0) {
+      pointwise(tile - G);
+      if (GMAX > 1) fetch_branch(held);
+    }
   };
+  if (GMAX == 1 && !late) fetch_branch(tile);
   if (late) run(std::true_type{});
   else run(std::false_type{});
   if (GMAX > 1 && held >= 0) {
@@ -495,6 +561,8 @@ struct DecArgs {
 // requested as early as registers allow, and nothing is loaded under a branch (that would make the compiler drain all
 // outstanding loads on the spot) - rows past the batch get an out-of-range buffer offset
 // instead: they read as zero and their stores are dropped.
+// MERGE = 1 / 2: the block's merge as epilogue, y_t * GeLU(branch_t) is what is written.
+template <int MERGE>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 decode_mfma_kernel(DecArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -597,6 +665,17 @@ decode_mfma_kernel(DecArgs a) {
     h_vo[i] = b < B ? ((unsigned)b * (unsigned)D + (unsigned)(g * BS + wv * 32 + (lane & 7) * 4)) * 4 : OOB;
     hin[i] = __builtin_amdgcn_raw_buffer_load_b128(h_rsrc, h_vo[i], 0, 0);
   }
+  // where this lane's 16 bytes of y (rows l/4 and l/4 + 16) go; the other branch is read there
+  unsigned y_vo[2];
+  u32x4 brq[2];
+  const __amdgpu_buffer_rsrc_t br_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_ptr(MERGE ? p.branch : p.u), 0, (unsigned)B * row2, 0x00020000);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int b = b0 + (lane >> 2) + 16 * i;
+    y_vo[i] = b < B ? ((unsigned)b * (unsigned)D + (unsigned)(g * BS + wv * 32 + (lane & 3) * 8)) * 2 : OOB;
+    if (MERGE) brq[i] = __builtin_amdgcn_raw_buffer_load_b128(br_rsrc, y_vo[i], 0, 0);
+  }
   RGLRU_TR(1);
 
   if (tid < 64) {
@@ -640,6 +719,18 @@ decode_mfma_kernel(DecArgs a) {
     *(u32x4 *)(xs + XT_ELEMS + (lr + 16 * i) * XS + 8 * lc) = lo4;
   }
   load_phase(1, stg[1]);
+  // GeLU of the other branch now, while the weights are on their way: the step is
+  // latency-bound and the vector unit idle here, at the end it would be on the critical path
+  float gl[2][8];
+  if (MERGE) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        gl[i][2 * k] = gelu<MERGE == 2, true>(bf_lo(brq[i][k]));
+        gl[i][2 * k + 1] = gelu<MERGE == 2, true>(bf_hi(brq[i][k]));
+      }
+  }
   RGLRU_TR(2);
   __syncthreads();
   RGLRU_TR(3);
@@ -707,9 +798,14 @@ decode_mfma_kernel(DecArgs a) {
     __builtin_amdgcn_raw_buffer_store_b128(*(const u32x4 *)(hl + i * 8 * DEC_WROW + hl_wide), h_rsrc, h_vo[i], 0, 0);
 #pragma unroll
   for (int i = 0; i < 2; ++i) {   // lane l: 16 bytes of rows l/4 + 16 i
-    const int row = (lane >> 2) + 16 * i, b = b0 + row;
-    const unsigned vo = b < B ? ((unsigned)b * (unsigned)D + (unsigned)(g * BS + wv * 32 + (lane & 3) * 8)) * 2 : OOB;
-    __builtin_amdgcn_raw_buffer_store_b128(*(const u32x4 *)(yl + row * DEC_YROW + (lane & 3) * 16), y_rsrc, vo, 0, 0);
+    const int row = (lane >> 2) + 16 * i;
+    u32x4 yv = *(const u32x4 *)(yl + row * DEC_YROW + (lane & 3) * 16);
+    if (MERGE) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        yv[k] = pack_bf16(bf_lo(yv[k]) * gl[i][2 * k], bf_hi(yv[k]) * gl[i][2 * k + 1]);
+    }
+    __builtin_amdgcn_raw_buffer_store_b128(yv, y_rsrc, y_vo[i], 0, 0);
   }
   RGLRU_TR(7);
   RGLRU_TR_FLUSH((int)(blockIdx.y * gridDim.x + blockIdx.x), wv, 0);
@@ -743,6 +839,7 @@ bool forward_mfma_supported(const Problem &p, bool bf) {
   return bf && p.bs == BS && p.T >= 1 && (size_t)p.T * p.D * 2 < ((size_t)1 << 32) &&
          ((uintptr_t)p.W_a % 16 == 0) && ((uintptr_t)p.W_x % 16 == 0) && ((uintptr_t)p.u % 4 == 0) &&
          ((uintptr_t)p.y % 16 == 0) &&
+         (!p.merge || ((uintptr_t)p.branch % 16 == 0 && (uintptr_t)p.out % 16 == 0)) &&
          (!p.state_in || (uintptr_t)p.state_in % 4 == 0) &&
          (!p.state_out || (uintptr_t)p.state_out % 4 == 0);
 }
@@ -767,19 +864,25 @@ size_t forward_mfma_ws_bytes(int B, int T, int D, int nb) {
   return 256 + (size_t)units * R * 2 * BS * sizeof(u64);
 }
 
-template <int GMAX>
-static hipError_t launch_t(const FwdArgs &a, int grid, size_t lds, hipStream_t s) {
+template <int GMAX, int MERGE>
+static hipError_t launch_tm(const FwdArgs &a, int grid, size_t lds, hipStream_t s) {
   static bool configured = false;  // the kernel asks for more than the default LDS limit
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void *)fwd_mfma_kernel<GMAX>,
+    hipError_t e = hipFuncSetAttribute((const void *)fwd_mfma_kernel<GMAX, MERGE>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                        FWD_LDS);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  KernelTimer kt("fwd_mfma_kernel", s);
-  hipLaunchKernelGGL(fwd_mfma_kernel<GMAX>, dim3(grid), dim3(NTHR), lds, s, a);
+  KernelTimer kt(MERGE ? "fwd_merge_mfma_kernel" : "fwd_mfma_kernel", s);
+  hipLaunchKernelGGL((fwd_mfma_kernel<GMAX, MERGE>), dim3(grid), dim3(NTHR), lds, s, a);
   return hipGetLastError();
+}
+template <int GMAX>
+static hipError_t launch_t(const FwdArgs &a, int grid, size_t lds, hipStream_t s) {
+  return a.p.merge == 0 ? launch_tm<GMAX, 0>(a, grid, lds, s)
+       : a.p.merge == 1 ? launch_tm<GMAX, 1>(a, grid, lds, s)
+                        : launch_tm<GMAX, 2>(a, grid, lds, s);
 }
 
 hipError_t launch_forward_mfma(const Problem &p, hipStream_t s) {
@@ -810,7 +913,8 @@ hipError_t launch_forward_mfma(const Problem &p, hipStream_t s) {
 bool decode_mfma_supported(const Problem &p, bool bf) {
   // 16-byte accesses throughout; 32-bit byte offsets into the ring
   const uintptr_t all = (uintptr_t)p.W_a | (uintptr_t)p.W_x | (uintptr_t)p.u | (uintptr_t)p.state_out |
-                        (uintptr_t)p.hT | (uintptr_t)p.y | (uintptr_t)p.conv_w | (uintptr_t)p.conv_b;
+                        (uintptr_t)p.hT | (uintptr_t)p.y | (uintptr_t)p.conv_w | (uintptr_t)p.conv_b |
+                        (uintptr_t)(p.merge ? p.branch : nullptr);
   return bf && p.bs == BS && all % 16 == 0 && (size_t)(p.B + TT) * 3 * p.D * 2 < ((size_t)1 << 31);
 }
 
@@ -818,7 +922,10 @@ hipError_t launch_decode_mfma(const Problem &p, hipStream_t s) {
   DecArgs a;
   a.p = p;
   KernelTimer kt("decode_mfma_kernel", s);
-  hipLaunchKernelGGL(decode_mfma_kernel, dim3(p.nb, (p.B + TT - 1) / TT), dim3(NTHR), DEC_LDS, s, a);
+  const dim3 grid(p.nb, (p.B + TT - 1) / TT);
+  if (p.merge == 0) hipLaunchKernelGGL(decode_mfma_kernel<0>, grid, dim3(NTHR), DEC_LDS, s, a);
+  else if (p.merge == 1) hipLaunchKernelGGL(decode_mfma_kernel<1>, grid, dim3(NTHR), DEC_LDS, s, a);
+  else hipLaunchKernelGGL(decode_mfma_kernel<2>, grid, dim3(NTHR), DEC_LDS, s, a);
   return hipGetLastError();
 }
 

@@ -12,6 +12,21 @@ constexpr float GELU_C1 = 0.044715f;
 constexpr float INV_SQRT2 = 0.7071067811865476f;
 constexpr float INV_SQRT_2PI = 0.3989422804014327f;
 
+// Phi(z) for the fast path, branch-free: the rational approximation of erfc (Abramowitz and
+// Stegun 7.1.26, absolute error below 1.5e-7) evaluated on |z|, which also keeps the negative
+// tail free of cancellation. `e` returns exp(-z^2 / 2).
+__device__ __forceinline__ float normal_cdf_fast(float z, float &e) {
+  const float az = fabsf(z) * INV_SQRT2;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, az, 1.f));
+  float pl = fmaf(1.061405429f, t, -1.453152027f);
+  pl = fmaf(pl, t, 1.421413741f);
+  pl = fmaf(pl, t, -0.284496736f);
+  pl = fmaf(pl, t, 0.254829592f);
+  e = __builtin_amdgcn_exp2f(-0.5f * 1.4426950408889634f * z * z);
+  const float q = 0.5f * pl * t * e;     // Phi(-|z|)
+  return z < 0.f ? q : 1.f - q;
+}
+
 template <bool TANH, bool FAST>
 __device__ __forceinline__ float gelu(float z) {
   if (TANH) {
@@ -20,7 +35,10 @@ __device__ __forceinline__ float gelu(float z) {
     return z / (1.f + expf(-k2));
   }
   // erfc keeps its relative accuracy in the negative tail, where 1 + erf cancels
-  if (FAST) return 0.5f * z * (1.f + erff(z * INV_SQRT2));
+  if (FAST) {
+    float e;
+    return z * normal_cdf_fast(z, e);
+  }
   return 0.5f * z * erfcf(-z * INV_SQRT2);
 }
 
@@ -36,8 +54,13 @@ __device__ __forceinline__ void gelu_and_grad(float z, float &val, float &grad) 
     grad = s + z * s * (1.f - s) * (2.f * GELU_C0) * (1.f + 3.f * GELU_C1 * z * z);
     return;
   }
-  const float phi = FAST ? 0.5f * (1.f + erff(z * INV_SQRT2)) : 0.5f * erfcf(-z * INV_SQRT2);
-  const float e = FAST ? __builtin_amdgcn_exp2f(-0.5f * 1.4426950408889634f * z * z) : expf(-0.5f * z * z);
+  float phi, e;
+  if (FAST) {
+    phi = normal_cdf_fast(z, e);
+  } else {
+    phi = 0.5f * erfcf(-z * INV_SQRT2);
+    e = expf(-0.5f * z * z);
+  }
   val = z * phi;
   grad = phi + z * INV_SQRT_2PI * e;
 }

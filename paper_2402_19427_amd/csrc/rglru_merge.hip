@@ -13,36 +13,74 @@ template <typename AT> struct Vec;              // elements per 16-byte access
 template <> struct Vec<float> { static constexpr int N = 4; };
 template <> struct Vec<bf16> { static constexpr int N = 8; };
 
+// V elements as one naturally aligned access: requested first (raw), unpacked to fp32 later,
+// so that all requests of a trip are in flight together
 template <typename AT, int V>
-struct Pack {
+struct __attribute__((aligned(sizeof(AT) * V))) Pack {
   AT e[V];
 };
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
 template <typename AT, int V>
-__device__ __forceinline__ void load_pack(const AT *p, size_t i, float (&f)[V]) {
-  typedef Pack<AT, V> __attribute__((aligned(sizeof(AT) * V))) P;
-  const P v = *(const P *)(p + i);
+__device__ __forceinline__ Pack<AT, V> load_raw(const AT *p, size_t i) {
+  return *(const Pack<AT, V> *)(p + i);
+}
+template <typename AT, int V>
+__device__ __forceinline__ void unpack(const Pack<AT, V> &v, float (&f)[V]) {
 #pragma unroll
   for (int k = 0; k < V; ++k) f[k] = ldf(v.e, k);
 }
 template <typename AT, int V>
 __device__ __forceinline__ void store_pack(AT *p, size_t i, const float (&f)[V]) {
-  typedef Pack<AT, V> __attribute__((aligned(sizeof(AT) * V))) P;
-  P v;
+  Pack<AT, V> v;
+  if constexpr (sizeof(AT) == 2 && V % 2 == 0) {   // v_cvt_pk_bf16_f32: two values per instruction
 #pragma unroll
-  for (int k = 0; k < V; ++k) stf(v.e, k, f[k]);
-  *(P *)(p + i) = v;
+    for (int k = 0; k < V; k += 2) {
+      const f32x2_t two = {f[k], f[k + 1]};
+      const bf16x2_t b = __builtin_convertvector(two, bf16x2_t);
+      const unsigned bits = *(const unsigned *)&b;
+      v.e[k].v = (unsigned short)(bits & 0xffffu);
+      v.e[k + 1].v = (unsigned short)(bits >> 16);
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < V; ++k) stf(v.e, k, f[k]);
+  }
+  *(Pack<AT, V> *)(p + i) = v;
 }
+
+constexpr int NP = 2;   // packs per thread and trip
 
 template <typename AT, int V, bool TANH>
 __global__ void __launch_bounds__(MTHR)
 merge_fwd_kernel(const AT *y, const AT *br, AT *out, size_t n) {
   constexpr bool FAST = sizeof(AT) == 2;
   const size_t stride = (size_t)gridDim.x * MTHR * V;
-  for (size_t i = ((size_t)blockIdx.x * MTHR + threadIdx.x) * V; i < n; i += stride) {
+  size_t i = ((size_t)blockIdx.x * MTHR + threadIdx.x) * V;
+  for (; i + (NP - 1) * stride < n; i += NP * stride) {
+    Pack<AT, V> ry[NP], rb[NP];
+#pragma unroll
+    for (int h = 0; h < NP; ++h) {
+      ry[h] = load_raw<AT, V>(y, i + h * stride);
+      rb[h] = load_raw<AT, V>(br, i + h * stride);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int h = 0; h < NP; ++h) {
+      float fy[V], fb[V], fo[V];
+      unpack<AT, V>(ry[h], fy);
+      unpack<AT, V>(rb[h], fb);
+#pragma unroll
+      for (int k = 0; k < V; ++k) fo[k] = fy[k] * gelu<TANH, FAST>(fb[k]);
+      store_pack<AT, V>(out, i + h * stride, fo);
+    }
+  }
+  for (; i < n; i += stride) {
     float fy[V], fb[V], fo[V];
-    load_pack<AT, V>(y, i, fy);
-    load_pack<AT, V>(br, i, fb);
+    unpack<AT, V>(load_raw<AT, V>(y, i), fy);
+    unpack<AT, V>(load_raw<AT, V>(br, i), fb);
 #pragma unroll
     for (int k = 0; k < V; ++k) fo[k] = fy[k] * gelu<TANH, FAST>(fb[k]);
     store_pack<AT, V>(out, i, fo);
@@ -54,11 +92,13 @@ __global__ void __launch_bounds__(MTHR)
 merge_bwd_kernel(const AT *y, const AT *br, const AT *dout, AT *dy, AT *dbr, size_t n) {
   constexpr bool FAST = sizeof(AT) == 2;
   const size_t stride = (size_t)gridDim.x * MTHR * V;
-  for (size_t i = ((size_t)blockIdx.x * MTHR + threadIdx.x) * V; i < n; i += stride) {
+  size_t i = ((size_t)blockIdx.x * MTHR + threadIdx.x) * V;
+  auto one = [&](const Pack<AT, V> &ry, const Pack<AT, V> &rb, const Pack<AT, V> &rd, size_t at)
+      __attribute__((always_inline)) {
     float fy[V], fb[V], fd[V], gy[V], gb[V];
-    load_pack<AT, V>(y, i, fy);
-    load_pack<AT, V>(br, i, fb);
-    load_pack<AT, V>(dout, i, fd);
+    unpack<AT, V>(ry, fy);
+    unpack<AT, V>(rb, fb);
+    unpack<AT, V>(rd, fd);
 #pragma unroll
     for (int k = 0; k < V; ++k) {
       float val, grad;
@@ -66,9 +106,22 @@ merge_bwd_kernel(const AT *y, const AT *br, const AT *dout, AT *dy, AT *dbr, siz
       gy[k] = fd[k] * val;
       gb[k] = fd[k] * fy[k] * grad;
     }
-    store_pack<AT, V>(dy, i, gy);
-    store_pack<AT, V>(dbr, i, gb);
+    store_pack<AT, V>(dy, at, gy);
+    store_pack<AT, V>(dbr, at, gb);
+  };
+  for (; i + (NP - 1) * stride < n; i += NP * stride) {
+    Pack<AT, V> ry[NP], rb[NP], rd[NP];
+#pragma unroll
+    for (int h = 0; h < NP; ++h) {
+      ry[h] = load_raw<AT, V>(y, i + h * stride);
+      rb[h] = load_raw<AT, V>(br, i + h * stride);
+      rd[h] = load_raw<AT, V>(dout, i + h * stride);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int h = 0; h < NP; ++h) one(ry[h], rb[h], rd[h], i + h * stride);
   }
+  for (; i < n; i += stride) one(load_raw<AT, V>(y, i), load_raw<AT, V>(br, i), load_raw<AT, V>(dout, i), i);
 }
 
 bool all_aligned16(std::initializer_list<const void *> ps) {

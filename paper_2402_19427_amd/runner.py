@@ -102,6 +102,14 @@ class DeviceProblem:
         R.rglru_decode_step(sh, self.params, u_t, h, conv_state, pos, y, stream)
         return y
 
+    def decode_step_merge(self, u_t, branch_t, h, conv_state, pos, flags=0, stream=None):
+        B, D = u_t.shape
+        sh = self.shape(T=1, B=B)
+        out = self.empty_act(B, D)
+        R.rglru_decode_step_merge(sh, self.params, u_t, branch_t, h, conv_state, pos, flags, out,
+                                  stream)
+        return out
+
     def alloc_grads(self):
         bs = self.D // self.nb
         g = dict(dW_a=self.empty_f32(self.nb, bs, bs), dW_x=self.empty_f32(self.nb, bs, bs),

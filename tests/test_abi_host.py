@@ -184,7 +184,7 @@ def test_merge_calls_validation_and_workspace():
         R.rglru_forward_merge(s, params(), FAKE, None, None, None, 0, 0, OUT, None, None, None, None, 0)
     assert e.value.code == R.ERR_INVALID_ARG and "branch is NULL" in str(e.value)
     with pytest.raises(R.RglruError) as e:
-        R.rglru_forward_merge(s, params(), FAKE, FAKE, None, None, 0, 2, OUT, None, None, None, None, 0)
+        R.rglru_forward_merge(s, params(), FAKE, FAKE, None, None, 0, 4, OUT, None, None, None, None, 0)
     assert e.value.code == R.ERR_INVALID_ARG and "flags" in str(e.value)
     with pytest.raises(R.RglruError) as e:
         R.rglru_forward_merge(s, params(), FAKE, Y, None, None, 0, 0, Y, None, None, None, None, 0)
@@ -208,3 +208,20 @@ def test_merge_calls_validation_and_workspace():
         R.rglru_backward_merge(s, params(), FAKE, FAKE, None, None, 0, 0, Y, FAKE, None, OUT, FAKE + 12288,
                                None, g2, FAKE, need)
     assert e.value.code == R.ERR_INVALID_ARG and "db_a" in str(e.value)
+
+
+def test_decode_step_merge_validation():
+    s = R.make_shape(2, 1, 16, 2, R.BF16)
+    OUT = FAKE + 4096
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_decode_step_merge(s, params(), FAKE, None, FAKE, FAKE, 0, 0, OUT)
+    assert e.value.code == R.ERR_INVALID_ARG and "branch_t is NULL" in str(e.value)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_decode_step_merge(s, params(), FAKE, FAKE, FAKE, FAKE, 0, R.MERGE_SEPARATE, OUT)
+    assert e.value.code == R.ERR_INVALID_ARG and "flags" in str(e.value)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_decode_step_merge(s, params(), FAKE, OUT, FAKE, FAKE, 0, 0, OUT)
+    assert e.value.code == R.ERR_INVALID_ARG and "alias" in str(e.value)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_decode_step_merge(s, params(), FAKE, FAKE, FAKE, FAKE, -1, 0, OUT)
+    assert e.value.code == R.ERR_INVALID_ARG and "pos" in str(e.value)

@@ -455,3 +455,30 @@ def test_merge_calls_reject_bad_arguments():
         R.rglru_forward_merge(sh, dp.params, u, u, None, None, 0, 8, out, None, None, None, ws, n)
     with pytest.raises(R.RglruError):       # branch missing
         R.rglru_forward_merge(sh, dp.params, u, None, None, None, 0, 0, out, None, None, None, ws, n)
+
+
+@pytest.mark.parametrize("B,D,nb,act", [(5, 64, 2, "f32"), (3, 320, 2, "bf16"), (64, 1024, 4, "bf16"),
+                                        (33, 256, 1, "bf16")])
+@pytest.mark.parametrize("tanh_form", [False, True])
+def test_decode_steps_with_merge_match_oracle(B, D, nb, act, tanh_form):
+    import paper_2402_19427_amd as R
+    rn = runner()
+    nsteps = 4
+    inp = gen.make_inputs(B, 1, D, nb, act=act, seed=B + D + 1, h0=True, state=True,
+                          decode_tokens=nsteps, bias=True)
+    br = gen.make_branch(nsteps, B, D, act=act, seed=B)
+    dp = rn.DeviceProblem(inp, B, 1, D, nb, act)
+    pos = 8
+    h = rn.to_device(inp["h0"], "f32")
+    ring = rn.to_device(gen.ring_from_chrono(inp["state"], pos), act)
+    q = f64(inp)
+    h_ref, st_ref = q["h0"].copy(), q["state"].copy()
+    for s in range(nsteps):
+        out = dp.decode_step_merge(rn.to_device(inp["u_dec"][s], act), rn.to_device(br[s], act), h, ring,
+                                   pos + s, flags=R.MERGE_GELU_TANH if tanh_form else 0)
+        y_ref = oracle.decode_step(q["u_dec"][s], q["W_a"], q["W_x"], q["b_a"], q["b_x"],
+                                   q["Lambda"], q["conv_w"], h_ref, st_ref, conv_b=q["conv_b"])
+        out_ref = oracle.merge(y_ref, br[s], approx=tanh_form)
+        assert gen.rel_err(rn.to_host(out), out_ref) < TOL[act], s
+        assert gen.rel_err(rn.to_host(h), h_ref) < TOL[act], s
+        np.testing.assert_array_equal(gen.chrono_from_ring(rn.to_host(ring), pos + s + 1), st_ref)
