@@ -206,10 +206,12 @@ int rglru_backward(const rglru_shape *shape, const rglru_params *params, const v
  * the RG-LRU branch is multiplied element by element with GeLU of the block's other branch):
  *   out_t = y_t * GeLU(branch_t),   y = rglru_forward(u, ...).
  * GeLU(z) = z * Phi(z), Phi the standard normal CDF; RGLRU_MERGE_GELU_TANH selects
- * 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))). The product is formed from the unrounded
- * fp32 h_t and rounded once to act.
+ * 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))). The product is formed in fp32 from y_t as
+ * stored (rounded to act) and rounded to act. Where it is faster the merge runs as the
+ * epilogue of the recurrence kernel (y then never travels through memory unless asked for),
+ * else as a streaming kernel after it; the results agree up to rounding.
  *   branch     [B][T][D] act, read: the other branch before its non-linearity.
- *   out        [B][T][D] act, written. May alias branch.
+ *   out        [B][T][D] act, written. Must not alias u, branch or y.
  *   y          [B][T][D] act, written as by rglru_forward, or NULL (skipped). Training keeps
  *              it for rglru_backward_merge; inference passes NULL and saves its write.
  *   the other arguments, the workspace (RGLRU_OP_FORWARD_MERGE) and T == 0: as rglru_forward.

@@ -452,7 +452,7 @@ int rglru_forward_merge(const rglru_shape *shape, const rglru_params *params, co
   hipStream_t s = (hipStream_t)stream;
   hipError_t e;
   q.merge = tanh_form ? 2 : 1; q.branch = branch; q.out = out; q.y = y;
-  if (!(flags & RGLRU_MERGE_SEPARATE) && forward_mfma_supported(q, bf)) {   // the merge is the kernel's epilogue
+  if (!(flags & RGLRU_MERGE_SEPARATE) && forward_mfma_supported(q, bf) && forward_mfma_merge_fused(q)) {
     e = launch_forward_mfma(q, s);
     if (e != hipSuccess) return hip_fail(e, "forward launch");
     g_err[0] = 0;

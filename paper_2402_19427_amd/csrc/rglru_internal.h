@@ -94,6 +94,7 @@ size_t generic_lds_bytes(int bs);
 bool forward_mfma_supported(const Problem &p, bool bf);
 size_t forward_mfma_ws_bytes(int B, int T, int D, int nb);
 hipError_t launch_forward_mfma(const Problem &p, hipStream_t s);
+bool forward_mfma_merge_fused(const Problem &p);   // merge as epilogue (else: a kernel of its own)
 
 // MFMA decode step (bf16 storage, gate blocks of 256)
 bool decode_mfma_supported(const Problem &p, bool bf);

@@ -1,6 +1,6 @@
 """Per-workload timing report of the Conv1D -> RG-LRU path on one MI355X.
 
-    python -m paper_2402_19427_amd.workloads [--configs C0,C1,C2,C3,C4,SCAN] [--json]
+    python -m paper_2402_19427_amd.workloads [--configs C0,C1,C2,C3,C4,SCAN,MERGE] [--json]
 
 For each of the five synthetic workloads it times the calls that workload is about (forward;
 forward and backward for the training shape; the single-token decode step for the decode shape,
@@ -11,7 +11,9 @@ against the dense bf16 MFMA peak. Small workloads rotate several buffer sets so 
 footprint of consecutive iterations exceeds the 256 MB last-level cache ("cold"); the decode
 step is also timed on one buffer set ("hot"). SCAN is the scan-only entry point (eq. 4 over
 given decays and gated inputs) at the shape the paper times it: batch 8, width 1024, a sweep of
-sequence lengths. Inputs are seeded and synthetic.
+sequence lengths. MERGE times the calls that take the recurrent block's merge with its GeLU
+branch along (as the kernels' epilogue, and as a kernel of its own for comparison) on the
+workloads C1-C4. Inputs are seeded and synthetic.
 """
 import argparse
 import json
@@ -41,13 +43,21 @@ def alg_bytes(kind, B, T, D, nb, act_b):
         return 4 * act_b * N + w + vec + 2 * nb * bs * bs * 4
     if kind == "decode":       # u_t, 3 ring slots in + 1 out, h in + out, y_t, weights
         return (act_b + 3 * act_b + act_b + 8 + act_b) * B * D + w + vec
+    if kind == "forward_merge":        # u, branch in; out out
+        return alg_bytes("forward", B, T, D, nb, act_b) + act_b * N
+    if kind == "forward_merge_keep":   # ... and y kept for the backward
+        return alg_bytes("forward", B, T, D, nb, act_b) + 2 * act_b * N
+    if kind == "backward_merge":       # u, y, branch, dout in; du, dbranch out
+        return alg_bytes("backward", B, T, D, nb, act_b) + 2 * act_b * N
+    if kind == "decode_merge":
+        return alg_bytes("decode", B, T, D, nb, act_b) + act_b * B * D
     raise ValueError(kind)
 
 
 def gate_flops(kind, B, T, D, nb):
     bs = D // nb
     N = B * T * D
-    return {"forward": 4, "decode": 4, "backward": 12}[kind] * bs * N
+    return {"forward": 4, "decode": 4, "backward": 12}[kind.split("_")[0]] * bs * N
 
 
 def time_calls(fn, nsets, iters, warmup):
@@ -222,9 +232,104 @@ def run_scan_workload(dev, out, lengths=(1024, 4096, 16384, 65536)):
         torch.cuda.empty_cache()
 
 
+def run_merge_workload(dev, out, names=("C1", "C2", "C3", "C4"), steps=1000):
+    """The calls with the block's merge (Section 2.3) on the sequence workloads and the decode
+    workload: out = y * GeLU(branch) as the kernels' epilogue, against the same merge run as a
+    streaming kernel of its own after the plain forward."""
+    sp = torch.cuda.current_stream().cuda_stream
+    for name in names:
+        w = gen.CONFIGS[name]
+        B, T, D, nb = w.B, w.T, w.D, w.nb
+        act_b = 2
+        inp = gen.make_inputs(1, 8, D, nb, act=w.act, seed=w.seed)
+        gtor = torch.Generator(device=dev)
+        gtor.manual_seed(w.seed + 1)
+        if w.kind == "decode":
+            dp = rn.DeviceProblem(inp, B, 1, D, nb, w.act, device=dev)
+            sh = dp.shape(T=1)
+            u, br = (torch.randn(B, D, device=dev, generator=gtor).to(dp.tdtype) for _ in range(2))
+            h = torch.randn(B, D, device=dev, generator=gtor)
+            st = torch.randn(B, 3, D, device=dev, generator=gtor).to(dp.tdtype)
+            o = dp.empty_act(B, D)
+            for label, call in (
+                    ("decode", lambda i, q: R.rglru_decode_step(sh, dp.params, u, h, st, 3 + i, o, q)),
+                    ("decode + merge", lambda i, q: R.rglru_decode_step_merge(sh, dp.params, u, br, h, st,
+                                                                              3 + i, 0, o, q))):
+                kind = "decode_merge" if "merge" in label else "decode"
+                graph = torch.cuda.CUDAGraph()
+                torch.cuda.synchronize()
+                with torch.cuda.graph(graph):
+                    spg = torch.cuda.current_stream().cuda_stream
+                    for i in range(steps):
+                        call(i, spg)
+                torch.cuda.synchronize()
+                graph.replay()
+                reps = []
+                for _ in range(3):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    graph.replay()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    reps.append(e0.elapsed_time(e1) / steps)
+                out.append(row("MERGE", "%s %s, one graph of %d steps" % (name, label, steps),
+                               "hot: 1 buffer set", np.array(reps), B, alg_bytes(kind, B, 1, D, nb, act_b),
+                               gate_flops("decode", B, 1, D, nb)))
+                del graph
+            continue
+        dp = rn.DeviceProblem(inp, B, T, D, nb, w.act, device=dev)
+        sh = dp.shape()
+        per_set = 3 * act_b * B * T * D
+        nsets = int(min(8, max(1, -(-LLC_BYTES * 5 // 4 // per_set))))
+        iters = 100 if B * T * D < (1 << 27) else 30
+        us = [torch.randn(B, T, D, device=dev, generator=gtor).to(dp.tdtype) for _ in range(nsets)]
+        brs = [torch.randn(B, T, D, device=dev, generator=gtor).to(dp.tdtype) for _ in range(nsets)]
+        outs = [dp.empty_act(B, T, D) for _ in range(nsets)]
+        ys = [dp.empty_act(B, T, D) for _ in range(nsets)]
+        h0 = torch.randn(B, D, device=dev, generator=gtor) if w.h0 else None
+        hT, st = dp.empty_f32(B, D), dp.empty_act(B, 3, D)
+        ws_f, n_f = dp.workspace(sh, R.OP_FORWARD_MERGE)
+        note = "%d buffer set%s" % (nsets, "s" if nsets > 1 else "")
+
+        def fwd(flags, keep):
+            def call(i):
+                R.rglru_forward_merge(sh, dp.params, us[i], brs[i], h0, None, 0, flags, outs[i],
+                                      ys[i] if keep else None, hT, st, ws_f, n_f, sp)
+            return call
+
+        for label, flags, keep in (("forward, merge as a kernel of its own", R.MERGE_SEPARATE, False),
+                                   ("forward + merge", 0, False),
+                                   ("forward + merge, tanh form", R.MERGE_GELU_TANH, False),
+                                   ("forward + merge, y kept", 0, True)):
+            ms = time_calls(fwd(flags, keep), nsets, iters, 10)
+            kind = "forward_merge_keep" if keep else "forward_merge"
+            out.append(row("MERGE", "%s %s" % (name, label), note, ms, B * T,
+                           alg_bytes(kind, B, T, D, nb, act_b), gate_flops("forward", B, T, D, nb)))
+        if w.kind != "train" and name != "C1":
+            del us, brs, outs, ys
+            torch.cuda.empty_cache()
+            continue
+        douts = [torch.randn(B, T, D, device=dev, generator=gtor).to(dp.tdtype) for _ in range(nsets)]
+        du, dbr, dh0 = dp.empty_act(B, T, D), dp.empty_act(B, T, D), dp.empty_f32(B, D)
+        g = dp.alloc_grads()
+        pg = R.make_param_grads(g["dW_a"], g["dW_x"], g["db_a"], g["db_x"], g["dLambda"],
+                                g["dconv_w"], g["dconv_b"])
+        ws_b, n_b = dp.workspace(sh, R.OP_BACKWARD_MERGE)
+
+        def bwd(i):
+            R.rglru_backward_merge(sh, dp.params, us[i], brs[i], h0, None, 0, 0, ys[i], douts[i], None,
+                                   du, dbr, dh0, pg, ws_b, n_b, sp)
+
+        ms = time_calls(bwd, nsets, iters, 5)
+        out.append(row("MERGE", "%s backward + merge" % name, note, ms, B * T,
+                       alg_bytes("backward_merge", B, T, D, nb, act_b), gate_flops("backward", B, T, D, nb)))
+        del us, brs, outs, ys, douts
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--configs", default="C0,C1,C2,C3,C4,SCAN")
+    ap.add_argument("--configs", default="C0,C1,C2,C3,C4,SCAN,MERGE")
     ap.add_argument("--scan-lengths", default="1024,4096,16384,65536")
     ap.add_argument("--json", action="store_true", help="print one JSON object per row instead of the table")
     args = ap.parse_args()
@@ -236,6 +341,8 @@ def main():
         w = gen.CONFIGS.get(name)
         if name == "SCAN":
             run_scan_workload(dev, out, tuple(int(x) for x in args.scan_lengths.split(",")))
+        elif name == "MERGE":
+            run_merge_workload(dev, out)
         elif w.kind == "decode":
             run_decode_workload(w, dev, out)
         else:
@@ -246,7 +353,7 @@ def main():
             if args.json:
                 print(json.dumps(r), flush=True)
             else:
-                print("%-3s %-38s %-22s median %9.2f us  min %9.2f us  %8.2f M tok/s  %7.1f GB/s "
+                print("%-5s %-46s %-22s median %9.2f us  min %9.2f us  %8.2f M tok/s  %7.1f GB/s "
                       "= %5.1f%% of HBM peak  %5.1f%% of MFMA peak"
                       % (r["workload"], r["call"], r["note"], r["ms_median"] * 1e3, r["ms_min"] * 1e3,
                          r["tokens_per_s"] / 1e6, r["alg_GBs"], 100 * r["hbm_frac"],

@@ -185,3 +185,27 @@ def test_scan_at_the_paper_s_measurement_shape_full_size():
     assert gen.rel_err(h_h[:, :, ch], h_ref) < TOL
     assert gen.rel_err(hT_h[:, ch], hT_ref) < 1e-4
     assert np.isfinite(h_h).all()
+
+
+@pytest.mark.parametrize("name,pairs", [("C1", [(0, 0), (5, 4)]), ("C2", [(0, 3)])])
+def test_forward_with_the_block_s_merge_full_size(name, pairs):
+    # C1: merge as the recurrence kernel's epilogue; C2: 16 time slices, where the library runs it
+    # as a kernel of its own
+    import paper_2402_19427_amd.runner as rn
+    w = gen.CONFIGS[name]
+    inp = gen.make_workload(name, dy=False)
+    br = gen.make_branch(w.B, w.T, w.D, act=w.act, seed=w.seed)
+    dp = rn.DeviceProblem(inp, w.B, w.T, w.D, w.nb, w.act)
+    out, y, hT, st = dp.forward_merge(rn.to_device(inp["u"], w.act), rn.to_device(br, w.act),
+                                      h0=rn.to_device(inp["h0"], "f32"), keep_y=False)
+    out_h, hT_h = rn.to_host(out), rn.to_host(hT)
+    del out
+    oracle.set_threads(1)
+    for b, g in pairs:
+        sl, par = block_params(inp, g, w.bs)
+        h0_u = None if inp["h0"] is None else np.asarray(inp["h0"][b:b + 1, sl], np.float64)
+        out_ref, _, hT_ref, _ = oracle.forward_merge(np.asarray(inp["u"][b:b + 1, :, sl], np.float64),
+                                                     br[b:b + 1, :, sl], *par, h0=h0_u)
+        assert gen.rel_err(out_h[b:b + 1, :, sl], out_ref) < TOL, (name, b, g)
+        assert gen.rel_err(hT_h[b:b + 1, sl], hT_ref) < TOL, (name, b, g)
+    assert np.isfinite(out_h).all()

@@ -380,6 +380,7 @@ MERGE_SHAPES = [
     (2, 130, 512, 2, "bf16"),    # MFMA path, ragged T
     (33, 70, 1024, 4, "bf16"),   # MFMA path, one workgroup per unit
     (8, 600, 2048, 8, "bf16"),   # MFMA path, time slices
+    (1, 1500, 256, 1, "bf16"),   # MFMA path, 16 time slices: the merge runs as a kernel of its own
 ]
 
 

@@ -37,6 +37,13 @@ def test_workload_report_algorithmic_bytes():
     assert wl.gate_flops("forward", c1.B, c1.T, c1.D, c1.nb) == 1024 * n1
     assert wl.gate_flops("backward", c4.B, c4.T, c4.D, c4.nb) == 3072 * n4
     assert wl.gate_flops("decode", c3.B, 1, c3.D, c3.nb) == 1024 * 256 * 4096
+    # with the block's merge: the other branch in (forward), y kept on top of out (training),
+    # the branch in and its gradient out (backward); one more [B][D] row per decode step
+    assert wl.alg_bytes("forward_merge", c1.B, c1.T, c1.D, c1.nb, 2) == fwd1 + 2 * n1
+    assert wl.alg_bytes("forward_merge_keep", c1.B, c1.T, c1.D, c1.nb, 2) == fwd1 + 4 * n1
+    assert wl.alg_bytes("backward_merge", c4.B, c4.T, c4.D, c4.nb, 2) == bwd4 + 4 * n4
+    assert wl.alg_bytes("decode_merge", c3.B, 1, c3.D, c3.nb, 2) == dec + 2 * 256 * 4096
+    assert wl.gate_flops("forward_merge", c1.B, c1.T, c1.D, c1.nb) == 1024 * n1
 
 
 def test_bench_costs_and_single_gpu_contract():
