@@ -130,7 +130,7 @@ size_t workspace_need(const rglru_shape *s, int op) {
       return merge_dy_bytes(s) + workspace_need(s, RGLRU_OP_BACKWARD);
     case RGLRU_OP_FORWARD_MERGE:
     case RGLRU_OP_FORWARD:
-      if (s->act_dtype == RGLRU_BF16 && s->D / s->num_blocks == 256 && s->T >= 1)
+      if (s->act_dtype == RGLRU_BF16 && forward_mfma_block(s->D / s->num_blocks) && s->T >= 1)
         return forward_mfma_ws_bytes(s->B, s->T, s->D, s->num_blocks);
       return 0;
     default:

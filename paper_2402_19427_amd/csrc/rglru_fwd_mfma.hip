@@ -94,7 +94,11 @@ __device__ __forceinline__ u32x4 merge8(const u32x4 yv, const u32x4 bv) {
 // GMAX = 1: one workgroup per (sequence, block); GMAX = 4 / 8 / 16: 2..4 / 5..8 / 9..16 time slices
 // MERGE = 0: y is the output; 1 / 2: the recurrent block's merge (Section 2.3) as epilogue,
 // out = y * GeLU(branch) with GeLU = z Phi(z) / its tanh form, y itself written only if asked for
-template <int GMAX, int MERGE>
+// PAD: gate blocks narrower than 256 channels (a multiple of 16, Section 4.1's 16 blocks at
+// width 2560 give 160) run in the 256-wide tile: parameter reads of the missing channels and
+// K-steps are clamped to existing ones (whatever they hold meets zeros: the Conv1D lanes of
+// missing channels write x = 0), their loads of u read nothing and their stores are dropped.
+template <int GMAX, int MERGE, bool PAD>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 fwd_mfma_kernel(FwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -118,7 +122,13 @@ fwd_mfma_kernel(FwdArgs a) {
   const int b = unit / p.nb, g = unit - b * p.nb;
   const int D = p.D, T = p.T;
   const int ch = wv * 32 + j;  // channel inside the block owned by this lane
-  const int d = g * BS + ch;
+  constexpr unsigned OOB = 0x80000000u;   // buffer offset past every range: loads give 0, stores are dropped
+  const int bs = PAD ? p.bs : BS;         // channels of a gate block in memory
+  const int nk = bs >> 4;                 // its K-steps
+  const bool ch_ok = !PAD || ch < bs;
+  const int chc = ch_ok ? ch : bs - 1;    // an existing channel to read parameters of
+  const int d = g * bs + chc;
+  auto kc = [&](int ks) __attribute__((always_inline)) { return PAD ? (ks < nk ? ks : nk - 1) : ks; };
 
   // ---- gate weights of this wave's 32 output channels, resident in registers
   // (the late waves keep their accumulators across the barrier, and a sequence sliced in time
@@ -129,13 +139,13 @@ fwd_mfma_kernel(FwdArgs a) {
   constexpr int NRES = MERGE == 0 ? NRES_PLAIN : (NRES_PLAIN >= 2 ? NRES_PLAIN - 2 : 0);
   constexpr int PF = 2;   // streamed fragments in flight (deeper rings measured no better)
   bf16x8 wa[16], wx[NRES > 0 ? NRES : 1];
-  const bf16x8 *pxs = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
+  const bf16x8 *pxs = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * bs + chc) * bs + hf * 8);
   {
-    const bf16x8 *pa = (const bf16x8 *)((const unsigned short *)p.W_a + ((size_t)g * BS + ch) * BS + hf * 8);
+    const bf16x8 *pa = (const bf16x8 *)((const unsigned short *)p.W_a + ((size_t)g * bs + chc) * bs + hf * 8);
 #pragma unroll
-    for (int ks = 0; ks < 16; ++ks) wa[ks] = pa[ks * 2];
+    for (int ks = 0; ks < 16; ++ks) wa[ks] = pa[kc(ks) * 2];
 #pragma unroll
-    for (int ks = 0; ks < NRES; ++ks) wx[ks] = pxs[ks * 2];
+    for (int ks = 0; ks < NRES; ++ks) wx[ks] = pxs[kc(ks) * 2];
   }
   // selection matrices that copy this wave's 32 columns of the tile into accumulator layout
   // (the same for every wave; parked in LDS to keep registers for the weights)
@@ -160,7 +170,8 @@ fwd_mfma_kernel(FwdArgs a) {
   // ---- Conv1D assignment: channel pair c2, rows 8*rg .. 8*rg+7 of the tile
   const int c2 = tid & 127;
   const int rg = __builtin_amdgcn_readfirstlane(tid >> 7);
-  const int dc = g * BS + 2 * c2;
+  const bool pair_ok = !PAD || 2 * c2 < bs;
+  const int dc = g * bs + (pair_ok ? 2 * c2 : 0);
   if (tid < 128) {  // taps (scaled by log2 e) and bias of the channel pair, parked in LDS
     f32x4 t0v, t1v, t2v;
     t0v[0] = p.conv_w[dc] * LOG2E;                  t0v[1] = p.conv_w[dc + 1] * LOG2E;
@@ -170,6 +181,7 @@ fwd_mfma_kernel(FwdArgs a) {
     t2v[0] = p.conv_b ? p.conv_b[dc] * LOG2E : 0.f;
     t2v[1] = p.conv_b ? p.conv_b[dc + 1] * LOG2E : 0.f;
     t2v[2] = t2v[3] = 0.f;
+    if (!pair_ok) t0v = t1v = t2v = f32x4{0.f, 0.f, 0.f, 0.f};
     cw_lds[c2] = t0v;
     cw_lds[128 + c2] = t1v;
     cw_lds[256 + c2] = t2v;
@@ -187,9 +199,9 @@ fwd_mfma_kernel(FwdArgs a) {
       uniform_ptr((const unsigned short *)(MERGE ? p.branch : p.u) + (size_t)b * T * D), 0, seq_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t out_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       uniform_ptr((unsigned short *)(MERGE ? p.out : p.y) + (size_t)b * T * D), 0, seq_bytes, 0x00020000);
-  const unsigned u_voff = (unsigned)dc * 2;
-  const unsigned *st32 =
-      p.state_in ? (const unsigned *)((const unsigned short *)p.state_in + (size_t)b * 3 * D + dc) : nullptr;
+  const unsigned u_voff = pair_ok ? (unsigned)dc * 2 : OOB;
+  const unsigned *st32 = (p.state_in && pair_ok)
+      ? (const unsigned *)((const unsigned short *)p.state_in + (size_t)b * 3 * D + dc) : nullptr;
 
   unsigned raw[11];  // inputs t0+8rg-3 .. t0+8rg+7 of the channel pair
   auto load_rows = [&](int t0) __attribute__((always_inline)) {
@@ -220,7 +232,7 @@ fwd_mfma_kernel(FwdArgs a) {
     const unsigned base = u_voff + (unsigned)(t0 + 8 * rg - 3) * row_bytes;
 #pragma unroll
     for (int n = 0; n < 11; ++n)
-      raw[n] = __builtin_amdgcn_raw_buffer_load_b32(u_rsrc, base + (unsigned)n * row_bytes, 0, 0);
+      raw[n] = __builtin_amdgcn_raw_buffer_load_b32(u_rsrc, pair_ok ? base + (unsigned)n * row_bytes : OOB, 0, 0);
   };
   // (without the epilogue nothing waits on an older load in between, and the version that
   // skips the loads of a tile that does not exist measured 3-4 % faster)
@@ -272,7 +284,9 @@ fwd_mfma_kernel(FwdArgs a) {
     o[3 * OT] = (unsigned short)(p1 >> 16);
   };
   // 16-byte stores of the staged tile: lane l owns 8 channels of rows l/4 and l/4+16
-  const unsigned yw_voff = (unsigned)(g * BS + wv * 32 + (lane & 3) * 8) * 2 + (unsigned)(lane >> 2) * row_bytes;
+  const bool chunk_ok = !PAD || wv * 32 + (lane & 3) * 8 < bs;
+  const unsigned yw_voff =
+      chunk_ok ? (unsigned)(g * bs + wv * 32 + (lane & 3) * 8) * 2 + (unsigned)(lane >> 2) * row_bytes : OOB;
 
   // state of the held tile (its local scan sits in LDS until the next iteration)
   int held = -1;
@@ -298,8 +312,8 @@ fwd_mfma_kernel(FwdArgs a) {
   auto fetch_branch = [&](int t) __attribute__((always_inline)) {
     if (MERGE) {
       const unsigned vo = yw_voff + (unsigned)(t * TT) * row_bytes;
-      bq0 = __builtin_amdgcn_raw_buffer_load_b128(br_rsrc, vo, 0, RGLRU_NT);
-      bq1 = __builtin_amdgcn_raw_buffer_load_b128(br_rsrc, vo + 16 * row_bytes, 0, RGLRU_NT);
+      bq0 = __builtin_amdgcn_raw_buffer_load_b128(br_rsrc, chunk_ok ? vo : OOB, 0, RGLRU_NT);
+      bq1 = __builtin_amdgcn_raw_buffer_load_b128(br_rsrc, chunk_ok ? vo + 16 * row_bytes : OOB, 0, RGLRU_NT);
     }
   };
   auto resolve = [&](int t) __attribute__((always_inline)) {
@@ -363,7 +377,7 @@ fwd_mfma_kernel(FwdArgs a) {
       bf16x8 st[PF];
       if (NRES < 16) {
 #pragma unroll
-        for (int i = 0; i < PF; ++i) st[i] = pxs[(NRES + i < 16 ? NRES + i : 15) * 2];
+        for (int i = 0; i < PF; ++i) st[i] = pxs[kc(NRES + i < 16 ? NRES + i : 15) * 2];
       }
 #pragma unroll
       for (int ks = 0; ks < 16; ++ks) {
@@ -373,7 +387,7 @@ fwd_mfma_kernel(FwdArgs a) {
           accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wx[ks], accq, 0, 0, 0);
         } else {
           accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, st[(ks - NRES) % PF], accq, 0, 0, 0);
-          if (ks + PF < 16) st[(ks - NRES) % PF] = pxs[(ks + PF) * 2];
+          if (ks + PF < 16) st[(ks - NRES) % PF] = pxs[kc(ks + PF) * 2];
         }
         __builtin_amdgcn_sched_barrier(0);
         a0 = a1;
@@ -524,8 +538,8 @@ fwd_mfma_kernel(FwdArgs a) {
 
   // the workgroup that ran the last tile owns the final states
   if ((a.ntile - 1) % G == w) {
-    if (p.hT && hf == 0) p.hT[(size_t)b * D + d] = carry;
-    if (p.state_out && tid < 128) {
+    if (p.hT && hf == 0 && ch_ok) p.hT[(size_t)b * D + d] = carry;
+    if (p.state_out && tid < 128 && pair_ok) {
       // ring slots of the last three inputs; older slots are carried over (Appendix F state)
       unsigned *so32 = (unsigned *)((unsigned short *)p.state_out + (size_t)b * 3 * D + dc);
       const long long end = p.pos0 + T;
@@ -844,8 +858,14 @@ hipError_t mfma::launch_prep(void *zero, size_t zero_bytes, hipStream_t s) {
   return hipGetLastError();
 }
 
+// gate block sizes the forward kernel takes: 256 channels, or narrower blocks (a multiple of 16,
+// at least half the tile: below that the padding costs more than the generic kernels)
+bool forward_mfma_block(int bs) { return bs == BS || (bs % 16 == 0 && bs >= BS / 2 && bs < BS); }
+
 bool forward_mfma_supported(const Problem &p, bool bf) {
-  return bf && p.bs == BS && p.T >= 1 && (size_t)p.T * p.D * 2 < ((size_t)1 << 32) &&
+  // (the narrower blocks mark dropped accesses with an offset of 2^31)
+  const bool block_ok = forward_mfma_block(p.bs) && (p.bs == BS || (size_t)p.T * p.D * 2 < ((size_t)1 << 31));
+  return bf && block_ok && p.T >= 1 && (size_t)p.T * p.D * 2 < ((size_t)1 << 32) &&
          ((uintptr_t)p.W_a % 16 == 0) && ((uintptr_t)p.W_x % 16 == 0) && ((uintptr_t)p.u % 4 == 0) &&
          ((uintptr_t)p.y % 16 == 0) &&
          (!p.merge || ((uintptr_t)p.branch % 16 == 0 && (uintptr_t)p.out % 16 == 0)) &&
@@ -882,19 +902,24 @@ size_t forward_mfma_ws_bytes(int B, int T, int D, int nb) {
   return 256 + (size_t)units * R * 2 * BS * sizeof(u64);
 }
 
-template <int GMAX, int MERGE>
-static hipError_t launch_tm(const FwdArgs &a, int grid, size_t lds, hipStream_t s) {
+template <int GMAX, int MERGE, bool PAD>
+static hipError_t launch_tmp(const FwdArgs &a, int grid, size_t lds, hipStream_t s) {
   static bool configured = false;  // the kernel asks for more than the default LDS limit
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void *)fwd_mfma_kernel<GMAX, MERGE>,
+    hipError_t e = hipFuncSetAttribute((const void *)fwd_mfma_kernel<GMAX, MERGE, PAD>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                        FWD_LDS);
     if (e != hipSuccess) return e;
     configured = true;
   }
   KernelTimer kt(MERGE ? "fwd_merge_mfma_kernel" : "fwd_mfma_kernel", s);
-  hipLaunchKernelGGL((fwd_mfma_kernel<GMAX, MERGE>), dim3(grid), dim3(NTHR), lds, s, a);
+  hipLaunchKernelGGL((fwd_mfma_kernel<GMAX, MERGE, PAD>), dim3(grid), dim3(NTHR), lds, s, a);
   return hipGetLastError();
+}
+template <int GMAX, int MERGE>
+static hipError_t launch_tm(const FwdArgs &a, int grid, size_t lds, hipStream_t s) {
+  return a.p.bs == BS ? launch_tmp<GMAX, MERGE, false>(a, grid, lds, s)
+                      : launch_tmp<GMAX, MERGE, true>(a, grid, lds, s);
 }
 template <int GMAX>
 static hipError_t launch_t(const FwdArgs &a, int grid, size_t lds, hipStream_t s) {

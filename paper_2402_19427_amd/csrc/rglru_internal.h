@@ -92,6 +92,7 @@ size_t generic_lds_bytes(int bs);
 
 // MFMA forward (bf16 storage, gate blocks of 256)
 bool forward_mfma_supported(const Problem &p, bool bf);
+bool forward_mfma_block(int bs);   // gate block sizes the forward kernel takes
 size_t forward_mfma_ws_bytes(int B, int T, int D, int nb);
 hipError_t launch_forward_mfma(const Problem &p, hipStream_t s);
 bool forward_mfma_merge_fused(const Problem &p);   // merge as epilogue (else: a kernel of its own)

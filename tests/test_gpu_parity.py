@@ -42,7 +42,10 @@ SHAPES = [
     (3, 5, 40, 5, "f32"),        # bs = 8, fewer steps than one tile
     (1, 1, 16, 1, "f32"),        # single step, single dense block
     (2, 130, 512, 2, "bf16"),    # bs = 256: the tuned block size, ragged T
-    (2, 70, 320, 2, "bf16"),     # bs = 160: the paper's 16 blocks at width 2560
+    (2, 70, 320, 2, "bf16"),     # bs = 160: the paper's 16 blocks at width 2560 (MFMA path, padded tile)
+    (3, 300, 2560, 16, "bf16"),  # the same at full width: 48 units x 5 slices, ragged T
+    (1, 1100, 384, 2, "bf16"),   # bs = 192, 16 slices
+    (40, 40, 288, 2, "bf16"),    # bs = 144 (a multiple of 16 only), one workgroup per unit
     (1, 9, 24, 24, "bf16"),      # nb = D: per-channel gates
     (2, 300, 600, 2, "bf16"),    # bs = 300 > workgroup size
     (1, 1, 256, 1, "bf16"),      # MFMA path, one step
@@ -381,6 +384,7 @@ MERGE_SHAPES = [
     (33, 70, 1024, 4, "bf16"),   # MFMA path, one workgroup per unit
     (8, 600, 2048, 8, "bf16"),   # MFMA path, time slices
     (1, 1500, 256, 1, "bf16"),   # MFMA path, 16 time slices: the merge runs as a kernel of its own
+    (3, 300, 2560, 16, "bf16"),  # bs = 160 in the padded tile, merge as epilogue
 ]
 
 
