@@ -115,12 +115,25 @@ size_t merge_dy_bytes(const rglru_shape *s) {
   return (n + 255) & ~(size_t)255;
 }
 
+// narrower gate blocks in bf16: the backward runs on a copy widened to 256-channel blocks
+bool backward_via_padding(const rglru_shape *s) {
+  return s->act_dtype == RGLRU_BF16 && backward_padded_block(s->D / s->num_blocks) && s->T >= 1 &&
+         (size_t)s->T * s->num_blocks * 256 * 4 < ((size_t)1 << 32);
+}
+
+size_t workspace_need(const rglru_shape *s, int op);
 size_t workspace_need(const rglru_shape *s, int op) {
   switch (op) {
     case RGLRU_OP_BACKWARD:
       if (s->act_dtype == RGLRU_BF16 && s->D / s->num_blocks == 256 &&
           (size_t)s->T * s->D * 4 < ((size_t)1 << 32))
         return backward_mfma_ws_bytes(s->B, s->T, s->D, s->num_blocks);
+      if (backward_via_padding(s)) {
+        // (the generic kernels remain the fallback for loosely aligned pointers)
+        const size_t a = backward_padded_ws_bytes(s->B, s->T, s->D, s->num_blocks);
+        const size_t b = backward_generic_ws_bytes(s->B, s->T, s->D, s->num_blocks);
+        return a > b ? a : b;
+      }
       return backward_generic_ws_bytes(s->B, s->T, s->D, s->num_blocks);
     case RGLRU_OP_SCAN:
       if (s->act_dtype == RGLRU_BF16 && s->D % 256 == 0 && s->T >= 1)
@@ -257,10 +270,13 @@ int rglru_workspace_status(const rglru_shape *shape, int op, const void *workspa
   if (!workspace) return fail(RGLRU_ERR_INVALID_ARG, "workspace is NULL");
   size_t off = 0;   // forward and scan keep the flag in the first word
   if (bwd) {
-    if (!(shape->act_dtype == RGLRU_BF16 && shape->D / shape->num_blocks == 256 &&
-          (size_t)shape->T * shape->D * 4 < ((size_t)1 << 32)))
+    if (shape->act_dtype == RGLRU_BF16 && shape->D / shape->num_blocks == 256 &&
+        (size_t)shape->T * shape->D * 4 < ((size_t)1 << 32))
+      off = backward_mfma_flag_offset(shape->B, shape->T, shape->D, shape->num_blocks);
+    else if (backward_via_padding(shape))
+      off = backward_padded_flag_offset(shape->B, shape->T, shape->D, shape->num_blocks);
+    else
       return RGLRU_OK;              // the generic kernels do not wait on each other
-    off = backward_mfma_flag_offset(shape->B, shape->T, shape->D, shape->num_blocks);
     if (op == RGLRU_OP_BACKWARD_MERGE) off += merge_dy_bytes(shape);
   }
   int flag = 0;
@@ -407,11 +423,22 @@ int rglru_backward(const rglru_shape *shape, const rglru_params *params, const v
   hipError_t e;
   if (backward_mfma_supported(q, bf)) {
     e = launch_backward_mfma(q, (hipStream_t)stream);
+  } else if (backward_padded_supported(q, bf)) {
+    e = launch_backward_padded(q, (hipStream_t)stream);
   } else {
     // pointers too loosely aligned for the MFMA kernels: the generic kernels need more scratch
     CHECK(check_workspace(workspace, workspace_bytes,
                           backward_generic_ws_bytes(shape->B, shape->T, shape->D, shape->num_blocks)));
     e = launch_backward_generic(q, bf, (hipStream_t)stream);
+    // where the shape would have taken kernels that wait on each other, their timeout flag
+    // lies inside the scratch the generic kernels have just used: leave it cleared
+    if (e == hipSuccess && bf && shape->D / shape->num_blocks == 256 &&
+        (size_t)shape->T * shape->D * 4 < ((size_t)1 << 32))
+      e = launch_clear((char *)workspace + backward_mfma_flag_offset(shape->B, shape->T, shape->D, shape->num_blocks),
+                       16, (hipStream_t)stream);
+    else if (e == hipSuccess && backward_via_padding(shape))
+      e = launch_clear((char *)workspace + backward_padded_flag_offset(shape->B, shape->T, shape->D, shape->num_blocks),
+                       16, (hipStream_t)stream);
   }
   if (e != hipSuccess) return hip_fail(e, "backward launch");
   g_err[0] = 0;

@@ -585,7 +585,8 @@ struct DecArgs {
 // outstanding loads on the spot) - rows past the batch get an out-of-range buffer offset
 // instead: they read as zero and their stores are dropped.
 // MERGE = 1 / 2: the block's merge as epilogue, y_t * GeLU(branch_t) is what is written.
-template <int MERGE>
+// PAD: gate blocks narrower than 256 channels in the 256-wide tile, as in the forward kernel.
+template <int MERGE, bool PAD>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 decode_mfma_kernel(DecArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -597,7 +598,8 @@ decode_mfma_kernel(DecArgs a) {
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = blockIdx.x, b0 = blockIdx.y * TT;
   const int D = p.D, B = p.B;
-  const int ch = wv * 32 + j, d = g * BS + ch;
+  const int bs = PAD ? p.bs : BS;
+  const int ch = wv * 32 + j, d = g * bs + ((!PAD || ch < bs) ? ch : bs - 1);
 #ifdef RGLRU_TRACE
   unsigned long long tr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 #endif
@@ -615,7 +617,9 @@ decode_mfma_kernel(DecArgs a) {
       uniform_ptr(p.y), 0, (unsigned)B * row2, 0x00020000);
 
   // ---- Conv1D assignment: 8 channels (16 bytes) of rows (sequences) lr and lr + 16 of the tile
-  const int lc = tid & 31, lr = tid >> 5, dc = g * BS + 8 * lc;
+  const int lc = tid & 31, lr = tid >> 5;
+  const bool lc_ok = !PAD || 8 * lc < bs;           // missing channels: no input, x = 0
+  const int dc = g * bs + (lc_ok ? 8 * lc : 0);
   // per-channel vectors first (loads return in order, and these are needed first)
   f32x4 cw[4][2], cb[2];
 #pragma unroll
@@ -628,7 +632,7 @@ decode_mfma_kernel(DecArgs a) {
     cb[0] = *(const f32x4 *)cbp;
     cb[1] = *(const f32x4 *)(cbp + 4);
   }
-  const float cb_on = p.conv_b ? 1.f : 0.f;
+  const float cb_on = (p.conv_b && lc_ok) ? 1.f : 0.f;
   const float bias_p = p.b_a[d] * LOG2E, bias_q = p.b_x[d] * LOG2E, lam = p.Lambda[d];
 
   const int s1 = ring_slot(p.pos0 - 1), s2 = ring_slot(p.pos0 - 2), s3 = ring_slot(p.pos0 - 3);
@@ -637,7 +641,7 @@ decode_mfma_kernel(DecArgs a) {
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int b = b0 + lr + 16 * i;
-    const bool ok = b < B;
+    const bool ok = b < B && lc_ok;
     const unsigned uvo = ok ? (unsigned)b * row2 + (unsigned)dc * 2 : OOB;
     const unsigned rvo = ok ? (unsigned)(b * 3) * row2 + (unsigned)dc * 2 : OOB;
     ring_vo[i] = rvo;
@@ -654,18 +658,27 @@ decode_mfma_kernel(DecArgs a) {
   // (one per gate; LDS serves a wave's accesses in order, so a phase may be written while the
   // reads of the previous one are still queued). One phase is requested here, the next once
   // the Conv1D inputs are in (more would only delay those, queued behind).
-  const unsigned char *wrow_a = (const unsigned char *)p.W_a + ((size_t)g * BS + wv * 32) * BS * 2;
-  const unsigned char *wrow_x = (const unsigned char *)p.W_x + ((size_t)g * BS + wv * 32) * BS * 2;
-  const unsigned w_lane = (unsigned)(lane >> 3) * (BS * 2) + (unsigned)(lane & 7) * 16;
+  // (missing rows and K-steps of a narrower block are read from existing ones: they meet
+  // zeros in x or end in outputs that are dropped)
+  const unsigned char *wrow_a = (const unsigned char *)p.W_a + (size_t)g * bs * bs * 2;
+  const unsigned char *wrow_x = (const unsigned char *)p.W_x + (size_t)g * bs * bs * 2;
+  unsigned w_row[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = wv * 32 + i * 8 + (lane >> 3);
+    w_row[i] = (unsigned)((!PAD || r < bs) ? r : bs - 1) * (unsigned)(bs * 2);
+  }
   unsigned char *wl = smem + DEC_OFF_W + wv * 2 * DEC_WPH;
   const unsigned wl_wr = (unsigned)(lane >> 3) * DEC_WROW + (unsigned)(lane & 7) * 16;
   const unsigned wl_rd = (unsigned)j * DEC_WROW + (unsigned)hf * 16;
   u32x4 stg[2][8];
   auto load_phase = [&](int ph, u32x4 (&dst)[8]) __attribute__((always_inline)) {
+    const int c = ph * 8 + (lane & 7);   // 16-byte chunk of the row
+    const unsigned w_col = (unsigned)((!PAD || c < (bs >> 3)) ? c : (bs >> 3) - 1) * 16;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      dst[i] = *(const u32x4 *)(wrow_a + ph * 128 + w_lane + i * 8 * BS * 2);
-      dst[4 + i] = *(const u32x4 *)(wrow_x + ph * 128 + w_lane + i * 8 * BS * 2);
+      dst[i] = *(const u32x4 *)(wrow_a + w_row[i] + w_col);
+      dst[4 + i] = *(const u32x4 *)(wrow_x + w_row[i] + w_col);
     }
   };
   auto write_phase = [&](const u32x4 (&src)[8]) __attribute__((always_inline)) {
@@ -685,7 +698,8 @@ decode_mfma_kernel(DecArgs a) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int b = b0 + (lane >> 3) + 8 * i;
-    h_vo[i] = b < B ? ((unsigned)b * (unsigned)D + (unsigned)(g * BS + wv * 32 + (lane & 7) * 4)) * 4 : OOB;
+    const bool ok = b < B && (!PAD || wv * 32 + (lane & 7) * 4 < bs);
+    h_vo[i] = ok ? ((unsigned)b * (unsigned)D + (unsigned)(g * bs + wv * 32 + (lane & 7) * 4)) * 4 : OOB;
     hin[i] = __builtin_amdgcn_raw_buffer_load_b128(h_rsrc, h_vo[i], 0, 0);
   }
   // where this lane's 16 bytes of y (rows l/4 and l/4 + 16) go; the other branch is read there
@@ -696,7 +710,8 @@ decode_mfma_kernel(DecArgs a) {
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int b = b0 + (lane >> 2) + 16 * i;
-    y_vo[i] = b < B ? ((unsigned)b * (unsigned)D + (unsigned)(g * BS + wv * 32 + (lane & 3) * 8)) * 2 : OOB;
+    const bool ok = b < B && (!PAD || wv * 32 + (lane & 3) * 8 < bs);
+    y_vo[i] = ok ? ((unsigned)b * (unsigned)D + (unsigned)(g * bs + wv * 32 + (lane & 3) * 8)) * 2 : OOB;
     if (MERGE) brq[i] = __builtin_amdgcn_raw_buffer_load_b128(br_rsrc, y_vo[i], 0, 0);
   }
   RGLRU_TR(1);
@@ -860,6 +875,8 @@ hipError_t mfma::launch_prep(void *zero, size_t zero_bytes, hipStream_t s) {
 
 // gate block sizes the forward kernel takes: 256 channels, or narrower blocks (a multiple of 16,
 // at least half the tile: below that the padding costs more than the generic kernels)
+hipError_t launch_clear(void *at, size_t bytes, hipStream_t s) { return launch_prep(at, bytes, s); }
+
 bool forward_mfma_block(int bs) { return bs == BS || (bs % 16 == 0 && bs >= BS / 2 && bs < BS); }
 
 bool forward_mfma_supported(const Problem &p, bool bf) {
@@ -958,7 +975,7 @@ bool decode_mfma_supported(const Problem &p, bool bf) {
   const uintptr_t all = (uintptr_t)p.W_a | (uintptr_t)p.W_x | (uintptr_t)p.u | (uintptr_t)p.state_out |
                         (uintptr_t)p.hT | (uintptr_t)p.y | (uintptr_t)p.conv_w | (uintptr_t)p.conv_b |
                         (uintptr_t)(p.merge ? p.branch : nullptr);
-  return bf && p.bs == BS && all % 16 == 0 && (size_t)(p.B + TT) * 3 * p.D * 2 < ((size_t)1 << 31);
+  return bf && forward_mfma_block(p.bs) && all % 16 == 0 && (size_t)(p.B + TT) * 3 * p.D * 2 < ((size_t)1 << 31);
 }
 
 hipError_t launch_decode_mfma(const Problem &p, hipStream_t s) {
@@ -966,9 +983,15 @@ hipError_t launch_decode_mfma(const Problem &p, hipStream_t s) {
   a.p = p;
   KernelTimer kt("decode_mfma_kernel", s);
   const dim3 grid(p.nb, (p.B + TT - 1) / TT);
-  if (p.merge == 0) hipLaunchKernelGGL(decode_mfma_kernel<0>, grid, dim3(NTHR), DEC_LDS, s, a);
-  else if (p.merge == 1) hipLaunchKernelGGL(decode_mfma_kernel<1>, grid, dim3(NTHR), DEC_LDS, s, a);
-  else hipLaunchKernelGGL(decode_mfma_kernel<2>, grid, dim3(NTHR), DEC_LDS, s, a);
+  if (p.bs == BS) {
+    if (p.merge == 0) hipLaunchKernelGGL((decode_mfma_kernel<0, false>), grid, dim3(NTHR), DEC_LDS, s, a);
+    else if (p.merge == 1) hipLaunchKernelGGL((decode_mfma_kernel<1, false>), grid, dim3(NTHR), DEC_LDS, s, a);
+    else hipLaunchKernelGGL((decode_mfma_kernel<2, false>), grid, dim3(NTHR), DEC_LDS, s, a);
+  } else {
+    if (p.merge == 0) hipLaunchKernelGGL((decode_mfma_kernel<0, true>), grid, dim3(NTHR), DEC_LDS, s, a);
+    else if (p.merge == 1) hipLaunchKernelGGL((decode_mfma_kernel<1, true>), grid, dim3(NTHR), DEC_LDS, s, a);
+    else hipLaunchKernelGGL((decode_mfma_kernel<2, true>), grid, dim3(NTHR), DEC_LDS, s, a);
+  }
   return hipGetLastError();
 }
 

@@ -107,6 +107,16 @@ size_t backward_mfma_ws_bytes(int B, int T, int D, int nb);
 size_t backward_mfma_flag_offset(int B, int T, int D, int nb);   // byte offset of the timeout flag
 hipError_t launch_backward_mfma(const Problem &p, hipStream_t s);
 
+// Backward for narrower gate blocks: the problem widened to 256-channel blocks in the workspace
+bool backward_padded_block(int bs);
+bool backward_padded_supported(const Problem &p, bool bf);
+size_t backward_padded_ws_bytes(int B, int T, int D, int nb);
+size_t backward_padded_flag_offset(int B, int T, int D, int nb);
+hipError_t launch_backward_padded(const Problem &p, hipStream_t s);
+
+// clears `bytes` (% 16 == 0) at a 16-byte aligned address with a fill kernel
+hipError_t launch_clear(void *at, size_t bytes, hipStream_t s);
+
 // Linear scan of eq. (4): any shape and storage type / bf16 storage with D % 256 == 0
 hipError_t launch_scan_generic(const ScanProblem &p, bool bf, hipStream_t s);
 bool scan_tiled_supported(const ScanProblem &p, bool bf);

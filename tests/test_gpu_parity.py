@@ -173,7 +173,9 @@ BWD_SHAPES = [
     (3, 3, 40, 5, "f32"),
     (2, 1, 16, 1, "f32"),
     (2, 75, 512, 2, "bf16"),
-    (2, 33, 320, 2, "bf16"),
+    (2, 33, 320, 2, "bf16"),      # bs = 160: the problem is widened to 256-channel blocks
+    (3, 300, 2560, 16, "bf16"),   # the same at the paper's width, 16 blocks
+    (1, 1100, 384, 2, "bf16"),    # bs = 192, long sequence in time slices
     (1, 270, 600, 2, "bf16"),
     (1, 1, 256, 1, "bf16"),       # MFMA path, single step
     (2, 31, 256, 1, "bf16"),      # MFMA path, one partial tile
