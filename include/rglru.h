@@ -42,6 +42,11 @@
  *   h_t = a_t h_{t-1} + sqrt(1 - a_t^2) (i_t x_t),  y_t = h_t             eq. (4)
  * (Appendix A prints softplus(+Lambda); that contradicts a = sigma(Lambda) of Section 2.4,
  * which is what this library follows.)
+ *
+ * Which kernels run: bf16 storage with gate blocks of 256 channels, or of a multiple of 16
+ * channels from 128 to 240 (e.g. Section 4.1's 16 blocks at width 2560 = 160 channels), runs on
+ * the matrix-core kernels; every other block size up to 2048 and fp32 storage run on generic
+ * kernels that give the same results far more slowly. rglru_workspace_bytes() accounts for it.
  */
 #ifndef RGLRU_H
 #define RGLRU_H

@@ -1,6 +1,6 @@
 """Per-workload timing report of the Conv1D -> RG-LRU path on one MI355X.
 
-    python -m paper_2402_19427_amd.workloads [--configs C0,C1,C2,C3,C4,SCAN,MERGE] [--json]
+    python -m paper_2402_19427_amd.workloads [--configs C0,C1,C2,C3,C4,SCAN,MERGE,NB16] [--json]
 
 For each of the five synthetic workloads it times the calls that workload is about (forward;
 forward and backward for the training shape; the single-token decode step for the decode shape,
@@ -13,9 +13,12 @@ step is also timed on one buffer set ("hot"). SCAN is the scan-only entry point 
 given decays and gated inputs) at the shape the paper times it: batch 8, width 1024, a sweep of
 sequence lengths. MERGE times the calls that take the recurrent block's merge with its GeLU
 branch along (as the kernels' epilogue, and as a kernel of its own for comparison) on the
-workloads C1-C4. Inputs are seeded and synthetic.
+workloads C1-C4. NB16 repeats C1 (forward, backward) and a decode step at width 2560 with the
+paper's 16 gate blocks of 160 channels (Section 4.1) instead of 10 blocks of 256. Inputs are
+seeded and synthetic.
 """
 import argparse
+import dataclasses
 import json
 import sys
 
@@ -130,7 +133,7 @@ def run_sequence_workload(w, dev, out):
                    gate_flops("backward", B, T, D, nb)))
 
 
-def run_decode_workload(w, dev, out, steps=1000):
+def run_decode_workload(w, dev, out, steps=1000, graph_only=False):
     B, D, nb = w.B, w.D, w.nb
     act_b = 2 if w.act == "bf16" else 4
     inp = gen.make_inputs(1, 8, D, nb, act=w.act, seed=w.seed)
@@ -159,18 +162,19 @@ def run_decode_workload(w, dev, out, steps=1000):
         pos[0] += 1
 
     for nsets, label in ((1, "hot: 1 buffer set"), (ncold, "cold: %d buffer sets" % ncold)):
-        ms = time_calls(step, nsets, steps, 20)
-        out.append(row(w.name, "decode, per launch", label, ms, B, nbytes, flops))
-        # the same 1000 steps back to back: launch overhead overlaps with execution
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for i in range(steps):
-            step(i % nsets)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = np.array([e0.elapsed_time(e1) / steps])
-        out.append(row(w.name, "decode, %d launches back to back" % steps, label, ms, B, nbytes, flops))
+        ms = time_calls(step, nsets, 20 if graph_only else steps, 20)
+        if not graph_only:
+            out.append(row(w.name, "decode, per launch", label, ms, B, nbytes, flops))
+            # the same 1000 steps back to back: launch overhead overlaps with execution
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(steps):
+                step(i % nsets)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = np.array([e0.elapsed_time(e1) / steps])
+            out.append(row(w.name, "decode, %d launches back to back" % steps, label, ms, B, nbytes, flops))
         # ... and replayed as one HIP graph (the position is baked in at capture: timing only)
         graph = torch.cuda.CUDAGraph()
         torch.cuda.synchronize()
@@ -329,7 +333,7 @@ def run_merge_workload(dev, out, names=("C1", "C2", "C3", "C4"), steps=1000):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--configs", default="C0,C1,C2,C3,C4,SCAN,MERGE")
+    ap.add_argument("--configs", default="C0,C1,C2,C3,C4,SCAN,MERGE,NB16")
     ap.add_argument("--scan-lengths", default="1024,4096,16384,65536")
     ap.add_argument("--json", action="store_true", help="print one JSON object per row instead of the table")
     args = ap.parse_args()
@@ -343,6 +347,11 @@ def main():
             run_scan_workload(dev, out, tuple(int(x) for x in args.scan_lengths.split(",")))
         elif name == "MERGE":
             run_merge_workload(dev, out)
+        elif name == "NB16":
+            c1 = gen.CONFIGS["C1"]
+            run_sequence_workload(dataclasses.replace(c1, name="NB16", nb=16, kind="train"), dev, out)
+            run_decode_workload(dataclasses.replace(gen.CONFIGS["C3"], name="NB16", D=2560), dev, out,
+                                graph_only=True)
         elif w.kind == "decode":
             run_decode_workload(w, dev, out)
         else:

@@ -225,3 +225,19 @@ def test_decode_step_merge_validation():
     with pytest.raises(R.RglruError) as e:
         R.rglru_decode_step_merge(s, params(), FAKE, FAKE, FAKE, FAKE, -1, 0, OUT)
     assert e.value.code == R.ERR_INVALID_ARG and "pos" in str(e.value)
+
+
+def test_workspace_sizes_for_narrower_gate_blocks():
+    # 16 blocks of 160 channels (bf16): forward in the padded tile needs the record rings of the
+    # tuned kernel; the backward a widened copy (four activation tensors of nb*256 channels) plus
+    # the tuned backward's workspace at that width
+    narrow = R.make_shape(8, 2048, 2560, 16, R.BF16)
+    wide = R.make_shape(8, 2048, 4096, 16, R.BF16)
+    assert R.rglru_workspace_bytes(narrow, R.OP_FORWARD) == R.rglru_workspace_bytes(wide, R.OP_FORWARD) > 0
+    need = R.rglru_workspace_bytes(narrow, R.OP_BACKWARD)
+    inner = R.rglru_workspace_bytes(wide, R.OP_BACKWARD)
+    assert need > inner + 4 * 8 * 2048 * 4096 * 2 and need % 256 == 0
+    # other block sizes stay on the generic kernels: no forward workspace
+    assert R.rglru_workspace_bytes(R.make_shape(8, 2048, 2560, 8, R.BF16), R.OP_FORWARD) == 0    # bs 320
+    assert R.rglru_workspace_bytes(R.make_shape(8, 2048, 2560, 32, R.BF16), R.OP_FORWARD) == 0   # bs 80
+    assert R.rglru_workspace_bytes(R.make_shape(8, 2048, 2560, 16, R.F32), R.OP_FORWARD) == 0

@@ -209,3 +209,37 @@ def test_forward_with_the_block_s_merge_full_size(name, pairs):
         assert gen.rel_err(out_h[b:b + 1, :, sl], out_ref) < TOL, (name, b, g)
         assert gen.rel_err(hT_h[b:b + 1, sl], hT_ref) < TOL, (name, b, g)
     assert np.isfinite(out_h).all()
+
+
+def test_the_paper_s_sixteen_blocks_at_width_2560_full_size():
+    # Section 4.1's 16 gate blocks at width 2560 (160 channels each) at C1's size: forward in the
+    # padded tile, backward on the widened copy; one sampled (sequence, block) pair for the
+    # activations, every sequence for the block's parameter gradients
+    import dataclasses
+    import paper_2402_19427_amd.runner as rn
+    w = dataclasses.replace(gen.CONFIGS["C1"], nb=16)
+    inp = gen.make_inputs(w.B, w.T, w.D, w.nb, act=w.act, seed=w.seed, dy=True)
+    dp = rn.DeviceProblem(inp, w.B, w.T, w.D, w.nb, w.act)
+    u = rn.to_device(inp["u"], w.act)
+    y, hT, st = dp.forward(u)
+    grads = dp.backward(u, y, rn.to_device(inp["dy"], w.act))
+    y_h, du_h = rn.to_host(y), rn.to_host(grads["du"])
+    dW_h, dL_h = rn.to_host(grads["dW_a"]), rn.to_host(grads["dLambda"])
+    oracle.set_threads(8)
+    g = 11
+    sl, par = block_params(inp, g, w.bs)
+    dW = np.zeros((w.bs, w.bs))
+    dL = np.zeros(w.bs)
+    for b in range(w.B):
+        ub = np.asarray(inp["u"][b:b + 1, :, sl], np.float64)
+        dyb = np.asarray(inp["dy"][b:b + 1, :, sl], np.float64)
+        ref = oracle.backward(ub, *par, dyb)
+        dW += ref["dW_a"][0]
+        dL += ref["dLambda"]
+        if b == 5:
+            y_ref, _, _ = oracle.forward(ub, *par)
+            assert gen.rel_err(y_h[b:b + 1, :, sl], y_ref) < TOL
+            assert gen.rel_err(du_h[b:b + 1, :, sl], ref["du"]) < TOL
+    assert gen.rel_err(dW_h[g], dW) < TOL
+    assert gen.rel_err(dL_h[sl], dL) < TOL
+    assert np.isfinite(y_h).all() and np.isfinite(du_h).all() and np.isfinite(dW_h).all()
