@@ -136,7 +136,11 @@ fwd_mfma_kernel(FwdArgs a) {
   // every tile - a far better spill space than scratch memory)
   // (the merge epilogue holds eight more registers: the tile's rows of the other branch)
   constexpr int NRES_PLAIN = GMAX == 1 ? 13 : (GMAX == 4 ? 9 : (GMAX == 8 ? 6 : 2));   // measured best
-  constexpr int NRES = MERGE == 0 ? NRES_PLAIN : (NRES_PLAIN >= 2 ? NRES_PLAIN - 2 : 0);
+  constexpr int NRES_M = MERGE == 0 ? NRES_PLAIN : (NRES_PLAIN >= 2 ? NRES_PLAIN - 2 : 0);
+  // (a narrower block has fewer K-steps that matter, and its clamped addresses cost registers;
+  // measured best at 160 channels)
+  constexpr int NRES_P = GMAX == 1 ? 11 : (GMAX == 4 ? 2 : (GMAX == 8 ? 0 : 2));
+  constexpr int NRES = !PAD ? NRES_M : (MERGE == 0 ? NRES_P : (NRES_P >= 2 ? NRES_P - 2 : 0));
   constexpr int PF = 2;   // streamed fragments in flight (deeper rings measured no better)
   bf16x8 wa[16], wx[NRES > 0 ? NRES : 1];
   const bf16x8 *pxs = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * bs + chc) * bs + hf * 8);
