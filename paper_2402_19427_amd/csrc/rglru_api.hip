@@ -145,6 +145,9 @@ size_t workspace_need(const rglru_shape *s, int op) {
     case RGLRU_OP_FORWARD:
       if (s->act_dtype == RGLRU_BF16 && forward_mfma_block(s->D / s->num_blocks) && s->T >= 1)
         return forward_mfma_ws_bytes(s->B, s->T, s->D, s->num_blocks);
+      if (s->act_dtype == RGLRU_BF16 && forward_wide_block(s->D / s->num_blocks) && s->T >= 1 &&
+          (size_t)s->B * s->T * s->D * 2 < ((size_t)1 << 31))
+        return forward_wide_ws_bytes(s->B, s->T, s->D, s->num_blocks);
       return 0;
     default:
       return 0;
@@ -215,6 +218,27 @@ int backward_checks(const rglru_shape *shape, const rglru_params *params, const 
 }
 }  // namespace
 
+namespace {
+// the forward over whole sequences on the fastest kernels that take the shape; y and the new
+// ring state are written
+int forward_dispatch(const Problem &q, bool bf, hipStream_t s) {
+  hipError_t e;
+  if (forward_mfma_supported(q, bf)) {
+    e = launch_forward_mfma(q, s);  // writes the new ring state itself
+  } else if (forward_wide_supported(q, bf) && q.ws &&
+             q.ws_bytes >= forward_wide_ws_bytes(q.B, q.T, q.D, q.nb)) {
+    e = launch_forward_wide(q, s);
+  } else {
+    e = launch_forward_generic(q, bf, s);
+    if (e != hipSuccess) return hip_fail(e, "forward launch");
+    // the new ring state is written after the last read of the incoming one (they may alias)
+    e = launch_state_update(q, bf, s);
+  }
+  if (e != hipSuccess) return hip_fail(e, "forward launch");
+  return RGLRU_OK;
+}
+}  // namespace
+
 extern "C" {
 
 int rglru_timing_enable(int enable) {
@@ -269,6 +293,13 @@ int rglru_workspace_status(const rglru_shape *shape, int op, const void *workspa
   if (need == 0) return RGLRU_OK;   // no time slices, no waits
   if (!workspace) return fail(RGLRU_ERR_INVALID_ARG, "workspace is NULL");
   size_t off = 0;   // forward and scan keep the flag in the first word
+  if ((op == RGLRU_OP_FORWARD || op == RGLRU_OP_FORWARD_MERGE) &&
+      !forward_mfma_block(shape->D / shape->num_blocks)) {
+    // the passes of the other block sizes: only the scan waits, its workspace follows three
+    // activation-sized buffers
+    if (shape->D % 256 != 0 || scan_tiled_ws_bytes(shape->B, shape->T, shape->D) == 0) return RGLRU_OK;
+    off = need - scan_tiled_ws_bytes(shape->B, shape->T, shape->D);
+  }
   if (bwd) {
     if (shape->act_dtype == RGLRU_BF16 && shape->D / shape->num_blocks == 256 &&
         (size_t)shape->T * shape->D * 4 < ((size_t)1 << 32))
@@ -340,17 +371,7 @@ int rglru_forward(const rglru_shape *shape, const rglru_params *params, const vo
   q.ws = workspace; q.ws_bytes = workspace_bytes;
   const bool bf = shape->act_dtype == RGLRU_BF16;
   hipStream_t s = (hipStream_t)stream;
-  hipError_t e;
-  if (forward_mfma_supported(q, bf)) {
-    e = launch_forward_mfma(q, s);  // writes the new ring state itself
-    if (e != hipSuccess) return hip_fail(e, "forward launch");
-  } else {
-    e = launch_forward_generic(q, bf, s);
-    if (e != hipSuccess) return hip_fail(e, "forward launch");
-    // the new ring state is written after the last read of the incoming one (they may alias)
-    e = launch_state_update(q, bf, s);
-  }
-  if (e != hipSuccess) return hip_fail(e, "conv state launch");
+  CHECK(forward_dispatch(q, bf, s));
   g_err[0] = 0;
   return RGLRU_OK;
 }
@@ -488,15 +509,7 @@ int rglru_forward_merge(const rglru_shape *shape, const rglru_params *params, co
   // without the fused epilogue: y goes to its own buffer, or through `out` when it is not kept
   q.merge = 0;
   q.y = y ? y : out;
-  if (forward_mfma_supported(q, bf)) {
-    e = launch_forward_mfma(q, s);
-    if (e != hipSuccess) return hip_fail(e, "forward launch");
-  } else {
-    e = launch_forward_generic(q, bf, s);
-    if (e != hipSuccess) return hip_fail(e, "forward launch");
-    e = launch_state_update(q, bf, s);
-    if (e != hipSuccess) return hip_fail(e, "conv state launch");
-  }
+  CHECK(forward_dispatch(q, bf, s));
   e = launch_merge_forward(q.y, branch, out, (size_t)shape->B * shape->T * shape->D, bf, tanh_form, s);
   if (e != hipSuccess) return hip_fail(e, "merge launch");
   g_err[0] = 0;

@@ -97,6 +97,13 @@ size_t forward_mfma_ws_bytes(int B, int T, int D, int nb);
 hipError_t launch_forward_mfma(const Problem &p, hipStream_t s);
 bool forward_mfma_merge_fused(const Problem &p);   // merge as epilogue (else: a kernel of its own)
 
+// Forward for the other block sizes in bf16 (any multiple of 16): Conv1D, gate products + gates,
+// scan as separate passes through the workspace
+bool forward_wide_block(int bs);
+bool forward_wide_supported(const Problem &p, bool bf);
+size_t forward_wide_ws_bytes(int B, int T, int D, int nb);
+hipError_t launch_forward_wide(const Problem &p, hipStream_t s);
+
 // MFMA decode step (bf16 storage, gate blocks of 256)
 bool decode_mfma_supported(const Problem &p, bool bf);
 hipError_t launch_decode_mfma(const Problem &p, hipStream_t s);

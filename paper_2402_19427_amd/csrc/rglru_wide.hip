@@ -1,0 +1,309 @@
+// Forward for the gate block sizes the fused kernel does not take (bf16 storage, any multiple of
+// 16 channels: Section 4.1's 16 blocks give 352 and 512 channels at widths 5632 and 8192), as
+// three passes over kernels that exist plus one that is new here:
+//   1. Conv1D (Section 2.3) into x, bf16, in the workspace        conv1d_kernel
+//   2. gates_wide_kernel: the gate products of eqs. (1)-(2) on the matrix cores over the whole
+//      K = bs of a block in chunks of 256 input channels, then eqs. (1)-(3) per element; it
+//      writes log a_t and b_t = sqrt(1 - a_t^2) i_t x_t (bf16) to the workspace
+//   3. eq. (4) as a linear scan over (log a_t, b_t)                the scan-only kernels
+// and the Conv1D ring update. About 16 bytes per element through memory instead of the fused
+// kernel's 4, and the gate weights come from L2 for every 64 rows; the generic kernels these
+// shapes ran on before are ~30 times slower.
+#include "rglru_mfma.h"
+
+#include <math.h>
+
+namespace rglru {
+using namespace mfma;
+
+namespace {
+
+constexpr int WM = 64;                       // rows (sequence, step) per workgroup: two MFMA row tiles
+constexpr int W_XT = WM * XS;                // one [64][264] bf16 tile, in elements
+constexpr int W_OFF_SEL = 2 * W_XT * 2;      // two buffers
+constexpr int W_OFF_OT = W_OFF_SEL + 64 * 32;
+constexpr int W_LDS = W_OFF_OT + NWAVE * OTILE_BYTES;
+constexpr unsigned OOB = 0x80000000u;        // buffer offset past every range
+
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+struct WideArgs {
+  Problem p;
+  const unsigned short *x;     // [M][D] Conv1D output
+  unsigned short *la, *gb;     // [M][D] log a_t, b_t
+  int nob;                     // groups of 256 output channels per block = K chunks per block
+  unsigned M;                  // B * T
+};
+
+__global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
+gates_wide_kernel(WideArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned short *xs = (unsigned short *)smem;                     // [2][WM][XS]
+  bf16x8 *sel_lds = (bf16x8 *)(smem + W_OFF_SEL);
+  const Problem &p = a.p;
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, j = lane & 31;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  unsigned short *otile = (unsigned short *)(smem + W_OFF_OT) + wv * (OTILE_BYTES / 2);
+  const int D = p.D, bs = p.bs;
+  const int g = blockIdx.y / a.nob, ob = blockIdx.y - g * a.nob;
+  const unsigned m0 = blockIdx.x * WM;
+  const unsigned row_bytes = (unsigned)D * 2;
+
+  // this lane's output channel; a channel past the block is computed from an existing one's
+  // parameters and never stored
+  const int och = ob * BS + wv * 32 + j;
+  const int ochc = och < bs ? och : bs - 1;
+  const int d = g * bs + ochc;
+  const float bias_p = p.b_a[d], bias_q = p.b_x[d];
+  float kdn;  // -c * softplus(-Lambda) = log of the fully open decay, eq. (3)
+  {
+    const float z = -p.Lambda[d];
+    const float sp = z > 0.f ? z + log1pf(expf(-z)) : log1pf(expf(z));
+    kdn = -p.c * sp;
+  }
+  const unsigned short *wa_row = (const unsigned short *)p.W_a + ((size_t)g * bs + ochc) * bs;
+  const unsigned short *wx_row = (const unsigned short *)p.W_x + ((size_t)g * bs + ochc) * bs;
+
+  if (tid < 64) {   // selection operands, as in the fused kernel
+    bf16x8 sel0, sel1;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      sel0[e] = (__bf16)((hf * 8 + e == j) ? 1.0f : 0.0f);
+      sel1[e] = (__bf16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
+    }
+    sel_lds[lane] = sel0;
+    sel_lds[64 + lane] = sel1;
+  }
+
+  // ---- x tile loader: thread -> 16 bytes (8 channels) of rows r0, r0 + 16, r0 + 32, r0 + 48
+  const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_ptr(a.x), 0, a.M * row_bytes, 0x00020000);
+  const int lc = tid & 31, r0 = tid >> 5;
+  u32x4 nx[4];
+  auto load_chunk = [&](int kc) __attribute__((always_inline)) {   // chunk kc of the block's input channels
+    const int col = kc * BS + lc * 8;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const unsigned m = m0 + r0 + 16 * i;
+      const bool ok = m < a.M && col < bs;   // (kc past the last chunk: col >= bs)
+      nx[i] = __builtin_amdgcn_raw_buffer_load_b128(
+          x_rsrc, ok ? m * row_bytes + (unsigned)(g * bs + col) * 2 : OOB, 0, 0);
+    }
+  };
+  auto park_chunk = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *(u32x4 *)(xs + buf * W_XT + (r0 + 16 * i) * XS + lc * 8) = nx[i];
+  };
+
+  const int arow = ((j >> 2) & 1) * 16 + (j >> 3) * 4 + (j & 3);   // row of this lane's A operand
+  f32x16 accp[2], accq[2], accx[2];
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      accp[mi][r] = bias_p;
+      accq[mi][r] = bias_q;
+      accx[mi][r] = 0.f;
+    }
+
+  load_chunk(0);
+  park_chunk(0);
+  __syncthreads();
+
+  for (int kc = 0; kc < a.nob; ++kc) {
+    const int buf = kc & 1;
+    load_chunk(kc + 1);   // lands during the products (nothing is read past the last chunk)
+    const unsigned short *ap = xs + buf * W_XT + arow * XS + hf * 8;
+    // weight fragments of K-step ks: 8 consecutive inputs of this lane's output row; K-steps
+    // past the block re-read the last one (their x columns are zero)
+    auto frag_off = [&](int ks) __attribute__((always_inline)) {
+      const int k0 = kc * BS + ks * 16 + hf * 8;
+      return k0 < bs ? k0 : bs - 8;
+    };
+    bf16x8 fa = *(const bf16x8 *)(wa_row + frag_off(0)), fx = *(const bf16x8 *)(wx_row + frag_off(0));
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) {
+      bf16x8 fa_n = fa, fx_n = fx;
+      if (ks + 1 < 16) {
+        fa_n = *(const bf16x8 *)(wa_row + frag_off(ks + 1));
+        fx_n = *(const bf16x8 *)(wx_row + frag_off(ks + 1));
+      }
+      const bf16x8 a0 = *(const bf16x8 *)(ap + ks * 16), a1 = *(const bf16x8 *)(ap + 32 * XS + ks * 16);
+      accp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, fa, accp[0], 0, 0, 0);
+      accq[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, fx, accq[0], 0, 0, 0);
+      accp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, fa, accp[1], 0, 0, 0);
+      accq[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, fx, accq[1], 0, 0, 0);
+      fa = fa_n;
+      fx = fx_n;
+    }
+    if (kc == ob) {   // this chunk holds the wave's own channels: x_t into accumulator layout
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi) {
+        const unsigned short *sp = ap + mi * 32 * XS;
+        accx[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(sp + (2 * wv) * 16), sel_lds[lane], accx[mi], 0, 0, 0);
+        accx[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(sp + (2 * wv + 1) * 16), sel_lds[64 + lane], accx[mi], 0, 0, 0);
+      }
+    }
+    park_chunk(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- eqs. (1)-(3) per element; the two results leave through the wave's staging tile as
+  // 16-byte rows
+  const __amdgpu_buffer_rsrc_t la_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_ptr(a.la), 0, a.M * row_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t gb_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_ptr(a.gb), 0, a.M * row_bytes, 0x00020000);
+  const bool chunk_ok = ob * BS + wv * 32 + (lane & 3) * 8 < bs;
+  const unsigned o_voff =
+      chunk_ok ? (unsigned)(g * bs + ob * BS + wv * 32 + (lane & 3) * 8) * 2 + (unsigned)(lane >> 2) * row_bytes : OOB;
+  unsigned short *ot_mine = otile + (hf * 16) * OT + j;
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi) {
+    const unsigned mrow = m0 + mi * 32;
+    const int nrows = (int)a.M - (int)mrow;
+    float bv[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float rg = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-LOG2E * accp[mi][r]));
+      const float la = kdn * rg;
+      const float av = __builtin_amdgcn_exp2f(LOG2E * la);
+      const float mm = __builtin_amdgcn_sqrtf(fmaf(-av, av, 1.f));
+      const float ig = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-LOG2E * accq[mi][r]));
+      bv[r] = mm * ig * accx[mi][r];
+      ot_mine[r * OT] = (unsigned short)(pack_bf16(la, 0.f) & 0xffff);
+    }
+    store_staged_tile_s<OT, 0>(otile, lane, la_rsrc, o_voff, mrow * row_bytes, row_bytes, nrows);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) ot_mine[r * OT] = (unsigned short)(pack_bf16(bv[r], 0.f) & 0xffff);
+    store_staged_tile_s<OT, 0>(otile, lane, gb_rsrc, o_voff, mrow * row_bytes, row_bytes, nrows);
+  }
+}
+
+inline size_t al256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+// ---- Conv1D (Section 2.3) as a streaming pass: a thread produces 8 channels (16 bytes) of CR
+// consecutive steps from CR + 3 input rows; steps before the sequence start read the carried
+// ring state (slot = position mod 3) or zero.
+constexpr int CR = 8;
+struct ConvArgs {
+  Problem p;
+  unsigned short *x;
+};
+__global__ void __launch_bounds__(256) conv_rows_kernel(ConvArgs a) {
+  const Problem &p = a.p;
+  const int D = p.D, T = p.T, nch = D / 8, ntr = (T + CR - 1) / CR;
+  const size_t total = (size_t)p.B * ntr * nch;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % nch);
+  const int tr = (int)((i / nch) % ntr);
+  const int b = (int)(i / ((size_t)nch * ntr));
+  const int t0 = tr * CR, d0 = c * 8;
+  float w[4][8], bias[8];
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) w[k][e] = p.conv_w[(size_t)k * D + d0 + e];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) bias[e] = p.conv_b ? p.conv_b[d0 + e] : 0.f;
+  const unsigned short *u = (const unsigned short *)p.u + (size_t)b * T * D + d0;
+  const unsigned short *st = p.state_in ? (const unsigned short *)p.state_in + (size_t)b * 3 * D + d0 : nullptr;
+  u32x4 in[CR + 3];
+#pragma unroll
+  for (int n = 0; n < CR + 3; ++n) {
+    const int t = t0 - 3 + n;
+    u32x4 v = {0, 0, 0, 0};
+    if (t >= 0) {
+      if (t < T) v = *(const u32x4 *)(u + (size_t)t * D);
+    } else if (st) {
+      v = *(const u32x4 *)(st + (size_t)ring_slot(p.pos0 + t) * D);
+    }
+    in[n] = v;
+  }
+#pragma unroll
+  for (int r = 0; r < CR; ++r) {
+    if (t0 + r >= T) break;
+    u32x4 o;
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+      float x0 = bias[2 * e2], x1 = bias[2 * e2 + 1];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {   // lag k multiplies the input k steps back
+        const unsigned v = in[r + 3 - k][e2];
+        x0 = fmaf(w[k][2 * e2], bf_lo(v), x0);
+        x1 = fmaf(w[k][2 * e2 + 1], bf_hi(v), x1);
+      }
+      o[e2] = pack_bf16(x0, x1);
+    }
+    *(u32x4 *)(a.x + ((size_t)b * T + t0 + r) * D + d0) = o;
+  }
+}
+
+}  // namespace
+
+bool forward_wide_block(int bs) { return bs % 16 == 0 && bs >= 16 && !forward_mfma_block(bs); }
+
+bool forward_wide_supported(const Problem &p, bool bf) {
+  const uintptr_t all = (uintptr_t)p.W_a | (uintptr_t)p.W_x | (uintptr_t)p.y;
+  return bf && forward_wide_block(p.bs) && p.T >= 1 && all % 16 == 0 &&
+         (size_t)p.B * p.T * p.D * 2 < ((size_t)1 << 31);
+}
+
+size_t forward_wide_ws_bytes(int B, int T, int D, int nb) {
+  const size_t n = al256((size_t)B * T * D * 2);
+  return 3 * n + (D % BS == 0 ? scan_tiled_ws_bytes(B, T, D) : 0);
+}
+
+hipError_t launch_forward_wide(const Problem &p, hipStream_t s) {
+  const size_t n = al256((size_t)p.B * p.T * p.D * 2);
+  char *ws = (char *)p.ws;
+  void *x = ws, *la = ws + n, *gb = ws + 2 * n;
+  hipError_t e;
+  {
+    KernelTimer kt("conv_rows_kernel", s);
+    const bool wide16 = p.D % 8 == 0 && ((uintptr_t)p.u % 16 == 0) && (!p.state_in || (uintptr_t)p.state_in % 16 == 0) &&
+                        ((uintptr_t)p.conv_w % 16 == 0);
+    if (wide16) {
+      ConvArgs c;
+      c.p = p;
+      c.x = (unsigned short *)x;
+      const size_t total = (size_t)p.B * ((p.T + CR - 1) / CR) * (p.D / 8);
+      hipLaunchKernelGGL(conv_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, c);
+      e = hipGetLastError();
+    } else {
+      e = launch_conv1d_generic(p, true, x, s);
+    }
+  }
+  if (e != hipSuccess) return e;
+  WideArgs a;
+  a.p = p;
+  a.x = (const unsigned short *)x;
+  a.la = (unsigned short *)la;
+  a.gb = (unsigned short *)gb;
+  a.nob = (p.bs + BS - 1) / BS;
+  a.M = (unsigned)((size_t)p.B * p.T);
+  static bool configured = false;
+  if (!configured) {
+    e = hipFuncSetAttribute((const void *)gates_wide_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  {
+    KernelTimer kt("gates_wide_kernel", s);
+    hipLaunchKernelGGL(gates_wide_kernel, dim3((a.M + WM - 1) / WM, p.nb * a.nob), dim3(NTHR), W_LDS, s, a);
+    e = hipGetLastError();
+  }
+  if (e != hipSuccess) return e;
+  ScanProblem q;
+  q.B = p.B; q.T = p.T; q.D = p.D;
+  q.flags = RGLRU_SCAN_LOG_A | RGLRU_SCAN_NO_INPUT_SCALE;   // b_t already carries sqrt(1 - a_t^2)
+  q.a = la; q.g = gb; q.h0 = p.h0; q.h = p.y; q.hT = p.hT;
+  q.ws = ws + 3 * n;
+  q.ws_bytes = p.ws_bytes > 3 * n ? p.ws_bytes - 3 * n : 0;
+  e = scan_tiled_supported(q, true) ? launch_scan_tiled(q, s) : launch_scan_generic(q, true, s);
+  if (e != hipSuccess) return e;
+  return launch_state_update(p, true, s);
+}
+
+}  // namespace rglru

@@ -46,6 +46,11 @@ SHAPES = [
     (3, 300, 2560, 16, "bf16"),  # the same at full width: 48 units x 5 slices, ragged T
     (1, 1100, 384, 2, "bf16"),   # bs = 192, 16 slices
     (40, 40, 288, 2, "bf16"),    # bs = 144 (a multiple of 16 only), one workgroup per unit
+    (2, 100, 2816, 8, "bf16"),   # bs = 352 (16 blocks at width 5632): separate passes, 2 K chunks
+    (1, 700, 1024, 2, "bf16"),   # bs = 512 (16 blocks at width 8192), scan in time slices
+    (3, 70, 256, 4, "bf16"),     # bs = 64: separate passes, one partial K chunk
+    (1, 130, 1536, 2, "bf16"),   # bs = 768: three K chunks
+    (2, 37, 96, 2, "bf16"),      # bs = 48, width not a multiple of 256: generic scan pass
     (1, 9, 24, 24, "bf16"),      # nb = D: per-channel gates
     (2, 300, 600, 2, "bf16"),    # bs = 300 > workgroup size
     (1, 1, 256, 1, "bf16"),      # MFMA path, one step
