@@ -22,7 +22,12 @@ constexpr int WM = 64;                       // rows (sequence, step) per workgr
 constexpr int W_XT = WM * XS;                // one [64][264] bf16 tile, in elements
 constexpr int W_OFF_SEL = 2 * W_XT * 2;      // two buffers
 constexpr int W_OFF_OT = W_OFF_SEL + 64 * 32;
-constexpr int W_LDS = W_OFF_OT + NWAVE * OTILE_BYTES;
+// per wave and gate: 4 K-steps (128 bytes) of the wave's 32 weight rows, turned into MFMA fragment
+// order through LDS; the row stride keeps 16-byte reads down a column free of bank conflicts
+constexpr int W_WROW = 128 + 16;
+constexpr int W_WPH = 32 * W_WROW;
+constexpr int W_OFF_W = W_OFF_OT + NWAVE * OTILE_BYTES;
+constexpr int W_LDS = W_OFF_W + NWAVE * 2 * W_WPH;
 constexpr unsigned OOB = 0x80000000u;        // buffer offset past every range
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
@@ -61,8 +66,39 @@ gates_wide_kernel(WideArgs a) {
     const float sp = z > 0.f ? z + log1pf(expf(-z)) : log1pf(expf(z));
     kdn = -p.c * sp;
   }
-  const unsigned short *wa_row = (const unsigned short *)p.W_a + ((size_t)g * bs + ochc) * bs;
-  const unsigned short *wx_row = (const unsigned short *)p.W_x + ((size_t)g * bs + ochc) * bs;
+  // ---- gate weights: a fragment read straight from the row-major matrix touches 32 cache lines
+  // per instruction; instead the wave reads whole 128-byte lines of its 32 rows (8 lanes per
+  // row, 4 K-steps of both gates per phase) and turns them into fragment order through its own
+  // LDS buffers. Rows and columns past the block are read from existing ones (they end in
+  // outputs that are dropped, or meet zeros in x).
+  const unsigned char *wbase_a = (const unsigned char *)p.W_a + (size_t)g * bs * bs * 2;
+  const unsigned char *wbase_x = (const unsigned char *)p.W_x + (size_t)g * bs * bs * 2;
+  unsigned w_row[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = ob * BS + wv * 32 + i * 8 + (lane >> 3);
+    w_row[i] = (unsigned)(r < bs ? r : bs - 1) * (unsigned)(bs * 2);
+  }
+  unsigned char *wl = smem + W_OFF_W + wv * 2 * W_WPH;
+  const unsigned wl_wr = (unsigned)(lane >> 3) * W_WROW + (unsigned)(lane & 7) * 16;
+  const unsigned wl_rd = (unsigned)j * W_WROW + (unsigned)hf * 16;
+  u32x4 stg[2][8];
+  auto load_phase = [&](int P, u32x4 (&dst)[8]) __attribute__((always_inline)) {   // phase P: K-steps 4P .. 4P+3 of the block
+    const int c = P * 8 + (lane & 7);   // 16-byte chunk of the row
+    const unsigned w_col = (unsigned)(c < (bs >> 3) ? c : (bs >> 3) - 1) * 16;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      dst[i] = *(const u32x4 *)(wbase_a + w_row[i] + w_col);
+      dst[4 + i] = *(const u32x4 *)(wbase_x + w_row[i] + w_col);
+    }
+  };
+  auto write_phase = [&](const u32x4 (&src)[8]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      *(u32x4 *)(wl + i * 8 * W_WROW + wl_wr) = src[i];
+      *(u32x4 *)(wl + W_WPH + i * 8 * W_WROW + wl_wr) = src[4 + i];
+    }
+  };
 
   if (tid < 64) {   // selection operands, as in the fused kernel
     bf16x8 sel0, sel1;
@@ -106,35 +142,41 @@ gates_wide_kernel(WideArgs a) {
       accx[mi][r] = 0.f;
     }
 
+  load_phase(0, stg[0]);
+  load_phase(1, stg[1]);
   load_chunk(0);
   park_chunk(0);
+  write_phase(stg[0]);
   __syncthreads();
 
   for (int kc = 0; kc < a.nob; ++kc) {
     const int buf = kc & 1;
     load_chunk(kc + 1);   // lands during the products (nothing is read past the last chunk)
     const unsigned short *ap = xs + buf * W_XT + arow * XS + hf * 8;
-    // weight fragments of K-step ks: 8 consecutive inputs of this lane's output row; K-steps
-    // past the block re-read the last one (their x columns are zero)
-    auto frag_off = [&](int ks) __attribute__((always_inline)) {
-      const int k0 = kc * BS + ks * 16 + hf * 8;
-      return k0 < bs ? k0 : bs - 8;
-    };
-    bf16x8 fa = *(const bf16x8 *)(wa_row + frag_off(0)), fx = *(const bf16x8 *)(wx_row + frag_off(0));
 #pragma unroll
-    for (int ks = 0; ks < 16; ++ks) {
-      bf16x8 fa_n = fa, fx_n = fx;
-      if (ks + 1 < 16) {
-        fa_n = *(const bf16x8 *)(wa_row + frag_off(ks + 1));
-        fx_n = *(const bf16x8 *)(wx_row + frag_off(ks + 1));
+    for (int ph = 0; ph < 4; ++ph) {
+      const int P = kc * 4 + ph;
+      // two phases ahead, into the registers whose contents are in LDS already (phases past
+      // the block re-read its last columns)
+      load_phase(P + 2, stg[ph & 1]);
+      wave_lds_fence();   // the fragments come from other lanes of this wave
+      bf16x8 fa[4], fx[4];
+#pragma unroll
+      for (int k2 = 0; k2 < 4; ++k2) {
+        fa[k2] = *(const bf16x8 *)(wl + wl_rd + k2 * 32);
+        fx[k2] = *(const bf16x8 *)(wl + W_WPH + wl_rd + k2 * 32);
       }
-      const bf16x8 a0 = *(const bf16x8 *)(ap + ks * 16), a1 = *(const bf16x8 *)(ap + 32 * XS + ks * 16);
-      accp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, fa, accp[0], 0, 0, 0);
-      accq[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, fx, accq[0], 0, 0, 0);
-      accp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, fa, accp[1], 0, 0, 0);
-      accq[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, fx, accq[1], 0, 0, 0);
-      fa = fa_n;
-      fx = fx_n;
+      wave_lds_fence();
+      write_phase(stg[(ph + 1) & 1]);   // LDS serves a wave's accesses in order: queued behind the reads
+#pragma unroll
+      for (int k2 = 0; k2 < 4; ++k2) {
+        const int ks = ph * 4 + k2;
+        const bf16x8 a0 = *(const bf16x8 *)(ap + ks * 16), a1 = *(const bf16x8 *)(ap + 32 * XS + ks * 16);
+        accp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, fa[k2], accp[0], 0, 0, 0);
+        accq[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, fx[k2], accq[0], 0, 0, 0);
+        accp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, fa[k2], accp[1], 0, 0, 0);
+        accq[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, fx[k2], accq[1], 0, 0, 0);
+      }
     }
     if (kc == ob) {   // this chunk holds the wave's own channels: x_t into accumulator layout
 #pragma unroll
