@@ -146,7 +146,7 @@ size_t workspace_need(const rglru_shape *s, int op) {
       if (s->act_dtype == RGLRU_BF16 && forward_mfma_block(s->D / s->num_blocks) && s->T >= 1)
         return forward_mfma_ws_bytes(s->B, s->T, s->D, s->num_blocks);
       if (s->act_dtype == RGLRU_BF16 && forward_wide_block(s->D / s->num_blocks) && s->T >= 1 &&
-          (size_t)s->B * s->T * s->D * 2 < ((size_t)1 << 31))
+          s->D % 256 == 0 && (size_t)s->B * s->T * s->D * 2 < ((size_t)1 << 31))
         return forward_wide_ws_bytes(s->B, s->T, s->D, s->num_blocks);
       return 0;
     default:
@@ -295,10 +295,11 @@ int rglru_workspace_status(const rglru_shape *shape, int op, const void *workspa
   size_t off = 0;   // forward and scan keep the flag in the first word
   if ((op == RGLRU_OP_FORWARD || op == RGLRU_OP_FORWARD_MERGE) &&
       !forward_mfma_block(shape->D / shape->num_blocks)) {
-    // the passes of the other block sizes: only the scan waits, its workspace follows three
+    // the passes of the other block sizes: only the scan waits, its workspace follows the
     // activation-sized buffers
-    if (shape->D % 256 != 0 || scan_tiled_ws_bytes(shape->B, shape->T, shape->D) == 0) return RGLRU_OK;
-    off = need - scan_tiled_ws_bytes(shape->B, shape->T, shape->D);
+    const size_t sw = scan_tiled_ws_bytes(shape->B, shape->T, shape->D);
+    if (sw == 0) return RGLRU_OK;
+    off = need - sw;
   }
   if (bwd) {
     if (shape->act_dtype == RGLRU_BF16 && shape->D / shape->num_blocks == 256 &&

@@ -60,6 +60,10 @@ struct Problem {
   void *out;
 };
 
+// internal scan flag (never accepted from the C ABI): g is stored in IEEE half precision; goes
+// with RGLRU_SCAN_LOG_A | RGLRU_SCAN_NO_INPUT_SCALE and the tiled kernel only
+constexpr unsigned SCAN_G_FP16 = 0x100u;
+
 // One rglru_scan call.
 struct ScanProblem {
   int B, T, D;

@@ -107,7 +107,9 @@ __device__ __forceinline__ void scan_terms(float av, float gv, float &a, float &
   }
 }
 
-template <int GMAX, bool LOGA, bool SCALE>
+// GF16: g_t is stored in IEEE half precision (the library's own intermediate of the forward in
+// separate passes); its columns are moved with the f16 form of the same selection product.
+template <int GMAX, bool LOGA, bool SCALE, bool GF16>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 scan_tiled_kernel(ScanArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -137,6 +139,13 @@ scan_tiled_kernel(ScanArgs a) {
     }
     sel_lds[lane] = sel0;
     sel_lds[64 + lane] = sel1;
+  }
+  typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+  f16x8 sh0, sh1;   // the same selection operands in half precision
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    sh0[e] = (_Float16)((hf * 8 + e == j) ? 1.0f : 0.0f);
+    sh1[e] = (_Float16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
   }
 
   const unsigned seq_bytes = (unsigned)((size_t)T * D * 2), row_bytes = (unsigned)D * 2;
@@ -251,9 +260,11 @@ scan_tiled_kernel(ScanArgs a) {
       const unsigned short *ta = (const unsigned short *)(smem + PAR * SC_BUF) + a_off;
       const bf16x8 s0 = sel_lds[lane], s1 = sel_lds[64 + lane];
       acca = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ta), s0, acca, 0, 0, 0);
-      accg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ta + SC_TILE / 2), s0, accg, 0, 0, 0);
+      if (GF16) accg = __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const f16x8 *)(ta + SC_TILE / 2), sh0, accg, 0, 0, 0);
+      else accg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ta + SC_TILE / 2), s0, accg, 0, 0, 0);
       acca = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ta + 16), s1, acca, 0, 0, 0);
-      accg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ta + SC_TILE / 2 + 16), s1, accg, 0, 0, 0);
+      if (GF16) accg = __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const f16x8 *)(ta + SC_TILE / 2 + 16), sh1, accg, 0, 0, 0);
+      else accg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ta + SC_TILE / 2 + 16), s1, accg, 0, 0, 0);
     }
     // local scan of this lane's 16-step run: prun = prod a, hrun = end state from zero
     float hrun = 0.f, prun = 1.f;
@@ -317,23 +328,24 @@ scan_tiled_kernel(ScanArgs a) {
   if ((a.ntile - 1) % G == w && p.hT && hf == 0) p.hT[(size_t)b * D + d] = carry;
 }
 
-template <int GMAX, bool LOGA, bool SCALE>
+template <int GMAX, bool LOGA, bool SCALE, bool GF16 = false>
 hipError_t launch_scan_t(const ScanArgs &a, int grid, hipStream_t s) {
   static bool configured = false;  // the kernel asks for more than the default LDS limit
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void *)scan_tiled_kernel<GMAX, LOGA, SCALE>,
+    hipError_t e = hipFuncSetAttribute((const void *)scan_tiled_kernel<GMAX, LOGA, SCALE, GF16>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, SC_LDS);
     if (e != hipSuccess) return e;
     configured = true;
   }
   KernelTimer kt("scan_tiled_kernel", s);
-  hipLaunchKernelGGL((scan_tiled_kernel<GMAX, LOGA, SCALE>), dim3(grid), dim3(NTHR), SC_LDS, s, a);
+  hipLaunchKernelGGL((scan_tiled_kernel<GMAX, LOGA, SCALE, GF16>), dim3(grid), dim3(NTHR), SC_LDS, s, a);
   return hipGetLastError();
 }
 
 template <int GMAX>
 hipError_t launch_scan_flags(const ScanArgs &a, int grid, hipStream_t s) {
   const bool loga = a.p.flags & RGLRU_SCAN_LOG_A, scale = !(a.p.flags & RGLRU_SCAN_NO_INPUT_SCALE);
+  if (a.p.flags & SCAN_G_FP16) return launch_scan_t<GMAX, true, false, true>(a, grid, s);   // internal use: this form only
   if (loga) return scale ? launch_scan_t<GMAX, true, true>(a, grid, s) : launch_scan_t<GMAX, true, false>(a, grid, s);
   return scale ? launch_scan_t<GMAX, false, true>(a, grid, s) : launch_scan_t<GMAX, false, false>(a, grid, s);
 }

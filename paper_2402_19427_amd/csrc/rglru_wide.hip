@@ -1,12 +1,13 @@
 // Forward for the gate block sizes the fused kernel does not take (bf16 storage, any multiple of
 // 16 channels: Section 4.1's 16 blocks give 352 and 512 channels at widths 5632 and 8192), as
 // three passes over kernels that exist plus one that is new here:
-//   1. Conv1D (Section 2.3) into x, bf16, in the workspace        conv1d_kernel
+//   1. Conv1D (Section 2.3) into x in the workspace, as bf16 (operand of the gate products) and
+//      in half precision (the x_t of i_t x_t: bf16 is too coarse there)   conv_rows_kernel
 //   2. gates_wide_kernel: the gate products of eqs. (1)-(2) on the matrix cores over the whole
 //      K = bs of a block in chunks of 256 input channels, then eqs. (1)-(3) per element; it
-//      writes log a_t and b_t = sqrt(1 - a_t^2) i_t x_t (bf16) to the workspace
+//      writes log a_t (bf16) and b_t = sqrt(1 - a_t^2) i_t x_t (half precision) to the workspace
 //   3. eq. (4) as a linear scan over (log a_t, b_t)                the scan-only kernels
-// and the Conv1D ring update. About 16 bytes per element through memory instead of the fused
+// and the Conv1D ring update. About 20 bytes per element through memory instead of the fused
 // kernel's 4, and the gate weights come from L2 for every 64 rows; the generic kernels these
 // shapes ran on before are ~30 times slower.
 #include "rglru_mfma.h"
@@ -34,8 +35,9 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 struct WideArgs {
   Problem p;
-  const unsigned short *x;     // [M][D] Conv1D output
-  unsigned short *la, *gb;     // [M][D] log a_t, b_t
+  const unsigned short *x;     // [M][D] Conv1D output, bf16: operand of the gate products
+  const unsigned short *xh;    // [M][D] the same in half precision: the x_t of i_t x_t
+  unsigned short *la, *gb;     // [M][D] log a_t (bf16), b_t (half precision)
   int nob;                     // groups of 256 output channels per block = K chunks per block
   unsigned M;                  // B * T
 };
@@ -44,7 +46,6 @@ __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)
 gates_wide_kernel(WideArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned short *xs = (unsigned short *)smem;                     // [2][WM][XS]
-  bf16x8 *sel_lds = (bf16x8 *)(smem + W_OFF_SEL);
   const Problem &p = a.p;
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, j = lane & 31;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -99,17 +100,6 @@ gates_wide_kernel(WideArgs a) {
       *(u32x4 *)(wl + W_WPH + i * 8 * W_WROW + wl_wr) = src[4 + i];
     }
   };
-
-  if (tid < 64) {   // selection operands, as in the fused kernel
-    bf16x8 sel0, sel1;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      sel0[e] = (__bf16)((hf * 8 + e == j) ? 1.0f : 0.0f);
-      sel1[e] = (__bf16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
-    }
-    sel_lds[lane] = sel0;
-    sel_lds[64 + lane] = sel1;
-  }
 
   // ---- x tile loader: thread -> 16 bytes (8 channels) of rows r0, r0 + 16, r0 + 32, r0 + 48
   const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -178,16 +168,40 @@ gates_wide_kernel(WideArgs a) {
         accq[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, fx[k2], accq[1], 0, 0, 0);
       }
     }
-    if (kc == ob) {   // this chunk holds the wave's own channels: x_t into accumulator layout
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi) {
-        const unsigned short *sp = ap + mi * 32 * XS;
-        accx[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(sp + (2 * wv) * 16), sel_lds[lane], accx[mi], 0, 0, 0);
-        accx[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(sp + (2 * wv + 1) * 16), sel_lds[64 + lane], accx[mi], 0, 0, 0);
-      }
-    }
     park_chunk(buf ^ 1);
     __syncthreads();
+  }
+
+  // ---- x_t of this workgroup's own channels, in half precision (bf16 is too coarse for the
+  // i_t x_t term), through the x tile buffer into accumulator layout with the f16 form of the
+  // selection product
+  {
+    const __amdgpu_buffer_rsrc_t xh_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        uniform_ptr(a.xh), 0, a.M * row_bytes, 0x00020000);
+    const int col = ob * BS + lc * 8;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const unsigned m = m0 + r0 + 16 * i;
+      const bool ok = m < a.M && col < bs;
+      nx[i] = __builtin_amdgcn_raw_buffer_load_b128(
+          xh_rsrc, ok ? m * row_bytes + (unsigned)(g * bs + col) * 2 : OOB, 0, 0);
+    }
+    park_chunk(0);
+    __syncthreads();
+    typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+    f16x8 sh0, sh1;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      sh0[e] = (_Float16)((hf * 8 + e == j) ? 1.0f : 0.0f);
+      sh1[e] = (_Float16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
+    }
+    const unsigned short *ap = xs + arow * XS + hf * 8;
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi) {
+      const unsigned short *sp = ap + mi * 32 * XS;
+      accx[mi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const f16x8 *)(sp + (2 * wv) * 16), sh0, accx[mi], 0, 0, 0);
+      accx[mi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const f16x8 *)(sp + (2 * wv + 1) * 16), sh1, accx[mi], 0, 0, 0);
+    }
   }
 
   // ---- eqs. (1)-(3) per element; the two results leave through the wave's staging tile as
@@ -217,7 +231,10 @@ gates_wide_kernel(WideArgs a) {
     }
     store_staged_tile_s<OT, 0>(otile, lane, la_rsrc, o_voff, mrow * row_bytes, row_bytes, nrows);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) ot_mine[r * OT] = (unsigned short)(pack_bf16(bv[r], 0.f) & 0xffff);
+    for (int r = 0; r < 16; ++r) {
+      const _Float16 hv = (_Float16)bv[r];
+      ot_mine[r * OT] = *(const unsigned short *)&hv;
+    }
     store_staged_tile_s<OT, 0>(otile, lane, gb_rsrc, o_voff, mrow * row_bytes, row_bytes, nrows);
   }
 }
@@ -230,7 +247,8 @@ inline size_t al256(size_t n) { return (n + 255) & ~(size_t)255; }
 constexpr int CR = 8;
 struct ConvArgs {
   Problem p;
-  unsigned short *x;
+  unsigned short *x;    // bf16
+  unsigned short *xh;   // half precision
 };
 __global__ void __launch_bounds__(256) conv_rows_kernel(ConvArgs a) {
   const Problem &p = a.p;
@@ -266,7 +284,8 @@ __global__ void __launch_bounds__(256) conv_rows_kernel(ConvArgs a) {
 #pragma unroll
   for (int r = 0; r < CR; ++r) {
     if (t0 + r >= T) break;
-    u32x4 o;
+    u32x4 o, oh;
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
     for (int e2 = 0; e2 < 4; ++e2) {
       float x0 = bias[2 * e2], x1 = bias[2 * e2 + 1];
@@ -277,8 +296,11 @@ __global__ void __launch_bounds__(256) conv_rows_kernel(ConvArgs a) {
         x1 = fmaf(w[k][2 * e2 + 1], bf_hi(v), x1);
       }
       o[e2] = pack_bf16(x0, x1);
+      const f16x2 h2 = {(_Float16)x0, (_Float16)x1};
+      oh[e2] = *(const unsigned *)&h2;
     }
     *(u32x4 *)(a.x + ((size_t)b * T + t0 + r) * D + d0) = o;
+    *(u32x4 *)(a.xh + ((size_t)b * T + t0 + r) * D + d0) = oh;
   }
 }
 
@@ -286,41 +308,39 @@ __global__ void __launch_bounds__(256) conv_rows_kernel(ConvArgs a) {
 
 bool forward_wide_block(int bs) { return bs % 16 == 0 && bs >= 16 && !forward_mfma_block(bs); }
 
+// (the scan pass needs a width that is a multiple of 256; 16-byte accesses throughout)
 bool forward_wide_supported(const Problem &p, bool bf) {
-  const uintptr_t all = (uintptr_t)p.W_a | (uintptr_t)p.W_x | (uintptr_t)p.y;
-  return bf && forward_wide_block(p.bs) && p.T >= 1 && all % 16 == 0 &&
+  const uintptr_t all = (uintptr_t)p.W_a | (uintptr_t)p.W_x | (uintptr_t)p.y | (uintptr_t)p.u |
+                        (uintptr_t)p.state_in | (uintptr_t)p.conv_w | (uintptr_t)p.conv_b;
+  return bf && forward_wide_block(p.bs) && p.D % BS == 0 && p.T >= 1 && all % 16 == 0 &&
          (size_t)p.B * p.T * p.D * 2 < ((size_t)1 << 31);
 }
 
 size_t forward_wide_ws_bytes(int B, int T, int D, int nb) {
   const size_t n = al256((size_t)B * T * D * 2);
-  return 3 * n + (D % BS == 0 ? scan_tiled_ws_bytes(B, T, D) : 0);
+  return 4 * n + scan_tiled_ws_bytes(B, T, D);
 }
 
 hipError_t launch_forward_wide(const Problem &p, hipStream_t s) {
   const size_t n = al256((size_t)p.B * p.T * p.D * 2);
   char *ws = (char *)p.ws;
-  void *x = ws, *la = ws + n, *gb = ws + 2 * n;
+  void *x = ws, *la = ws + n, *gb = ws + 2 * n, *xh = ws + 3 * n;
   hipError_t e;
   {
     KernelTimer kt("conv_rows_kernel", s);
-    const bool wide16 = p.D % 8 == 0 && ((uintptr_t)p.u % 16 == 0) && (!p.state_in || (uintptr_t)p.state_in % 16 == 0) &&
-                        ((uintptr_t)p.conv_w % 16 == 0);
-    if (wide16) {
-      ConvArgs c;
-      c.p = p;
-      c.x = (unsigned short *)x;
-      const size_t total = (size_t)p.B * ((p.T + CR - 1) / CR) * (p.D / 8);
-      hipLaunchKernelGGL(conv_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, c);
-      e = hipGetLastError();
-    } else {
-      e = launch_conv1d_generic(p, true, x, s);
-    }
+    ConvArgs c;
+    c.p = p;
+    c.x = (unsigned short *)x;
+    c.xh = (unsigned short *)xh;
+    const size_t total = (size_t)p.B * ((p.T + CR - 1) / CR) * (p.D / 8);
+    hipLaunchKernelGGL(conv_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, c);
+    e = hipGetLastError();
   }
   if (e != hipSuccess) return e;
   WideArgs a;
   a.p = p;
   a.x = (const unsigned short *)x;
+  a.xh = (const unsigned short *)xh;
   a.la = (unsigned short *)la;
   a.gb = (unsigned short *)gb;
   a.nob = (p.bs + BS - 1) / BS;
@@ -339,11 +359,12 @@ hipError_t launch_forward_wide(const Problem &p, hipStream_t s) {
   if (e != hipSuccess) return e;
   ScanProblem q;
   q.B = p.B; q.T = p.T; q.D = p.D;
-  q.flags = RGLRU_SCAN_LOG_A | RGLRU_SCAN_NO_INPUT_SCALE;   // b_t already carries sqrt(1 - a_t^2)
+  q.flags = RGLRU_SCAN_LOG_A | RGLRU_SCAN_NO_INPUT_SCALE | SCAN_G_FP16;   // b_t carries sqrt(1 - a_t^2)
   q.a = la; q.g = gb; q.h0 = p.h0; q.h = p.y; q.hT = p.hT;
-  q.ws = ws + 3 * n;
-  q.ws_bytes = p.ws_bytes > 3 * n ? p.ws_bytes - 3 * n : 0;
-  e = scan_tiled_supported(q, true) ? launch_scan_tiled(q, s) : launch_scan_generic(q, true, s);
+  q.ws = ws + 4 * n;
+  q.ws_bytes = p.ws_bytes > 4 * n ? p.ws_bytes - 4 * n : 0;
+  if (!scan_tiled_supported(q, true)) return hipErrorInvalidValue;
+  e = launch_scan_tiled(q, s);
   if (e != hipSuccess) return e;
   return launch_state_update(p, true, s);
 }

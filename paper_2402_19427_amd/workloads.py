@@ -86,7 +86,7 @@ def row(name, phase, note, ms, tokens, nbytes, flops):
             "mfma_frac": flops / (med * 1e-3) / MFMA_PEAK}
 
 
-def run_sequence_workload(w, dev, out):
+def run_sequence_workload(w, dev, out, label="forward"):
     B, T, D, nb = w.B, w.T, w.D, w.nb
     act_b = 2 if w.act == "bf16" else 4
     inp = gen.make_inputs(1, 8, D, nb, act=w.act, seed=w.seed)       # parameters only
@@ -110,7 +110,7 @@ def run_sequence_workload(w, dev, out):
 
     note = "%d buffer set%s" % (nsets, "s" if nsets > 1 else "")
     ms = time_calls(fwd, nsets, iters, 10)
-    out.append(row(w.name, "forward", note, ms, B * T, alg_bytes("forward", B, T, D, nb, act_b),
+    out.append(row(w.name, label, note, ms, B * T, alg_bytes("forward", B, T, D, nb, act_b),
                    gate_flops("forward", B, T, D, nb)))
     if w.kind != "train" and w.name != "C1":
         return
@@ -352,6 +352,11 @@ def main():
             run_sequence_workload(dataclasses.replace(c1, name="NB16", nb=16, kind="train"), dev, out)
             run_decode_workload(dataclasses.replace(gen.CONFIGS["C3"], name="NB16", D=2560), dev, out,
                                 graph_only=True)
+            # the larger widths of the model family, 352 and 512 channels per block: forward only
+            # (separate passes on the matrix cores)
+            for D in (5632, 8192):
+                run_sequence_workload(dataclasses.replace(c1, name="NB16", D=D, nb=16, kind="forward"),
+                                      dev, out, label="forward, width %d" % D)
         elif w.kind == "decode":
             run_decode_workload(w, dev, out)
         else:

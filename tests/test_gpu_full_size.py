@@ -243,3 +243,29 @@ def test_the_paper_s_sixteen_blocks_at_width_2560_full_size():
     assert gen.rel_err(dW_h[g], dW) < TOL
     assert gen.rel_err(dL_h[sl], dL) < TOL
     assert np.isfinite(y_h).all() and np.isfinite(du_h).all() and np.isfinite(dW_h).all()
+
+
+@pytest.mark.parametrize("D", [5632, 8192])
+def test_sixteen_blocks_at_the_larger_widths_forward_full_size(D):
+    # 16 gate blocks at widths 5632 and 8192 (352 and 512 channels per block): the forward as
+    # separate passes on the matrix cores, C1's batch and length, two sampled (sequence, block) pairs
+    import dataclasses
+    import paper_2402_19427_amd as R
+    import paper_2402_19427_amd.runner as rn
+    w = dataclasses.replace(gen.CONFIGS["C1"], D=D, nb=16)
+    inp = gen.make_inputs(w.B, w.T, w.D, w.nb, act=w.act, seed=w.seed + D, h0=True)
+    dp = rn.DeviceProblem(inp, w.B, w.T, w.D, w.nb, w.act)
+    y, hT, st = dp.forward(rn.to_device(inp["u"], w.act), h0=rn.to_device(inp["h0"], "f32"))
+    sh = dp.shape()
+    ws, _ = dp.workspace(sh, R.OP_FORWARD)
+    R.rglru_workspace_status(sh, R.OP_FORWARD, ws)
+    y_h, hT_h = rn.to_host(y), rn.to_host(hT)
+    del y
+    oracle.set_threads(8)
+    for b, g in [(0, 0), (6, 15)]:
+        sl, par = block_params(inp, g, w.bs)
+        y_ref, hT_ref, _ = oracle.forward(np.asarray(inp["u"][b:b + 1, :, sl], np.float64), *par,
+                                          h0=np.asarray(inp["h0"][b:b + 1, sl], np.float64))
+        assert gen.rel_err(y_h[b:b + 1, :, sl], y_ref) < TOL, (D, b, g)
+        assert gen.rel_err(hT_h[b:b + 1, sl], hT_ref) < TOL, (D, b, g)
+    assert np.isfinite(y_h).all()

@@ -392,6 +392,7 @@ MERGE_SHAPES = [
     (8, 600, 2048, 8, "bf16"),   # MFMA path, time slices
     (1, 1500, 256, 1, "bf16"),   # MFMA path, 16 time slices: the merge runs as a kernel of its own
     (3, 300, 2560, 16, "bf16"),  # bs = 160 in the padded tile, merge as epilogue
+    (2, 100, 2816, 8, "bf16"),   # bs = 352: separate passes, then the merge kernel
 ]
 
 
