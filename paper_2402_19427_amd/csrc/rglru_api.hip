@@ -421,8 +421,9 @@ int rglru_decode_step(const rglru_shape *shape, const rglru_params *params, cons
   q.T = 1; q.pos0 = pos; q.u = u_t; q.hT = h; q.state_in = conv_state;
   q.state_out = conv_state; q.y = y_t;
   const bool bf = shape->act_dtype == RGLRU_BF16;
-  hipError_t e = decode_mfma_supported(q, bf) ? launch_decode_mfma(q, (hipStream_t)stream)
-                                             : launch_decode_generic(q, bf, (hipStream_t)stream);
+  hipError_t e = decode_mfma_supported(q, bf)   ? launch_decode_mfma(q, (hipStream_t)stream)
+                 : decode_wide_supported(q, bf) ? launch_decode_wide(q, (hipStream_t)stream)
+                                                : launch_decode_generic(q, bf, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "decode launch");
   g_err[0] = 0;
   return RGLRU_OK;
@@ -545,6 +546,9 @@ int rglru_decode_step_merge(const rglru_shape *shape, const rglru_params *params
   hipError_t e;
   if (decode_mfma_supported(q, bf)) {
     e = launch_decode_mfma(q, s);
+    if (e != hipSuccess) return hip_fail(e, "decode launch");
+  } else if (decode_wide_supported(q, bf)) {
+    e = launch_decode_wide(q, s);
     if (e != hipSuccess) return hip_fail(e, "decode launch");
   } else {
     q.merge = 0;

@@ -107,6 +107,8 @@ bool forward_wide_block(int bs);
 bool forward_wide_supported(const Problem &p, bool bf);
 size_t forward_wide_ws_bytes(int B, int T, int D, int nb);
 hipError_t launch_forward_wide(const Problem &p, hipStream_t s);
+bool decode_wide_supported(const Problem &p, bool bf);
+hipError_t launch_decode_wide(const Problem &p, hipStream_t s);
 
 // MFMA decode step (bf16 storage, gate blocks of 256)
 bool decode_mfma_supported(const Problem &p, bool bf);

@@ -10,6 +10,7 @@
 // and the Conv1D ring update. About 20 bytes per element through memory instead of the fused
 // kernel's 4, and the gate weights come from L2 for every 64 rows; the generic kernels these
 // shapes ran on before are ~30 times slower.
+#include "rglru_gelu.h"
 #include "rglru_mfma.h"
 
 #include <math.h>
@@ -239,6 +240,288 @@ gates_wide_kernel(WideArgs a) {
   }
 }
 
+// ------------------------------------------------------------------------------ decode
+// One decode step (Section 5; states of Appendix F) for the same block sizes: a workgroup takes
+// 32 sequences and 256 output channels of one gate block and walks the block's input channels
+// in chunks of 256: Conv1D over the ring for the chunk into an LDS tile (high + low bf16 part,
+// scaled by log2 e), then its 16 K-steps with the weights read as whole lines and turned into
+// fragment order through wave-private LDS. The Conv1D inputs and taps of the next chunk are
+// requested as soon as those of the current one are used up, so they land during the products.
+// Every workgroup of a block reads the whole ring of the block, so the new token cannot replace
+// the oldest slot in place here: a second kernel writes it once this one has finished.
+constexpr int DW_OFF_W = 2 * XT_ELEMS * 2;                 // x tile (high, low) first
+constexpr int DW_OFF_H = DW_OFF_W + NWAVE * 2 * W_WPH;     // per wave: h / y staging, 32 rows
+constexpr int DW_MAXCH = 3;                                // chunks of input channels: blocks up to 768
+constexpr int DW_OFF_CW = DW_OFF_H + NWAVE * W_WPH;        // Conv1D taps and bias: [chunk][5][256] f32
+constexpr int DW_LDS = DW_OFF_CW + DW_MAXCH * 5 * BS * 4;
+constexpr int DW_YROW = 64 + 16;
+
+struct DecWideArgs {
+  Problem p;   // u = u_t [B][D], hT = h [B][D] (in place), state_out = ring (read), y = y_t / out_t
+  int nob;
+};
+
+template <int MERGE>
+__global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
+decode_wide_kernel(DecWideArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned short *xs = (unsigned short *)smem;   // [high, low][32][XS]
+  const Problem &p = a.p;
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, j = lane & 31;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = blockIdx.x / a.nob, ob = blockIdx.x - g * a.nob, b0 = blockIdx.y * TT;
+  const int D = p.D, B = p.B, bs = p.bs;
+  const unsigned row2 = (unsigned)D * 2;
+
+  const int och = ob * BS + wv * 32 + j;
+  const int d = g * bs + (och < bs ? och : bs - 1);
+  const float bias_p = p.b_a[d] * LOG2E, bias_q = p.b_x[d] * LOG2E, lam = p.Lambda[d];
+
+  const __amdgpu_buffer_rsrc_t u_rsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(p.u), 0, (unsigned)B * row2, 0x00020000);
+  const __amdgpu_buffer_rsrc_t ring_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(p.state_out), 0, 3u * (unsigned)B * row2, 0x00020000);
+  const __amdgpu_buffer_rsrc_t h_rsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(p.hT), 0, 2u * (unsigned)B * row2, 0x00020000);
+  const __amdgpu_buffer_rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(p.y), 0, (unsigned)B * row2, 0x00020000);
+
+  // ---- Conv1D inputs and taps of chunk kc: 8 channels (16 bytes) of rows lr and lr + 16
+  const int lc = tid & 31, lr = tid >> 5;
+  const int s1 = ring_slot(p.pos0 - 1), s2 = ring_slot(p.pos0 - 2), s3 = ring_slot(p.pos0 - 3);
+  u32x4 ru[2][4];
+  // taps and bias of every chunk parked in LDS once (missing channels: zero bias, any taps -
+  // their inputs read as zero), so that only the inputs are in flight during the products
+  float *cw_lds = (float *)(smem + DW_OFF_CW);
+  if (lr < a.nob) {
+    const int col = lr * BS + lc * 8;
+    const bool cok = col < bs;
+    const int dcc = g * bs + (cok ? col : 0);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      *(f32x4 *)(cw_lds + (lr * 5 + k) * BS + lc * 8) = *(const f32x4 *)(p.conv_w + (size_t)k * D + dcc);
+      *(f32x4 *)(cw_lds + (lr * 5 + k) * BS + lc * 8 + 4) = *(const f32x4 *)(p.conv_w + (size_t)k * D + dcc + 4);
+    }
+    const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+    const bool bon = p.conv_b && cok;
+    *(f32x4 *)(cw_lds + (lr * 5 + 4) * BS + lc * 8) = bon ? *(const f32x4 *)(p.conv_b + dcc) : z;
+    *(f32x4 *)(cw_lds + (lr * 5 + 4) * BS + lc * 8 + 4) = bon ? *(const f32x4 *)(p.conv_b + dcc + 4) : z;
+  }
+  auto load_conv = [&](int kc) __attribute__((always_inline)) {
+    const int col = kc * BS + lc * 8;
+    const bool cok = col < bs;                       // (also false for every chunk past the block)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int b = b0 + lr + 16 * i;
+      const bool ok = b < B && cok;
+      const unsigned uvo = ok ? (unsigned)b * row2 + (unsigned)(g * bs + col) * 2 : OOB;
+      const unsigned rvo = ok ? (unsigned)(b * 3) * row2 + (unsigned)(g * bs + col) * 2 : OOB;
+      ru[i][0] = __builtin_amdgcn_raw_buffer_load_b128(u_rsrc, uvo, 0, 0);
+      ru[i][1] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, rvo, (unsigned)s1 * row2, 0);
+      ru[i][2] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, rvo, (unsigned)s2 * row2, 0);
+      ru[i][3] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, rvo, (unsigned)s3 * row2, 0);
+    }
+  };
+  auto conv_chunk = [&](int kc) __attribute__((always_inline)) {   // x tile of the chunk whose inputs are in ru
+    f32x4 cw[4][2], cb[2];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      cw[k][0] = *(const f32x4 *)(cw_lds + (kc * 5 + k) * BS + lc * 8);
+      cw[k][1] = *(const f32x4 *)(cw_lds + (kc * 5 + k) * BS + lc * 8 + 4);
+    }
+    cb[0] = *(const f32x4 *)(cw_lds + (kc * 5 + 4) * BS + lc * 8);
+    cb[1] = *(const f32x4 *)(cw_lds + (kc * 5 + 4) * BS + lc * 8 + 4);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      u32x4 hi4, lo4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {   // channels 2e, 2e+1 of the 8
+        const int v = e >> 1, c0 = (2 * e) & 3;
+        const unsigned u0 = ru[i][0][e], u1 = ru[i][1][e], u2 = ru[i][2][e], u3 = ru[i][3][e];
+        float x0 = cb[v][c0], x1 = cb[v][c0 + 1];
+        x0 = fmaf(cw[0][v][c0], bf_lo(u0), x0); x1 = fmaf(cw[0][v][c0 + 1], bf_hi(u0), x1);
+        x0 = fmaf(cw[1][v][c0], bf_lo(u1), x0); x1 = fmaf(cw[1][v][c0 + 1], bf_hi(u1), x1);
+        x0 = fmaf(cw[2][v][c0], bf_lo(u2), x0); x1 = fmaf(cw[2][v][c0 + 1], bf_hi(u2), x1);
+        x0 = fmaf(cw[3][v][c0], bf_lo(u3), x0); x1 = fmaf(cw[3][v][c0 + 1], bf_hi(u3), x1);
+        unsigned hi_pk, lo_pk;
+        split_bf16(x0 * LOG2E, x1 * LOG2E, hi_pk, lo_pk);   // missing rows and channels: all inputs read as zero
+        hi4[e] = hi_pk;
+        lo4[e] = lo_pk;
+      }
+      *(u32x4 *)(xs + (lr + 16 * i) * XS + 8 * lc) = hi4;
+      *(u32x4 *)(xs + XT_ELEMS + (lr + 16 * i) * XS + 8 * lc) = lo4;
+    }
+  };
+  load_conv(0);
+
+  // ---- gate weights, as in gates_wide_kernel
+  const unsigned char *wbase_a = (const unsigned char *)p.W_a + (size_t)g * bs * bs * 2;
+  const unsigned char *wbase_x = (const unsigned char *)p.W_x + (size_t)g * bs * bs * 2;
+  unsigned w_row[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = ob * BS + wv * 32 + i * 8 + (lane >> 3);
+    w_row[i] = (unsigned)(r < bs ? r : bs - 1) * (unsigned)(bs * 2);
+  }
+  unsigned char *wl = smem + DW_OFF_W + wv * 2 * W_WPH;
+  const unsigned wl_wr = (unsigned)(lane >> 3) * W_WROW + (unsigned)(lane & 7) * 16;
+  const unsigned wl_rd = (unsigned)j * W_WROW + (unsigned)hf * 16;
+  u32x4 stg[2][8];
+  auto load_phase = [&](int P, u32x4 (&dst)[8]) __attribute__((always_inline)) {
+    const int c = P * 8 + (lane & 7);
+    const unsigned w_col = (unsigned)(c < (bs >> 3) ? c : (bs >> 3) - 1) * 16;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      dst[i] = *(const u32x4 *)(wbase_a + w_row[i] + w_col);
+      dst[4 + i] = *(const u32x4 *)(wbase_x + w_row[i] + w_col);
+    }
+  };
+  auto write_phase = [&](const u32x4 (&src)[8]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      *(u32x4 *)(wl + i * 8 * W_WROW + wl_wr) = src[i];
+      *(u32x4 *)(wl + W_WPH + i * 8 * W_WROW + wl_wr) = src[4 + i];
+    }
+  };
+  load_phase(0, stg[0]);
+
+  // ---- recurrent state of this wave's 32 x 32 tile, and where its outputs go
+  unsigned char *hl = smem + DW_OFF_H + wv * W_WPH;
+  const unsigned hl_wide = (unsigned)(lane >> 3) * W_WROW + (unsigned)(lane & 7) * 16;
+  unsigned h_vo[4];
+  u32x4 hin[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int b = b0 + (lane >> 3) + 8 * i;
+    const int c = ob * BS + wv * 32 + (lane & 7) * 4;
+    h_vo[i] = (b < B && c < bs) ? ((unsigned)b * (unsigned)D + (unsigned)(g * bs + c)) * 4 : OOB;
+    hin[i] = __builtin_amdgcn_raw_buffer_load_b128(h_rsrc, h_vo[i], 0, 0);
+  }
+  unsigned y_vo[2];
+  u32x4 brq[2];
+  const __amdgpu_buffer_rsrc_t br_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(MERGE ? p.branch : p.u), 0, (unsigned)B * row2, 0x00020000);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int b = b0 + (lane >> 2) + 16 * i;
+    const int c = ob * BS + wv * 32 + (lane & 3) * 8;
+    y_vo[i] = (b < B && c < bs) ? ((unsigned)b * (unsigned)D + (unsigned)(g * bs + c)) * 2 : OOB;
+    if (MERGE) brq[i] = __builtin_amdgcn_raw_buffer_load_b128(br_rsrc, y_vo[i], 0, 0);
+  }
+  load_phase(1, stg[1]);
+
+  typedef bf16x8 frag_t;
+  bf16x8 sel0, sel1;   // selection operands, in registers (nothing else is resident here)
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    sel0[e] = (__bf16)((hf * 8 + e == j) ? 1.0f : 0.0f);
+    sel1[e] = (__bf16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
+  }
+  float kd;
+  {
+    const float z = -lam;
+    const float sp = z > 0.f ? z + log1pf(expf(-z)) : log1pf(expf(z));
+    kd = -p.c * sp * LOG2E;
+  }
+
+  const int arow = ((j >> 2) & 1) * 16 + (j >> 3) * 4 + (j & 3);
+  const unsigned short *ap = xs + arow * XS + hf * 8;
+  f32x16 accp, accq, accx;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    accp[r] = bias_p;
+    accq[r] = bias_q;
+    accx[r] = 0.f;
+  }
+  write_phase(stg[0]);
+  float gl[2][8];
+  __syncthreads();   // the taps parked in LDS are visible
+  for (int kc = 0; kc < a.nob; ++kc) {
+    conv_chunk(kc);
+    load_conv(kc + 1);   // inputs and taps of the next chunk (nothing is read past the block)
+    if (MERGE && kc == 0) {   // GeLU of the other branch while the weights are on their way
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          gl[i][2 * k] = gelu<MERGE == 2, true>(bf_lo(brq[i][k]));
+          gl[i][2 * k + 1] = gelu<MERGE == 2, true>(bf_hi(brq[i][k]));
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ph = 0; ph < 4; ++ph) {
+      const int P = kc * 4 + ph;
+      load_phase(P + 2, stg[ph & 1]);
+      wave_lds_fence();
+      frag_t av[4], fa[4], fx[4];
+#pragma unroll
+      for (int k2 = 0; k2 < 4; ++k2) {
+        av[k2] = *(const bf16x8 *)(ap + (ph * 4 + k2) * 16);
+        fa[k2] = *(const bf16x8 *)(wl + wl_rd + k2 * 32);
+        fx[k2] = *(const bf16x8 *)(wl + W_WPH + wl_rd + k2 * 32);
+      }
+      wave_lds_fence();
+      write_phase(stg[(ph + 1) & 1]);
+#pragma unroll
+      for (int k2 = 0; k2 < 4; ++k2) {
+        accp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[k2], fa[k2], accp, 0, 0, 0);
+        accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[k2], fx[k2], accq, 0, 0, 0);
+      }
+    }
+    if (kc == ob) {   // the chunk with this workgroup's own channels: x_t (high + low part)
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ap + (2 * wv) * 16), sel0, accx, 0, 0, 0);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ap + (2 * wv + 1) * 16), sel1, accx, 0, 0, 0);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ap + XT_ELEMS + (2 * wv) * 16), sel0, accx, 0, 0, 0);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ap + XT_ELEMS + (2 * wv + 1) * 16), sel1, accx, 0, 0, 0);
+    }
+    __syncthreads();   // the x tile is free for the next chunk
+  }
+
+  // ---- h into accumulator layout: lane (j, hf) owns channel j of rows 16 hf .. 16 hf + 15
+#pragma unroll
+  for (int i = 0; i < 4; ++i) *(u32x4 *)(hl + i * 8 * W_WROW + hl_wide) = hin[i];
+  wave_lds_fence();
+  float rh[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) rh[r] = *(const float *)(hl + (hf * 16 + r) * W_WROW + j * 4);
+  wave_lds_fence();
+
+  // ---- eqs. (1)-(4) with base-2 exponentials (the pre-activations and x carry log2 e)
+  unsigned char *yl = wl;   // weight buffer 0 of this wave is free again
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const float rg = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-accp[r]));
+    const float av_ = __builtin_amdgcn_exp2f(kd * rg);
+    const float mm = __builtin_amdgcn_sqrtf(fmaf(-av_, av_, 1.f));
+    const float eq = __builtin_amdgcn_exp2f(-accq[r]);
+    const float il = __builtin_amdgcn_rcpf(fmaf(eq, LOG2E, LOG2E));   // sigmoid(q) / log2 e
+    const float hn = fmaf(av_, rh[r], (mm * il) * accx[r]);
+    *(float *)(hl + (hf * 16 + r) * W_WROW + j * 4) = hn;
+    *(unsigned short *)(yl + (hf * 16 + r) * DW_YROW + j * 2) = (unsigned short)(pack_bf16(hn, 0.f) & 0xffff);
+  }
+  wave_lds_fence();
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    __builtin_amdgcn_raw_buffer_store_b128(*(const u32x4 *)(hl + i * 8 * W_WROW + hl_wide), h_rsrc, h_vo[i], 0, 0);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {   // lane l: 16 bytes of rows l/4 + 16 i
+    const int row = (lane >> 2) + 16 * i;
+    u32x4 yv = *(const u32x4 *)(yl + row * DW_YROW + (lane & 3) * 16);
+    if (MERGE) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        yv[k] = pack_bf16(bf_lo(yv[k]) * gl[i][2 * k], bf_hi(yv[k]) * gl[i][2 * k + 1]);
+    }
+    __builtin_amdgcn_raw_buffer_store_b128(yv, y_rsrc, y_vo[i], 0, 0);
+  }
+}
+
+// the new token into ring slot pos mod 3, 16 bytes per thread
+__global__ void __launch_bounds__(256) ring_store_kernel(const uint4 *u, uint4 *ring, int B, int chunks, int slot) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= B * chunks) return;
+  const int b = i / chunks, c = i - b * chunks;
+  ring[((size_t)b * 3 + slot) * chunks + c] = u[i];
+}
+
 inline size_t al256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 // ---- Conv1D (Section 2.3) as a streaming pass: a thread produces 8 channels (16 bytes) of CR
@@ -367,6 +650,45 @@ hipError_t launch_forward_wide(const Problem &p, hipStream_t s) {
   e = launch_scan_tiled(q, s);
   if (e != hipSuccess) return e;
   return launch_state_update(p, true, s);
+}
+
+}  // namespace rglru
+
+namespace rglru {
+
+bool decode_wide_supported(const Problem &p, bool bf) {
+  const uintptr_t all = (uintptr_t)p.W_a | (uintptr_t)p.W_x | (uintptr_t)p.u | (uintptr_t)p.state_out |
+                        (uintptr_t)p.hT | (uintptr_t)p.y | (uintptr_t)p.conv_w | (uintptr_t)p.conv_b |
+                        (uintptr_t)(p.merge ? p.branch : nullptr);
+  return bf && forward_wide_block(p.bs) && p.bs <= DW_MAXCH * BS && all % 16 == 0 &&
+         (size_t)(p.B + TT) * 3 * p.D * 2 < ((size_t)1 << 31);
+}
+
+hipError_t launch_decode_wide(const Problem &p, hipStream_t s) {
+  DecWideArgs a;
+  a.p = p;
+  a.nob = (p.bs + BS - 1) / BS;
+  static bool configured = false;
+  hipError_t e;
+  if (!configured) {
+    if ((e = hipFuncSetAttribute((const void *)decode_wide_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, DW_LDS)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute((const void *)decode_wide_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, DW_LDS)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute((const void *)decode_wide_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, DW_LDS)) != hipSuccess) return e;
+    configured = true;
+  }
+  const dim3 grid(p.nb * a.nob, (p.B + TT - 1) / TT);
+  {
+    KernelTimer kt("decode_wide_kernel", s);
+    if (p.merge == 0) hipLaunchKernelGGL(decode_wide_kernel<0>, grid, dim3(NTHR), DW_LDS, s, a);
+    else if (p.merge == 1) hipLaunchKernelGGL(decode_wide_kernel<1>, grid, dim3(NTHR), DW_LDS, s, a);
+    else hipLaunchKernelGGL(decode_wide_kernel<2>, grid, dim3(NTHR), DW_LDS, s, a);
+    e = hipGetLastError();
+  }
+  if (e != hipSuccess) return e;
+  const int chunks = p.D / 8;
+  hipLaunchKernelGGL(ring_store_kernel, dim3((p.B * chunks + 255) / 256), dim3(256), 0, s, (const uint4 *)p.u,
+                     (uint4 *)p.state_out, p.B, chunks, ring_slot(p.pos0));
+  return hipGetLastError();
 }
 
 }  // namespace rglru

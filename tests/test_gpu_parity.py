@@ -138,7 +138,11 @@ def test_conv1d_matches_oracle(B, T, D, act, full):
 
 
 @pytest.mark.parametrize("B,D,nb,act", [(5, 64, 2, "f32"), (19, 512, 2, "bf16"), (3, 320, 2, "bf16"),
-                                        (64, 1024, 4, "bf16"), (33, 256, 1, "bf16")])
+                                        (64, 1024, 4, "bf16"), (33, 256, 1, "bf16"),
+                                        (37, 1024, 2, "bf16"),    # bs = 512: two chunks of input channels
+                                        (5, 704, 2, "bf16"),      # bs = 352: a partial second chunk
+                                        (70, 1536, 2, "bf16"),    # bs = 768: three chunks
+                                        (3, 256, 4, "bf16")])     # bs = 64: one partial chunk
 def test_decode_steps_match_oracle_and_wrap_the_ring(B, D, nb, act):
     rn = runner()
     nsteps = 7
@@ -471,7 +475,7 @@ def test_merge_calls_reject_bad_arguments():
 
 
 @pytest.mark.parametrize("B,D,nb,act", [(5, 64, 2, "f32"), (3, 320, 2, "bf16"), (64, 1024, 4, "bf16"),
-                                        (33, 256, 1, "bf16")])
+                                        (33, 256, 1, "bf16"), (37, 1024, 2, "bf16"), (5, 704, 2, "bf16")])
 @pytest.mark.parametrize("tanh_form", [False, True])
 def test_decode_steps_with_merge_match_oracle(B, D, nb, act, tanh_form):
     import paper_2402_19427_amd as R
