@@ -46,10 +46,11 @@
  * Which kernels run (bf16 storage): gate blocks of 256 channels, or of a multiple of 16 channels
  * from 128 to 240 (e.g. Section 4.1's 16 blocks at width 2560 = 160 channels), run on the fused
  * matrix-core kernels in every call. Any other multiple of 16 (e.g. 352 and 512 channels at
- * widths 5632 and 8192) at a width that is a multiple of 256: rglru_forward runs as three
- * matrix-core passes through the workspace; decode steps and the backward of those shapes, all
- * other block sizes up to 2048 and fp32 storage run on generic kernels that give the same
- * results far more slowly. rglru_workspace_bytes() accounts for all of it.
+ * widths 5632 and 8192): rglru_forward runs as three matrix-core passes through the workspace
+ * (widths that are a multiple of 256), decode steps on a matrix-core kernel of their own
+ * (blocks up to 768 channels). The backward of those shapes, all other block sizes up to 2048
+ * and fp32 storage run on generic kernels that give the same results far more slowly.
+ * rglru_workspace_bytes() accounts for all of it.
  */
 #ifndef RGLRU_H
 #define RGLRU_H

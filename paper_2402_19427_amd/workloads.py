@@ -133,7 +133,7 @@ def run_sequence_workload(w, dev, out, label="forward"):
                    gate_flops("backward", B, T, D, nb)))
 
 
-def run_decode_workload(w, dev, out, steps=1000, graph_only=False):
+def run_decode_workload(w, dev, out, steps=1000, graph_only=False, label="decode,"):
     B, D, nb = w.B, w.D, w.nb
     act_b = 2 if w.act == "bf16" else 4
     inp = gen.make_inputs(1, 8, D, nb, act=w.act, seed=w.seed)
@@ -161,6 +161,7 @@ def run_decode_workload(w, dev, out, steps=1000, graph_only=False):
         R.rglru_decode_step(sh, dp.params, s["u"], s["h"], s["st"], pos[0], s["y"], sp)
         pos[0] += 1
 
+    label_head = label
     for nsets, label in ((1, "hot: 1 buffer set"), (ncold, "cold: %d buffer sets" % ncold)):
         ms = time_calls(step, nsets, 20 if graph_only else steps, 20)
         if not graph_only:
@@ -194,7 +195,7 @@ def run_decode_workload(w, dev, out, steps=1000, graph_only=False):
             e1.record()
             torch.cuda.synchronize()
             reps.append(e0.elapsed_time(e1) / steps)
-        out.append(row(w.name, "decode, one graph of %d steps" % steps, label, np.array(reps), B,
+        out.append(row(w.name, "%s one graph of %d steps" % (label_head, steps), label, np.array(reps), B,
                        nbytes, flops))
         del graph
 
@@ -357,6 +358,8 @@ def main():
             for D in (5632, 8192):
                 run_sequence_workload(dataclasses.replace(c1, name="NB16", D=D, nb=16, kind="forward"),
                                       dev, out, label="forward, width %d" % D)
+                run_decode_workload(dataclasses.replace(gen.CONFIGS["C3"], name="NB16", D=D), dev, out,
+                                    graph_only=True, label="decode, width %d," % D)
         elif w.kind == "decode":
             run_decode_workload(w, dev, out)
         else:
