@@ -80,10 +80,13 @@ def test_forward_matches_oracle(B, T, D, nb, act, full):
     np.testing.assert_array_equal(gen.chrono_from_ring(rn.to_host(st), pos0 + T), st_ref)
 
 
-@pytest.mark.parametrize("act", ["f32", "bf16"])
-def test_forward_in_pieces_equals_one_shot_and_states_may_alias(act):
+@pytest.mark.parametrize("act,D,nb", [("f32", 64, 2), ("bf16", 64, 2),
+                                      ("bf16", 512, 2),    # fused kernel
+                                      ("bf16", 320, 2),    # fused kernel, narrower blocks in the padded tile
+                                      ("bf16", 256, 4)])   # separate passes (blocks of 64 channels)
+def test_forward_in_pieces_equals_one_shot_and_states_may_alias(act, D, nb):
     rn = runner()
-    B, T, D, nb = 2, 45, 64, 2
+    B, T = 2, 45
     inp = gen.make_inputs(B, T, D, nb, act=act, seed=77, h0=True)
     dp = rn.DeviceProblem(inp, B, T, D, nb, act)
     u = rn.to_device(inp["u"], act)
