@@ -305,6 +305,56 @@ def test_whole_step_replays_as_a_hip_graph():
             assert torch.equal(v, eager[k]), (rep, k)
 
 
+@pytest.mark.parametrize("D,nb", [(2560, 16),     # 160-channel blocks: padded tile, backward on the widened copy
+                                  (1024, 2)])      # 512-channel blocks: forward and decode as separate kernels
+def test_merge_step_replays_as_a_hip_graph(D, nb):
+    """forward + merge, backward + merge and a decode step + merge captured into one HIP graph on
+    the paths of the other block sizes: every replay gives the bits of the eager run."""
+    import torch
+    import paper_2402_19427_amd as R
+    rn = runner()
+    B, T, act = 3, 200, "bf16"
+    inp = gen.make_inputs(B, T + 1, D, nb, act=act, seed=22, dy=True)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    u_all = rn.to_device(inp["u"], act)
+    u, u_next = u_all[:, :T].contiguous(), u_all[:, T].contiguous()
+    br_all = rn.to_device(gen.make_branch(B, T + 1, D, act=act, seed=23), act)
+    br, br_next = br_all[:, :T].contiguous(), br_all[:, T].contiguous()
+    dout = rn.to_device(inp["dy"][:, :T], act)
+    sh, sh1 = dp.shape(), dp.shape(T=1)
+    ws_f, n_f = dp.workspace(sh, R.OP_FORWARD_MERGE)
+    ws_b, n_b = dp.workspace(sh, R.OP_BACKWARD_MERGE)
+    out, y, hT, st = dp.empty_act(B, T, D), dp.empty_act(B, T, D), dp.empty_f32(B, D), dp.empty_act(B, 3, D)
+    o1, du, dbr, dh0 = dp.empty_act(B, D), dp.empty_act(B, T, D), dp.empty_act(B, T, D), dp.empty_f32(B, D)
+    g = dp.alloc_grads()
+    pg = R.make_param_grads(g["dW_a"], g["dW_x"], g["db_a"], g["db_x"], g["dLambda"],
+                            g["dconv_w"], g["dconv_b"])
+    outs = dict(out=out, y=y, hT=hT, st=st, o1=o1, du=du, dbr=dbr, dh0=dh0, **g)
+
+    def step(stream):
+        R.rglru_forward_merge(sh, dp.params, u, br, None, None, 0, 0, out, y, hT, st, ws_f, n_f, stream)
+        R.rglru_backward_merge(sh, dp.params, u, br, None, None, 0, 0, y, dout, None, du, dbr, dh0, pg,
+                               ws_b, n_b, stream)
+        R.rglru_decode_step_merge(sh1, dp.params, u_next, br_next, hT, st, T, 0, o1, stream)
+
+    step(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    eager = {k: v.clone() for k, v in outs.items()}
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(torch.cuda.current_stream().cuda_stream)
+    for rep in range(3):
+        for v in outs.values():
+            v.fill_(7.0)
+        ws_f.fill_(rep + 1)
+        ws_b.fill_(rep + 1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, v in outs.items():
+            assert torch.equal(v, eager[k]), (rep, k)
+
+
 SCAN_SHAPES = [
     # B, T, D, act
     (2, 37, 96, "f32"),          # generic kernel, ragged everything
