@@ -509,6 +509,20 @@ def test_backward_merge_matches_oracle(B, T, D, nb, act, tanh_form):
     R.rglru_workspace_status(sh, R.OP_BACKWARD_MERGE, ws)
 
 
+def test_forward_merge_zero_length_passes_states_through():
+    import paper_2402_19427_amd as R
+    rn = runner()
+    B, D, nb = 2, 512, 2
+    inp = gen.make_inputs(B, 4, D, nb, act="bf16", seed=5, h0=True, state=True)
+    dp = rn.DeviceProblem(inp, B, 0, D, nb, "bf16")
+    ring = rn.to_device(gen.ring_from_chrono(inp["state"], 7), "bf16")
+    out, y, hT, st = dp.forward_merge(dp.empty_act(B, 0, D), dp.empty_act(B, 0, D),
+                                      h0=rn.to_device(inp["h0"], "f32"), state_in=ring, pos0=7)
+    np.testing.assert_array_equal(rn.to_host(hT), inp["h0"])
+    np.testing.assert_array_equal(rn.to_host(st), rn.to_host(ring))
+    assert out.numel() == 0
+
+
 def test_merge_calls_reject_bad_arguments():
     import paper_2402_19427_amd as R
     rn = runner()
@@ -528,7 +542,8 @@ def test_merge_calls_reject_bad_arguments():
 
 
 @pytest.mark.parametrize("B,D,nb,act", [(5, 64, 2, "f32"), (3, 320, 2, "bf16"), (64, 1024, 4, "bf16"),
-                                        (33, 256, 1, "bf16"), (37, 1024, 2, "bf16"), (5, 704, 2, "bf16")])
+                                        (33, 256, 1, "bf16"), (37, 1024, 2, "bf16"), (5, 704, 2, "bf16"),
+                                        (1, 512, 2, "bf16")])
 @pytest.mark.parametrize("tanh_form", [False, True])
 def test_decode_steps_with_merge_match_oracle(B, D, nb, act, tanh_form):
     import paper_2402_19427_amd as R
