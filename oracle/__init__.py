@@ -111,6 +111,20 @@ def scan(a, g, h0=None, a_is_log=False, normalize=True):
     return h, hT
 
 
+def scan_adjoint(a, dy, dhT=None, a_is_log=False):
+    """Adjoint of the unscaled scan h_t = a_t h_{t-1} + b_t: delta_t = dy_t + a_{t+1} delta_{t+1}
+    (delta_{T-1} = dy_{T-1} + dhT). Returns delta [B,T,D] (= dL/db) and dh0 = a_0 delta_0 [B,D]."""
+    a, dy, dhT = map(_f64, (a, dy, dhT))
+    B, T, D = a.shape
+    assert dy.shape == (B, T, D) and (dhT is None or dhT.shape == (B, D))
+    delta = np.empty((B, T, D))
+    dh0 = np.empty((B, D))
+    _load().oracle_scan_adjoint(B, T, D, int(bool(a_is_log)), _p(a), _p(dy), _p(dhT), _p(delta), _p(dh0))
+    if T == 0:
+        dh0[...] = 0.0 if dhT is None else dhT
+    return delta, dh0
+
+
 def gelu(z, approx=False):
     """GeLU(z) = z Phi(z) (Section 2.3's non-linearity); approx selects the tanh form."""
     lib = _load()

@@ -208,6 +208,33 @@ void oracle_scan(int B, int T, int D, int a_is_log, int normalize,
 }
 
 /* ------------------------------------------------------------------------ */
+/* The adjoint of that scan with respect to its inputs (not printed in the   */
+/* paper; it is what training through eq. (4) needs): for                    */
+/*   h_t = a_t h_{t-1} + b_t  and  L = sum_t dy_t h_t + dhT h_{T-1}          */
+/* the gradient reaching h_t is                                              */
+/*   delta_t = dy_t + a_{t+1} delta_{t+1},  delta_{T-1} = dy_{T-1} + dhT,    */
+/* dL/db_t = delta_t, dL/da_t = delta_t h_{t-1}, dL/dh_{-1} = a_0 delta_0.   */
+/* a, dy, delta: [B][T][D]; dhT, dh0: [B][D] (dhT NULL = zeros, dh0 NULL =   */
+/* skipped). ``a`` holds a_t, or log a_t when a_is_log.                      */
+/* ------------------------------------------------------------------------ */
+void oracle_scan_adjoint(int B, int T, int D, int a_is_log, const double *a,
+                         const double *dy, const double *dhT, double *delta,
+                         double *dh0) {
+  for (int b = 0; b < B; ++b) {
+    for (int d = 0; d < D; ++d) {
+      double s = dhT ? dhT[(size_t)b * D + d] : 0.0;  /* a_{t+1} delta_{t+1} */
+      for (int t = T - 1; t >= 0; --t) {
+        const size_t o = ((size_t)b * T + t) * D + d;
+        const double dl = dy[o] + s;
+        delta[o] = dl;
+        s = (a_is_log ? exp(a[o]) : a[o]) * dl;
+      }
+      if (dh0) dh0[(size_t)b * D + d] = s;
+    }
+  }
+}
+
+/* ------------------------------------------------------------------------ */
 /* The recurrent block's merge (Section 2.3, "Recurrent block"): the output  */
 /* of the RG-LRU branch is multiplied element by element with GeLU of the    */
 /* other branch.  GeLU(z) = z * Phi(z) with Phi the standard normal CDF (the */

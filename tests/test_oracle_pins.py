@@ -543,3 +543,46 @@ def test_backward_merge_matches_finite_differences_through_the_whole_path():
     big = np.full_like(br, 40.0)
     out, y, _, _ = oracle.forward_merge(q["u"], big, *args, h0=q["h0"])
     np.testing.assert_allclose(out, 40.0 * y, rtol=1e-14)
+
+
+# ------------------------------------------------------------------ adjoint of the scan
+def test_scan_adjoint_is_the_transpose_of_the_scan():
+    # <dy, scan(b)> + <dhT, h_{T-1}> == <delta, b> + <dh0, h0> for the linear map (b, h0) -> h
+    a, b, h0 = _scan_inputs(2, 23, 4, 8)
+    rng = np.random.default_rng(9)
+    dy = rng.standard_normal(a.shape)
+    dhT = rng.standard_normal(h0.shape)
+    h, hT = oracle.scan(a, b, h0, normalize=False)
+    delta, dh0 = oracle.scan_adjoint(a, dy, dhT)
+    lhs = np.sum(dy * h) + np.sum(dhT * hT)
+    rhs = np.sum(delta * b) + np.sum(dh0 * h0)
+    assert abs(lhs - rhs) < 1e-10 * max(1.0, abs(lhs))
+    # the same recurrence run on flipped arrays: delta = flip(scan(flip(shifted a), flip(dy), dhT))
+    a_next = np.concatenate([a[:, 1:], np.ones_like(a[:, :1])], axis=1)
+    d2, _ = oracle.scan(a_next[:, ::-1].copy(), dy[:, ::-1].copy(), dhT, normalize=False)
+    np.testing.assert_allclose(delta, d2[:, ::-1], rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(dh0, a[:, 0] * delta[:, 0], rtol=1e-13)
+    # log form, and no dhT
+    d3, dh3 = oracle.scan_adjoint(np.log(a), dy, dhT, a_is_log=True)
+    np.testing.assert_allclose(d3, delta, rtol=1e-12, atol=1e-13)
+    d4, _ = oracle.scan_adjoint(a, dy, None)
+    d5, _ = oracle.scan_adjoint(a, dy, np.zeros_like(dhT))
+    np.testing.assert_array_equal(d4, d5)
+
+
+def test_scan_adjoint_gives_the_gradient_of_the_decays_by_finite_differences():
+    a, b, h0 = _scan_inputs(1, 9, 3, 10)
+    rng = np.random.default_rng(11)
+    dy = rng.standard_normal(a.shape)
+    h, _ = oracle.scan(a, b, h0, normalize=False)
+    delta, _ = oracle.scan_adjoint(a, dy)
+    h_prev = np.concatenate([h0[:, None, :], h[:, :-1]], axis=1)
+    da = delta * h_prev                       # dL/da_t = delta_t h_{t-1}
+    e = 1e-6
+    for idx in [(0, 0, 0), (0, 4, 1), (0, 8, 2)]:
+        ap, am = a.copy(), a.copy()
+        ap[idx] += e
+        am[idx] -= e
+        fd = (np.sum(dy * oracle.scan(ap, b, h0, normalize=False)[0])
+              - np.sum(dy * oracle.scan(am, b, h0, normalize=False)[0])) / (2 * e)
+        assert abs(da[idx] - fd) < 1e-7
