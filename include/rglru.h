@@ -133,6 +133,8 @@ int rglru_conv1d(const rglru_shape *shape, const void *u, const float *conv_w,
 /* flags of rglru_scan() */
 #define RGLRU_SCAN_LOG_A 1u          /* `a` holds log a_t (<= 0) instead of a_t            */
 #define RGLRU_SCAN_NO_INPUT_SCALE 2u /* h_t = a_t h_{t-1} + g_t, without sqrt(1 - a_t^2)   */
+#define RGLRU_SCAN_ADJOINT 4u        /* the adjoint recurrence, backwards in time (below);  */
+                                     /* only together with RGLRU_SCAN_NO_INPUT_SCALE        */
 
 /*
  * Eq. (4) alone, as a linear scan over given sequences (Section 4.2, "A custom linear scan";
@@ -147,6 +149,12 @@ int rglru_conv1d(const rglru_shape *shape, const void *u, const float *conv_w,
  *   workspace: rglru_workspace_bytes(shape, RGLRU_OP_SCAN) bytes.
  * The state is carried in fp32 whatever the storage type. Of `shape`, only B, T (>= 0), D and
  * act_dtype are used (the other fields must still be valid). T == 0 writes hT = h0 only.
+ * With RGLRU_SCAN_ADJOINT the call runs the adjoint of the unscaled scan (what training through
+ * eq. (4) needs; not printed in the paper): for L = sum_t g_t h_t + h0 . h_{T-1} it returns
+ *     delta_t = g_t + a_{t+1} delta_{t+1},   delta_{T-1} = g_{T-1} + h0
+ * in `h` (delta_t = dL/db_t for h_t = a_t h_{t-1} + b_t; dL/da_t = delta_t h_{t-1}) and
+ * a_0 delta_0 = dL/dh_{-1} in `hT`: `g` carries the upstream gradient, `h0` the gradient
+ * reaching the final state (NULL = zeros), `a` is the forward call's array, unshifted.
  */
 int rglru_scan(const rglru_shape *shape, const void *a, const void *g, const float *h0,
                unsigned flags, void *h, float *hT, void *workspace, size_t workspace_bytes,

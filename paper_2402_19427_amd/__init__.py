@@ -11,7 +11,7 @@ import importlib
 _EXPORTS = (
     "BF16", "F32", "OK", "ERR_HIP", "ERR_TIMEOUT", "rglru_workspace_status", "ERR_INVALID_ARG", "ERR_UNSUPPORTED", "ERR_WORKSPACE",
     "OP_BACKWARD", "OP_BACKWARD_MERGE", "OP_FORWARD_MERGE", "MERGE_GELU_TANH", "MERGE_SEPARATE", "rglru_forward_merge", "rglru_decode_step_merge",
-    "rglru_backward_merge", "OP_CONV1D", "OP_DECODE", "OP_FORWARD", "OP_SCAN", "SCAN_LOG_A",
+    "rglru_backward_merge", "OP_CONV1D", "OP_DECODE", "OP_FORWARD", "OP_SCAN", "SCAN_LOG_A", "SCAN_ADJOINT",
     "SCAN_NO_INPUT_SCALE", "rglru_scan", "LIB_PATH", "ParamGrads", "Params",
     "RglruError", "Shape", "make_param_grads", "make_params", "make_shape", "rglru_backward",
     "rglru_conv1d", "rglru_decode_step", "rglru_forward", "rglru_last_error", "rglru_version",

@@ -15,7 +15,7 @@ F32, BF16 = 0, 1
 OP_CONV1D, OP_FORWARD, OP_DECODE, OP_BACKWARD, OP_SCAN = 0, 1, 2, 3, 4
 OP_FORWARD_MERGE, OP_BACKWARD_MERGE = 5, 6
 MERGE_GELU_TANH, MERGE_SEPARATE = 1, 2
-SCAN_LOG_A, SCAN_NO_INPUT_SCALE = 1, 2
+SCAN_LOG_A, SCAN_NO_INPUT_SCALE, SCAN_ADJOINT = 1, 2, 4
 
 
 class Shape(ctypes.Structure):

@@ -381,8 +381,10 @@ int rglru_scan(const rglru_shape *shape, const void *a, const void *g, const flo
                unsigned flags, void *h, float *hT, void *workspace, size_t workspace_bytes,
                void *stream) {
   CHECK(check_shape(shape, false, true, 0));
-  if (flags & ~(RGLRU_SCAN_LOG_A | RGLRU_SCAN_NO_INPUT_SCALE))
+  if (flags & ~(RGLRU_SCAN_LOG_A | RGLRU_SCAN_NO_INPUT_SCALE | RGLRU_SCAN_ADJOINT))
     return fail(RGLRU_ERR_INVALID_ARG, "unknown scan flags 0x%x", flags);
+  if ((flags & RGLRU_SCAN_ADJOINT) && !(flags & RGLRU_SCAN_NO_INPUT_SCALE))
+    return fail(RGLRU_ERR_INVALID_ARG, "scan flags: RGLRU_SCAN_ADJOINT needs RGLRU_SCAN_NO_INPUT_SCALE");
   const size_t as = act_size(shape);
   CHECK(check_ptr(a, "a", as, shape->T > 0));
   CHECK(check_ptr(g, "g", as, shape->T > 0));

@@ -44,6 +44,19 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_generic_kernel(ScanProblem 
   float h = p.h0 ? p.h0[(size_t)b * p.D + d] : 0.f;
   const AT *a = (const AT *)p.a, *g = (const AT *)p.g;
   AT *out = (AT *)p.h;
+  if (p.flags & RGLRU_SCAN_ADJOINT) {   // delta_t = g_t + a_{t+1} delta_{t+1}, backwards in time
+    float s = h;                         // a_{t+1} delta_{t+1}; starts as the gradient of the final state
+    for (int t = p.T - 1; t >= 0; --t) {
+      const size_t o = ((size_t)b * p.T + t) * p.D + d;
+      float av, mv;
+      decay_terms(ldf(a, o), p.flags, av, mv);
+      const float dl = ldf(g, o) + s;
+      stf(out, o, dl);
+      s = av * dl;
+    }
+    if (p.hT) p.hT[(size_t)b * p.D + d] = s;
+    return;
+  }
   for (int t = 0; t < p.T; ++t) {
     const size_t o = ((size_t)b * p.T + t) * p.D + d;
     float av, mv;
@@ -109,7 +122,11 @@ __device__ __forceinline__ void scan_terms(float av, float gv, float &a, float &
 
 // GF16: g_t is stored in IEEE half precision (the library's own intermediate of the forward in
 // separate passes); its columns are moved with the f16 form of the same selection product.
-template <int GMAX, bool LOGA, bool SCALE, bool GF16>
+// REV: the adjoint recurrence. The kernel runs in logical time tau = T-1-t: rows are read and
+// written at their mirrored positions, the decay of logical step tau is a_{t+1} (one row further
+// on; the first logical step has none: it reads as log a = 0, or is set to 1), and the state
+// after the last step, times a_0, is the gradient of the initial state.
+template <int GMAX, bool LOGA, bool SCALE, bool GF16, bool REV>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 scan_tiled_kernel(ScanArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -164,6 +181,14 @@ scan_tiled_kernel(ScanArgs a) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int row = t0 + lr + 16 * i;
+      if (REV) {
+        const unsigned vg = row < T ? in_voff + (unsigned)(T - 1 - row) * row_bytes : 0x80000000u;
+        const unsigned va = (row >= 1 && row < T) ? in_voff + (unsigned)(T - row) * row_bytes : 0x80000000u;
+        xa[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, va, 0, RGLRU_NT);
+        xg[i] = __builtin_amdgcn_raw_buffer_load_b128(g_rsrc, vg, 0, RGLRU_NT);
+        if (!LOGA && row == 0) xa[i] = u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};   // a = 1
+        continue;
+      }
       const unsigned vo = row < T ? in_voff + (unsigned)(lr + 16 * i) * row_bytes : 0x80000000u;
       xa[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, vo, (unsigned)t0 * row_bytes, RGLRU_NT);
       xg[i] = __builtin_amdgcn_raw_buffer_load_b128(g_rsrc, vo, (unsigned)t0 * row_bytes, RGLRU_NT);
@@ -238,8 +263,17 @@ scan_tiled_kernel(ScanArgs a) {
     }
     wave_lds_fence();
     // (inputs are read non-temporally, outputs written through the cache: measured best)
-    store_staged_tile_s<OT, 0>(otile, lane, h_rsrc, hw_voff, (unsigned)(t * TT) * row_bytes, row_bytes,
-                                      T - t * TT);
+    if (REV) {   // rows at their mirrored positions
+      const int row = t * TT + (lane >> 2);
+      const unsigned cvo = (unsigned)(cg * BS + wv * 32 + (lane & 3) * 8) * 2;
+      const u32x4 v0 = *(const u32x4 *)(otile + (lane >> 2) * OT + (lane & 3) * 8);
+      const u32x4 v1 = *(const u32x4 *)(otile + ((lane >> 2) + 16) * OT + (lane & 3) * 8);
+      if (row < T) __builtin_amdgcn_raw_buffer_store_b128(v0, h_rsrc, cvo + (unsigned)(T - 1 - row) * row_bytes, 0, 0);
+      if (row + 16 < T) __builtin_amdgcn_raw_buffer_store_b128(v1, h_rsrc, cvo + (unsigned)(T - 17 - row) * row_bytes, 0, 0);
+    } else {
+      store_staged_tile_s<OT, 0>(otile, lane, h_rsrc, hw_voff, (unsigned)(t * TT) * row_bytes, row_bytes,
+                                 T - t * TT);
+    }
     wave_lds_fence();
     carry = fmaf(agg[P][2], h, agg[P][3]);
   };
@@ -325,20 +359,27 @@ scan_tiled_kernel(ScanArgs a) {
     if (spins >= SPIN_LIMIT) *a.err = 1;
   }
   // the workgroup that ran the last tile owns the final state
-  if ((a.ntile - 1) % G == w && p.hT && hf == 0) p.hT[(size_t)b * D + d] = carry;
+  if ((a.ntile - 1) % G == w && p.hT && hf == 0) {
+    float fin = carry;
+    if (REV) {   // times a_0: the gradient reaching the state before the first step
+      const float v0 = bf_lo((unsigned)((const unsigned short *)p.a)[(size_t)b * T * D + d]);
+      fin *= LOGA ? __builtin_amdgcn_exp2f(v0 * LOG2E) : v0;
+    }
+    p.hT[(size_t)b * D + d] = fin;
+  }
 }
 
-template <int GMAX, bool LOGA, bool SCALE, bool GF16 = false>
+template <int GMAX, bool LOGA, bool SCALE, bool GF16 = false, bool REV = false>
 hipError_t launch_scan_t(const ScanArgs &a, int grid, hipStream_t s) {
   static bool configured = false;  // the kernel asks for more than the default LDS limit
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void *)scan_tiled_kernel<GMAX, LOGA, SCALE, GF16>,
+    hipError_t e = hipFuncSetAttribute((const void *)scan_tiled_kernel<GMAX, LOGA, SCALE, GF16, REV>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, SC_LDS);
     if (e != hipSuccess) return e;
     configured = true;
   }
   KernelTimer kt("scan_tiled_kernel", s);
-  hipLaunchKernelGGL((scan_tiled_kernel<GMAX, LOGA, SCALE, GF16>), dim3(grid), dim3(NTHR), SC_LDS, s, a);
+  hipLaunchKernelGGL((scan_tiled_kernel<GMAX, LOGA, SCALE, GF16, REV>), dim3(grid), dim3(NTHR), SC_LDS, s, a);
   return hipGetLastError();
 }
 
@@ -346,6 +387,9 @@ template <int GMAX>
 hipError_t launch_scan_flags(const ScanArgs &a, int grid, hipStream_t s) {
   const bool loga = a.p.flags & RGLRU_SCAN_LOG_A, scale = !(a.p.flags & RGLRU_SCAN_NO_INPUT_SCALE);
   if (a.p.flags & SCAN_G_FP16) return launch_scan_t<GMAX, true, false, true>(a, grid, s);   // internal use: this form only
+  if (a.p.flags & RGLRU_SCAN_ADJOINT)   // (always without the input scale)
+    return loga ? launch_scan_t<GMAX, true, false, false, true>(a, grid, s)
+                : launch_scan_t<GMAX, false, false, false, true>(a, grid, s);
   if (loga) return scale ? launch_scan_t<GMAX, true, true>(a, grid, s) : launch_scan_t<GMAX, true, false>(a, grid, s);
   return scale ? launch_scan_t<GMAX, false, true>(a, grid, s) : launch_scan_t<GMAX, false, false>(a, grid, s);
 }

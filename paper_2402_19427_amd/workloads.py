@@ -227,7 +227,8 @@ def run_scan_workload(dev, out, lengths=(1024, 4096, 16384, 65536)):
         nbytes = per_set + 8 * B * D
         note = "%d buffer set%s" % (nsets, "s" if nsets > 1 else "")
         iters = 100 if T <= 16384 else 30
-        for key, flags, label in (("a", 0, "scan T=%d" % T), ("la", R.SCAN_LOG_A, "scan T=%d, log a_t" % T)):
+        for key, flags, label in (("a", 0, "scan T=%d" % T), ("la", R.SCAN_LOG_A, "scan T=%d, log a_t" % T),
+                                  ("a", R.SCAN_ADJOINT | R.SCAN_NO_INPUT_SCALE, "scan adjoint T=%d" % T)):
             def call(i):
                 st = sets[i]
                 R.rglru_scan(sh, st[key], st["g"], h0, flags, st["h"], hT, ws, n, sp)

@@ -153,6 +153,9 @@ def test_scan_validation():
     with pytest.raises(R.RglruError) as e:
         R.rglru_scan(s, FAKE, FAKE, None, 8, FAKE, None, None, 0)
     assert e.value.code == R.ERR_INVALID_ARG and "flags" in str(e.value)
+    with pytest.raises(R.RglruError) as e:      # the adjoint exists for the unscaled recurrence only
+        R.rglru_scan(s, FAKE, FAKE, None, R.SCAN_ADJOINT, FAKE, None, None, 0)
+    assert e.value.code == R.ERR_INVALID_ARG and "ADJOINT" in str(e.value)
     with pytest.raises(R.RglruError) as e:
         R.rglru_scan(s, FAKE + 1, FAKE, None, 0, FAKE, None, None, 0)
     assert e.value.code == R.ERR_INVALID_ARG and "aligned" in str(e.value)

@@ -383,6 +383,21 @@ def test_scan_matches_oracle(B, T, D, act, log_a, scale):
     assert gen.rel_err(rn.to_host(hT), hT_ref) < (1e-5 if act == "f32" else 1e-4)   # hT is fp32
 
 
+@pytest.mark.parametrize("B,T,D,act", SCAN_SHAPES)
+@pytest.mark.parametrize("log_a", [False, True])
+def test_scan_adjoint_matches_oracle(B, T, D, act, log_a):
+    import paper_2402_19427_amd as R
+    rn = runner()
+    inp = gen.make_scan_inputs(B, T, D, act=act, seed=2 * B + T + D, log_a=log_a)
+    flags = R.SCAN_ADJOINT | R.SCAN_NO_INPUT_SCALE | (R.SCAN_LOG_A if log_a else 0)
+    delta, dh0 = rn.scan(rn.to_device(inp["a"], act), rn.to_device(inp["g"], act),
+                         rn.to_device(inp["h0"], "f32"), flags=flags, act=act)
+    oracle.set_threads(1)
+    d_ref, dh0_ref = oracle.scan_adjoint(inp["a"], inp["g"], inp["h0"], a_is_log=log_a)
+    assert gen.rel_err(rn.to_host(delta), d_ref) < TOL[act]
+    assert gen.rel_err(rn.to_host(dh0), dh0_ref) < TOL[act]
+
+
 def test_scan_without_h0_and_without_hT_and_empty():
     import torch
     import paper_2402_19427_amd as R
