@@ -121,6 +121,13 @@ bool backward_via_padding(const rglru_shape *s) {
          (size_t)s->T * s->num_blocks * 256 * 4 < ((size_t)1 << 32);
 }
 
+// the other multiples of 16 at widths that are multiples of 256: the backward's pointwise pass
+// runs as passes on the tuned kernels (its workspace contains the generic kernels' own)
+bool backward_in_passes(const rglru_shape *s) {
+  return s->act_dtype == RGLRU_BF16 && forward_wide_block(s->D / s->num_blocks) && s->D % 256 == 0 &&
+         s->T >= 1 && (size_t)s->B * s->T * s->D * 2 < ((size_t)1 << 31);
+}
+
 size_t workspace_need(const rglru_shape *s, int op);
 size_t workspace_need(const rglru_shape *s, int op) {
   switch (op) {
@@ -134,6 +141,7 @@ size_t workspace_need(const rglru_shape *s, int op) {
         const size_t b = backward_generic_ws_bytes(s->B, s->T, s->D, s->num_blocks);
         return a > b ? a : b;
       }
+      if (backward_in_passes(s)) return backward_wide_ws_bytes(s->B, s->T, s->D, s->num_blocks);
       return backward_generic_ws_bytes(s->B, s->T, s->D, s->num_blocks);
     case RGLRU_OP_SCAN:
       if (s->act_dtype == RGLRU_BF16 && s->D % 256 == 0 && s->T >= 1)
@@ -307,6 +315,9 @@ int rglru_workspace_status(const rglru_shape *shape, int op, const void *workspa
       off = backward_mfma_flag_offset(shape->B, shape->T, shape->D, shape->num_blocks);
     else if (backward_via_padding(shape))
       off = backward_padded_flag_offset(shape->B, shape->T, shape->D, shape->num_blocks);
+    else if (backward_in_passes(shape) &&
+             (off = backward_wide_flag_offset(shape->B, shape->T, shape->D, shape->num_blocks)) != 0)
+      ;                             // only the adjoint scan of that path waits
     else
       return RGLRU_OK;              // the generic kernels do not wait on each other
     if (op == RGLRU_OP_BACKWARD_MERGE) off += merge_dy_bytes(shape);
@@ -450,6 +461,9 @@ int rglru_backward(const rglru_shape *shape, const rglru_params *params, const v
     e = launch_backward_mfma(q, (hipStream_t)stream);
   } else if (backward_padded_supported(q, bf)) {
     e = launch_backward_padded(q, (hipStream_t)stream);
+  } else if (backward_wide_supported(q, bf) &&
+             workspace_bytes >= backward_wide_ws_bytes(shape->B, shape->T, shape->D, shape->num_blocks)) {
+    e = launch_backward_wide(q, (hipStream_t)stream);
   } else {
     // pointers too loosely aligned for the MFMA kernels: the generic kernels need more scratch
     CHECK(check_workspace(workspace, workspace_bytes,

@@ -495,7 +495,7 @@ hipError_t launch_decode_generic(const Problem &p, bool bf, hipStream_t s) {
 }
 
 template <typename AT>
-static hipError_t backward_generic_t(const Problem &p, hipStream_t s) {
+static hipError_t backward_generic_t(const Problem &p, hipStream_t s, bool with_pointwise = true) {
   const BwdWs w = carve_bwd_ws(p.ws, p.B, p.T, p.D);
   const size_t lds = generic_lds_bytes(p.bs);
   hipError_t e = allow_lds(bwd_pointwise_kernel<AT>, lds);
@@ -505,8 +505,10 @@ static hipError_t backward_generic_t(const Problem &p, hipStream_t s) {
   const size_t n = (size_t)p.B * p.T * p.D;
   const int dblocks = (p.D + NTHREADS - 1) / NTHREADS;
 
-  hipLaunchKernelGGL(bwd_pointwise_kernel<AT>, dim3(p.nb, p.B), dim3(NTHREADS), lds, s, p, w);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (with_pointwise) {
+    hipLaunchKernelGGL(bwd_pointwise_kernel<AT>, dim3(p.nb, p.B), dim3(NTHREADS), lds, s, p, w);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   const RowOuts gate_outs = {{p.g.db_a, p.g.db_x, p.g.dLambda, nullptr, nullptr}};
   hipLaunchKernelGGL(reduce_parts_kernel, dim3(dblocks, 3), dim3(NTHREADS), 0, s, w.partA, p.B, 3,
                      p.D, gate_outs);
@@ -533,6 +535,16 @@ static hipError_t backward_generic_t(const Problem &p, hipStream_t s) {
 
 hipError_t launch_backward_generic(const Problem &p, bool bf, hipStream_t s) {
   return bf ? backward_generic_t<bf16>(p, s) : backward_generic_t<float>(p, s);
+}
+
+// everything after the pointwise pass: the caller has filled x, dp, dq, dx and partA itself
+hipError_t launch_backward_generic_tail(const Problem &p, bool bf, hipStream_t s) {
+  return bf ? backward_generic_t<bf16>(p, s, false) : backward_generic_t<float>(p, s, false);
+}
+
+void backward_generic_arrays(const Problem &p, float **x, float **dp, float **dq, float **dx, float **partA) {
+  const BwdWs w = carve_bwd_ws(p.ws, p.B, p.T, p.D);
+  *x = w.x; *dp = w.dp; *dq = w.dq; *dx = w.dx; *partA = w.partA;
 }
 
 }  // namespace rglru

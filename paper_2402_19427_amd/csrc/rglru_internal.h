@@ -63,6 +63,8 @@ struct Problem {
 // internal scan flag (never accepted from the C ABI): g is stored in IEEE half precision; goes
 // with RGLRU_SCAN_LOG_A | RGLRU_SCAN_NO_INPUT_SCALE and the tiled kernel only
 constexpr unsigned SCAN_G_FP16 = 0x100u;
+// internal: the adjoint scan writes delta in IEEE half precision (tiled kernel, log-decay form)
+constexpr unsigned SCAN_OUT_FP16 = 0x200u;
 
 // One rglru_scan call.
 struct ScanProblem {
@@ -92,6 +94,8 @@ hipError_t launch_forward_generic(const Problem &p, bool bf, hipStream_t s);
 hipError_t launch_decode_generic(const Problem &p, bool bf, hipStream_t s);
 hipError_t launch_backward_generic(const Problem &p, bool bf, hipStream_t s);
 size_t backward_generic_ws_bytes(int B, int T, int D, int nb);
+hipError_t launch_backward_generic_tail(const Problem &p, bool bf, hipStream_t s);   // without the pointwise pass
+void backward_generic_arrays(const Problem &p, float **x, float **dp, float **dq, float **dx, float **partA);
 size_t generic_lds_bytes(int bs);
 
 // MFMA forward (bf16 storage, gate blocks of 256)
@@ -107,6 +111,10 @@ bool forward_wide_block(int bs);
 bool forward_wide_supported(const Problem &p, bool bf);
 size_t forward_wide_ws_bytes(int B, int T, int D, int nb);
 hipError_t launch_forward_wide(const Problem &p, hipStream_t s);
+bool backward_wide_supported(const Problem &p, bool bf);
+size_t backward_wide_ws_bytes(int B, int T, int D, int nb);
+size_t backward_wide_flag_offset(int B, int T, int D, int nb);
+hipError_t launch_backward_wide(const Problem &p, hipStream_t s);
 bool decode_wide_supported(const Problem &p, bool bf);
 hipError_t launch_decode_wide(const Problem &p, hipStream_t s);
 

@@ -254,7 +254,16 @@ scan_tiled_kernel(ScanArgs a) {
       const float h0v = fmaf(ha[P][4 * q], hrun, hb[P][4 * q]), h1v = fmaf(ha[P][4 * q + 1], h0v, hb[P][4 * q + 1]);
       const float h2v = fmaf(ha[P][4 * q + 2], h1v, hb[P][4 * q + 2]), h3v = fmaf(ha[P][4 * q + 3], h2v, hb[P][4 * q + 3]);
       hrun = h3v;
-      const unsigned p0 = pack_bf16(h0v, h1v), p1 = pack_bf16(h2v, h3v);
+      unsigned p0, p1;
+      if (REV && (p.flags & SCAN_OUT_FP16)) {   // the library's own intermediate: half precision
+        typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+        const f16x2 q0 = {(_Float16)h0v, (_Float16)h1v}, q1 = {(_Float16)h2v, (_Float16)h3v};
+        p0 = *(const unsigned *)&q0;
+        p1 = *(const unsigned *)&q1;
+      } else {
+        p0 = pack_bf16(h0v, h1v);
+        p1 = pack_bf16(h2v, h3v);
+      }
       unsigned short *o = ot_mine + (4 * q) * OT;
       o[0] = (unsigned short)(p0 & 0xffff);
       o[OT] = (unsigned short)(p0 >> 16);

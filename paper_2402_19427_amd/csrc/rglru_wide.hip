@@ -39,10 +39,14 @@ struct WideArgs {
   const unsigned short *x;     // [M][D] Conv1D output, bf16: operand of the gate products
   const unsigned short *xh;    // [M][D] the same in half precision: the x_t of i_t x_t
   unsigned short *la, *gb;     // [M][D] log a_t (bf16), b_t (half precision)
+  unsigned short *rv;          // backward only: [M][D] the recurrence gate r_t (half precision)
   int nob;                     // groups of 256 output channels per block = K chunks per block
   unsigned M;                  // B * T
 };
 
+// BWD: for the backward in passes the second result is the input gate i_t itself (half
+// precision) instead of b_t, and x_t is not needed here.
+template <bool BWD>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 gates_wide_kernel(WideArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -176,7 +180,7 @@ gates_wide_kernel(WideArgs a) {
   // ---- x_t of this workgroup's own channels, in half precision (bf16 is too coarse for the
   // i_t x_t term), through the x tile buffer into accumulator layout with the f16 form of the
   // selection product
-  {
+  if (!BWD) {
     const __amdgpu_buffer_rsrc_t xh_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         uniform_ptr(a.xh), 0, a.M * row_bytes, 0x00020000);
     const int col = ob * BS + lc * 8;
@@ -219,15 +223,16 @@ gates_wide_kernel(WideArgs a) {
   for (int mi = 0; mi < 2; ++mi) {
     const unsigned mrow = m0 + mi * 32;
     const int nrows = (int)a.M - (int)mrow;
-    float bv[16];
+    float bv[16], rr[BWD ? 16 : 1];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const float rg = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-LOG2E * accp[mi][r]));
+      if (BWD) rr[r] = rg;
       const float la = kdn * rg;
       const float av = __builtin_amdgcn_exp2f(LOG2E * la);
       const float mm = __builtin_amdgcn_sqrtf(fmaf(-av, av, 1.f));
       const float ig = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-LOG2E * accq[mi][r]));
-      bv[r] = mm * ig * accx[mi][r];
+      bv[r] = BWD ? ig : mm * ig * accx[mi][r];
       ot_mine[r * OT] = (unsigned short)(pack_bf16(la, 0.f) & 0xffff);
     }
     store_staged_tile_s<OT, 0>(otile, lane, la_rsrc, o_voff, mrow * row_bytes, row_bytes, nrows);
@@ -237,6 +242,16 @@ gates_wide_kernel(WideArgs a) {
       ot_mine[r * OT] = *(const unsigned short *)&hv;
     }
     store_staged_tile_s<OT, 0>(otile, lane, gb_rsrc, o_voff, mrow * row_bytes, row_bytes, nrows);
+    if (BWD) {   // r_t in half precision too: log a_t in bf16 is too coarse for the adjoints
+      const __amdgpu_buffer_rsrc_t rv_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+          uniform_ptr(a.rv), 0, a.M * row_bytes, 0x00020000);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const _Float16 hv = (_Float16)rr[r];
+        ot_mine[r * OT] = *(const unsigned short *)&hv;
+      }
+      store_staged_tile_s<OT, 0>(otile, lane, rv_rsrc, o_voff, mrow * row_bytes, row_bytes, nrows);
+    }
   }
 }
 
@@ -587,6 +602,67 @@ __global__ void __launch_bounds__(256) conv_rows_kernel(ConvArgs a) {
   }
 }
 
+// ---- backward in passes, pointwise part: with delta_t from the adjoint scan, log a_t and i_t
+// from the gates pass, x_t and h_{t-1}, the adjoints of eqs. (1)-(4) per element
+//   dL/d(log a_t) = delta_t a_t (h_{t-1} - a_t i_t x_t / m_t),   dL/d(i_t x_t) = delta_t m_t
+// (r_t, i_t from the gates pass: a_t = exp(-c softplus(-Lambda) r_t), m_t = sqrt(1 - a_t^2))
+// written as fp32 x, dp, dq and the direct part of dx where the contraction passes expect them,
+// plus the sums over a chunk of steps of dp, dq and of the Lambda term per (sequence, channel).
+constexpr int PT_STEPS = 128;   // steps per thread
+struct PointArgs {
+  Problem p;
+  const unsigned short *xh, *rv, *iv, *delta;   // x_t, r_t, i_t, delta_t in half precision, all [B][T][D]
+  float *x, *dp, *dq, *dx;                      // [B][T][D] fp32
+  float *part;                                  // [chunk][B][3][D]
+};
+__device__ __forceinline__ float half_bits(unsigned short v) { return (float)__builtin_bit_cast(_Float16, v); }
+
+__global__ void __launch_bounds__(256) point_adjoint_kernel(PointArgs a) {
+  const Problem &p = a.p;
+  const int d = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y, ch = blockIdx.z;
+  if (d >= p.D) return;
+  const int t0 = ch * PT_STEPS, t1 = min(t0 + PT_STEPS, p.T);
+  const float lam = p.Lambda[d];
+  const float z = -lam;
+  const float neg_cs = -p.c * (z > 0.f ? z + log1pf(expf(-z)) : log1pf(expf(z)));   // -c softplus(-Lambda)
+  const float lam_scale = p.c / (1.f + expf(lam));                                   // c sigmoid(-Lambda)
+  float s_ba = 0.f, s_bx = 0.f, s_lam = 0.f;
+  for (int t = t0; t < t1; ++t) {
+    const size_t o = ((size_t)b * p.T + t) * p.D + d;
+    const float r = half_bits(a.rv[o]), la = neg_cs * r;
+    const float av = expf(la), mv = sqrtf(-expm1f(2.f * la));
+    const float iv = half_bits(a.iv[o]), x = half_bits(a.xh[o]), delta = half_bits(a.delta[o]);
+    const float hprev = t > 0 ? bf_lo((unsigned)((const unsigned short *)p.y_in)[o - p.D])
+                              : (p.h0 ? p.h0[(size_t)b * p.D + d] : 0.f);
+    const float gin = iv * x;
+    const float corr = mv > 0.f ? av * gin / mv : 0.f;   // the term vanishes with the gate as m -> 0
+    const float dla = delta * av * (hprev - corr);
+    const float dg = delta * mv;
+    const float dpv = neg_cs * dla * r * (1.f - r);
+    const float dqv = dg * x * iv * (1.f - iv);
+    s_lam = fmaf(dla * r, lam_scale, s_lam);
+    s_ba += dpv;
+    s_bx += dqv;
+    a.x[o] = x;
+    a.dp[o] = dpv;
+    a.dq[o] = dqv;
+    a.dx[o] = dg * iv;
+  }
+  float *out = a.part + ((size_t)ch * p.B + b) * 3 * p.D + d;
+  out[0] = s_ba;
+  out[p.D] = s_bx;
+  out[2 * (size_t)p.D] = s_lam;
+}
+
+// partA[b][r][d] = sum over chunks, in a fixed order
+__global__ void __launch_bounds__(256) sum_chunks_kernel(const float *part, float *partA, int nch, size_t per_chunk) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= per_chunk) return;
+  float s = 0.f;
+  for (int c = 0; c < nch; ++c) s += part[(size_t)c * per_chunk + i];
+  partA[i] = s;
+}
+
 }  // namespace
 
 bool forward_wide_block(int bs) { return bs % 16 == 0 && bs >= 16 && !forward_mfma_block(bs); }
@@ -630,13 +706,15 @@ hipError_t launch_forward_wide(const Problem &p, hipStream_t s) {
   a.M = (unsigned)((size_t)p.B * p.T);
   static bool configured = false;
   if (!configured) {
-    e = hipFuncSetAttribute((const void *)gates_wide_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS);
+    e = hipFuncSetAttribute((const void *)gates_wide_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)gates_wide_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS);
     if (e != hipSuccess) return e;
     configured = true;
   }
   {
     KernelTimer kt("gates_wide_kernel", s);
-    hipLaunchKernelGGL(gates_wide_kernel, dim3((a.M + WM - 1) / WM, p.nb * a.nob), dim3(NTHR), W_LDS, s, a);
+    hipLaunchKernelGGL(gates_wide_kernel<false>, dim3((a.M + WM - 1) / WM, p.nb * a.nob), dim3(NTHR), W_LDS, s, a);
     e = hipGetLastError();
   }
   if (e != hipSuccess) return e;
@@ -655,6 +733,113 @@ hipError_t launch_forward_wide(const Problem &p, hipStream_t s) {
 }  // namespace rglru
 
 namespace rglru {
+
+// ---- backward for these block sizes: the pointwise pass of the generic kernels (sequential in
+// time, with the gate products on the vector unit: 80 % of their time) replaced by passes -
+// Conv1D rows, gate products on the matrix cores, the adjoint scan, the pointwise adjoints - that
+// leave x, dp, dq and the direct part of dx where the generic contraction passes expect them.
+namespace {
+struct BwdWidePlan {
+  size_t generic, n2, off_x, off_xh, off_la, off_iv, off_rv, off_delta, off_part, off_scan, total;
+  int nch;
+};
+BwdWidePlan plan_bwd_wide(int B, int T, int D, int nb) {
+  BwdWidePlan q;
+  q.generic = al256(backward_generic_ws_bytes(B, T, D, nb));
+  q.n2 = al256((size_t)B * T * D * 2);
+  q.nch = (T + PT_STEPS - 1) / PT_STEPS;
+  size_t off = q.generic;
+  q.off_x = off; off += q.n2;
+  q.off_xh = off; off += q.n2;
+  q.off_la = off; off += q.n2;
+  q.off_iv = off; off += q.n2;
+  q.off_rv = off; off += q.n2;
+  q.off_delta = off; off += q.n2;
+  q.off_part = off; off += al256((size_t)q.nch * B * 3 * D * 4);
+  q.off_scan = off; off += scan_tiled_ws_bytes(B, T, D);
+  q.total = off;
+  return q;
+}
+}  // namespace
+
+bool backward_wide_supported(const Problem &p, bool bf) {
+  const uintptr_t all = (uintptr_t)p.W_a | (uintptr_t)p.W_x | (uintptr_t)p.u | (uintptr_t)p.dy |
+                        (uintptr_t)p.state_in | (uintptr_t)p.conv_w | (uintptr_t)p.conv_b;
+  return bf && forward_wide_block(p.bs) && p.D % BS == 0 && p.T >= 1 && all % 16 == 0 &&
+         (size_t)p.B * p.T * p.D * 2 < ((size_t)1 << 31) && (p.T + PT_STEPS - 1) / PT_STEPS <= 65535 &&
+         p.B <= 65535;
+}
+
+size_t backward_wide_ws_bytes(int B, int T, int D, int nb) { return plan_bwd_wide(B, T, D, nb).total; }
+
+size_t backward_wide_flag_offset(int B, int T, int D, int nb) {   // 0 if the scan does not slice
+  return scan_tiled_ws_bytes(B, T, D) ? plan_bwd_wide(B, T, D, nb).off_scan : 0;
+}
+
+hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
+  const BwdWidePlan q = plan_bwd_wide(p.B, p.T, p.D, p.nb);
+  char *ws = (char *)p.ws;
+  hipError_t e;
+  {
+    KernelTimer kt("conv_rows_kernel", s);
+    ConvArgs c;
+    c.p = p;
+    c.x = (unsigned short *)(ws + q.off_x);
+    c.xh = (unsigned short *)(ws + q.off_xh);
+    const size_t total = (size_t)p.B * ((p.T + CR - 1) / CR) * (p.D / 8);
+    hipLaunchKernelGGL(conv_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, c);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  WideArgs a;
+  a.p = p;
+  a.x = (const unsigned short *)(ws + q.off_x);
+  a.xh = (const unsigned short *)(ws + q.off_xh);
+  a.la = (unsigned short *)(ws + q.off_la);
+  a.gb = (unsigned short *)(ws + q.off_iv);
+  a.rv = (unsigned short *)(ws + q.off_rv);
+  a.nob = (p.bs + BS - 1) / BS;
+  a.M = (unsigned)((size_t)p.B * p.T);
+  static bool configured = false;
+  if (!configured) {
+    e = hipFuncSetAttribute((const void *)gates_wide_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  {
+    KernelTimer kt("gates_wide_kernel", s);
+    hipLaunchKernelGGL(gates_wide_kernel<true>, dim3((a.M + WM - 1) / WM, p.nb * a.nob), dim3(NTHR), W_LDS, s, a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  // delta_t = dy_t + a_{t+1} delta_{t+1}; its last value times a_0 is dh0
+  ScanProblem sp;
+  sp.B = p.B; sp.T = p.T; sp.D = p.D;
+  sp.flags = RGLRU_SCAN_LOG_A | RGLRU_SCAN_NO_INPUT_SCALE | RGLRU_SCAN_ADJOINT | SCAN_OUT_FP16;
+  sp.a = ws + q.off_la; sp.g = p.dy; sp.h0 = p.dhT; sp.h = ws + q.off_delta; sp.hT = p.dh0;
+  sp.ws = ws + q.off_scan;
+  sp.ws_bytes = q.total - q.off_scan;
+  if (!scan_tiled_supported(sp, true)) return hipErrorInvalidValue;
+  if ((e = launch_scan_tiled(sp, s)) != hipSuccess) return e;
+  {
+    KernelTimer kt("point_adjoint_kernel", s);
+    PointArgs pa;
+    pa.p = p;
+    pa.xh = (const unsigned short *)(ws + q.off_xh);
+    pa.rv = (const unsigned short *)(ws + q.off_rv);
+    pa.iv = (const unsigned short *)(ws + q.off_iv);
+    pa.delta = (const unsigned short *)(ws + q.off_delta);
+    float *gx, *gdp, *gdq, *gdx, *gpartA;
+    backward_generic_arrays(p, &gx, &gdp, &gdq, &gdx, &gpartA);
+    pa.x = gx; pa.dp = gdp; pa.dq = gdq; pa.dx = gdx;
+    pa.part = (float *)(ws + q.off_part);
+    hipLaunchKernelGGL(point_adjoint_kernel, dim3((p.D + 255) / 256, p.B, q.nch), dim3(256), 0, s, pa);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const size_t per_chunk = (size_t)p.B * 3 * p.D;
+    hipLaunchKernelGGL(sum_chunks_kernel, dim3((unsigned)((per_chunk + 255) / 256)), dim3(256), 0, s,
+                       (const float *)(ws + q.off_part), gpartA, q.nch, per_chunk);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  return launch_backward_generic_tail(p, true, s);
+}
 
 bool decode_wide_supported(const Problem &p, bool bf) {
   const uintptr_t all = (uintptr_t)p.W_a | (uintptr_t)p.W_x | (uintptr_t)p.u | (uintptr_t)p.state_out |

@@ -188,6 +188,9 @@ BWD_SHAPES = [
     (2, 33, 320, 2, "bf16"),      # bs = 160: the problem is widened to 256-channel blocks
     (3, 300, 2560, 16, "bf16"),   # the same at the paper's width, 16 blocks
     (1, 1100, 384, 2, "bf16"),    # bs = 192, long sequence in time slices
+    (2, 100, 2816, 8, "bf16"),    # bs = 352: pointwise part in passes, contractions on the generic kernels
+    (1, 700, 1024, 2, "bf16"),    # bs = 512, adjoint scan in time slices
+    (3, 70, 256, 4, "bf16"),      # bs = 64
     (1, 270, 600, 2, "bf16"),
     (1, 1, 256, 1, "bf16"),       # MFMA path, single step
     (2, 31, 256, 1, "bf16"),      # MFMA path, one partial tile
