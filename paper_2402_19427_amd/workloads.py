@@ -129,7 +129,8 @@ def run_sequence_workload(w, dev, out, label="forward"):
                          ws_b, n_b, sp)
 
     ms = time_calls(bwd, nsets, iters, 5)
-    out.append(row(w.name, "backward", note, ms, B * T, alg_bytes("backward", B, T, D, nb, act_b),
+    out.append(row(w.name, label.replace("forward", "backward"), note, ms, B * T,
+                   alg_bytes("backward", B, T, D, nb, act_b),
                    gate_flops("backward", B, T, D, nb)))
 
 
@@ -357,7 +358,7 @@ def main():
             # the larger widths of the model family, 352 and 512 channels per block: forward only
             # (separate passes on the matrix cores)
             for D in (5632, 8192):
-                run_sequence_workload(dataclasses.replace(c1, name="NB16", D=D, nb=16, kind="forward"),
+                run_sequence_workload(dataclasses.replace(c1, name="NB16", D=D, nb=16, kind="train"),
                                       dev, out, label="forward, width %d" % D)
                 run_decode_workload(dataclasses.replace(gen.CONFIGS["C3"], name="NB16", D=D), dev, out,
                                     graph_only=True, label="decode, width %d," % D)
