@@ -125,7 +125,7 @@ bool backward_via_padding(const rglru_shape *s) {
 // runs as passes on the tuned kernels (its workspace contains the generic kernels' own)
 bool backward_in_passes(const rglru_shape *s) {
   return s->act_dtype == RGLRU_BF16 && forward_wide_block(s->D / s->num_blocks) && s->D % 256 == 0 &&
-         s->T >= 1 && (size_t)s->B * s->T * s->D * 2 < ((size_t)1 << 31);
+         s->T >= 1 && (size_t)s->B * s->T * s->D * 4 < ((size_t)1 << 31);
 }
 
 size_t workspace_need(const rglru_shape *s, int op);

@@ -495,7 +495,8 @@ hipError_t launch_decode_generic(const Problem &p, bool bf, hipStream_t s) {
 }
 
 template <typename AT>
-static hipError_t backward_generic_t(const Problem &p, hipStream_t s, bool with_pointwise = true) {
+static hipError_t backward_generic_t(const Problem &p, hipStream_t s, bool with_pointwise = true,
+                                     bool with_dgrad = true) {
   const BwdWs w = carve_bwd_ws(p.ws, p.B, p.T, p.D);
   const size_t lds = generic_lds_bytes(p.bs);
   hipError_t e = allow_lds(bwd_pointwise_kernel<AT>, lds);
@@ -516,8 +517,10 @@ static hipError_t backward_generic_t(const Problem &p, hipStream_t s, bool with_
   // dgrad: time tiles in gridDim.z (<= 65535), sequences in y
   const int ntile = (p.T + GT - 1) / GT;
   if (ntile > 65535 || p.B > 65535) return hipErrorInvalidConfiguration;
-  hipLaunchKernelGGL(bwd_dgrad_kernel<AT>, dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds, s, p, w);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (with_dgrad) {
+    hipLaunchKernelGGL(bwd_dgrad_kernel<AT>, dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds, s, p, w);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   hipLaunchKernelGGL(bwd_conv_input_kernel<AT>, dim3(grid_1d(n)), dim3(NTHREADS), 0, s, p, w);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (w.nchunk > 65535) return hipErrorInvalidConfiguration;
@@ -538,8 +541,8 @@ hipError_t launch_backward_generic(const Problem &p, bool bf, hipStream_t s) {
 }
 
 // everything after the pointwise pass: the caller has filled x, dp, dq, dx and partA itself
-hipError_t launch_backward_generic_tail(const Problem &p, bool bf, hipStream_t s) {
-  return bf ? backward_generic_t<bf16>(p, s, false) : backward_generic_t<float>(p, s, false);
+hipError_t launch_backward_generic_tail(const Problem &p, bool bf, hipStream_t s, bool with_dgrad) {
+  return bf ? backward_generic_t<bf16>(p, s, false, with_dgrad) : backward_generic_t<float>(p, s, false, with_dgrad);
 }
 
 void backward_generic_arrays(const Problem &p, float **x, float **dp, float **dq, float **dx, float **partA) {

@@ -40,15 +40,24 @@ struct WideArgs {
   const unsigned short *xh;    // [M][D] the same in half precision: the x_t of i_t x_t
   unsigned short *la, *gb;     // [M][D] log a_t (bf16), b_t (half precision)
   unsigned short *rv;          // backward only: [M][D] the recurrence gate r_t (half precision)
-  int nob;                     // groups of 256 output channels per block = K chunks per block
+  int nob;                     // groups of 256 output channels per block
+  int nkc;                     // chunks of 256 input channels (K) per block
+  int kdim;                    // input channels per block: bs, or 2 bs for the dgrad product
+  unsigned x_row_bytes;        // bytes of a row of x
+  float *dx;                   // dgrad: [M][D] fp32, accumulated into
   unsigned M;                  // B * T
 };
+constexpr int MODE_FWD = 0, MODE_BWD = 1, MODE_DGRAD = 2;
 
-// BWD: for the backward in passes the second result is the input gate i_t itself (half
-// precision) instead of b_t, and x_t is not needed here.
-template <bool BWD>
+// MODE_BWD: for the backward in passes the second result is the input gate i_t itself (half
+// precision) instead of b_t, plus r_t, and x_t is not needed here.
+// MODE_DGRAD: the same product machinery as the plain matrix pass dx += [dp | dq] [W_a | W_x]^T:
+// "x" holds dp and dq of a block side by side (K = 2 bs), the weights are the transposed gate
+// matrices side by side, one accumulator, and the result is added to the fp32 dx.
+template <int MODE>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 gates_wide_kernel(WideArgs a) {
+  constexpr bool BWD = MODE == MODE_BWD, DG = MODE == MODE_DGRAD;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned short *xs = (unsigned short *)smem;                     // [2][WM][XS]
   const Problem &p = a.p;
@@ -58,16 +67,17 @@ gates_wide_kernel(WideArgs a) {
   const int D = p.D, bs = p.bs;
   const int g = blockIdx.y / a.nob, ob = blockIdx.y - g * a.nob;
   const unsigned m0 = blockIdx.x * WM;
-  const unsigned row_bytes = (unsigned)D * 2;
+  const unsigned row_bytes = (unsigned)D * 2, xrow = a.x_row_bytes;
+  const int kdim = a.kdim;
 
   // this lane's output channel; a channel past the block is computed from an existing one's
   // parameters and never stored
   const int och = ob * BS + wv * 32 + j;
   const int ochc = och < bs ? och : bs - 1;
   const int d = g * bs + ochc;
-  const float bias_p = p.b_a[d], bias_q = p.b_x[d];
-  float kdn;  // -c * softplus(-Lambda) = log of the fully open decay, eq. (3)
-  {
+  const float bias_p = DG ? 0.f : p.b_a[d], bias_q = DG ? 0.f : p.b_x[d];
+  float kdn = 0.f;  // -c * softplus(-Lambda) = log of the fully open decay, eq. (3)
+  if (!DG) {
     const float z = -p.Lambda[d];
     const float sp = z > 0.f ? z + log1pf(expf(-z)) : log1pf(expf(z));
     kdn = -p.c * sp;
@@ -77,13 +87,13 @@ gates_wide_kernel(WideArgs a) {
   // row, 4 K-steps of both gates per phase) and turns them into fragment order through its own
   // LDS buffers. Rows and columns past the block are read from existing ones (they end in
   // outputs that are dropped, or meet zeros in x).
-  const unsigned char *wbase_a = (const unsigned char *)p.W_a + (size_t)g * bs * bs * 2;
-  const unsigned char *wbase_x = (const unsigned char *)p.W_x + (size_t)g * bs * bs * 2;
+  const unsigned char *wbase_a = (const unsigned char *)p.W_a + (size_t)g * bs * kdim * 2;
+  const unsigned char *wbase_x = (const unsigned char *)p.W_x + (size_t)g * bs * kdim * 2;
   unsigned w_row[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int r = ob * BS + wv * 32 + i * 8 + (lane >> 3);
-    w_row[i] = (unsigned)(r < bs ? r : bs - 1) * (unsigned)(bs * 2);
+    w_row[i] = (unsigned)(r < bs ? r : bs - 1) * (unsigned)(kdim * 2);
   }
   unsigned char *wl = smem + W_OFF_W + wv * 2 * W_WPH;
   const unsigned wl_wr = (unsigned)(lane >> 3) * W_WROW + (unsigned)(lane & 7) * 16;
@@ -91,11 +101,11 @@ gates_wide_kernel(WideArgs a) {
   u32x4 stg[2][8];
   auto load_phase = [&](int P, u32x4 (&dst)[8]) __attribute__((always_inline)) {   // phase P: K-steps 4P .. 4P+3 of the block
     const int c = P * 8 + (lane & 7);   // 16-byte chunk of the row
-    const unsigned w_col = (unsigned)(c < (bs >> 3) ? c : (bs >> 3) - 1) * 16;
+    const unsigned w_col = (unsigned)(c < (kdim >> 3) ? c : (kdim >> 3) - 1) * 16;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       dst[i] = *(const u32x4 *)(wbase_a + w_row[i] + w_col);
-      dst[4 + i] = *(const u32x4 *)(wbase_x + w_row[i] + w_col);
+      if (!DG) dst[4 + i] = *(const u32x4 *)(wbase_x + w_row[i] + w_col);
     }
   };
   auto write_phase = [&](const u32x4 (&src)[8]) __attribute__((always_inline)) {
@@ -108,7 +118,7 @@ gates_wide_kernel(WideArgs a) {
 
   // ---- x tile loader: thread -> 16 bytes (8 channels) of rows r0, r0 + 16, r0 + 32, r0 + 48
   const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      uniform_ptr(a.x), 0, a.M * row_bytes, 0x00020000);
+      uniform_ptr(a.x), 0, a.M * xrow, 0x00020000);
   const int lc = tid & 31, r0 = tid >> 5;
   u32x4 nx[4];
   auto load_chunk = [&](int kc) __attribute__((always_inline)) {   // chunk kc of the block's input channels
@@ -116,9 +126,9 @@ gates_wide_kernel(WideArgs a) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const unsigned m = m0 + r0 + 16 * i;
-      const bool ok = m < a.M && col < bs;   // (kc past the last chunk: col >= bs)
+      const bool ok = m < a.M && col < kdim;   // (kc past the last chunk: col >= kdim)
       nx[i] = __builtin_amdgcn_raw_buffer_load_b128(
-          x_rsrc, ok ? m * row_bytes + (unsigned)(g * bs + col) * 2 : OOB, 0, 0);
+          x_rsrc, ok ? m * xrow + (unsigned)(g * kdim + col) * 2 : OOB, 0, 0);
     }
   };
   auto park_chunk = [&](int buf) __attribute__((always_inline)) {
@@ -144,7 +154,7 @@ gates_wide_kernel(WideArgs a) {
   write_phase(stg[0]);
   __syncthreads();
 
-  for (int kc = 0; kc < a.nob; ++kc) {
+  for (int kc = 0; kc < a.nkc; ++kc) {
     const int buf = kc & 1;
     load_chunk(kc + 1);   // lands during the products (nothing is read past the last chunk)
     const unsigned short *ap = xs + buf * W_XT + arow * XS + hf * 8;
@@ -159,7 +169,7 @@ gates_wide_kernel(WideArgs a) {
 #pragma unroll
       for (int k2 = 0; k2 < 4; ++k2) {
         fa[k2] = *(const bf16x8 *)(wl + wl_rd + k2 * 32);
-        fx[k2] = *(const bf16x8 *)(wl + W_WPH + wl_rd + k2 * 32);
+        if (!DG) fx[k2] = *(const bf16x8 *)(wl + W_WPH + wl_rd + k2 * 32);
       }
       wave_lds_fence();
       write_phase(stg[(ph + 1) & 1]);   // LDS serves a wave's accesses in order: queued behind the reads
@@ -168,9 +178,9 @@ gates_wide_kernel(WideArgs a) {
         const int ks = ph * 4 + k2;
         const bf16x8 a0 = *(const bf16x8 *)(ap + ks * 16), a1 = *(const bf16x8 *)(ap + 32 * XS + ks * 16);
         accp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, fa[k2], accp[0], 0, 0, 0);
-        accq[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, fx[k2], accq[0], 0, 0, 0);
+        if (!DG) accq[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, fx[k2], accq[0], 0, 0, 0);
         accp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, fa[k2], accp[1], 0, 0, 0);
-        accq[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, fx[k2], accq[1], 0, 0, 0);
+        if (!DG) accq[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, fx[k2], accq[1], 0, 0, 0);
       }
     }
     park_chunk(buf ^ 1);
@@ -180,7 +190,7 @@ gates_wide_kernel(WideArgs a) {
   // ---- x_t of this workgroup's own channels, in half precision (bf16 is too coarse for the
   // i_t x_t term), through the x tile buffer into accumulator layout with the f16 form of the
   // selection product
-  if (!BWD) {
+  if (MODE == MODE_FWD) {
     const __amdgpu_buffer_rsrc_t xh_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         uniform_ptr(a.xh), 0, a.M * row_bytes, 0x00020000);
     const int col = ob * BS + lc * 8;
@@ -209,6 +219,18 @@ gates_wide_kernel(WideArgs a) {
     }
   }
 
+  if (DG) {   // dx += the products: lane (j, hf) holds channel och of rows 16 hf .. 16 hf + 15
+    if (och < bs) {
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const unsigned m = m0 + mi * 32 + hf * 16 + r;
+          if (m < a.M) a.dx[(size_t)m * D + g * bs + och] += accp[mi][r];
+        }
+    }
+    return;
+  }
   // ---- eqs. (1)-(3) per element; the two results leave through the wave's staging tile as
   // 16-byte rows
   const __amdgpu_buffer_rsrc_t la_rsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -614,6 +636,7 @@ struct PointArgs {
   const unsigned short *xh, *rv, *iv, *delta;   // x_t, r_t, i_t, delta_t in half precision, all [B][T][D]
   float *x, *dp, *dq, *dx;                      // [B][T][D] fp32
   float *part;                                  // [chunk][B][3][D]
+  unsigned short *dpq;                          // [B][T][nb][2][bs] bf16: dp and dq of a block side by side
 };
 __device__ __forceinline__ float half_bits(unsigned short v) { return (float)__builtin_bit_cast(_Float16, v); }
 
@@ -627,6 +650,7 @@ __global__ void __launch_bounds__(256) point_adjoint_kernel(PointArgs a) {
   const float neg_cs = -p.c * (z > 0.f ? z + log1pf(expf(-z)) : log1pf(expf(z)));   // -c softplus(-Lambda)
   const float lam_scale = p.c / (1.f + expf(lam));                                   // c sigmoid(-Lambda)
   float s_ba = 0.f, s_bx = 0.f, s_lam = 0.f;
+  const int gb_ = d / p.bs, cb_ = d - gb_ * p.bs;
   for (int t = t0; t < t1; ++t) {
     const size_t o = ((size_t)b * p.T + t) * p.D + d;
     const float r = half_bits(a.rv[o]), la = neg_cs * r;
@@ -647,11 +671,29 @@ __global__ void __launch_bounds__(256) point_adjoint_kernel(PointArgs a) {
     a.dp[o] = dpv;
     a.dq[o] = dqv;
     a.dx[o] = dg * iv;
+    {
+      const size_t oq = (((size_t)b * p.T + t) * p.nb + gb_) * 2 * p.bs + cb_;
+      a.dpq[oq] = (unsigned short)(pack_bf16(dpv, 0.f) & 0xffff);
+      a.dpq[oq + p.bs] = (unsigned short)(pack_bf16(dqv, 0.f) & 0xffff);
+    }
   }
   float *out = a.part + ((size_t)ch * p.B + b) * 3 * p.D + d;
   out[0] = s_ba;
   out[p.D] = s_bx;
   out[2 * (size_t)p.D] = s_lam;
+}
+
+// W'[g][k][gate * bs + j] = W_gate[g][j][k]: the transposed gate matrices of a block side by side
+__global__ void __launch_bounds__(256) wt_concat_kernel(const unsigned short *Wa, const unsigned short *Wx,
+                                                        unsigned short *out, int nb, int bs) {
+  const size_t total = (size_t)nb * bs * 2 * bs;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int jj = (int)(i % (2 * bs));
+  const int k = (int)((i / (2 * bs)) % bs);
+  const int g = (int)(i / ((size_t)2 * bs * bs));
+  const int gate = jj >= bs, j = jj - gate * bs;
+  out[i] = (gate ? Wx : Wa)[((size_t)g * bs + j) * bs + k];
 }
 
 // partA[b][r][d] = sum over chunks, in a fixed order
@@ -703,18 +745,22 @@ hipError_t launch_forward_wide(const Problem &p, hipStream_t s) {
   a.la = (unsigned short *)la;
   a.gb = (unsigned short *)gb;
   a.nob = (p.bs + BS - 1) / BS;
+  a.nkc = a.nob;
+  a.kdim = p.bs;
+  a.x_row_bytes = (unsigned)p.D * 2;
+  a.dx = nullptr;
   a.M = (unsigned)((size_t)p.B * p.T);
   static bool configured = false;
   if (!configured) {
-    e = hipFuncSetAttribute((const void *)gates_wide_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS);
+    e = hipFuncSetAttribute((const void *)gates_wide_kernel<MODE_FWD>, hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)gates_wide_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS);
+    e = hipFuncSetAttribute((const void *)gates_wide_kernel<MODE_BWD>, hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS);
     if (e != hipSuccess) return e;
     configured = true;
   }
   {
     KernelTimer kt("gates_wide_kernel", s);
-    hipLaunchKernelGGL(gates_wide_kernel<false>, dim3((a.M + WM - 1) / WM, p.nb * a.nob), dim3(NTHR), W_LDS, s, a);
+    hipLaunchKernelGGL(gates_wide_kernel<MODE_FWD>, dim3((a.M + WM - 1) / WM, p.nb * a.nob), dim3(NTHR), W_LDS, s, a);
     e = hipGetLastError();
   }
   if (e != hipSuccess) return e;
@@ -740,7 +786,7 @@ namespace rglru {
 // leave x, dp, dq and the direct part of dx where the generic contraction passes expect them.
 namespace {
 struct BwdWidePlan {
-  size_t generic, n2, off_x, off_xh, off_la, off_iv, off_rv, off_delta, off_part, off_scan, total;
+  size_t generic, n2, off_x, off_xh, off_la, off_iv, off_rv, off_delta, off_part, off_dpq, off_wt, off_scan, total;
   int nch;
 };
 BwdWidePlan plan_bwd_wide(int B, int T, int D, int nb) {
@@ -756,6 +802,8 @@ BwdWidePlan plan_bwd_wide(int B, int T, int D, int nb) {
   q.off_rv = off; off += q.n2;
   q.off_delta = off; off += q.n2;
   q.off_part = off; off += al256((size_t)q.nch * B * 3 * D * 4);
+  q.off_dpq = off; off += 2 * q.n2;
+  q.off_wt = off; off += al256((size_t)nb * (D / nb) * 2 * (D / nb) * 2);
   q.off_scan = off; off += scan_tiled_ws_bytes(B, T, D);
   q.total = off;
   return q;
@@ -766,7 +814,7 @@ bool backward_wide_supported(const Problem &p, bool bf) {
   const uintptr_t all = (uintptr_t)p.W_a | (uintptr_t)p.W_x | (uintptr_t)p.u | (uintptr_t)p.dy |
                         (uintptr_t)p.state_in | (uintptr_t)p.conv_w | (uintptr_t)p.conv_b;
   return bf && forward_wide_block(p.bs) && p.D % BS == 0 && p.T >= 1 && all % 16 == 0 &&
-         (size_t)p.B * p.T * p.D * 2 < ((size_t)1 << 31) && (p.T + PT_STEPS - 1) / PT_STEPS <= 65535 &&
+         (size_t)p.B * p.T * p.D * 4 < ((size_t)1 << 31) && (p.T + PT_STEPS - 1) / PT_STEPS <= 65535 &&
          p.B <= 65535;
 }
 
@@ -798,16 +846,20 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
   a.gb = (unsigned short *)(ws + q.off_iv);
   a.rv = (unsigned short *)(ws + q.off_rv);
   a.nob = (p.bs + BS - 1) / BS;
+  a.nkc = a.nob;
+  a.kdim = p.bs;
+  a.x_row_bytes = (unsigned)p.D * 2;
+  a.dx = nullptr;
   a.M = (unsigned)((size_t)p.B * p.T);
   static bool configured = false;
   if (!configured) {
-    e = hipFuncSetAttribute((const void *)gates_wide_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS);
+    e = hipFuncSetAttribute((const void *)gates_wide_kernel<MODE_BWD>, hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS);
     if (e != hipSuccess) return e;
     configured = true;
   }
   {
     KernelTimer kt("gates_wide_kernel", s);
-    hipLaunchKernelGGL(gates_wide_kernel<true>, dim3((a.M + WM - 1) / WM, p.nb * a.nob), dim3(NTHR), W_LDS, s, a);
+    hipLaunchKernelGGL(gates_wide_kernel<MODE_BWD>, dim3((a.M + WM - 1) / WM, p.nb * a.nob), dim3(NTHR), W_LDS, s, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   // delta_t = dy_t + a_{t+1} delta_{t+1}; its last value times a_0 is dh0
@@ -831,6 +883,7 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
     backward_generic_arrays(p, &gx, &gdp, &gdq, &gdx, &gpartA);
     pa.x = gx; pa.dp = gdp; pa.dq = gdq; pa.dx = gdx;
     pa.part = (float *)(ws + q.off_part);
+    pa.dpq = (unsigned short *)(ws + q.off_dpq);
     hipLaunchKernelGGL(point_adjoint_kernel, dim3((p.D + 255) / 256, p.B, q.nch), dim3(256), 0, s, pa);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     const size_t per_chunk = (size_t)p.B * 3 * p.D;
@@ -838,7 +891,41 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
                        (const float *)(ws + q.off_part), gpartA, q.nch, per_chunk);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  return launch_backward_generic_tail(p, true, s);
+  // dx += [dp | dq] [W_a | W_x]^T on the matrix cores (the product machinery of the gates pass)
+  {
+    KernelTimer kt("wt_concat_kernel", s);
+    const size_t total = (size_t)p.nb * p.bs * 2 * p.bs;
+    hipLaunchKernelGGL(wt_concat_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                       (const unsigned short *)p.W_a, (const unsigned short *)p.W_x,
+                       (unsigned short *)(ws + q.off_wt), p.nb, p.bs);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  {
+    WideArgs dg;
+    dg.p = p;
+    dg.p.W_a = ws + q.off_wt;
+    dg.p.W_x = ws + q.off_wt;
+    dg.x = (const unsigned short *)(ws + q.off_dpq);
+    dg.xh = nullptr; dg.la = dg.gb = dg.rv = nullptr;
+    dg.nob = (p.bs + BS - 1) / BS;
+    dg.kdim = 2 * p.bs;
+    dg.nkc = (dg.kdim + BS - 1) / BS;
+    dg.x_row_bytes = (unsigned)p.D * 4;
+    dg.M = (unsigned)((size_t)p.B * p.T);
+    float *gx, *gdp, *gdq, *gdx, *gpartA;
+    backward_generic_arrays(p, &gx, &gdp, &gdq, &gdx, &gpartA);
+    dg.dx = gdx;
+    static bool configured_dg = false;
+    if (!configured_dg) {
+      e = hipFuncSetAttribute((const void *)gates_wide_kernel<MODE_DGRAD>, hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS);
+      if (e != hipSuccess) return e;
+      configured_dg = true;
+    }
+    KernelTimer kt("dgrad_wide_kernel", s);
+    hipLaunchKernelGGL(gates_wide_kernel<MODE_DGRAD>, dim3((dg.M + WM - 1) / WM, p.nb * dg.nob), dim3(NTHR), W_LDS, s, dg);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  return launch_backward_generic_tail(p, true, s, false);
 }
 
 bool decode_wide_supported(const Problem &p, bool bf) {
