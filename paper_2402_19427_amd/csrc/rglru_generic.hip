@@ -496,7 +496,7 @@ hipError_t launch_decode_generic(const Problem &p, bool bf, hipStream_t s) {
 
 template <typename AT>
 static hipError_t backward_generic_t(const Problem &p, hipStream_t s, bool with_pointwise = true,
-                                     bool with_dgrad = true) {
+                                     bool with_dgrad = true, bool with_wgrad = true) {
   const BwdWs w = carve_bwd_ws(p.ws, p.B, p.T, p.D);
   const size_t lds = generic_lds_bytes(p.bs);
   hipError_t e = allow_lds(bwd_pointwise_kernel<AT>, lds);
@@ -531,6 +531,7 @@ static hipError_t backward_generic_t(const Problem &p, hipStream_t s, bool with_
   hipLaunchKernelGGL(reduce_parts_kernel, dim3(dblocks, 5), dim3(NTHREADS), 0, s, w.partC, w.nchunk,
                      5, p.D, conv_outs);
   if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (!with_wgrad) return hipSuccess;
   const int tiles = (p.bs + 31) / 32;
   hipLaunchKernelGGL(bwd_wgrad_kernel, dim3(p.nb, tiles, tiles), dim3(NTHREADS), 0, s, p, w);
   return hipGetLastError();
@@ -541,8 +542,9 @@ hipError_t launch_backward_generic(const Problem &p, bool bf, hipStream_t s) {
 }
 
 // everything after the pointwise pass: the caller has filled x, dp, dq, dx and partA itself
-hipError_t launch_backward_generic_tail(const Problem &p, bool bf, hipStream_t s, bool with_dgrad) {
-  return bf ? backward_generic_t<bf16>(p, s, false, with_dgrad) : backward_generic_t<float>(p, s, false, with_dgrad);
+hipError_t launch_backward_generic_tail(const Problem &p, bool bf, hipStream_t s, bool with_dgrad, bool with_wgrad) {
+  return bf ? backward_generic_t<bf16>(p, s, false, with_dgrad, with_wgrad)
+            : backward_generic_t<float>(p, s, false, with_dgrad, with_wgrad);
 }
 
 void backward_generic_arrays(const Problem &p, float **x, float **dp, float **dq, float **dx, float **partA) {

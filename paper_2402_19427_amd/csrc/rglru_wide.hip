@@ -45,19 +45,27 @@ struct WideArgs {
   int kdim;                    // input channels per block: bs, or 2 bs for the dgrad product
   unsigned x_row_bytes;        // bytes of a row of x
   float *dx;                   // dgrad: [M][D] fp32, accumulated into
+  size_t w_block_elems;        // elements between the weight rows of consecutive blocks
+  float *dWa, *dWx;            // wgrad: [nb][bs][bs] fp32, written
   unsigned M;                  // B * T
 };
-constexpr int MODE_FWD = 0, MODE_BWD = 1, MODE_DGRAD = 2;
+constexpr int MODE_FWD = 0, MODE_BWD = 1, MODE_DGRAD = 2, MODE_WGRAD = 3;
 
 // MODE_BWD: for the backward in passes the second result is the input gate i_t itself (half
 // precision) instead of b_t, plus r_t, and x_t is not needed here.
 // MODE_DGRAD: the same product machinery as the plain matrix pass dx += [dp | dq] [W_a | W_x]^T:
 // "x" holds dp and dq of a block side by side (K = 2 bs), the weights are the transposed gate
 // matrices side by side, one accumulator, and the result is added to the fp32 dx.
+// MODE_WGRAD: dW[j][k] = sum over (sequence, step) of dp[.][j] x[.][k] with the roles turned: the
+// rows of "x" are the channels k of a block (x transposed, half precision, K = B T), the "weights"
+// are dp and dq transposed (rows j), the products run on the f16 form of the MFMA (x in bf16 is
+// too coarse for the weight gradients), and the accumulators are dW_a and dW_x themselves.
 template <int MODE>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 gates_wide_kernel(WideArgs a) {
-  constexpr bool BWD = MODE == MODE_BWD, DG = MODE == MODE_DGRAD;
+  constexpr bool BWD = MODE == MODE_BWD, WG = MODE == MODE_WGRAD;
+  constexpr bool DG = MODE == MODE_DGRAD;          // one product, no parameters
+  constexpr bool NOPAR = DG || WG;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned short *xs = (unsigned short *)smem;                     // [2][WM][XS]
   const Problem &p = a.p;
@@ -66,7 +74,9 @@ gates_wide_kernel(WideArgs a) {
   unsigned short *otile = (unsigned short *)(smem + W_OFF_OT) + wv * (OTILE_BYTES / 2);
   const int D = p.D, bs = p.bs;
   const int g = blockIdx.y / a.nob, ob = blockIdx.y - g * a.nob;
-  const unsigned m0 = blockIdx.x * WM;
+  // (wgrad: the row tiles lie inside block g's rows of the transposed x)
+  const unsigned m0 = WG ? (unsigned)(g * bs) + blockIdx.x * WM : blockIdx.x * WM;
+  const unsigned m_end = WG ? (unsigned)(g * bs + bs) : a.M;
   const unsigned row_bytes = (unsigned)D * 2, xrow = a.x_row_bytes;
   const int kdim = a.kdim;
 
@@ -75,9 +85,9 @@ gates_wide_kernel(WideArgs a) {
   const int och = ob * BS + wv * 32 + j;
   const int ochc = och < bs ? och : bs - 1;
   const int d = g * bs + ochc;
-  const float bias_p = DG ? 0.f : p.b_a[d], bias_q = DG ? 0.f : p.b_x[d];
+  const float bias_p = NOPAR ? 0.f : p.b_a[d], bias_q = NOPAR ? 0.f : p.b_x[d];
   float kdn = 0.f;  // -c * softplus(-Lambda) = log of the fully open decay, eq. (3)
-  if (!DG) {
+  if (!NOPAR) {
     const float z = -p.Lambda[d];
     const float sp = z > 0.f ? z + log1pf(expf(-z)) : log1pf(expf(z));
     kdn = -p.c * sp;
@@ -87,8 +97,8 @@ gates_wide_kernel(WideArgs a) {
   // row, 4 K-steps of both gates per phase) and turns them into fragment order through its own
   // LDS buffers. Rows and columns past the block are read from existing ones (they end in
   // outputs that are dropped, or meet zeros in x).
-  const unsigned char *wbase_a = (const unsigned char *)p.W_a + (size_t)g * bs * kdim * 2;
-  const unsigned char *wbase_x = (const unsigned char *)p.W_x + (size_t)g * bs * kdim * 2;
+  const unsigned char *wbase_a = (const unsigned char *)p.W_a + (size_t)g * a.w_block_elems * 2;
+  const unsigned char *wbase_x = (const unsigned char *)p.W_x + (size_t)g * a.w_block_elems * 2;
   unsigned w_row[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -118,7 +128,7 @@ gates_wide_kernel(WideArgs a) {
 
   // ---- x tile loader: thread -> 16 bytes (8 channels) of rows r0, r0 + 16, r0 + 32, r0 + 48
   const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      uniform_ptr(a.x), 0, a.M * xrow, 0x00020000);
+      uniform_ptr(a.x), 0, (WG ? (unsigned)p.D : a.M) * xrow, 0x00020000);
   const int lc = tid & 31, r0 = tid >> 5;
   u32x4 nx[4];
   auto load_chunk = [&](int kc) __attribute__((always_inline)) {   // chunk kc of the block's input channels
@@ -126,9 +136,9 @@ gates_wide_kernel(WideArgs a) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const unsigned m = m0 + r0 + 16 * i;
-      const bool ok = m < a.M && col < kdim;   // (kc past the last chunk: col >= kdim)
+      const bool ok = m < m_end && col < kdim;   // (kc past the last chunk: col >= kdim)
       nx[i] = __builtin_amdgcn_raw_buffer_load_b128(
-          x_rsrc, ok ? m * xrow + (unsigned)(g * kdim + col) * 2 : OOB, 0, 0);
+          x_rsrc, ok ? m * xrow + (unsigned)((WG ? 0 : g * kdim) + col) * 2 : OOB, 0, 0);
     }
   };
   auto park_chunk = [&](int buf) __attribute__((always_inline)) {
@@ -177,6 +187,16 @@ gates_wide_kernel(WideArgs a) {
       for (int k2 = 0; k2 < 4; ++k2) {
         const int ks = ph * 4 + k2;
         const bf16x8 a0 = *(const bf16x8 *)(ap + ks * 16), a1 = *(const bf16x8 *)(ap + 32 * XS + ks * 16);
+        if (WG) {
+          typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+          const f16x8 h0 = __builtin_bit_cast(f16x8, a0), h1 = __builtin_bit_cast(f16x8, a1);
+          const f16x8 ha = __builtin_bit_cast(f16x8, fa[k2]), hx = __builtin_bit_cast(f16x8, fx[k2]);
+          accp[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(h0, ha, accp[0], 0, 0, 0);
+          accq[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(h0, hx, accq[0], 0, 0, 0);
+          accp[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(h1, ha, accp[1], 0, 0, 0);
+          accq[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(h1, hx, accq[1], 0, 0, 0);
+          continue;
+        }
         accp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, fa[k2], accp[0], 0, 0, 0);
         if (!DG) accq[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, fx[k2], accq[0], 0, 0, 0);
         accp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, fa[k2], accp[1], 0, 0, 0);
@@ -219,6 +239,22 @@ gates_wide_kernel(WideArgs a) {
     }
   }
 
+  if (WG) {   // lane (j, hf) holds dW[och][k] for the 16 rows k = tile row 16 hf .. 16 hf + 15
+    if (och < bs) {
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const unsigned m = m0 + mi * 32 + hf * 16 + r;
+          if (m < m_end) {
+            const size_t o = ((size_t)g * bs + och) * bs + (m - (unsigned)(g * bs));
+            a.dWa[o] = accp[mi][r];
+            a.dWx[o] = accq[mi][r];
+          }
+        }
+    }
+    return;
+  }
   if (DG) {   // dx += the products: lane (j, hf) holds channel och of rows 16 hf .. 16 hf + 15
     if (och < bs) {
 #pragma unroll
@@ -637,6 +673,7 @@ struct PointArgs {
   float *x, *dp, *dq, *dx;                      // [B][T][D] fp32
   float *part;                                  // [chunk][B][3][D]
   unsigned short *dpq;                          // [B][T][nb][2][bs] bf16: dp and dq of a block side by side
+  unsigned short *dpqh;                         // the same in half precision (operand of the weight gradients)
 };
 __device__ __forceinline__ float half_bits(unsigned short v) { return (float)__builtin_bit_cast(_Float16, v); }
 
@@ -675,6 +712,8 @@ __global__ void __launch_bounds__(256) point_adjoint_kernel(PointArgs a) {
       const size_t oq = (((size_t)b * p.T + t) * p.nb + gb_) * 2 * p.bs + cb_;
       a.dpq[oq] = (unsigned short)(pack_bf16(dpv, 0.f) & 0xffff);
       a.dpq[oq + p.bs] = (unsigned short)(pack_bf16(dqv, 0.f) & 0xffff);
+      a.dpqh[oq] = __builtin_bit_cast(unsigned short, (_Float16)dpv);
+      a.dpqh[oq + p.bs] = __builtin_bit_cast(unsigned short, (_Float16)dqv);
     }
   }
   float *out = a.part + ((size_t)ch * p.B + b) * 3 * p.D + d;
@@ -694,6 +733,19 @@ __global__ void __launch_bounds__(256) wt_concat_kernel(const unsigned short *Wa
   const int g = (int)(i / ((size_t)2 * bs * bs));
   const int gate = jj >= bs, j = jj - gate * bs;
   out[i] = (gate ? Wx : Wa)[((size_t)g * bs + j) * bs + k];
+}
+
+// dst[c][r] = src[r][c] for 16-bit elements, 64 x 64 tiles through LDS
+__global__ void __launch_bounds__(256) transpose16_kernel(const unsigned short *src, unsigned short *dst,
+                                                          unsigned R, unsigned C) {
+  __shared__ unsigned short tile[64][66];
+  const unsigned r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const unsigned tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (unsigned i = ty; i < 64; i += 4)
+    tile[i][tx] = (r0 + i < R && c0 + tx < C) ? src[(size_t)(r0 + i) * C + c0 + tx] : (unsigned short)0;
+  __syncthreads();
+  for (unsigned i = ty; i < 64; i += 4)
+    if (c0 + i < C && r0 + tx < R) dst[(size_t)(c0 + i) * R + r0 + tx] = tile[tx][i];
 }
 
 // partA[b][r][d] = sum over chunks, in a fixed order
@@ -749,6 +801,8 @@ hipError_t launch_forward_wide(const Problem &p, hipStream_t s) {
   a.kdim = p.bs;
   a.x_row_bytes = (unsigned)p.D * 2;
   a.dx = nullptr;
+  a.w_block_elems = (size_t)p.bs * p.bs;
+  a.dWa = a.dWx = nullptr;
   a.M = (unsigned)((size_t)p.B * p.T);
   static bool configured = false;
   if (!configured) {
@@ -786,7 +840,8 @@ namespace rglru {
 // leave x, dp, dq and the direct part of dx where the generic contraction passes expect them.
 namespace {
 struct BwdWidePlan {
-  size_t generic, n2, off_x, off_xh, off_la, off_iv, off_rv, off_delta, off_part, off_dpq, off_wt, off_scan, total;
+  size_t generic, n2, off_x, off_xh, off_la, off_iv, off_rv, off_delta, off_part, off_dpq, off_dpqh, off_xT,
+      off_dpqT, off_wt, off_scan, total;
   int nch;
 };
 BwdWidePlan plan_bwd_wide(int B, int T, int D, int nb) {
@@ -803,6 +858,9 @@ BwdWidePlan plan_bwd_wide(int B, int T, int D, int nb) {
   q.off_delta = off; off += q.n2;
   q.off_part = off; off += al256((size_t)q.nch * B * 3 * D * 4);
   q.off_dpq = off; off += 2 * q.n2;
+  q.off_dpqh = off; off += 2 * q.n2;
+  q.off_xT = off; off += q.n2;
+  q.off_dpqT = off; off += 2 * q.n2;
   q.off_wt = off; off += al256((size_t)nb * (D / nb) * 2 * (D / nb) * 2);
   q.off_scan = off; off += scan_tiled_ws_bytes(B, T, D);
   q.total = off;
@@ -850,6 +908,8 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
   a.kdim = p.bs;
   a.x_row_bytes = (unsigned)p.D * 2;
   a.dx = nullptr;
+  a.w_block_elems = (size_t)p.bs * p.bs;
+  a.dWa = a.dWx = nullptr;
   a.M = (unsigned)((size_t)p.B * p.T);
   static bool configured = false;
   if (!configured) {
@@ -884,6 +944,7 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
     pa.x = gx; pa.dp = gdp; pa.dq = gdq; pa.dx = gdx;
     pa.part = (float *)(ws + q.off_part);
     pa.dpq = (unsigned short *)(ws + q.off_dpq);
+    pa.dpqh = (unsigned short *)(ws + q.off_dpqh);
     hipLaunchKernelGGL(point_adjoint_kernel, dim3((p.D + 255) / 256, p.B, q.nch), dim3(256), 0, s, pa);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     const size_t per_chunk = (size_t)p.B * 3 * p.D;
@@ -911,6 +972,8 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
     dg.kdim = 2 * p.bs;
     dg.nkc = (dg.kdim + BS - 1) / BS;
     dg.x_row_bytes = (unsigned)p.D * 4;
+    dg.w_block_elems = (size_t)p.bs * 2 * p.bs;
+    dg.dWa = dg.dWx = nullptr;
     dg.M = (unsigned)((size_t)p.B * p.T);
     float *gx, *gdp, *gdq, *gdx, *gpartA;
     backward_generic_arrays(p, &gx, &gdp, &gdq, &gdx, &gpartA);
@@ -925,7 +988,46 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
     hipLaunchKernelGGL(gates_wide_kernel<MODE_DGRAD>, dim3((dg.M + WM - 1) / WM, p.nb * dg.nob), dim3(NTHR), W_LDS, s, dg);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  return launch_backward_generic_tail(p, true, s, false);
+  // dW_a, dW_x on the matrix cores: transposed half-precision copies of x and of dp | dq, then the
+  // product machinery with the roles turned (the sum over all (sequence, step) rows is one
+  // workgroup's K loop: no partial sums, a fixed order)
+  const unsigned M = (unsigned)((size_t)p.B * p.T);
+  const bool mfma_wgrad = M % 8 == 0;
+  if (mfma_wgrad) {
+    {
+      KernelTimer kt("transpose16_kernel", s);
+      hipLaunchKernelGGL(transpose16_kernel, dim3((p.D + 63) / 64, (M + 63) / 64), dim3(256), 0, s,
+                         (const unsigned short *)(ws + q.off_xh), (unsigned short *)(ws + q.off_xT), M, (unsigned)p.D);
+      hipLaunchKernelGGL(transpose16_kernel, dim3((2 * p.D + 63) / 64, (M + 63) / 64), dim3(256), 0, s,
+                         (const unsigned short *)(ws + q.off_dpqh), (unsigned short *)(ws + q.off_dpqT), M,
+                         2u * (unsigned)p.D);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    WideArgs wg;
+    wg.p = p;
+    wg.p.W_a = ws + q.off_dpqT;
+    wg.p.W_x = ws + q.off_dpqT + (size_t)p.bs * M * 2;
+    wg.x = (const unsigned short *)(ws + q.off_xT);
+    wg.xh = nullptr; wg.la = wg.gb = wg.rv = nullptr; wg.dx = nullptr;
+    wg.nob = (p.bs + BS - 1) / BS;
+    wg.kdim = (int)M;
+    wg.nkc = (int)((M + BS - 1) / BS);
+    wg.x_row_bytes = M * 2;
+    wg.w_block_elems = (size_t)2 * p.bs * M;
+    wg.M = M;
+    wg.dWa = p.g.dW_a;
+    wg.dWx = p.g.dW_x;
+    static bool configured_wg = false;
+    if (!configured_wg) {
+      e = hipFuncSetAttribute((const void *)gates_wide_kernel<MODE_WGRAD>, hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS);
+      if (e != hipSuccess) return e;
+      configured_wg = true;
+    }
+    KernelTimer kt("wgrad_wide_kernel", s);
+    hipLaunchKernelGGL(gates_wide_kernel<MODE_WGRAD>, dim3((p.bs + WM - 1) / WM, p.nb * wg.nob), dim3(NTHR), W_LDS, s, wg);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  return launch_backward_generic_tail(p, true, s, false, !mfma_wgrad);
 }
 
 bool decode_wide_supported(const Problem &p, bool bf) {
