@@ -674,6 +674,7 @@ struct PointArgs {
   float *part;                                  // [chunk][B][3][D]
   unsigned short *dpq;                          // [B][T][nb][2][bs] bf16: dp and dq of a block side by side
   unsigned short *dpqh;                         // the same in half precision (operand of the weight gradients)
+  int fp32_operands;                            // also write fp32 x, dp, dq (the generic wgrad pass reads them)
 };
 __device__ __forceinline__ float half_bits(unsigned short v) { return (float)__builtin_bit_cast(_Float16, v); }
 
@@ -704,9 +705,11 @@ __global__ void __launch_bounds__(256) point_adjoint_kernel(PointArgs a) {
     s_lam = fmaf(dla * r, lam_scale, s_lam);
     s_ba += dpv;
     s_bx += dqv;
-    a.x[o] = x;
-    a.dp[o] = dpv;
-    a.dq[o] = dqv;
+    if (a.fp32_operands) {
+      a.x[o] = x;
+      a.dp[o] = dpv;
+      a.dq[o] = dqv;
+    }
     a.dx[o] = dg * iv;
     {
       const size_t oq = (((size_t)b * p.T + t) * p.nb + gb_) * 2 * p.bs + cb_;
@@ -945,6 +948,7 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
     pa.part = (float *)(ws + q.off_part);
     pa.dpq = (unsigned short *)(ws + q.off_dpq);
     pa.dpqh = (unsigned short *)(ws + q.off_dpqh);
+    pa.fp32_operands = ((size_t)p.B * p.T) % 8 != 0;   // (else both contractions run on the matrix cores)
     hipLaunchKernelGGL(point_adjoint_kernel, dim3((p.D + 255) / 256, p.B, q.nch), dim3(256), 0, s, pa);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     const size_t per_chunk = (size_t)p.B * 3 * p.D;
