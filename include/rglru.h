@@ -48,9 +48,9 @@
  * matrix-core kernels in every call. Any other multiple of 16 (e.g. 352 and 512 channels at
  * widths 5632 and 8192): rglru_forward runs as three matrix-core passes through the workspace
  * (widths that are a multiple of 256), decode steps on a matrix-core kernel of their own
- * (blocks up to 768 channels), the backward with its gate products and scans on the matrix-core
- * kernels and its two weight contractions on generic ones. All other block sizes up to 2048
- * and fp32 storage run on generic kernels that give the same results far more slowly.
+ * (blocks up to 768 channels), the backward as matrix-core passes as well. All other block
+ * sizes up to 2048 and fp32 storage run on generic kernels that give the same results far
+ * more slowly.
  * rglru_workspace_bytes() accounts for all of it.
  */
 #ifndef RGLRU_H
