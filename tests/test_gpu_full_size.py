@@ -269,3 +269,42 @@ def test_sixteen_blocks_at_the_larger_widths_forward_full_size(D):
         assert gen.rel_err(y_h[b:b + 1, :, sl], y_ref) < TOL, (D, b, g)
         assert gen.rel_err(hT_h[b:b + 1, sl], hT_ref) < TOL, (D, b, g)
     assert np.isfinite(y_h).all()
+
+
+def test_sixteen_blocks_at_width_5632_backward_full_size():
+    # 352 channels per block: the backward as passes on the matrix cores at C1's batch and length;
+    # one sampled block, every sequence through the oracle for its parameter gradients
+    import dataclasses
+    import paper_2402_19427_amd as R
+    import paper_2402_19427_amd.runner as rn
+    w = dataclasses.replace(gen.CONFIGS["C1"], D=5632, nb=16)
+    inp = gen.make_inputs(w.B, w.T, w.D, w.nb, act=w.act, seed=w.seed + 7, dy=True)
+    dp = rn.DeviceProblem(inp, w.B, w.T, w.D, w.nb, w.act)
+    u = rn.to_device(inp["u"], w.act)
+    y, hT, st = dp.forward(u)
+    grads = dp.backward(u, y, rn.to_device(inp["dy"], w.act))
+    sh = dp.shape()
+    ws, _ = dp.workspace(sh, R.OP_BACKWARD)
+    R.rglru_workspace_status(sh, R.OP_BACKWARD, ws)
+    du_h = rn.to_host(grads["du"])
+    dWa_h, dWx_h, dL_h = rn.to_host(grads["dW_a"]), rn.to_host(grads["dW_x"]), rn.to_host(grads["dLambda"])
+    dcw_h = rn.to_host(grads["dconv_w"])
+    oracle.set_threads(8)
+    g = 9
+    sl, par = block_params(inp, g, w.bs)
+    acc = dict(dW_a=np.zeros((w.bs, w.bs)), dW_x=np.zeros((w.bs, w.bs)), dLambda=np.zeros(w.bs),
+               dconv_w=np.zeros((4, w.bs)))
+    for b in range(w.B):
+        ref = oracle.backward(np.asarray(inp["u"][b:b + 1, :, sl], np.float64), *par,
+                              np.asarray(inp["dy"][b:b + 1, :, sl], np.float64))
+        acc["dW_a"] += ref["dW_a"][0]
+        acc["dW_x"] += ref["dW_x"][0]
+        acc["dLambda"] += ref["dLambda"]
+        acc["dconv_w"] += ref["dconv_w"]
+        if b == 2:
+            assert gen.rel_err(du_h[b:b + 1, :, sl], ref["du"]) < TOL
+    assert gen.rel_err(dWa_h[g], acc["dW_a"]) < TOL
+    assert gen.rel_err(dWx_h[g], acc["dW_x"]) < TOL
+    assert gen.rel_err(dL_h[sl], acc["dLambda"]) < TOL
+    assert gen.rel_err(dcw_h[:, sl], acc["dconv_w"]) < TOL
+    assert np.isfinite(du_h).all() and np.isfinite(dWa_h).all() and np.isfinite(dWx_h).all()
