@@ -495,7 +495,9 @@ def test_forward_merge_matches_oracle(B, T, D, nb, act, tanh_form, keep_y):
 
 
 @pytest.mark.parametrize("B,T,D,nb,act", [(2, 37, 96, 3, "f32"), (1, 9, 24, 24, "bf16"),
-                                          (2, 130, 512, 2, "bf16"), (8, 600, 2048, 8, "bf16")])
+                                          (2, 130, 512, 2, "bf16"), (8, 600, 2048, 8, "bf16"),
+                                          (3, 300, 2560, 16, "bf16"),   # widened copy behind the merge adjoint
+                                          (2, 100, 2816, 8, "bf16")])   # backward in passes behind it
 @pytest.mark.parametrize("tanh_form", [False, True])
 def test_backward_merge_matches_oracle(B, T, D, nb, act, tanh_form):
     import paper_2402_19427_amd as R
