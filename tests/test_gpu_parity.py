@@ -50,7 +50,9 @@ SHAPES = [
     (1, 700, 1024, 2, "bf16"),   # bs = 512 (16 blocks at width 8192), scan in time slices
     (3, 70, 256, 4, "bf16"),     # bs = 64: separate passes, one partial K chunk
     (1, 130, 1536, 2, "bf16"),   # bs = 768: three K chunks
-    (2, 37, 96, 2, "bf16"),      # bs = 48, width not a multiple of 256: generic scan pass
+    (2, 37, 96, 2, "bf16"),      # bs = 48, width not a multiple of 256: generic kernels
+    (4, 1, 1024, 2, "bf16"),     # bs = 512, a single step: four rows in all
+    (1, 3, 512, 8, "bf16"),      # bs = 64, fewer rows than a tile
     (1, 9, 24, 24, "bf16"),      # nb = D: per-channel gates
     (2, 300, 600, 2, "bf16"),    # bs = 300 > workgroup size
     (1, 1, 256, 1, "bf16"),      # MFMA path, one step
@@ -191,6 +193,8 @@ BWD_SHAPES = [
     (2, 100, 2816, 8, "bf16"),    # bs = 352: pointwise part in passes, contractions on the generic kernels
     (1, 700, 1024, 2, "bf16"),    # bs = 512, adjoint scan in time slices
     (3, 70, 256, 4, "bf16"),      # bs = 64
+    (4, 1, 1024, 2, "bf16"),      # bs = 512, a single step
+    (1, 24, 512, 8, "bf16"),      # bs = 64, B T a multiple of 8 but smaller than a tile
     (1, 270, 600, 2, "bf16"),
     (1, 1, 256, 1, "bf16"),       # MFMA path, single step
     (2, 31, 256, 1, "bf16"),      # MFMA path, one partial tile
