@@ -985,6 +985,18 @@ bool decode_mfma_supported(const Problem &p, bool bf) {
 hipError_t launch_decode_mfma(const Problem &p, hipStream_t s) {
   DecArgs a;
   a.p = p;
+  static bool configured = false;  // the kernel asks for more than the default LDS limit
+  if (!configured) {
+    hipError_t e;
+    auto big = [](const void *k) { return hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, DEC_LDS); };
+    if ((e = big((const void *)decode_mfma_kernel<0, false>)) != hipSuccess) return e;
+    if ((e = big((const void *)decode_mfma_kernel<1, false>)) != hipSuccess) return e;
+    if ((e = big((const void *)decode_mfma_kernel<2, false>)) != hipSuccess) return e;
+    if ((e = big((const void *)decode_mfma_kernel<0, true>)) != hipSuccess) return e;
+    if ((e = big((const void *)decode_mfma_kernel<1, true>)) != hipSuccess) return e;
+    if ((e = big((const void *)decode_mfma_kernel<2, true>)) != hipSuccess) return e;
+    configured = true;
+  }
   KernelTimer kt("decode_mfma_kernel", s);
   const dim3 grid(p.nb, (p.B + TT - 1) / TT);
   if (p.bs == BS) {

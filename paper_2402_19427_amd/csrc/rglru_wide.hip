@@ -122,7 +122,7 @@ gates_wide_kernel(WideArgs a) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       *(u32x4 *)(wl + i * 8 * W_WROW + wl_wr) = src[i];
-      *(u32x4 *)(wl + W_WPH + i * 8 * W_WROW + wl_wr) = src[4 + i];
+      if (!DG) *(u32x4 *)(wl + W_WPH + i * 8 * W_WROW + wl_wr) = src[4 + i];
     }
   };
 
@@ -799,6 +799,7 @@ hipError_t launch_forward_wide(const Problem &p, hipStream_t s) {
   a.xh = (const unsigned short *)xh;
   a.la = (unsigned short *)la;
   a.gb = (unsigned short *)gb;
+  a.rv = nullptr;
   a.nob = (p.bs + BS - 1) / BS;
   a.nkc = a.nob;
   a.kdim = p.bs;
