@@ -275,7 +275,7 @@ int rglru_timing_get(int index, const char **name, float *ms) {
 
 const char *rglru_last_error(void) { return g_err; }
 
-int rglru_version(void) { return 100; }
+int rglru_version(void) { return 200; }
 
 size_t rglru_workspace_bytes(const rglru_shape *shape, int op) {
   if (op < RGLRU_OP_CONV1D || op > RGLRU_OP_BACKWARD_MERGE) return 0;
