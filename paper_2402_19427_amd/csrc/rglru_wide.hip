@@ -48,6 +48,7 @@ struct WideArgs {
   size_t w_block_elems;        // elements between the weight rows of consecutive blocks
   float *dWa, *dWx;            // wgrad: [nb][bs][bs] fp32, written
   unsigned M;                  // B * T
+  unsigned ntiles;             // row tiles a workgroup column walks (persistent workgroups)
 };
 constexpr int MODE_FWD = 0, MODE_BWD = 1, MODE_DGRAD = 2, MODE_WGRAD = 3;
 
@@ -75,8 +76,9 @@ gates_wide_kernel(WideArgs a) {
   const int D = p.D, bs = p.bs;
   const int g = blockIdx.y / a.nob, ob = blockIdx.y - g * a.nob;
   // (wgrad: the row tiles lie inside block g's rows of the transposed x)
-  const unsigned m0 = WG ? (unsigned)(g * bs) + blockIdx.x * WM : blockIdx.x * WM;
+  const unsigned m_base = WG ? (unsigned)(g * bs) : 0u;
   const unsigned m_end = WG ? (unsigned)(g * bs + bs) : a.M;
+  unsigned m0 = m_base + blockIdx.x * WM;   // first row of the tile in hand
   const unsigned row_bytes = (unsigned)D * 2, xrow = a.x_row_bytes;
   const int kdim = a.kdim;
 
@@ -131,11 +133,11 @@ gates_wide_kernel(WideArgs a) {
       uniform_ptr(a.x), 0, (WG ? (unsigned)p.D : a.M) * xrow, 0x00020000);
   const int lc = tid & 31, r0 = tid >> 5;
   u32x4 nx[4];
-  auto load_chunk = [&](int kc) __attribute__((always_inline)) {   // chunk kc of the block's input channels
+  auto load_chunk = [&](unsigned mt, int kc) __attribute__((always_inline)) {   // chunk kc of the input channels, tile at row mt
     const int col = kc * BS + lc * 8;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const unsigned m = m0 + r0 + 16 * i;
+      const unsigned m = mt + r0 + 16 * i;
       const bool ok = m < m_end && col < kdim;   // (kc past the last chunk: col >= kdim)
       nx[i] = __builtin_amdgcn_raw_buffer_load_b128(
           x_rsrc, ok ? m * xrow + (unsigned)((WG ? 0 : g * kdim) + col) * 2 : OOB, 0, 0);
@@ -147,6 +149,22 @@ gates_wide_kernel(WideArgs a) {
   };
 
   const int arow = ((j >> 2) & 1) * 16 + (j >> 3) * 4 + (j & 3);   // row of this lane's A operand
+  // ---- persistent over row tiles: the weights of this workgroup are the same for every tile, so
+  // their phase pipeline simply wraps around, and the first chunk of the next tile is requested
+  // during the last chunk of this one - loads, products and epilogue of consecutive tiles overlap
+  // instead of forming one dependent chain per workgroup
+  const int nph = a.nkc * 4;
+  int bufp = 0;   // LDS buffer that holds the chunk to be multiplied next
+  load_phase(0, stg[0]);
+  load_phase(1 % nph, stg[1]);
+  load_chunk(m0, 0);
+  park_chunk(0);
+  write_phase(stg[0]);
+  __syncthreads();
+
+  for (unsigned tile = blockIdx.x; tile < a.ntiles; tile += gridDim.x) {
+  m0 = m_base + tile * WM;
+  const unsigned m0_next = m0 + gridDim.x * WM;   // (past the rows if this was the last tile: reads as zero)
   f32x16 accp[2], accq[2], accx[2];
 #pragma unroll
   for (int mi = 0; mi < 2; ++mi)
@@ -157,23 +175,18 @@ gates_wide_kernel(WideArgs a) {
       accx[mi][r] = 0.f;
     }
 
-  load_phase(0, stg[0]);
-  load_phase(1, stg[1]);
-  load_chunk(0);
-  park_chunk(0);
-  write_phase(stg[0]);
-  __syncthreads();
-
   for (int kc = 0; kc < a.nkc; ++kc) {
-    const int buf = kc & 1;
-    load_chunk(kc + 1);   // lands during the products (nothing is read past the last chunk)
+    const int buf = bufp;
+    const bool last = kc + 1 == a.nkc;
+    load_chunk(last ? m0_next : m0, last ? 0 : kc + 1);   // lands during the products
     const unsigned short *ap = xs + buf * W_XT + arow * XS + hf * 8;
 #pragma unroll
     for (int ph = 0; ph < 4; ++ph) {
       const int P = kc * 4 + ph;
-      // two phases ahead, into the registers whose contents are in LDS already (phases past
-      // the block re-read its last columns)
-      load_phase(P + 2, stg[ph & 1]);
+      int P2 = P + 2;
+      if (P2 >= nph) P2 -= nph;
+      // two phases ahead, into the registers whose contents are in LDS already
+      load_phase(P2, stg[ph & 1]);
       wave_lds_fence();   // the fragments come from other lanes of this wave
       bf16x8 fa[4], fx[4];
 #pragma unroll
@@ -205,6 +218,7 @@ gates_wide_kernel(WideArgs a) {
     }
     park_chunk(buf ^ 1);
     __syncthreads();
+    bufp = buf ^ 1;
   }
 
   // ---- x_t of this workgroup's own channels, in half precision (bf16 is too coarse for the
@@ -221,7 +235,7 @@ gates_wide_kernel(WideArgs a) {
       nx[i] = __builtin_amdgcn_raw_buffer_load_b128(
           xh_rsrc, ok ? m * row_bytes + (unsigned)(g * bs + col) * 2 : OOB, 0, 0);
     }
-    park_chunk(0);
+    park_chunk(bufp ^ 1);   // (bufp holds the first chunk of the next tile)
     __syncthreads();
     typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
     f16x8 sh0, sh1;
@@ -230,13 +244,14 @@ gates_wide_kernel(WideArgs a) {
       sh0[e] = (_Float16)((hf * 8 + e == j) ? 1.0f : 0.0f);
       sh1[e] = (_Float16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
     }
-    const unsigned short *ap = xs + arow * XS + hf * 8;
+    const unsigned short *ap = xs + (bufp ^ 1) * W_XT + arow * XS + hf * 8;
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi) {
       const unsigned short *sp = ap + mi * 32 * XS;
       accx[mi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const f16x8 *)(sp + (2 * wv) * 16), sh0, accx[mi], 0, 0, 0);
       accx[mi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const f16x8 *)(sp + (2 * wv + 1) * 16), sh1, accx[mi], 0, 0, 0);
     }
+    __syncthreads();   // the next tile's second chunk goes into this buffer
   }
 
   if (WG) {   // lane (j, hf) holds dW[och][k] for the 16 rows k = tile row 16 hf .. 16 hf + 15
@@ -253,7 +268,7 @@ gates_wide_kernel(WideArgs a) {
           }
         }
     }
-    return;
+    continue;
   }
   if (DG) {   // dx += the products: lane (j, hf) holds channel och of rows 16 hf .. 16 hf + 15
     if (och < bs) {
@@ -265,7 +280,7 @@ gates_wide_kernel(WideArgs a) {
           if (m < a.M) a.dx[(size_t)m * D + g * bs + och] += accp[mi][r];
         }
     }
-    return;
+    continue;
   }
   // ---- eqs. (1)-(3) per element; the two results leave through the wave's staging tile as
   // 16-byte rows
@@ -311,6 +326,7 @@ gates_wide_kernel(WideArgs a) {
       store_staged_tile_s<OT, 0>(otile, lane, rv_rsrc, o_voff, mrow * row_bytes, row_bytes, nrows);
     }
   }
+  }   // row tiles
 }
 
 // ------------------------------------------------------------------------------ decode
@@ -597,6 +613,17 @@ __global__ void __launch_bounds__(256) ring_store_kernel(const uint4 *u, uint4 *
 
 inline size_t al256(size_t n) { return (n + 255) & ~(size_t)255; }
 
+// workgroups along the row tiles: each walks a few tiles (enough to overlap their loads, products
+// and epilogues), and there stay many more workgroups than CUs so that the hardware balances them
+#ifndef WIDE_TILES_PER_WG
+#define WIDE_TILES_PER_WG 4
+#endif
+inline unsigned wide_grid_x(unsigned ntiles, int gy) {
+  (void)gy;
+  const unsigned gx = (ntiles + WIDE_TILES_PER_WG - 1) / WIDE_TILES_PER_WG;
+  return gx < 1 ? 1 : gx;
+}
+
 // ---- Conv1D (Section 2.3) as a streaming pass: a thread produces 8 channels (16 bytes) of CR
 // consecutive steps from CR + 3 input rows; steps before the sequence start read the carried
 // ring state (slot = position mod 3) or zero.
@@ -807,6 +834,7 @@ hipError_t launch_forward_wide(const Problem &p, hipStream_t s) {
   a.dx = nullptr;
   a.w_block_elems = (size_t)p.bs * p.bs;
   a.dWa = a.dWx = nullptr;
+  a.ntiles = (unsigned)(((size_t)p.B * p.T + WM - 1) / WM);
   a.M = (unsigned)((size_t)p.B * p.T);
   static bool configured = false;
   if (!configured) {
@@ -818,7 +846,7 @@ hipError_t launch_forward_wide(const Problem &p, hipStream_t s) {
   }
   {
     KernelTimer kt("gates_wide_kernel", s);
-    hipLaunchKernelGGL(gates_wide_kernel<MODE_FWD>, dim3((a.M + WM - 1) / WM, p.nb * a.nob), dim3(NTHR), W_LDS, s, a);
+    hipLaunchKernelGGL(gates_wide_kernel<MODE_FWD>, dim3(wide_grid_x(a.ntiles, p.nb * a.nob), p.nb * a.nob), dim3(NTHR), W_LDS, s, a);
     e = hipGetLastError();
   }
   if (e != hipSuccess) return e;
@@ -914,6 +942,7 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
   a.dx = nullptr;
   a.w_block_elems = (size_t)p.bs * p.bs;
   a.dWa = a.dWx = nullptr;
+  a.ntiles = (unsigned)(((size_t)p.B * p.T + WM - 1) / WM);
   a.M = (unsigned)((size_t)p.B * p.T);
   static bool configured = false;
   if (!configured) {
@@ -923,7 +952,7 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
   }
   {
     KernelTimer kt("gates_wide_kernel", s);
-    hipLaunchKernelGGL(gates_wide_kernel<MODE_BWD>, dim3((a.M + WM - 1) / WM, p.nb * a.nob), dim3(NTHR), W_LDS, s, a);
+    hipLaunchKernelGGL(gates_wide_kernel<MODE_BWD>, dim3(wide_grid_x(a.ntiles, p.nb * a.nob), p.nb * a.nob), dim3(NTHR), W_LDS, s, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   // delta_t = dy_t + a_{t+1} delta_{t+1}; its last value times a_0 is dh0
@@ -980,6 +1009,7 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
     dg.w_block_elems = (size_t)p.bs * 2 * p.bs;
     dg.dWa = dg.dWx = nullptr;
     dg.M = (unsigned)((size_t)p.B * p.T);
+    dg.ntiles = (dg.M + WM - 1) / WM;
     float *gx, *gdp, *gdq, *gdx, *gpartA;
     backward_generic_arrays(p, &gx, &gdp, &gdq, &gdx, &gpartA);
     dg.dx = gdx;
@@ -990,7 +1020,7 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
       configured_dg = true;
     }
     KernelTimer kt("dgrad_wide_kernel", s);
-    hipLaunchKernelGGL(gates_wide_kernel<MODE_DGRAD>, dim3((dg.M + WM - 1) / WM, p.nb * dg.nob), dim3(NTHR), W_LDS, s, dg);
+    hipLaunchKernelGGL(gates_wide_kernel<MODE_DGRAD>, dim3(wide_grid_x(dg.ntiles, p.nb * dg.nob), p.nb * dg.nob), dim3(NTHR), W_LDS, s, dg);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   // dW_a, dW_x on the matrix cores: transposed half-precision copies of x and of dp | dq, then the
@@ -1020,6 +1050,7 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
     wg.x_row_bytes = M * 2;
     wg.w_block_elems = (size_t)2 * p.bs * M;
     wg.M = M;
+    wg.ntiles = (unsigned)((p.bs + WM - 1) / WM);   // few row tiles with a very long K: one per workgroup
     wg.dWa = p.g.dW_a;
     wg.dWx = p.g.dW_x;
     static bool configured_wg = false;
@@ -1029,7 +1060,7 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
       configured_wg = true;
     }
     KernelTimer kt("wgrad_wide_kernel", s);
-    hipLaunchKernelGGL(gates_wide_kernel<MODE_WGRAD>, dim3((p.bs + WM - 1) / WM, p.nb * wg.nob), dim3(NTHR), W_LDS, s, wg);
+    hipLaunchKernelGGL(gates_wide_kernel<MODE_WGRAD>, dim3(wg.ntiles, p.nb * wg.nob), dim3(NTHR), W_LDS, s, wg);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   return launch_backward_generic_tail(p, true, s, false, !mfma_wgrad);
