@@ -765,17 +765,24 @@ __global__ void __launch_bounds__(256) wt_concat_kernel(const unsigned short *Wa
   out[i] = (gate ? Wx : Wa)[((size_t)g * bs + j) * bs + k];
 }
 
-// dst[c][r] = src[r][c] for 16-bit elements, 64 x 64 tiles through LDS
+// dst[c][r] = src[r][c] for 16-bit elements, 64 x 64 tiles through LDS, two elements per access
+// on both sides (R and C even)
 __global__ void __launch_bounds__(256) transpose16_kernel(const unsigned short *src, unsigned short *dst,
                                                           unsigned R, unsigned C) {
   __shared__ unsigned short tile[64][66];
   const unsigned r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-  const unsigned tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (unsigned i = ty; i < 64; i += 4)
-    tile[i][tx] = (r0 + i < R && c0 + tx < C) ? src[(size_t)(r0 + i) * C + c0 + tx] : (unsigned short)0;
+  const unsigned tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 pairs across, 8 lines down
+  for (unsigned i = ty; i < 64; i += 8) {
+    unsigned v = 0;
+    if (r0 + i < R && c0 + 2 * tx < C) v = *(const unsigned *)(src + (size_t)(r0 + i) * C + c0 + 2 * tx);
+    tile[i][2 * tx] = (unsigned short)(v & 0xffffu);
+    tile[i][2 * tx + 1] = (unsigned short)(v >> 16);
+  }
   __syncthreads();
-  for (unsigned i = ty; i < 64; i += 4)
-    if (c0 + i < C && r0 + tx < R) dst[(size_t)(c0 + i) * R + r0 + tx] = tile[tx][i];
+  for (unsigned i = ty; i < 64; i += 8)
+    if (c0 + i < C && r0 + 2 * tx < R)
+      *(unsigned *)(dst + (size_t)(c0 + i) * R + r0 + 2 * tx) =
+          (unsigned)tile[2 * tx][i] | ((unsigned)tile[2 * tx + 1][i] << 16);
 }
 
 // partA[b][r][d] = sum over chunks, in a fixed order
