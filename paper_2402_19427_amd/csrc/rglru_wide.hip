@@ -55,8 +55,9 @@ constexpr int MODE_FWD = 0, MODE_BWD = 1, MODE_DGRAD = 2, MODE_WGRAD = 3;
 // MODE_BWD: for the backward in passes the second result is the input gate i_t itself (half
 // precision) instead of b_t, plus r_t, and x_t is not needed here.
 // MODE_DGRAD: the same product machinery as the plain matrix pass dx += [dp | dq] [W_a | W_x]^T:
-// "x" holds dp and dq of a block side by side (K = 2 bs), the weights are the transposed gate
-// matrices side by side, one accumulator, and the result is added to the fp32 dx.
+// "x" holds dp and dq of a block side by side (K = 2 bs, half precision), the weights are the
+// transposed gate matrices side by side (converted to half precision), one accumulator on the
+// f16 form of the MFMA, and the result is added to the fp32 dx.
 // MODE_WGRAD: dW[j][k] = sum over (sequence, step) of dp[.][j] x[.][k] with the roles turned: the
 // rows of "x" are the channels k of a block (x transposed, half precision, K = B T), the "weights"
 // are dp and dq transposed (rows j), the products run on the f16 form of the MFMA (x in bf16 is
@@ -200,14 +201,17 @@ gates_wide_kernel(WideArgs a) {
       for (int k2 = 0; k2 < 4; ++k2) {
         const int ks = ph * 4 + k2;
         const bf16x8 a0 = *(const bf16x8 *)(ap + ks * 16), a1 = *(const bf16x8 *)(ap + 32 * XS + ks * 16);
-        if (WG) {
+        if (WG || DG) {   // half-precision operands
           typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
           const f16x8 h0 = __builtin_bit_cast(f16x8, a0), h1 = __builtin_bit_cast(f16x8, a1);
-          const f16x8 ha = __builtin_bit_cast(f16x8, fa[k2]), hx = __builtin_bit_cast(f16x8, fx[k2]);
+          const f16x8 ha = __builtin_bit_cast(f16x8, fa[k2]);
           accp[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(h0, ha, accp[0], 0, 0, 0);
-          accq[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(h0, hx, accq[0], 0, 0, 0);
           accp[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(h1, ha, accp[1], 0, 0, 0);
-          accq[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(h1, hx, accq[1], 0, 0, 0);
+          if (WG) {
+            const f16x8 hx = __builtin_bit_cast(f16x8, fx[k2]);
+            accq[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(h0, hx, accq[0], 0, 0, 0);
+            accq[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(h1, hx, accq[1], 0, 0, 0);
+          }
           continue;
         }
         accp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, fa[k2], accp[0], 0, 0, 0);
@@ -699,8 +703,8 @@ struct PointArgs {
   const unsigned short *xh, *rv, *iv, *delta;   // x_t, r_t, i_t, delta_t in half precision, all [B][T][D]
   float *x, *dp, *dq, *dx;                      // [B][T][D] fp32
   float *part;                                  // [chunk][B][3][D]
-  unsigned short *dpq;                          // [B][T][nb][2][bs] bf16: dp and dq of a block side by side
-  unsigned short *dpqh;                         // the same in half precision (operand of the weight gradients)
+  unsigned short *dpqh;                         // [B][T][nb][2][bs] half precision: dp and dq of a block side by
+                                                // side (operand of both contractions)
   int fp32_operands;                            // also write fp32 x, dp, dq (the generic wgrad pass reads them)
 };
 __device__ __forceinline__ float half_bits(unsigned short v) { return (float)__builtin_bit_cast(_Float16, v); }
@@ -740,8 +744,6 @@ __global__ void __launch_bounds__(256) point_adjoint_kernel(PointArgs a) {
     a.dx[o] = dg * iv;
     {
       const size_t oq = (((size_t)b * p.T + t) * p.nb + gb_) * 2 * p.bs + cb_;
-      a.dpq[oq] = (unsigned short)(pack_bf16(dpv, 0.f) & 0xffff);
-      a.dpq[oq + p.bs] = (unsigned short)(pack_bf16(dqv, 0.f) & 0xffff);
       a.dpqh[oq] = __builtin_bit_cast(unsigned short, (_Float16)dpv);
       a.dpqh[oq + p.bs] = __builtin_bit_cast(unsigned short, (_Float16)dqv);
     }
@@ -752,7 +754,8 @@ __global__ void __launch_bounds__(256) point_adjoint_kernel(PointArgs a) {
   out[2 * (size_t)p.D] = s_lam;
 }
 
-// W'[g][k][gate * bs + j] = W_gate[g][j][k]: the transposed gate matrices of a block side by side
+// W'[g][k][gate * bs + j] = W_gate[g][j][k]: the transposed gate matrices of a block side by side,
+// in half precision
 __global__ void __launch_bounds__(256) wt_concat_kernel(const unsigned short *Wa, const unsigned short *Wx,
                                                         unsigned short *out, int nb, int bs) {
   const size_t total = (size_t)nb * bs * 2 * bs;
@@ -762,7 +765,10 @@ __global__ void __launch_bounds__(256) wt_concat_kernel(const unsigned short *Wa
   const int k = (int)((i / (2 * bs)) % bs);
   const int g = (int)(i / ((size_t)2 * bs * bs));
   const int gate = jj >= bs, j = jj - gate * bs;
-  out[i] = (gate ? Wx : Wa)[((size_t)g * bs + j) * bs + k];
+  // (bf16 -> half precision is exact from 6.1e-5 up to 65504; smaller weights round with an
+  // absolute error below 3e-8)
+  const float w = __uint_as_float((unsigned)(gate ? Wx : Wa)[((size_t)g * bs + j) * bs + k] << 16);
+  out[i] = __builtin_bit_cast(unsigned short, (_Float16)w);
 }
 
 // dst[c][r] = src[r][c] for 16-bit elements, 64 x 64 tiles through LDS, two elements per access
@@ -879,7 +885,7 @@ namespace rglru {
 // leave x, dp, dq and the direct part of dx where the generic contraction passes expect them.
 namespace {
 struct BwdWidePlan {
-  size_t generic, n2, off_x, off_xh, off_la, off_iv, off_rv, off_delta, off_part, off_dpq, off_dpqh, off_xT,
+  size_t generic, n2, off_x, off_xh, off_la, off_iv, off_rv, off_delta, off_part, off_dpqh, off_xT,
       off_dpqT, off_wt, off_scan, total;
   int nch;
 };
@@ -896,7 +902,6 @@ BwdWidePlan plan_bwd_wide(int B, int T, int D, int nb) {
   q.off_rv = off; off += q.n2;
   q.off_delta = off; off += q.n2;
   q.off_part = off; off += al256((size_t)q.nch * B * 3 * D * 4);
-  q.off_dpq = off; off += 2 * q.n2;
   q.off_dpqh = off; off += 2 * q.n2;
   q.off_xT = off; off += q.n2;
   q.off_dpqT = off; off += 2 * q.n2;
@@ -983,7 +988,6 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
     backward_generic_arrays(p, &gx, &gdp, &gdq, &gdx, &gpartA);
     pa.x = gx; pa.dp = gdp; pa.dq = gdq; pa.dx = gdx;
     pa.part = (float *)(ws + q.off_part);
-    pa.dpq = (unsigned short *)(ws + q.off_dpq);
     pa.dpqh = (unsigned short *)(ws + q.off_dpqh);
     pa.fp32_operands = ((size_t)p.B * p.T) % 8 != 0;   // (else both contractions run on the matrix cores)
     hipLaunchKernelGGL(point_adjoint_kernel, dim3((p.D + 255) / 256, p.B, q.nch), dim3(256), 0, s, pa);
@@ -1007,7 +1011,7 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
     dg.p = p;
     dg.p.W_a = ws + q.off_wt;
     dg.p.W_x = ws + q.off_wt;
-    dg.x = (const unsigned short *)(ws + q.off_dpq);
+    dg.x = (const unsigned short *)(ws + q.off_dpqh);
     dg.xh = nullptr; dg.la = dg.gb = dg.rv = nullptr;
     dg.nob = (p.bs + BS - 1) / BS;
     dg.kdim = 2 * p.bs;
