@@ -36,8 +36,9 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 struct WideArgs {
   Problem p;
-  const unsigned short *x;     // [M][D] Conv1D output, bf16: operand of the gate products
-  const unsigned short *xh;    // [M][D] the same in half precision: the x_t of i_t x_t
+  const unsigned short *x;     // [M][D] Conv1D output in half precision: operand of the gate products and
+                               // the x_t of i_t x_t (bf16 is too coarse for that term)
+  const unsigned short *xh;    // unused
   unsigned short *la, *gb;     // [M][D] log a_t (bf16), b_t (half precision)
   unsigned short *rv;          // backward only: [M][D] the recurrence gate r_t (half precision)
   int nob;                     // groups of 256 output channels per block
@@ -201,61 +202,38 @@ gates_wide_kernel(WideArgs a) {
       for (int k2 = 0; k2 < 4; ++k2) {
         const int ks = ph * 4 + k2;
         const bf16x8 a0 = *(const bf16x8 *)(ap + ks * 16), a1 = *(const bf16x8 *)(ap + 32 * XS + ks * 16);
-        if (WG || DG) {   // half-precision operands
+        {   // half-precision operands in every mode
           typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
           const f16x8 h0 = __builtin_bit_cast(f16x8, a0), h1 = __builtin_bit_cast(f16x8, a1);
           const f16x8 ha = __builtin_bit_cast(f16x8, fa[k2]);
           accp[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(h0, ha, accp[0], 0, 0, 0);
           accp[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(h1, ha, accp[1], 0, 0, 0);
-          if (WG) {
+          if (!DG) {
             const f16x8 hx = __builtin_bit_cast(f16x8, fx[k2]);
             accq[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(h0, hx, accq[0], 0, 0, 0);
             accq[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(h1, hx, accq[1], 0, 0, 0);
           }
-          continue;
         }
-        accp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, fa[k2], accp[0], 0, 0, 0);
-        if (!DG) accq[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, fx[k2], accq[0], 0, 0, 0);
-        accp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, fa[k2], accp[1], 0, 0, 0);
-        if (!DG) accq[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, fx[k2], accq[1], 0, 0, 0);
+      }
+    }
+    if (MODE == MODE_FWD && kc == ob) {   // this chunk holds the wave's own channels: x_t into accumulator layout
+      typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+      f16x8 sh0, sh1;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        sh0[e] = (_Float16)((hf * 8 + e == j) ? 1.0f : 0.0f);
+        sh1[e] = (_Float16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
+      }
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi) {
+        const unsigned short *sp = ap + mi * 32 * XS;
+        accx[mi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const f16x8 *)(sp + (2 * wv) * 16), sh0, accx[mi], 0, 0, 0);
+        accx[mi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const f16x8 *)(sp + (2 * wv + 1) * 16), sh1, accx[mi], 0, 0, 0);
       }
     }
     park_chunk(buf ^ 1);
     __syncthreads();
     bufp = buf ^ 1;
-  }
-
-  // ---- x_t of this workgroup's own channels, in half precision (bf16 is too coarse for the
-  // i_t x_t term), through the x tile buffer into accumulator layout with the f16 form of the
-  // selection product
-  if (MODE == MODE_FWD) {
-    const __amdgpu_buffer_rsrc_t xh_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        uniform_ptr(a.xh), 0, a.M * row_bytes, 0x00020000);
-    const int col = ob * BS + lc * 8;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const unsigned m = m0 + r0 + 16 * i;
-      const bool ok = m < a.M && col < bs;
-      nx[i] = __builtin_amdgcn_raw_buffer_load_b128(
-          xh_rsrc, ok ? m * row_bytes + (unsigned)(g * bs + col) * 2 : OOB, 0, 0);
-    }
-    park_chunk(bufp ^ 1);   // (bufp holds the first chunk of the next tile)
-    __syncthreads();
-    typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-    f16x8 sh0, sh1;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      sh0[e] = (_Float16)((hf * 8 + e == j) ? 1.0f : 0.0f);
-      sh1[e] = (_Float16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
-    }
-    const unsigned short *ap = xs + (bufp ^ 1) * W_XT + arow * XS + hf * 8;
-#pragma unroll
-    for (int mi = 0; mi < 2; ++mi) {
-      const unsigned short *sp = ap + mi * 32 * XS;
-      accx[mi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const f16x8 *)(sp + (2 * wv) * 16), sh0, accx[mi], 0, 0, 0);
-      accx[mi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const f16x8 *)(sp + (2 * wv + 1) * 16), sh1, accx[mi], 0, 0, 0);
-    }
-    __syncthreads();   // the next tile's second chunk goes into this buffer
   }
 
   if (WG) {   // lane (j, hf) holds dW[och][k] for the 16 rows k = tile row 16 hf .. 16 hf + 15
@@ -686,7 +664,7 @@ __global__ void __launch_bounds__(256) conv_rows_kernel(ConvArgs a) {
       const f16x2 h2 = {(_Float16)x0, (_Float16)x1};
       oh[e2] = *(const unsigned *)&h2;
     }
-    *(u32x4 *)(a.x + ((size_t)b * T + t0 + r) * D + d0) = o;
+    if (a.x) *(u32x4 *)(a.x + ((size_t)b * T + t0 + r) * D + d0) = o;
     *(u32x4 *)(a.xh + ((size_t)b * T + t0 + r) * D + d0) = oh;
   }
 }
@@ -754,6 +732,14 @@ __global__ void __launch_bounds__(256) point_adjoint_kernel(PointArgs a) {
   out[2 * (size_t)p.D] = s_lam;
 }
 
+// bf16 -> half precision, n elements (gate weights: the products run on the f16 form of the MFMA
+// with x in half precision; exact for weights from 6.1e-5 up to 65504, smaller ones round with
+// an absolute error below 3e-8)
+__global__ void __launch_bounds__(256) to_f16_kernel(const unsigned short *src, unsigned short *dst, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = __builtin_bit_cast(unsigned short, (_Float16)__uint_as_float((unsigned)src[i] << 16));
+}
+
 // W'[g][k][gate * bs + j] = W_gate[g][j][k]: the transposed gate matrices of a block side by side,
 // in half precision
 __global__ void __launch_bounds__(256) wt_concat_kernel(const unsigned short *Wa, const unsigned short *Wx,
@@ -814,19 +800,31 @@ bool forward_wide_supported(const Problem &p, bool bf) {
 
 size_t forward_wide_ws_bytes(int B, int T, int D, int nb) {
   const size_t n = al256((size_t)B * T * D * 2);
-  return 4 * n + scan_tiled_ws_bytes(B, T, D);
+  const size_t wf = al256((size_t)nb * (D / nb) * (D / nb) * 2);   // a gate's weights in half precision
+  return 4 * n + 2 * wf + scan_tiled_ws_bytes(B, T, D);
 }
 
 hipError_t launch_forward_wide(const Problem &p, hipStream_t s) {
   const size_t n = al256((size_t)p.B * p.T * p.D * 2);
   char *ws = (char *)p.ws;
-  void *x = ws, *la = ws + n, *gb = ws + 2 * n, *xh = ws + 3 * n;
+  void *la = ws + n, *gb = ws + 2 * n, *xh = ws + 3 * n;
+  const size_t wf = al256((size_t)p.nb * p.bs * p.bs * 2);
+  unsigned short *wfa = (unsigned short *)(ws + 4 * n), *wfx = (unsigned short *)(ws + 4 * n + wf);
+  const size_t scan_off = 4 * n + 2 * wf;
+  {
+    KernelTimer kt("to_f16_kernel", s);
+    const size_t nw = (size_t)p.nb * p.bs * p.bs;
+    hipLaunchKernelGGL(to_f16_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, s, (const unsigned short *)p.W_a, wfa, nw);
+    hipLaunchKernelGGL(to_f16_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, s, (const unsigned short *)p.W_x, wfx, nw);
+    hipError_t e0 = hipGetLastError();
+    if (e0 != hipSuccess) return e0;
+  }
   hipError_t e;
   {
     KernelTimer kt("conv_rows_kernel", s);
     ConvArgs c;
     c.p = p;
-    c.x = (unsigned short *)x;
+    c.x = nullptr;
     c.xh = (unsigned short *)xh;
     const size_t total = (size_t)p.B * ((p.T + CR - 1) / CR) * (p.D / 8);
     hipLaunchKernelGGL(conv_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, c);
@@ -835,8 +833,10 @@ hipError_t launch_forward_wide(const Problem &p, hipStream_t s) {
   if (e != hipSuccess) return e;
   WideArgs a;
   a.p = p;
-  a.x = (const unsigned short *)x;
-  a.xh = (const unsigned short *)xh;
+  a.p.W_a = wfa;
+  a.p.W_x = wfx;
+  a.x = (const unsigned short *)xh;
+  a.xh = nullptr;
   a.la = (unsigned short *)la;
   a.gb = (unsigned short *)gb;
   a.rv = nullptr;
@@ -867,8 +867,8 @@ hipError_t launch_forward_wide(const Problem &p, hipStream_t s) {
   q.B = p.B; q.T = p.T; q.D = p.D;
   q.flags = RGLRU_SCAN_LOG_A | RGLRU_SCAN_NO_INPUT_SCALE | SCAN_G_FP16;   // b_t carries sqrt(1 - a_t^2)
   q.a = la; q.g = gb; q.h0 = p.h0; q.h = p.y; q.hT = p.hT;
-  q.ws = ws + 4 * n;
-  q.ws_bytes = p.ws_bytes > 4 * n ? p.ws_bytes - 4 * n : 0;
+  q.ws = ws + scan_off;
+  q.ws_bytes = p.ws_bytes > scan_off ? p.ws_bytes - scan_off : 0;
   if (!scan_tiled_supported(q, true)) return hipErrorInvalidValue;
   e = launch_scan_tiled(q, s);
   if (e != hipSuccess) return e;
@@ -885,7 +885,7 @@ namespace rglru {
 // leave x, dp, dq and the direct part of dx where the generic contraction passes expect them.
 namespace {
 struct BwdWidePlan {
-  size_t generic, n2, off_x, off_xh, off_la, off_iv, off_rv, off_delta, off_part, off_dpqh, off_xT,
+  size_t generic, n2, off_x, off_xh, off_la, off_iv, off_rv, off_delta, off_part, off_dpqh, off_xT, off_wf, wf,
       off_dpqT, off_wt, off_scan, total;
   int nch;
 };
@@ -903,6 +903,8 @@ BwdWidePlan plan_bwd_wide(int B, int T, int D, int nb) {
   q.off_delta = off; off += q.n2;
   q.off_part = off; off += al256((size_t)q.nch * B * 3 * D * 4);
   q.off_dpqh = off; off += 2 * q.n2;
+  q.wf = al256((size_t)nb * (D / nb) * (D / nb) * 2);
+  q.off_wf = off; off += 2 * q.wf;
   q.off_xT = off; off += q.n2;
   q.off_dpqT = off; off += 2 * q.n2;
   q.off_wt = off; off += al256((size_t)nb * (D / nb) * 2 * (D / nb) * 2);
@@ -934,7 +936,7 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
     KernelTimer kt("conv_rows_kernel", s);
     ConvArgs c;
     c.p = p;
-    c.x = (unsigned short *)(ws + q.off_x);
+    c.x = nullptr;
     c.xh = (unsigned short *)(ws + q.off_xh);
     const size_t total = (size_t)p.B * ((p.T + CR - 1) / CR) * (p.D / 8);
     hipLaunchKernelGGL(conv_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, c);
@@ -942,8 +944,19 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
   }
   WideArgs a;
   a.p = p;
-  a.x = (const unsigned short *)(ws + q.off_x);
-  a.xh = (const unsigned short *)(ws + q.off_xh);
+  {
+    KernelTimer kt("to_f16_kernel", s);
+    const size_t nw = (size_t)p.nb * p.bs * p.bs;
+    hipLaunchKernelGGL(to_f16_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, s, (const unsigned short *)p.W_a,
+                       (unsigned short *)(ws + q.off_wf), nw);
+    hipLaunchKernelGGL(to_f16_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, s, (const unsigned short *)p.W_x,
+                       (unsigned short *)(ws + q.off_wf + q.wf), nw);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  a.p.W_a = ws + q.off_wf;
+  a.p.W_x = ws + q.off_wf + q.wf;
+  a.x = (const unsigned short *)(ws + q.off_xh);
+  a.xh = nullptr;
   a.la = (unsigned short *)(ws + q.off_la);
   a.gb = (unsigned short *)(ws + q.off_iv);
   a.rv = (unsigned short *)(ws + q.off_rv);
