@@ -496,7 +496,7 @@ hipError_t launch_decode_generic(const Problem &p, bool bf, hipStream_t s) {
 
 template <typename AT>
 static hipError_t backward_generic_t(const Problem &p, hipStream_t s, bool with_pointwise = true,
-                                     bool with_dgrad = true, bool with_wgrad = true) {
+                                     bool with_dgrad = true, bool with_wgrad = true, bool with_du = true) {
   const BwdWs w = carve_bwd_ws(p.ws, p.B, p.T, p.D);
   const size_t lds = generic_lds_bytes(p.bs);
   hipError_t e = allow_lds(bwd_pointwise_kernel<AT>, lds);
@@ -521,8 +521,10 @@ static hipError_t backward_generic_t(const Problem &p, hipStream_t s, bool with_
     hipLaunchKernelGGL(bwd_dgrad_kernel<AT>, dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds, s, p, w);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(bwd_conv_input_kernel<AT>, dim3(grid_1d(n)), dim3(NTHREADS), 0, s, p, w);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (with_du) {
+    hipLaunchKernelGGL(bwd_conv_input_kernel<AT>, dim3(grid_1d(n)), dim3(NTHREADS), 0, s, p, w);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   if (w.nchunk > 65535) return hipErrorInvalidConfiguration;
   hipLaunchKernelGGL(bwd_conv_weight_kernel<AT>, dim3(dblocks, w.nchunk), dim3(NTHREADS), 0, s, p, w);
   if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -542,9 +544,10 @@ hipError_t launch_backward_generic(const Problem &p, bool bf, hipStream_t s) {
 }
 
 // everything after the pointwise pass: the caller has filled x, dp, dq, dx and partA itself
-hipError_t launch_backward_generic_tail(const Problem &p, bool bf, hipStream_t s, bool with_dgrad, bool with_wgrad) {
-  return bf ? backward_generic_t<bf16>(p, s, false, with_dgrad, with_wgrad)
-            : backward_generic_t<float>(p, s, false, with_dgrad, with_wgrad);
+hipError_t launch_backward_generic_tail(const Problem &p, bool bf, hipStream_t s, bool with_dgrad, bool with_wgrad,
+                                        bool with_du) {
+  return bf ? backward_generic_t<bf16>(p, s, false, with_dgrad, with_wgrad, with_du)
+            : backward_generic_t<float>(p, s, false, with_dgrad, with_wgrad, with_du);
 }
 
 void backward_generic_arrays(const Problem &p, float **x, float **dp, float **dq, float **dx, float **partA) {

@@ -96,7 +96,7 @@ hipError_t launch_backward_generic(const Problem &p, bool bf, hipStream_t s);
 size_t backward_generic_ws_bytes(int B, int T, int D, int nb);
 // without the pointwise pass (and without the dgrad pass if the caller has added W^T dp + W^T dq to dx)
 hipError_t launch_backward_generic_tail(const Problem &p, bool bf, hipStream_t s, bool with_dgrad = true,
-                                        bool with_wgrad = true);
+                                        bool with_wgrad = true, bool with_du = true);
 void backward_generic_arrays(const Problem &p, float **x, float **dp, float **dq, float **dx, float **partA);
 size_t generic_lds_bytes(int bs);
 

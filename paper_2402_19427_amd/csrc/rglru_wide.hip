@@ -732,6 +732,46 @@ __global__ void __launch_bounds__(256) point_adjoint_kernel(PointArgs a) {
   out[2 * (size_t)p.D] = s_lam;
 }
 
+// du[b,t,d] = sum_k conv_w[k][d] dx[b,t+k,d] (adjoint of the Conv1D with respect to its input): a
+// thread makes 4 channels of CR consecutive steps from CR + 3 rows of the fp32 dx
+struct ConvAdjArgs {
+  const float *dx, *conv_w;
+  unsigned short *du;
+  int B, T, D;
+};
+__global__ void __launch_bounds__(256) conv_adjoint_rows_kernel(ConvAdjArgs a) {
+  const int D = a.D, T = a.T, nch = D / 4, ntr = (T + CR - 1) / CR;
+  const size_t total = (size_t)a.B * ntr * nch;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % nch);
+  const int tr = (int)((i / nch) % ntr);
+  const int b = (int)(i / ((size_t)nch * ntr));
+  const int t0 = tr * CR, d0 = c * 4;
+  f32x4 w[4], in[CR + 3];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) w[k] = *(const f32x4 *)(a.conv_w + (size_t)k * D + d0);
+  const float *dx = a.dx + (size_t)b * T * D + d0;
+#pragma unroll
+  for (int n = 0; n < CR + 3; ++n) {
+    const int t = t0 + n;
+    in[n] = t < T ? *(const f32x4 *)(dx + (size_t)t * D) : f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+#pragma unroll
+  for (int r = 0; r < CR; ++r) {
+    if (t0 + r >= T) break;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[e] = fmaf(w[k][e], in[r + k][e], acc[e]);
+    uint2 o;
+    o.x = pack_bf16(acc[0], acc[1]);
+    o.y = pack_bf16(acc[2], acc[3]);
+    *(uint2 *)(a.du + ((size_t)b * T + t0 + r) * D + d0) = o;
+  }
+}
+
 // bf16 -> half precision, n elements (gate weights: the products run on the f16 form of the MFMA
 // with x in half precision; exact for weights from 6.1e-5 up to 65504, smaller ones round with
 // an absolute error below 3e-8)
@@ -1087,7 +1127,19 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
     hipLaunchKernelGGL(gates_wide_kernel<MODE_WGRAD>, dim3(wg.ntiles, p.nb * wg.nob), dim3(NTHR), W_LDS, s, wg);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  return launch_backward_generic_tail(p, true, s, false, !mfma_wgrad);
+  const bool own_du = ((uintptr_t)p.du % 8 == 0);
+  if (own_du) {
+    KernelTimer kt("conv_adjoint_rows_kernel", s);
+    ConvAdjArgs ca;
+    float *gx, *gdp, *gdq, *gdx, *gpartA;
+    backward_generic_arrays(p, &gx, &gdp, &gdq, &gdx, &gpartA);
+    ca.dx = gdx; ca.conv_w = p.conv_w; ca.du = (unsigned short *)p.du;
+    ca.B = p.B; ca.T = p.T; ca.D = p.D;
+    const size_t total = (size_t)p.B * ((p.T + CR - 1) / CR) * (p.D / 4);
+    hipLaunchKernelGGL(conv_adjoint_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, ca);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  return launch_backward_generic_tail(p, true, s, false, !mfma_wgrad, !own_du);
 }
 
 bool decode_wide_supported(const Problem &p, bool bf) {
