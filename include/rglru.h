@@ -241,6 +241,16 @@ int rglru_forward_merge(const rglru_shape *shape, const rglru_params *params, co
                         void *stream);
 
 /*
+ * rglru_decode_step with a position per sequence (sequences of a batch that are at different
+ * lengths, as in continuous batching): the ring slots of sequence b follow pos[b].
+ *   pos        [B] int64, DEVICE pointer, read: absolute position of the new token of each
+ *              sequence (>= 0).
+ *   the other arguments: as rglru_decode_step.
+ */
+int rglru_decode_step_at(const rglru_shape *shape, const rglru_params *params, const void *u_t,
+                         float *h, void *conv_state, const int64_t *pos, void *y_t, void *stream);
+
+/*
  * One decode step with the merge as its epilogue: rglru_decode_step, then
  * out_t = y_t * GeLU(branch_t) is what is written (RGLRU_MERGE_SEPARATE is not accepted).
  *   branch_t   [B][D] act, read.

@@ -55,6 +55,7 @@ def _load():
     lib.rglru_conv1d.argtypes = [sp, vp, vp, vp, vp, i64, vp, vp, vp]
     lib.rglru_forward.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp, vp, vp, sz, vp]
     lib.rglru_decode_step.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp]
+    lib.rglru_decode_step_at.argtypes = [sp, pp, vp, vp, vp, vp, vp, vp]
     lib.rglru_backward.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp, vp, vp, vp, gp, vp, sz, vp]
     lib.rglru_forward_merge.argtypes = [sp, pp, vp, vp, vp, vp, i64, ctypes.c_uint, vp, vp, vp, vp, vp, sz, vp]
     lib.rglru_backward_merge.argtypes = [sp, pp, vp, vp, vp, vp, i64, ctypes.c_uint, vp, vp, vp, vp, vp, vp,
@@ -172,6 +173,11 @@ def rglru_forward(shape, params, u, h0, conv_state_in, pos0, y, hT, conv_state_o
 def rglru_decode_step(shape, params, u_t, h, conv_state, pos, y_t, stream=None):
     _check(_lib.rglru_decode_step(_ref(shape), _ref(params), _addr(u_t), _addr(h),
                                   _addr(conv_state), pos, _addr(y_t), _stream(stream)))
+
+
+def rglru_decode_step_at(shape, params, u_t, h, conv_state, pos, y_t, stream=None):
+    _check(_lib.rglru_decode_step_at(_ref(shape), _ref(params), _addr(u_t), _addr(h),
+                                     _addr(conv_state), _addr(pos), _addr(y_t), _stream(stream)))
 
 
 def rglru_backward(shape, params, u, h0, conv_state_in, pos0, y, dy, dhT, du, dh0, grads,

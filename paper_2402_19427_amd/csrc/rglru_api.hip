@@ -442,6 +442,31 @@ int rglru_decode_step(const rglru_shape *shape, const rglru_params *params, cons
   return RGLRU_OK;
 }
 
+int rglru_decode_step_at(const rglru_shape *shape, const rglru_params *params, const void *u_t,
+                         float *h, void *conv_state, const int64_t *pos, void *y_t, void *stream) {
+  CHECK(check_shape(shape, true, false, 0));
+  CHECK(check_params(shape, params));
+  const size_t as = act_size(shape);
+  CHECK(check_ptr(u_t, "u_t", as, true));
+  CHECK(check_ptr(h, "h", 4, true));
+  CHECK(check_ptr(conv_state, "conv_state", as, true));
+  CHECK(check_ptr(pos, "pos", 8, true));
+  CHECK(check_ptr(y_t, "y_t", as, true));
+
+  Problem q;
+  memset(&q, 0, sizeof(q));
+  fill_params(q, shape, params);
+  q.T = 1; q.pos_rows = (const long long *)pos; q.u = u_t; q.hT = h; q.state_in = conv_state;
+  q.state_out = conv_state; q.y = y_t;
+  const bool bf = shape->act_dtype == RGLRU_BF16;
+  hipError_t e = decode_mfma_supported(q, bf)   ? launch_decode_mfma(q, (hipStream_t)stream)
+                 : decode_wide_supported(q, bf) ? launch_decode_wide(q, (hipStream_t)stream)
+                                                : launch_decode_generic(q, bf, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "decode launch");
+  g_err[0] = 0;
+  return RGLRU_OK;
+}
+
 int rglru_backward(const rglru_shape *shape, const rglru_params *params, const void *u,
                    const float *h0, const void *conv_state_in, int64_t pos0, const void *y,
                    const void *dy, const float *dhT, void *du, float *dh0,

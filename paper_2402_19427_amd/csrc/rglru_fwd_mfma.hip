@@ -590,7 +590,9 @@ struct DecArgs {
 // instead: they read as zero and their stores are dropped.
 // MERGE = 1 / 2: the block's merge as epilogue, y_t * GeLU(branch_t) is what is written.
 // PAD: gate blocks narrower than 256 channels in the 256-wide tile, as in the forward kernel.
-template <int MERGE, bool PAD>
+// PERSEQ: a position per sequence; the ring slots then differ from row to row and travel in the
+// per-lane offsets.
+template <int MERGE, bool PAD, bool PERSEQ = false>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 decode_mfma_kernel(DecArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -648,8 +650,17 @@ decode_mfma_kernel(DecArgs a) {
     const bool ok = b < B && lc_ok;
     const unsigned uvo = ok ? (unsigned)b * row2 + (unsigned)dc * 2 : OOB;
     const unsigned rvo = ok ? (unsigned)(b * 3) * row2 + (unsigned)dc * 2 : OOB;
-    ring_vo[i] = rvo;
     ru[i][0] = __builtin_amdgcn_raw_buffer_load_b128(u_rsrc, uvo, 0, 0);
+    if (PERSEQ) {
+      const long long pb = p.pos_rows[b < B ? b : B - 1];
+      const unsigned q1 = ring_slot(pb - 1), q2 = ring_slot(pb - 2), q3 = ring_slot(pb - 3);
+      ring_vo[i] = ok ? rvo + q3 * row2 : OOB;   // where the new token goes
+      ru[i][1] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, ok ? rvo + q1 * row2 : OOB, 0, 0);
+      ru[i][2] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, ok ? rvo + q2 * row2 : OOB, 0, 0);
+      ru[i][3] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, ring_vo[i], 0, 0);
+      continue;
+    }
+    ring_vo[i] = rvo;
     ru[i][1] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, rvo, (unsigned)s1 * row2, 0);
     ru[i][2] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, rvo, (unsigned)s2 * row2, 0);
     ru[i][3] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, rvo, (unsigned)s3 * row2, 0);
@@ -756,7 +767,7 @@ decode_mfma_kernel(DecArgs a) {
       lo4[e] = lo_pk;
     }
     // slot pos mod 3 == slot (pos-3) mod 3
-    __builtin_amdgcn_raw_buffer_store_b128(ru[i][0], ring_rsrc, ring_vo[i], (unsigned)s3 * row2, 0);
+    __builtin_amdgcn_raw_buffer_store_b128(ru[i][0], ring_rsrc, ring_vo[i], PERSEQ ? 0u : (unsigned)s3 * row2, 0);
     *(u32x4 *)(xs + (lr + 16 * i) * XS + 8 * lc) = hi4;
     *(u32x4 *)(xs + XT_ELEMS + (lr + 16 * i) * XS + 8 * lc) = lo4;
   }
@@ -995,11 +1006,16 @@ hipError_t launch_decode_mfma(const Problem &p, hipStream_t s) {
     if ((e = big((const void *)decode_mfma_kernel<0, true>)) != hipSuccess) return e;
     if ((e = big((const void *)decode_mfma_kernel<1, true>)) != hipSuccess) return e;
     if ((e = big((const void *)decode_mfma_kernel<2, true>)) != hipSuccess) return e;
+    if ((e = big((const void *)decode_mfma_kernel<0, false, true>)) != hipSuccess) return e;
+    if ((e = big((const void *)decode_mfma_kernel<0, true, true>)) != hipSuccess) return e;
     configured = true;
   }
   KernelTimer kt("decode_mfma_kernel", s);
   const dim3 grid(p.nb, (p.B + TT - 1) / TT);
-  if (p.bs == BS) {
+  if (p.pos_rows) {   // (callers pass no merge here)
+    if (p.bs == BS) hipLaunchKernelGGL((decode_mfma_kernel<0, false, true>), grid, dim3(NTHR), DEC_LDS, s, a);
+    else hipLaunchKernelGGL((decode_mfma_kernel<0, true, true>), grid, dim3(NTHR), DEC_LDS, s, a);
+  } else if (p.bs == BS) {
     if (p.merge == 0) hipLaunchKernelGGL((decode_mfma_kernel<0, false>), grid, dim3(NTHR), DEC_LDS, s, a);
     else if (p.merge == 1) hipLaunchKernelGGL((decode_mfma_kernel<1, false>), grid, dim3(NTHR), DEC_LDS, s, a);
     else hipLaunchKernelGGL((decode_mfma_kernel<2, false>), grid, dim3(NTHR), DEC_LDS, s, a);

@@ -168,15 +168,15 @@ __global__ void __launch_bounds__(NTHREADS) decode_kernel(Problem p) {
       const int b = b0 + tt;
       acc = p.conv_b ? p.conv_b[d] : 0.f;
       acc = fmaf(p.conv_w[d], ldf((const AT *)p.u, (size_t)b * p.D + d), acc);
+      const long long posb = p.pos_rows ? p.pos_rows[b] : p.pos0;
 #pragma unroll
       for (int k = 1; k < 4; ++k)
         acc = fmaf(p.conv_w[(size_t)k * p.D + d],
-                   ldf(state, ((size_t)b * 3 + ring_slot(p.pos0 - k)) * p.D + d), acc);
+                   ldf(state, ((size_t)b * 3 + ring_slot(posb - k)) * p.D + d), acc);
     }
     xs[idx] = acc;
   }
   __syncthreads();
-  const int wslot = ring_slot(p.pos0);
   for (int j = tid; j < bs; j += NTHREADS) {
     const int d = g * bs + j;
     float pa[GT], qa[GT];
@@ -190,6 +190,7 @@ __global__ void __launch_bounds__(NTHREADS) decode_kernel(Problem p) {
         const float h = fmaf(gt.a, p.hT[o], gt.m * (gt.i * xs[tt * bs + j]));
         p.hT[o] = h;
         stf((AT *)p.y, o, h);
+        const int wslot = ring_slot(p.pos_rows ? p.pos_rows[b0 + tt] : p.pos0);
         state[((size_t)(b0 + tt) * 3 + wslot) * p.D + d] = ((const AT *)p.u)[o];
       }
     }

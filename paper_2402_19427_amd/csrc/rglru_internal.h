@@ -38,6 +38,7 @@ struct Problem {
   int B, T, D, nb, bs;
   float c;
   long long pos0;
+  const long long *pos_rows;   // decode only: position per sequence (device, [B]) instead of pos0
   const void *u;
   const void *W_a, *W_x;
   const float *b_a, *b_x, *Lambda, *conv_w, *conv_b;

@@ -332,7 +332,7 @@ struct DecWideArgs {
   int nob;
 };
 
-template <int MERGE>
+template <int MERGE, bool PERSEQ = false>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 decode_wide_kernel(DecWideArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -358,6 +358,16 @@ decode_wide_kernel(DecWideArgs a) {
   const int lc = tid & 31, lr = tid >> 5;
   const int s1 = ring_slot(p.pos0 - 1), s2 = ring_slot(p.pos0 - 2), s3 = ring_slot(p.pos0 - 3);
   u32x4 ru[2][4];
+  unsigned rq[2][3] = {};
+  if constexpr (PERSEQ) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int b = b0 + lr + 16 * i;
+      const long long pb = p.pos_rows[b < B ? b : B - 1];
+#pragma unroll
+      for (int k = 0; k < 3; ++k) rq[i][k] = (unsigned)ring_slot(pb - 1 - k);
+    }
+  }
   // taps and bias of every chunk parked in LDS once (missing channels: zero bias, any taps -
   // their inputs read as zero), so that only the inputs are in flight during the products
   float *cw_lds = (float *)(smem + DW_OFF_CW);
@@ -385,9 +395,15 @@ decode_wide_kernel(DecWideArgs a) {
       const unsigned uvo = ok ? (unsigned)b * row2 + (unsigned)(g * bs + col) * 2 : OOB;
       const unsigned rvo = ok ? (unsigned)(b * 3) * row2 + (unsigned)(g * bs + col) * 2 : OOB;
       ru[i][0] = __builtin_amdgcn_raw_buffer_load_b128(u_rsrc, uvo, 0, 0);
-      ru[i][1] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, rvo, (unsigned)s1 * row2, 0);
-      ru[i][2] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, rvo, (unsigned)s2 * row2, 0);
-      ru[i][3] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, rvo, (unsigned)s3 * row2, 0);
+      if constexpr (PERSEQ) {   // slots of this row's own position, carried in the lane offset
+        ru[i][1] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, ok ? rvo + rq[i][0] * row2 : OOB, 0, 0);
+        ru[i][2] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, ok ? rvo + rq[i][1] * row2 : OOB, 0, 0);
+        ru[i][3] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, ok ? rvo + rq[i][2] * row2 : OOB, 0, 0);
+      } else {
+        ru[i][1] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, rvo, (unsigned)s1 * row2, 0);
+        ru[i][2] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, rvo, (unsigned)s2 * row2, 0);
+        ru[i][3] = __builtin_amdgcn_raw_buffer_load_b128(ring_rsrc, rvo, (unsigned)s3 * row2, 0);
+      }
     }
   };
   auto conv_chunk = [&](int kc) __attribute__((always_inline)) {   // x tile of the chunk whose inputs are in ru
@@ -586,10 +602,12 @@ decode_wide_kernel(DecWideArgs a) {
 }
 
 // the new token into ring slot pos mod 3, 16 bytes per thread
-__global__ void __launch_bounds__(256) ring_store_kernel(const uint4 *u, uint4 *ring, int B, int chunks, int slot) {
+__global__ void __launch_bounds__(256) ring_store_kernel(const uint4 *u, uint4 *ring, int B, int chunks, int slot,
+                                                         const long long *pos_rows) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i >= B * chunks) return;
   const int b = i / chunks, c = i - b * chunks;
+  if (pos_rows) slot = ring_slot(pos_rows[b]);
   ring[((size_t)b * 3 + slot) * chunks + c] = u[i];
 }
 
@@ -1160,12 +1178,14 @@ hipError_t launch_decode_wide(const Problem &p, hipStream_t s) {
     if ((e = hipFuncSetAttribute((const void *)decode_wide_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, DW_LDS)) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute((const void *)decode_wide_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, DW_LDS)) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute((const void *)decode_wide_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, DW_LDS)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute((const void *)decode_wide_kernel<0, true>, hipFuncAttributeMaxDynamicSharedMemorySize, DW_LDS)) != hipSuccess) return e;
     configured = true;
   }
   const dim3 grid(p.nb * a.nob, (p.B + TT - 1) / TT);
   {
     KernelTimer kt("decode_wide_kernel", s);
-    if (p.merge == 0) hipLaunchKernelGGL(decode_wide_kernel<0>, grid, dim3(NTHR), DW_LDS, s, a);
+    if (p.pos_rows) hipLaunchKernelGGL((decode_wide_kernel<0, true>), grid, dim3(NTHR), DW_LDS, s, a);
+    else if (p.merge == 0) hipLaunchKernelGGL(decode_wide_kernel<0>, grid, dim3(NTHR), DW_LDS, s, a);
     else if (p.merge == 1) hipLaunchKernelGGL(decode_wide_kernel<1>, grid, dim3(NTHR), DW_LDS, s, a);
     else hipLaunchKernelGGL(decode_wide_kernel<2>, grid, dim3(NTHR), DW_LDS, s, a);
     e = hipGetLastError();
@@ -1173,7 +1193,7 @@ hipError_t launch_decode_wide(const Problem &p, hipStream_t s) {
   if (e != hipSuccess) return e;
   const int chunks = p.D / 8;
   hipLaunchKernelGGL(ring_store_kernel, dim3((p.B * chunks + 255) / 256), dim3(256), 0, s, (const uint4 *)p.u,
-                     (uint4 *)p.state_out, p.B, chunks, ring_slot(p.pos0));
+                     (uint4 *)p.state_out, p.B, chunks, ring_slot(p.pos0), p.pos_rows);
   return hipGetLastError();
 }
 

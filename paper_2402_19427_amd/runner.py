@@ -102,6 +102,14 @@ class DeviceProblem:
         R.rglru_decode_step(sh, self.params, u_t, h, conv_state, pos, y, stream)
         return y
 
+    def decode_step_at(self, u_t, h, conv_state, pos, stream=None):
+        """pos: int64 device tensor [B], a position per sequence."""
+        B, D = u_t.shape
+        sh = self.shape(T=1, B=B)
+        y = self.empty_act(B, D)
+        R.rglru_decode_step_at(sh, self.params, u_t, h, conv_state, pos, y, stream)
+        return y
+
     def decode_step_merge(self, u_t, branch_t, h, conv_state, pos, flags=0, stream=None):
         B, D = u_t.shape
         sh = self.shape(T=1, B=B)

@@ -213,6 +213,15 @@ def test_merge_calls_validation_and_workspace():
     assert e.value.code == R.ERR_INVALID_ARG and "db_a" in str(e.value)
 
 
+def test_decode_step_at_validation():
+    s = R.make_shape(2, 1, 16, 2, R.BF16)
+    with pytest.raises(R.RglruError, match="pos") as e:
+        R.rglru_decode_step_at(s, params(), FAKE, FAKE, FAKE, None, FAKE)
+    assert e.value.code == R.ERR_INVALID_ARG
+    with pytest.raises(R.RglruError, match="pos"):
+        R.rglru_decode_step_at(s, params(), FAKE, FAKE, FAKE, FAKE + 4, FAKE)
+
+
 def test_decode_step_merge_validation():
     s = R.make_shape(2, 1, 16, 2, R.BF16)
     OUT = FAKE + 4096

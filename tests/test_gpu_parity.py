@@ -168,6 +168,53 @@ def test_decode_steps_match_oracle_and_wrap_the_ring(B, D, nb, act):
         np.testing.assert_array_equal(gen.chrono_from_ring(rn.to_host(ring), pos + s + 1), st_ref)
 
 
+@pytest.mark.parametrize("B,D,nb,act", [(5, 64, 2, "f32"), (19, 512, 2, "bf16"), (3, 320, 2, "bf16"),
+                                        (37, 1024, 2, "bf16"), (5, 704, 2, "bf16"), (40, 600, 2, "bf16")])
+def test_decode_steps_with_a_position_per_sequence(B, D, nb, act):
+    """Sequences of one batch at different lengths: every row's ring follows its own position,
+    the arithmetic is that of the ordinary step (tuned, chunked and generic kernels)."""
+    import torch
+    rn = runner()
+    nsteps = 5
+    inp = gen.make_inputs(B, 1, D, nb, act=act, seed=B + D + 2, h0=True, state=True,
+                          decode_tokens=nsteps, bias=True)
+    dp = rn.DeviceProblem(inp, B, 1, D, nb, act)
+    pos = np.array([3 + (5 * b) % 11 + 1000003 * (b % 3) for b in range(B)], dtype=np.int64)
+    h = rn.to_device(inp["h0"], "f32")
+    ring_host = np.stack([gen.ring_from_chrono(inp["state"][b:b + 1], int(pos[b]))[0] for b in range(B)])
+    ring = rn.to_device(ring_host, act)
+    q = f64(inp)
+    h_ref, st_ref = q["h0"].copy(), q["state"].copy()
+    for s in range(nsteps):
+        pos_dev = torch.from_numpy(pos + s).cuda()
+        y = dp.decode_step_at(rn.to_device(inp["u_dec"][s], act), h, ring, pos_dev)
+        y_ref = oracle.decode_step(q["u_dec"][s], q["W_a"], q["W_x"], q["b_a"], q["b_x"],
+                                   q["Lambda"], q["conv_w"], h_ref, st_ref, conv_b=q["conv_b"])
+        assert gen.rel_err(rn.to_host(y), y_ref) < TOL[act], s
+        assert gen.rel_err(rn.to_host(h), h_ref) < TOL[act], s
+        got = rn.to_host(ring)
+        for b in range(B):
+            np.testing.assert_array_equal(gen.chrono_from_ring(got[b:b + 1], int(pos[b]) + s + 1)[0], st_ref[b])
+
+
+def test_decode_with_equal_positions_is_the_ordinary_step():
+    import torch
+    rn = runner()
+    B, D, nb, act = 33, 2560, 10, "bf16"
+    inp = gen.make_inputs(B, 1, D, nb, act=act, seed=77, h0=True, state=True, decode_tokens=1)
+    dp = rn.DeviceProblem(inp, B, 1, D, nb, act)
+    u = rn.to_device(inp["u_dec"][0], act)
+    res = []
+    for per_seq in (False, True):
+        h = rn.to_device(inp["h0"], "f32")
+        ring = rn.to_device(gen.ring_from_chrono(inp["state"], 10), act)
+        y = (dp.decode_step_at(u, h, ring, torch.full((B,), 10, dtype=torch.int64, device="cuda"))
+             if per_seq else dp.decode_step(u, h, ring, 10))
+        res.append([rn.to_host(t) for t in (y, h, ring)])
+    for a, b in zip(*res):
+        np.testing.assert_array_equal(a, b)
+
+
 def test_decode_continues_a_forward_call():
     rn = runner()
     B, T, D, nb, act = 4, 21, 512, 2, "bf16"
