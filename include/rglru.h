@@ -241,11 +241,16 @@ int rglru_forward_merge(const rglru_shape *shape, const rglru_params *params, co
                         void *stream);
 
 /*
- * rglru_decode_step with a position per sequence (sequences of a batch that are at different
- * lengths, as in continuous batching): the ring slots of sequence b follow pos[b].
- *   pos        [B] int64, DEVICE pointer, read: absolute position of the new token of each
- *              sequence (>= 0).
- *   the other arguments: as rglru_decode_step.
+ * The decode step (Section 5; Conv1D of Section 2.3 feeding eqs. (1)-(4) for one new token)
+ * with a position per sequence, for a batch whose sequences are at different lengths: the
+ * ring slots of sequence b follow pos[b]; the arithmetic is that of rglru_decode_step.
+ *   pos        [B] int64, DEVICE pointer (8-byte aligned), read by the kernels, owned by the
+ *              caller: absolute position of the new token of each sequence. Values must be
+ *              >= 0; they are not checked on the host, a negative one selects a slot as if it
+ *              were taken modulo 3 (never an access outside conv_state).
+ *   u_t, h, conv_state, y_t: as in rglru_decode_step (states updated in place).
+ * shape.T is ignored. No workspace is needed. Errors: RGLRU_ERR_INVALID_ARG for a NULL or
+ * misaligned pointer or an invalid shape; nothing is launched then.
  */
 int rglru_decode_step_at(const rglru_shape *shape, const rglru_params *params, const void *u_t,
                          float *h, void *conv_state, const int64_t *pos, void *y_t, void *stream);
