@@ -239,6 +239,12 @@ int forward_dispatch(const Problem &q, bool bf, hipStream_t s) {
   } else {
     e = launch_forward_generic(q, bf, s);
     if (e != hipSuccess) return hip_fail(e, "forward launch");
+    // the generic kernels never wait on each other; where the shape would have taken kernels
+    // that do (pointers too loosely aligned for them), their status word is cleared all the same
+    if (q.ws && q.ws_bytes >= 256) {
+      e = launch_clear(q.ws, 16, s);
+      if (e != hipSuccess) return hip_fail(e, "forward launch");
+    }
     // the new ring state is written after the last read of the incoming one (they may alias)
     e = launch_state_update(q, bf, s);
   }
@@ -411,7 +417,13 @@ int rglru_scan(const rglru_shape *shape, const void *a, const void *g, const flo
   q.ws = workspace; q.ws_bytes = workspace_bytes;
   const bool bf = shape->act_dtype == RGLRU_BF16;
   hipStream_t s = (hipStream_t)stream;
-  const hipError_t e = scan_tiled_supported(q, bf) ? launch_scan_tiled(q, s) : launch_scan_generic(q, bf, s);
+  hipError_t e;
+  if (scan_tiled_supported(q, bf)) {
+    e = launch_scan_tiled(q, s);
+  } else {
+    e = launch_scan_generic(q, bf, s);
+    if (e == hipSuccess && workspace && workspace_bytes >= 256) e = launch_clear(workspace, 16, s);
+  }
   if (e != hipSuccess) return hip_fail(e, "scan launch");
   g_err[0] = 0;
   return RGLRU_OK;

@@ -42,32 +42,6 @@ constexpr int G_OFF_HOLD = G_OFF_YT + TR_BYTES;
 constexpr int G_OFF_WX = G_OFF_HOLD + HOLD_BYTES / 2;
 constexpr int G_LDS = G_OFF_WX + G_NLDS * NWAVE * 64 * 16;
 
-// Optional phase timestamps for tuning builds (compiled out otherwise)
-#ifdef RGLRU_TRACE
-__device__ unsigned long long g_trace_bwd[512 * 8 * 32 * 8];
-#define RGLRU_TR(k) tr[k] = __builtin_amdgcn_s_memtime()
-#define RGLRU_TR_FLUSH(wg, wv, it)                                                                  \
-  if (lane == 0 && (it) < 32 && (wg) < 512) {                                                        \
-    for (int k_ = 0; k_ < 8; ++k_) g_trace_bwd[((((wg) * 8 + (wv)) * 32 + (it)) << 3) + k_] = tr[k_]; \
-  }
-#else
-#define RGLRU_TR(k)
-#define RGLRU_TR_FLUSH(wg, wv, it)
-#endif
-#if defined(RGLRU_TRACE) && defined(RGLRU_TRACE_DGRAD)
-#define RGLRU_TRD(k) RGLRU_TR(k)
-#define RGLRU_TRD_FLUSH(wg, wv, it) RGLRU_TR_FLUSH(wg, wv, it)
-#else
-#define RGLRU_TRD(k)
-#define RGLRU_TRD_FLUSH(wg, wv, it)
-#endif
-#if defined(RGLRU_TRACE) && defined(RGLRU_TRACE_WGRAD)
-#define RGLRU_TRW(k) RGLRU_TR(k)
-#define RGLRU_TRW_FLUSH(wg, wv, it) RGLRU_TR_FLUSH(wg, wv, it)
-#else
-#define RGLRU_TRW(k)
-#define RGLRU_TRW_FLUSH(wg, wv, it)
-#endif
 
 struct BwdArgs {
   Problem p;
@@ -275,10 +249,6 @@ bwd_gates_kernel(BwdArgs a) {
   for (int it = 0; tile >= 0; tile -= G, ++it) {
     const int t0 = tile * TT;
     const int next = tile - G;
-#ifdef RGLRU_TRACE
-    unsigned long long tr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#endif
-    RGLRU_TR(0);
 
     // ---- gate pre-activations on the matrix cores
     f32x16 accp, accq, accx;
@@ -323,12 +293,9 @@ bwd_gates_kernel(BwdArgs a) {
       accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(l0, sel_lds[lane], accx, 0, 0, 0);
       accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(l1, sel_lds[64 + lane], accx, 0, 0, 0);
     }
-    RGLRU_TR(4);
     park_dy_y();
     if (next >= 0) load_rows(next * TT);  // consumed by conv_rows at the end of the iteration
-    RGLRU_TR(1);
     __syncthreads();
-    RGLRU_TR(2);
 
     // ---- first sweep (latest step first): r_t, a_t into LDS, aggregate of this lane's run:
     // eps_out = prun * eps_in + erun
@@ -359,7 +326,6 @@ bwd_gates_kernel(BwdArgs a) {
     const float A_t = A_lo * A_up, E_t = fmaf(A_lo, E_up, E_lo);
 
     float e_in = carry;
-    RGLRU_TR(3);
     if (GMAX > 1) {
       publish(ring + (size_t)(tile % a.R) * 2 * BS + hf * BS, hf ? E_t : A_t, (unsigned)(tile + 1));
       // eps entering this tile: own state after tile+G carried across tiles tile+G-1 .. tile+1.
@@ -393,7 +359,6 @@ bwd_gates_kernel(BwdArgs a) {
       }
     }
     carry = fmaf(A_t, e_in, E_t);
-    RGLRU_TR(5);
 
     // ---- second sweep: adjoints with the true eps, latest step first
     float erev = hf ? e_in : fmaf(A_up, e_in, E_up);  // eps_{t+1} for the last step of this run
@@ -459,7 +424,6 @@ bwd_gates_kernel(BwdArgs a) {
       }
     }
 
-    RGLRU_TR(6);
     if (next >= 0) {
       conv_rows();
       // dy and y of the next tile: requested before the barrier, so that part of the trip to HBM
@@ -467,8 +431,6 @@ bwd_gates_kernel(BwdArgs a) {
       load_dy_y(next * TT);
     }
     __syncthreads();
-    RGLRU_TR(7);
-    RGLRU_TR_FLUSH((int)blockIdx.x, wv, it);
   }
   if (GMAX > 1 && spins >= SPIN_LIMIT) *a.err = 1;
 
@@ -716,13 +678,9 @@ bwd_dgrad_kernel(DgradArgs a) {
     load_dxd(tile * TT, true);
     load_u(tile * TT, tile != hi);
     __syncthreads();
-#if defined(RGLRU_TRACE) && defined(RGLRU_TRACE_DGRAD)
-    unsigned long long tr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#endif
     for (int it = 0; tile >= lo; --tile, ++it) {
       const int buf = it & 1, t0 = tile * TT;
       const bool halo = tile == hi;
-      RGLRU_TRD(0);
 
       f32x16 acc0, acc1;
 #pragma unroll
@@ -742,7 +700,6 @@ bwd_dgrad_kernel(DgradArgs a) {
           a1 = n1;
         }
       }
-      RGLRU_TRD(1);
       float dx[19];
 #pragma unroll
       for (int r = 0; r < 16; ++r) dx[r] = dxd_at(r) + (acc0[r] + acc1[r]);
@@ -754,13 +711,10 @@ bwd_dgrad_kernel(DgradArgs a) {
       dx[18] = hf ? nx2 : s2v;
       nx0 = s0v; nx1 = s1v; nx2 = s2v;
       if (!halo) park_u(buf);
-      RGLRU_TRD(2);
       __syncthreads();
-      RGLRU_TRD(3);
       if (tile - 2 >= lo) load_a(buf, t0 - 2 * TT);
       load_dxd(t0 - TT, tile > lo);   // (nothing left to fetch after the last tile: out of range, zeros)
       load_u(t0 - TT, tile > lo);
-      RGLRU_TRD(4);
       if (!halo) {
         // Conv1D adjoint towards the input; the wave's [32 steps][32 channels] results leave
         // through its staging tile as 16-byte stores
@@ -792,8 +746,6 @@ bwd_dgrad_kernel(DgradArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) sb += dx[r];
       }
-      RGLRU_TRD(5);
-      RGLRU_TRD_FLUSH((int)blockIdx.x, wv, it);
     }
   }
   // partial sums of this workgroup
@@ -1081,36 +1033,21 @@ bwd_wgrad_kernel(WgradArgs a) {
     if (late && st_lo + 1 < st_hi) load_tiles(st_lo + 1);
     __syncthreads();
     int it = 0;
-#if defined(RGLRU_TRACE) && defined(RGLRU_TRACE_WGRAD)
-    unsigned long long tr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#endif
     if (!late) {
       for (long long step = st_lo; step < st_hi; ++step, ++it) {
         const int buf = it & 1;
-        RGLRU_TRW(0);
         if (step + 1 < st_hi) load_tiles(step + 1);
-        RGLRU_TRW(1);
         products(buf);
-        RGLRU_TRW(2);
         if (step + 1 < st_hi) park_tiles(step + 1, buf ^ 1);
-        RGLRU_TRW(3);
         __syncthreads();
-        RGLRU_TRW(4);
-        RGLRU_TRW_FLUSH((int)blockIdx.x, wv, it);
       }
     } else {
       for (long long step = st_lo; step < st_hi; ++step, ++it) {
         const int buf = it & 1;
-        RGLRU_TRW(0);
         if (step + 1 < st_hi) park_tiles(step + 1, buf ^ 1);
-        RGLRU_TRW(1);
         if (step + 2 < st_hi) load_tiles(step + 2);
-        RGLRU_TRW(2);
         products(buf);
-        RGLRU_TRW(3);
         __syncthreads();
-        RGLRU_TRW(4);
-        RGLRU_TRW_FLUSH((int)blockIdx.x, wv, it);
       }
     }
   }
@@ -1266,8 +1203,9 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   const int grid = q.units * q.G;
   a.swizzle = (q.G > 1 && grid % 8 == 0) ? 1 : 0;
   a.wxf = (const unsigned short *)(ws + q.off_wxf);
-  // the records only exist (and need clearing) when sequences are sliced in time
-  const size_t clear = q.G > 1 ? 256 + (size_t)q.units * q.R * 2 * BS * sizeof(u64) : 0;
+  // the records only exist (and need clearing) when sequences are sliced in time; the status
+  // word in front of them is cleared in any case (a later health check reads it)
+  const size_t clear = q.G > 1 ? 256 + (size_t)q.units * q.R * 2 * BS * sizeof(u64) : 256;
   {
     PrepArgs pa;
     pa.Wa = (const unsigned short *)p.W_a; pa.Wx = (const unsigned short *)p.W_x;
@@ -1339,10 +1277,5 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   return hipGetLastError();
 }
 
-#ifdef RGLRU_TRACE
-extern "C" int rglru_trace_read_bwd(unsigned long long *dst, size_t n) {
-  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_trace_bwd), n * sizeof(unsigned long long));
-}
-#endif
 
 }  // namespace rglru

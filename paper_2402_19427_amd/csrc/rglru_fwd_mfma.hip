@@ -32,19 +32,6 @@ namespace {
 
 constexpr int FWD_LDS = XS_BYTES + CONST_BYTES + HOLD_BYTES + NWAVE * OTILE_BYTES;
 
-// Optional phase timestamps for tuning builds (compiled out otherwise): wave `wv` of workgroup
-// `wg` records the shader clock at up to 8 points of each of its first 32 iterations.
-#ifdef RGLRU_TRACE
-__device__ unsigned long long g_trace[512 * 8 * 32 * 8];
-#define RGLRU_TR(k) tr[k] = __builtin_amdgcn_s_memtime()
-#define RGLRU_TR_FLUSH(wg, wv, it)                                                              \
-  if (lane == 0 && (it) < 32 && (wg) < 512) {                                                    \
-    for (int k_ = 0; k_ < 8; ++k_) g_trace[((((wg) * 8 + (wv)) * 32 + (it)) << 3) + k_] = tr[k_]; \
-  }
-#else
-#define RGLRU_TR(k)
-#define RGLRU_TR_FLUSH(wg, wv, it)
-#endif
 
 struct FwdArgs {
   Problem p;
@@ -360,9 +347,6 @@ fwd_mfma_kernel(FwdArgs a) {
     carry = fmaf(hA_t, h, hH_t);
   };
 
-#ifdef RGLRU_TRACE
-  unsigned long long tr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#endif
   // ---- gate pre-activations of the tile in LDS buffer `buf` on the matrix cores, and the
   // tile's own columns (high + low part) moved into accumulator layout by selection
   f32x16 accp, accq, accx;
@@ -415,7 +399,6 @@ fwd_mfma_kernel(FwdArgs a) {
   auto pointwise = [&](int tl) __attribute__((always_inline)) {
     const int t0 = tl * TT;
     if (GMAX > 1 && held >= 0) resolve(held);
-    RGLRU_TR(2);
 
     // gates (eqs. 1-3); the (a_t, b_t) pairs go to LDS, the lane keeps the aggregate of
     // its 16-step run: prun = prod a, hrun = end state for a zero incoming state
@@ -459,7 +442,6 @@ fwd_mfma_kernel(FwdArgs a) {
       }
     }
     // combine the two lane halves: lower half = steps 0..15, upper = 16..31
-    RGLRU_TR(3);
     {
       const float oA = __shfl_xor(prun, 32), oH = __shfl_xor(hrun, 32);
       hA_lo = hf ? oA : prun;
@@ -498,33 +480,26 @@ fwd_mfma_kernel(FwdArgs a) {
     for (; tile < a.ntile; tile += G, ++it) {
       const int buf = it & 1;
       const int next = tile + G;
-      RGLRU_TR(0);
       if (!LATE) {
         // rows of the next tile: after the streamed W_x fragments (loads return in order, and
         // these are trips to HBM); they land during the pointwise work
         gemm(buf);
-        RGLRU_TR(1);
         next_rows(next);
         pointwise(tile);
         fetch_branch(GMAX > 1 ? held : next);   // for the tile that is finished next
       } else {
-        RGLRU_TR(1);
         if (it > 0) pointwise(tile - G);
         fetch_branch(GMAX > 1 ? held : tile);
         next_rows(next);                              // lands during the products
         gemm(buf);
       }
       // next tile of this workgroup into the other LDS buffer
-      RGLRU_TR(4);
       if (next < a.ntile) conv_rows(buf ^ 1);
       // aggregates the parked tile will need: requested here, a whole step before their use and
       // clear of the streamed weight fragments (loads return in order); the other slices
       // published them earlier in this step
       if (GMAX > 1 && held >= 0) fetch_records(held);
-      RGLRU_TR(5);
       __syncthreads();
-      RGLRU_TR(6);
-      RGLRU_TR_FLUSH((int)blockIdx.x, wv, it);
     }
     if (LATE && it > 0) {
       pointwise(tile - G);
@@ -606,10 +581,6 @@ decode_mfma_kernel(DecArgs a) {
   const int D = p.D, B = p.B;
   const int bs = PAD ? p.bs : BS;
   const int ch = wv * 32 + j, d = g * bs + ((!PAD || ch < bs) ? ch : bs - 1);
-#ifdef RGLRU_TRACE
-  unsigned long long tr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#endif
-  RGLRU_TR(0);
 
   constexpr unsigned OOB = 0x80000000u;
   const unsigned row2 = (unsigned)D * 2;
@@ -729,7 +700,6 @@ decode_mfma_kernel(DecArgs a) {
     y_vo[i] = ok ? ((unsigned)b * (unsigned)D + (unsigned)(g * bs + wv * 32 + (lane & 3) * 8)) * 2 : OOB;
     if (MERGE) brq[i] = __builtin_amdgcn_raw_buffer_load_b128(br_rsrc, y_vo[i], 0, 0);
   }
-  RGLRU_TR(1);
 
   if (tid < 64) {
     bf16x8 sel0, sel1;
@@ -784,9 +754,7 @@ decode_mfma_kernel(DecArgs a) {
         gl[i][2 * k + 1] = gelu<MERGE == 2, true>(bf_hi(brq[i][k]));
       }
   }
-  RGLRU_TR(2);
   __syncthreads();
-  RGLRU_TR(3);
 
   const int arow = ((j >> 2) & 1) * 16 + (j >> 3) * 4 + (j & 3);
   const unsigned short *ap = xs + arow * XS + hf * 8;
@@ -797,7 +765,6 @@ decode_mfma_kernel(DecArgs a) {
     accq[r] = bias_q;
     accx[r] = 0.f;
   }
-  RGLRU_TR(4);
   write_phase(stg[0]);
 #pragma unroll
   for (int ph = 0; ph < 4; ++ph) {
@@ -819,12 +786,10 @@ decode_mfma_kernel(DecArgs a) {
       accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[k2], fx[k2], accq, 0, 0, 0);
     }
   }
-  RGLRU_TR(5);
   accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ap + (2 * wv) * 16), sel_lds[lane], accx, 0, 0, 0);
   accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ap + (2 * wv + 1) * 16), sel_lds[64 + lane], accx, 0, 0, 0);
   accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ap + XT_ELEMS + (2 * wv) * 16), sel_lds[lane], accx, 0, 0, 0);
   accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ap + XT_ELEMS + (2 * wv + 1) * 16), sel_lds[64 + lane], accx, 0, 0, 0);
-  RGLRU_TR(6);
 
   // ---- h into accumulator layout: lane (j, hf) owns channel j of rows 16 hf .. 16 hf + 15
 #pragma unroll
@@ -860,8 +825,6 @@ decode_mfma_kernel(DecArgs a) {
     }
     __builtin_amdgcn_raw_buffer_store_b128(yv, y_rsrc, y_vo[i], 0, 0);
   }
-  RGLRU_TR(7);
-  RGLRU_TR_FLUSH((int)(blockIdx.y * gridDim.x + blockIdx.x), wv, 0);
 }
 
 }  // namespace
@@ -974,6 +937,12 @@ hipError_t launch_forward_mfma(const Problem &p, hipStream_t s) {
   if (a.G == 1) {
     a.rec = nullptr;
     a.err = nullptr;
+    // a workspace sized for more compute units than this device has: nothing waits here, the
+    // status word a later health check reads is cleared all the same
+    if (p.ws && p.ws_bytes >= 256) {
+      hipError_t e = launch_prep(p.ws, 256, s);
+      if (e != hipSuccess) return e;
+    }
     return launch_t<1>(a, grid, FWD_LDS, s);
   }
   a.err = (int *)p.ws;
@@ -1027,10 +996,5 @@ hipError_t launch_decode_mfma(const Problem &p, hipStream_t s) {
   return hipGetLastError();
 }
 
-#ifdef RGLRU_TRACE
-extern "C" int rglru_trace_read(unsigned long long *dst, size_t n) {
-  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_trace), n * sizeof(unsigned long long));
-}
-#endif
 
 }  // namespace rglru

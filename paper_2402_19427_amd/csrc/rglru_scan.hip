@@ -434,6 +434,10 @@ hipError_t launch_scan_tiled(const ScanProblem &p, hipStream_t s) {
   if (a.G == 1) {
     a.rec = nullptr;
     a.err = nullptr;
+    if (p.ws && p.ws_bytes >= 256) {   // workspace sized for a larger device: clear its status word
+      hipError_t e = launch_prep(p.ws, 256, s);
+      if (e != hipSuccess) return e;
+    }
     return launch_scan_flags<1>(a, grid, s);
   }
   a.err = (int *)p.ws;

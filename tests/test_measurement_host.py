@@ -50,12 +50,18 @@ def test_bench_costs_and_single_gpu_contract():
     bench = importlib.import_module("bench")
     c1 = gen.CONFIGS["C1"]
     n = c1.B * c1.T * c1.D
-    costs = bench.algorithmic_costs(c1.B, c1.T, c1.D, c1.nb)
+    costs = bench.algorithmic_costs(c1.B, c1.T, c1.D, c1.nb, c1.B)
     assert costs["fwd_mfma_kernel"]["flops"] == 1024 * n
     assert abs(costs["fwd_mfma_kernel"]["bytes"] / 1e6 - 170.7) < 0.5
     assert costs["bwd_gates_kernel"]["bytes"] >= 6 * n          # u, y, dy
     assert costs["bwd_dgrad_kernel"]["bytes"] >= 4 * n          # u in, du out
     assert costs["bwd_wgrad_kernel"]["bytes"] == 2 * 10 * 256 * 256 * 4
+    # the default workload is the largest one, with the decode leg at the decode workload's batch
+    c4, c3 = gen.CONFIGS["C4"], gen.CONFIGS["C3"]
+    assert bench.DECODE_BATCH == c3.B
+    big = bench.algorithmic_costs(c4.B, c4.T, c4.D, c4.nb, c3.B)
+    assert abs(big["decode_mfma_kernel"]["bytes"] / 1e6 - 25.3) < 0.1
+    assert big["bwd_gates_kernel"]["flops"] == 1024 * c4.B * c4.T * c4.D
     # more than one GPU is refused with a message
     argv = sys.argv
     sys.argv = ["bench.py", "--gpus", "2"]
