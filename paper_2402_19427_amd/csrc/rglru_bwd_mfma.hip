@@ -4,9 +4,10 @@
 //     recomputes the Conv1D and the gates (same MFMA layout as the forward kernel), runs the
 //     reverse scan eps_t = a_t (dy_t + eps_{t+1}) (so that delta_t = dy_t + eps_{t+1}) and forms
 //     the pointwise adjoints of Section 2.4 eqs. (1)-(4):
-//        dla_t = delta_t (h_t - g_t / m_t)      g = i x, m = sqrt(1 - a^2)
-//                (equal to delta a (h_{t-1} - a g / m) because a h_{t-1} = h_t - m g and
-//                 a^2 + m^2 = 1; it needs y_t only, never h0)
+//        dla_t = delta_t a_t (h_{t-1} - a_t g_t / m_t)      g = i x, m = sqrt(1 - a^2)
+//                (h_{t-1} is the stored y_{t-1}, or h0 at the first step. The algebraically
+//                 equal delta (h_t - g / m) would need y_t only, but it cancels: for small a_t
+//                 the state h_{t-1} has left no trace in the rounded y_t)
 //        dp_t  = -c softplus(-Lambda) dla_t r_t (1 - r_t)
 //        dq_t  = delta_t m_t g_t (1 - i_t)
 //        dxd_t = delta_t m_t i_t                 (the part of dx that bypasses the gates)
@@ -27,7 +28,6 @@ using namespace mfma;
 
 namespace {
 
-constexpr float LN2 = 0.6931471805599453f;
 typedef unsigned u32x3 __attribute__((ext_vector_type(3)));
 constexpr int TS = TT + 8;                       // row stride (bf16) of the [channel][time] tiles
 constexpr int TR_BYTES = BS * TS * 2;            // one transposed tile
@@ -67,7 +67,7 @@ __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)
 bwd_gates_kernel(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned short *xs = (unsigned short *)smem;
-  bf16x8 *sel_lds = (bf16x8 *)(smem + G_OFF_CONST);
+  f16x8 *sel_lds = (f16x8 *)(smem + G_OFF_CONST);
   f32x4 *cw_lds = (f32x4 *)(smem + G_OFF_CONST + 64 * 32);
   unsigned short *dyT = (unsigned short *)(smem + G_OFF_DYT);
   unsigned short *yT = (unsigned short *)(smem + G_OFF_YT);
@@ -93,26 +93,27 @@ bwd_gates_kernel(BwdArgs a) {
   // every tile as contiguous 1 KB fragments (the register file cannot hold everything this
   // kernel needs, and L2 is a far better spill space than scratch)
   constexpr int NRES = GMAX == 1 ? G_NRES + 1 : G_NRES, NLDS = G_NLDS;
-  bf16x8 wa[16], wx[NRES];
+  // (the products run in half precision, see w_to_f16; the streamed copy is already converted)
+  f16x8 wa[16], wx[NRES];
   // fragment ks of this lane when streamed: pxs[ks * 64] (W_x in fragment order)
-  const bf16x8 *pxs = (const bf16x8 *)a.wxf + (size_t)(g * NWAVE + wv) * 16 * 64 + lane;
-  bf16x8 *wxl = (bf16x8 *)(smem + G_OFF_WX) + (size_t)wv * NLDS * 64 + lane;   // [K-step][lane]
+  const f16x8 *pxs = (const f16x8 *)a.wxf + (size_t)(g * NWAVE + wv) * 16 * 64 + lane;
+  f16x8 *wxl = (f16x8 *)(smem + G_OFF_WX) + (size_t)wv * NLDS * 64 + lane;   // [K-step][lane]
   {
     const bf16x8 *pa = (const bf16x8 *)((const unsigned short *)p.W_a + ((size_t)g * BS + ch) * BS + hf * 8);
     const bf16x8 *px = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
 #pragma unroll
-    for (int ks = 0; ks < 16; ++ks) wa[ks] = pa[ks * 2];
+    for (int ks = 0; ks < 16; ++ks) wa[ks] = w_to_f16(pa[ks * 2]);
 #pragma unroll
-    for (int ks = 0; ks < NRES; ++ks) wx[ks] = px[ks * 2];
+    for (int ks = 0; ks < NRES; ++ks) wx[ks] = w_to_f16(px[ks * 2]);
 #pragma unroll
-    for (int i = 0; i < NLDS; ++i) wxl[i * 64] = px[(NRES + i) * 2];   // read back by the same lane only
+    for (int i = 0; i < NLDS; ++i) wxl[i * 64] = w_to_f16(px[(NRES + i) * 2]);   // read back by the same lane only
   }
   if (tid < 64) {
-    bf16x8 sel0, sel1;
+    f16x8 sel0, sel1;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      sel0[e] = (__bf16)((hf * 8 + e == j) ? 1.0f : 0.0f);
-      sel1[e] = (__bf16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
+      sel0[e] = (_Float16)((hf * 8 + e == j) ? 1.0f : 0.0f);
+      sel1[e] = (_Float16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
     }
     sel_lds[lane] = sel0;
     sel_lds[64 + lane] = sel1;
@@ -196,13 +197,13 @@ bwd_gates_kernel(BwdArgs a) {
       x0 = fmaf(w23[0], bf_lo(raw[r + 1]), x0); x1 = fmaf(w23[1], bf_hi(raw[r + 1]), x1);
       x0 = fmaf(w23[2], bf_lo(raw[r]), x0);     x1 = fmaf(w23[3], bf_hi(raw[r]), x1);
       unsigned hi_pk, lo_pk;
-      split_bf16(x0, x1, hi_pk, lo_pk);
+      split_f16(x0, x1, hi_pk, lo_pk);
       *(unsigned *)(xw + r * XS) = hi_pk;
       *(unsigned *)(xw + XT_ELEMS + r * XS) = lo_pk;
     }
   };
   // dy and y rows 8*rg..8*rg+7 of tile t0 for the channel pair (zero past the sequence end)
-  unsigned rdy[8], ry[8];
+  unsigned rdy[8], ry[8], ryh;   // ryh: the row before the tile (h_{t-1} of its first step)
   // (no branch around the loads: rows past the end of the sequence are out of the descriptors'
   // range and read as zero; a conditional load would make the compiler wait for it on the spot)
   auto load_dy_y = [&](int t0) {
@@ -212,6 +213,9 @@ bwd_gates_kernel(BwdArgs a) {
       rdy[r] = __builtin_amdgcn_raw_buffer_load_b32(dy_rsrc, c_voff, so, RGLRU_NT);
       ry[r] = __builtin_amdgcn_raw_buffer_load_b32(y_rsrc, c_voff, so, RGLRU_NT);
     }
+    // (t0 = 0: the offset wraps to the top of the 32-bit range, far outside the descriptor,
+    // and reads as zero; the lanes take h0 there instead)
+    ryh = __builtin_amdgcn_raw_buffer_load_b32(y_rsrc, c_voff, (unsigned)(t0 - 1) * row_bytes, RGLRU_NT);
   };
   // transposed [channel][time] copies: 8 consecutive steps of one channel are 16 contiguous bytes
   auto park_dy_y = [&]() {
@@ -225,6 +229,10 @@ bwd_gates_kernel(BwdArgs a) {
       *(uint4 *)(dyT + (2 * c2 + c) * TS + 8 * rg) = vd;
       *(uint4 *)(yT + (2 * c2 + c) * TS + 8 * rg) = vy;
     }
+    if (rg == 0) {   // the row before the tile goes to the spare column TS - 1 of the y tile
+      yT[(2 * c2) * TS + TS - 1] = (unsigned short)(ryh & 0xffffu);
+      yT[(2 * c2 + 1) * TS + TS - 1] = (unsigned short)(ryh >> 16);
+    }
   };
 
   const int arow = ((j >> 2) & 1) * 16 + (j >> 3) * 4 + (j & 3);
@@ -235,6 +243,7 @@ bwd_gates_kernel(BwdArgs a) {
 
   u64 *ring = GMAX > 1 ? a.rec + (size_t)unit * a.R * 2 * BS + ch : nullptr;
   float carry = p.dhT ? p.dhT[(size_t)b * D + d] : 0.f;  // eps entering this workgroup's next tile
+  const float h_first = p.h0 ? p.h0[(size_t)b * D + d] : 0.f;   // h_{-1}
   float s_ba = 0.f, s_bx = 0.f, s_lam = 0.f;
   int spins = 0;
 
@@ -260,21 +269,21 @@ bwd_gates_kernel(BwdArgs a) {
     }
     const unsigned short *ap = arow_base;
     {
-      bf16x8 a0 = *(const bf16x8 *)(ap), a1 = *(const bf16x8 *)(ap + 16);
+      f16x8 a0 = *(const f16x8 *)(ap), a1 = *(const f16x8 *)(ap + 16);
       constexpr int NS = NRES + NLDS;                            // first streamed K-step
-      bf16x8 s0 = pxs[NS * 64], s1 = pxs[(NS + 1) * 64];         // streamed W_x fragments, two in flight
-      bf16x8 l0 = wxl[0];                                        // LDS-resident fragment, one ahead
+      f16x8 s0 = pxs[NS * 64], s1 = pxs[(NS + 1) * 64];          // streamed W_x fragments, two in flight
+      f16x8 l0 = wxl[0];                                         // LDS-resident fragment, one ahead
 #pragma unroll
       for (int ks = 0; ks < 16; ++ks) {
-        const bf16x8 a2 = *(const bf16x8 *)(ap + ((ks + 2) & 15) * 16);
-        accp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wa[ks], accp, 0, 0, 0);
+        const f16x8 a2 = *(const f16x8 *)(ap + ((ks + 2) & 15) * 16);
+        accp = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, wa[ks], accp, 0, 0, 0);
         if (ks < NRES) {
-          accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wx[ks], accq, 0, 0, 0);
+          accq = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, wx[ks], accq, 0, 0, 0);
         } else if (ks < NS) {
-          accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, l0, accq, 0, 0, 0);
+          accq = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, l0, accq, 0, 0, 0);
           if (ks + 1 < NS) l0 = wxl[(ks + 1 - NRES) * 64];
         } else {
-          accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, s0, accq, 0, 0, 0);
+          accq = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, s0, accq, 0, 0, 0);
           s0 = s1;
           if (ks + 2 < 16) s1 = pxs[(ks + 2) * 64];
         }
@@ -284,14 +293,14 @@ bwd_gates_kernel(BwdArgs a) {
       }
     }
     {
-      const bf16x8 s0 = *(const bf16x8 *)(ap + (2 * wv) * 16);
-      const bf16x8 s1 = *(const bf16x8 *)(ap + (2 * wv + 1) * 16);
-      const bf16x8 l0 = *(const bf16x8 *)(ap + XT_ELEMS + (2 * wv) * 16);
-      const bf16x8 l1 = *(const bf16x8 *)(ap + XT_ELEMS + (2 * wv + 1) * 16);
-      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(s0, sel_lds[lane], accx, 0, 0, 0);
-      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(s1, sel_lds[64 + lane], accx, 0, 0, 0);
-      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(l0, sel_lds[lane], accx, 0, 0, 0);
-      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(l1, sel_lds[64 + lane], accx, 0, 0, 0);
+      const f16x8 s0 = *(const f16x8 *)(ap + (2 * wv) * 16);
+      const f16x8 s1 = *(const f16x8 *)(ap + (2 * wv + 1) * 16);
+      const f16x8 l0 = *(const f16x8 *)(ap + XT_ELEMS + (2 * wv) * 16);
+      const f16x8 l1 = *(const f16x8 *)(ap + XT_ELEMS + (2 * wv + 1) * 16);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_f16(s0, sel_lds[lane], accx, 0, 0, 0);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_f16(s1, sel_lds[64 + lane], accx, 0, 0, 0);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_f16(l0, sel_lds[lane], accx, 0, 0, 0);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_f16(l1, sel_lds[64 + lane], accx, 0, 0, 0);
     }
     park_dy_y();
     if (next >= 0) load_rows(next * TT);  // consumed by conv_rows at the end of the iteration
@@ -371,20 +380,29 @@ bwd_gates_kernel(BwdArgs a) {
       const float dyv[4] = {bf_lo(d01), bf_hi(d01), bf_lo(d23), bf_hi(d23)};
       const float yv[4] = {bf_lo(y01), bf_hi(y01), bf_lo(y23), bf_hi(y23)};
       const f32x4 rq = hold_mine[q * 64];
+      // h_{t-1} of the quad's first step: the step before it in the y tile (the spare column
+      // for the first step of the tile, h0 for the first step of the sequence)
+      const int pcol = q == 0 ? (hf ? 15 : TS - 1) : hf * 16 + 4 * q - 1;
+      float hfirst = bf_lo((unsigned)yT[ch * TS + pcol]);
+      if (q == 0 && hf == 0 && tile == 0) hfirst = h_first;
       float dpv[4], dqv[4], dxv[4];
 #pragma unroll
       for (int e = 3; e >= 0; --e) {
         const float rv = rq[e];
-        const float av = __builtin_amdgcn_exp2f(kd * rv);
+        const float l2 = kd * rv;
+        const float av = __builtin_amdgcn_exp2f(l2);
         const bool ok = 4 * q + e < nvalid;
         const float delta = ok ? dyv[e] + erev : 0.f;
-        const float m2 = fmaxf(fmaf(-av, av, 1.f), 1e-30f);
+        // (a gate closed so far that r_t = 0 in fp32 gives m = 0: the floor keeps 1/m finite,
+        // and the terms it scales carry the factor r_t (1 - r_t) = 0)
+        const float m2 = fmaxf(one_minus_sq(av, l2), 1e-30f);
         const float rs = __builtin_amdgcn_rsqf(m2);       // 1 / m
         const float m = m2 * rs;
         const float eq = __builtin_amdgcn_exp2f(-accq[4 * q + e]);
         const float iv = __builtin_amdgcn_rcpf(1.f + eq);
         const float gin = iv * (accx[4 * q + e] * LN2);   // i_t x_t
-        const float dla = delta * fmaf(-gin, rs, yv[e]);  // delta (h_t - g/m)
+        const float hprev = e > 0 ? yv[e - 1] : hfirst;
+        const float dla = (delta * av) * fmaf(-av * gin, rs, hprev);   // delta a (h_{t-1} - a g/m)
         const float dg = delta * m;
         dxv[e] = dg * iv;
         dqv[e] = dg * gin * (1.f - iv);
@@ -511,7 +529,10 @@ __global__ void __launch_bounds__(256) bwd_prep_kernel(PrepArgs a) {
   if (i < (size_t)a.nb * BS * BS / 8) {
     const int lane = (int)(i & 63), ks = (int)((i >> 6) & 15), wv = (int)((i >> 10) & 7), g = (int)(i >> 13);
     const int hf = lane >> 5, j = lane & 31;
-    a.wxf[i] = ((const uint4 *)a.Wx)[((size_t)g * BS + wv * 32 + j) * (BS / 8) + ks * 2 + hf];
+    // (in half precision: the gates kernel's products run on the f16 form of the MFMA)
+    const uint4 w = ((const uint4 *)a.Wx)[((size_t)g * BS + wv * 32 + j) * (BS / 8) + ks * 2 + hf];
+    a.wxf[i] = make_uint4(pack_f16(bf_lo(w.x), bf_hi(w.x)), pack_f16(bf_lo(w.y), bf_hi(w.y)),
+                          pack_f16(bf_lo(w.z), bf_hi(w.z)), pack_f16(bf_lo(w.w), bf_hi(w.w)));
   }
 }
 

@@ -2,9 +2,9 @@
 //
 // One workgroup of 8 waves owns one (sequence, gate block) pair - or one of G interleaved
 // time slices of it - and walks it in tiles of 32 steps:
-//   Conv1D (Section 2.3) in fp32 -> tile in LDS as bf16 high part + bf16 low part; the gate
-//     products read the high part, the recurrence input x_t is rebuilt from both
-//   gate pre-activations W_a x, W_x x (eqs. 1-2) with v_mfma_f32_32x32x16_bf16; each wave keeps
+//   Conv1D (Section 2.3) in fp32 -> tile in LDS as a high part + a low part in half precision;
+//     the gate products read the high part, the recurrence input x_t is rebuilt from both
+//   gate pre-activations W_a x, W_x x (eqs. 1-2) with v_mfma_f32_32x32x16_f16; each wave keeps
 //     its 32 output channels of both gate matrices in registers for the whole kernel
 //   gates, a_t, sqrt(1-a_t^2) (eqs. 1-3, Appendix A) and the scan (eq. 4) in registers: every
 //     lane runs 16 consecutive steps of one channel, the two lane halves are combined with
@@ -41,6 +41,7 @@ struct FwdArgs {
   u64 *rec;      // [unit][R][2][256] records (A then H), zeroed before launch; NULL if G == 1
   int *err;      // set to 1 if a bounded wait expired
   int swizzle;   // remap block ids so that neighbouring time slices share an XCD
+  const unsigned short *wx16;   // W_x in half precision, same layout (fwd_prep_kernel)
 };
 
 // eqs. (1)-(3) with base-2 exponentials; pp, qq, xx carry a factor log2(e).
@@ -49,8 +50,9 @@ __device__ __forceinline__ void gate_fast(float pp, float qq, float xx, float kd
                                           float &b) {
   const float ep = __builtin_amdgcn_exp2f(-pp);
   const float r = __builtin_amdgcn_rcpf(1.f + ep);
-  a = __builtin_amdgcn_exp2f(kd * r);
-  const float m = __builtin_amdgcn_sqrtf(fmaf(-a, a, 1.f));
+  const float l2 = kd * r;
+  a = __builtin_amdgcn_exp2f(l2);
+  const float m = __builtin_amdgcn_sqrtf(one_minus_sq(a, l2));
   const float eq = __builtin_amdgcn_exp2f(-qq);
   const float il = __builtin_amdgcn_rcpf(fmaf(eq, LOG2E, LOG2E));  // ln2 * sigmoid(q)
   b = (m * il) * xx;
@@ -61,6 +63,19 @@ __device__ __forceinline__ void gate_fast(float pp, float qq, float xx, float kd
 __global__ void __launch_bounds__(256) prep_kernel(uint4 *zero, size_t n16) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n16) zero[i] = make_uint4(0, 0, 0, 0);
+}
+// The forward kernel's own preparation: the same clearing, and W_x once in half precision (its
+// K-steps that do not fit the registers are re-read every tile; converting them there would
+// cost more than this pass; n8 = groups of eight weights).
+__global__ void __launch_bounds__(256) fwd_prep_kernel(uint4 *zero, size_t n16, const uint4 *wx, uint4 *wx16,
+                                                       size_t n8) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n16) zero[i] = make_uint4(0, 0, 0, 0);
+  if (i < n8) {
+    const uint4 w = wx[i];
+    wx16[i] = make_uint4(pack_f16(bf_lo(w.x), bf_hi(w.x)), pack_f16(bf_lo(w.y), bf_hi(w.y)),
+                         pack_f16(bf_lo(w.z), bf_hi(w.z)), pack_f16(bf_lo(w.w), bf_hi(w.w)));
+  }
 }
 
 constexpr int FWD_MAX_SLICES = 16;
@@ -90,7 +105,7 @@ __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)
 fwd_mfma_kernel(FwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned short *xs = (unsigned short *)smem;                   // [2 buffers][high, low][TT][XS]
-  bf16x8 *sel_lds = (bf16x8 *)(smem + XS_BYTES);                 // [2][64] selection operands
+  f16x8 *sel_lds = (f16x8 *)(smem + XS_BYTES);                   // [2][64] selection operands
   f32x4 *cw_lds = (f32x4 *)(smem + XS_BYTES + 64 * 32);          // [3][128] Conv1D taps and bias
   float *hold = (float *)(smem + XS_BYTES + CONST_BYTES);        // [wave][8][64] float4
   const Problem &p = a.p;
@@ -129,23 +144,23 @@ fwd_mfma_kernel(FwdArgs a) {
   constexpr int NRES_P = GMAX == 1 ? 11 : (GMAX == 4 ? 2 : (GMAX == 8 ? 0 : 2));
   constexpr int NRES = !PAD ? NRES_M : (MERGE == 0 ? NRES_P : (NRES_P >= 2 ? NRES_P - 2 : 0));
   constexpr int PF = 2;   // streamed fragments in flight (deeper rings measured no better)
-  bf16x8 wa[16], wx[NRES > 0 ? NRES : 1];
-  const bf16x8 *pxs = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * bs + chc) * bs + hf * 8);
+  f16x8 wa[16], wx[NRES > 0 ? NRES : 1];   // (half precision, see w_to_f16)
+  const f16x8 *pxs = (const f16x8 *)(a.wx16 + ((size_t)g * bs + chc) * bs + hf * 8);
   {
     const bf16x8 *pa = (const bf16x8 *)((const unsigned short *)p.W_a + ((size_t)g * bs + chc) * bs + hf * 8);
 #pragma unroll
-    for (int ks = 0; ks < 16; ++ks) wa[ks] = pa[kc(ks) * 2];
+    for (int ks = 0; ks < 16; ++ks) wa[ks] = w_to_f16(pa[kc(ks) * 2]);
 #pragma unroll
     for (int ks = 0; ks < NRES; ++ks) wx[ks] = pxs[kc(ks) * 2];
   }
   // selection matrices that copy this wave's 32 columns of the tile into accumulator layout
   // (the same for every wave; parked in LDS to keep registers for the weights)
   if (tid < 64) {
-    bf16x8 sel0, sel1;
+    f16x8 sel0, sel1;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      sel0[e] = (__bf16)((hf * 8 + e == j) ? 1.0f : 0.0f);
-      sel1[e] = (__bf16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
+      sel0[e] = (_Float16)((hf * 8 + e == j) ? 1.0f : 0.0f);
+      sel1[e] = (_Float16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
     }
     sel_lds[lane] = sel0;
     sel_lds[64 + lane] = sel1;
@@ -245,7 +260,7 @@ fwd_mfma_kernel(FwdArgs a) {
       x0 = fmaf(w23[0], bf_lo(raw[r + 1]), x0); x1 = fmaf(w23[1], bf_hi(raw[r + 1]), x1);
       x0 = fmaf(w23[2], bf_lo(raw[r]), x0);     x1 = fmaf(w23[3], bf_hi(raw[r]), x1);
       unsigned hi_pk, lo_pk;
-      split_bf16(x0, x1, hi_pk, lo_pk);
+      split_f16(x0, x1, hi_pk, lo_pk);
       *(unsigned *)(xw + buf * (2 * XT_ELEMS) + r * XS) = hi_pk;
       *(unsigned *)(xw + buf * (2 * XT_ELEMS) + XT_ELEMS + r * XS) = lo_pk;
     }
@@ -359,22 +374,22 @@ fwd_mfma_kernel(FwdArgs a) {
     }
     const unsigned short *ap = arow_base + buf * (2 * XT_ELEMS);
     {
-      bf16x8 a0 = *(const bf16x8 *)(ap), a1 = *(const bf16x8 *)(ap + 16);
+      f16x8 a0 = *(const f16x8 *)(ap), a1 = *(const f16x8 *)(ap + 16);
       // streamed W_x fragments: a ring of PF, all requested up front (the resident K-steps
       // come first, so the ring has that long to fill)
-      bf16x8 st[PF];
+      f16x8 st[PF];
       if (NRES < 16) {
 #pragma unroll
         for (int i = 0; i < PF; ++i) st[i] = pxs[kc(NRES + i < 16 ? NRES + i : 15) * 2];
       }
 #pragma unroll
       for (int ks = 0; ks < 16; ++ks) {
-        const bf16x8 a2 = *(const bf16x8 *)(ap + ((ks + 2) & 15) * 16);  // two steps ahead
-        accp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wa[ks], accp, 0, 0, 0);
+        const f16x8 a2 = *(const f16x8 *)(ap + ((ks + 2) & 15) * 16);  // two steps ahead
+        accp = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, wa[ks], accp, 0, 0, 0);
         if (ks < NRES) {
-          accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wx[ks], accq, 0, 0, 0);
+          accq = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, wx[ks], accq, 0, 0, 0);
         } else {
-          accq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, st[(ks - NRES) % PF], accq, 0, 0, 0);
+          accq = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, st[(ks - NRES) % PF], accq, 0, 0, 0);
           if (ks + PF < 16) st[(ks - NRES) % PF] = pxs[kc(ks + PF) * 2];
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -383,14 +398,14 @@ fwd_mfma_kernel(FwdArgs a) {
       }
     }
     {
-      const bf16x8 s0 = *(const bf16x8 *)(ap + (2 * wv) * 16);
-      const bf16x8 s1 = *(const bf16x8 *)(ap + (2 * wv + 1) * 16);
-      const bf16x8 l0 = *(const bf16x8 *)(ap + XT_ELEMS + (2 * wv) * 16);
-      const bf16x8 l1 = *(const bf16x8 *)(ap + XT_ELEMS + (2 * wv + 1) * 16);
-      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(s0, sel_lds[lane], accx, 0, 0, 0);
-      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(s1, sel_lds[64 + lane], accx, 0, 0, 0);
-      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(l0, sel_lds[lane], accx, 0, 0, 0);
-      accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(l1, sel_lds[64 + lane], accx, 0, 0, 0);
+      const f16x8 s0 = *(const f16x8 *)(ap + (2 * wv) * 16);
+      const f16x8 s1 = *(const f16x8 *)(ap + (2 * wv + 1) * 16);
+      const f16x8 l0 = *(const f16x8 *)(ap + XT_ELEMS + (2 * wv) * 16);
+      const f16x8 l1 = *(const f16x8 *)(ap + XT_ELEMS + (2 * wv + 1) * 16);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_f16(s0, sel_lds[lane], accx, 0, 0, 0);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_f16(s1, sel_lds[64 + lane], accx, 0, 0, 0);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_f16(l0, sel_lds[lane], accx, 0, 0, 0);
+      accx = __builtin_amdgcn_mfma_f32_32x32x16_f16(l1, sel_lds[64 + lane], accx, 0, 0, 0);
     }
   };
 
@@ -889,12 +904,16 @@ int mfma::pick_slices(int units, int ntile, int ncu, int cap) {
 
 // Workspace: one record ring per unit when the sequence is sliced in time. Sized for the
 // worst case of 256 compute units so that it does not depend on the device.
-size_t forward_mfma_ws_bytes(int B, int T, int D, int nb) {
+static size_t fwd_rec_bytes(int B, int T, int nb) {   // status word + record rings, 256-byte granules
   const int units = B * nb, ntile = (T + TT - 1) / TT;
   const int G = pick_slices(units, ntile, 256, FWD_MAX_SLICES);
-  if (G == 1) return 0;
   const size_t R = 8 * (size_t)G;
-  return 256 + (size_t)units * R * 2 * BS * sizeof(u64);
+  return 256 + (G == 1 ? 0 : (size_t)units * R * 2 * BS * sizeof(u64));
+}
+// ... followed by W_x in half precision
+size_t forward_mfma_ws_bytes(int B, int T, int D, int nb) {
+  const size_t w = (size_t)D * (D / nb) * 2;
+  return fwd_rec_bytes(B, T, nb) + ((w + 255) & ~(size_t)255);
 }
 
 template <int GMAX, int MERGE, bool PAD>
@@ -934,21 +953,26 @@ hipError_t launch_forward_mfma(const Problem &p, hipStream_t s) {
   a.R = 8 * a.G;
   const int grid = units * a.G;
   a.swizzle = (a.G > 1 && grid % 8 == 0) ? 1 : 0;
+  // workspace: status word, record rings (sized for 256 compute units), W_x in half precision
+  unsigned short *wx16 = (unsigned short *)((char *)p.ws + fwd_rec_bytes(p.B, p.T, p.nb));
+  a.wx16 = wx16;
+  const size_t n8 = (size_t)p.D * p.bs / 8;
+  const size_t n16 = (a.G == 1 ? 256 : 256 + (size_t)units * a.R * 2 * BS * sizeof(u64)) / 16;
+  {
+    const size_t n = n8 > n16 ? n8 : n16;
+    KernelTimer kt("prep_kernel", s);
+    hipLaunchKernelGGL(fwd_prep_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (uint4 *)p.ws, n16,
+                       (const uint4 *)p.W_x, (uint4 *)wx16, n8);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   if (a.G == 1) {
     a.rec = nullptr;
     a.err = nullptr;
-    // a workspace sized for more compute units than this device has: nothing waits here, the
-    // status word a later health check reads is cleared all the same
-    if (p.ws && p.ws_bytes >= 256) {
-      hipError_t e = launch_prep(p.ws, 256, s);
-      if (e != hipSuccess) return e;
-    }
     return launch_t<1>(a, grid, FWD_LDS, s);
   }
   a.err = (int *)p.ws;
   a.rec = (u64 *)((char *)p.ws + 256);
-  hipError_t e = launch_prep(p.ws, 256 + (size_t)units * a.R * 2 * BS * sizeof(u64), s);
-  if (e != hipSuccess) return e;
   return a.G <= 4 ? launch_t<4>(a, grid, FWD_LDS, s)
        : a.G <= 8 ? launch_t<8>(a, grid, FWD_LDS, s)
                   : launch_t<16>(a, grid, FWD_LDS, s);

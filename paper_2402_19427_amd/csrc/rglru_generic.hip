@@ -21,14 +21,27 @@ __device__ __forceinline__ float softplus_f(float z) {
 }
 __device__ __forceinline__ float sigmoid_f(float z) { return 1.f / (1.f + expf(-z)); }
 
+// total += v with the rounding error of the addition carried in `comp` (compensated summation:
+// the parameter gradients are sums over every (sequence, step) and have to stay inside the
+// fp32 contract however long they are)
+__device__ __forceinline__ void comp_add(float &total, float &comp, float v) {
+  const float y = v - comp;
+  const float t = total + y;
+  comp = (t - total) - y;
+  total = t;
+}
+
 struct Gates {
   float r, i, a, m;
+  float rc, ic;   // 1 - r, 1 - i as sigmoid(-p), sigmoid(-q): no cancellation when a gate saturates open
 };
 // eqs. (1)-(3): neg_cs = -c * softplus(-Lambda) = c * log sigmoid(Lambda)
 __device__ __forceinline__ Gates gate_math(float p, float q, float neg_cs) {
   Gates g;
   g.r = sigmoid_f(p);
   g.i = sigmoid_f(q);
+  g.rc = sigmoid_f(-p);
+  g.ic = sigmoid_f(-q);
   const float la = neg_cs * g.r;
   g.a = expf(la);
   g.m = sqrtf(-expm1f(2.f * la));  // sqrt(1 - a^2) without cancellation
@@ -240,9 +253,11 @@ __global__ void __launch_bounds__(NTHREADS) bwd_pointwise_kernel(Problem p, BwdW
   float *xs = smem;                 // [GT][bs]
   float *carry = smem + GT * bs;    // [bs]  a_{t+1} * delta_{t+1}
   float *sums = carry + bs;         // [3][bs] running db_a, db_x, dLambda of this sequence
+  float *comps = sums + 3 * bs;     // [3][bs] their compensation terms
   for (int j = tid; j < bs; j += NTHREADS) {
     carry[j] = p.dhT ? p.dhT[(size_t)b * p.D + g * bs + j] : 0.f;
     sums[j] = sums[bs + j] = sums[2 * bs + j] = 0.f;
+    comps[j] = comps[bs + j] = comps[2 * bs + j] = 0.f;
   }
   const int ntile = (p.T + GT - 1) / GT;
   for (int tile = ntile - 1; tile >= 0; --tile) {
@@ -278,8 +293,8 @@ __global__ void __launch_bounds__(NTHREADS) bwd_pointwise_kernel(Problem p, BwdW
           const float dg = delta * gt.m;
           const float di = dg * x;
           const float dr = neg_cs * dla;
-          const float dpv = dr * gt.r * (1.f - gt.r);
-          const float dqv = di * gt.i * (1.f - gt.i);
+          const float dpv = dr * gt.r * gt.rc;
+          const float dqv = di * gt.i * gt.ic;
           s_lam = fmaf(dla * gt.r, lam_scale, s_lam);
           s_ba += dpv;
           s_bx += dqv;
@@ -291,9 +306,9 @@ __global__ void __launch_bounds__(NTHREADS) bwd_pointwise_kernel(Problem p, BwdW
         }
       }
       carry[j] = cy;
-      sums[j] += s_ba;
-      sums[bs + j] += s_bx;
-      sums[2 * bs + j] += s_lam;
+      comp_add(sums[j], comps[j], s_ba);
+      comp_add(sums[bs + j], comps[bs + j], s_bx);
+      comp_add(sums[2 * bs + j], comps[2 * bs + j], s_lam);
     }
   }
   __syncthreads();
@@ -364,18 +379,24 @@ __global__ void __launch_bounds__(NTHREADS) bwd_conv_weight_kernel(Problem p, Bw
   const int nct = (p.T + w.tchunk - 1) / w.tchunk;
   const int b = blockIdx.y / nct, c = blockIdx.y % nct;
   const int t0 = c * w.tchunk, t1 = min(p.T, t0 + w.tchunk);
-  float s[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+  float s[5] = {0.f, 0.f, 0.f, 0.f, 0.f}, sc[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
   float u1 = input_at<AT>(p, b, t0 - 1, d), u2 = input_at<AT>(p, b, t0 - 2, d),
         u3 = input_at<AT>(p, b, t0 - 3, d);
-  for (int t = t0; t < t1; ++t) {
-    const size_t o = ((size_t)b * p.T + t) * p.D + d;
-    const float dx = w.dx[o], u0 = ldf((const AT *)p.u, o);
-    s[0] = fmaf(dx, u0, s[0]);
-    s[1] = fmaf(dx, u1, s[1]);
-    s[2] = fmaf(dx, u2, s[2]);
-    s[3] = fmaf(dx, u3, s[3]);
-    s[4] += dx;
-    u3 = u2; u2 = u1; u1 = u0;
+  for (int tc = t0; tc < t1; tc += 16) {   // short plain sums, added up with compensation
+    float l[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+    const int te = min(t1, tc + 16);
+    for (int t = tc; t < te; ++t) {
+      const size_t o = ((size_t)b * p.T + t) * p.D + d;
+      const float dx = w.dx[o], u0 = ldf((const AT *)p.u, o);
+      l[0] = fmaf(dx, u0, l[0]);
+      l[1] = fmaf(dx, u1, l[1]);
+      l[2] = fmaf(dx, u2, l[2]);
+      l[3] = fmaf(dx, u3, l[3]);
+      l[4] += dx;
+      u3 = u2; u2 = u1; u1 = u0;
+    }
+#pragma unroll
+    for (int k = 0; k < 5; ++k) comp_add(s[k], sc[k], l[k]);
   }
 #pragma unroll
   for (int k = 0; k < 5; ++k) w.partC[((size_t)blockIdx.y * 5 + k) * p.D + d] = s[k];
@@ -389,8 +410,8 @@ __global__ void __launch_bounds__(NTHREADS) reduce_parts_kernel(const float *par
                                                                 int rows, int D, RowOuts out) {
   const int d = blockIdx.x * NTHREADS + threadIdx.x, r = blockIdx.y;
   if (d >= D || !out.p[r]) return;
-  float s = 0.f;
-  for (int q = 0; q < nparts; ++q) s += part[((size_t)q * rows + r) * D + d];
+  float s = 0.f, c = 0.f;
+  for (int q = 0; q < nparts; ++q) comp_add(s, c, part[((size_t)q * rows + r) * D + d]);
   out.p[r][d] = s;
 }
 
@@ -402,6 +423,7 @@ __global__ void __launch_bounds__(NTHREADS) bwd_wgrad_kernel(Problem p, BwdWs w)
   const int g = blockIdx.x, j0 = blockIdx.y * 32, k0 = blockIdx.z * 32, bs = p.bs;
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
   float aa[2][2] = {{0.f, 0.f}, {0.f, 0.f}}, ax[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
+  float ca[2][2] = {{0.f, 0.f}, {0.f, 0.f}}, cx[2][2] = {{0.f, 0.f}, {0.f, 0.f}};   // compensation terms
   const size_t rows = (size_t)p.B * p.T;
   for (size_t r0 = 0; r0 < rows; r0 += 32) {
     __syncthreads();
@@ -415,16 +437,25 @@ __global__ void __launch_bounds__(NTHREADS) bwd_wgrad_kernel(Problem p, BwdWs w)
       qs[rr][cc] = (okr && j0 + cc < bs) ? w.dq[base + j0 + cc] : 0.f;
     }
     __syncthreads();
+    // the 32 rows of the chunk as plain sums, the chunks added up with compensation
+    float la[2][2] = {{0.f, 0.f}, {0.f, 0.f}}, lx[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
 #pragma unroll 8
     for (int rr = 0; rr < 32; ++rr) {
       const float x0 = xs[rr][tx], x1 = xs[rr][tx + 16];
       const float p0 = ps[rr][ty], p1 = ps[rr][ty + 16];
       const float q0 = qs[rr][ty], q1 = qs[rr][ty + 16];
-      aa[0][0] = fmaf(p0, x0, aa[0][0]); aa[0][1] = fmaf(p0, x1, aa[0][1]);
-      aa[1][0] = fmaf(p1, x0, aa[1][0]); aa[1][1] = fmaf(p1, x1, aa[1][1]);
-      ax[0][0] = fmaf(q0, x0, ax[0][0]); ax[0][1] = fmaf(q0, x1, ax[0][1]);
-      ax[1][0] = fmaf(q1, x0, ax[1][0]); ax[1][1] = fmaf(q1, x1, ax[1][1]);
+      la[0][0] = fmaf(p0, x0, la[0][0]); la[0][1] = fmaf(p0, x1, la[0][1]);
+      la[1][0] = fmaf(p1, x0, la[1][0]); la[1][1] = fmaf(p1, x1, la[1][1]);
+      lx[0][0] = fmaf(q0, x0, lx[0][0]); lx[0][1] = fmaf(q0, x1, lx[0][1]);
+      lx[1][0] = fmaf(q1, x0, lx[1][0]); lx[1][1] = fmaf(q1, x1, lx[1][1]);
     }
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        comp_add(aa[a][c], ca[a][c], la[a][c]);
+        comp_add(ax[a][c], cx[a][c], lx[a][c]);
+      }
   }
 #pragma unroll
   for (int a = 0; a < 2; ++a)

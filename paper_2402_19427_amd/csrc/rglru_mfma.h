@@ -11,6 +11,7 @@ constexpr int NTHR = NWAVE * 64;
 constexpr int TT = 32;           // time steps per tile
 constexpr int XS = BS + 8;       // LDS row stride in bf16 elements (528 B: conflict-free b128 reads)
 constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
 constexpr int XT_ELEMS = TT * XS;                   // one [32][264] bf16 tile
 constexpr int XS_BYTES = 4 * XT_ELEMS * 2;          // two buffers x (high part, low part) of the x tile
 constexpr int CONST_BYTES = 64 * 32 + 128 * 48;      // selection operands + Conv1D taps per lane
@@ -37,6 +38,56 @@ __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {  // v_cvt_pk
 __device__ __forceinline__ void split_bf16(float x0, float x1, unsigned &hi_pk, unsigned &lo_pk) {
   hi_pk = pack_bf16(x0, x1);
   lo_pk = pack_bf16(x0 - bf_lo(hi_pk), x1 - bf_hi(hi_pk));
+}
+
+// ---- half-precision operands of the gate products. The activations are bf16 in memory, but
+// x_t (the Conv1D output, fp32 in registers) enters the matrix cores as IEEE half precision:
+// 11 significant bits instead of 8 at the same MFMA rate. log a_t = c log(sigma(Lambda)) r_t
+// and the closed side of a sigmoid amplify the rounding of the pre-activations, and with bf16
+// x_t that rounding was the largest single error of the path. The bf16 gate weights convert
+// exactly (7-bit significands; below 6.1e-5 they land on half precision's subnormal grid with
+// an absolute error under 3e-8).
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ unsigned pack_f16(float lo, float hi) {   // v_cvt_pkrtz_f16_f32
+  const auto h = __builtin_amdgcn_cvt_pkrtz(lo, hi);
+  return __builtin_bit_cast(unsigned, h);
+}
+__device__ __forceinline__ float f16_lo(unsigned v) {
+  return (float)__builtin_bit_cast(f16x2, v)[0];
+}
+__device__ __forceinline__ float f16_hi(unsigned v) {
+  return (float)__builtin_bit_cast(f16x2, v)[1];
+}
+// x = high + low with both parts in half precision (21 bits or more in total; values beyond
+// +-65504 saturate): the gate products read the high part, x itself is rebuilt from both
+__device__ __forceinline__ void split_f16(float x0, float x1, unsigned &hi_pk, unsigned &lo_pk) {
+  hi_pk = pack_f16(x0, x1);
+  lo_pk = pack_f16(x0 - f16_lo(hi_pk), x1 - f16_hi(hi_pk));
+}
+// eight bf16 weights (an MFMA fragment as it lies in memory) as half precision
+__device__ __forceinline__ f16x8 w_to_f16(bf16x8 w) {
+  const u32x4_t v = __builtin_bit_cast(u32x4_t, w);
+  u32x4_t o;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) o[k] = pack_f16(bf_lo(v[k]), bf_hi(v[k]));
+  return __builtin_bit_cast(f16x8, o);
+}
+
+// 1 - a^2 for a decay a = exp2(l2) <= 1 given with its base-2 logarithm l2 <= 0, without the
+// cancellation of 1 - a*a as a -> 1 (the reason Appendix A evaluates eq. (3) in log space):
+// 1 - a^2 = -expm1(z) with z = 2 ln2 l2. The series -z - z^2/2 never exceeds the true value
+// (it falls short by |z|^3/6); 1 - a*a carries the rounding of a, up to 1.2e-7 either way, and
+// is therefore lowered by 2^-22 = 2.4e-7 so that it never exceeds the true value either. The
+// larger of the two is then the series for |z| < 9e-3 (relative error < 1.4e-5) and 1 - a*a
+// beyond |z| = 1.1e-2 (absolute error < 3.6e-7, relative < 3.3e-5): three instructions more
+// than the cancelling form.
+__device__ __forceinline__ float one_minus_sq(float a, float l2) {
+  constexpr float C = 2.f * LN2;
+  const float ser = l2 * fmaf(l2, -0.5f * C * C, -C);
+  return __builtin_fmaxf(ser, fmaf(-a, a, 1.f - 0x1p-22f));
 }
 
 // 64-bit address made provably wave-uniform (kept in scalar registers), for buffer descriptors

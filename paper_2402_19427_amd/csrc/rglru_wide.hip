@@ -282,12 +282,17 @@ gates_wide_kernel(WideArgs a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const float rg = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-LOG2E * accp[mi][r]));
-      if (BWD) rr[r] = rg;
+      // (the backward keeps the pre-activation, not r_t: half precision has no relative
+      // accuracy left for r_t below 6e-5, a recurrence gate closed that far still decides
+      // sqrt(1 - a_t^2), and the logit is as accurate as r_t everywhere else)
+      if (BWD) rr[r] = fminf(fmaxf(accp[mi][r], -60000.f), 60000.f);
       const float la = kdn * rg;
       const float av = __builtin_amdgcn_exp2f(LOG2E * la);
-      const float mm = __builtin_amdgcn_sqrtf(fmaf(-av, av, 1.f));
+      const float mm = __builtin_amdgcn_sqrtf(one_minus_sq(av, LOG2E * la));
       const float ig = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-LOG2E * accq[mi][r]));
-      bv[r] = BWD ? ig : mm * ig * accx[mi][r];
+      // (the backward keeps the logit of i_t as well: 1 - i_t of an open input gate is not
+      // representable next to i_t in half precision)
+      bv[r] = BWD ? fminf(fmaxf(accq[mi][r], -60000.f), 60000.f) : mm * ig * accx[mi][r];
       ot_mine[r * OT] = (unsigned short)(pack_bf16(la, 0.f) & 0xffff);
     }
     store_staged_tile_s<OT, 0>(otile, lane, la_rsrc, o_voff, mrow * row_bytes, row_bytes, nrows);
@@ -577,7 +582,7 @@ decode_wide_kernel(DecWideArgs a) {
   for (int r = 0; r < 16; ++r) {
     const float rg = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-accp[r]));
     const float av_ = __builtin_amdgcn_exp2f(kd * rg);
-    const float mm = __builtin_amdgcn_sqrtf(fmaf(-av_, av_, 1.f));
+    const float mm = __builtin_amdgcn_sqrtf(one_minus_sq(av_, kd * rg));
     const float eq = __builtin_amdgcn_exp2f(-accq[r]);
     const float il = __builtin_amdgcn_rcpf(fmaf(eq, LOG2E, LOG2E));   // sigmoid(q) / log2 e
     const float hn = fmaf(av_, rh[r], (mm * il) * accx[r]);
@@ -696,7 +701,7 @@ __global__ void __launch_bounds__(256) conv_rows_kernel(ConvArgs a) {
 constexpr int PT_STEPS = 128;   // steps per thread
 struct PointArgs {
   Problem p;
-  const unsigned short *xh, *rv, *iv, *delta;   // x_t, r_t, i_t, delta_t in half precision, all [B][T][D]
+  const unsigned short *xh, *rv, *iv, *delta;   // x_t, the logits of r_t and i_t, delta_t in half precision, all [B][T][D]
   float *x, *dp, *dq, *dx;                      // [B][T][D] fp32
   float *part;                                  // [chunk][B][3][D]
   unsigned short *dpqh;                         // [B][T][nb][2][bs] half precision: dp and dq of a block side by
@@ -718,17 +723,20 @@ __global__ void __launch_bounds__(256) point_adjoint_kernel(PointArgs a) {
   const int gb_ = d / p.bs, cb_ = d - gb_ * p.bs;
   for (int t = t0; t < t1; ++t) {
     const size_t o = ((size_t)b * p.T + t) * p.D + d;
-    const float r = half_bits(a.rv[o]), la = neg_cs * r;
+    const float pl = half_bits(a.rv[o]);   // the logit of r_t
+    const float r = 1.f / (1.f + expf(-pl)), rc = 1.f / (1.f + expf(pl)), la = neg_cs * r;
     const float av = expf(la), mv = sqrtf(-expm1f(2.f * la));
-    const float iv = half_bits(a.iv[o]), x = half_bits(a.xh[o]), delta = half_bits(a.delta[o]);
+    const float ql = half_bits(a.iv[o]);   // the logit of i_t
+    const float iv = 1.f / (1.f + expf(-ql)), ic = 1.f / (1.f + expf(ql));
+    const float x = half_bits(a.xh[o]), delta = half_bits(a.delta[o]);
     const float hprev = t > 0 ? bf_lo((unsigned)((const unsigned short *)p.y_in)[o - p.D])
                               : (p.h0 ? p.h0[(size_t)b * p.D + d] : 0.f);
     const float gin = iv * x;
     const float corr = mv > 0.f ? av * gin / mv : 0.f;   // the term vanishes with the gate as m -> 0
     const float dla = delta * av * (hprev - corr);
     const float dg = delta * mv;
-    const float dpv = neg_cs * dla * r * (1.f - r);
-    const float dqv = dg * x * iv * (1.f - iv);
+    const float dpv = neg_cs * dla * r * rc;
+    const float dqv = dg * x * iv * ic;
     s_lam = fmaf(dla * r, lam_scale, s_lam);
     s_ba += dpv;
     s_bx += dqv;
@@ -833,6 +841,57 @@ __global__ void __launch_bounds__(256) transpose16_kernel(const unsigned short *
     if (c0 + i < C && r0 + 2 * tx < R)
       *(unsigned *)(dst + (size_t)(c0 + i) * R + r0 + 2 * tx) =
           (unsigned)tile[2 * tx][i] | ((unsigned)tile[2 * tx + 1][i] << 16);
+}
+
+// ---- range of the upstream gradient. The backward in passes keeps delta_t, dp_t and dq_t in IEEE
+// half precision (operands of the f16 matrix-core products), whose exponent range is narrow,
+// while gradients are linear in dy and arrive at any scale (a mean-reduced loss gives 1e-5 ..
+// 1e-7 per element). The passes therefore run on dy * S and dhT * S with S the power of two that
+// brings max(|dy|, |dhT|) into [16, 32) - exact in bf16 and fp32 - and every result is multiplied
+// by 1 / S at the end.
+// bits of max |v| over n bf16 values (the bit patterns of non-negative floats order like integers)
+__global__ void __launch_bounds__(256) absmax_bf16_kernel(const unsigned short *v, size_t n, unsigned *out) {
+  unsigned m = 0;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const unsigned b = ((unsigned)v[i] & 0x7fffu) << 16;
+    if (b <= 0x7f800000u) m = max(m, b);   // NaNs are left out of the range estimate
+  }
+  for (int o = 32; o > 0; o >>= 1) m = max(m, (unsigned)__shfl_xor((int)m, o));
+  if ((threadIdx.x & 63) == 0 && m) atomicMax(out, m);
+}
+__global__ void __launch_bounds__(256) absmax_f32_kernel(const float *v, size_t n, unsigned *out) {
+  unsigned m = 0;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const unsigned b = __float_as_uint(v[i]) & 0x7fffffffu;
+    if (b <= 0x7f800000u) m = max(m, b);
+  }
+  for (int o = 32; o > 0; o >>= 1) m = max(m, (unsigned)__shfl_xor((int)m, o));
+  if ((threadIdx.x & 63) == 0 && m) atomicMax(out, m);
+}
+// sc[0] = bits of the maximum (in), sc[1] = S, sc[2] = 1 / S (out)
+__global__ void scale_setup_kernel(float *sc) {
+  const unsigned bits = __float_as_uint(sc[0]);
+  // max in [2^(e+4), 2^(e+5)): the scaled maximum lands in [16, 32). The adjoints stay below
+  // a few thousand times that, inside half precision's 65504, and the small ones (channels
+  // whose gates are nearly shut) keep four more bits above its subnormal range.
+  int e = (int)(bits >> 23) - 127 - 4;
+  if (bits == 0 || bits >= 0x7f800000u) e = 0;   // all zero, or infinite: leave the values alone
+  if (e > 126) e = 126;
+  if (e < -126) e = -126;
+  sc[1] = __uint_as_float((unsigned)(127 - e) << 23);
+  sc[2] = __uint_as_float((unsigned)(127 + e) << 23);
+}
+// dst = src * sc[which] for bf16 values (a power of two: exact unless the result leaves the range)
+__global__ void __launch_bounds__(256) scale_bf16_kernel(const unsigned short *src, unsigned short *dst, size_t n,
+                                                         const float *sc, int which) {
+  const float f = sc[which];
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256)
+    dst[i] = (unsigned short)(pack_bf16(bf_lo((unsigned)src[i]) * f, 0.f) & 0xffffu);
+}
+__global__ void __launch_bounds__(256) scale_f32_kernel(const float *src, float *dst, size_t n, const float *sc,
+                                                        int which) {
+  const float f = sc[which];
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i] * f;
 }
 
 // partA[b][r][d] = sum over chunks, in a fixed order
@@ -944,7 +1003,7 @@ namespace rglru {
 namespace {
 struct BwdWidePlan {
   size_t generic, n2, off_x, off_xh, off_la, off_iv, off_rv, off_delta, off_part, off_dpqh, off_xT, off_wf, wf,
-      off_dpqT, off_wt, off_scan, total;
+      off_dpqT, off_wt, off_dys, off_dhTs, off_scale, off_scan, total;
   int nch;
 };
 BwdWidePlan plan_bwd_wide(int B, int T, int D, int nb) {
@@ -966,6 +1025,9 @@ BwdWidePlan plan_bwd_wide(int B, int T, int D, int nb) {
   q.off_xT = off; off += q.n2;
   q.off_dpqT = off; off += 2 * q.n2;
   q.off_wt = off; off += al256((size_t)nb * (D / nb) * 2 * (D / nb) * 2);
+  q.off_dys = off; off += q.n2;                               // dy * S
+  q.off_dhTs = off; off += al256((size_t)B * D * 4);          // dhT * S
+  q.off_scale = off; off += 256;                              // max bits, S, 1 / S
   q.off_scan = off; off += scan_tiled_ws_bytes(B, T, D);
   q.total = off;
   return q;
@@ -986,10 +1048,34 @@ size_t backward_wide_flag_offset(int B, int T, int D, int nb) {   // 0 if the sc
   return scan_tiled_ws_bytes(B, T, D) ? plan_bwd_wide(B, T, D, nb).off_scan : 0;
 }
 
-hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
-  const BwdWidePlan q = plan_bwd_wide(p.B, p.T, p.D, p.nb);
-  char *ws = (char *)p.ws;
+static unsigned stream_grid(size_t n) { return (unsigned)((n + 255) / 256 < 2048 ? (n + 255) / 256 : 2048); }
+
+hipError_t launch_backward_wide(const Problem &p_in, hipStream_t s) {
+  const BwdWidePlan q = plan_bwd_wide(p_in.B, p_in.T, p_in.D, p_in.nb);
+  char *ws = (char *)p_in.ws;
   hipError_t e;
+  // the passes run on dy * S and dhT * S (see absmax_bf16_kernel); results are unscaled at the end
+  Problem p = p_in;
+  float *sc = (float *)(ws + q.off_scale);
+  const size_t N = (size_t)p.B * p.T * p.D, BD = (size_t)p.B * p.D;
+  {
+    KernelTimer kt("grad_scale_kernels", s);
+    if ((e = launch_clear(sc, 256, s)) != hipSuccess) return e;
+    hipLaunchKernelGGL(absmax_bf16_kernel, dim3(stream_grid(N)), dim3(256), 0, s, (const unsigned short *)p_in.dy, N,
+                       (unsigned *)sc);
+    if (p_in.dhT)
+      hipLaunchKernelGGL(absmax_f32_kernel, dim3(stream_grid(BD)), dim3(256), 0, s, p_in.dhT, BD, (unsigned *)sc);
+    hipLaunchKernelGGL(scale_setup_kernel, dim3(1), dim3(1), 0, s, sc);
+    hipLaunchKernelGGL(scale_bf16_kernel, dim3(stream_grid(N)), dim3(256), 0, s, (const unsigned short *)p_in.dy,
+                       (unsigned short *)(ws + q.off_dys), N, (const float *)sc, 1);
+    p.dy = ws + q.off_dys;
+    if (p_in.dhT) {
+      hipLaunchKernelGGL(scale_f32_kernel, dim3(stream_grid(BD)), dim3(256), 0, s, p_in.dhT,
+                         (float *)(ws + q.off_dhTs), BD, (const float *)sc, 1);
+      p.dhT = (const float *)(ws + q.off_dhTs);
+    }
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   {
     KernelTimer kt("conv_rows_kernel", s);
     ConvArgs c;
@@ -1157,7 +1243,21 @@ hipError_t launch_backward_wide(const Problem &p, hipStream_t s) {
     hipLaunchKernelGGL(conv_adjoint_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, ca);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  return launch_backward_generic_tail(p, true, s, false, !mfma_wgrad, !own_du);
+  if ((e = launch_backward_generic_tail(p, true, s, false, !mfma_wgrad, !own_du)) != hipSuccess) return e;
+  {
+    KernelTimer kt("grad_scale_kernels", s);
+    hipLaunchKernelGGL(scale_bf16_kernel, dim3(stream_grid(N)), dim3(256), 0, s, (const unsigned short *)p.du,
+                       (unsigned short *)p.du, N, (const float *)sc, 2);
+    const size_t nw = (size_t)p.nb * p.bs * p.bs, D = (size_t)p.D;
+    float *outs[8] = {p.g.dW_a, p.g.dW_x, p.g.db_a, p.g.db_x, p.g.dLambda, p.g.dconv_w, p.g.dconv_b, p.dh0};
+    const size_t ns[8] = {nw, nw, D, D, D, 4 * D, D, BD};
+    for (int i = 0; i < 8; ++i)
+      if (outs[i])
+        hipLaunchKernelGGL(scale_f32_kernel, dim3(stream_grid(ns[i])), dim3(256), 0, s, (const float *)outs[i],
+                           outs[i], ns[i], (const float *)sc, 2);
+    e = hipGetLastError();
+  }
+  return e;
 }
 
 bool decode_wide_supported(const Problem &p, bool bf) {

@@ -241,11 +241,14 @@ def test_decode_step_merge_validation():
 
 def test_workspace_sizes_for_narrower_gate_blocks():
     # 16 blocks of 160 channels (bf16): forward in the padded tile needs the record rings of the
-    # tuned kernel; the backward a widened copy (four activation tensors of nb*256 channels) plus
-    # the tuned backward's workspace at that width
+    # tuned kernel and, like it, W_x once more in half precision; the backward a widened copy
+    # (four activation tensors of nb*256 channels) plus the tuned backward's workspace at that width
     narrow = R.make_shape(8, 2048, 2560, 16, R.BF16)
     wide = R.make_shape(8, 2048, 4096, 16, R.BF16)
-    assert R.rglru_workspace_bytes(narrow, R.OP_FORWARD) == R.rglru_workspace_bytes(wide, R.OP_FORWARD) > 0
+    assert (R.rglru_workspace_bytes(narrow, R.OP_FORWARD) - 16 * 160 * 160 * 2
+            == R.rglru_workspace_bytes(wide, R.OP_FORWARD) - 16 * 256 * 256 * 2 > 0)
+    # one workgroup per (sequence, block), no records: the status word and the weight copy
+    assert R.rglru_workspace_bytes(R.make_shape(16, 4096, 4096, 16, R.BF16), R.OP_FORWARD) == 256 + 16 * 256 * 256 * 2
     need = R.rglru_workspace_bytes(narrow, R.OP_BACKWARD)
     inner = R.rglru_workspace_bytes(wide, R.OP_BACKWARD)
     assert need > inner + 4 * 8 * 2048 * 4096 * 2 and need % 256 == 0

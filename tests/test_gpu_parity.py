@@ -15,8 +15,9 @@ import rglru_inputs as gen
 pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-5, "bf16": 2e-2}
-# parameter gradients are long sums of rounded products; the bf16 bar applies to each tensor
-GRAD_TOL = {"f32": 2e-5, "bf16": 2e-2}
+# parameter gradients are long sums of rounded products (compensated in the fp32 kernels); the
+# same bars apply to each tensor
+GRAD_TOL = {"f32": 1e-5, "bf16": 2e-2}
 
 
 def runner():
@@ -509,8 +510,8 @@ def test_workspace_status_reports_an_expired_wait():
     with pytest.raises(R.RglruError) as e:
         R.rglru_workspace_status(ssh, R.OP_SCAN, ws)
     assert e.value.code == R.ERR_TIMEOUT
-    # shapes that run without time slices have nothing to report
-    R.rglru_workspace_status(R.make_shape(40, 70, 2048, 8, R.BF16), R.OP_FORWARD, None)
+    # shapes that need no workspace have nothing to report
+    R.rglru_workspace_status(R.make_shape(40, 70, 2048, 8, R.F32), R.OP_FORWARD, None)
 
 
 # ------------------------------------------------------------------ the block's merge as epilogue
