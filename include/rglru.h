@@ -178,6 +178,29 @@ int rglru_forward(const rglru_shape *shape, const rglru_params *params, const vo
                   void *conv_state_out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * rglru_forward without a workspace argument, for callers that cannot allocate device memory or
+ * carry a workspace along: code that runs under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc. The scratch rglru_forward takes from its workspace (status
+ * word, carry records of sequences sliced in time, W_x in half precision) lives in a static
+ * device array of RGLRU_STATIC_SCRATCH_BYTES inside the library instead; each GPU the library
+ * runs on holds its own copy until the process ends. The call allocates and frees nothing.
+ *   Arguments, results and error codes: as rglru_forward (same kernels, same results bit for bit).
+ *   RGLRU_ERR_WORKSPACE if rglru_workspace_bytes(shape, RGLRU_OP_FORWARD) exceeds
+ *   RGLRU_STATIC_SCRATCH_BYTES (the five workloads this library is tuned for need 2 - 9 MB);
+ *   nothing is launched then.
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on the same GPU
+ * (different streams or threads) race on it - serialise them, or give the overlapping ones a
+ * workspace of their own through rglru_forward. The array keeps the last call's contents; the
+ * call clears what must start at zero with a kernel on `stream`, so it may be captured into a
+ * HIP graph after one ordinary call on that GPU (the first call on a GPU looks the array's
+ * address up).
+ */
+#define RGLRU_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+int rglru_forward_static(const rglru_shape *shape, const rglru_params *params, const void *u,
+                         const float *h0, const void *conv_state_in, int64_t pos0, void *y,
+                         float *hT, void *conv_state_out, void *stream);
+
+/*
  * One decode step (Section 5; state sizes of Appendix F): the forward equations for one new
  * token per sequence, with both states updated in place.
  *   u_t        [B][D] act, the new input of every sequence.

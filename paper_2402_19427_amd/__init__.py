@@ -14,7 +14,7 @@ _EXPORTS = (
     "rglru_backward_merge", "OP_CONV1D", "OP_DECODE", "OP_FORWARD", "OP_SCAN", "SCAN_LOG_A", "SCAN_ADJOINT",
     "SCAN_NO_INPUT_SCALE", "rglru_scan", "LIB_PATH", "ParamGrads", "Params",
     "RglruError", "Shape", "make_param_grads", "make_params", "make_shape", "rglru_backward",
-    "rglru_conv1d", "rglru_decode_step", "rglru_decode_step_at", "rglru_forward", "rglru_last_error", "rglru_version",
+    "rglru_conv1d", "rglru_forward_static", "STATIC_SCRATCH_BYTES", "rglru_decode_step", "rglru_decode_step_at", "rglru_forward", "rglru_last_error", "rglru_version",
     "rglru_workspace_bytes", "rglru_timing_enable", "rglru_timing_select", "rglru_timing_count", "rglru_timing_get",
 )
 __all__ = list(_EXPORTS)

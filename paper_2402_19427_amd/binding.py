@@ -16,6 +16,7 @@ OP_CONV1D, OP_FORWARD, OP_DECODE, OP_BACKWARD, OP_SCAN = 0, 1, 2, 3, 4
 OP_FORWARD_MERGE, OP_BACKWARD_MERGE = 5, 6
 MERGE_GELU_TANH, MERGE_SEPARATE = 1, 2
 SCAN_LOG_A, SCAN_NO_INPUT_SCALE, SCAN_ADJOINT = 1, 2, 4
+STATIC_SCRATCH_BYTES = 16 << 20
 
 
 class Shape(ctypes.Structure):
@@ -54,6 +55,8 @@ def _load():
     sp, pp, gp = ctypes.POINTER(Shape), ctypes.POINTER(Params), ctypes.POINTER(ParamGrads)
     lib.rglru_conv1d.argtypes = [sp, vp, vp, vp, vp, i64, vp, vp, vp]
     lib.rglru_forward.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp, vp, vp, sz, vp]
+    lib.rglru_forward_static.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp, vp, vp]
+    lib.rglru_forward_static.restype = ctypes.c_int
     lib.rglru_decode_step.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp]
     lib.rglru_decode_step_at.argtypes = [sp, pp, vp, vp, vp, vp, vp, vp]
     lib.rglru_backward.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp, vp, vp, vp, gp, vp, sz, vp]
@@ -168,6 +171,12 @@ def rglru_forward(shape, params, u, h0, conv_state_in, pos0, y, hT, conv_state_o
                               _addr(conv_state_in), pos0, _addr(y), _addr(hT),
                               _addr(conv_state_out), _addr(workspace), workspace_bytes,
                               _stream(stream)))
+
+
+def rglru_forward_static(shape, params, u, h0, conv_state_in, pos0, y, hT, conv_state_out, stream=None):
+    _check(_lib.rglru_forward_static(_ref(shape), _ref(params), _addr(u), _addr(h0),
+                                     _addr(conv_state_in), pos0, _addr(y), _addr(hT),
+                                     _addr(conv_state_out), _stream(stream)))
 
 
 def rglru_decode_step(shape, params, u_t, h, conv_state, pos, y_t, stream=None):

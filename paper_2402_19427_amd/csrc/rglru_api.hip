@@ -22,6 +22,17 @@ int fail(int code, const char *fmt, ...) {
   return code;
 }
 
+}  // namespace
+
+void rglru::set_last_error(const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+namespace {
+
 bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 size_t act_size(const rglru_shape *s) { return s->act_dtype == RGLRU_BF16 ? 2 : 4; }

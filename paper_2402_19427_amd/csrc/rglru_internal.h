@@ -79,6 +79,9 @@ struct ScanProblem {
   size_t ws_bytes;
 };
 
+// sets the calling thread's error string (printf-style)
+void set_last_error(const char *fmt, ...);
+
 // Benchmark timing: brackets a kernel launch with HIP events when timing is enabled on this
 // thread (see rglru_timing_enable in rglru.h). Usage: { KernelTimer t("name", stream); launch; }
 struct KernelTimer {
