@@ -291,8 +291,10 @@ int rglru_decode_step_merge(const rglru_shape *shape, const rglru_params *params
 /*
  * Backward of rglru_forward_merge for the loss L = sum(dout * out) + sum(dhT * hT): the
  * adjoint of the merge, dy = dout * GeLU(branch) and dbranch = dout * y * GeLU'(branch),
- * followed by rglru_backward on dy (dy is rounded to act in between, as it would be between
- * two separate calls).
+ * followed by rglru_backward on dy. dy is not rounded to act in between (in bf16 storage it
+ * travels as the sum of two bf16 tensors in the workspace, 16 significant bits): the reverse scan
+ * accumulates dy over the memory of the recurrence, and an 8-bit dy would move single elements
+ * of dW_a by several times the bf16 tolerance.
  *   branch, y  [B][T][D] act: the forward call's input and its saved y.
  *   dout       [B][T][D] act, upstream gradient of out.
  *   dbranch    [B][T][D] act, written. May alias dout or branch.

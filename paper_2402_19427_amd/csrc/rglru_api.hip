@@ -121,10 +121,13 @@ void fill_params(Problem &q, const rglru_shape *s, const rglru_params *p) {
   q.conv_w = p->conv_w; q.conv_b = p->conv_b;
 }
 
-size_t merge_dy_bytes(const rglru_shape *s) {
+// dy between the merge adjoint and the backward: one fp32 tensor, or in bf16 storage two bf16
+// tensors (dy as stored and what its rounding took away)
+size_t merge_dy_part(const rglru_shape *s) {
   const size_t n = (size_t)s->B * s->T * s->D * (s->act_dtype == RGLRU_BF16 ? 2 : 4);
   return (n + 255) & ~(size_t)255;
 }
+size_t merge_dy_bytes(const rglru_shape *s) { return (s->act_dtype == RGLRU_BF16 ? 2 : 1) * merge_dy_part(s); }
 
 // narrower gate blocks in bf16: the backward runs on a copy widened to 256-channel blocks
 bool backward_via_padding(const rglru_shape *s) {
@@ -158,7 +161,7 @@ size_t workspace_need(const rglru_shape *s, int op) {
       if (s->act_dtype == RGLRU_BF16 && s->D % 256 == 0 && s->T >= 1)
         return scan_tiled_ws_bytes(s->B, s->T, s->D);
       return 0;
-    case RGLRU_OP_BACKWARD_MERGE:   // dy between the merge adjoint and the backward, then the backward's own
+    case RGLRU_OP_BACKWARD_MERGE:   // dy (+ dy_lo) between the merge adjoint and the backward, then the backward's own
       return merge_dy_bytes(s) + workspace_need(s, RGLRU_OP_BACKWARD);
     case RGLRU_OP_FORWARD_MERGE:
     case RGLRU_OP_FORWARD:
@@ -490,18 +493,22 @@ int rglru_decode_step_at(const rglru_shape *shape, const rglru_params *params, c
   return RGLRU_OK;
 }
 
-int rglru_backward(const rglru_shape *shape, const rglru_params *params, const void *u,
-                   const float *h0, const void *conv_state_in, int64_t pos0, const void *y,
-                   const void *dy, const float *dhT, void *du, float *dh0,
-                   const rglru_param_grads *grads, void *workspace, size_t workspace_bytes,
-                   void *stream) {
+}  // extern "C"
+
+namespace {
+// rglru_backward with the upstream gradient given as dy + dy_lo (dy_lo null: dy alone)
+int backward_run(const rglru_shape *shape, const rglru_params *params, const void *u,
+                 const float *h0, const void *conv_state_in, int64_t pos0, const void *y,
+                 const void *dy, const void *dy_lo, const float *dhT, void *du, float *dh0,
+                 const rglru_param_grads *grads, void *workspace, size_t workspace_bytes,
+                 void *stream) {
   CHECK(backward_checks(shape, params, u, h0, conv_state_in, pos0, y, dy, dhT, du, dh0, grads, workspace,
                         workspace_bytes));
   Problem q;
   memset(&q, 0, sizeof(q));
   fill_params(q, shape, params);
   q.pos0 = pos0; q.u = u; q.h0 = h0; q.state_in = conv_state_in;
-  q.y_in = y; q.dy = dy; q.dhT = dhT; q.du = du; q.dh0 = dh0; q.g = *grads;
+  q.y_in = y; q.dy = dy; q.dy_lo = dy_lo; q.dhT = dhT; q.du = du; q.dh0 = dh0; q.g = *grads;
   q.ws = workspace; q.ws_bytes = workspace_bytes;
   const bool bf = shape->act_dtype == RGLRU_BF16;
   hipError_t e;
@@ -530,6 +537,18 @@ int rglru_backward(const rglru_shape *shape, const rglru_params *params, const v
   if (e != hipSuccess) return hip_fail(e, "backward launch");
   g_err[0] = 0;
   return RGLRU_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int rglru_backward(const rglru_shape *shape, const rglru_params *params, const void *u,
+                   const float *h0, const void *conv_state_in, int64_t pos0, const void *y,
+                   const void *dy, const float *dhT, void *du, float *dh0,
+                   const rglru_param_grads *grads, void *workspace, size_t workspace_bytes,
+                   void *stream) {
+  return backward_run(shape, params, u, h0, conv_state_in, pos0, y, dy, nullptr, dhT, du, dh0, grads, workspace,
+                      workspace_bytes, stream);
 }
 
 int rglru_forward_merge(const rglru_shape *shape, const rglru_params *params, const void *u,
@@ -644,17 +663,18 @@ int rglru_backward_merge(const rglru_shape *shape, const rglru_params *params, c
   // the rest of the arguments are checked by rglru_backward before anything is launched:
   // a dry run of its checks first, so that a bad argument leaves every output untouched
   const size_t dyb = merge_dy_bytes(shape);
+  const bool bf = shape->act_dtype == RGLRU_BF16;
   void *dy = workspace;
+  void *dy_lo = bf ? (char *)workspace + merge_dy_part(shape) : nullptr;
   void *rest = (char *)workspace + dyb;
   CHECK(backward_checks(shape, params, u, h0, conv_state_in, pos0, y, dy, dhT, du, dh0, grads, rest,
                         workspace_bytes - dyb));
-  const bool bf = shape->act_dtype == RGLRU_BF16;
-  hipError_t e = launch_merge_backward(y, branch, dout, dy, dbranch,
+  hipError_t e = launch_merge_backward(y, branch, dout, dy, dy_lo, dbranch,
                                        (size_t)shape->B * shape->T * shape->D, bf,
                                        (flags & RGLRU_MERGE_GELU_TANH) != 0, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "merge launch");
-  return rglru_backward(shape, params, u, h0, conv_state_in, pos0, y, dy, dhT, du, dh0, grads, rest,
-                        workspace_bytes - dyb, stream);
+  return backward_run(shape, params, u, h0, conv_state_in, pos0, y, dy, dy_lo, dhT, du, dh0, grads, rest,
+                      workspace_bytes - dyb, stream);
 }
 
 }  // extern "C"

@@ -11,8 +11,10 @@
 //        dp_t  = -c softplus(-Lambda) dla_t r_t (1 - r_t)
 //        dq_t  = delta_t m_t g_t (1 - i_t)
 //        dxd_t = delta_t m_t i_t                 (the part of dx that bypasses the gates)
-//     and writes dp, dq (bf16), dxd (24 bits: sign, exponent, 15 mantissa bits; four steps of a
-//     channel packed in 12 bytes) plus per-channel sums for db_a, db_x, dLambda.
+//     and writes S dp, S dq in half precision (S: the power of two that brings max |dy| into
+//     [32, 64), found by a pass over dy beforehand; the dgrad and wgrad kernels undo it), dxd (24
+//     bits: sign, exponent, 15 mantissa bits; four steps of a channel packed in 12 bytes) plus
+//     per-channel sums for db_a, db_x, dLambda.
 //     Time slices of one sequence exchange tile aggregates (prod a, local eps) as tagged 8-byte
 //     records; a first sweep over the tile computes a_t and the aggregate, a second sweep the
 //     adjoints once the incoming eps is known.
@@ -34,13 +36,17 @@ constexpr int TR_BYTES = BS * TS * 2;            // one transposed tile
 // LDS of the gates kernel: x tile (high, low) | constants | dy^T | y^T | r_t of the tile |
 // W_x fragments
 constexpr int G_NRES = 4;                        // K-steps of W_x resident in registers (5 without time slices)
-constexpr int G_NLDS = 5;                        // further K-steps of W_x resident in LDS
+// further K-steps of W_x resident in LDS (an upstream gradient given as two bf16 tensors needs
+// a second transposed tile, which takes the room of two of them)
+constexpr int g_nlds(bool dylo) { return dylo ? 3 : 5; }
 constexpr int G_OFF_CONST = XS_BYTES / 2;        // one x buffer: the kernel has two barriers per tile
 constexpr int G_OFF_DYT = G_OFF_CONST + CONST_BYTES;
 constexpr int G_OFF_YT = G_OFF_DYT + TR_BYTES;
-constexpr int G_OFF_HOLD = G_OFF_YT + TR_BYTES;
-constexpr int G_OFF_WX = G_OFF_HOLD + HOLD_BYTES / 2;
-constexpr int G_LDS = G_OFF_WX + G_NLDS * NWAVE * 64 * 16;
+constexpr int G_OFF_DYLO = G_OFF_YT + TR_BYTES;   // only with dy_lo
+constexpr int g_off_hold(bool dylo) { return G_OFF_YT + TR_BYTES + (dylo ? TR_BYTES : 0); }
+constexpr int g_off_wx(bool dylo) { return g_off_hold(dylo) + HOLD_BYTES / 2; }
+constexpr int g_lds(bool dylo) { return g_off_wx(dylo) + g_nlds(dylo) * NWAVE * 64 * 16; }
+static_assert(g_lds(false) <= 160 * 1024 && g_lds(true) <= 160 * 1024, "LDS of the gates kernel");
 
 
 struct BwdArgs {
@@ -50,7 +56,8 @@ struct BwdArgs {
   int *err;
   int swizzle;
   const unsigned short *wxf;              // W_x in fragment order (bwd_prep_kernel)
-  unsigned short *dpo, *dqo;              // bf16 [B][T][D]: dp, dq
+  unsigned short *dpo, *dqo;              // half precision [B][T][D]: S dp, S dq
+  const float *sc;                        // sc[1] = S, sc[2] = 1 / S (launch_grad_scale)
   unsigned char *dxo;                     // dxd, 24 bits per value (bf16 would break du: it sums four taps of it
                                           // with cancellation)
   float *part;                            // [B*G][3][D]: sums for db_a, db_x, dLambda
@@ -62,7 +69,8 @@ __device__ __forceinline__ unsigned pick_halves(unsigned lo_src, unsigned hi_src
              : __builtin_amdgcn_perm(hi_src, lo_src, 0x05040100u);  // lo16(hi_src) : lo16(lo_src)
 }
 
-template <int GMAX>
+// DYLO: the upstream gradient is dy + dy_lo, two bf16 tensors (16 significant bits)
+template <int GMAX, bool DYLO = false>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 bwd_gates_kernel(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -71,7 +79,8 @@ bwd_gates_kernel(BwdArgs a) {
   f32x4 *cw_lds = (f32x4 *)(smem + G_OFF_CONST + 64 * 32);
   unsigned short *dyT = (unsigned short *)(smem + G_OFF_DYT);
   unsigned short *yT = (unsigned short *)(smem + G_OFF_YT);
-  float *hold = (float *)(smem + G_OFF_HOLD);
+  unsigned short *dyTlo = (unsigned short *)(smem + G_OFF_DYLO);
+  float *hold = (float *)(smem + g_off_hold(DYLO));
   const Problem &p = a.p;
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, j = lane & 31;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -92,12 +101,12 @@ bwd_gates_kernel(BwdArgs a) {
   // stay in registers, the next NLDS K-steps of W_x in LDS, and the rest is re-read from L2
   // every tile as contiguous 1 KB fragments (the register file cannot hold everything this
   // kernel needs, and L2 is a far better spill space than scratch)
-  constexpr int NRES = GMAX == 1 ? G_NRES + 1 : G_NRES, NLDS = G_NLDS;
+  constexpr int NRES = GMAX == 1 ? G_NRES + 1 : G_NRES, NLDS = g_nlds(DYLO);
   // (the products run in half precision, see w_to_f16; the streamed copy is already converted)
   f16x8 wa[16], wx[NRES];
   // fragment ks of this lane when streamed: pxs[ks * 64] (W_x in fragment order)
   const f16x8 *pxs = (const f16x8 *)a.wxf + (size_t)(g * NWAVE + wv) * 16 * 64 + lane;
-  f16x8 *wxl = (f16x8 *)(smem + G_OFF_WX) + (size_t)wv * NLDS * 64 + lane;   // [K-step][lane]
+  f16x8 *wxl = (f16x8 *)(smem + g_off_wx(DYLO)) + (size_t)wv * NLDS * 64 + lane;   // [K-step][lane]
   {
     const bf16x8 *pa = (const bf16x8 *)((const unsigned short *)p.W_a + ((size_t)g * BS + ch) * BS + hf * 8);
     const bf16x8 *px = (const bf16x8 *)((const unsigned short *)p.W_x + ((size_t)g * BS + ch) * BS + hf * 8);
@@ -119,6 +128,7 @@ bwd_gates_kernel(BwdArgs a) {
     sel_lds[64 + lane] = sel1;
   }
   const float bias_p = p.b_a[d] * LOG2E, bias_q = p.b_x[d] * LOG2E;
+  const float S = a.sc[1], invS = a.sc[2];
   float kd, kd_ln, lam_scale;
   {
     const float z = -p.Lambda[d];
@@ -153,6 +163,7 @@ bwd_gates_kernel(BwdArgs a) {
                                              seq_bytes, 0x00020000);
   };
   const __amdgpu_buffer_rsrc_t u_rsrc = rsrc(p.u), y_rsrc = rsrc(p.y_in), dy_rsrc = rsrc(p.dy);
+  const __amdgpu_buffer_rsrc_t dyl_rsrc = rsrc(DYLO ? p.dy_lo : p.dy);
   const __amdgpu_buffer_rsrc_t dp_rsrc = rsrc(a.dpo), dq_rsrc = rsrc(a.dqo);
   // dxd: [group of 4 steps][channel][12 bytes], four values of 24 bits (top three bytes of fp32)
   const unsigned grp_bytes = (unsigned)D * 12, ngrp = (unsigned)(T + 3) / 4;
@@ -204,6 +215,7 @@ bwd_gates_kernel(BwdArgs a) {
   };
   // dy and y rows 8*rg..8*rg+7 of tile t0 for the channel pair (zero past the sequence end)
   unsigned rdy[8], ry[8], ryh;   // ryh: the row before the tile (h_{t-1} of its first step)
+  unsigned rdl[DYLO ? 8 : 1];
   // (no branch around the loads: rows past the end of the sequence are out of the descriptors'
   // range and read as zero; a conditional load would make the compiler wait for it on the spot)
   auto load_dy_y = [&](int t0) {
@@ -212,6 +224,7 @@ bwd_gates_kernel(BwdArgs a) {
       const unsigned so = (unsigned)(t0 + 8 * rg + r) * row_bytes;
       rdy[r] = __builtin_amdgcn_raw_buffer_load_b32(dy_rsrc, c_voff, so, RGLRU_NT);
       ry[r] = __builtin_amdgcn_raw_buffer_load_b32(y_rsrc, c_voff, so, RGLRU_NT);
+      if (DYLO) rdl[r] = __builtin_amdgcn_raw_buffer_load_b32(dyl_rsrc, c_voff, so, RGLRU_NT);
     }
     // (t0 = 0: the offset wraps to the top of the 32-bit range, far outside the descriptor,
     // and reads as zero; the lanes take h0 there instead)
@@ -228,6 +241,12 @@ bwd_gates_kernel(BwdArgs a) {
       vy.z = pick_halves(ry[4], ry[5], c);   vy.w = pick_halves(ry[6], ry[7], c);
       *(uint4 *)(dyT + (2 * c2 + c) * TS + 8 * rg) = vd;
       *(uint4 *)(yT + (2 * c2 + c) * TS + 8 * rg) = vy;
+      if (DYLO) {
+        uint4 vl;
+        vl.x = pick_halves(rdl[0], rdl[1], c); vl.y = pick_halves(rdl[2], rdl[3], c);
+        vl.z = pick_halves(rdl[4], rdl[5], c); vl.w = pick_halves(rdl[6], rdl[7], c);
+        *(uint4 *)(dyTlo + (2 * c2 + c) * TS + 8 * rg) = vl;
+      }
     }
     if (rg == 0) {   // the row before the tile goes to the spare column TS - 1 of the y tile
       yT[(2 * c2) * TS + TS - 1] = (unsigned short)(ryh & 0xffffu);
@@ -235,11 +254,13 @@ bwd_gates_kernel(BwdArgs a) {
     }
   };
 
+  const float kdS = kd_ln * S;
   const int arow = ((j >> 2) & 1) * 16 + (j >> 3) * 4 + (j & 3);
   const unsigned short *arow_base = xs + arow * XS + hf * 8;
   f32x4 *hold_mine = (f32x4 *)hold + (size_t)wv * 4 * 64 + lane;
   const uint4 *dyT_mine = (const uint4 *)(dyT + ch * TS + hf * 16);
   const uint4 *yT_mine = (const uint4 *)(yT + ch * TS + hf * 16);
+  const uint4 *dyTlo_mine = (const uint4 *)(dyTlo + ch * TS + hf * 16);
 
   u64 *ring = GMAX > 1 ? a.rec + (size_t)unit * a.R * 2 * BS + ch : nullptr;
   float carry = p.dhT ? p.dhT[(size_t)b * D + d] : 0.f;  // eps entering this workgroup's next tile
@@ -314,7 +335,12 @@ bwd_gates_kernel(BwdArgs a) {
     for (int q = 3; q >= 0; --q) {
       const uint4 dq4 = dyT_mine[q >> 1];
       const unsigned d01 = (q & 1) ? dq4.z : dq4.x, d23 = (q & 1) ? dq4.w : dq4.y;
-      const float dyv[4] = {bf_lo(d01), bf_hi(d01), bf_lo(d23), bf_hi(d23)};
+      float dyv[4] = {bf_lo(d01), bf_hi(d01), bf_lo(d23), bf_hi(d23)};
+      if (DYLO) {
+        const uint4 dl4 = dyTlo_mine[q >> 1];
+        const unsigned l01 = (q & 1) ? dl4.z : dl4.x, l23 = (q & 1) ? dl4.w : dl4.y;
+        dyv[0] += bf_lo(l01); dyv[1] += bf_hi(l01); dyv[2] += bf_lo(l23); dyv[3] += bf_hi(l23);
+      }
       f32x4 rq;
 #pragma unroll
       for (int e = 3; e >= 0; --e) {
@@ -377,7 +403,12 @@ bwd_gates_kernel(BwdArgs a) {
       const uint4 dq4 = dyT_mine[q >> 1], yq4 = yT_mine[q >> 1];
       const unsigned d01 = (q & 1) ? dq4.z : dq4.x, d23 = (q & 1) ? dq4.w : dq4.y;
       const unsigned y01 = (q & 1) ? yq4.z : yq4.x, y23 = (q & 1) ? yq4.w : yq4.y;
-      const float dyv[4] = {bf_lo(d01), bf_hi(d01), bf_lo(d23), bf_hi(d23)};
+      float dyv[4] = {bf_lo(d01), bf_hi(d01), bf_lo(d23), bf_hi(d23)};
+      if (DYLO) {
+        const uint4 dl4 = dyTlo_mine[q >> 1];
+        const unsigned l01 = (q & 1) ? dl4.z : dl4.x, l23 = (q & 1) ? dl4.w : dl4.y;
+        dyv[0] += bf_lo(l01); dyv[1] += bf_hi(l01); dyv[2] += bf_lo(l23); dyv[3] += bf_hi(l23);
+      }
       const float yv[4] = {bf_lo(y01), bf_hi(y01), bf_lo(y23), bf_hi(y23)};
       const f32x4 rq = hold_mine[q * 64];
       // h_{t-1} of the quad's first step: the step before it in the y tile (the spare column
@@ -405,17 +436,18 @@ bwd_gates_kernel(BwdArgs a) {
         const float dla = (delta * av) * fmaf(-av * gin, rs, hprev);   // delta a (h_{t-1} - a g/m)
         const float dg = delta * m;
         dxv[e] = dg * iv;
-        dqv[e] = dg * gin * (1.f - iv);
-        dpv[e] = (kd_ln * dla) * fmaf(-rv, rv, rv);
+        const float dqu = dg * gin * (1.f - iv);
+        dqv[e] = dqu * S;
+        dpv[e] = (kdS * dla) * fmaf(-rv, rv, rv);   // S dp
         s_lam = fmaf(dla, rv, s_lam);
-        s_ba += dpv[e];
-        s_bx += dqv[e];
+        s_ba += dpv[e];                             // (unscaled at the end)
+        s_bx += dqu;
         erev = ok ? av * delta : erev;
       }
-      // dp, dq (bf16): one 64-byte piece of a row per lane half and step
+      // S dp, S dq (half precision): one 64-byte piece of a row per lane half and step
       {
-        const unsigned p0 = pack_bf16(dpv[0], dpv[1]), p1 = pack_bf16(dpv[2], dpv[3]);
-        const unsigned q0 = pack_bf16(dqv[0], dqv[1]), q1 = pack_bf16(dqv[2], dqv[3]);
+        const unsigned p0 = pack_f16(dpv[0], dpv[1]), p1 = pack_f16(dpv[2], dpv[3]);
+        const unsigned q0 = pack_f16(dqv[0], dqv[1]), q1 = pack_f16(dqv[2], dqv[3]);
         const unsigned soq = so + (unsigned)(4 * q) * row_bytes;
         const int nv = nvalid - 4 * q;
 #pragma unroll
@@ -458,7 +490,7 @@ bwd_gates_kernel(BwdArgs a) {
   s_lam += __shfl_xor(s_lam, 32);
   if (hf == 0) {
     float *pp = a.part + ((size_t)(b * G + w) * 3) * D + d;
-    pp[0] = s_ba;
+    pp[0] = s_ba * invS;
     pp[D] = s_bx;
     pp[2 * (size_t)D] = s_lam * lam_scale;
     // the workgroup that ran tile 0 holds eps_0 = dL/dh0
@@ -468,7 +500,7 @@ bwd_gates_kernel(BwdArgs a) {
 
 
 // ------------------------------------------------------------------------------ dgrad
-// A tile: 32 steps x (dp 256 | dq 256) bf16, filled by direct-to-LDS loads (layout below);
+// A tile: 32 steps x (S dp 256 | S dq 256) half precision, filled by direct-to-LDS loads (layout below);
 // two of them, two u tiles of 35 rows, the selection fragments, and a staging tile per wave that
 // turns the du columns into 16-byte stores. Few, wide memory instructions matter here: a
 // compute unit issues roughly one vector memory instruction per 8 cycles, whatever its width
@@ -486,9 +518,10 @@ constexpr int D_LDS = D_OFF_OT + NWAVE * OTILE_BYTES;
 struct DgradArgs {
   Problem p;
   int C, ntile;                            // contiguous time chunks per unit, tiles per sequence
-  const unsigned short *dpo, *dqo;         // bf16 [B][T][D]
+  const unsigned short *dpo, *dqo;         // half precision [B][T][D]: S dp, S dq
+  const float *sc;                         // sc[2] = 1 / S
   const unsigned char *dxo;                // dxd [B][ceil(T/4)][D][12 bytes]
-  const unsigned short *wta, *wtx;         // transposed gate weights [nb][in k][out j], bf16
+  const unsigned short *wta, *wtx;         // transposed gate weights [nb][in k][out j], half precision
   float *part;                             // [B*C][5][D]: dconv_w[0..3], dconv_b partial sums
 };
 
@@ -520,7 +553,9 @@ __global__ void __launch_bounds__(256) bwd_prep_kernel(PrepArgs a) {
     __syncthreads();
     for (int i = threadIdx.x; i < 32 * 32; i += 256) {
       const int r = i >> 5, c = i & 31;
-      dst[(size_t)(bx + r) * BS + by + c] = tile[c][r];
+      // (in half precision: exact for bf16 weights from 6.1e-5 up)
+      const float wv_ = __uint_as_float((unsigned)tile[c][r] << 16);
+      dst[(size_t)(bx + r) * BS + by + c] = (unsigned short)(pack_f16(wv_, 0.f) & 0xffffu);
     }
     return;
   }
@@ -552,10 +587,11 @@ bwd_dgrad_kernel(DgradArgs a) {
   const int d = g * BS + ch;
 
   // transposed weights of this wave's 32 columns: B operand rows are output channels
-  bf16x8 wa[16], wx[16];
+  const float invS = a.sc[2];
+  f16x8 wa[16], wx[16];
   {
-    const bf16x8 *pa = (const bf16x8 *)(a.wta + ((size_t)g * BS + ch) * BS + hf * 8);
-    const bf16x8 *px = (const bf16x8 *)(a.wtx + ((size_t)g * BS + ch) * BS + hf * 8);
+    const f16x8 *pa = (const f16x8 *)(a.wta + ((size_t)g * BS + ch) * BS + hf * 8);
+    const f16x8 *px = (const f16x8 *)(a.wtx + ((size_t)g * BS + ch) * BS + hf * 8);
 #pragma unroll
     for (int ks = 0; ks < 16; ++ks) {
       wa[ks] = pa[ks * 2];
@@ -709,13 +745,13 @@ bwd_dgrad_kernel(DgradArgs a) {
       const unsigned short *ap = arow_base + buf * (D_A_TILE / 2);
       {
         constexpr int DQ = D_A_TILE / 4;   // dq slots, in elements
-        bf16x8 a0 = *(const bf16x8 *)(ap), a1 = *(const bf16x8 *)(ap + DQ);
+        f16x8 a0 = *(const f16x8 *)(ap), a1 = *(const f16x8 *)(ap + DQ);
 #pragma unroll
         for (int ks = 0; ks < 16; ++ks) {
-          const bf16x8 n0 = *(const bf16x8 *)(ap + ((ks + 1) & 15) * 16);
-          const bf16x8 n1 = *(const bf16x8 *)(ap + DQ + ((ks + 1) & 15) * 16);
-          acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, wa[ks], acc0, 0, 0, 0);
-          acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, wx[ks], acc1, 0, 0, 0);
+          const f16x8 n0 = *(const f16x8 *)(ap + ((ks + 1) & 15) * 16);
+          const f16x8 n1 = *(const f16x8 *)(ap + DQ + ((ks + 1) & 15) * 16);
+          acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, wa[ks], acc0, 0, 0, 0);
+          acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, wx[ks], acc1, 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
           a0 = n0;
           a1 = n1;
@@ -723,7 +759,7 @@ bwd_dgrad_kernel(DgradArgs a) {
       }
       float dx[19];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dx[r] = dxd_at(r) + (acc0[r] + acc1[r]);
+      for (int r = 0; r < 16; ++r) dx[r] = fmaf(acc0[r] + acc1[r], invS, dxd_at(r));
       // steps 16..18 of this lane's run: the other half's first three (lower lanes) or the
       // next tile's first three (upper lanes)
       const float s0v = __shfl_xor(dx[0], 32), s1v = __shfl_xor(dx[1], 32), s2v = __shfl_xor(dx[2], 32);
@@ -787,14 +823,15 @@ bwd_dgrad_kernel(DgradArgs a) {
 // Wave (mw, nw) owns output rows 64*mw.. (2 blocks of 32) and columns 128*nw.. (4 blocks).
 // The product contracts over time, so a fragment is 8 consecutive steps of one channel.
 // x is rebuilt here from u with the Conv1D of Section 2.3 (cheaper than a round trip of x
-// through HBM): a thread produces 8 consecutive steps of a channel pair, splits them into a
-// bf16 high and low part and lays them into [channel][time] tiles, where a fragment is one
-// 16-byte read. dp (or dq) arrives as the [time][channel] rows the gates kernel wrote; a
-// selection MFMA turns a 32-channel column block of it into (channel, 16 consecutive steps)
-// registers, which packed to bf16 are the fragments of the other operand.
-constexpr int W_TILE = TT * XS * 2;          // dp or dq: one [32 steps][264] bf16 tile
-constexpr int W_XT = BS * TS * 2;            // x part: one [256 channels][40] bf16 tile, time fastest
-constexpr int W_BUF = W_TILE + 2 * W_XT;     // one buffer: dp|dq tile, x high part, x low part
+// through HBM): a thread produces 8 consecutive steps of a channel pair in half precision and
+// lays them into a [channel][time] tile, where a fragment is one 16-byte read. S dp (or S dq)
+// arrives as the [time][channel] half-precision rows the gates kernel wrote; a selection MFMA
+// turns a 32-channel column block of it into (channel, 16 consecutive steps) registers, which
+// packed to half precision again (exactly) are the fragments of the other operand. Both
+// operands carry 11 significant bits; the factor S is taken out by the finishing pass.
+constexpr int W_TILE = TT * XS * 2;          // dp or dq: one [32 steps][264] 16-bit tile
+constexpr int W_XT = BS * TS * 2;            // x: one [256 channels][40] half-precision tile, time fastest
+constexpr int W_BUF = W_TILE + W_XT;         // one buffer: dp|dq tile, x tile
 constexpr int W_OFF_SEL = 2 * W_BUF;
 constexpr int W_OFF_CW = W_OFF_SEL + 64 * 32;
 constexpr int W_LDS = W_OFF_CW + 128 * 48;   // Conv1D taps and bias per channel pair
@@ -803,7 +840,7 @@ struct WgradArgs {
   int nb, S, D, T;
   long long rows;                           // B*T
   long long pos0;
-  const unsigned short *dpo, *dqo;          // bf16 [rows][D]
+  const unsigned short *dpo, *dqo;          // half precision [rows][D]: S dp, S dq
   const unsigned short *u;                  // bf16 [rows][D]
   const unsigned short *state_in;           // bf16 [B][3][D] ring, or NULL
   const float *conv_w, *conv_b;             // [4][D], [D] or NULL
@@ -813,7 +850,7 @@ struct WgradArgs {
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 bwd_wgrad_kernel(WgradArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16x8 *sel_lds = (bf16x8 *)(smem + W_OFF_SEL);
+  f16x8 *sel_lds = (f16x8 *)(smem + W_OFF_SEL);
   f32x4 *cw_lds = (f32x4 *)(smem + W_OFF_CW);
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, j = lane & 31;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -829,11 +866,11 @@ bwd_wgrad_kernel(WgradArgs a) {
   const int D = a.D, T = a.T;
 
   if (tid < 64) {
-    bf16x8 sel0, sel1;
+    f16x8 sel0, sel1;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      sel0[e] = (__bf16)((hf * 8 + e == j) ? 1.0f : 0.0f);
-      sel1[e] = (__bf16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
+      sel0[e] = (_Float16)((hf * 8 + e == j) ? 1.0f : 0.0f);
+      sel1[e] = (_Float16)((hf * 8 + e + 16 == j) ? 1.0f : 0.0f);
     }
     sel_lds[lane] = sel0;
     sel_lds[64 + lane] = sel1;
@@ -960,17 +997,14 @@ bwd_wgrad_kernel(WgradArgs a) {
         }
       }
     }
-    uint4 ah, al, bh, bl;
-    split_bf16(xa[0], xa[1], ah.x, al.x); split_bf16(xa[2], xa[3], ah.y, al.y);
-    split_bf16(xa[4], xa[5], ah.z, al.z); split_bf16(xa[6], xa[7], ah.w, al.w);
-    split_bf16(xb[0], xb[1], bh.x, bl.x); split_bf16(xb[2], xb[3], bh.y, bl.y);
-    split_bf16(xb[4], xb[5], bh.z, bl.z); split_bf16(xb[6], xb[7], bh.w, bl.w);
+    uint4 ah, bh;
+    ah.x = pack_f16(xa[0], xa[1]); ah.y = pack_f16(xa[2], xa[3]);
+    ah.z = pack_f16(xa[4], xa[5]); ah.w = pack_f16(xa[6], xa[7]);
+    bh.x = pack_f16(xb[0], xb[1]); bh.y = pack_f16(xb[2], xb[3]);
+    bh.z = pack_f16(xb[4], xb[5]); bh.w = pack_f16(xb[6], xb[7]);
     unsigned short *xh = (unsigned short *)(smem + (size_t)buf * W_BUF + W_TILE) + (2 * c2) * TS + 8 * rg;
-    unsigned short *xl = xh + BS * TS;
     *(uint4 *)(xh) = ah;
     *(uint4 *)(xh + TS) = bh;
-    *(uint4 *)(xl) = al;
-    *(uint4 *)(xl + TS) = bl;
   };
 
   const int arow = ((j >> 2) & 1) * 16 + (j >> 3) * 4 + (j & 3);
@@ -989,54 +1023,47 @@ bwd_wgrad_kernel(WgradArgs a) {
     const unsigned short *tg = (const unsigned short *)(smem + (size_t)buf * W_BUF) + a_off;
     const unsigned short *xh = (const unsigned short *)(smem + (size_t)buf * W_BUF + W_TILE) +
                                (4 * nw * 32 + j) * TS + 16 * hf;
-    const unsigned short *xl = xh + BS * TS;
-    const bf16x8 sl0 = sel_lds[lane], sl1 = sel_lds[64 + lane];
-    // x fragments (x = high + low, both bf16; as in the dp / dq fragments, lane half hf holds
-    // steps 16 hf .. 16 hf + 7 in the first K-step and the following 8 in the second), in the
-    // order of their use: f = 8 r + 2 q + i is column block 2 r + i, part q (high K0, high K1,
-    // low K0, low K1). LDS latency is several products long, so the reads run six fragments
-    // ahead of the products: the first six are requested before the dp / dq fragments are built.
+    const f16x8 sl0 = sel_lds[lane], sl1 = sel_lds[64 + lane];
+    // x fragments (as in the dp / dq fragments, lane half hf holds steps 16 hf .. 16 hf + 7 in
+    // the first K-step and the following 8 in the second), in the order of their use: f = 4 r +
+    // 2 q + i is column block 2 r + i, K-step q. LDS latency is several products long, so the
+    // reads run ahead of the products: the first four are requested before the dp / dq fragments
+    // are built.
     auto xfrag = [&](int f) __attribute__((always_inline)) {
-      const int r = f >> 3, q = (f >> 1) & 3, i = f & 1;
-      return *(const bf16x8 *)((q < 2 ? xh : xl) + (2 * r + i) * 32 * TS + (q & 1) * 8);
+      const int r = f >> 2, q = (f >> 1) & 1, i = f & 1;
+      return *(const f16x8 *)(xh + (2 * r + i) * 32 * TS + q * 8);
     };
-    bf16x8 w[16];
+    f16x8 w[8];
 #pragma unroll
-    for (int f = 0; f < 6; ++f) w[f] = xfrag(f);
+    for (int f = 0; f < 4; ++f) w[f] = xfrag(f);
     __builtin_amdgcn_sched_barrier(0);
     // dp / dq fragments: column block c of the tile -> two K-steps of 8 consecutive steps per lane
-    bf16x8 fa[2][2];
+    f16x8 fa[2][2];
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
       const unsigned short *tile = tg + (2 * mw + m) * 32;
       f32x16 t;
 #pragma unroll
       for (int r = 0; r < 16; ++r) t[r] = 0.f;
-      t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(tile), sl0, t, 0, 0, 0);
-      t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(tile + 16), sl1, t, 0, 0, 0);
+      t = __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const f16x8 *)(tile), sl0, t, 0, 0, 0);
+      t = __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const f16x8 *)(tile + 16), sl1, t, 0, 0, 0);
       unsigned pk[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) pk[e] = pack_bf16(t[2 * e], t[2 * e + 1]);
+      for (int e = 0; e < 8; ++e) pk[e] = pack_f16(t[2 * e], t[2 * e + 1]);   // exact: the values are half precision
       uint4 lo4 = make_uint4(pk[0], pk[1], pk[2], pk[3]), hi4 = make_uint4(pk[4], pk[5], pk[6], pk[7]);
-      fa[m][0] = __builtin_bit_cast(bf16x8, lo4);
-      fa[m][1] = __builtin_bit_cast(bf16x8, hi4);
+      fa[m][0] = __builtin_bit_cast(f16x8, lo4);
+      fa[m][1] = __builtin_bit_cast(f16x8, hi4);
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int f = 6; f < 16; ++f) w[f] = xfrag(f);
+    for (int f = 4; f < 8; ++f) w[f] = xfrag(f);
 #pragma unroll
-    for (int pr = 0; pr < 8; ++pr) {   // four independent accumulators per round: no product waits for its predecessor
-      const int r = pr >> 2, q = pr & 3;
-      acc[0][2 * r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][q & 1], w[2 * pr], acc[0][2 * r], 0, 0, 0);
-      acc[1][2 * r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][q & 1], w[2 * pr], acc[1][2 * r], 0, 0, 0);
-      acc[0][2 * r + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][q & 1], w[2 * pr + 1], acc[0][2 * r + 1], 0, 0, 0);
-      acc[1][2 * r + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][q & 1], w[2 * pr + 1], acc[1][2 * r + 1], 0, 0, 0);
-    }
-    // issue order: four products, then the next two reads
-#pragma unroll
-    for (int pr = 0; pr < 8; ++pr) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-      if (pr < 5) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    for (int pr = 0; pr < 4; ++pr) {   // four independent accumulators per round: no product waits for its predecessor
+      const int r = pr >> 1, q = pr & 1;
+      acc[0][2 * r] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[0][q], w[2 * pr], acc[0][2 * r], 0, 0, 0);
+      acc[1][2 * r] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[1][q], w[2 * pr], acc[1][2 * r], 0, 0, 0);
+      acc[0][2 * r + 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[0][q], w[2 * pr + 1], acc[0][2 * r + 1], 0, 0, 0);
+      acc[1][2 * r + 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[1][q], w[2 * pr + 1], acc[1][2 * r + 1], 0, 0, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
   };
@@ -1092,6 +1119,7 @@ bwd_wgrad_kernel(WgradArgs a) {
 //   then 5 rows x D: dconv_w[0..3], dconv_b from the dgrad kernel's B*C partial rows
 struct FinishArgs {
   const float *partW, *partA, *partC;
+  const float *sc;   // sc[2] = 1 / S: the wgrad partial sums carry the factor S of dp, dq
   int S, nA, nC, D;
   size_t per_gate;
   float *dWa, *dWx;
@@ -1106,6 +1134,7 @@ __global__ void __launch_bounds__(256) bwd_finish_kernel(FinishArgs a) {
     if (i >= 2 * a.per_gate) return;
     float sum = 0.f;
     for (int s = 0; s < a.S; ++s) sum += a.partW[(size_t)s * 2 * a.per_gate + i];
+    sum *= a.sc[2];
     if (i < a.per_gate)
       a.dWa[i] = sum;
     else
@@ -1134,7 +1163,7 @@ size_t al256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 struct BwdPlan {
   int units, ntile, G, R, C, S;
-  size_t off_dp, off_dq, off_dx, off_wta, off_wtx, off_wxf, off_rec, off_partA, off_partC, off_partW, total;
+  size_t off_dp, off_dq, off_dx, off_wta, off_wtx, off_wxf, off_sc, off_rec, off_partA, off_partC, off_partW, total;
 };
 
 BwdPlan plan_backward(int B, int T, int D, int nb, int ncu) {
@@ -1160,6 +1189,7 @@ BwdPlan plan_backward(int B, int T, int D, int nb, int ncu) {
   q.off_wta = off; off += wbytes;
   q.off_wtx = off; off += wbytes;
   q.off_wxf = off; off += wbytes;
+  q.off_sc = off; off += 256;
   q.off_rec = off; off += al256(256 + (size_t)q.units * q.R * 2 * BS * sizeof(u64));
   q.off_partA = off; off += al256((size_t)B * q.G * 3 * D * 4);
   q.off_partC = off; off += al256((size_t)B * q.C * 5 * D * 4);
@@ -1173,7 +1203,7 @@ BwdPlan plan_backward(int B, int T, int D, int nb, int ncu) {
 bool backward_mfma_supported(const Problem &p, bool bf) {
   auto al = [](const void *q, size_t n) { return ((uintptr_t)q % n) == 0; };
   return bf && p.bs == BS && p.T >= 1 && (size_t)p.T * p.D * 4 < ((size_t)1 << 32) &&
-         al(p.W_a, 16) && al(p.W_x, 16) && al(p.u, 16) && al(p.y_in, 4) && al(p.dy, 4) &&
+         al(p.W_a, 16) && al(p.W_x, 16) && al(p.u, 16) && al(p.y_in, 4) && al(p.dy, 4) && al(p.dy_lo, 4) &&
          al(p.du, 2) && (!p.state_in || al(p.state_in, 16));
 }
 
@@ -1201,15 +1231,28 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   hipError_t e;
   static bool configured = false;
   if (!configured) {
-    if ((e = big_lds(bwd_gates_kernel<1>, G_LDS)) != hipSuccess) return e;
-    if ((e = big_lds(bwd_gates_kernel<4>, G_LDS)) != hipSuccess) return e;
-    if ((e = big_lds(bwd_gates_kernel<8>, G_LDS)) != hipSuccess) return e;
-    if ((e = big_lds(bwd_gates_kernel<16>, G_LDS)) != hipSuccess) return e;
+    if ((e = big_lds(bwd_gates_kernel<1>, g_lds(false))) != hipSuccess) return e;
+    if ((e = big_lds(bwd_gates_kernel<4>, g_lds(false))) != hipSuccess) return e;
+    if ((e = big_lds(bwd_gates_kernel<8>, g_lds(false))) != hipSuccess) return e;
+    if ((e = big_lds(bwd_gates_kernel<16>, g_lds(false))) != hipSuccess) return e;
+    if ((e = big_lds(bwd_gates_kernel<1, true>, g_lds(true))) != hipSuccess) return e;
+    if ((e = big_lds(bwd_gates_kernel<4, true>, g_lds(true))) != hipSuccess) return e;
+    if ((e = big_lds(bwd_gates_kernel<8, true>, g_lds(true))) != hipSuccess) return e;
+    if ((e = big_lds(bwd_gates_kernel<16, true>, g_lds(true))) != hipSuccess) return e;
     if ((e = big_lds(bwd_dgrad_kernel, D_LDS)) != hipSuccess) return e;
     if ((e = big_lds(bwd_wgrad_kernel, W_LDS)) != hipSuccess) return e;
     configured = true;
   }
   unsigned short *wta = (unsigned short *)(ws + q.off_wta), *wtx = (unsigned short *)(ws + q.off_wtx);
+  // 0. the scale of the upstream gradient: dp and dq travel between the kernels in half
+  // precision as S dp, S dq with max(|dy|, |dhT|) S in [32, 64). delta sums dy over the memory
+  // of the recurrence and the adjoints are a small multiple of it: they stay inside half
+  // precision's 65504 unless thousands of steps of dy at its maximum and of one sign pile up
+  // (the conversion then saturates, it does not overflow to infinity), and keep 11 bits down
+  // to 2e-6 of that maximum.
+  float *sc = (float *)(ws + q.off_sc);
+  if ((e = launch_grad_scale(p.dy, (size_t)p.B * p.T * p.D, p.dhT, (size_t)p.B * p.D, sc, 5, s)) != hipSuccess)
+    return e;
 
   // 1. gates, reverse scan, pointwise adjoints
   BwdArgs a;
@@ -1220,6 +1263,7 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   a.dpo = (unsigned short *)(ws + q.off_dp);
   a.dqo = (unsigned short *)(ws + q.off_dq);
   a.dxo = (unsigned char *)(ws + q.off_dx);
+  a.sc = sc;
   a.part = (float *)(ws + q.off_partA);
   const int grid = q.units * q.G;
   a.swizzle = (q.G > 1 && grid % 8 == 0) ? 1 : 0;
@@ -1242,14 +1286,23 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   if ((e = hipGetLastError()) != hipSuccess) return e;
   {
     KernelTimer kt("bwd_gates_kernel", s);
-    if (q.G == 1)
-      hipLaunchKernelGGL(bwd_gates_kernel<1>, dim3(grid), dim3(NTHR), G_LDS, s, a);
+    if (p.dy_lo) {
+      if (q.G == 1)
+        hipLaunchKernelGGL((bwd_gates_kernel<1, true>), dim3(grid), dim3(NTHR), g_lds(true), s, a);
+      else if (q.G <= 4)
+        hipLaunchKernelGGL((bwd_gates_kernel<4, true>), dim3(grid), dim3(NTHR), g_lds(true), s, a);
+      else if (q.G <= 8)
+        hipLaunchKernelGGL((bwd_gates_kernel<8, true>), dim3(grid), dim3(NTHR), g_lds(true), s, a);
+      else
+        hipLaunchKernelGGL((bwd_gates_kernel<16, true>), dim3(grid), dim3(NTHR), g_lds(true), s, a);
+    } else if (q.G == 1)
+      hipLaunchKernelGGL(bwd_gates_kernel<1>, dim3(grid), dim3(NTHR), g_lds(false), s, a);
     else if (q.G <= 4)
-      hipLaunchKernelGGL(bwd_gates_kernel<4>, dim3(grid), dim3(NTHR), G_LDS, s, a);
+      hipLaunchKernelGGL(bwd_gates_kernel<4>, dim3(grid), dim3(NTHR), g_lds(false), s, a);
     else if (q.G <= 8)
-      hipLaunchKernelGGL(bwd_gates_kernel<8>, dim3(grid), dim3(NTHR), G_LDS, s, a);
+      hipLaunchKernelGGL(bwd_gates_kernel<8>, dim3(grid), dim3(NTHR), g_lds(false), s, a);
     else
-      hipLaunchKernelGGL(bwd_gates_kernel<16>, dim3(grid), dim3(NTHR), G_LDS, s, a);
+      hipLaunchKernelGGL(bwd_gates_kernel<16>, dim3(grid), dim3(NTHR), g_lds(false), s, a);
   }
   if ((e = hipGetLastError()) != hipSuccess) return e;
 
@@ -1258,6 +1311,7 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   dg.p = p;
   dg.C = q.C; dg.ntile = q.ntile;
   dg.dpo = a.dpo; dg.dqo = a.dqo; dg.dxo = a.dxo;
+  dg.sc = sc;
   dg.wta = wta; dg.wtx = wtx;
   dg.part = (float *)(ws + q.off_partC);
   {
@@ -1284,6 +1338,7 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   // 4. all partial sums
   FinishArgs fa;
   fa.partW = wg.part; fa.partA = a.part; fa.partC = dg.part;
+  fa.sc = sc;
   fa.S = q.S; fa.nA = p.B * q.G; fa.nC = p.B * q.C; fa.D = p.D;
   fa.per_gate = (size_t)p.nb * BS * BS;
   fa.dWa = p.g.dW_a; fa.dWx = p.g.dW_x;

@@ -283,7 +283,7 @@ __global__ void __launch_bounds__(NTHREADS) bwd_pointwise_kernel(Problem p, BwdW
           const size_t o = ((size_t)b * p.T + t) * p.D + d;
           const Gates gt = gate_math(pa[tt], qa[tt], neg_cs);
           const float x = xs[tt * bs + j];
-          const float delta = ldf((const AT *)p.dy, o) + cy;
+          const float delta = ldf((const AT *)p.dy, o) + (p.dy_lo ? ldf((const AT *)p.dy_lo, o) : 0.f) + cy;
           const float hprev = t > 0 ? ldf((const AT *)p.y_in, o - p.D)
                                     : (p.h0 ? p.h0[(size_t)b * p.D + d] : 0.f);
           const float gin = gt.i * x;

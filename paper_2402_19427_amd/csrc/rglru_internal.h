@@ -49,6 +49,8 @@ struct Problem {
   void *state_out;
   // backward only
   const void *y_in, *dy;
+  const void *dy_lo;    // bf16 storage only, may be null: dy is the sum of two bf16 tensors, dy + dy_lo
+                        // (an upstream gradient the library formed itself and must not round to 8 bits)
   const float *dhT;
   void *du;
   float *dh0;
@@ -141,6 +143,12 @@ size_t backward_padded_ws_bytes(int B, int T, int D, int nb);
 size_t backward_padded_flag_offset(int B, int T, int D, int nb);
 hipError_t launch_backward_padded(const Problem &p, hipStream_t s);
 
+// sc (256 bytes of scratch) <- sc[1] = S, sc[2] = 1 / S with S the power of two that brings
+// max(|dy|, |dhT|) into [2^shift, 2^(shift+1)); dy bf16 [n], dhT fp32 [nd] or null. Gradients are
+// linear in dy: kernels that keep adjoints in half precision work on S dy and undo it at the end.
+hipError_t launch_grad_scale(const void *dy, size_t n, const float *dhT, size_t nd, float *sc, int shift,
+                             hipStream_t s);
+
 // clears `bytes` (% 16 == 0) at a 16-byte aligned address with a fill kernel
 hipError_t launch_clear(void *at, size_t bytes, hipStream_t s);
 
@@ -156,7 +164,8 @@ hipError_t launch_scan_tiled(const ScanProblem &p, hipStream_t s);
 //   backward: dy = dout * GeLU(branch), dbranch = dout * y * GeLU'(branch)
 hipError_t launch_merge_forward(const void *y, const void *branch, void *out, size_t n, bool bf,
                                 bool tanh_form, hipStream_t s);
-hipError_t launch_merge_backward(const void *y, const void *branch, const void *dout, void *dy,
+//   dy_lo (bf16 storage, may be null): dy - bf16(dy), so that dy + dy_lo carries 16 significant bits
+hipError_t launch_merge_backward(const void *y, const void *branch, const void *dout, void *dy, void *dy_lo,
                                  void *dbranch, size_t n, bool bf, bool tanh_form, hipStream_t s);
 
 }  // namespace rglru

@@ -89,7 +89,7 @@ merge_fwd_kernel(const AT *y, const AT *br, AT *out, size_t n) {
 
 template <typename AT, int V, bool TANH>
 __global__ void __launch_bounds__(MTHR)
-merge_bwd_kernel(const AT *y, const AT *br, const AT *dout, AT *dy, AT *dbr, size_t n) {
+merge_bwd_kernel(const AT *y, const AT *br, const AT *dout, AT *dy, AT *dy_lo, AT *dbr, size_t n) {
   constexpr bool FAST = sizeof(AT) == 2;
   const size_t stride = (size_t)gridDim.x * MTHR * V;
   size_t i = ((size_t)blockIdx.x * MTHR + threadIdx.x) * V;
@@ -108,6 +108,13 @@ merge_bwd_kernel(const AT *y, const AT *br, const AT *dout, AT *dy, AT *dbr, siz
     }
     store_pack<AT, V>(dy, at, gy);
     store_pack<AT, V>(dbr, at, gb);
+    if (FAST && dy_lo) {   // what the bf16 rounding of dy took away, as a second bf16 tensor
+      float gl[V];
+#pragma unroll
+      for (int k = 0; k < V; ++k)
+        gl[k] = gy[k] - __uint_as_float((unsigned)f32_to_bf16_bits(gy[k]) << 16);
+      store_pack<AT, V>(dy_lo, at, gl);
+    }
   };
   for (; i + (NP - 1) * stride < n; i += NP * stride) {
     Pack<AT, V> ry[NP], rb[NP], rd[NP];
@@ -150,16 +157,16 @@ hipError_t fwd_typed(const void *y, const void *br, void *out, size_t n, hipStre
 }
 
 template <typename AT, bool TANH>
-hipError_t bwd_typed(const void *y, const void *br, const void *dout, void *dy, void *dbr, size_t n,
+hipError_t bwd_typed(const void *y, const void *br, const void *dout, void *dy, void *dy_lo, void *dbr, size_t n,
                      hipStream_t s) {
   constexpr int V = Vec<AT>::N;
   KernelTimer t("merge_bwd_kernel", s);
-  if (n % V == 0 && all_aligned16({y, br, dout, dy, dbr}))
+  if (n % V == 0 && all_aligned16({y, br, dout, dy, dy_lo, dbr}))
     hipLaunchKernelGGL((merge_bwd_kernel<AT, V, TANH>), dim3(grid_for(n, V)), dim3(MTHR), 0, s,
-                       (const AT *)y, (const AT *)br, (const AT *)dout, (AT *)dy, (AT *)dbr, n);
+                       (const AT *)y, (const AT *)br, (const AT *)dout, (AT *)dy, (AT *)dy_lo, (AT *)dbr, n);
   else
     hipLaunchKernelGGL((merge_bwd_kernel<AT, 1, TANH>), dim3(grid_for(n, 1)), dim3(MTHR), 0, s,
-                       (const AT *)y, (const AT *)br, (const AT *)dout, (AT *)dy, (AT *)dbr, n);
+                       (const AT *)y, (const AT *)br, (const AT *)dout, (AT *)dy, (AT *)dy_lo, (AT *)dbr, n);
   return hipGetLastError();
 }
 
@@ -172,14 +179,14 @@ hipError_t launch_merge_forward(const void *y, const void *branch, void *out, si
   return tanh_form ? fwd_typed<float, true>(y, branch, out, n, s) : fwd_typed<float, false>(y, branch, out, n, s);
 }
 
-hipError_t launch_merge_backward(const void *y, const void *branch, const void *dout, void *dy,
+hipError_t launch_merge_backward(const void *y, const void *branch, const void *dout, void *dy, void *dy_lo,
                                  void *dbranch, size_t n, bool bf, bool tanh_form, hipStream_t s) {
   if (n == 0) return hipSuccess;
   if (bf)
-    return tanh_form ? bwd_typed<bf16, true>(y, branch, dout, dy, dbranch, n, s)
-                     : bwd_typed<bf16, false>(y, branch, dout, dy, dbranch, n, s);
-  return tanh_form ? bwd_typed<float, true>(y, branch, dout, dy, dbranch, n, s)
-                   : bwd_typed<float, false>(y, branch, dout, dy, dbranch, n, s);
+    return tanh_form ? bwd_typed<bf16, true>(y, branch, dout, dy, dy_lo, dbranch, n, s)
+                     : bwd_typed<bf16, false>(y, branch, dout, dy, dy_lo, dbranch, n, s);
+  return tanh_form ? bwd_typed<float, true>(y, branch, dout, dy, nullptr, dbranch, n, s)
+                   : bwd_typed<float, false>(y, branch, dout, dy, nullptr, dbranch, n, s);
 }
 
 }  // namespace rglru

@@ -107,7 +107,7 @@ int grid_of(size_t total) {
 
 struct PadPlan {
   int Dp;
-  size_t act, off_u, off_y, off_dy, off_du, off_wa, off_wx, off_vec, off_h0, off_dhT, off_dh0, off_state,
+  size_t act, off_u, off_y, off_dy, off_dylo, off_du, off_wa, off_wx, off_vec, off_h0, off_dhT, off_dh0, off_state,
       off_dwa, off_dwx, off_gvec, off_inner, total;
 };
 
@@ -119,6 +119,7 @@ PadPlan plan(int B, int T, int D, int nb) {
   q.off_u = off; off += q.act;
   q.off_y = off; off += q.act;
   q.off_dy = off; off += q.act;
+  q.off_dylo = off; off += q.act;   // second half of an upstream gradient given as a sum of two tensors
   q.off_du = off; off += q.act;
   q.off_wa = off; off += al256((size_t)nb * PBS * PBS * 2);
   q.off_wx = off; off += al256((size_t)nb * PBS * PBS * 2);
@@ -143,7 +144,7 @@ bool backward_padded_supported(const Problem &p, bool bf) {
   auto al = [](const void *q) { return ((uintptr_t)q % 16) == 0; };
   return bf && backward_padded_block(p.bs) && p.T >= 1 &&
          (size_t)p.T * p.nb * PBS * 4 < ((size_t)1 << 32) && al(p.W_a) && al(p.W_x) && al(p.u) &&
-         al(p.y_in) && al(p.dy) && al(p.du) && (!p.state_in || al(p.state_in)) && al(p.g.dW_a) &&
+         al(p.y_in) && al(p.dy) && al(p.dy_lo) && al(p.du) && (!p.state_in || al(p.state_in)) && al(p.g.dW_a) &&
          al(p.g.dW_x) && al(p.h0) && al(p.dhT) && al(p.dh0);
 }
 
@@ -169,6 +170,12 @@ hipError_t launch_backward_padded(const Problem &p, hipStream_t s) {
     a.t[1] = {(const uint4 *)p.y_in, (uint4 *)(ws + q.off_y)};
     a.t[2] = {(const uint4 *)p.dy, (uint4 *)(ws + q.off_dy)};
     hipLaunchKernelGGL(pad_rows_kernel, dim3(grid_of(a.rows * nb * a.cp)), dim3(PTHR), 0, s, a);
+    if (p.dy_lo) {
+      ActArgs b = a;
+      b.n = 1;
+      b.t[0] = {(const uint4 *)p.dy_lo, (uint4 *)(ws + q.off_dylo)};
+      hipLaunchKernelGGL(pad_rows_kernel, dim3(grid_of(b.rows * nb * b.cp)), dim3(PTHR), 0, s, b);
+    }
     if (p.state_in) {
       ActArgs b = a;
       b.n = 1; b.rows = (size_t)p.B * 3;
@@ -204,6 +211,7 @@ hipError_t launch_backward_padded(const Problem &p, hipStream_t s) {
   Problem w = p;
   w.D = Dp; w.bs = PBS;
   w.u = ws + q.off_u; w.y_in = ws + q.off_y; w.dy = ws + q.off_dy; w.du = ws + q.off_du;
+  w.dy_lo = p.dy_lo ? ws + q.off_dylo : nullptr;
   w.W_a = ws + q.off_wa; w.W_x = ws + q.off_wx;
   w.b_a = vec; w.b_x = vec + Dp; w.Lambda = vec + 2 * (size_t)Dp; w.conv_w = vec + 3 * (size_t)Dp;
   w.conv_b = p.conv_b ? vec + 7 * (size_t)Dp : nullptr;

@@ -395,7 +395,9 @@ hipError_t launch_scan_t(const ScanArgs &a, int grid, hipStream_t s) {
 template <int GMAX>
 hipError_t launch_scan_flags(const ScanArgs &a, int grid, hipStream_t s) {
   const bool loga = a.p.flags & RGLRU_SCAN_LOG_A, scale = !(a.p.flags & RGLRU_SCAN_NO_INPUT_SCALE);
-  if (a.p.flags & SCAN_G_FP16) return launch_scan_t<GMAX, true, false, true>(a, grid, s);   // internal use: this form only
+  if (a.p.flags & SCAN_G_FP16)   // internal use: the log-decay form without the input scale only
+    return (a.p.flags & RGLRU_SCAN_ADJOINT) ? launch_scan_t<GMAX, true, false, true, true>(a, grid, s)
+                                            : launch_scan_t<GMAX, true, false, true>(a, grid, s);
   if (a.p.flags & RGLRU_SCAN_ADJOINT)   // (always without the input scale)
     return loga ? launch_scan_t<GMAX, true, false, false, true>(a, grid, s)
                 : launch_scan_t<GMAX, false, false, false, true>(a, grid, s);

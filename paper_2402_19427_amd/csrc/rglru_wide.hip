@@ -852,12 +852,34 @@ __global__ void __launch_bounds__(256) transpose16_kernel(const unsigned short *
 // bits of max |v| over n bf16 values (the bit patterns of non-negative floats order like integers)
 __global__ void __launch_bounds__(256) absmax_bf16_kernel(const unsigned short *v, size_t n, unsigned *out) {
   unsigned m = 0;
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
-    const unsigned b = ((unsigned)v[i] & 0x7fffu) << 16;
+  auto take = [&](unsigned bits16) {
+    const unsigned b = (bits16 & 0x7fffu) << 16;
     if (b <= 0x7f800000u) m = max(m, b);   // NaNs are left out of the range estimate
+  };
+  // 16 bytes per thread where the address allows it (always, for tensors the matrix-core paths take)
+  const size_t n8 = (((uintptr_t)v & 15) == 0) ? n / 8 : 0;
+  const uint4 *v8 = (const uint4 *)v;
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  auto take8 = [&](const uint4 &w) {
+    take(w.x); take(w.x >> 16); take(w.y); take(w.y >> 16);
+    take(w.z); take(w.z >> 16); take(w.w); take(w.w >> 16);
+  };
+  for (; i + 3 * stride < n8; i += 4 * stride) {   // four loads in flight per thread
+    const uint4 w0 = v8[i], w1 = v8[i + stride], w2 = v8[i + 2 * stride], w3 = v8[i + 3 * stride];
+    take8(w0); take8(w1); take8(w2); take8(w3);
   }
+  for (; i < n8; i += stride) take8(v8[i]);
+  for (size_t k = n8 * 8 + (size_t)blockIdx.x * 256 + threadIdx.x; k < n; k += stride) take(v[k]);
   for (int o = 32; o > 0; o >>= 1) m = max(m, (unsigned)__shfl_xor((int)m, o));
-  if ((threadIdx.x & 63) == 0 && m) atomicMax(out, m);
+  // one atomic per workgroup: thousands of them on one address would cost more than the pass itself
+  __shared__ unsigned wm[4];
+  if ((threadIdx.x & 63) == 0) wm[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    m = max(max(wm[0], wm[1]), max(wm[2], wm[3]));
+    if (m) atomicMax(out, m);
+  }
 }
 __global__ void __launch_bounds__(256) absmax_f32_kernel(const float *v, size_t n, unsigned *out) {
   unsigned m = 0;
@@ -868,13 +890,11 @@ __global__ void __launch_bounds__(256) absmax_f32_kernel(const float *v, size_t 
   for (int o = 32; o > 0; o >>= 1) m = max(m, (unsigned)__shfl_xor((int)m, o));
   if ((threadIdx.x & 63) == 0 && m) atomicMax(out, m);
 }
-// sc[0] = bits of the maximum (in), sc[1] = S, sc[2] = 1 / S (out)
-__global__ void scale_setup_kernel(float *sc) {
+// sc[0] = bits of the maximum (in), sc[1] = S, sc[2] = 1 / S (out); the scaled maximum lands in
+// [2^shift, 2^(shift+1))
+__global__ void scale_setup_kernel(float *sc, int shift) {
   const unsigned bits = __float_as_uint(sc[0]);
-  // max in [2^(e+4), 2^(e+5)): the scaled maximum lands in [16, 32). The adjoints stay below
-  // a few thousand times that, inside half precision's 65504, and the small ones (channels
-  // whose gates are nearly shut) keep four more bits above its subnormal range.
-  int e = (int)(bits >> 23) - 127 - 4;
+  int e = (int)(bits >> 23) - 127 - shift;        // max in [2^(e+shift), 2^(e+shift+1))
   if (bits == 0 || bits >= 0x7f800000u) e = 0;   // all zero, or infinite: leave the values alone
   if (e > 126) e = 126;
   if (e < -126) e = -126;
@@ -887,6 +907,15 @@ __global__ void __launch_bounds__(256) scale_bf16_kernel(const unsigned short *s
   const float f = sc[which];
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256)
     dst[i] = (unsigned short)(pack_bf16(bf_lo((unsigned)src[i]) * f, 0.f) & 0xffffu);
+}
+// dst (half precision) = (hi + lo) * sc[1] for an upstream gradient given as two bf16 tensors
+__global__ void __launch_bounds__(256) scale_sum_f16_kernel(const unsigned short *hi, const unsigned short *lo,
+                                                            unsigned short *dst, size_t n, const float *sc) {
+  const float f = sc[1];
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const _Float16 h = (_Float16)((bf_lo((unsigned)hi[i]) + bf_lo((unsigned)lo[i])) * f);
+    dst[i] = __builtin_bit_cast(unsigned short, h);
+  }
 }
 __global__ void __launch_bounds__(256) scale_f32_kernel(const float *src, float *dst, size_t n, const float *sc,
                                                         int which) {
@@ -1050,6 +1079,20 @@ size_t backward_wide_flag_offset(int B, int T, int D, int nb) {   // 0 if the sc
 
 static unsigned stream_grid(size_t n) { return (unsigned)((n + 255) / 256 < 2048 ? (n + 255) / 256 : 2048); }
 
+// sc (256 bytes of scratch, 16-byte aligned) <- the power of two S that brings max(|dy|, |dhT|)
+// into [2^shift, 2^(shift+1)) and 1 / S, as sc[1] and sc[2]; dy bf16 [n], dhT fp32 [nd] or null
+hipError_t launch_grad_scale(const void *dy, size_t n, const float *dhT, size_t nd, float *sc, int shift,
+                             hipStream_t s) {
+  KernelTimer kt("grad_scale_kernels", s);
+  hipError_t e = launch_clear(sc, 256, s);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(absmax_bf16_kernel, dim3(stream_grid((n + 7) / 8)), dim3(256), 0, s, (const unsigned short *)dy, n,
+                     (unsigned *)sc);
+  if (dhT) hipLaunchKernelGGL(absmax_f32_kernel, dim3(stream_grid(nd)), dim3(256), 0, s, dhT, nd, (unsigned *)sc);
+  hipLaunchKernelGGL(scale_setup_kernel, dim3(1), dim3(1), 0, s, sc, shift);
+  return hipGetLastError();
+}
+
 hipError_t launch_backward_wide(const Problem &p_in, hipStream_t s) {
   const BwdWidePlan q = plan_bwd_wide(p_in.B, p_in.T, p_in.D, p_in.nb);
   char *ws = (char *)p_in.ws;
@@ -1059,15 +1102,17 @@ hipError_t launch_backward_wide(const Problem &p_in, hipStream_t s) {
   float *sc = (float *)(ws + q.off_scale);
   const size_t N = (size_t)p.B * p.T * p.D, BD = (size_t)p.B * p.D;
   {
+    // the scaled maximum lands in [16, 32): the adjoints stay below a few thousand times that,
+    // inside half precision's 65504, and the small ones (channels whose gates are nearly shut)
+    // keep four more bits above its subnormal range
+    if ((e = launch_grad_scale(p_in.dy, N, p_in.dhT, BD, sc, 4, s)) != hipSuccess) return e;
     KernelTimer kt("grad_scale_kernels", s);
-    if ((e = launch_clear(sc, 256, s)) != hipSuccess) return e;
-    hipLaunchKernelGGL(absmax_bf16_kernel, dim3(stream_grid(N)), dim3(256), 0, s, (const unsigned short *)p_in.dy, N,
-                       (unsigned *)sc);
-    if (p_in.dhT)
-      hipLaunchKernelGGL(absmax_f32_kernel, dim3(stream_grid(BD)), dim3(256), 0, s, p_in.dhT, BD, (unsigned *)sc);
-    hipLaunchKernelGGL(scale_setup_kernel, dim3(1), dim3(1), 0, s, sc);
-    hipLaunchKernelGGL(scale_bf16_kernel, dim3(stream_grid(N)), dim3(256), 0, s, (const unsigned short *)p_in.dy,
-                       (unsigned short *)(ws + q.off_dys), N, (const float *)sc, 1);
+    if (p_in.dy_lo)   // dy + dy_lo: 16 significant bits, kept as far as half precision holds them
+      hipLaunchKernelGGL(scale_sum_f16_kernel, dim3(stream_grid(N)), dim3(256), 0, s, (const unsigned short *)p_in.dy,
+                         (const unsigned short *)p_in.dy_lo, (unsigned short *)(ws + q.off_dys), N, (const float *)sc);
+    else
+      hipLaunchKernelGGL(scale_bf16_kernel, dim3(stream_grid(N)), dim3(256), 0, s, (const unsigned short *)p_in.dy,
+                         (unsigned short *)(ws + q.off_dys), N, (const float *)sc, 1);
     p.dy = ws + q.off_dys;
     if (p_in.dhT) {
       hipLaunchKernelGGL(scale_f32_kernel, dim3(stream_grid(BD)), dim3(256), 0, s, p_in.dhT,
@@ -1127,7 +1172,8 @@ hipError_t launch_backward_wide(const Problem &p_in, hipStream_t s) {
   // delta_t = dy_t + a_{t+1} delta_{t+1}; its last value times a_0 is dh0
   ScanProblem sp;
   sp.B = p.B; sp.T = p.T; sp.D = p.D;
-  sp.flags = RGLRU_SCAN_LOG_A | RGLRU_SCAN_NO_INPUT_SCALE | RGLRU_SCAN_ADJOINT | SCAN_OUT_FP16;
+  sp.flags = RGLRU_SCAN_LOG_A | RGLRU_SCAN_NO_INPUT_SCALE | RGLRU_SCAN_ADJOINT | SCAN_OUT_FP16 |
+             (p_in.dy_lo ? SCAN_G_FP16 : 0u);
   sp.a = ws + q.off_la; sp.g = p.dy; sp.h0 = p.dhT; sp.h = ws + q.off_delta; sp.hT = p.dh0;
   sp.ws = ws + q.off_scan;
   sp.ws_bytes = q.total - q.off_scan;

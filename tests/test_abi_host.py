@@ -192,10 +192,15 @@ def test_merge_calls_validation_and_workspace():
     with pytest.raises(R.RglruError) as e:
         R.rglru_forward_merge(s, params(), FAKE, Y, None, None, 0, 0, Y, None, None, None, None, 0)
     assert e.value.code == R.ERR_INVALID_ARG and "alias" in str(e.value)
-    # the backward needs room for dy on top of the plain backward's workspace
+    # the backward needs room for dy on top of the plain backward's workspace: in bf16 storage as
+    # two bf16 tensors (dy as stored and what its rounding took away), so that it reaches the
+    # backward with 16 significant bits
     plain = R.rglru_workspace_bytes(s, R.OP_BACKWARD)
     need = R.rglru_workspace_bytes(s, R.OP_BACKWARD_MERGE)
-    assert need == plain + 2 * 8 * 16 * 2 and need % 256 == 0
+    assert need == plain + 2 * (2 * 8 * 16 * 2) and need % 256 == 0
+    s32 = R.make_shape(2, 8, 16, 2, R.F32)
+    assert (R.rglru_workspace_bytes(s32, R.OP_BACKWARD_MERGE)
+            == R.rglru_workspace_bytes(s32, R.OP_BACKWARD) + 2 * 8 * 16 * 4)
     assert R.rglru_workspace_bytes(s, R.OP_FORWARD_MERGE) == R.rglru_workspace_bytes(s, R.OP_FORWARD)
     g = R.make_param_grads(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)
     args = (s, params(), FAKE, FAKE, None, None, 0, 0, Y, FAKE, None, OUT, FAKE + 12288, None, g)

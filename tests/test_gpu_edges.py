@@ -84,6 +84,17 @@ def rel_err_windows(got, want, win=128):
     return max(gen.rel_err(got[:, t:t + win], want[:, t:t + win]) for t in range(0, T, win))
 
 
+def rel_err_floor(got, want, floor):
+    """The error metric with a lower bound on the scale it measures against. The bf16 backward
+    keeps its adjoints dp, dq in half precision relative to the largest |dy|: a parameter
+    gradient whose EVERY entry lies some ten orders of magnitude below the upstream gradient
+    (a decay of e^-24 with the recurrence gate saturated open) is below what that resolves and
+    comes out as zero; `floor` is that resolution."""
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    rms = max(float(np.sqrt(np.mean(want * want))), floor)
+    return float(np.max(np.abs(got - want) / (np.abs(want) + rms)))
+
+
 def edge_inputs(B, T, D, nb, act, seed, lam, b_a, b_x, uscale):
     inp = gen.make_inputs(B, T, D, nb, act=act, seed=seed, h0=True, dy=True, bias=True)
     if lam is not None:
@@ -135,6 +146,10 @@ def test_backward_on_saturated_gates_and_extreme_decays(B, T, D, nb, act, lam, b
                           q["dy"], conv_b=q.get("conv_b"), h0=q["h0"], dhT=q["dhT"])
     errs = {k: gen.rel_err(rn.to_host(g[k]), ref[k]) for k in g}
     errs["du"] = rel_err_windows(rn.to_host(g["du"]), ref["du"])
+    if act == "bf16":   # 1e-7 of the upstream gradient summed over the rows (dy ~ N(0, 1) here)
+        floor = 1e-7 * np.sqrt(B * T)
+        for k in ("dW_a", "dW_x"):
+            errs[k] = rel_err_floor(rn.to_host(g[k]), ref[k], floor)
     print("errors:", {k: float("%.3g" % v) for k, v in errs.items()})
     for k in ("du", "dh0", "dW_a", "dW_x", "db_a", "db_x", "dLambda", "dconv_w", "dconv_b"):
         assert errs[k] < EDGE_BWD_TOL[act], (k, errs)

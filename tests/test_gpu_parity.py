@@ -568,15 +568,9 @@ def test_backward_merge_matches_oracle(B, T, D, nb, act, tanh_form):
     dhT = rn.to_device(inp["dhT"], "f32")
     g = dp.backward_merge(u, brd, y, rn.to_device(inp["dy"], act), h0=h0, dhT=dhT, flags=flags)
     q = f64(inp)
-    # the call is defined as the merge adjoint followed by the backward, with dy stored in the
-    # activation type in between: the oracle is composed the same way (in bf16 that one rounding
-    # alone moves single elements of dW_a by more than the bar, measured on the oracle)
-    args = (q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"], q["conv_w"])
-    y_ref, _, _ = oracle.forward(q["u"], *args, conv_b=q.get("conv_b"), h0=q["h0"])
-    dy_ref, dbr_ref = oracle.merge_backward(y_ref, br, q["dy"], approx=tanh_form)
-    dy_ref = gen.round_to_act(dy_ref.astype(np.float32), act).astype(np.float64)
-    ref = oracle.backward(q["u"], *args, dy_ref, conv_b=q.get("conv_b"), h0=q["h0"], dhT=q["dhT"])
-    ref["dbranch"] = dbr_ref
+    # against the float64 adjoint of the whole composition, nothing rounded in between
+    ref = oracle.backward_merge(q["u"], br, q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"], q["conv_w"],
+                                q["dy"], conv_b=q.get("conv_b"), h0=q["h0"], dhT=q["dhT"], approx=tanh_form)
     for k in ("du", "dbranch", "dh0"):
         assert gen.rel_err(rn.to_host(g[k]), ref[k]) < TOL[act], k
     for k in ("dW_a", "dW_x", "db_a", "db_x", "dLambda", "dconv_w", "dconv_b"):
