@@ -90,7 +90,10 @@ typedef struct rglru_shape {
   int32_t T;          /* time steps per sequence                    (>= 0; ignored by decode) */
   int32_t D;          /* channels (D_RNN)                           (>= 1)                 */
   int32_t num_blocks; /* gate blocks nb; D % nb == 0                (ignored by conv1d)    */
-  int32_t conv_width; /* temporal filter width; only 4 is supported                        */
+  int32_t conv_width; /* temporal filter width: 4, or 0 = no Conv1D, the input is already  */
+                      /* x_t (the RG-LRU layer of Section 2.4 alone): conv_w, conv_b and   */
+                      /* every conv state argument are then ignored and may be NULL, and   */
+                      /* dconv_w, dconv_b are not produced. rglru_conv1d takes 4 only.     */
   float c;            /* exponent scale of eq. (3); the paper uses 8                       */
   int32_t act_dtype;  /* RGLRU_F32 or RGLRU_BF16: u, y, dy, du, x, conv state              */
   int32_t w_dtype;    /* RGLRU_F32 or RGLRU_BF16: W_a, W_x. Supported pairs:               */

@@ -41,7 +41,7 @@ constexpr int MAX_BLOCK = 2048;  // largest gate block the generic kernels stage
 
 // Checks everything about `s` that does not involve pointers. need_blocks: the op uses the
 // gate matrices. Returns RGLRU_OK or an error code with the message set.
-int check_shape(const rglru_shape *s, bool need_blocks, bool need_T, int min_T) {
+int check_shape(const rglru_shape *s, bool need_blocks, bool need_T, int min_T, bool conv_optional = true) {
   if (!s) return fail(RGLRU_ERR_INVALID_ARG, "shape is NULL");
   if (s->B < 1) return fail(RGLRU_ERR_INVALID_ARG, "B must be >= 1 (got %d)", s->B);
   if (s->D < 1) return fail(RGLRU_ERR_INVALID_ARG, "D must be >= 1 (got %d)", s->D);
@@ -60,8 +60,9 @@ int check_shape(const rglru_shape *s, bool need_blocks, bool need_T, int min_T) 
       return fail(RGLRU_ERR_INVALID_ARG, "D (%d) is not a multiple of num_blocks (%d)", s->D,
                   s->num_blocks);
   }
-  if (s->conv_width != 4)
-    return fail(RGLRU_ERR_UNSUPPORTED, "conv_width %d is not supported (only 4)", s->conv_width);
+  if (s->conv_width != 4 && !(s->conv_width == 0 && conv_optional))
+    return fail(RGLRU_ERR_UNSUPPORTED, "conv_width %d is not supported (4%s)", s->conv_width,
+                conv_optional ? ", or 0: the input is already x_t" : " only");
   if (s->act_dtype != s->w_dtype)
     return fail(RGLRU_ERR_UNSUPPORTED,
                 "act_dtype %d with w_dtype %d is not supported (use f32/f32 or bf16/bf16)",
@@ -94,7 +95,7 @@ int check_params(const rglru_shape *s, const rglru_params *p) {
   CHECK(check_ptr(p->b_a, "params.b_a", 4, true));
   CHECK(check_ptr(p->b_x, "params.b_x", 4, true));
   CHECK(check_ptr(p->Lambda, "params.Lambda", 4, true));
-  CHECK(check_ptr(p->conv_w, "params.conv_w", 4, true));
+  CHECK(check_ptr(p->conv_w, "params.conv_w", 4, s->conv_width != 0));   // (ignored without the Conv1D)
   CHECK(check_ptr(p->conv_b, "params.conv_b", 4, false));
   return RGLRU_OK;
 }
@@ -119,6 +120,7 @@ void fill_params(Problem &q, const rglru_shape *s, const rglru_params *p) {
   q.W_a = p->W_a; q.W_x = p->W_x;
   q.b_a = p->b_a; q.b_x = p->b_x; q.Lambda = p->Lambda;
   q.conv_w = p->conv_w; q.conv_b = p->conv_b;
+  if (s->conv_width == 0) q.conv_w = q.conv_b = nullptr;   // the kernels read a null tap array as x_t = u_t
 }
 
 // dy between the merge adjoint and the backward: one fp32 tensor, or in bf16 storage two bf16
@@ -232,7 +234,7 @@ int backward_checks(const rglru_shape *shape, const rglru_params *params, const 
   CHECK(check_ptr(grads->db_a, "grads.db_a", 4, true));
   CHECK(check_ptr(grads->db_x, "grads.db_x", 4, true));
   CHECK(check_ptr(grads->dLambda, "grads.dLambda", 4, true));
-  CHECK(check_ptr(grads->dconv_w, "grads.dconv_w", 4, true));
+  CHECK(check_ptr(grads->dconv_w, "grads.dconv_w", 4, shape->conv_width != 0));
   CHECK(check_ptr(grads->dconv_b, "grads.dconv_b", 4, false));
   CHECK(check_workspace(workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_BACKWARD)));
 
@@ -354,7 +356,7 @@ int rglru_workspace_status(const rglru_shape *shape, int op, const void *workspa
 int rglru_conv1d(const rglru_shape *shape, const void *u, const float *conv_w,
                  const float *conv_b, const void *conv_state_in, int64_t pos0, void *x_out,
                  void *conv_state_out, void *stream) {
-  CHECK(check_shape(shape, false, true, 0));
+  CHECK(check_shape(shape, false, true, 0, false));
   const size_t as = act_size(shape);
   if (pos0 < 0) return fail(RGLRU_ERR_INVALID_ARG, "pos0 must be >= 0");
   CHECK(check_ptr(u, "u", as, shape->T > 0));
@@ -400,6 +402,7 @@ int rglru_forward(const rglru_shape *shape, const rglru_params *params, const vo
   fill_params(q, shape, params);
   q.pos0 = pos0; q.u = u; q.h0 = h0; q.state_in = conv_state_in;
   q.y = y; q.hT = hT; q.state_out = conv_state_out;
+  if (shape->conv_width == 0) q.state_in = q.state_out = nullptr;   // no Conv1D, no ring
   q.ws = workspace; q.ws_bytes = workspace_bytes;
   const bool bf = shape->act_dtype == RGLRU_BF16;
   hipStream_t s = (hipStream_t)stream;
@@ -451,7 +454,7 @@ int rglru_decode_step(const rglru_shape *shape, const rglru_params *params, cons
   if (pos < 0) return fail(RGLRU_ERR_INVALID_ARG, "pos must be >= 0");
   CHECK(check_ptr(u_t, "u_t", as, true));
   CHECK(check_ptr(h, "h", 4, true));
-  CHECK(check_ptr(conv_state, "conv_state", as, true));
+  CHECK(check_ptr(conv_state, "conv_state", as, shape->conv_width != 0));
   CHECK(check_ptr(y_t, "y_t", as, true));
 
   Problem q;
@@ -459,6 +462,7 @@ int rglru_decode_step(const rglru_shape *shape, const rglru_params *params, cons
   fill_params(q, shape, params);
   q.T = 1; q.pos0 = pos; q.u = u_t; q.hT = h; q.state_in = conv_state;
   q.state_out = conv_state; q.y = y_t;
+  if (shape->conv_width == 0) q.state_in = q.state_out = nullptr;
   const bool bf = shape->act_dtype == RGLRU_BF16;
   hipError_t e = decode_mfma_supported(q, bf)   ? launch_decode_mfma(q, (hipStream_t)stream)
                  : decode_wide_supported(q, bf) ? launch_decode_wide(q, (hipStream_t)stream)
@@ -475,7 +479,7 @@ int rglru_decode_step_at(const rglru_shape *shape, const rglru_params *params, c
   const size_t as = act_size(shape);
   CHECK(check_ptr(u_t, "u_t", as, true));
   CHECK(check_ptr(h, "h", 4, true));
-  CHECK(check_ptr(conv_state, "conv_state", as, true));
+  CHECK(check_ptr(conv_state, "conv_state", as, shape->conv_width != 0));
   CHECK(check_ptr(pos, "pos", 8, true));
   CHECK(check_ptr(y_t, "y_t", as, true));
 
@@ -484,6 +488,7 @@ int rglru_decode_step_at(const rglru_shape *shape, const rglru_params *params, c
   fill_params(q, shape, params);
   q.T = 1; q.pos_rows = (const long long *)pos; q.u = u_t; q.hT = h; q.state_in = conv_state;
   q.state_out = conv_state; q.y = y_t;
+  if (shape->conv_width == 0) q.state_in = q.state_out = nullptr;
   const bool bf = shape->act_dtype == RGLRU_BF16;
   hipError_t e = decode_mfma_supported(q, bf)   ? launch_decode_mfma(q, (hipStream_t)stream)
                  : decode_wide_supported(q, bf) ? launch_decode_wide(q, (hipStream_t)stream)
@@ -509,6 +514,10 @@ int backward_run(const rglru_shape *shape, const rglru_params *params, const voi
   fill_params(q, shape, params);
   q.pos0 = pos0; q.u = u; q.h0 = h0; q.state_in = conv_state_in;
   q.y_in = y; q.dy = dy; q.dy_lo = dy_lo; q.dhT = dhT; q.du = du; q.dh0 = dh0; q.g = *grads;
+  if (shape->conv_width == 0) {   // no Conv1D: no carried inputs, no tap gradients
+    q.state_in = nullptr;
+    q.g.dconv_w = q.g.dconv_b = nullptr;
+  }
   q.ws = workspace; q.ws_bytes = workspace_bytes;
   const bool bf = shape->act_dtype == RGLRU_BF16;
   hipError_t e;
@@ -579,6 +588,7 @@ int rglru_forward_merge(const rglru_shape *shape, const rglru_params *params, co
   fill_params(q, shape, params);
   q.pos0 = pos0; q.u = u; q.h0 = h0; q.state_in = conv_state_in;
   q.hT = hT; q.state_out = conv_state_out;
+  if (shape->conv_width == 0) q.state_in = q.state_out = nullptr;
   q.ws = workspace; q.ws_bytes = workspace_bytes;
   const bool bf = shape->act_dtype == RGLRU_BF16;
   const bool tanh_form = (flags & RGLRU_MERGE_GELU_TANH) != 0;
@@ -612,7 +622,7 @@ int rglru_decode_step_merge(const rglru_shape *shape, const rglru_params *params
   CHECK(check_ptr(u_t, "u_t", as, true));
   CHECK(check_ptr(branch_t, "branch_t", as, true));
   CHECK(check_ptr(h, "h", 4, true));
-  CHECK(check_ptr(conv_state, "conv_state", as, true));
+  CHECK(check_ptr(conv_state, "conv_state", as, shape->conv_width != 0));
   CHECK(check_ptr(out_t, "out_t", as, true));
   if (out_t == branch_t || out_t == u_t)
     return fail(RGLRU_ERR_INVALID_ARG, "out_t must not alias branch_t or u_t");
@@ -622,6 +632,7 @@ int rglru_decode_step_merge(const rglru_shape *shape, const rglru_params *params
   fill_params(q, shape, params);
   q.T = 1; q.pos0 = pos; q.u = u_t; q.hT = h; q.state_in = conv_state;
   q.state_out = conv_state; q.y = out_t;
+  if (shape->conv_width == 0) q.state_in = q.state_out = nullptr;
   const bool bf = shape->act_dtype == RGLRU_BF16;
   const bool tanh_form = (flags & RGLRU_MERGE_GELU_TANH) != 0;
   hipStream_t s = (hipStream_t)stream;

@@ -141,7 +141,11 @@ bwd_gates_kernel(BwdArgs a) {
   const int c2 = tid & 127;
   const int rg = __builtin_amdgcn_readfirstlane(tid >> 7);
   const int dc = g * BS + 2 * c2;
-  if (tid < 128) {
+  if (tid < 128 && !p.conv_w) {   // no Conv1D: x_t = u_t
+    cw_lds[c2] = f32x4{LOG2E, LOG2E, 0.f, 0.f};
+    cw_lds[128 + c2] = f32x4{0.f, 0.f, 0.f, 0.f};
+    cw_lds[256 + c2] = f32x4{0.f, 0.f, 0.f, 0.f};
+  } else if (tid < 128) {
     f32x4 t0v, t1v, t2v;
     t0v[0] = p.conv_w[dc] * LOG2E;                  t0v[1] = p.conv_w[dc + 1] * LOG2E;
     t0v[2] = p.conv_w[(size_t)D + dc] * LOG2E;      t0v[3] = p.conv_w[(size_t)D + dc + 1] * LOG2E;
@@ -610,7 +614,7 @@ bwd_dgrad_kernel(DgradArgs a) {
   }
   float cw[4];
 #pragma unroll
-  for (int k = 0; k < 4; ++k) cw[k] = p.conv_w[(size_t)k * D + d];
+  for (int k = 0; k < 4; ++k) cw[k] = p.conv_w ? p.conv_w[(size_t)k * D + d] : (k == 0 ? 1.f : 0.f);
 
   const unsigned seq_bytes = (unsigned)((size_t)T * D * 2);
   const unsigned row_bytes = (unsigned)D * 2;
@@ -879,7 +883,11 @@ bwd_wgrad_kernel(WgradArgs a) {
   const int c2 = tid & 127;
   const int rg = __builtin_amdgcn_readfirstlane(tid >> 7);
   const int dc = g * BS + 2 * c2;
-  if (tid < 128) {
+  if (tid < 128 && !a.conv_w) {   // no Conv1D: x_t = u_t
+    cw_lds[c2] = f32x4{1.f, 1.f, 0.f, 0.f};
+    cw_lds[128 + c2] = f32x4{0.f, 0.f, 0.f, 0.f};
+    cw_lds[256 + c2] = f32x4{0.f, 0.f, 0.f, 0.f};
+  } else if (tid < 128) {
     f32x4 t0v, t1v, t2v;
     t0v[0] = a.conv_w[dc];                  t0v[1] = a.conv_w[dc + 1];
     t0v[2] = a.conv_w[(size_t)D + dc];      t0v[3] = a.conv_w[(size_t)D + dc + 1];
@@ -1343,7 +1351,7 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   fa.per_gate = (size_t)p.nb * BS * BS;
   fa.dWa = p.g.dW_a; fa.dWx = p.g.dW_x;
   fa.rowsA[0] = p.g.db_a; fa.rowsA[1] = p.g.db_x; fa.rowsA[2] = p.g.dLambda;
-  for (int k = 0; k < 4; ++k) fa.rowsC[k] = p.g.dconv_w + (size_t)k * p.D;
+  for (int k = 0; k < 4; ++k) fa.rowsC[k] = p.g.dconv_w ? p.g.dconv_w + (size_t)k * p.D : nullptr;
   fa.rowsC[4] = p.g.dconv_b;
   {
     const unsigned nW = (unsigned)((2 * fa.per_gate + 255) / 256), dblocks = (unsigned)((p.D + 255) / 256);

@@ -178,7 +178,11 @@ fwd_mfma_kernel(FwdArgs a) {
   const int rg = __builtin_amdgcn_readfirstlane(tid >> 7);
   const bool pair_ok = !PAD || 2 * c2 < bs;
   const int dc = g * bs + (pair_ok ? 2 * c2 : 0);
-  if (tid < 128) {  // taps (scaled by log2 e) and bias of the channel pair, parked in LDS
+  if (tid < 128 && !p.conv_w) {   // no Conv1D: x_t = u_t, the identity tap
+    cw_lds[c2] = pair_ok ? f32x4{LOG2E, LOG2E, 0.f, 0.f} : f32x4{0.f, 0.f, 0.f, 0.f};
+    cw_lds[128 + c2] = f32x4{0.f, 0.f, 0.f, 0.f};
+    cw_lds[256 + c2] = f32x4{0.f, 0.f, 0.f, 0.f};
+  } else if (tid < 128) {  // taps (scaled by log2 e) and bias of the channel pair, parked in LDS
     f32x4 t0v, t1v, t2v;
     t0v[0] = p.conv_w[dc] * LOG2E;                  t0v[1] = p.conv_w[dc + 1] * LOG2E;
     t0v[2] = p.conv_w[(size_t)D + dc] * LOG2E;      t0v[3] = p.conv_w[(size_t)D + dc + 1] * LOG2E;
@@ -983,7 +987,9 @@ bool decode_mfma_supported(const Problem &p, bool bf) {
   const uintptr_t all = (uintptr_t)p.W_a | (uintptr_t)p.W_x | (uintptr_t)p.u | (uintptr_t)p.state_out |
                         (uintptr_t)p.hT | (uintptr_t)p.y | (uintptr_t)p.conv_w | (uintptr_t)p.conv_b |
                         (uintptr_t)(p.merge ? p.branch : nullptr);
-  return bf && forward_mfma_block(p.bs) && all % 16 == 0 && (size_t)(p.B + TT) * 3 * p.D * 2 < ((size_t)1 << 31);
+  // (a step without the Conv1D and its ring runs on the generic kernel)
+  return bf && p.conv_w && forward_mfma_block(p.bs) && all % 16 == 0 &&
+         (size_t)(p.B + TT) * 3 * p.D * 2 < ((size_t)1 << 31);
 }
 
 hipError_t launch_decode_mfma(const Problem &p, hipStream_t s) {

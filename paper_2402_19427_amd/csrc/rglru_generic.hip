@@ -59,6 +59,7 @@ __device__ __forceinline__ float input_at(const Problem &p, int b, int t, int d)
 // Conv1D output x[b,t,d] (Section 2.3), lag-indexed taps
 template <typename AT>
 __device__ __forceinline__ float conv_at(const Problem &p, int b, int t, int d) {
+  if (!p.conv_w) return input_at<AT>(p, b, t, d);   // no Conv1D: x_t = u_t
   float acc = p.conv_b ? p.conv_b[d] : 0.f;
 #pragma unroll
   for (int k = 0; k < 4; ++k) acc = fmaf(p.conv_w[(size_t)k * p.D + d], input_at<AT>(p, b, t - k, d), acc);
@@ -179,13 +180,17 @@ __global__ void __launch_bounds__(NTHREADS) decode_kernel(Problem p) {
     float acc = 0.f;
     if (tt < nbat) {
       const int b = b0 + tt;
-      acc = p.conv_b ? p.conv_b[d] : 0.f;
-      acc = fmaf(p.conv_w[d], ldf((const AT *)p.u, (size_t)b * p.D + d), acc);
-      const long long posb = p.pos_rows ? p.pos_rows[b] : p.pos0;
+      if (!p.conv_w) {   // no Conv1D (and no ring): x_t = u_t
+        acc = ldf((const AT *)p.u, (size_t)b * p.D + d);
+      } else {
+        acc = p.conv_b ? p.conv_b[d] : 0.f;
+        acc = fmaf(p.conv_w[d], ldf((const AT *)p.u, (size_t)b * p.D + d), acc);
+        const long long posb = p.pos_rows ? p.pos_rows[b] : p.pos0;
 #pragma unroll
-      for (int k = 1; k < 4; ++k)
-        acc = fmaf(p.conv_w[(size_t)k * p.D + d],
-                   ldf(state, ((size_t)b * 3 + ring_slot(posb - k)) * p.D + d), acc);
+        for (int k = 1; k < 4; ++k)
+          acc = fmaf(p.conv_w[(size_t)k * p.D + d],
+                     ldf(state, ((size_t)b * 3 + ring_slot(posb - k)) * p.D + d), acc);
+      }
     }
     xs[idx] = acc;
   }
@@ -203,8 +208,10 @@ __global__ void __launch_bounds__(NTHREADS) decode_kernel(Problem p) {
         const float h = fmaf(gt.a, p.hT[o], gt.m * (gt.i * xs[tt * bs + j]));
         p.hT[o] = h;
         stf((AT *)p.y, o, h);
-        const int wslot = ring_slot(p.pos_rows ? p.pos_rows[b0 + tt] : p.pos0);
-        state[((size_t)(b0 + tt) * 3 + wslot) * p.D + d] = ((const AT *)p.u)[o];
+        if (state) {
+          const int wslot = ring_slot(p.pos_rows ? p.pos_rows[b0 + tt] : p.pos0);
+          state[((size_t)(b0 + tt) * 3 + wslot) * p.D + d] = ((const AT *)p.u)[o];
+        }
       }
     }
   }
@@ -363,9 +370,13 @@ __global__ void __launch_bounds__(NTHREADS) bwd_conv_input_kernel(Problem p, Bwd
     const int d = (int)(idx % p.D);
     const int t = (int)((idx / p.D) % p.T);
     float acc = 0.f;
+    if (!p.conv_w) {
+      acc = w.dx[idx];   // no Conv1D: du = dx
+    } else {
 #pragma unroll
-    for (int k = 0; k < 4; ++k)
-      if (t + k < p.T) acc = fmaf(p.conv_w[(size_t)k * p.D + d], w.dx[idx + (size_t)k * p.D], acc);
+      for (int k = 0; k < 4; ++k)
+        if (t + k < p.T) acc = fmaf(p.conv_w[(size_t)k * p.D + d], w.dx[idx + (size_t)k * p.D], acc);
+    }
     stf((AT *)p.du, idx, acc);
   }
 }
@@ -557,14 +568,16 @@ static hipError_t backward_generic_t(const Problem &p, hipStream_t s, bool with_
     hipLaunchKernelGGL(bwd_conv_input_kernel<AT>, dim3(grid_1d(n)), dim3(NTHREADS), 0, s, p, w);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  if (w.nchunk > 65535) return hipErrorInvalidConfiguration;
-  hipLaunchKernelGGL(bwd_conv_weight_kernel<AT>, dim3(dblocks, w.nchunk), dim3(NTHREADS), 0, s, p, w);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  const RowOuts conv_outs = {{p.g.dconv_w, p.g.dconv_w + p.D, p.g.dconv_w + 2 * (size_t)p.D,
-                              p.g.dconv_w + 3 * (size_t)p.D, p.g.dconv_b}};
-  hipLaunchKernelGGL(reduce_parts_kernel, dim3(dblocks, 5), dim3(NTHREADS), 0, s, w.partC, w.nchunk,
-                     5, p.D, conv_outs);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (p.g.dconv_w) {   // (absent without a Conv1D)
+    if (w.nchunk > 65535) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(bwd_conv_weight_kernel<AT>, dim3(dblocks, w.nchunk), dim3(NTHREADS), 0, s, p, w);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const RowOuts conv_outs = {{p.g.dconv_w, p.g.dconv_w + p.D, p.g.dconv_w + 2 * (size_t)p.D,
+                                p.g.dconv_w + 3 * (size_t)p.D, p.g.dconv_b}};
+    hipLaunchKernelGGL(reduce_parts_kernel, dim3(dblocks, 5), dim3(NTHREADS), 0, s, w.partC, w.nchunk,
+                       5, p.D, conv_outs);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   if (!with_wgrad) return hipSuccess;
   const int tiles = (p.bs + 31) / 32;
   hipLaunchKernelGGL(bwd_wgrad_kernel, dim3(p.nb, tiles, tiles), dim3(NTHREADS), 0, s, p, w);

@@ -41,7 +41,7 @@ struct Problem {
   const long long *pos_rows;   // decode only: position per sequence (device, [B]) instead of pos0
   const void *u;
   const void *W_a, *W_x;
-  const float *b_a, *b_x, *Lambda, *conv_w, *conv_b;
+  const float *b_a, *b_x, *Lambda, *conv_w, *conv_b;   // conv_w null: no Conv1D, x_t = u_t (identity tap)
   const float *h0;
   const void *state_in;
   void *y;

@@ -196,8 +196,9 @@ hipError_t launch_backward_padded(const Problem &p, hipStream_t s) {
     hipLaunchKernelGGL(pad_mats_kernel, dim3(grid_of((size_t)nb * PBS * PBS * 2 / 16)), dim3(PTHR), 0, s, m);
     VecArgs v;
     v.n = 8; v.nb = nb; v.bs = bs;
-    const float *rows[8] = {p.b_a, p.b_x, p.Lambda, p.conv_w, p.conv_w + p.D, p.conv_w + 2 * (size_t)p.D,
-                            p.conv_w + 3 * (size_t)p.D, p.conv_b};
+    const float *cw = p.conv_w;   // null (no Conv1D) stays null for the tuned kernels
+    const float *rows[8] = {p.b_a, p.b_x, p.Lambda, cw, cw ? cw + p.D : nullptr, cw ? cw + 2 * (size_t)p.D : nullptr,
+                            cw ? cw + 3 * (size_t)p.D : nullptr, p.conv_b};
     for (int k = 0; k < 8; ++k) {
       v.src[k] = rows[k];
       v.dst[k] = vec + (size_t)k * Dp;
@@ -213,7 +214,8 @@ hipError_t launch_backward_padded(const Problem &p, hipStream_t s) {
   w.u = ws + q.off_u; w.y_in = ws + q.off_y; w.dy = ws + q.off_dy; w.du = ws + q.off_du;
   w.dy_lo = p.dy_lo ? ws + q.off_dylo : nullptr;
   w.W_a = ws + q.off_wa; w.W_x = ws + q.off_wx;
-  w.b_a = vec; w.b_x = vec + Dp; w.Lambda = vec + 2 * (size_t)Dp; w.conv_w = vec + 3 * (size_t)Dp;
+  w.b_a = vec; w.b_x = vec + Dp; w.Lambda = vec + 2 * (size_t)Dp;
+  w.conv_w = p.conv_w ? vec + 3 * (size_t)Dp : nullptr;
   w.conv_b = p.conv_b ? vec + 7 * (size_t)Dp : nullptr;
   w.h0 = p.h0 ? (const float *)(ws + q.off_h0) : nullptr;
   w.dhT = p.dhT ? (const float *)(ws + q.off_dhT) : nullptr;
@@ -221,8 +223,8 @@ hipError_t launch_backward_padded(const Problem &p, hipStream_t s) {
   w.state_in = p.state_in ? ws + q.off_state : nullptr;
   w.g.dW_a = (float *)(ws + q.off_dwa); w.g.dW_x = (float *)(ws + q.off_dwx);
   w.g.db_a = gvec; w.g.db_x = gvec + Dp; w.g.dLambda = gvec + 2 * (size_t)Dp;
-  w.g.dconv_w = gvec + 3 * (size_t)Dp;
-  w.g.dconv_b = gvec + 7 * (size_t)Dp;
+  w.g.dconv_w = p.g.dconv_w ? gvec + 3 * (size_t)Dp : nullptr;
+  w.g.dconv_b = p.g.dconv_b ? gvec + 7 * (size_t)Dp : nullptr;
   w.ws = ws + q.off_inner;
   w.ws_bytes = q.total - q.off_inner;
   if (!backward_mfma_supported(w, true)) return hipErrorInvalidValue;
@@ -243,8 +245,9 @@ hipError_t launch_backward_padded(const Problem &p, hipStream_t s) {
     hipLaunchKernelGGL(unpad_mats_kernel, dim3(grid_of((size_t)nb * bs * bs * 4 / 16)), dim3(PTHR), 0, s, m);
     VecArgs v;
     v.n = 8; v.nb = nb; v.bs = bs;
-    float *rows[8] = {p.g.db_a, p.g.db_x, p.g.dLambda, p.g.dconv_w, p.g.dconv_w + p.D,
-                      p.g.dconv_w + 2 * (size_t)p.D, p.g.dconv_w + 3 * (size_t)p.D, p.g.dconv_b};
+    float *dcw = p.g.dconv_w;
+    float *rows[8] = {p.g.db_a, p.g.db_x, p.g.dLambda, dcw, dcw ? dcw + p.D : nullptr,
+                      dcw ? dcw + 2 * (size_t)p.D : nullptr, dcw ? dcw + 3 * (size_t)p.D : nullptr, p.g.dconv_b};
     for (int k = 0; k < 8; ++k) {
       v.src[k] = gvec + (size_t)k * Dp;
       v.dst[k] = rows[k];

@@ -652,7 +652,7 @@ __global__ void __launch_bounds__(256) conv_rows_kernel(ConvArgs a) {
 #pragma unroll
   for (int k = 0; k < 4; ++k)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) w[k][e] = p.conv_w[(size_t)k * D + d0 + e];
+    for (int e = 0; e < 8; ++e) w[k][e] = p.conv_w ? p.conv_w[(size_t)k * D + d0 + e] : (k == 0 ? 1.f : 0.f);
 #pragma unroll
   for (int e = 0; e < 8; ++e) bias[e] = p.conv_b ? p.conv_b[d0 + e] : 0.f;
   const unsigned short *u = (const unsigned short *)p.u + (size_t)b * T * D + d0;
@@ -776,7 +776,10 @@ __global__ void __launch_bounds__(256) conv_adjoint_rows_kernel(ConvAdjArgs a) {
   const int t0 = tr * CR, d0 = c * 4;
   f32x4 w[4], in[CR + 3];
 #pragma unroll
-  for (int k = 0; k < 4; ++k) w[k] = *(const f32x4 *)(a.conv_w + (size_t)k * D + d0);
+  for (int k = 0; k < 4; ++k) {
+    const float id = k == 0 ? 1.f : 0.f;   // no Conv1D: du = dx
+    w[k] = a.conv_w ? *(const f32x4 *)(a.conv_w + (size_t)k * D + d0) : f32x4{id, id, id, id};
+  }
   const float *dx = a.dx + (size_t)b * T * D + d0;
 #pragma unroll
   for (int n = 0; n < CR + 3; ++n) {
@@ -1310,7 +1313,7 @@ bool decode_wide_supported(const Problem &p, bool bf) {
   const uintptr_t all = (uintptr_t)p.W_a | (uintptr_t)p.W_x | (uintptr_t)p.u | (uintptr_t)p.state_out |
                         (uintptr_t)p.hT | (uintptr_t)p.y | (uintptr_t)p.conv_w | (uintptr_t)p.conv_b |
                         (uintptr_t)(p.merge ? p.branch : nullptr);
-  return bf && forward_wide_block(p.bs) && p.bs <= DW_MAXCH * BS && all % 16 == 0 &&
+  return bf && p.conv_w && forward_wide_block(p.bs) && p.bs <= DW_MAXCH * BS && all % 16 == 0 &&
          (size_t)(p.B + TT) * 3 * p.D * 2 < ((size_t)1 << 31);
 }
 

@@ -51,7 +51,7 @@ def fwd(shape, p=None, u=FAKE, y=FAKE, ws=None, ws_bytes=0, pos0=0, h0=None):
     (dict(c=0.0), R.ERR_INVALID_ARG),
     (dict(act_dtype=7), R.ERR_INVALID_ARG),
     (dict(conv_width=3), R.ERR_UNSUPPORTED),
-    (dict(conv_width=0), R.ERR_UNSUPPORTED),
+    (dict(conv_width=5), R.ERR_UNSUPPORTED),
     (dict(act_dtype=R.BF16, w_dtype=R.F32), R.ERR_UNSUPPORTED),
     (dict(D=4096 * 4, num_blocks=1), R.ERR_UNSUPPORTED),  # block larger than the LDS tile
     (dict(B=70000), R.ERR_UNSUPPORTED),
@@ -63,6 +63,23 @@ def test_forward_rejects_bad_shapes(kw, code):
         fwd(R.make_shape(**base))
     assert e.value.code == code
     assert R.rglru_last_error() != ""
+
+
+def test_conv_width_zero_needs_no_conv_arguments_and_conv1d_needs_the_filter():
+    # no Conv1D: the filter taps may be NULL (everything else is validated as usual) ...
+    s0 = R.make_shape(2, 8, 16, 2, R.F32, conv_width=0)
+    no_taps = R.make_params(FAKE, FAKE, FAKE, FAKE, FAKE, None)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_forward(s0, no_taps, None, None, None, 0, FAKE, None, None, None, 0)
+    assert e.value.code == R.ERR_INVALID_ARG and "u is NULL" in str(e.value)
+    # ... with the filter they are required
+    with pytest.raises(R.RglruError) as e:
+        fwd(R.make_shape(2, 8, 16, 2, R.F32), p=no_taps)
+    assert e.value.code == R.ERR_INVALID_ARG and "conv_w" in str(e.value)
+    # the Conv1D alone has no width 0
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_conv1d(s0, FAKE, FAKE, None, None, 0, FAKE, None)
+    assert e.value.code == R.ERR_UNSUPPORTED
 
 
 def test_null_and_misaligned_pointers():

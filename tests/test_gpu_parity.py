@@ -638,3 +638,55 @@ def test_decode_steps_with_merge_match_oracle(B, D, nb, act, tanh_form):
         assert gen.rel_err(rn.to_host(out), out_ref) < TOL[act], s
         assert gen.rel_err(rn.to_host(h), h_ref) < TOL[act], s
         np.testing.assert_array_equal(gen.chrono_from_ring(rn.to_host(ring), pos + s + 1), st_ref)
+
+
+# ------------------------------------------------------------------ the layer without its Conv1D
+@pytest.mark.parametrize("B,T,D,nb,act", [(2, 37, 96, 3, "f32"),      # generic kernels
+                                          (2, 130, 512, 2, "bf16"),   # fused kernels
+                                          (1, 1100, 256, 1, "bf16"),  # fused, 16 time slices
+                                          (2, 70, 320, 2, "bf16"),    # padded tile
+                                          (1, 75, 1024, 2, "bf16")])  # passes of the wide blocks
+def test_conv_width_zero_is_the_rglru_layer_alone(B, T, D, nb, act):
+    """conv_width = 0: the input is already x_t (eqs. 1-4 of Section 2.4 without the Conv1D of
+    Section 2.3). Forward, one decode step and the backward against the oracle's RG-LRU layer;
+    conv parameters and states are not passed at all."""
+    import paper_2402_19427_amd as R
+    rn = runner()
+    inp = gen.make_inputs(B, T + 1, D, nb, act=act, seed=3 * B + T + D, h0=True, dy=True, bias=True)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    q = f64(inp)
+    x_all, x = q["u"], q["u"][:, :T]
+    par = R.make_params(dp.W_a, dp.W_x, dp.b_a, dp.b_x, dp.Lambda, None, None)
+    dt = R.BF16 if act == "bf16" else R.F32
+    sh = R.make_shape(B, T, D, nb, dt, conv_width=0)
+    u_dev = rn.to_device(inp["u"][:, :T], act)
+    h0 = rn.to_device(inp["h0"], "f32")
+    ws, n = dp.workspace(sh, R.OP_FORWARD)
+    y, hT = dp.empty_act(B, T, D), dp.empty_f32(B, D)
+    R.rglru_forward(sh, par, u_dev, h0, None, 0, y, hT, None, ws, n)
+    y_ref, hT_ref = oracle.rglru(x_all, q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"], h0=q["h0"])
+    assert gen.rel_err(rn.to_host(y), y_ref[:, :T]) < TOL[act]
+    hT_mid, _ = oracle.rglru(x, q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"], h0=q["h0"])[1], None
+    assert gen.rel_err(rn.to_host(hT), hT_mid) < TOL[act]
+    # backward: the oracle's backward with the identity filter (1, 0, 0, 0) is the layer's own adjoint
+    dy = rn.to_device(inp["dy"][:, :T], act)
+    dhT = rn.to_device(inp["dhT"], "f32")
+    wsb, nb_ = dp.workspace(sh, R.OP_BACKWARD)
+    g = dp.alloc_grads()
+    pg = R.make_param_grads(g["dW_a"], g["dW_x"], g["db_a"], g["db_x"], g["dLambda"], None, None)
+    du, dh0 = dp.empty_act(B, T, D), dp.empty_f32(B, D)
+    R.rglru_backward(sh, par, u_dev, h0, None, 0, y, dy, dhT, du, dh0, pg, wsb, nb_)
+    ident = np.zeros((4, D)); ident[0] = 1.0
+    ref = oracle.backward(x, q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"], ident, q["dy"][:, :T],
+                          h0=q["h0"], dhT=q["dhT"])
+    for k, got in (("du", du), ("dh0", dh0)):
+        assert gen.rel_err(rn.to_host(got), ref[k]) < TOL[act], k
+    for k in ("dW_a", "dW_x", "db_a", "db_x", "dLambda"):
+        assert gen.rel_err(rn.to_host(g[k]), ref[k]) < GRAD_TOL[act], k
+    R.rglru_workspace_status(sh, R.OP_BACKWARD, wsb)
+    # one decode step continuing the sequences: no ring at all
+    sh1 = R.make_shape(B, 1, D, nb, dt, conv_width=0)
+    y1 = dp.empty_act(B, D)
+    R.rglru_decode_step(sh1, par, rn.to_device(inp["u"][:, T], act), hT, None, T, y1)
+    assert gen.rel_err(rn.to_host(y1), y_ref[:, T]) < TOL[act]
+    assert gen.rel_err(rn.to_host(hT), hT_ref) < TOL[act]
