@@ -314,16 +314,32 @@ int rglru_backward_merge(const rglru_shape *shape, const rglru_params *params, c
 size_t rglru_workspace_bytes(const rglru_shape *shape, int op);
 
 /*
- * Health check of a finished call (for tests and debugging: it synchronises). When sequences
- * are cut into time slices, the workgroups of a launch hand carries to each other through
- * records in `workspace`. Every wait on such a record is bounded; a wait that expires - it
- * would mean that the workgroups of the launch were not all resident at once, which the launch
- * sizes rule out - sets a flag in the workspace instead of hanging, and the outputs of that
- * call are invalid. This function waits for `stream`, reads the flag left by the last call of
- * `op` (RGLRU_OP_FORWARD, _BACKWARD, _SCAN or a _MERGE variant) that ran with this `shape` and `workspace`, and
- * returns RGLRU_OK or RGLRU_ERR_TIMEOUT (or RGLRU_ERR_INVALID_ARG / RGLRU_ERR_HIP).
+ * Health check of the calls made on a workspace (it synchronises). When sequences are cut into
+ * time slices, the workgroups of a launch hand carries to each other through records in
+ * `workspace`. Every wait on such a record is bounded. A wait that expires - it would mean that
+ * the workgroups of the launch were not all resident at once, which the launch sizes rule out
+ * on a GPU the process has to itself - does not hang: it marks the workspace's status word,
+ * and from that point on the outputs of that call are filled with NaN, and so are the outputs of
+ * every later call on the same workspace (each call looks at the word before it starts), so that
+ * the failure cannot go unnoticed downstream. This function waits for `stream`, reads the word
+ * left by the calls of `op` (RGLRU_OP_FORWARD, _BACKWARD, _SCAN or a _MERGE variant) that ran
+ * with this `shape` and `workspace`, and returns RGLRU_OK, or RGLRU_ERR_TIMEOUT after clearing
+ * the word (the next call starts afresh; see rglru_set_max_time_slices for a retry that cannot
+ * time out), or RGLRU_ERR_INVALID_ARG / RGLRU_ERR_HIP. Uninitialised workspace memory is never
+ * mistaken for the mark (a 16-byte pattern).
  */
 int rglru_workspace_status(const rglru_shape *shape, int op, const void *workspace, void *stream);
+
+/*
+ * Upper bound on the number of time slices a sequence is cut into (process-wide; 0 = automatic,
+ * the default). With 1 no kernel ever waits on another workgroup: every (sequence, gate block)
+ * pair is walked by a single workgroup, slower for few long sequences but independent of all
+ * workgroups of a launch being resident at once. This is the setting to retry with after
+ * rglru_workspace_status has reported RGLRU_ERR_TIMEOUT (e.g. when another process occupies part
+ * of the GPU). Workspace sizes depend on it: query them again after changing it.
+ * Returns RGLRU_OK or RGLRU_ERR_INVALID_ARG (negative value).
+ */
+int rglru_set_max_time_slices(int max_slices);
 
 /* Description of the last error returned on the calling thread ("" if none). */
 const char *rglru_last_error(void);

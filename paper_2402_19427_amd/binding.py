@@ -65,6 +65,8 @@ def _load():
                                          gp, vp, sz, vp]
     lib.rglru_decode_step_merge.argtypes = [sp, pp, vp, vp, vp, vp, i64, ctypes.c_uint, vp, vp]
     lib.rglru_scan.argtypes = [sp, vp, vp, vp, ctypes.c_uint, vp, vp, vp, sz, vp]
+    lib.rglru_set_max_time_slices.argtypes = [ctypes.c_int]
+    lib.rglru_set_max_time_slices.restype = ctypes.c_int
     lib.rglru_workspace_status.argtypes = [sp, ctypes.c_int, vp, vp]
     lib.rglru_workspace_status.restype = ctypes.c_int
     lib.rglru_workspace_bytes.argtypes = [sp, ctypes.c_int]
@@ -224,6 +226,10 @@ def rglru_backward_merge(shape, params, u, branch, h0, conv_state_in, pos0, flag
 def rglru_scan(shape, a, g, h0, flags, h, hT, workspace, workspace_bytes, stream=None):
     _check(_lib.rglru_scan(_ref(shape), _addr(a), _addr(g), _addr(h0), flags, _addr(h), _addr(hT),
                            _addr(workspace), workspace_bytes, _stream(stream)))
+
+
+def rglru_set_max_time_slices(max_slices):
+    _check(_lib.rglru_set_max_time_slices(int(max_slices)))
 
 
 def rglru_workspace_status(shape, op, workspace, stream=None):

@@ -7,6 +7,7 @@
 #include <cstring>
 
 #include "rglru_internal.h"
+#include "rglru_mfma.h"
 
 using namespace rglru;
 
@@ -297,7 +298,13 @@ int rglru_timing_get(int index, const char **name, float *ms) {
 
 const char *rglru_last_error(void) { return g_err; }
 
-int rglru_version(void) { return 200; }
+int rglru_version(void) { return 300; }
+
+int rglru_set_max_time_slices(int max_slices) {
+  if (max_slices < 0) return fail(RGLRU_ERR_INVALID_ARG, "max_slices must be >= 0 (0 = automatic)");
+  rglru::mfma::set_slice_cap(max_slices);
+  return RGLRU_OK;
+}
 
 size_t rglru_workspace_bytes(const rglru_shape *shape, int op) {
   if (op < RGLRU_OP_CONV1D || op > RGLRU_OP_BACKWARD_MERGE) return 0;
@@ -347,8 +354,13 @@ int rglru_workspace_status(const rglru_shape *shape, int op, const void *workspa
   int flag = 0;
   e = hipMemcpy(&flag, (const char *)workspace + off, sizeof(flag), hipMemcpyDeviceToHost);
   if (e != hipSuccess) return hip_fail(e, "hipMemcpy");
-  if (flag != 0)
-    return fail(RGLRU_ERR_TIMEOUT, "a bounded wait between workgroups expired: the outputs of the call are invalid");
+  if (flag != 0) {
+    // reported once: the word is cleared, so that the next call on this workspace starts afresh
+    e = hipMemset((char *)const_cast<void *>(workspace) + off, 0, 16);
+    if (e != hipSuccess) return hip_fail(e, "hipMemset");
+    return fail(RGLRU_ERR_TIMEOUT, "a bounded wait between workgroups expired: the outputs of the calls on this "
+                                   "workspace since then are invalid (filled with NaN)");
+  }
   g_err[0] = 0;
   return RGLRU_OK;
 }

@@ -270,7 +270,8 @@ bwd_gates_kernel(BwdArgs a) {
   float carry = p.dhT ? p.dhT[(size_t)b * D + d] : 0.f;  // eps entering this workgroup's next tile
   const float h_first = p.h0 ? p.h0[(size_t)b * D + d] : 0.f;   // h_{-1}
   float s_ba = 0.f, s_bx = 0.f, s_lam = 0.f;
-  int spins = 0;
+  // (a workspace that still reports an expired wait of an earlier call: no waiting, NaN throughout)
+  int spins = (GMAX > 1 && expired_before(a.err)) ? SPIN_LIMIT : 0;
 
   // tiles are walked from the end of the sequence: this workgroup owns ntile-1-w, -G, ...
   int tile = a.ntile - 1 - w;
@@ -397,6 +398,8 @@ bwd_gates_kernel(BwdArgs a) {
         }
       }
     }
+    // a wait that expired: this channel's results are NaN from here on, visibly invalid
+    if (GMAX > 1 && (spins >= SPIN_LIMIT || __shfl_xor(spins, 32) >= SPIN_LIMIT)) e_in = __builtin_nanf("");
     carry = fmaf(A_t, e_in, E_t);
 
     // ---- second sweep: adjoints with the true eps, latest step first
@@ -486,7 +489,7 @@ bwd_gates_kernel(BwdArgs a) {
     }
     __syncthreads();
   }
-  if (GMAX > 1 && spins >= SPIN_LIMIT) *a.err = 1;
+  if (GMAX > 1 && spins >= SPIN_LIMIT) mark_expired(a.err);
 
   // per-channel sums of this workgroup (both lane halves hold the same channel)
   s_ba += __shfl_xor(s_ba, 32);
@@ -564,7 +567,7 @@ __global__ void __launch_bounds__(256) bwd_prep_kernel(PrepArgs a) {
     return;
   }
   const size_t i = (size_t)(blockIdx.x - nT) * 256 + threadIdx.x;
-  if (i < a.n16) a.zero[i] = make_uint4(0, 0, 0, 0);
+  if (i < a.n16) a.zero[i] = cleared_word(a.zero, i, true);
   if (i < (size_t)a.nb * BS * BS / 8) {
     const int lane = (int)(i & 63), ks = (int)((i >> 6) & 15), wv = (int)((i >> 10) & 7), g = (int)(i >> 13);
     const int hf = lane >> 5, j = lane & 31;

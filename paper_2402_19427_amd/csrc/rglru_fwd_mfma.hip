@@ -22,6 +22,7 @@
 #include "rglru_gelu.h"
 #include "rglru_mfma.h"
 
+#include <atomic>
 #include <type_traits>
 
 namespace rglru {
@@ -60,9 +61,9 @@ __device__ __forceinline__ void gate_fast(float pp, float qq, float xx, float kd
 
 // Preparation pass of the sliced forward kernel: clears the record rings (a fill kernel rather
 // than a memset, so that a caller may capture the call in a HIP graph).
-__global__ void __launch_bounds__(256) prep_kernel(uint4 *zero, size_t n16) {
+__global__ void __launch_bounds__(256) prep_kernel(uint4 *zero, size_t n16, bool keep_status) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < n16) zero[i] = make_uint4(0, 0, 0, 0);
+  if (i < n16) zero[i] = cleared_word(zero, i, keep_status);
 }
 // The forward kernel's own preparation: the same clearing, and W_x once in half precision (its
 // K-steps that do not fit the registers are re-read every tile; converting them there would
@@ -70,7 +71,7 @@ __global__ void __launch_bounds__(256) prep_kernel(uint4 *zero, size_t n16) {
 __global__ void __launch_bounds__(256) fwd_prep_kernel(uint4 *zero, size_t n16, const uint4 *wx, uint4 *wx16,
                                                        size_t n8) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < n16) zero[i] = make_uint4(0, 0, 0, 0);
+  if (i < n16) zero[i] = cleared_word(zero, i, true);
   if (i < n8) {
     const uint4 w = wx[i];
     wx16[i] = make_uint4(pack_f16(bf_lo(w.x), bf_hi(w.x)), pack_f16(bf_lo(w.y), bf_hi(w.y)),
@@ -277,7 +278,8 @@ fwd_mfma_kernel(FwdArgs a) {
 
   u64 *ring = GMAX > 1 ? a.rec + (size_t)unit * a.R * 2 * BS + ch : nullptr;
   float carry = p.h0 ? p.h0[(size_t)b * D + d] : 0.f;  // state after this workgroup's previous tile
-  int spins = 0;
+  // (a workspace that still reports an expired wait of an earlier call: no waiting, NaN throughout)
+  int spins = (GMAX > 1 && expired_before(a.err)) ? SPIN_LIMIT : 0;
 
   // four consecutive steps (quarter q) of this lane's run: h <- a h + b, y = h (eq. 4); the
   // bf16 results go to the wave's staging tile at (row = step, column = channel)
@@ -343,6 +345,8 @@ fwd_mfma_kernel(FwdArgs a) {
         h = fmaf(hf ? other : mine, h, hf ? mine : other);
       }
     }
+    // a wait that expired: this channel's outputs are NaN from here on, visibly invalid
+    if (GMAX > 1 && (spins >= SPIN_LIMIT || __shfl_xor(spins, 32) >= SPIN_LIMIT)) h = __builtin_nanf("");
     float hrun = hf ? fmaf(hA_lo, h, hH_lo) : h;  // state entering this lane's run
 #pragma unroll
     for (int q = 0; q < 4; ++q) run_quarter(q, hold_mine[q * 64], hold_mine[(q + 4) * 64], hrun);
@@ -531,7 +535,7 @@ fwd_mfma_kernel(FwdArgs a) {
   if (GMAX > 1 && held >= 0) {
     fetch_records(held);
     resolve(held);
-    if (spins >= SPIN_LIMIT) *a.err = 1;
+    if (spins >= SPIN_LIMIT) mark_expired(a.err);
   }
 
   // the workgroup that ran the last tile owns the final states
@@ -863,10 +867,10 @@ int mfma::num_cu() {
   return g_num_cu;
 }
 
-hipError_t mfma::launch_prep(void *zero, size_t zero_bytes, hipStream_t s) {
+hipError_t mfma::launch_prep(void *zero, size_t zero_bytes, hipStream_t s, bool keep_status) {
   const size_t n16 = zero_bytes / 16;
   KernelTimer kt("prep_kernel", s);
-  hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s, (uint4 *)zero, n16);
+  hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s, (uint4 *)zero, n16, keep_status);
   return hipGetLastError();
 }
 
@@ -898,11 +902,16 @@ bool forward_mfma_merge_fused(const Problem &p) {
 
 // time slices per (sequence, block): as many as keep every workgroup resident at once, at
 // most 8 (every tile reads the aggregates of the G-1 tiles before it)
+static std::atomic<int> g_slice_cap{0};
+void mfma::set_slice_cap(int cap) { g_slice_cap.store(cap); }
+
 int mfma::pick_slices(int units, int ntile, int ncu, int cap) {
   int G = ncu / units;
   if (G < 1) G = 1;
   if (G > ntile) G = ntile;
   if (G > cap) G = cap;
+  const int user = g_slice_cap.load();
+  if (user > 0 && G > user) G = user;
   return G;
 }
 

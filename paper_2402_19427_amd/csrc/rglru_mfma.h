@@ -19,6 +19,28 @@ constexpr int HOLD_BYTES = NWAVE * 64 * 32 * 4;     // local scan of one tile, p
 constexpr int OT = 40;                              // row stride (bf16) of a wave's output staging tile
 constexpr int OTILE_BYTES = TT * OT * 2;            // [32 steps][32 channels] bf16 per wave
 constexpr int SPIN_LIMIT = 1 << 22;
+// Status word of a workspace whose kernels wait on each other (its first 16 bytes). A wait that
+// expires writes this pattern; the outputs of that call are then filled with NaN from the point
+// of the failure on, and so are those of every later call on the workspace (the preparation pass
+// of a call keeps the word if and only if it holds exactly this pattern - whatever else an
+// uninitialised workspace contains is cleared) until rglru_workspace_status has reported it.
+#define RGLRU_EXPIRED_WORDS 0x4c474c52u, 0x58452d55u, 0x45524950u, 0xb3d3b3adu
+__device__ __forceinline__ void mark_expired(int *status) {
+  *(uint4 *)status = make_uint4(RGLRU_EXPIRED_WORDS);
+}
+__device__ __forceinline__ bool is_expired(const uint4 &w) {
+  const uint4 m = make_uint4(RGLRU_EXPIRED_WORDS);
+  return w.x == m.x && w.y == m.y && w.z == m.z && w.w == m.w;
+}
+// the status word at the start of a launch (uniform over the grid: nothing has written it yet)
+__device__ __forceinline__ bool expired_before(const int *status) {
+  return is_expired(*(const uint4 *)status);
+}
+// what the preparation pass leaves in 16-byte word i of a region whose first word is the status
+__device__ __forceinline__ uint4 cleared_word(const uint4 *region, size_t i, bool keep_status) {
+  if (keep_status && i == 0 && is_expired(region[0])) return region[0];
+  return make_uint4(0, 0, 0, 0);
+}
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -148,8 +170,10 @@ __device__ __forceinline__ void store_staged_tile(const unsigned short *ot, int 
 // host side (defined with the forward kernel)
 int num_cu();                                    // compute units of the current device
 int pick_slices(int units, int ntile, int ncu, int cap);  // time slices per (sequence, block), at most cap
+void set_slice_cap(int cap);                              // process-wide upper bound on that (0 = none)
 // clears zero_bytes (% 16 == 0) at `zero` with a fill kernel
-hipError_t launch_prep(void *zero, size_t zero_bytes, hipStream_t s);
+//   keep_status: the region starts with a status word, which stays if it reports an expired wait
+hipError_t launch_prep(void *zero, size_t zero_bytes, hipStream_t s, bool keep_status = false);
 
 }  // namespace mfma
 }  // namespace rglru

@@ -209,7 +209,8 @@ scan_tiled_kernel(ScanArgs a) {
 
   u64 *ring = GMAX > 1 ? a.rec + (size_t)unit * a.R * 2 * BS + ch : nullptr;
   float carry = p.h0 ? p.h0[(size_t)b * D + d] : 0.f;  // state after this workgroup's previous tile
-  int spins = 0;
+  // (a workspace that still reports an expired wait of an earlier call: no waiting, NaN throughout)
+  int spins = (GMAX > 1 && expired_before(a.err)) ? SPIN_LIMIT : 0;
 
   unsigned short *ot_mine = otile + (hf * 16) * OT + j;
   const unsigned hw_voff = (unsigned)(cg * BS + wv * 32 + (lane & 3) * 8) * 2 + (unsigned)(lane >> 2) * row_bytes;
@@ -248,6 +249,8 @@ scan_tiled_kernel(ScanArgs a) {
         h = fmaf(hf ? other : mine, h, hf ? mine : other);
       }
     }
+    // a wait that expired: this channel's outputs are NaN from here on, visibly invalid
+    if (GMAX > 1 && (spins >= SPIN_LIMIT || __shfl_xor(spins, 32) >= SPIN_LIMIT)) h = __builtin_nanf("");
     float hrun = hf ? fmaf(agg[P][0], h, agg[P][1]) : h;  // state entering this lane's run
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -365,7 +368,7 @@ scan_tiled_kernel(ScanArgs a) {
     fetch_records(held);
     if (last_par) resolve(held, std::integral_constant<int, 1>{});
     else resolve(held, std::integral_constant<int, 0>{});
-    if (spins >= SPIN_LIMIT) *a.err = 1;
+    if (spins >= SPIN_LIMIT) mark_expired(a.err);
   }
   // the workgroup that ran the last tile owns the final state
   if ((a.ntile - 1) % G == w && p.hT && hf == 0) {
@@ -444,7 +447,7 @@ hipError_t launch_scan_tiled(const ScanProblem &p, hipStream_t s) {
   }
   a.err = (int *)p.ws;
   a.rec = (u64 *)((char *)p.ws + 256);
-  hipError_t e = launch_prep(p.ws, 256 + (size_t)units * a.R * 2 * BS * sizeof(u64), s);
+  hipError_t e = launch_prep(p.ws, 256 + (size_t)units * a.R * 2 * BS * sizeof(u64), s, true);
   if (e != hipSuccess) return e;
   return launch_scan_flags<16>(a, grid, s);
 }

@@ -690,3 +690,54 @@ def test_conv_width_zero_is_the_rglru_layer_alone(B, T, D, nb, act):
     R.rglru_decode_step(sh1, par, rn.to_device(inp["u"][:, T], act), hT, None, T, y1)
     assert gen.rel_err(rn.to_host(y1), y_ref[:, T]) < TOL[act]
     assert gen.rel_err(rn.to_host(hT), hT_ref) < TOL[act]
+
+
+def test_an_expired_wait_poisons_later_calls_until_it_is_reported():
+    """The mark an expired wait leaves in a workspace (planted here from the host: no kernel
+    misbehaves) makes the next calls on that workspace return NaN instead of plausible numbers;
+    rglru_workspace_status reports it once and clears it; with the time slices capped at one
+    nothing waits and the same results come out."""
+    import struct
+    import torch
+    import paper_2402_19427_amd as R
+    rn = runner()
+    B, T, D, nb = 1, 700, 256, 1          # one unit in 16 time slices
+    inp = gen.make_inputs(B, T, D, nb, act="bf16", seed=9, dy=True)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, "bf16")
+    u, dy = rn.to_device(inp["u"], "bf16"), rn.to_device(inp["dy"], "bf16")
+    sh = dp.shape()
+    y_ok, hT_ok, _ = dp.forward(u)
+    g_ok = dp.backward(u, y_ok, dy)
+    torch.cuda.synchronize()
+    mark = torch.tensor(list(struct.pack("<4I", 0x4c474c52, 0x58452d55, 0x45524950, 0xb3d3b3ad)),
+                        dtype=torch.uint8, device="cuda:0")
+    # forward
+    ws, n = dp.workspace(sh, R.OP_FORWARD)
+    ws[:16] = mark
+    y_bad, hT_bad, _ = dp.forward(u)
+    assert torch.isnan(y_bad.float()).all() and torch.isnan(hT_bad).all()
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_workspace_status(sh, R.OP_FORWARD, ws)
+    assert e.value.code == R.ERR_TIMEOUT
+    R.rglru_workspace_status(sh, R.OP_FORWARD, ws)          # reported once, then clean
+    y_again, _, _ = dp.forward(u)
+    assert torch.equal(y_again, y_ok)
+    # backward: the word sits in front of its record rings, inside the workspace
+    wsb, nb_ = dp.workspace(sh, R.OP_BACKWARD)
+    R.rglru_workspace_status(sh, R.OP_BACKWARD, wsb)
+    # uninitialised scratch that merely looks non-zero is not the mark: results stay valid
+    wsb.fill_(0x5a)
+    g_fill = dp.backward(u, y_ok, dy)
+    assert torch.equal(g_fill["du"], g_ok["du"])
+    R.rglru_workspace_status(sh, R.OP_BACKWARD, wsb)
+    # the retry that cannot time out: one workgroup per (sequence, block)
+    R.rglru_set_max_time_slices(1)
+    try:
+        y_one, hT_one, _ = dp.forward(u)
+        q = f64(inp)
+        y_ref, _, _ = oracle.forward(q["u"], q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"], q["conv_w"])
+        assert gen.rel_err(rn.to_host(y_one), y_ref) < TOL["bf16"]
+        g_one = dp.backward(u, y_one, dy)
+        assert gen.rel_err(rn.to_host(g_one["du"]), rn.to_host(g_ok["du"])) < 1e-2
+    finally:
+        R.rglru_set_max_time_slices(0)
