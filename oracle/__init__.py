@@ -55,6 +55,16 @@ def _f64(a):
     return None if a is None else np.ascontiguousarray(a, dtype=np.float64)
 
 
+def _mask(reset, B, T):
+    """unsigned char* for a document-boundary mask [B,T] (non-zero: a new document starts at
+    that step), or NULL for None. Returns (keep-alive array, pointer)."""
+    if reset is None:
+        return None, ctypes.c_void_p(0)
+    m = np.ascontiguousarray(np.asarray(reset) != 0, dtype=np.uint8)
+    assert m.shape == (B, T)
+    return m, m.ctypes.data_as(ctypes.c_void_p)
+
+
 def set_threads(n):
     """Threads for the (batch, gate-block) loop; 1 is the canonical order."""
     _load().oracle_set_threads(int(n))
@@ -64,7 +74,7 @@ def max_threads():
     return int(_load().oracle_max_threads())
 
 
-def conv1d(u, conv_w, conv_b=None, state_in=None, want_state=False):
+def conv1d(u, conv_w, conv_b=None, state_in=None, want_state=False, reset=None):
     """Causal separable Conv1D (Section 2.3). u [B,T,D], conv_w [K,D] lag-indexed.
 
     state_in / returned state: [B,K-1,D] chronological (row 0 oldest).
@@ -75,11 +85,12 @@ def conv1d(u, conv_w, conv_b=None, state_in=None, want_state=False):
     assert conv_w.shape == (K, D)
     x = np.empty((B, T, D))
     st = np.empty((B, K - 1, D)) if want_state else None
-    _load().oracle_conv1d(B, T, D, K, _p(u), _p(conv_w), _p(conv_b), _p(state_in), _p(x), _p(st))
+    keep, mp = _mask(reset, B, T)
+    _load().oracle_conv1d(B, T, D, K, _p(u), _p(conv_w), _p(conv_b), _p(state_in), _p(x), _p(st), mp)
     return (x, st) if want_state else x
 
 
-def rglru(x, W_a, W_x, b_a, b_x, Lambda, h0=None, c=8.0, want_gates=False):
+def rglru(x, W_a, W_x, b_a, b_x, Lambda, h0=None, c=8.0, want_gates=False, reset=None):
     """RG-LRU eqs. (1)-(4) on convolved input x [B,T,D]; W [nb,bs,bs]. Returns y, hT[, gates]."""
     x, W_a, W_x, b_a, b_x, Lambda, h0 = map(_f64, (x, W_a, W_x, b_a, b_x, Lambda, h0))
     B, T, D = x.shape
@@ -89,7 +100,8 @@ def rglru(x, W_a, W_x, b_a, b_x, Lambda, h0=None, c=8.0, want_gates=False):
     hT = np.empty((B, D))
     g = [np.empty((B, T, D)) for _ in range(4)] if want_gates else [None] * 4
     _load().oracle_rglru(B, T, D, nb, ctypes.c_double(c), _p(x), _p(W_a), _p(W_x), _p(b_a),
-                         _p(b_x), _p(Lambda), _p(h0), _p(y), _p(hT), *map(_p, g))
+                         _p(b_x), _p(Lambda), _p(h0), _p(y), _p(hT), *map(_p, g),
+                         (_keep := _mask(reset, B, T))[1])
     if T == 0:
         hT[...] = 0.0 if h0 is None else h0
     if want_gates:
@@ -179,7 +191,8 @@ def backward_merge(u, branch, W_a, W_x, b_a, b_x, Lambda, conv_w, dout, conv_b=N
     return out
 
 
-def forward(u, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b=None, h0=None, state_in=None, c=8.0):
+def forward(u, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b=None, h0=None, state_in=None, c=8.0,
+            reset=None):
     """Conv1D then RG-LRU. Returns y [B,T,D], hT [B,D], state_out [B,K-1,D] (chronological)."""
     u, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b, h0, state_in = map(
         _f64, (u, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b, h0, state_in))
@@ -192,7 +205,7 @@ def forward(u, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b=None, h0=None, state_i
     st = np.empty((B, K - 1, D))
     _load().oracle_forward(B, T, D, nb, K, ctypes.c_double(c), _p(u), _p(W_a), _p(W_x), _p(b_a),
                            _p(b_x), _p(Lambda), _p(conv_w), _p(conv_b), _p(h0), _p(state_in),
-                           _p(y), _p(hT), _p(st))
+                           _p(y), _p(hT), _p(st), (_keep := _mask(reset, B, T))[1])
     if T == 0:
         hT[...] = 0.0 if h0 is None else h0
     return y, hT, st
@@ -216,7 +229,7 @@ def decode_step(u_t, W_a, W_x, b_a, b_x, Lambda, conv_w, h, state, conv_b=None, 
 
 
 def backward(u, W_a, W_x, b_a, b_x, Lambda, conv_w, dy, conv_b=None, h0=None, state_in=None,
-             dhT=None, c=8.0):
+             dhT=None, c=8.0, reset=None):
     """Adjoint of ``forward`` for L = sum(dy*y) + sum(dhT*hT). Returns a dict of float64 grads:
     du, dh0, dW_a, dW_x, db_a, db_x, dLambda, dconv_w, dconv_b."""
     u, W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b, h0, state_in, dy, dhT = map(
@@ -231,5 +244,6 @@ def backward(u, W_a, W_x, b_a, b_x, Lambda, conv_w, dy, conv_b=None, h0=None, st
                             _p(b_x), _p(Lambda), _p(conv_w), _p(conv_b), _p(h0), _p(state_in),
                             _p(dy), _p(dhT), _p(out["du"]), _p(out["dh0"]), _p(out["dW_a"]),
                             _p(out["dW_x"]), _p(out["db_a"]), _p(out["db_x"]),
-                            _p(out["dLambda"]), _p(out["dconv_w"]), _p(out["dconv_b"]))
+                            _p(out["dLambda"]), _p(out["dconv_w"]), _p(out["dconv_b"]),
+                            (_keep := _mask(reset, B, T))[1])
     return out

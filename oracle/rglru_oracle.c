@@ -34,6 +34,13 @@
  *     selects that reference's tanh form; the paper does not say which.
  *   - h_{-1} = h0 if given, else 0; the sqrt(1-a^2) factor applies at t = 0
  *     like at any other step.
+ *   - Documents packed into one sequence (the paper trains on packed
+ *     sequences but gives no convention): an optional mask reset[b][t] != 0
+ *     says that a new document starts at step t. Nothing crosses that
+ *     boundary: the state entering step t is zero (h_{t-1} := 0) and the
+ *     Conv1D sees zeros in place of every input before t - exactly as if the
+ *     document were a sequence of its own with no carried states. A NULL
+ *     mask means no boundaries.
  *
  * Layouts (all double, row-major, last index fastest):
  *   u, x, y, dy, du : [B][T][D]
@@ -67,6 +74,16 @@ static double softplus(double z) {
   return z > 0.0 ? z + log1p(exp(-z)) : log1p(exp(z));
 }
 
+/* 1 if a document boundary lies at one of the steps lo+1 .. hi of sequence b
+   (steps below 0 are before the call and carry no boundary) */
+static int boundary_between(const unsigned char *reset, int T, int b, int lo,
+                            int hi) {
+  if (!reset) return 0;
+  for (int j = (lo + 1 > 0 ? lo + 1 : 0); j <= hi; ++j)
+    if (reset[(size_t)b * T + j]) return 1;
+  return 0;
+}
+
 int oracle_max_threads(void) {
 #ifdef _OPENMP
   return omp_get_max_threads();
@@ -92,7 +109,8 @@ void oracle_set_threads(int n) {
 /* ------------------------------------------------------------------------ */
 void oracle_conv1d(int B, int T, int D, int K, const double *u,
                    const double *w, const double *bias,
-                   const double *state_in, double *x, double *state_out) {
+                   const double *state_in, double *x, double *state_out,
+                   const unsigned char *reset) {
   const int S = K - 1;
   for (int b = 0; b < B; ++b) {
     for (int t = 0; t < T; ++t) {
@@ -101,7 +119,9 @@ void oracle_conv1d(int B, int T, int D, int K, const double *u,
         for (int k = 0; k < K; ++k) {
           int s = t - k;
           double v;
-          if (s >= 0)
+          if (boundary_between(reset, T, b, s, t))
+            v = 0.0; /* the input at s belongs to an earlier document */
+          else if (s >= 0)
             v = u[((size_t)b * T + s) * D + d];
           else if (state_in)
             v = state_in[((size_t)b * S + (S + s)) * D + d];
@@ -118,7 +138,9 @@ void oracle_conv1d(int B, int T, int D, int K, const double *u,
         int s = T - S + r;
         for (int d = 0; d < D; ++d) {
           double v;
-          if (s >= 0)
+          if (boundary_between(reset, T, b, s, T - 1))
+            v = 0.0; /* before the last document: not part of its history */
+          else if (s >= 0)
             v = u[((size_t)b * T + s) * D + d];
           else if (state_in)
             v = state_in[((size_t)b * S + (S + s)) * D + d];
@@ -140,7 +162,7 @@ void oracle_rglru(int B, int T, int D, int nb, double c, const double *x,
                   const double *W_a, const double *W_x, const double *b_a,
                   const double *b_x, const double *Lambda, const double *h0,
                   double *y, double *hT, double *r_out, double *i_out,
-                  double *a_out, double *m_out) {
+                  double *a_out, double *m_out, const unsigned char *reset) {
   const int bs = D / nb;
 #pragma omp parallel for collapse(2) schedule(dynamic)
   for (int b = 0; b < B; ++b) {
@@ -164,6 +186,7 @@ void oracle_rglru(int B, int T, int D, int nb, double c, const double *x,
           const double la = c * r * log_a;        /* eq. (3), log space */
           const double a = exp(la);
           const double m = sqrt(-expm1(2.0 * la)); /* sqrt(1 - a^2) */
+          if (reset && reset[(size_t)b * T + t]) h = 0.0; /* new document */
           h = a * h + m * (i * xt[d]);            /* eq. (4) */
           const size_t o = ((size_t)b * T + t) * D + d;
           y[o] = h;
@@ -284,11 +307,11 @@ void oracle_forward(int B, int T, int D, int nb, int K, double c,
                     const double *b_a, const double *b_x, const double *Lambda,
                     const double *conv_w, const double *conv_b,
                     const double *h0, const double *state_in, double *y,
-                    double *hT, double *state_out) {
+                    double *hT, double *state_out, const unsigned char *reset) {
   double *x = (double *)malloc((size_t)B * T * D * sizeof(double));
-  oracle_conv1d(B, T, D, K, u, conv_w, conv_b, state_in, x, state_out);
+  oracle_conv1d(B, T, D, K, u, conv_w, conv_b, state_in, x, state_out, reset);
   oracle_rglru(B, T, D, nb, c, x, W_a, W_x, b_a, b_x, Lambda, h0, y, hT, NULL,
-               NULL, NULL, NULL);
+               NULL, NULL, NULL, reset);
   free(x);
 }
 
@@ -356,6 +379,10 @@ void oracle_decode_step(int B, int D, int nb, int K, double c,
 /* Inputs before the sequence start (the carried conv state) receive no     */
 /* gradient.  Parameter gradients are overwritten (summed over B and T).    */
 /* Any of dhT, dh0, dconv_b may be NULL.                                    */
+/* With document boundaries (reset, see the top of this file) nothing flows  */
+/* across a boundary at step t: a_t delta_t does not reach step t-1 (nor     */
+/* dh0 when t = 0), h_{t-1} counts as zero in dla_t, and the Conv1D adjoint   */
+/* skips every (step, lag) pair whose input lies before the boundary.        */
 /* ------------------------------------------------------------------------ */
 void oracle_backward(int B, int T, int D, int nb, int K, double c,
                      const double *u, const double *W_a, const double *W_x,
@@ -365,7 +392,8 @@ void oracle_backward(int B, int T, int D, int nb, int K, double c,
                      const double *state_in, const double *dy,
                      const double *dhT, double *du, double *dh0, double *dW_a,
                      double *dW_x, double *db_a, double *db_x, double *dLambda,
-                     double *dconv_w, double *dconv_b) {
+                     double *dconv_w, double *dconv_b,
+                     const unsigned char *reset) {
   const int bs = D / nb, S = K - 1;
   const size_t N = (size_t)B * T * D;
   double *x = (double *)malloc(N * sizeof(double));
@@ -379,9 +407,9 @@ void oracle_backward(int B, int T, int D, int nb, int K, double c,
   double *dx = (double *)malloc(N * sizeof(double));
 
   /* forward, keeping every intermediate */
-  oracle_conv1d(B, T, D, K, u, conv_w, conv_b, state_in, x, NULL);
+  oracle_conv1d(B, T, D, K, u, conv_w, conv_b, state_in, x, NULL, reset);
   oracle_rglru(B, T, D, nb, c, x, W_a, W_x, b_a, b_x, Lambda, h0, y, NULL, r,
-               ig, a, m);
+               ig, a, m, reset);
 
   memset(dW_a, 0, (size_t)nb * bs * bs * sizeof(double));
   memset(dW_x, 0, (size_t)nb * bs * bs * sizeof(double));
@@ -402,8 +430,10 @@ void oracle_backward(int B, int T, int D, int nb, int K, double c,
         const size_t o = ((size_t)b * T + t) * D + d;
         double delta = dy[o] + a_next * delta_next;
         if (t == T - 1 && dhT) delta += dhT[(size_t)b * D + d];
+        const int fresh = reset && reset[(size_t)b * T + t]; /* new document */
         const double h_prev =
-            t > 0 ? y[o - D] : (h0 ? h0[(size_t)b * D + d] : 0.0);
+            fresh ? 0.0
+                  : (t > 0 ? y[o - D] : (h0 ? h0[(size_t)b * D + d] : 0.0));
         const double g = ig[o] * x[o];
         const double dla = delta * a[o] * (h_prev - a[o] * g / m[o]);
         const double dg = delta * m[o];
@@ -416,7 +446,7 @@ void oracle_backward(int B, int T, int D, int nb, int K, double c,
         db_a[d] += dp[o];
         db_x[d] += dq[o];
         delta_next = delta;
-        a_next = a[o];
+        a_next = fresh ? 0.0 : a[o]; /* nothing reaches the step before */
       }
       if (dh0) dh0[(size_t)b * D + d] = a_next * delta_next;
     }
@@ -450,6 +480,7 @@ void oracle_backward(int B, int T, int D, int nb, int K, double c,
         for (int k = 0; k < K; ++k) {
           const int sidx = t - k;
           double v;
+          if (boundary_between(reset, T, b, sidx, t)) continue;
           if (sidx >= 0) {
             const size_t o = ((size_t)b * T + sidx) * D + d;
             du[o] += conv_w[(size_t)k * D + d] * dxt;

@@ -586,3 +586,154 @@ def test_scan_adjoint_gives_the_gradient_of_the_decays_by_finite_differences():
         fd = (np.sum(dy * oracle.scan(ap, b, h0, normalize=False)[0])
               - np.sum(dy * oracle.scan(am, b, h0, normalize=False)[0])) / (2 * e)
         assert abs(da[idx] - fd) < 1e-7
+
+
+# --------------------------------------------- document boundaries in packed sequences
+# A row of the batch may hold several documents back to back; reset[b, t] != 0 marks the first
+# step of a document. Nothing crosses such a step (no recurrent state, no Conv1D history), so a
+# packed row must give exactly what its documents give when each is run alone as its own
+# sequence - by the calls without a mask, which the pins above cover.
+def _documents(reset_row, T):
+    starts = [0] + [t for t in range(1, T) if reset_row[t]]
+    return list(zip(starts, starts[1:] + [T]))
+
+
+def _packed_case(seed, T=17):
+    p = small(seed=seed, B=2, T=T, D=8, nb=2, h0=True, bias=True, dy=True, state=True)
+    reset = np.zeros((2, T), np.uint8)
+    reset[0, [4, 5, 11]] = 1            # a one-step document (4), no boundary at step 0
+    reset[1, [0, 9, T - 2]] = 1         # boundary at step 0; the last document has 2 steps
+    return p, reset
+
+
+def test_reset_forward_equals_each_document_run_alone():
+    p, reset = _packed_case(60)
+    T = reset.shape[1]
+    params = (p["W_a"], p["W_x"], p["b_a"], p["b_x"], p["Lambda"], p["conv_w"])
+    y, hT, st = oracle.forward(p["u"], *params, conv_b=p["conv_b"], h0=p["h0"],
+                               state_in=p["state"], reset=reset)
+    for b in range(2):
+        for lo, hi in _documents(reset[b], T):
+            carried = lo == 0 and not reset[b, 0]
+            yd, hd, sd = oracle.forward(p["u"][b:b + 1, lo:hi], *params, conv_b=p["conv_b"],
+                                        h0=p["h0"][b:b + 1] if carried else None,
+                                        state_in=p["state"][b:b + 1] if carried else None)
+            np.testing.assert_allclose(y[b, lo:hi], yd[0], rtol=1e-14, atol=1e-300)
+        np.testing.assert_allclose(hT[b], hd[0], rtol=1e-14)
+        np.testing.assert_array_equal(st[b], sd[0])
+    # row 1's last document has two steps: the oldest state row is the zero in front of it
+    np.testing.assert_array_equal(st[1, 0], np.zeros(8))
+    np.testing.assert_array_equal(st[1, 1:], p["u"][1, T - 2:])
+
+
+def test_reset_special_cases():
+    p = small(seed=61, B=2, T=11, D=8, nb=2, h0=True, bias=True, state=True)
+    params = (p["W_a"], p["W_x"], p["b_a"], p["b_x"], p["Lambda"], p["conv_w"])
+    kw = dict(conv_b=p["conv_b"], h0=p["h0"], state_in=p["state"])
+    plain = oracle.forward(p["u"], *params, **kw)
+    none = oracle.forward(p["u"], *params, reset=np.zeros((2, 11), np.uint8), **kw)
+    for a, b in zip(plain, none):
+        np.testing.assert_array_equal(a, b)
+    # a boundary at step 0 alone = a fresh sequence: the states handed in are not used
+    first = np.zeros((2, 11), np.uint8); first[:, 0] = 1
+    fresh = oracle.forward(p["u"], *params, conv_b=p["conv_b"])
+    at0 = oracle.forward(p["u"], *params, reset=first, **kw)
+    for a, b in zip(fresh, at0):
+        np.testing.assert_array_equal(a, b)
+    # a boundary at every step: each output is the one-step layer on u_t alone,
+    # y_t = sqrt(1 - a_t^2) i_t (w_0 u_t + b) with gates taken from that same x_t
+    every = np.ones((2, 11), np.uint8)
+    y, hT, st = oracle.forward(p["u"], *params, reset=every, **kw)
+    x = p["conv_w"][0] * p["u"] + p["conv_b"]
+    _, _, g = oracle.rglru(x, *params[:5], want_gates=True)
+    np.testing.assert_allclose(y, np.sqrt(1 - g["a"] ** 2) * g["i"] * x, rtol=1e-11, atol=1e-300)
+    np.testing.assert_array_equal(hT, y[:, -1])
+    np.testing.assert_array_equal(st[:, :2], np.zeros((2, 2, 8)))
+    np.testing.assert_array_equal(st[:, 2], p["u"][:, -1])
+
+
+def test_reset_conv_and_recurrence_are_masked_separately_and_consistently():
+    p, reset = _packed_case(62)
+    params = (p["W_a"], p["W_x"], p["b_a"], p["b_x"], p["Lambda"], p["conv_w"])
+    y, hT, st = oracle.forward(p["u"], *params, conv_b=p["conv_b"], h0=p["h0"],
+                               state_in=p["state"], reset=reset)
+    x, st2 = oracle.conv1d(p["u"], p["conv_w"], conv_b=p["conv_b"], state_in=p["state"],
+                           want_state=True, reset=reset)
+    y2, hT2 = oracle.rglru(x, *params[:5], h0=p["h0"], reset=reset)
+    np.testing.assert_array_equal(y, y2)
+    np.testing.assert_array_equal(hT, hT2)
+    np.testing.assert_array_equal(st, st2)
+    # the masked Conv1D by hand: lags that reach behind the document's first step drop out
+    T = reset.shape[1]
+    for b in range(2):
+        for lo, hi in _documents(reset[b], T):
+            for t in range(lo, hi):
+                want = p["conv_b"].copy()
+                for k in range(4):
+                    s = t - k
+                    if s >= lo:
+                        want += p["conv_w"][k] * p["u"][b, s]
+                    elif lo == 0 and not reset[b, 0]:
+                        want += p["conv_w"][k] * p["state"][b, 3 + s]
+                np.testing.assert_allclose(x[b, t], want, rtol=1e-14, atol=1e-15)
+
+
+def test_reset_backward_equals_the_sum_over_documents_run_alone():
+    p, reset = _packed_case(63)
+    T = reset.shape[1]
+    params = (p["W_a"], p["W_x"], p["b_a"], p["b_x"], p["Lambda"], p["conv_w"])
+    g = oracle.backward(p["u"], *params, p["dy"], conv_b=p["conv_b"], h0=p["h0"],
+                        state_in=p["state"], dhT=p["dhT"], reset=reset)
+    total = {k: np.zeros_like(v) for k, v in g.items() if k not in ("du", "dh0")}
+    for b in range(2):
+        docs = _documents(reset[b], T)
+        for lo, hi in docs:
+            carried = lo == 0 and not reset[b, 0]
+            gd = oracle.backward(p["u"][b:b + 1, lo:hi], *params, p["dy"][b:b + 1, lo:hi],
+                                 conv_b=p["conv_b"],
+                                 h0=p["h0"][b:b + 1] if carried else None,
+                                 state_in=p["state"][b:b + 1] if carried else None,
+                                 dhT=p["dhT"][b:b + 1] if hi == T else None)
+            np.testing.assert_allclose(g["du"][b, lo:hi], gd["du"][0], rtol=1e-12, atol=1e-300)
+            if lo == 0:
+                want = gd["dh0"][0] if carried else np.zeros(8)
+                np.testing.assert_allclose(g["dh0"][b], want, rtol=1e-12, atol=0)
+            for k in total:
+                total[k] += gd[k]
+    for k in total:
+        np.testing.assert_allclose(g[k], total[k], rtol=1e-11, atol=1e-14, err_msg=k)
+
+
+def test_reset_backward_matches_central_finite_differences():
+    p = small(seed=64, B=2, T=7, D=8, nb=2, h0=True, bias=True, dy=True, state=True)
+    reset = np.zeros((2, 7), np.uint8)
+    reset[0, [2, 3]] = 1
+    reset[1, [0, 5]] = 1
+    dy, dhT = p["dy"], p["dhT"]
+
+    def loss(**over):
+        q = dict(p); q.update(over)
+        y, hT, _ = oracle.forward(q["u"], q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"],
+                                  q["conv_w"], conv_b=q["conv_b"], h0=q["h0"],
+                                  state_in=q["state"], reset=reset)
+        return float(np.sum(dy * y) + np.sum(dhT * hT))
+
+    g = oracle.backward(p["u"], p["W_a"], p["W_x"], p["b_a"], p["b_x"], p["Lambda"], p["conv_w"],
+                        dy, conv_b=p["conv_b"], h0=p["h0"], state_in=p["state"], dhT=dhT,
+                        reset=reset)
+    names = {"u": "du", "h0": "dh0", "W_a": "dW_a", "W_x": "dW_x", "b_a": "db_a", "b_x": "db_x",
+             "Lambda": "dLambda", "conv_w": "dconv_w", "conv_b": "dconv_b"}
+    eps = 1e-6
+    for k, gk in names.items():
+        base = p[k]
+        fd = np.zeros_like(base)
+        it = np.nditer(base, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            hi = base.copy(); hi[idx] += eps
+            lo = base.copy(); lo[idx] -= eps
+            fd[idx] = (loss(**{k: hi}) - loss(**{k: lo})) / (2 * eps)
+        scale = np.abs(fd).max() + 1e-12
+        err = np.abs(g[gk] - fd).max() / scale
+        assert err < 2e-7, (k, err)
+    np.testing.assert_array_equal(g["dh0"][1], np.zeros(8))
