@@ -84,6 +84,8 @@ extern "C" {
 #define RGLRU_OP_SCAN 4
 #define RGLRU_OP_FORWARD_MERGE 5
 #define RGLRU_OP_BACKWARD_MERGE 6
+#define RGLRU_OP_FORWARD_PACKED 7
+#define RGLRU_OP_BACKWARD_PACKED 8
 
 typedef struct rglru_shape {
   int32_t B;          /* sequences                                  (>= 1)                 */
@@ -238,6 +240,35 @@ int rglru_backward(const rglru_shape *shape, const rglru_params *params, const v
                    const void *dy, const float *dhT, void *du, float *dh0,
                    const rglru_param_grads *grads, void *workspace, size_t workspace_bytes,
                    void *stream);
+
+/*
+ * Forward and backward over packed sequences: a row of the batch may hold several documents
+ * back to back. Sections 2.3-2.4 define the Conv1D and the recurrence per sequence and say
+ * nothing about packing; the convention here is that NOTHING crosses the first step of a
+ * document: at a step t with reset[b][t] != 0 the recurrence starts from h_{t-1} := 0, the
+ * Conv1D takes every input before t as zero, and in the backward no gradient flows from the
+ * document into the steps (or the incoming states) in front of it. Each document then gets
+ * exactly what it would get as a sequence of its own.
+ *   reset      [B][T] bytes, read, or NULL (no boundaries: rglru_forward / rglru_backward).
+ *              reset[b][0] != 0 makes row b ignore h0 and conv_state_in.
+ *   hT, conv_state_out   the states after the last step, those of the row's last document: ring
+ *              slots of inputs in front of that document's first step hold zeros.
+ *   dh0        zero for a row whose reset[b][0] != 0.
+ *   every other argument: as in rglru_forward / rglru_backward; conv_width 0 is accepted.
+ *   workspace  the forward needs none; the backward needs
+ *              rglru_workspace_bytes(shape, RGLRU_OP_BACKWARD_PACKED) bytes.
+ * These calls run on the library's general kernels (one workgroup per (sequence, gate block),
+ * plain fp32 arithmetic for either storage type) for every shape, not on the matrix-core
+ * kernels of the unpacked calls; no kernel waits on another, so there is no workspace status.
+ */
+int rglru_forward_packed(const rglru_shape *shape, const rglru_params *params, const void *u,
+                         const uint8_t *reset, const float *h0, const void *conv_state_in,
+                         int64_t pos0, void *y, float *hT, void *conv_state_out, void *stream);
+int rglru_backward_packed(const rglru_shape *shape, const rglru_params *params, const void *u,
+                          const uint8_t *reset, const float *h0, const void *conv_state_in,
+                          int64_t pos0, const void *y, const void *dy, const float *dhT, void *du,
+                          float *dh0, const rglru_param_grads *grads, void *workspace,
+                          size_t workspace_bytes, void *stream);
 
 /* flags of the merge calls */
 #define RGLRU_MERGE_GELU_TANH 1u /* GeLU in its tanh form instead of z * Phi(z)             */

@@ -14,6 +14,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_TIMEOUT = 0, -
 F32, BF16 = 0, 1
 OP_CONV1D, OP_FORWARD, OP_DECODE, OP_BACKWARD, OP_SCAN = 0, 1, 2, 3, 4
 OP_FORWARD_MERGE, OP_BACKWARD_MERGE = 5, 6
+OP_FORWARD_PACKED, OP_BACKWARD_PACKED = 7, 8
 MERGE_GELU_TANH, MERGE_SEPARATE = 1, 2
 SCAN_LOG_A, SCAN_NO_INPUT_SCALE, SCAN_ADJOINT = 1, 2, 4
 STATIC_SCRATCH_BYTES = 16 << 20
@@ -60,6 +61,10 @@ def _load():
     lib.rglru_decode_step.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp]
     lib.rglru_decode_step_at.argtypes = [sp, pp, vp, vp, vp, vp, vp, vp]
     lib.rglru_backward.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp, vp, vp, vp, gp, vp, sz, vp]
+    lib.rglru_forward_packed.argtypes = [sp, pp, vp, vp, vp, vp, i64, vp, vp, vp, vp]
+    lib.rglru_forward_packed.restype = ctypes.c_int
+    lib.rglru_backward_packed.argtypes = [sp, pp, vp, vp, vp, vp, i64, vp, vp, vp, vp, vp, gp, vp, sz, vp]
+    lib.rglru_backward_packed.restype = ctypes.c_int
     lib.rglru_forward_merge.argtypes = [sp, pp, vp, vp, vp, vp, i64, ctypes.c_uint, vp, vp, vp, vp, vp, sz, vp]
     lib.rglru_backward_merge.argtypes = [sp, pp, vp, vp, vp, vp, i64, ctypes.c_uint, vp, vp, vp, vp, vp, vp,
                                          gp, vp, sz, vp]
@@ -197,6 +202,21 @@ def rglru_backward(shape, params, u, h0, conv_state_in, pos0, y, dy, dhT, du, dh
                                _addr(conv_state_in), pos0, _addr(y), _addr(dy), _addr(dhT),
                                _addr(du), _addr(dh0), _ref(grads), _addr(workspace),
                                workspace_bytes, _stream(stream)))
+
+
+def rglru_forward_packed(shape, params, u, reset, h0, conv_state_in, pos0, y, hT, conv_state_out,
+                         stream=None):
+    _check(_lib.rglru_forward_packed(_ref(shape), _ref(params), _addr(u), _addr(reset), _addr(h0),
+                                     _addr(conv_state_in), pos0, _addr(y), _addr(hT),
+                                     _addr(conv_state_out), _stream(stream)))
+
+
+def rglru_backward_packed(shape, params, u, reset, h0, conv_state_in, pos0, y, dy, dhT, du, dh0,
+                          grads, workspace, workspace_bytes, stream=None):
+    _check(_lib.rglru_backward_packed(_ref(shape), _ref(params), _addr(u), _addr(reset), _addr(h0),
+                                      _addr(conv_state_in), pos0, _addr(y), _addr(dy), _addr(dhT),
+                                      _addr(du), _addr(dh0), _ref(grads), _addr(workspace),
+                                      workspace_bytes, _stream(stream)))
 
 
 def rglru_forward_merge(shape, params, u, branch, h0, conv_state_in, pos0, flags, out, y, hT,

@@ -164,6 +164,10 @@ size_t workspace_need(const rglru_shape *s, int op) {
       if (s->act_dtype == RGLRU_BF16 && s->D % 256 == 0 && s->T >= 1)
         return scan_tiled_ws_bytes(s->B, s->T, s->D);
       return 0;
+    case RGLRU_OP_FORWARD_PACKED:
+      return 0;
+    case RGLRU_OP_BACKWARD_PACKED:
+      return backward_generic_ws_bytes(s->B, s->T, s->D, s->num_blocks);
     case RGLRU_OP_BACKWARD_MERGE:   // dy (+ dy_lo) between the merge adjoint and the backward, then the backward's own
       return merge_dy_bytes(s) + workspace_need(s, RGLRU_OP_BACKWARD);
     case RGLRU_OP_FORWARD_MERGE:
@@ -216,7 +220,8 @@ namespace {
 int backward_checks(const rglru_shape *shape, const rglru_params *params, const void *u,
                     const float *h0, const void *conv_state_in, int64_t pos0, const void *y,
                     const void *dy, const float *dhT, void *du, float *dh0,
-                    const rglru_param_grads *grads, void *workspace, size_t workspace_bytes) {
+                    const rglru_param_grads *grads, void *workspace, size_t workspace_bytes,
+                    bool with_workspace = true) {
   CHECK(check_shape(shape, true, true, 1));
   CHECK(check_params(shape, params));
   const size_t as = act_size(shape);
@@ -237,8 +242,8 @@ int backward_checks(const rglru_shape *shape, const rglru_params *params, const 
   CHECK(check_ptr(grads->dLambda, "grads.dLambda", 4, true));
   CHECK(check_ptr(grads->dconv_w, "grads.dconv_w", 4, shape->conv_width != 0));
   CHECK(check_ptr(grads->dconv_b, "grads.dconv_b", 4, false));
-  CHECK(check_workspace(workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_BACKWARD)));
-
+  if (with_workspace)
+    CHECK(check_workspace(workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_BACKWARD)));
   return RGLRU_OK;
 }
 }  // namespace
@@ -298,7 +303,7 @@ int rglru_timing_get(int index, const char **name, float *ms) {
 
 const char *rglru_last_error(void) { return g_err; }
 
-int rglru_version(void) { return 300; }
+int rglru_version(void) { return 310; }
 
 int rglru_set_max_time_slices(int max_slices) {
   if (max_slices < 0) return fail(RGLRU_ERR_INVALID_ARG, "max_slices must be >= 0 (0 = automatic)");
@@ -307,11 +312,11 @@ int rglru_set_max_time_slices(int max_slices) {
 }
 
 size_t rglru_workspace_bytes(const rglru_shape *shape, int op) {
-  if (op < RGLRU_OP_CONV1D || op > RGLRU_OP_BACKWARD_MERGE) return 0;
+  if (op < RGLRU_OP_CONV1D || op > RGLRU_OP_BACKWARD_PACKED) return 0;
   char keep[sizeof(g_err)];
   memcpy(keep, g_err, sizeof(g_err));
   const bool blocks = op != RGLRU_OP_CONV1D && op != RGLRU_OP_SCAN;
-  const bool bwd = op == RGLRU_OP_BACKWARD || op == RGLRU_OP_BACKWARD_MERGE;
+  const bool bwd = op == RGLRU_OP_BACKWARD || op == RGLRU_OP_BACKWARD_MERGE || op == RGLRU_OP_BACKWARD_PACKED;
   const int rc = check_shape(shape, blocks, op != RGLRU_OP_DECODE, bwd ? 1 : 0);
   memcpy(g_err, keep, sizeof(g_err));  // a size query does not disturb the error string
   if (rc != RGLRU_OK) return 0;
@@ -419,6 +424,37 @@ int rglru_forward(const rglru_shape *shape, const rglru_params *params, const vo
   const bool bf = shape->act_dtype == RGLRU_BF16;
   hipStream_t s = (hipStream_t)stream;
   CHECK(forward_dispatch(q, bf, s));
+  g_err[0] = 0;
+  return RGLRU_OK;
+}
+
+int rglru_forward_packed(const rglru_shape *shape, const rglru_params *params, const void *u,
+                         const uint8_t *reset, const float *h0, const void *conv_state_in, int64_t pos0,
+                         void *y, float *hT, void *conv_state_out, void *stream) {
+  CHECK(check_shape(shape, true, true, 0));
+  CHECK(check_params(shape, params));
+  const size_t as = act_size(shape);
+  if (pos0 < 0) return fail(RGLRU_ERR_INVALID_ARG, "pos0 must be >= 0");
+  CHECK(check_ptr(u, "u", as, shape->T > 0));
+  CHECK(check_ptr(y, "y", as, shape->T > 0));
+  CHECK(check_ptr(reset, "reset", 1, false));
+  CHECK(check_ptr(h0, "h0", 4, false));
+  CHECK(check_ptr(hT, "hT", 4, false));
+  CHECK(check_ptr(conv_state_in, "conv_state_in", as, false));
+  CHECK(check_ptr(conv_state_out, "conv_state_out", as, false));
+
+  Problem q;
+  memset(&q, 0, sizeof(q));
+  fill_params(q, shape, params);
+  q.pos0 = pos0; q.u = u; q.h0 = h0; q.state_in = conv_state_in; q.reset = reset;
+  q.y = y; q.hT = hT; q.state_out = conv_state_out;
+  if (shape->conv_width == 0) q.state_in = q.state_out = nullptr;
+  const bool bf = shape->act_dtype == RGLRU_BF16;
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t e = launch_forward_generic(q, bf, s);
+  // the new ring state is written after the last read of the incoming one (they may alias)
+  if (e == hipSuccess) e = launch_state_update(q, bf, s);
+  if (e != hipSuccess) return hip_fail(e, "forward launch");
   g_err[0] = 0;
   return RGLRU_OK;
 }
@@ -570,6 +606,31 @@ int rglru_backward(const rglru_shape *shape, const rglru_params *params, const v
                    void *stream) {
   return backward_run(shape, params, u, h0, conv_state_in, pos0, y, dy, nullptr, dhT, du, dh0, grads, workspace,
                       workspace_bytes, stream);
+}
+
+int rglru_backward_packed(const rglru_shape *shape, const rglru_params *params, const void *u,
+                          const uint8_t *reset, const float *h0, const void *conv_state_in, int64_t pos0,
+                          const void *y, const void *dy, const float *dhT, void *du, float *dh0,
+                          const rglru_param_grads *grads, void *workspace, size_t workspace_bytes,
+                          void *stream) {
+  CHECK(backward_checks(shape, params, u, h0, conv_state_in, pos0, y, dy, dhT, du, dh0, grads, nullptr, 0,
+                        false));
+  CHECK(check_ptr(reset, "reset", 1, false));
+  CHECK(check_workspace(workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_BACKWARD_PACKED)));
+  Problem q;
+  memset(&q, 0, sizeof(q));
+  fill_params(q, shape, params);
+  q.pos0 = pos0; q.u = u; q.h0 = h0; q.state_in = conv_state_in; q.reset = reset;
+  q.y_in = y; q.dy = dy; q.dhT = dhT; q.du = du; q.dh0 = dh0; q.g = *grads;
+  if (shape->conv_width == 0) {
+    q.state_in = nullptr;
+    q.g.dconv_w = q.g.dconv_b = nullptr;
+  }
+  q.ws = workspace; q.ws_bytes = workspace_bytes;
+  const hipError_t e = launch_backward_generic(q, shape->act_dtype == RGLRU_BF16, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "backward launch");
+  g_err[0] = 0;
+  return RGLRU_OK;
 }
 
 int rglru_forward_merge(const rglru_shape *shape, const rglru_params *params, const void *u,

@@ -56,13 +56,34 @@ __device__ __forceinline__ float input_at(const Problem &p, int b, int t, int d)
   return ldf((const AT *)p.state_in, ((size_t)b * 3 + ring_slot(p.pos0 + t)) * p.D + d);
 }
 
+// true where step t of sequence b starts a new document (packed sequences)
+__device__ __forceinline__ bool starts_document(const Problem &p, int b, int t) {
+  return p.reset && p.reset[(size_t)b * p.T + t] != 0;
+}
+
+// the largest lag (0..3) the Conv1D may reach back from step t without crossing the first step
+// of a document: inputs in front of a document's start count as zeros
+__device__ __forceinline__ int lags_at(const Problem &p, int b, int t) {
+  if (!p.reset) return 3;
+  int n = 0;
+#pragma unroll
+  for (int k = 1; k < 4; ++k) {
+    const int tb = t - k + 1;   // lag k crosses the starts at steps tb .. t
+    if (tb >= 0 && p.reset[(size_t)b * p.T + tb]) break;
+    n = k;
+  }
+  return n;
+}
+
 // Conv1D output x[b,t,d] (Section 2.3), lag-indexed taps
 template <typename AT>
 __device__ __forceinline__ float conv_at(const Problem &p, int b, int t, int d) {
   if (!p.conv_w) return input_at<AT>(p, b, t, d);   // no Conv1D: x_t = u_t
   float acc = p.conv_b ? p.conv_b[d] : 0.f;
+  const int n = lags_at(p, b, t);
 #pragma unroll
-  for (int k = 0; k < 4; ++k) acc = fmaf(p.conv_w[(size_t)k * p.D + d], input_at<AT>(p, b, t - k, d), acc);
+  for (int k = 0; k < 4; ++k)
+    if (k <= n) acc = fmaf(p.conv_w[(size_t)k * p.D + d], input_at<AT>(p, b, t - k, d), acc);
   return acc;
 }
 
@@ -119,6 +140,11 @@ __global__ void __launch_bounds__(NTHREADS) state_update_kernel(Problem p) {
       v = ldf((const AT *)p.u, ((size_t)b * p.T + (size_t)(npos - p.pos0)) * p.D + d);
     else
       v = p.state_in ? ldf((const AT *)p.state_in, idx) : 0.f;
+    if (p.reset) {   // an input in front of the last document's first step is not part of its history
+      const long long first = npos - p.pos0 + 1;   // (at least T - 2: at most three steps to look at)
+      for (int t = first > 0 ? (int)first : 0; t < p.T; ++t)
+        if (p.reset[(size_t)b * p.T + t]) v = 0.f;
+    }
     stf((AT *)p.state_out, idx, v);
   }
 }
@@ -152,6 +178,7 @@ __global__ void __launch_bounds__(NTHREADS) forward_kernel(Problem p) {
       for (int tt = 0; tt < GT; ++tt) {
         if (tt < nt) {
           const Gates gt = gate_math(pa[tt], qa[tt], neg_cs);
+          if (starts_document(p, b, t0 + tt)) h = 0.f;
           h = fmaf(gt.a, h, gt.m * (gt.i * xs[tt * bs + j]));  // eq. (4)
           stf((AT *)p.y, ((size_t)b * p.T + t0 + tt) * p.D + d, h);
         }
@@ -291,8 +318,10 @@ __global__ void __launch_bounds__(NTHREADS) bwd_pointwise_kernel(Problem p, BwdW
           const Gates gt = gate_math(pa[tt], qa[tt], neg_cs);
           const float x = xs[tt * bs + j];
           const float delta = ldf((const AT *)p.dy, o) + (p.dy_lo ? ldf((const AT *)p.dy_lo, o) : 0.f) + cy;
-          const float hprev = t > 0 ? ldf((const AT *)p.y_in, o - p.D)
-                                    : (p.h0 ? p.h0[(size_t)b * p.D + d] : 0.f);
+          const bool fresh = starts_document(p, b, t);   // h_{t-1} := 0, nothing flows further back
+          const float hprev = fresh ? 0.f
+                              : t > 0 ? ldf((const AT *)p.y_in, o - p.D)
+                                      : (p.h0 ? p.h0[(size_t)b * p.D + d] : 0.f);
           const float gin = gt.i * x;
           // d m / d a = -a / m; the term vanishes with the gate in the limit m -> 0
           const float corr = gt.m > 0.f ? gt.a * gin / gt.m : 0.f;
@@ -309,7 +338,7 @@ __global__ void __launch_bounds__(NTHREADS) bwd_pointwise_kernel(Problem p, BwdW
           w.dp[o] = dpv;
           w.dq[o] = dqv;
           w.dx[o] = dg * gt.i;
-          cy = gt.a * delta;
+          cy = fresh ? 0.f : gt.a * delta;
         }
       }
       carry[j] = cy;
@@ -368,14 +397,16 @@ __global__ void __launch_bounds__(NTHREADS) bwd_conv_input_kernel(Problem p, Bwd
   for (size_t idx = (size_t)blockIdx.x * NTHREADS + threadIdx.x; idx < n;
        idx += (size_t)gridDim.x * NTHREADS) {
     const int d = (int)(idx % p.D);
-    const int t = (int)((idx / p.D) % p.T);
+    const int t = (int)((idx / p.D) % p.T), b = (int)(idx / ((size_t)p.T * p.D));
     float acc = 0.f;
     if (!p.conv_w) {
       acc = w.dx[idx];   // no Conv1D: du = dx
     } else {
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
-        if (t + k < p.T) acc = fmaf(p.conv_w[(size_t)k * p.D + d], w.dx[idx + (size_t)k * p.D], acc);
+      for (int k = 0; k < 4; ++k) {
+        if (t + k >= p.T || (k > 0 && starts_document(p, b, t + k))) break;   // x of a later document does not see u_t
+        acc = fmaf(p.conv_w[(size_t)k * p.D + d], w.dx[idx + (size_t)k * p.D], acc);
+      }
     }
     stf((AT *)p.du, idx, acc);
   }
@@ -391,14 +422,16 @@ __global__ void __launch_bounds__(NTHREADS) bwd_conv_weight_kernel(Problem p, Bw
   const int b = blockIdx.y / nct, c = blockIdx.y % nct;
   const int t0 = c * w.tchunk, t1 = min(p.T, t0 + w.tchunk);
   float s[5] = {0.f, 0.f, 0.f, 0.f, 0.f}, sc[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
-  float u1 = input_at<AT>(p, b, t0 - 1, d), u2 = input_at<AT>(p, b, t0 - 2, d),
-        u3 = input_at<AT>(p, b, t0 - 3, d);
+  const int n0 = t0 < t1 ? lags_at(p, b, t0) : 3;   // history in front of a document's start is zero
+  float u1 = n0 >= 1 ? input_at<AT>(p, b, t0 - 1, d) : 0.f, u2 = n0 >= 2 ? input_at<AT>(p, b, t0 - 2, d) : 0.f,
+        u3 = n0 >= 3 ? input_at<AT>(p, b, t0 - 3, d) : 0.f;
   for (int tc = t0; tc < t1; tc += 16) {   // short plain sums, added up with compensation
     float l[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
     const int te = min(t1, tc + 16);
     for (int t = tc; t < te; ++t) {
       const size_t o = ((size_t)b * p.T + t) * p.D + d;
       const float dx = w.dx[o], u0 = ldf((const AT *)p.u, o);
+      if (starts_document(p, b, t)) u1 = u2 = u3 = 0.f;
       l[0] = fmaf(dx, u0, l[0]);
       l[1] = fmaf(dx, u1, l[1]);
       l[2] = fmaf(dx, u2, l[2]);

@@ -44,6 +44,8 @@ struct Problem {
   const float *b_a, *b_x, *Lambda, *conv_w, *conv_b;   // conv_w null: no Conv1D, x_t = u_t (identity tap)
   const float *h0;
   const void *state_in;
+  const unsigned char *reset;  // [B][T] or null: non-zero where a new document starts (packed sequences):
+                               // h_{t-1} := 0 and the Conv1D sees zeros before that step
   void *y;
   float *hT;
   void *state_out;

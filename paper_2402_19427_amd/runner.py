@@ -82,6 +82,32 @@ class DeviceProblem:
         R.rglru_forward(sh, self.params, u, h0, state_in, pos0, y, hT, st, ws, n, stream)
         return y, hT, st
 
+    def forward_packed(self, u, reset, h0=None, state_in=None, pos0=0, stream=None):
+        """reset: uint8 device tensor [B,T], non-zero where a document starts."""
+        B, T, D = u.shape
+        sh = self.shape(T=T, B=B)
+        y = self.empty_act(B, T, D)
+        hT = self.empty_f32(B, D)
+        st = self.empty_act(B, 3, D)
+        R.rglru_forward_packed(sh, self.params, u, reset, h0, state_in, pos0, y, hT, st, stream)
+        return y, hT, st
+
+    def backward_packed(self, u, reset, y, dy, h0=None, state_in=None, pos0=0, dhT=None,
+                        stream=None):
+        B, T, D = u.shape
+        sh = self.shape(T=T, B=B)
+        ws, n = self.workspace(sh, R.OP_BACKWARD_PACKED)
+        du = self.empty_act(B, T, D)
+        dh0 = self.empty_f32(B, D)
+        g = self.alloc_grads()
+        pg = R.make_param_grads(g["dW_a"], g["dW_x"], g["db_a"], g["db_x"], g["dLambda"],
+                                g["dconv_w"], g["dconv_b"])
+        R.rglru_backward_packed(sh, self.params, u, reset, h0, state_in, pos0, y, dy, dhT, du,
+                                dh0, pg, ws, n, stream)
+        out = dict(g)
+        out["du"], out["dh0"] = du, dh0
+        return out
+
     def forward_merge(self, u, branch, h0=None, state_in=None, pos0=0, flags=0, keep_y=True,
                       stream=None):
         B, T, D = u.shape

@@ -146,6 +146,26 @@ def make_branch(B, T, D, act="bf16", seed=0):
     return round_to_act(rng.standard_normal((B, T, D), dtype=np.float32), act)
 
 
+def make_resets(B, T, seed=0, mean_len=64):
+    """Document-boundary mask [B,T] uint8 for packed sequences: non-zero where a document
+    starts. Document lengths are geometric with mean `mean_len` (at least one step), the length
+    mix of short and long documents packed into fixed-length training rows; row b starts a
+    document at step 0 when b is odd (even rows continue a document carried in through h0 and
+    the conv state). Row 0 additionally gets a one-step document and a boundary at the very
+    last step where they fit."""
+    rng = np.random.Generator(np.random.PCG64(5000 + seed))
+    m = np.zeros((B, T), np.uint8)
+    for b in range(B):
+        t = 0 if b % 2 == 1 else int(rng.geometric(1.0 / mean_len))
+        while t < T:
+            m[b, t] = 1
+            t += int(rng.geometric(1.0 / mean_len))
+    if T >= 8:
+        m[0, 4] = m[0, 5] = 1
+        m[0, T - 1] = 1
+    return m
+
+
 def make_workload(name, **override):
     """Inputs of one of the named workloads C0..C4 (sizes may be overridden for sampling)."""
     w = CONFIGS[name]

@@ -149,6 +149,30 @@ def test_backward_validation_and_workspace():
     assert e.value.code == R.ERR_INVALID_ARG
 
 
+def test_packed_calls_validation_and_workspace():
+    s = R.make_shape(2, 8, 512, 2, R.BF16)
+    assert R.rglru_workspace_bytes(s, R.OP_FORWARD_PACKED) == 0
+    need = R.rglru_workspace_bytes(s, R.OP_BACKWARD_PACKED)
+    assert need >= 4 * 2 * 8 * 512 * 4 and need % 256 == 0
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_forward_packed(s, params(), None, FAKE, None, None, 0, FAKE, None, None)
+    assert e.value.code == R.ERR_INVALID_ARG and "u" in str(e.value)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_forward_packed(s, params(), FAKE, FAKE, None, None, -1, FAKE, None, None)
+    assert e.value.code == R.ERR_INVALID_ARG
+    g = R.make_param_grads(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)
+    args = (s, params(), FAKE, FAKE + 1, None, None, 0, FAKE, FAKE, None, FAKE, None, g)   # the mask is bytes: any address
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_backward_packed(*args, FAKE, need - 1)
+    assert e.value.code == R.ERR_WORKSPACE
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_backward_packed(*args, None, 0)
+    assert e.value.code == R.ERR_WORKSPACE
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_workspace_status(s, R.OP_BACKWARD_PACKED, None)
+    assert e.value.code == R.ERR_INVALID_ARG
+
+
 def test_workspace_query_is_zero_for_invalid_shapes_and_keeps_error_string():
     bad = R.make_shape(2, 8, 16, 3, R.F32)
     with pytest.raises(R.RglruError):

@@ -741,3 +741,66 @@ def test_an_expired_wait_poisons_later_calls_until_it_is_reported():
         assert gen.rel_err(rn.to_host(g_one["du"]), rn.to_host(g_ok["du"])) < 1e-2
     finally:
         R.rglru_set_max_time_slices(0)
+
+
+# ------------------------------------------------- packed sequences (document boundaries)
+PACKED = [
+    # B, T, D, nb, act, mean document length
+    (2, 37, 96, 3, "f32", 6),
+    (3, 5, 40, 5, "f32", 2),
+    (3, 300, 512, 2, "bf16", 40),
+    (2, 130, 320, 2, "bf16", 16),
+    (1, 700, 1024, 2, "bf16", 100),
+    (4, 2, 64, 2, "bf16", 1),      # fewer steps than the filter is wide, a boundary at most steps
+]
+
+
+@pytest.mark.parametrize("B,T,D,nb,act,mean_len", PACKED)
+def test_packed_forward_and_backward_match_oracle(B, T, D, nb, act, mean_len):
+    import torch
+    rn = runner()
+    inp = gen.make_inputs(B, T, D, nb, act=act, seed=B * 100 + T + D + 1, h0=True, state=True,
+                          bias=True, dy=True)
+    reset = gen.make_resets(B, T, seed=T + D, mean_len=mean_len)
+    pos0 = 4
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    u, h0 = rn.to_device(inp["u"], act), rn.to_device(inp["h0"], "f32")
+    ring = rn.to_device(gen.ring_from_chrono(inp["state"], pos0), act)
+    rdev = torch.from_numpy(reset).cuda()
+    y, hT, st = dp.forward_packed(u, rdev, h0=h0, state_in=ring, pos0=pos0)
+    q = f64(inp)
+    args = (q["u"], q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"], q["conv_w"])
+    y_ref, hT_ref, st_ref = oracle.forward(*args, conv_b=q["conv_b"], h0=q["h0"],
+                                           state_in=q["state"], reset=reset)
+    assert gen.rel_err(rn.to_host(y), y_ref) < TOL[act]
+    assert gen.rel_err(rn.to_host(hT), hT_ref) < TOL[act]
+    np.testing.assert_array_equal(gen.chrono_from_ring(rn.to_host(st), pos0 + T), st_ref)
+    g = dp.backward_packed(u, rdev, y, rn.to_device(inp["dy"], act), h0=h0, state_in=ring,
+                           pos0=pos0, dhT=rn.to_device(inp["dhT"], "f32"))
+    ref = oracle.backward(*args, q["dy"], conv_b=q["conv_b"], h0=q["h0"], state_in=q["state"],
+                          dhT=q["dhT"], reset=reset)
+    for k in ("du", "dh0"):
+        assert gen.rel_err(rn.to_host(g[k]), ref[k]) < TOL[act], k
+    for k in ("dW_a", "dW_x", "db_a", "db_x", "dLambda", "dconv_w", "dconv_b"):
+        assert gen.rel_err(rn.to_host(g[k]), ref[k]) < GRAD_TOL[act], k
+    # rows that start a document at step 0 take nothing from, and send nothing to, the states
+    for b in range(B):
+        if reset[b, 0]:
+            np.testing.assert_array_equal(rn.to_host(g["dh0"])[b], np.zeros(D, np.float32))
+
+
+def test_packed_calls_without_a_mask_are_the_plain_calls():
+    rn = runner()
+    B, T, D, nb, act = 2, 50, 96, 3, "f32"
+    inp = gen.make_inputs(B, T, D, nb, act=act, seed=9, h0=True, dy=True)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    u, h0 = rn.to_device(inp["u"], act), rn.to_device(inp["h0"], "f32")
+    y, hT, st = dp.forward(u, h0=h0)
+    y2, hT2, st2 = dp.forward_packed(u, None, h0=h0)
+    np.testing.assert_array_equal(rn.to_host(y), rn.to_host(y2))
+    np.testing.assert_array_equal(rn.to_host(hT), rn.to_host(hT2))
+    np.testing.assert_array_equal(rn.to_host(st), rn.to_host(st2))
+    dy = rn.to_device(inp["dy"], act)
+    g, g2 = dp.backward(u, y, dy, h0=h0), dp.backward_packed(u, None, y, dy, h0=h0)
+    for k in g:
+        np.testing.assert_array_equal(rn.to_host(g[k]), rn.to_host(g2[k]))
