@@ -7,13 +7,16 @@ from it.  Only the test suite, the smoke check and the benchmark's
 ``cpu_baseline`` leg may import it; the product path never does.
 
 Every function takes and returns float64 numpy arrays in the layouts given at
-the top of ``rglru_oracle.c``.
+the top of ``rglru_oracle.c``.  The complex-gated variant of Appendix B lives in
+``cglru.py`` (plain numpy, complex128) and is re-exported here.
 """
 import ctypes
 import os
 import subprocess
 
 import numpy as np
+
+from .cglru import cg_backward, cg_decode_step, cg_forward, cg_gates, cg_lru  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "rglru_oracle.c")

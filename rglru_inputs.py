@@ -122,6 +122,42 @@ def make_inputs(B, T, D, nb, act="bf16", seed=0, h0=False, dy=False, state=False
     return out
 
 
+def make_cg_inputs(B, T, D, nb, act="bf16", seed=0, h0=False, dy=False, state=False,
+                   decode_tokens=0, bias=False):
+    """Seeded tensors for the complex-gated variant (Appendix B): D real channels, H = D/2
+    complex ones, gate weights [nb, hs, 2 hs] with hs = H / nb (LeCun normal over the 2 hs
+    inputs of a block), b_a / b_x / Lambda / theta [H]. Lambda as for the real layer. The
+    appendix gives no initialisation for theta: it is drawn uniform in [0, pi/10] (small
+    phases, the choice of the LRU paper the appendix builds on). Everything else as make_inputs."""
+    assert D % 2 == 0 and (D // 2) % nb == 0
+    H = D // 2
+    hs = H // nb
+    rng = np.random.Generator(np.random.PCG64(seed))
+    nrm = lambda *shape: rng.standard_normal(shape, dtype=np.float32)
+    out = {}
+    out["u"] = round_to_act(nrm(B, T, D), act)
+    scale = np.float32(1.0 / np.sqrt(2 * hs))
+    out["W_a"] = round_to_act(nrm(nb, hs, 2 * hs) * scale, act)
+    out["W_x"] = round_to_act(nrm(nb, hs, 2 * hs) * scale, act)
+    out["conv_w"] = nrm(CONV_WIDTH, D) * np.float32(0.5)
+    out["Lambda"] = make_lambda(rng, H)
+    out["theta"] = rng.uniform(0.0, np.pi / 10, size=H).astype(np.float32)
+    out["h0"] = nrm(B, D) if h0 else None
+    out["dy"] = round_to_act(nrm(B, T, D), act) if dy else None
+    out["dhT"] = nrm(B, D) if dy else None
+    out["state"] = round_to_act(nrm(B, CONV_WIDTH - 1, D), act) if state else None
+    out["u_dec"] = round_to_act(nrm(decode_tokens, B, D), act) if decode_tokens else None
+    if bias:
+        out["b_a"] = nrm(H) * np.float32(0.5)
+        out["b_x"] = nrm(H) * np.float32(0.5)
+        out["conv_b"] = nrm(D) * np.float32(0.1)
+    else:
+        out["b_a"] = np.zeros(H, np.float32)
+        out["b_x"] = np.zeros(H, np.float32)
+        out["conv_b"] = None
+    return out
+
+
 def make_scan_inputs(B, T, D, act="bf16", seed=0, log_a=False, h0=True):
     """Seeded inputs of the scan-only entry point: decays distributed like the layer's own
     (a base decay per channel with base^8 ~ U[0.9, 0.999], raised to a per-element power in
