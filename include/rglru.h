@@ -86,6 +86,7 @@ extern "C" {
 #define RGLRU_OP_BACKWARD_MERGE 6
 #define RGLRU_OP_FORWARD_PACKED 7
 #define RGLRU_OP_BACKWARD_PACKED 8
+#define RGLRU_OP_CG_BACKWARD 9
 
 typedef struct rglru_shape {
   int32_t B;          /* sequences                                  (>= 1)                 */
@@ -269,6 +270,67 @@ int rglru_backward_packed(const rglru_shape *shape, const rglru_params *params, 
                           int64_t pos0, const void *y, const void *dy, const float *dhT, void *du,
                           float *dh0, const rglru_param_grads *grads, void *workspace,
                           size_t workspace_bytes, void *stream);
+
+/*
+ * Complex-gated LRU (Appendix B, "Complex-Gated Linear Recurrent Unit"): the RG-LRU with the
+ * complex diagonal recurrence weight a~ = sigmoid(Lambda) e^{i theta}. The D real channels of
+ * x_t (D even) are read as H = D / 2 complex ones, first half real parts, second half
+ * imaginary parts; gates, decay and state have H entries:
+ *     r_t = sigmoid(W_a x_t + b_a),  i_t = sigmoid(W_x x_t + b_x)            in R^H
+ *     a~_t = a~^(c r_t) = exp(c r_t (log sigmoid(Lambda) + i theta))
+ *     h~_t = a~_t h~_{t-1} + sqrt(1 - |a~_t|^2) (i_t x~_t),   y_t = [Re h~_t ; Im h~_t]  in R^D
+ * The appendix does not say how the block-diagonal gates of Section 4.1 carry over. Here gate
+ * block g (of shape.num_blocks; H % num_blocks == 0, hs = H / num_blocks) owns the complex
+ * channels g*hs .. (g+1)*hs-1 and sees the real and the imaginary parts of exactly those:
+ * W[g] is [hs][2 hs], input k < hs = real channel g*hs + k, input k >= hs = real channel
+ * H + g*hs + (k - hs). One block is the appendix's dense H x D matrix. The power is
+ * exp(c r_t log a~) with log a~ = log sigmoid(Lambda) + i theta (theta as given, not reduced).
+ * States ([B][D] f32) hold [Re h~ ; Im h~] like y_t. The Conv1D in front (shape.conv_width 4,
+ * or 0 for none) is the real layer's, on all D channels, with the same ring state.
+ */
+typedef struct rglru_cg_params {
+  const void *W_a;     /* [nb][hs][2 hs] w   recurrence-gate weights */
+  const void *W_x;     /* [nb][hs][2 hs] w   input-gate weights      */
+  const float *b_a;    /* [H]                                         */
+  const float *b_x;    /* [H]                                         */
+  const float *Lambda; /* [H]   |a~| = sigmoid(Lambda)                */
+  const float *theta;  /* [H]   arg a~                                */
+  const float *conv_w; /* [4][D] or NULL with conv_width 0            */
+  const float *conv_b; /* [D] or NULL                                 */
+} rglru_cg_params;
+
+typedef struct rglru_cg_param_grads {
+  float *dW_a;     /* [nb][hs][2 hs] */
+  float *dW_x;     /* [nb][hs][2 hs] */
+  float *db_a;     /* [H]            */
+  float *db_x;     /* [H]            */
+  float *dLambda;  /* [H]            */
+  float *dtheta;   /* [H]            */
+  float *dconv_w;  /* [4][D]; not produced with conv_width 0 */
+  float *dconv_b;  /* [D] or NULL (skipped) */
+} rglru_cg_param_grads;
+
+/*
+ * Forward, decode step and backward of the complex-gated layer. Arguments, layouts, state
+ * handling and error codes are those of rglru_forward, rglru_decode_step and rglru_backward
+ * (the backward is the adjoint for the real loss L = sum(dy * y) + sum(dhT * hT), derived from
+ * the appendix's equations with real and imaginary parts as independent variables; it also
+ * returns dtheta; it takes no y: the gradient of the decay multiplies the state's adjoint by
+ * conj(h~_{t-1}), which needs more than the 8 bits of a bf16 y, so the backward recomputes the
+ * states in fp32 into its workspace). They run on shape-generic kernels (fp32 arithmetic for either storage
+ * type, one workgroup per (sequence, gate block)); no kernel waits on another. The forward and
+ * the decode step need no workspace, the backward needs
+ * rglru_workspace_bytes(shape, RGLRU_OP_CG_BACKWARD) bytes. hs may be at most 1024.
+ */
+int rglru_cg_forward(const rglru_shape *shape, const rglru_cg_params *params, const void *u,
+                     const float *h0, const void *conv_state_in, int64_t pos0, void *y, float *hT,
+                     void *conv_state_out, void *stream);
+int rglru_cg_decode_step(const rglru_shape *shape, const rglru_cg_params *params, const void *u_t,
+                         float *h, void *conv_state, int64_t pos, void *y_t, void *stream);
+int rglru_cg_backward(const rglru_shape *shape, const rglru_cg_params *params, const void *u,
+                      const float *h0, const void *conv_state_in, int64_t pos0, const void *dy,
+                      const float *dhT, void *du, float *dh0, const rglru_cg_param_grads *grads,
+                      void *workspace, size_t workspace_bytes, void *stream);
 
 /* flags of the merge calls */
 #define RGLRU_MERGE_GELU_TANH 1u /* GeLU in its tanh form instead of z * Phi(z)             */

@@ -15,6 +15,7 @@ F32, BF16 = 0, 1
 OP_CONV1D, OP_FORWARD, OP_DECODE, OP_BACKWARD, OP_SCAN = 0, 1, 2, 3, 4
 OP_FORWARD_MERGE, OP_BACKWARD_MERGE = 5, 6
 OP_FORWARD_PACKED, OP_BACKWARD_PACKED = 7, 8
+OP_CG_BACKWARD = 9
 MERGE_GELU_TANH, MERGE_SEPARATE = 1, 2
 SCAN_LOG_A, SCAN_NO_INPUT_SCALE, SCAN_ADJOINT = 1, 2, 4
 STATIC_SCRATCH_BYTES = 16 << 20
@@ -34,6 +35,16 @@ class Params(ctypes.Structure):
 class ParamGrads(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in
                 ("dW_a", "dW_x", "db_a", "db_x", "dLambda", "dconv_w", "dconv_b")]
+
+
+class CgParams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("W_a", "W_x", "b_a", "b_x", "Lambda", "theta", "conv_w", "conv_b")]
+
+
+class CgParamGrads(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("dW_a", "dW_x", "db_a", "db_x", "dLambda", "dtheta", "dconv_w", "dconv_b")]
 
 
 class RglruError(RuntimeError):
@@ -65,6 +76,12 @@ def _load():
     lib.rglru_forward_packed.restype = ctypes.c_int
     lib.rglru_backward_packed.argtypes = [sp, pp, vp, vp, vp, vp, i64, vp, vp, vp, vp, vp, gp, vp, sz, vp]
     lib.rglru_backward_packed.restype = ctypes.c_int
+    cp, cgp = ctypes.POINTER(CgParams), ctypes.POINTER(CgParamGrads)
+    lib.rglru_cg_forward.argtypes = [sp, cp, vp, vp, vp, i64, vp, vp, vp, vp]
+    lib.rglru_cg_decode_step.argtypes = [sp, cp, vp, vp, vp, i64, vp, vp]
+    lib.rglru_cg_backward.argtypes = [sp, cp, vp, vp, vp, i64, vp, vp, vp, vp, cgp, vp, sz, vp]
+    for f in (lib.rglru_cg_forward, lib.rglru_cg_decode_step, lib.rglru_cg_backward):
+        f.restype = ctypes.c_int
     lib.rglru_forward_merge.argtypes = [sp, pp, vp, vp, vp, vp, i64, ctypes.c_uint, vp, vp, vp, vp, vp, sz, vp]
     lib.rglru_backward_merge.argtypes = [sp, pp, vp, vp, vp, vp, i64, ctypes.c_uint, vp, vp, vp, vp, vp, vp,
                                          gp, vp, sz, vp]
@@ -131,6 +148,14 @@ def make_params(W_a, W_x, b_a, b_x, Lambda, conv_w, conv_b=None):
 
 def make_param_grads(dW_a, dW_x, db_a, db_x, dLambda, dconv_w, dconv_b=None):
     return ParamGrads(*[_addr(t) for t in (dW_a, dW_x, db_a, db_x, dLambda, dconv_w, dconv_b)])
+
+
+def make_cg_params(W_a, W_x, b_a, b_x, Lambda, theta, conv_w=None, conv_b=None):
+    return CgParams(*[_addr(t) for t in (W_a, W_x, b_a, b_x, Lambda, theta, conv_w, conv_b)])
+
+
+def make_cg_param_grads(dW_a, dW_x, db_a, db_x, dLambda, dtheta, dconv_w=None, dconv_b=None):
+    return CgParamGrads(*[_addr(t) for t in (dW_a, dW_x, db_a, db_x, dLambda, dtheta, dconv_w, dconv_b)])
 
 
 def rglru_version():
@@ -217,6 +242,24 @@ def rglru_backward_packed(shape, params, u, reset, h0, conv_state_in, pos0, y, d
                                       _addr(conv_state_in), pos0, _addr(y), _addr(dy), _addr(dhT),
                                       _addr(du), _addr(dh0), _ref(grads), _addr(workspace),
                                       workspace_bytes, _stream(stream)))
+
+
+def rglru_cg_forward(shape, params, u, h0, conv_state_in, pos0, y, hT, conv_state_out, stream=None):
+    _check(_lib.rglru_cg_forward(_ref(shape), _ref(params), _addr(u), _addr(h0), _addr(conv_state_in),
+                                 pos0, _addr(y), _addr(hT), _addr(conv_state_out), _stream(stream)))
+
+
+def rglru_cg_decode_step(shape, params, u_t, h, conv_state, pos, y_t, stream=None):
+    _check(_lib.rglru_cg_decode_step(_ref(shape), _ref(params), _addr(u_t), _addr(h),
+                                     _addr(conv_state), pos, _addr(y_t), _stream(stream)))
+
+
+def rglru_cg_backward(shape, params, u, h0, conv_state_in, pos0, dy, dhT, du, dh0, grads,
+                      workspace, workspace_bytes, stream=None):
+    _check(_lib.rglru_cg_backward(_ref(shape), _ref(params), _addr(u), _addr(h0),
+                                  _addr(conv_state_in), pos0, _addr(dy), _addr(dhT),
+                                  _addr(du), _addr(dh0), _ref(grads), _addr(workspace),
+                                  workspace_bytes, _stream(stream)))
 
 
 def rglru_forward_merge(shape, params, u, branch, h0, conv_state_in, pos0, flags, out, y, hT,

@@ -124,6 +124,40 @@ void fill_params(Problem &q, const rglru_shape *s, const rglru_params *p) {
   if (s->conv_width == 0) q.conv_w = q.conv_b = nullptr;   // the kernels read a null tap array as x_t = u_t
 }
 
+// the complex-gated variant: D even, the D / 2 complex channels in num_blocks gate blocks
+int check_cg_shape(const rglru_shape *s) {
+  if (s->D % 2 != 0) return fail(RGLRU_ERR_INVALID_ARG, "D (%d) must be even: two real channels per complex one", s->D);
+  if ((s->D / 2) % s->num_blocks != 0)
+    return fail(RGLRU_ERR_INVALID_ARG, "D / 2 (%d) is not a multiple of num_blocks (%d)", s->D / 2, s->num_blocks);
+  if (s->D / 2 / s->num_blocks > 1024)
+    return fail(RGLRU_ERR_UNSUPPORTED, "%d complex channels per gate block exceed 1024", s->D / 2 / s->num_blocks);
+  return RGLRU_OK;
+}
+
+int check_cg_params(const rglru_shape *s, const rglru_cg_params *p) {
+  if (!p) return fail(RGLRU_ERR_INVALID_ARG, "params is NULL");
+  const size_t ws = s->w_dtype == RGLRU_BF16 ? 2 : 4;
+  CHECK(check_ptr(p->W_a, "params.W_a", ws, true));
+  CHECK(check_ptr(p->W_x, "params.W_x", ws, true));
+  CHECK(check_ptr(p->b_a, "params.b_a", 4, true));
+  CHECK(check_ptr(p->b_x, "params.b_x", 4, true));
+  CHECK(check_ptr(p->Lambda, "params.Lambda", 4, true));
+  CHECK(check_ptr(p->theta, "params.theta", 4, true));
+  CHECK(check_ptr(p->conv_w, "params.conv_w", 4, s->conv_width != 0));
+  CHECK(check_ptr(p->conv_b, "params.conv_b", 4, false));
+  return RGLRU_OK;
+}
+
+void fill_cg_params(Problem &q, const rglru_shape *s, const rglru_cg_params *p) {
+  q.B = s->B; q.T = s->T; q.D = s->D;
+  q.nb = s->num_blocks; q.bs = s->D / 2 / s->num_blocks;
+  q.c = s->c;
+  q.W_a = p->W_a; q.W_x = p->W_x;
+  q.b_a = p->b_a; q.b_x = p->b_x; q.Lambda = p->Lambda; q.theta = p->theta;
+  q.conv_w = p->conv_w; q.conv_b = p->conv_b;
+  if (s->conv_width == 0) q.conv_w = q.conv_b = nullptr;
+}
+
 // dy between the merge adjoint and the backward: one fp32 tensor, or in bf16 storage two bf16
 // tensors (dy as stored and what its rounding took away)
 size_t merge_dy_part(const rglru_shape *s) {
@@ -168,6 +202,8 @@ size_t workspace_need(const rglru_shape *s, int op) {
       return 0;
     case RGLRU_OP_BACKWARD_PACKED:
       return backward_generic_ws_bytes(s->B, s->T, s->D, s->num_blocks);
+    case RGLRU_OP_CG_BACKWARD:
+      return cg_backward_ws_bytes(s->B, s->T, s->D, s->num_blocks);
     case RGLRU_OP_BACKWARD_MERGE:   // dy (+ dy_lo) between the merge adjoint and the backward, then the backward's own
       return merge_dy_bytes(s) + workspace_need(s, RGLRU_OP_BACKWARD);
     case RGLRU_OP_FORWARD_MERGE:
@@ -303,7 +339,7 @@ int rglru_timing_get(int index, const char **name, float *ms) {
 
 const char *rglru_last_error(void) { return g_err; }
 
-int rglru_version(void) { return 310; }
+int rglru_version(void) { return 320; }
 
 int rglru_set_max_time_slices(int max_slices) {
   if (max_slices < 0) return fail(RGLRU_ERR_INVALID_ARG, "max_slices must be >= 0 (0 = automatic)");
@@ -312,12 +348,14 @@ int rglru_set_max_time_slices(int max_slices) {
 }
 
 size_t rglru_workspace_bytes(const rglru_shape *shape, int op) {
-  if (op < RGLRU_OP_CONV1D || op > RGLRU_OP_BACKWARD_PACKED) return 0;
+  if (op < RGLRU_OP_CONV1D || op > RGLRU_OP_CG_BACKWARD) return 0;
   char keep[sizeof(g_err)];
   memcpy(keep, g_err, sizeof(g_err));
   const bool blocks = op != RGLRU_OP_CONV1D && op != RGLRU_OP_SCAN;
-  const bool bwd = op == RGLRU_OP_BACKWARD || op == RGLRU_OP_BACKWARD_MERGE || op == RGLRU_OP_BACKWARD_PACKED;
-  const int rc = check_shape(shape, blocks, op != RGLRU_OP_DECODE, bwd ? 1 : 0);
+  const bool bwd = op == RGLRU_OP_BACKWARD || op == RGLRU_OP_BACKWARD_MERGE || op == RGLRU_OP_BACKWARD_PACKED ||
+                   op == RGLRU_OP_CG_BACKWARD;
+  int rc = check_shape(shape, blocks, op != RGLRU_OP_DECODE, bwd ? 1 : 0);
+  if (rc == RGLRU_OK && op == RGLRU_OP_CG_BACKWARD) rc = check_cg_shape(shape);
   memcpy(g_err, keep, sizeof(g_err));  // a size query does not disturb the error string
   if (rc != RGLRU_OK) return 0;
   return workspace_need(shape, op);
@@ -759,6 +797,103 @@ int rglru_backward_merge(const rglru_shape *shape, const rglru_params *params, c
   if (e != hipSuccess) return hip_fail(e, "merge launch");
   return backward_run(shape, params, u, h0, conv_state_in, pos0, y, dy, dy_lo, dhT, du, dh0, grads, rest,
                       workspace_bytes - dyb, stream);
+}
+
+int rglru_cg_forward(const rglru_shape *shape, const rglru_cg_params *params, const void *u,
+                     const float *h0, const void *conv_state_in, int64_t pos0, void *y, float *hT,
+                     void *conv_state_out, void *stream) {
+  CHECK(check_shape(shape, true, true, 0));
+  CHECK(check_cg_shape(shape));
+  CHECK(check_cg_params(shape, params));
+  const size_t as = act_size(shape);
+  if (pos0 < 0) return fail(RGLRU_ERR_INVALID_ARG, "pos0 must be >= 0");
+  CHECK(check_ptr(u, "u", as, shape->T > 0));
+  CHECK(check_ptr(y, "y", as, shape->T > 0));
+  CHECK(check_ptr(h0, "h0", 4, false));
+  CHECK(check_ptr(hT, "hT", 4, false));
+  CHECK(check_ptr(conv_state_in, "conv_state_in", as, false));
+  CHECK(check_ptr(conv_state_out, "conv_state_out", as, false));
+  Problem q;
+  memset(&q, 0, sizeof(q));
+  fill_cg_params(q, shape, params);
+  q.pos0 = pos0; q.u = u; q.h0 = h0; q.state_in = conv_state_in;
+  q.y = y; q.hT = hT; q.state_out = conv_state_out;
+  if (shape->conv_width == 0) q.state_in = q.state_out = nullptr;
+  const bool bf = shape->act_dtype == RGLRU_BF16;
+  hipError_t e = launch_cg_forward(q, bf, (hipStream_t)stream);
+  // the new ring state is written after the last read of the incoming one (they may alias)
+  if (e == hipSuccess) e = launch_state_update(q, bf, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "forward launch");
+  g_err[0] = 0;
+  return RGLRU_OK;
+}
+
+int rglru_cg_decode_step(const rglru_shape *shape, const rglru_cg_params *params, const void *u_t,
+                         float *h, void *conv_state, int64_t pos, void *y_t, void *stream) {
+  CHECK(check_shape(shape, true, false, 0));
+  CHECK(check_cg_shape(shape));
+  CHECK(check_cg_params(shape, params));
+  const size_t as = act_size(shape);
+  if (pos < 0) return fail(RGLRU_ERR_INVALID_ARG, "pos must be >= 0");
+  CHECK(check_ptr(u_t, "u_t", as, true));
+  CHECK(check_ptr(h, "h", 4, true));
+  CHECK(check_ptr(conv_state, "conv_state", as, shape->conv_width != 0));
+  CHECK(check_ptr(y_t, "y_t", as, true));
+  Problem q;
+  memset(&q, 0, sizeof(q));
+  fill_cg_params(q, shape, params);
+  q.T = 1;
+  q.pos0 = pos; q.u = u_t; q.hT = h; q.y = y_t;
+  q.state_in = q.state_out = shape->conv_width == 0 ? nullptr : conv_state;
+  const hipError_t e = launch_cg_decode(q, shape->act_dtype == RGLRU_BF16, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "decode launch");
+  g_err[0] = 0;
+  return RGLRU_OK;
+}
+
+int rglru_cg_backward(const rglru_shape *shape, const rglru_cg_params *params, const void *u,
+                      const float *h0, const void *conv_state_in, int64_t pos0, const void *dy,
+                      const float *dhT, void *du, float *dh0, const rglru_cg_param_grads *grads,
+                      void *workspace, size_t workspace_bytes, void *stream) {
+  CHECK(check_shape(shape, true, true, 1));
+  CHECK(check_cg_shape(shape));
+  CHECK(check_cg_params(shape, params));
+  const size_t as = act_size(shape);
+  if (pos0 < 0) return fail(RGLRU_ERR_INVALID_ARG, "pos0 must be >= 0");
+  CHECK(check_ptr(u, "u", as, true));
+  CHECK(check_ptr(dy, "dy", as, true));
+  CHECK(check_ptr(du, "du", as, true));
+  CHECK(check_ptr(h0, "h0", 4, false));
+  CHECK(check_ptr(dhT, "dhT", 4, false));
+  CHECK(check_ptr(dh0, "dh0", 4, false));
+  CHECK(check_ptr(conv_state_in, "conv_state_in", as, false));
+  if (!grads) return fail(RGLRU_ERR_INVALID_ARG, "grads is NULL");
+  CHECK(check_ptr(grads->dW_a, "grads.dW_a", 4, true));
+  CHECK(check_ptr(grads->dW_x, "grads.dW_x", 4, true));
+  CHECK(check_ptr(grads->db_a, "grads.db_a", 4, true));
+  CHECK(check_ptr(grads->db_x, "grads.db_x", 4, true));
+  CHECK(check_ptr(grads->dLambda, "grads.dLambda", 4, true));
+  CHECK(check_ptr(grads->dtheta, "grads.dtheta", 4, true));
+  CHECK(check_ptr(grads->dconv_w, "grads.dconv_w", 4, shape->conv_width != 0));
+  CHECK(check_ptr(grads->dconv_b, "grads.dconv_b", 4, false));
+  CHECK(check_workspace(workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_CG_BACKWARD)));
+  Problem q;
+  memset(&q, 0, sizeof(q));
+  fill_cg_params(q, shape, params);
+  q.pos0 = pos0; q.u = u; q.h0 = h0; q.state_in = conv_state_in;
+  q.dy = dy; q.dhT = dhT; q.du = du; q.dh0 = dh0;
+  q.g.dW_a = grads->dW_a; q.g.dW_x = grads->dW_x; q.g.db_a = grads->db_a; q.g.db_x = grads->db_x;
+  q.g.dLambda = grads->dLambda; q.dtheta = grads->dtheta;
+  q.g.dconv_w = grads->dconv_w; q.g.dconv_b = grads->dconv_b;
+  if (shape->conv_width == 0) {
+    q.state_in = nullptr;
+    q.g.dconv_w = q.g.dconv_b = nullptr;
+  }
+  q.ws = workspace; q.ws_bytes = workspace_bytes;
+  const hipError_t e = launch_cg_backward(q, shape->act_dtype == RGLRU_BF16, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "backward launch");
+  g_err[0] = 0;
+  return RGLRU_OK;
 }
 
 }  // extern "C"

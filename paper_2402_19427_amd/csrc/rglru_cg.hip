@@ -1,0 +1,445 @@
+// Complex-gated LRU (Appendix B of the Griffin/Hawk paper): the RG-LRU with a complex diagonal
+// recurrence weight a~ = sigmoid(Lambda) e^{i theta}. The D real channels of x_t are read as
+// H = D / 2 complex ones (first half real parts, second half imaginary parts); the gates, the
+// decay and the state have H entries:
+//     r_t = sigmoid(W_a x_t + b_a),  i_t = sigmoid(W_x x_t + b_x)
+//     a~_t = a~^(c r_t) = exp(c r_t (log sigmoid(Lambda) + i theta))
+//     h~_t = a~_t h~_{t-1} + sqrt(1 - |a~_t|^2) (i_t x~_t),   y_t = [Re h~_t ; Im h~_t]
+// Gate block g (of nb) owns the complex channels g*hs .. (g+1)*hs-1 (hs = H / nb) and sees the
+// real and the imaginary parts of exactly those channels: W[g] is [hs][2 hs].
+//
+// Shape-generic kernels (any block size, fp32 or bf16 storage, fp32 arithmetic with accurate
+// math), built like the real layer's general kernels: one workgroup per (gate block, sequence)
+// walks the sequence in tiles of GT steps. In Problem, bs = hs and D is the real width.
+#include "rglru_generic.h"
+
+namespace rglru {
+
+namespace {
+
+// real channel of input k (0 .. 2 hs - 1) of gate block g
+__device__ __forceinline__ int cg_channel(int g, int hs, int H, int k) {
+  return k < hs ? g * hs + k : H + g * hs + (k - hs);
+}
+
+struct CGates {
+  float r, i, rc, ic;   // gates and their complements sigmoid(-p), sigmoid(-q)
+  float ar, ai;         // a~_t
+  float m;              // sqrt(1 - |a~_t|^2)
+  float mod2;           // |a~_t|^2
+};
+// neg_cs = c log sigmoid(Lambda) = log|a~| * c, c_theta = c * theta
+__device__ __forceinline__ CGates cg_gate_math(float p, float q, float neg_cs, float c_theta) {
+  CGates g;
+  g.r = sigmoid_f(p);
+  g.i = sigmoid_f(q);
+  g.rc = sigmoid_f(-p);
+  g.ic = sigmoid_f(-q);
+  const float lm = neg_cs * g.r;   // log |a~_t| <= 0
+  const float mod = expf(lm);
+  float sn, cs;
+  sincosf(c_theta * g.r, &sn, &cs);
+  g.ar = mod * cs;
+  g.ai = mod * sn;
+  g.mod2 = expf(2.f * lm);
+  g.m = sqrtf(-expm1f(2.f * lm));   // no cancellation as |a~_t| -> 1
+  return g;
+}
+
+// the x tile of gate block g: xs[tt][k] for the GT steps from t0 (zero past the sequence's end)
+template <typename AT>
+__device__ __forceinline__ void cg_load_tile(const Problem &p, int g, int b, int t0, int nt, float *xs) {
+  const int hs = p.bs, H = p.D / 2;
+  for (int idx = threadIdx.x; idx < GT * 2 * hs; idx += NTHREADS) {
+    const int tt = idx / (2 * hs), k = idx - tt * 2 * hs;
+    xs[idx] = tt < nt ? conv_at<AT>(p, b, t0 + tt, cg_channel(g, hs, H, k)) : 0.f;
+  }
+}
+
+// pre-activations of output j of block g for the GT rows of the tile: b + W[g][j][:] . xs[tt][:]
+template <typename AT>
+__device__ __forceinline__ void cg_gate_rows(const Problem &p, int g, int j, const float *xs, float *pa,
+                                             float *qa) {
+  const int hs = p.bs, nin = 2 * hs, h = g * hs + j;
+  const AT *wa = (const AT *)p.W_a + (size_t)h * nin;
+  const AT *wx = (const AT *)p.W_x + (size_t)h * nin;
+#pragma unroll
+  for (int tt = 0; tt < GT; ++tt) {
+    pa[tt] = p.b_a[h];
+    qa[tt] = p.b_x[h];
+  }
+  for (int k = 0; k < nin; ++k) {
+    const float a = ldf(wa, k), x = ldf(wx, k);
+#pragma unroll
+    for (int tt = 0; tt < GT; ++tt) {
+      const float v = xs[tt * nin + k];
+      pa[tt] = fmaf(a, v, pa[tt]);
+      qa[tt] = fmaf(x, v, qa[tt]);
+    }
+  }
+}
+
+// --------------------------------------------------------------------------- forward
+// OT: storage type of y (the backward recomputes the states into an fp32 array)
+template <typename AT, typename OT = AT>
+__global__ void __launch_bounds__(NTHREADS) cg_forward_kernel(Problem p) {
+  extern __shared__ float smem[];
+  const int g = blockIdx.x, b = blockIdx.y, hs = p.bs, H = p.D / 2, tid = threadIdx.x;
+  float *xs = smem, *hc = smem + GT * 2 * hs;   // state: [hs] real parts, [hs] imaginary parts
+  for (int j = tid; j < hs; j += NTHREADS) {
+    hc[j] = p.h0 ? p.h0[(size_t)b * p.D + g * hs + j] : 0.f;
+    hc[hs + j] = p.h0 ? p.h0[(size_t)b * p.D + H + g * hs + j] : 0.f;
+  }
+  for (int t0 = 0; t0 < p.T; t0 += GT) {
+    const int nt = min(GT, p.T - t0);
+    __syncthreads();
+    cg_load_tile<AT>(p, g, b, t0, nt, xs);
+    __syncthreads();
+    for (int j = tid; j < hs; j += NTHREADS) {
+      const int h = g * hs + j;
+      float pa[GT], qa[GT];
+      cg_gate_rows<AT>(p, g, j, xs, pa, qa);
+      const float neg_cs = -p.c * softplus_f(-p.Lambda[h]), c_theta = p.c * p.theta[h];
+      float hr = hc[j], hi = hc[hs + j];
+#pragma unroll
+      for (int tt = 0; tt < GT; ++tt) {
+        if (tt < nt) {
+          const CGates gt = cg_gate_math(pa[tt], qa[tt], neg_cs, c_theta);
+          const float gain = gt.m * gt.i;
+          const float nr = fmaf(gt.ar, hr, fmaf(-gt.ai, hi, gain * xs[tt * 2 * hs + j]));
+          const float ni = fmaf(gt.ar, hi, fmaf(gt.ai, hr, gain * xs[tt * 2 * hs + hs + j]));
+          hr = nr;
+          hi = ni;
+          const size_t o = ((size_t)b * p.T + t0 + tt) * p.D;
+          stf((OT *)p.y, o + h, hr);
+          stf((OT *)p.y, o + H + h, hi);
+        }
+      }
+      hc[j] = hr;
+      hc[hs + j] = hi;
+    }
+  }
+  __syncthreads();
+  if (p.hT)
+    for (int j = tid; j < hs; j += NTHREADS) {
+      p.hT[(size_t)b * p.D + g * hs + j] = hc[j];
+      p.hT[(size_t)b * p.D + H + g * hs + j] = hc[hs + j];
+    }
+}
+
+// ---------------------------------------------------------------------------- decode
+// One workgroup per (gate block, tile of GT sequences); states updated in place. The ring slot
+// of the new token is written by the workgroup that owns the channels, after all its reads.
+template <typename AT>
+__global__ void __launch_bounds__(NTHREADS) cg_decode_kernel(Problem p) {
+  extern __shared__ float smem[];
+  const int g = blockIdx.x, b0 = blockIdx.y * GT, hs = p.bs, H = p.D / 2, tid = threadIdx.x;
+  const int nbat = min(GT, p.B - b0);
+  float *xs = smem;
+  AT *state = (AT *)p.state_out;  // in-place ring
+  for (int idx = tid; idx < GT * 2 * hs; idx += NTHREADS) {
+    const int tt = idx / (2 * hs), k = idx - tt * 2 * hs, d = cg_channel(g, hs, H, k);
+    float acc = 0.f;
+    if (tt < nbat) {
+      const int b = b0 + tt;
+      if (!p.conv_w) {
+        acc = ldf((const AT *)p.u, (size_t)b * p.D + d);
+      } else {
+        acc = p.conv_b ? p.conv_b[d] : 0.f;
+        acc = fmaf(p.conv_w[d], ldf((const AT *)p.u, (size_t)b * p.D + d), acc);
+#pragma unroll
+        for (int l = 1; l < 4; ++l)
+          acc = fmaf(p.conv_w[(size_t)l * p.D + d],
+                     ldf(state, ((size_t)b * 3 + ring_slot(p.pos0 - l)) * p.D + d), acc);
+      }
+    }
+    xs[idx] = acc;
+  }
+  __syncthreads();
+  for (int j = tid; j < hs; j += NTHREADS) {
+    const int h = g * hs + j;
+    float pa[GT], qa[GT];
+    cg_gate_rows<AT>(p, g, j, xs, pa, qa);
+    const float neg_cs = -p.c * softplus_f(-p.Lambda[h]), c_theta = p.c * p.theta[h];
+#pragma unroll
+    for (int tt = 0; tt < GT; ++tt) {
+      if (tt < nbat) {
+        const size_t o = (size_t)(b0 + tt) * p.D;
+        const CGates gt = cg_gate_math(pa[tt], qa[tt], neg_cs, c_theta);
+        const float gain = gt.m * gt.i, hr = p.hT[o + h], hi = p.hT[o + H + h];
+        const float nr = fmaf(gt.ar, hr, fmaf(-gt.ai, hi, gain * xs[tt * 2 * hs + j]));
+        const float ni = fmaf(gt.ar, hi, fmaf(gt.ai, hr, gain * xs[tt * 2 * hs + hs + j]));
+        p.hT[o + h] = nr;
+        p.hT[o + H + h] = ni;
+        stf((AT *)p.y, o + h, nr);
+        stf((AT *)p.y, o + H + h, ni);
+        if (state) {
+          const size_t so = ((size_t)(b0 + tt) * 3 + ring_slot(p.pos0)) * p.D;
+          state[so + h] = ((const AT *)p.u)[o + h];
+          state[so + H + h] = ((const AT *)p.u)[o + H + h];
+        }
+      }
+    }
+  }
+}
+
+// --------------------------------------------------------------------------- backward
+// Pass 0 is the forward kernel once more, writing the states h~_t in fp32 into the workspace
+// (`hs32`): the gradient of the decay multiplies delta~_t by conj(h~_{t-1}), and with the
+// phases in play the 8 bits of a bf16 y would leave dW_a some 3e-2 off.
+// Pass 1: one workgroup per (gate block, sequence), backwards in time. The adjoint of the state
+// is complex, delta~_t = dy~_t + conj(a~_{t+1}) delta~_{t+1} (a complex number standing for the
+// pair of derivatives with respect to the real and the imaginary part). Stores x, the gate
+// adjoints dp, dq ([B*T][H]) and the direct part of dx for the later contractions.
+template <typename AT>
+__global__ void __launch_bounds__(NTHREADS) cg_bwd_pointwise_kernel(Problem p, BwdWs w, const float *hs32) {
+  extern __shared__ float smem[];
+  const int g = blockIdx.x, b = blockIdx.y, hs = p.bs, H = p.D / 2, tid = threadIdx.x;
+  float *xs = smem;                    // [GT][2 hs]
+  float *carry = smem + GT * 2 * hs;   // [2][hs]  conj(a~_{t+1}) delta~_{t+1}
+  float *sums = carry + 2 * hs;        // [4][hs]  running db_a, db_x, dLambda, dtheta of this sequence
+  float *comps = sums + 4 * hs;        // [4][hs]  their compensation terms
+  for (int j = tid; j < hs; j += NTHREADS) {
+    carry[j] = p.dhT ? p.dhT[(size_t)b * p.D + g * hs + j] : 0.f;
+    carry[hs + j] = p.dhT ? p.dhT[(size_t)b * p.D + H + g * hs + j] : 0.f;
+    for (int q = 0; q < 4; ++q) sums[q * hs + j] = comps[q * hs + j] = 0.f;
+  }
+  const int ntile = (p.T + GT - 1) / GT;
+  for (int tile = ntile - 1; tile >= 0; --tile) {
+    const int t0 = tile * GT, nt = min(GT, p.T - t0);
+    __syncthreads();
+    cg_load_tile<AT>(p, g, b, t0, nt, xs);
+    __syncthreads();
+    for (int j = tid; j < hs; j += NTHREADS) {
+      const int h = g * hs + j;
+      float pa[GT], qa[GT];
+      cg_gate_rows<AT>(p, g, j, xs, pa, qa);
+      const float theta = p.theta[h];
+      const float log_sig = -softplus_f(-p.Lambda[h]);         // log sigmoid(Lambda)
+      const float neg_cs = p.c * log_sig, c_theta = p.c * theta;
+      const float lam_scale = p.c * sigmoid_f(-p.Lambda[h]);   // c d log sigmoid(Lambda) / d Lambda
+      float cr = carry[j], ci = carry[hs + j];
+      float s_ba = 0.f, s_bx = 0.f, s_lam = 0.f, s_th = 0.f;
+#pragma unroll
+      for (int tt = GT - 1; tt >= 0; --tt) {
+        if (tt < nt) {
+          const int t = t0 + tt;
+          const size_t o = ((size_t)b * p.T + t) * p.D;
+          const CGates gt = cg_gate_math(pa[tt], qa[tt], neg_cs, c_theta);
+          const float xr = xs[tt * 2 * hs + j], xi = xs[tt * 2 * hs + hs + j];
+          const float dr_ = ldf((const AT *)p.dy, o + h) + cr, di_ = ldf((const AT *)p.dy, o + H + h) + ci;
+          float pr, pi;   // h~_{t-1}
+          if (t > 0) {
+            pr = hs32[o - p.D + h];
+            pi = hs32[o - p.D + H + h];
+          } else {
+            pr = p.h0 ? p.h0[(size_t)b * p.D + h] : 0.f;
+            pi = p.h0 ? p.h0[(size_t)b * p.D + H + h] : 0.f;
+          }
+          // G = delta~ conj(h~_{t-1}) = (dL/dRe a~_t, dL/dIm a~_t)
+          const float Gr = fmaf(dr_, pr, di_ * pi), Gi = fmaf(di_, pr, -dr_ * pi);
+          const float s = fmaf(dr_, xr, di_ * xi);   // dL/d(m_t i_t)
+          // a~_t = exp(lm + i ph): d/d lm = a~_t, d/d ph = i a~_t;  m_t = sqrt(1 - e^{2 lm})
+          float dlm = fmaf(Gr, gt.ar, Gi * gt.ai);
+          const float dph = fmaf(Gi, gt.ar, -Gr * gt.ai);
+          if (gt.m > 0.f) dlm -= s * gt.i * gt.mod2 / gt.m;
+          const float dgate_r = p.c * fmaf(dlm, log_sig, dph * theta);
+          const float dpv = dgate_r * gt.r * gt.rc;
+          const float dqv = s * gt.m * gt.i * gt.ic;
+          s_lam = fmaf(dlm * gt.r, lam_scale, s_lam);
+          s_th = fmaf(dph * gt.r, p.c, s_th);
+          s_ba += dpv;
+          s_bx += dqv;
+          const size_t oh = ((size_t)b * p.T + t) * H + h;
+          w.dp[oh] = dpv;
+          w.dq[oh] = dqv;
+          w.x[o + h] = xr;
+          w.x[o + H + h] = xi;
+          const float gain = gt.m * gt.i;
+          w.dx[o + h] = dr_ * gain;
+          w.dx[o + H + h] = di_ * gain;
+          // conj(a~_t) delta~_t
+          cr = fmaf(gt.ar, dr_, gt.ai * di_);
+          ci = fmaf(gt.ar, di_, -gt.ai * dr_);
+        }
+      }
+      carry[j] = cr;
+      carry[hs + j] = ci;
+      comp_add(sums[j], comps[j], s_ba);
+      comp_add(sums[hs + j], comps[hs + j], s_bx);
+      comp_add(sums[2 * hs + j], comps[2 * hs + j], s_lam);
+      comp_add(sums[3 * hs + j], comps[3 * hs + j], s_th);
+    }
+  }
+  __syncthreads();
+  for (int j = tid; j < hs; j += NTHREADS) {
+    const int h = g * hs + j;
+    if (p.dh0) {
+      p.dh0[(size_t)b * p.D + h] = carry[j];
+      p.dh0[(size_t)b * p.D + H + h] = carry[hs + j];
+    }
+    for (int q = 0; q < 4; ++q) w.partA[((size_t)b * 4 + q) * H + h] = sums[q * hs + j];
+  }
+}
+
+// Pass 2: dx[t][chan(k)] += sum_j W_a[g][j][k] dp[t][j] + W_x[g][j][k] dq[t][j]
+template <typename AT>
+__global__ void __launch_bounds__(NTHREADS) cg_bwd_dgrad_kernel(Problem p, BwdWs w) {
+  extern __shared__ float smem[];
+  const int g = blockIdx.x, b = blockIdx.y, t0 = blockIdx.z * GT, hs = p.bs, H = p.D / 2, tid = threadIdx.x;
+  const int nt = min(GT, p.T - t0), nin = 2 * hs;
+  float *dps = smem, *dqs = smem + GT * hs;   // [GT][hs] each
+  for (int idx = tid; idx < GT * hs; idx += NTHREADS) {
+    const int tt = idx / hs, j = idx - tt * hs;
+    const size_t o = ((size_t)b * p.T + t0 + tt) * H + g * hs + j;
+    dps[idx] = tt < nt ? w.dp[o] : 0.f;
+    dqs[idx] = tt < nt ? w.dq[o] : 0.f;
+  }
+  __syncthreads();
+  const AT *Wa = (const AT *)p.W_a + (size_t)g * hs * nin;
+  const AT *Wx = (const AT *)p.W_x + (size_t)g * hs * nin;
+  for (int k = tid; k < nin; k += NTHREADS) {
+    const int d = cg_channel(g, hs, H, k);
+    float acc[GT];
+#pragma unroll
+    for (int tt = 0; tt < GT; ++tt) acc[tt] = tt < nt ? w.dx[((size_t)b * p.T + t0 + tt) * p.D + d] : 0.f;
+    for (int j = 0; j < hs; ++j) {
+      const float wa = ldf(Wa, (size_t)j * nin + k), wx = ldf(Wx, (size_t)j * nin + k);
+#pragma unroll
+      for (int tt = 0; tt < GT; ++tt)
+        acc[tt] = fmaf(wa, dps[tt * hs + j], fmaf(wx, dqs[tt * hs + j], acc[tt]));
+    }
+#pragma unroll
+    for (int tt = 0; tt < GT; ++tt)
+      if (tt < nt) w.dx[((size_t)b * p.T + t0 + tt) * p.D + d] = acc[tt];
+  }
+}
+
+// Pass 4: dW_a[g][j][k] = sum_{b,t} dp[b,t,j] x[b,t,chan(k)], dW_x likewise with dq. One
+// workgroup per 32x32 output tile of one block, 16x16 threads with 2x2 outputs each, rows
+// streamed through LDS 32 at a time; the chunks of 32 rows are added up with compensation.
+__global__ void __launch_bounds__(NTHREADS) cg_bwd_wgrad_kernel(Problem p, BwdWs w) {
+  __shared__ float xs[32][33], ps[32][33], qs[32][33];
+  const int g = blockIdx.x, j0 = blockIdx.y * 32, k0 = blockIdx.z * 32, hs = p.bs, H = p.D / 2, nin = 2 * hs;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  float aa[2][2] = {{0.f, 0.f}, {0.f, 0.f}}, ax[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
+  float ca[2][2] = {{0.f, 0.f}, {0.f, 0.f}}, cx[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
+  const size_t rows = (size_t)p.B * p.T;
+  for (size_t r0 = 0; r0 < rows; r0 += 32) {
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < 32 * 32; idx += NTHREADS) {
+      const int rr = idx >> 5, cc = idx & 31;
+      const size_t row = r0 + rr;
+      const bool okr = row < rows;
+      xs[rr][cc] = (okr && k0 + cc < nin) ? w.x[row * p.D + cg_channel(g, hs, H, k0 + cc)] : 0.f;
+      ps[rr][cc] = (okr && j0 + cc < hs) ? w.dp[row * H + g * hs + j0 + cc] : 0.f;
+      qs[rr][cc] = (okr && j0 + cc < hs) ? w.dq[row * H + g * hs + j0 + cc] : 0.f;
+    }
+    __syncthreads();
+    float la[2][2] = {{0.f, 0.f}, {0.f, 0.f}}, lx[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
+#pragma unroll 8
+    for (int rr = 0; rr < 32; ++rr) {
+      const float x0 = xs[rr][tx], x1 = xs[rr][tx + 16];
+      const float p0 = ps[rr][ty], p1 = ps[rr][ty + 16];
+      const float q0 = qs[rr][ty], q1 = qs[rr][ty + 16];
+      la[0][0] = fmaf(p0, x0, la[0][0]); la[0][1] = fmaf(p0, x1, la[0][1]);
+      la[1][0] = fmaf(p1, x0, la[1][0]); la[1][1] = fmaf(p1, x1, la[1][1]);
+      lx[0][0] = fmaf(q0, x0, lx[0][0]); lx[0][1] = fmaf(q0, x1, lx[0][1]);
+      lx[1][0] = fmaf(q1, x0, lx[1][0]); lx[1][1] = fmaf(q1, x1, lx[1][1]);
+    }
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        comp_add(aa[a][c], ca[a][c], la[a][c]);
+        comp_add(ax[a][c], cx[a][c], lx[a][c]);
+      }
+  }
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      const int j = j0 + ty + 16 * a, k = k0 + tx + 16 * c;
+      if (j < hs && k < nin) {
+        p.g.dW_a[((size_t)g * hs + j) * nin + k] = aa[a][c];
+        p.g.dW_x[((size_t)g * hs + j) * nin + k] = ax[a][c];
+      }
+    }
+}
+
+template <typename K>
+hipError_t allow_lds(K kernel, size_t bytes) {
+  if (bytes <= 48 * 1024) return hipSuccess;
+  return hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+template <typename AT>
+hipError_t cg_backward_t(const Problem &p, hipStream_t s) {
+  const BwdWs w = carve_bwd_ws(p.ws, p.B, p.T, p.D);
+  const int hs = p.bs, H = p.D / 2;
+  const size_t lds1 = (size_t)(GT * 2 * hs + 10 * hs) * sizeof(float), lds2 = (size_t)(2 * GT * hs) * sizeof(float);
+  hipError_t e = allow_lds(cg_bwd_pointwise_kernel<AT>, lds1);
+  if (e != hipSuccess) return e;
+  const int ntile = (p.T + GT - 1) / GT;
+  if (ntile > 65535 || p.B > 65535) return hipErrorInvalidConfiguration;
+  float *hs32 = (float *)((char *)p.ws + backward_generic_ws_bytes(p.B, p.T, p.D, p.nb));
+  {
+    Problem f = p;
+    f.y = hs32;
+    f.hT = nullptr;
+    const size_t ldsf = (size_t)(GT * 2 * hs + 2 * hs) * sizeof(float);
+    if ((e = allow_lds(cg_forward_kernel<AT, float>, ldsf)) != hipSuccess) return e;
+    hipLaunchKernelGGL((cg_forward_kernel<AT, float>), dim3(p.nb, p.B), dim3(NTHREADS), ldsf, s, f);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(cg_bwd_pointwise_kernel<AT>, dim3(p.nb, p.B), dim3(NTHREADS), lds1, s, p, w, hs32);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  const RowOuts outs = {{p.g.db_a, p.g.db_x, p.g.dLambda, p.dtheta, nullptr}};
+  if ((e = launch_reduce_parts(w.partA, p.B, 4, H, outs, s)) != hipSuccess) return e;
+  hipLaunchKernelGGL(cg_bwd_dgrad_kernel<AT>, dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds2, s, p, w);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  const int tj = (hs + 31) / 32, tk = (2 * hs + 31) / 32;
+  hipLaunchKernelGGL(cg_bwd_wgrad_kernel, dim3(p.nb, tj, tk), dim3(NTHREADS), 0, s, p, w);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  // the Conv1D's adjoint is the real layer's: du from dx, tap and bias gradients
+  Problem q = p;
+  q.g.db_a = q.g.db_x = q.g.dLambda = nullptr;
+  return launch_backward_generic_tail(q, sizeof(AT) == 2, s, false, false, true);
+}
+
+}  // namespace
+
+size_t cg_backward_ws_bytes(int B, int T, int D, int nb) {
+  const size_t n = (size_t)B * T * D * sizeof(float);
+  return backward_generic_ws_bytes(B, T, D, nb) + ((n + 255) & ~(size_t)255);
+}
+
+hipError_t launch_cg_forward(const Problem &p, bool bf, hipStream_t s) {
+  const size_t lds = (size_t)(GT * 2 * p.bs + 2 * p.bs) * sizeof(float);
+  hipError_t e = bf ? allow_lds(cg_forward_kernel<bf16>, lds) : allow_lds(cg_forward_kernel<float>, lds);
+  if (e != hipSuccess) return e;
+  const dim3 grid(p.nb, p.B);
+  if (bf)
+    hipLaunchKernelGGL(cg_forward_kernel<bf16>, grid, dim3(NTHREADS), lds, s, p);
+  else
+    hipLaunchKernelGGL(cg_forward_kernel<float>, grid, dim3(NTHREADS), lds, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_cg_decode(const Problem &p, bool bf, hipStream_t s) {
+  const size_t lds = (size_t)(GT * 2 * p.bs) * sizeof(float);
+  hipError_t e = bf ? allow_lds(cg_decode_kernel<bf16>, lds) : allow_lds(cg_decode_kernel<float>, lds);
+  if (e != hipSuccess) return e;
+  const dim3 grid(p.nb, (p.B + GT - 1) / GT);
+  if (bf)
+    hipLaunchKernelGGL(cg_decode_kernel<bf16>, grid, dim3(NTHREADS), lds, s, p);
+  else
+    hipLaunchKernelGGL(cg_decode_kernel<float>, grid, dim3(NTHREADS), lds, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_cg_backward(const Problem &p, bool bf, hipStream_t s) {
+  return bf ? cg_backward_t<bf16>(p, s) : cg_backward_t<float>(p, s);
+}
+
+}  // namespace rglru

@@ -42,6 +42,8 @@ struct Problem {
   const void *u;
   const void *W_a, *W_x;
   const float *b_a, *b_x, *Lambda, *conv_w, *conv_b;   // conv_w null: no Conv1D, x_t = u_t (identity tap)
+  const float *theta;   // complex-gated variant only: [D/2] phases of the recurrence weight
+  float *dtheta;        //   and their gradient (backward)
   const float *h0;
   const void *state_in;
   const unsigned char *reset;  // [B][T] or null: non-zero where a new document starts (packed sequences):
@@ -107,6 +109,14 @@ hipError_t launch_backward_generic_tail(const Problem &p, bool bf, hipStream_t s
                                         bool with_wgrad = true, bool with_du = true);
 void backward_generic_arrays(const Problem &p, float **x, float **dp, float **dq, float **dx, float **partA);
 size_t generic_lds_bytes(int bs);
+
+// Complex-gated variant (Appendix B): D real channels as D / 2 complex ones, Problem.bs = complex
+// channels per gate block, W [nb][bs][2 bs]; shape-generic kernels. The backward's workspace is
+// the real layer's generic one for the same B, T, D followed by the recomputed states in fp32.
+size_t cg_backward_ws_bytes(int B, int T, int D, int nb);
+hipError_t launch_cg_forward(const Problem &p, bool bf, hipStream_t s);
+hipError_t launch_cg_decode(const Problem &p, bool bf, hipStream_t s);
+hipError_t launch_cg_backward(const Problem &p, bool bf, hipStream_t s);
 
 // MFMA forward (bf16 storage, gate blocks of 256)
 bool forward_mfma_supported(const Problem &p, bool bf);

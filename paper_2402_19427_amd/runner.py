@@ -187,6 +187,60 @@ class DeviceProblem:
         return out
 
 
+class CgDeviceProblem:
+    """Device copies of a complex-gated layer's parameters (Appendix B) and one-call helpers."""
+
+    def __init__(self, inp, B, T, D, nb, act, device="cuda:0", c=8.0, conv=True):
+        self.B, self.T, self.D, self.nb, self.act, self.device, self.c = B, T, D, nb, act, device, c
+        self.dt = R.BF16 if act == "bf16" else R.F32
+        self.tdtype = torch.bfloat16 if act == "bf16" else torch.float32
+        self.conv = conv
+        self.t = {k: to_device(inp[k], act if k in ("W_a", "W_x") else "f32", device)
+                  for k in ("W_a", "W_x", "b_a", "b_x", "Lambda", "theta", "conv_w", "conv_b")
+                  if inp.get(k) is not None}
+        self.params = R.make_cg_params(self.t["W_a"], self.t["W_x"], self.t["b_a"], self.t["b_x"],
+                                       self.t["Lambda"], self.t["theta"],
+                                       self.t["conv_w"] if conv else None,
+                                       self.t.get("conv_b") if conv else None)
+
+    def shape(self, T=None, B=None):
+        return R.make_shape(self.B if B is None else B, self.T if T is None else T, self.D, self.nb,
+                            self.dt, c=self.c, conv_width=4 if self.conv else 0)
+
+    def forward(self, u, h0=None, state_in=None, pos0=0, stream=None):
+        B, T, D = u.shape
+        y = torch.empty(B, T, D, dtype=self.tdtype, device=self.device)
+        hT = torch.empty(B, D, dtype=torch.float32, device=self.device)
+        st = torch.empty(B, 3, D, dtype=self.tdtype, device=self.device) if self.conv else None
+        R.rglru_cg_forward(self.shape(T=T, B=B), self.params, u, h0, state_in, pos0, y, hT, st, stream)
+        return y, hT, st
+
+    def decode_step(self, u_t, h, conv_state, pos, stream=None):
+        B, D = u_t.shape
+        y = torch.empty(B, D, dtype=self.tdtype, device=self.device)
+        R.rglru_cg_decode_step(self.shape(T=1, B=B), self.params, u_t, h, conv_state, pos, y, stream)
+        return y
+
+    def backward(self, u, dy, h0=None, state_in=None, pos0=0, dhT=None, stream=None):
+        B, T, D = u.shape
+        H, hs = D // 2, D // 2 // self.nb
+        f32 = lambda *s: torch.empty(*s, dtype=torch.float32, device=self.device)
+        g = dict(dW_a=f32(self.nb, hs, 2 * hs), dW_x=f32(self.nb, hs, 2 * hs), db_a=f32(H), db_x=f32(H),
+                 dLambda=f32(H), dtheta=f32(H))
+        if self.conv:
+            g["dconv_w"], g["dconv_b"] = f32(4, D), f32(D)
+        pg = R.make_cg_param_grads(g["dW_a"], g["dW_x"], g["db_a"], g["db_x"], g["dLambda"], g["dtheta"],
+                                   g.get("dconv_w"), g.get("dconv_b"))
+        sh = self.shape(T=T, B=B)
+        n = R.rglru_workspace_bytes(sh, R.OP_CG_BACKWARD)
+        ws = torch.empty(max(n, 256), dtype=torch.uint8, device=self.device)
+        du = torch.empty(B, T, D, dtype=self.tdtype, device=self.device)
+        dh0 = f32(B, D)
+        R.rglru_cg_backward(sh, self.params, u, h0, state_in, pos0, dy, dhT, du, dh0, pg, ws, n, stream)
+        g["du"], g["dh0"] = du, dh0
+        return g
+
+
 def scan(a, g, h0=None, flags=0, act="bf16", device="cuda:0", stream=None):
     """rglru_scan on device tensors a, g [B,T,D] (dtype of `act`); returns h, hT."""
     B, T, D = a.shape

@@ -173,6 +173,34 @@ def test_packed_calls_validation_and_workspace():
     assert e.value.code == R.ERR_INVALID_ARG
 
 
+def test_cg_calls_validation_and_workspace():
+    cg = R.make_cg_params(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)
+    s = R.make_shape(2, 8, 64, 2, R.F32)
+    need = R.rglru_workspace_bytes(s, R.OP_CG_BACKWARD)
+    assert need >= 5 * 2 * 8 * 64 * 4 and need % 256 == 0
+    for bad, what in ((R.make_shape(2, 8, 63, 1, R.F32), "even"), (R.make_shape(2, 8, 64, 3, R.F32), "multiple"),
+                      (R.make_shape(2, 8, 8192, 1, R.BF16), "exceeds")):
+        with pytest.raises(R.RglruError) as e:
+            R.rglru_cg_forward(bad, cg, FAKE, None, None, 0, FAKE, None, None)
+        assert what in str(e.value)
+        assert R.rglru_workspace_bytes(bad, R.OP_CG_BACKWARD) == 0
+    no_theta = R.make_cg_params(FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_cg_forward(s, no_theta, FAKE, None, None, 0, FAKE, None, None)
+    assert e.value.code == R.ERR_INVALID_ARG and "theta" in str(e.value)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_cg_decode_step(s, cg, FAKE, None, FAKE, 0, FAKE)
+    assert e.value.code == R.ERR_INVALID_ARG and "h" in str(e.value)
+    g = R.make_cg_param_grads(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_cg_backward(s, cg, FAKE, None, None, 0, FAKE, None, FAKE, None, g, FAKE, need - 1)
+    assert e.value.code == R.ERR_WORKSPACE
+    g2 = R.make_cg_param_grads(FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE)
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_cg_backward(s, cg, FAKE, None, None, 0, FAKE, None, FAKE, None, g2, FAKE, need)
+    assert e.value.code == R.ERR_INVALID_ARG and "dtheta" in str(e.value)
+
+
 def test_workspace_query_is_zero_for_invalid_shapes_and_keeps_error_string():
     bad = R.make_shape(2, 8, 16, 3, R.F32)
     with pytest.raises(R.RglruError):
