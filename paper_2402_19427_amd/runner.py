@@ -5,6 +5,8 @@ ctypes binding. It performs no arithmetic of the method.
 import numpy as np
 import torch
 
+import rglru_inputs as gen
+
 from . import binding as R
 
 
@@ -25,6 +27,22 @@ def to_device(a, act, device="cuda:0"):
 
 def to_host(t):
     return None if t is None else t.detach().float().cpu().numpy()
+
+
+class SeededDraws:
+    """Seeded synthetic tensors on the device: numpy PCG64 draws on the host (the generator of
+    rglru_inputs), rounded to the storage type and uploaded."""
+
+    def __init__(self, seed, device="cuda:0"):
+        self.rng = np.random.Generator(np.random.PCG64(seed))
+        self.device = device
+
+    def normal(self, *shape, act="f32"):
+        a = self.rng.standard_normal(shape, dtype=np.float32)
+        return to_device(gen.round_to_act(a, act) if act != "f32" else a, act, self.device)
+
+    def uniform(self, *shape):
+        return to_device(self.rng.random(shape, dtype=np.float32), "f32", self.device)
 
 
 class DeviceProblem:

@@ -95,10 +95,9 @@ def run_sequence_workload(w, dev, out, label="forward"):
     per_set = 2 * act_b * B * T * D
     nsets = int(min(8, max(1, -(-LLC_BYTES * 5 // 4 // per_set))))
     iters = 100 if B * T * D < (1 << 27) else 30
-    gtor = torch.Generator(device=dev)
-    gtor.manual_seed(w.seed)
-    us = [torch.randn(B, T, D, device=dev, generator=gtor).to(dp.tdtype) for _ in range(nsets)]
-    h0 = torch.randn(B, D, device=dev, generator=gtor) if w.h0 else None
+    draws = rn.SeededDraws(w.seed + 200, dev)
+    us = [draws.normal(B, T, D, act=w.act) for _ in range(nsets)]
+    h0 = draws.normal(B, D) if w.h0 else None
     ys = [dp.empty_act(B, T, D) for _ in range(nsets)]
     hT = dp.empty_f32(B, D)
     st = dp.empty_act(B, 3, D)
@@ -116,7 +115,7 @@ def run_sequence_workload(w, dev, out, label="forward"):
         return
     for i in range(nsets):
         fwd(i)
-    dys = [torch.randn(B, T, D, device=dev, generator=gtor).to(dp.tdtype) for _ in range(nsets)]
+    dys = [draws.normal(B, T, D, act=w.act) for _ in range(nsets)]
     du = dp.empty_act(B, T, D)
     dh0 = dp.empty_f32(B, D)
     g = dp.alloc_grads()
@@ -144,13 +143,12 @@ def run_decode_workload(w, dev, out, steps=1000, graph_only=False, label="decode
     flops = gate_flops("decode", B, 1, D, nb)
     per_set = (6 * act_b + 8) * B * D
     ncold = int(-(-LLC_BYTES * 5 // 4 // per_set))
-    gtor = torch.Generator(device=dev)
-    gtor.manual_seed(w.seed)
+    draws = rn.SeededDraws(w.seed + 200, dev)
 
     def make_set():
-        return dict(u=torch.randn(B, D, device=dev, generator=gtor).to(dp.tdtype),
-                    h=torch.randn(B, D, device=dev, generator=gtor),
-                    st=torch.randn(B, 3, D, device=dev, generator=gtor).to(dp.tdtype),
+        return dict(u=draws.normal(B, D, act=w.act),
+                    h=draws.normal(B, D),
+                    st=draws.normal(B, 3, D, act=w.act),
                     y=dp.empty_act(B, D))
 
     sets = [make_set() for _ in range(ncold)]
@@ -205,8 +203,6 @@ def run_scan_workload(dev, out, lengths=(1024, 4096, 16384, 65536)):
     """rglru_scan at batch 8, width 1024 (Appendix A.3), bf16 storage: a_t and g_t read, h_t
     written, 6 bytes per element; the state lives on chip."""
     B, D = 8, 1024
-    gtor = torch.Generator(device=dev)
-    gtor.manual_seed(7)
     for T in lengths:
         per_set = 3 * 2 * B * T * D
         nsets = int(min(8, max(1, -(-LLC_BYTES * 5 // 4 // per_set))))
@@ -214,15 +210,17 @@ def run_scan_workload(dev, out, lengths=(1024, 4096, 16384, 65536)):
         n = R.rglru_workspace_bytes(sh, R.OP_SCAN)
         ws = torch.empty(max(n, 256), dtype=torch.uint8, device=dev)
         sets = []
-        for _ in range(nsets):
-            # decays distributed like the layer's: base^8 ~ U[0.9, 0.999], power 8 r with r ~ U(0, 1)
-            base = torch.empty(D, device=dev).uniform_(0.9, 0.999, generator=gtor) ** 0.125
-            la = torch.rand(B, T, D, device=dev, generator=gtor) * 8.0 * torch.log(base)
-            sets.append(dict(a=torch.exp(la).to(torch.bfloat16), la=la.to(torch.bfloat16),
-                             g=torch.randn(B, T, D, device=dev, generator=gtor).to(torch.bfloat16),
+        for i in range(nsets):
+            # decays distributed like the layer's (the seeded generator of the parity tests):
+            # base^8 ~ U[0.9, 0.999], power 8 r with r ~ U(0, 1); a_t and log a_t of different draws
+            si = gen.make_scan_inputs(B, T, D, act="bf16", seed=7000 + 2 * i, h0=(i == 0))
+            sl = gen.make_scan_inputs(B, T, D, act="bf16", seed=7001 + 2 * i, log_a=True, h0=False)
+            if i == 0:
+                h0 = rn.to_device(si["h0"], "f32", dev)
+            sets.append(dict(a=rn.to_device(si["a"], "bf16", dev), la=rn.to_device(sl["a"], "bf16", dev),
+                             g=rn.to_device(si["g"], "bf16", dev),
                              h=torch.empty(B, T, D, dtype=torch.bfloat16, device=dev)))
-            del la
-        h0 = torch.randn(B, D, device=dev, generator=gtor)
+            del si, sl
         hT = torch.empty(B, D, device=dev)
         sp = torch.cuda.current_stream().cuda_stream
         nbytes = per_set + 8 * B * D
@@ -249,14 +247,13 @@ def run_merge_workload(dev, out, names=("C1", "C2", "C3", "C4"), steps=1000):
         B, T, D, nb = w.B, w.T, w.D, w.nb
         act_b = 2
         inp = gen.make_inputs(1, 8, D, nb, act=w.act, seed=w.seed)
-        gtor = torch.Generator(device=dev)
-        gtor.manual_seed(w.seed + 1)
+        draws = rn.SeededDraws(w.seed + 201, dev)
         if w.kind == "decode":
             dp = rn.DeviceProblem(inp, B, 1, D, nb, w.act, device=dev)
             sh = dp.shape(T=1)
-            u, br = (torch.randn(B, D, device=dev, generator=gtor).to(dp.tdtype) for _ in range(2))
-            h = torch.randn(B, D, device=dev, generator=gtor)
-            st = torch.randn(B, 3, D, device=dev, generator=gtor).to(dp.tdtype)
+            u, br = (draws.normal(B, D, act=w.act) for _ in range(2))
+            h = draws.normal(B, D)
+            st = draws.normal(B, 3, D, act=w.act)
             o = dp.empty_act(B, D)
             for label, call in (
                     ("decode", lambda i, q: R.rglru_decode_step(sh, dp.params, u, h, st, 3 + i, o, q)),
@@ -289,11 +286,11 @@ def run_merge_workload(dev, out, names=("C1", "C2", "C3", "C4"), steps=1000):
         per_set = 3 * act_b * B * T * D
         nsets = int(min(8, max(1, -(-LLC_BYTES * 5 // 4 // per_set))))
         iters = 100 if B * T * D < (1 << 27) else 30
-        us = [torch.randn(B, T, D, device=dev, generator=gtor).to(dp.tdtype) for _ in range(nsets)]
-        brs = [torch.randn(B, T, D, device=dev, generator=gtor).to(dp.tdtype) for _ in range(nsets)]
+        us = [draws.normal(B, T, D, act=w.act) for _ in range(nsets)]
+        brs = [draws.normal(B, T, D, act=w.act) for _ in range(nsets)]
         outs = [dp.empty_act(B, T, D) for _ in range(nsets)]
         ys = [dp.empty_act(B, T, D) for _ in range(nsets)]
-        h0 = torch.randn(B, D, device=dev, generator=gtor) if w.h0 else None
+        h0 = draws.normal(B, D) if w.h0 else None
         hT, st = dp.empty_f32(B, D), dp.empty_act(B, 3, D)
         ws_f, n_f = dp.workspace(sh, R.OP_FORWARD_MERGE)
         note = "%d buffer set%s" % (nsets, "s" if nsets > 1 else "")
@@ -316,7 +313,7 @@ def run_merge_workload(dev, out, names=("C1", "C2", "C3", "C4"), steps=1000):
             del us, brs, outs, ys
             torch.cuda.empty_cache()
             continue
-        douts = [torch.randn(B, T, D, device=dev, generator=gtor).to(dp.tdtype) for _ in range(nsets)]
+        douts = [draws.normal(B, T, D, act=w.act) for _ in range(nsets)]
         du, dbr, dh0 = dp.empty_act(B, T, D), dp.empty_act(B, T, D), dp.empty_f32(B, D)
         g = dp.alloc_grads()
         pg = R.make_param_grads(g["dW_a"], g["dW_x"], g["db_a"], g["db_x"], g["dLambda"],
