@@ -256,15 +256,20 @@ int rglru_backward(const rglru_shape *shape, const rglru_params *params, const v
  *              slots of inputs in front of that document's first step hold zeros.
  *   dh0        zero for a row whose reset[b][0] != 0.
  *   every other argument: as in rglru_forward / rglru_backward; conv_width 0 is accepted.
- *   workspace  the forward needs none; the backward needs
- *              rglru_workspace_bytes(shape, RGLRU_OP_BACKWARD_PACKED) bytes.
- * These calls run on the library's general kernels (one workgroup per (sequence, gate block),
- * plain fp32 arithmetic for either storage type) for every shape, not on the matrix-core
- * kernels of the unpacked calls; no kernel waits on another, so there is no workspace status.
+ *   workspace  rglru_workspace_bytes(shape, RGLRU_OP_FORWARD_PACKED) bytes for the forward,
+ *              rglru_workspace_bytes(shape, RGLRU_OP_BACKWARD_PACKED) bytes for the backward.
+ * The forward runs on the fused matrix-core kernel of rglru_forward where that takes the shape
+ * (bf16 storage, gate blocks of 128 - 256 channels; the boundaries reach it as bit masks per
+ * tile of 32 steps, and tiles without a boundary run the unpacked code), with
+ * rglru_workspace_status(shape, RGLRU_OP_FORWARD_PACKED, ...) as for rglru_forward; every
+ * other shape, and the backward for all shapes, run on the library's general kernels (one
+ * workgroup per (sequence, gate block), plain fp32 arithmetic for either storage type), where
+ * no kernel waits on another.
  */
 int rglru_forward_packed(const rglru_shape *shape, const rglru_params *params, const void *u,
                          const uint8_t *reset, const float *h0, const void *conv_state_in,
-                         int64_t pos0, void *y, float *hT, void *conv_state_out, void *stream);
+                         int64_t pos0, void *y, float *hT, void *conv_state_out, void *workspace,
+                         size_t workspace_bytes, void *stream);
 int rglru_backward_packed(const rglru_shape *shape, const rglru_params *params, const void *u,
                           const uint8_t *reset, const float *h0, const void *conv_state_in,
                           int64_t pos0, const void *y, const void *dy, const float *dhT, void *du,

@@ -72,7 +72,7 @@ def _load():
     lib.rglru_decode_step.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp]
     lib.rglru_decode_step_at.argtypes = [sp, pp, vp, vp, vp, vp, vp, vp]
     lib.rglru_backward.argtypes = [sp, pp, vp, vp, vp, i64, vp, vp, vp, vp, vp, gp, vp, sz, vp]
-    lib.rglru_forward_packed.argtypes = [sp, pp, vp, vp, vp, vp, i64, vp, vp, vp, vp]
+    lib.rglru_forward_packed.argtypes = [sp, pp, vp, vp, vp, vp, i64, vp, vp, vp, vp, sz, vp]
     lib.rglru_forward_packed.restype = ctypes.c_int
     lib.rglru_backward_packed.argtypes = [sp, pp, vp, vp, vp, vp, i64, vp, vp, vp, vp, vp, gp, vp, sz, vp]
     lib.rglru_backward_packed.restype = ctypes.c_int
@@ -230,10 +230,11 @@ def rglru_backward(shape, params, u, h0, conv_state_in, pos0, y, dy, dhT, du, dh
 
 
 def rglru_forward_packed(shape, params, u, reset, h0, conv_state_in, pos0, y, hT, conv_state_out,
-                         stream=None):
+                         workspace, workspace_bytes, stream=None):
     _check(_lib.rglru_forward_packed(_ref(shape), _ref(params), _addr(u), _addr(reset), _addr(h0),
                                      _addr(conv_state_in), pos0, _addr(y), _addr(hT),
-                                     _addr(conv_state_out), _stream(stream)))
+                                     _addr(conv_state_out), _addr(workspace), workspace_bytes,
+                                     _stream(stream)))
 
 
 def rglru_backward_packed(shape, params, u, reset, h0, conv_state_in, pos0, y, dy, dhT, du, dh0,

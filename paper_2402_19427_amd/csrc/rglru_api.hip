@@ -198,7 +198,9 @@ size_t workspace_need(const rglru_shape *s, int op) {
       if (s->act_dtype == RGLRU_BF16 && s->D % 256 == 0 && s->T >= 1)
         return scan_tiled_ws_bytes(s->B, s->T, s->D);
       return 0;
-    case RGLRU_OP_FORWARD_PACKED:
+    case RGLRU_OP_FORWARD_PACKED:   // the fused kernel's own scratch, then the boundary masks
+      if (s->act_dtype == RGLRU_BF16 && forward_mfma_block(s->D / s->num_blocks) && s->T >= 1)
+        return forward_mfma_ws_bytes(s->B, s->T, s->D, s->num_blocks) + forward_mfma_mask_bytes(s->B, s->T);
       return 0;
     case RGLRU_OP_BACKWARD_PACKED:
       return backward_generic_ws_bytes(s->B, s->T, s->D, s->num_blocks);
@@ -363,7 +365,7 @@ size_t rglru_workspace_bytes(const rglru_shape *shape, int op) {
 
 int rglru_workspace_status(const rglru_shape *shape, int op, const void *workspace, void *stream) {
   if (op != RGLRU_OP_FORWARD && op != RGLRU_OP_BACKWARD && op != RGLRU_OP_SCAN &&
-      op != RGLRU_OP_FORWARD_MERGE && op != RGLRU_OP_BACKWARD_MERGE)
+      op != RGLRU_OP_FORWARD_MERGE && op != RGLRU_OP_BACKWARD_MERGE && op != RGLRU_OP_FORWARD_PACKED)
     return fail(RGLRU_ERR_INVALID_ARG, "op %d has no workspace status", op);
   const bool bwd = op == RGLRU_OP_BACKWARD || op == RGLRU_OP_BACKWARD_MERGE;
   CHECK(check_shape(shape, op != RGLRU_OP_SCAN, true, bwd ? 1 : 0));
@@ -374,7 +376,7 @@ int rglru_workspace_status(const rglru_shape *shape, int op, const void *workspa
   if (!workspace) return fail(RGLRU_ERR_INVALID_ARG, "workspace is NULL");
   size_t off = 0;   // forward and scan keep the flag in the first word
   if ((op == RGLRU_OP_FORWARD || op == RGLRU_OP_FORWARD_MERGE) &&
-      !forward_mfma_block(shape->D / shape->num_blocks)) {
+      !forward_mfma_block(shape->D / shape->num_blocks)) {   // (packed: no workspace at these block sizes)
     // the passes of the other block sizes: only the scan waits, its workspace follows the
     // activation-sized buffers
     const size_t sw = scan_tiled_ws_bytes(shape->B, shape->T, shape->D);
@@ -468,7 +470,8 @@ int rglru_forward(const rglru_shape *shape, const rglru_params *params, const vo
 
 int rglru_forward_packed(const rglru_shape *shape, const rglru_params *params, const void *u,
                          const uint8_t *reset, const float *h0, const void *conv_state_in, int64_t pos0,
-                         void *y, float *hT, void *conv_state_out, void *stream) {
+                         void *y, float *hT, void *conv_state_out, void *workspace, size_t workspace_bytes,
+                         void *stream) {
   CHECK(check_shape(shape, true, true, 0));
   CHECK(check_params(shape, params));
   const size_t as = act_size(shape);
@@ -480,6 +483,7 @@ int rglru_forward_packed(const rglru_shape *shape, const rglru_params *params, c
   CHECK(check_ptr(hT, "hT", 4, false));
   CHECK(check_ptr(conv_state_in, "conv_state_in", as, false));
   CHECK(check_ptr(conv_state_out, "conv_state_out", as, false));
+  CHECK(check_workspace(workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_FORWARD_PACKED)));
 
   Problem q;
   memset(&q, 0, sizeof(q));
@@ -487,11 +491,20 @@ int rglru_forward_packed(const rglru_shape *shape, const rglru_params *params, c
   q.pos0 = pos0; q.u = u; q.h0 = h0; q.state_in = conv_state_in; q.reset = reset;
   q.y = y; q.hT = hT; q.state_out = conv_state_out;
   if (shape->conv_width == 0) q.state_in = q.state_out = nullptr;
+  q.ws = workspace; q.ws_bytes = workspace_bytes;
   const bool bf = shape->act_dtype == RGLRU_BF16;
   hipStream_t s = (hipStream_t)stream;
-  hipError_t e = launch_forward_generic(q, bf, s);
-  // the new ring state is written after the last read of the incoming one (they may alias)
-  if (e == hipSuccess) e = launch_state_update(q, bf, s);
+  hipError_t e;
+  if (forward_mfma_supported(q, bf)) {
+    e = launch_forward_mfma(q, s);   // the fused kernel takes the boundaries as bit masks per tile
+  } else {
+    e = launch_forward_generic(q, bf, s);
+    // where the shape would have taken the fused kernel (pointers too loosely aligned for it),
+    // its status word is cleared all the same
+    if (e == hipSuccess && q.ws && q.ws_bytes >= 256) e = launch_clear(q.ws, 16, s);
+    // the new ring state is written after the last read of the incoming one (they may alias)
+    if (e == hipSuccess) e = launch_state_update(q, bf, s);
+  }
   if (e != hipSuccess) return hip_fail(e, "forward launch");
   g_err[0] = 0;
   return RGLRU_OK;

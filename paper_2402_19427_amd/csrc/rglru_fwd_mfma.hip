@@ -43,6 +43,8 @@ struct FwdArgs {
   int *err;      // set to 1 if a bounded wait expired
   int swizzle;   // remap block ids so that neighbouring time slices share an XCD
   const unsigned short *wx16;   // W_x in half precision, same layout (fwd_prep_kernel)
+  const uint4 *rmask;           // packed sequences: per (sequence, tile) bit masks of the document
+                                // boundaries (reset_mask_kernel), or NULL
 };
 
 // eqs. (1)-(3) with base-2 exponentials; pp, qq, xx carry a factor log2(e).
@@ -79,6 +81,32 @@ __global__ void __launch_bounds__(256) fwd_prep_kernel(uint4 *zero, size_t n16, 
   }
 }
 
+typedef unsigned u32x4m __attribute__((ext_vector_type(4)));
+
+// Document boundaries of packed sequences as bit masks, one uint4 per (sequence, tile of 32
+// steps), bit i = step 32 tile + i:
+//   x: a document starts at this step (the recurrence takes h_{t-1} = 0)
+//   y, z, w: the Conv1D's lag 1, 2, 3 of this step stays inside the step's document (no start at
+//            steps t .. t-lag+1; inputs in front of a document count as zeros)
+__global__ void __launch_bounds__(256) reset_mask_kernel(const unsigned char *reset, uint4 *out, int B, int T,
+                                                         int ntile) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= B * ntile) return;
+  const int b = i / ntile, t0 = (i - b * ntile) * TT;
+  const unsigned char *m = reset + (size_t)b * T;
+  unsigned r = 0, l1 = 0, l2 = 0, l3 = 0;
+  for (int k = 0; k < TT; ++k) {
+    const int t = t0 + k;
+    if (t >= T) break;
+    const bool s0 = m[t] != 0, s1 = t >= 1 && m[t - 1] != 0, s2 = t >= 2 && m[t - 2] != 0;
+    r |= (unsigned)s0 << k;
+    l1 |= (unsigned)(!s0) << k;
+    l2 |= (unsigned)(!s0 && !s1) << k;
+    l3 |= (unsigned)(!s0 && !s1 && !s2) << k;
+  }
+  out[i] = make_uint4(r, l1, l2, l3);
+}
+
 constexpr int FWD_MAX_SLICES = 16;
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
@@ -101,7 +129,9 @@ __device__ __forceinline__ u32x4 merge8(const u32x4 yv, const u32x4 bv) {
 // width 2560 give 160) run in the 256-wide tile: parameter reads of the missing channels and
 // K-steps are clamped to existing ones (whatever they hold meets zeros: the Conv1D lanes of
 // missing channels write x = 0), their loads of u read nothing and their stores are dropped.
-template <int GMAX, int MERGE, bool PAD>
+// PACKED: the sequences hold several documents (FwdArgs.rmask); a variant of its own, so that
+// the plain kernel keeps its register allocation
+template <int GMAX, int MERGE, bool PAD, bool PACKED = false>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 fwd_mfma_kernel(FwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -143,7 +173,9 @@ fwd_mfma_kernel(FwdArgs a) {
   // (a narrower block has fewer K-steps that matter, and its clamped addresses cost registers;
   // measured best at 160 channels)
   constexpr int NRES_P = GMAX == 1 ? 11 : (GMAX == 4 ? 2 : (GMAX == 8 ? 0 : 2));
-  constexpr int NRES = !PAD ? NRES_M : (MERGE == 0 ? NRES_P : (NRES_P >= 2 ? NRES_P - 2 : 0));
+  constexpr int NRES_U = !PAD ? NRES_M : (MERGE == 0 ? NRES_P : (NRES_P >= 2 ? NRES_P - 2 : 0));
+  // (the masks of packed sequences take registers of their own)
+  constexpr int NRES = !PACKED ? NRES_U : (NRES_U >= 1 ? NRES_U - 1 : 0);
   constexpr int PF = 2;   // streamed fragments in flight (deeper rings measured no better)
   f16x8 wa[16], wx[NRES > 0 ? NRES : 1];   // (half precision, see w_to_f16)
   const f16x8 *pxs = (const f16x8 *)(a.wx16 + ((size_t)g * bs + chc) * bs + hf * 8);
@@ -255,15 +287,27 @@ fwd_mfma_kernel(FwdArgs a) {
     }
   };
   unsigned short *xw = xs + (8 * rg) * XS + 2 * c2;
-  auto conv_rows = [&](int buf) __attribute__((always_inline)) {
+  // (tl: the tile whose rows `raw` holds, mk: its mask word)
+  auto conv_rows = [&](int buf, int tl, const u32x4m &mk) __attribute__((always_inline)) {
     const f32x4 w01 = cw_lds[c2], w23 = cw_lds[128 + c2], bb = cw_lds[256 + c2];
+    // packed sequences: lags that reach in front of the row's document drop out (uniform over
+    // the workgroup; tiles without a boundary nearby take the plain path)
+    unsigned l1 = ~0u, l2 = ~0u, l3 = ~0u;
+    if (PACKED) {
+      l1 = mk[1]; l2 = mk[2]; l3 = mk[3];   // (rows past the end of the sequence: zero inputs either way)
+    }
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
+      // (packed sequences: a select per lag on a scalar condition, no branch around the rows)
+      const int bit = 8 * rg + r;
+      const unsigned v1 = (!PACKED || ((l1 >> bit) & 1u)) ? raw[r + 2] : 0u;
+      const unsigned v2 = (!PACKED || ((l2 >> bit) & 1u)) ? raw[r + 1] : 0u;
+      const unsigned v3 = (!PACKED || ((l3 >> bit) & 1u)) ? raw[r] : 0u;
       float x0 = bb[0], x1 = bb[1];
       x0 = fmaf(w01[0], bf_lo(raw[r + 3]), x0); x1 = fmaf(w01[1], bf_hi(raw[r + 3]), x1);
-      x0 = fmaf(w01[2], bf_lo(raw[r + 2]), x0); x1 = fmaf(w01[3], bf_hi(raw[r + 2]), x1);
-      x0 = fmaf(w23[0], bf_lo(raw[r + 1]), x0); x1 = fmaf(w23[1], bf_hi(raw[r + 1]), x1);
-      x0 = fmaf(w23[2], bf_lo(raw[r]), x0);     x1 = fmaf(w23[3], bf_hi(raw[r]), x1);
+      x0 = fmaf(w01[2], bf_lo(v1), x0);         x1 = fmaf(w01[3], bf_hi(v1), x1);
+      x0 = fmaf(w23[0], bf_lo(v2), x0);         x1 = fmaf(w23[1], bf_hi(v2), x1);
+      x0 = fmaf(w23[2], bf_lo(v3), x0);         x1 = fmaf(w23[3], bf_hi(v3), x1);
       unsigned hi_pk, lo_pk;
       split_f16(x0, x1, hi_pk, lo_pk);
       *(unsigned *)(xw + buf * (2 * XT_ELEMS) + r * XS) = hi_pk;
@@ -419,14 +463,15 @@ fwd_mfma_kernel(FwdArgs a) {
 
   // ---- everything after the products for tile `tl`, whose pre-activations sit in the
   // accumulators: finish the tile parked one step earlier, gates, aggregates, publication
-  auto pointwise = [&](int tl) __attribute__((always_inline)) {
+  auto pointwise = [&](int tl, unsigned starts) __attribute__((always_inline)) {
     const int t0 = tl * TT;
     if (GMAX > 1 && held >= 0) resolve(held);
 
     // gates (eqs. 1-3); the (a_t, b_t) pairs go to LDS, the lane keeps the aggregate of
     // its 16-step run: prun = prod a, hrun = end state for a zero incoming state
     float hrun = 0.f, prun = 1.f;
-    if (T - t0 >= TT) {  // full tile (uniform over the workgroup)
+    // (starts: the steps of this tile that start a document, packed sequences only)
+    if (T - t0 >= TT && starts == 0u) {  // full tile without a boundary (uniform over the workgroup)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         f32x4 aq, bq;
@@ -444,6 +489,7 @@ fwd_mfma_kernel(FwdArgs a) {
       }
     } else {
       const int nvalid = T - t0 - hf * 16;
+      const unsigned st16 = hf ? starts >> 16 : starts;   // this lane's 16 steps
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         f32x4 aq, bq;
@@ -455,6 +501,9 @@ fwd_mfma_kernel(FwdArgs a) {
             av = 1.f;
             bv = 0.f;
           }
+          // a document's first step starts from h_{t-1} = 0: nothing is carried into it (its
+          // own input still enters with sqrt(1 - a_t^2) of the true a_t)
+          if (PACKED && ((st16 >> (4 * q + e)) & 1u)) av = 0.f;
           hrun = fmaf(av, hrun, bv);
           prun *= av;
           aq[e] = av;
@@ -492,7 +541,30 @@ fwd_mfma_kernel(FwdArgs a) {
   int tile = w;
   if (tile < a.ntile) load_rows(tile * TT);
   __syncthreads();  // the constants parked in LDS are visible to every wave
-  if (tile < a.ntile) conv_rows(0);
+  // Mask words of packed sequences: lanes 0..3 of a wave fetch the four dwords of a tile's word two
+  // tiles ahead, as the first load of an iteration (a load consumed any sooner would make its
+  // wait a wait for the prefetched rows and weight fragments behind it as well); the word reaches
+  // the scalar registers by lane reads one iteration later. Tiles past the end read as zero.
+  const __amdgpu_buffer_rsrc_t mk_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_ptr(PACKED ? (const void *)(a.rmask + (size_t)b * a.ntile) : (const void *)p.u), 0,
+      PACKED ? (unsigned)a.ntile * 16u : 0u, 0x00020000);
+  auto mask_fetch = [&](int tl) __attribute__((always_inline)) {
+    return __builtin_amdgcn_raw_buffer_load_b32(mk_rsrc, (unsigned)(lane & 3) * 4u, (unsigned)tl * 16u, 0);
+  };
+  auto mask_word = [&](unsigned v) __attribute__((always_inline)) {
+    u32x4m m;
+    m[0] = __builtin_amdgcn_readlane(v, 0); m[1] = __builtin_amdgcn_readlane(v, 1);
+    m[2] = __builtin_amdgcn_readlane(v, 2); m[3] = __builtin_amdgcn_readlane(v, 3);
+    return m;
+  };
+  u32x4m mk0 = {0u, 0u, 0u, 0u};
+  unsigned mv_next = 0u;   // (lanes 0..3) word of the tile after this iteration's
+  if (PACKED) {
+    mk0 = mask_word(mask_fetch(tile));
+    mv_next = mask_fetch(tile + G);
+  }
+  if (tile < a.ntile) conv_rows(0, tile, mk0);
+  unsigned st_cur = mk0[0], st_prev = 0u;   // starts of this iteration's tile and of the one before
   __syncthreads();
 
   // (two copies of the loop, one per order, so that the accumulators are live across the
@@ -503,21 +575,29 @@ fwd_mfma_kernel(FwdArgs a) {
     for (; tile < a.ntile; tile += G, ++it) {
       const int buf = it & 1;
       const int next = tile + G;
+      u32x4m mkn = {0u, 0u, 0u, 0u};
+      unsigned mv_after = 0u;
+      if (PACKED) mv_after = mask_fetch(next + G);
       if (!LATE) {
         // rows of the next tile: after the streamed W_x fragments (loads return in order, and
         // these are trips to HBM); they land during the pointwise work
         gemm(buf);
         next_rows(next);
-        pointwise(tile);
+        pointwise(tile, st_cur);
         fetch_branch(GMAX > 1 ? held : next);   // for the tile that is finished next
       } else {
-        if (it > 0) pointwise(tile - G);
+        if (it > 0) pointwise(tile - G, st_prev);
         fetch_branch(GMAX > 1 ? held : tile);
         next_rows(next);                              // lands during the products
         gemm(buf);
       }
       // next tile of this workgroup into the other LDS buffer
-      if (next < a.ntile) conv_rows(buf ^ 1);
+      // (the word of the next tile is read where the tile's rows are waited for anyway)
+      if (PACKED) mkn = mask_word(mv_next);
+      if (next < a.ntile) conv_rows(buf ^ 1, next, mkn);
+      st_prev = st_cur;
+      st_cur = mkn[0];
+      mv_next = mv_after;
       // aggregates the parked tile will need: requested here, a whole step before their use and
       // clear of the streamed weight fragments (loads return in order); the other slices
       // published them earlier in this step
@@ -525,7 +605,7 @@ fwd_mfma_kernel(FwdArgs a) {
       __syncthreads();
     }
     if (LATE && it > 0) {
-      pointwise(tile - G);
+      pointwise(tile - G, st_prev);
       if (GMAX > 1) fetch_branch(held);
     }
   };
@@ -553,6 +633,11 @@ fwd_mfma_kernel(FwdArgs a) {
           v = __builtin_amdgcn_raw_buffer_load_b32(u_rsrc, u_voff, (unsigned)(npos - p.pos0) * row_bytes, 0);
         else if (st32)
           v = st32[(size_t)slot * (D / 2)];
+        if (PACKED) {   // an input in front of the last document's first step is not part of its history
+          const long long first = npos - p.pos0 + 1;   // (at least T - 2)
+          for (int t = first > 0 ? (int)first : 0; t < T; ++t)
+            if (p.reset[(size_t)b * T + t]) v = 0;
+        }
         so32[(size_t)slot * (D / 2)] = v;
       }
     }
@@ -929,6 +1014,12 @@ size_t forward_mfma_ws_bytes(int B, int T, int D, int nb) {
   return fwd_rec_bytes(B, T, nb) + ((w + 255) & ~(size_t)255);
 }
 
+// ... and, for packed sequences, by the boundary masks
+size_t forward_mfma_mask_bytes(int B, int T) {
+  const size_t n = (size_t)B * ((T + TT - 1) / TT) * sizeof(uint4);
+  return (n + 255) & ~(size_t)255;
+}
+
 template <int GMAX, int MERGE, bool PAD>
 static hipError_t launch_tmp(const FwdArgs &a, int grid, size_t lds, hipStream_t s) {
   static bool configured = false;  // the kernel asks for more than the default LDS limit
@@ -943,6 +1034,19 @@ static hipError_t launch_tmp(const FwdArgs &a, int grid, size_t lds, hipStream_t
   hipLaunchKernelGGL((fwd_mfma_kernel<GMAX, MERGE, PAD>), dim3(grid), dim3(NTHR), lds, s, a);
   return hipGetLastError();
 }
+template <int GMAX, bool PAD>
+static hipError_t launch_packed_tp(const FwdArgs &a, int grid, size_t lds, hipStream_t s) {
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void *)fwd_mfma_kernel<GMAX, 0, PAD, true>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, FWD_LDS);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  KernelTimer kt("fwd_packed_mfma_kernel", s);
+  hipLaunchKernelGGL((fwd_mfma_kernel<GMAX, 0, PAD, true>), dim3(grid), dim3(NTHR), lds, s, a);
+  return hipGetLastError();
+}
 template <int GMAX, int MERGE>
 static hipError_t launch_tm(const FwdArgs &a, int grid, size_t lds, hipStream_t s) {
   return a.p.bs == BS ? launch_tmp<GMAX, MERGE, false>(a, grid, lds, s)
@@ -950,6 +1054,8 @@ static hipError_t launch_tm(const FwdArgs &a, int grid, size_t lds, hipStream_t 
 }
 template <int GMAX>
 static hipError_t launch_t(const FwdArgs &a, int grid, size_t lds, hipStream_t s) {
+  if (a.rmask)   // (the packed entry point has no merge epilogue)
+    return a.p.bs == BS ? launch_packed_tp<GMAX, false>(a, grid, lds, s) : launch_packed_tp<GMAX, true>(a, grid, lds, s);
   return a.p.merge == 0 ? launch_tm<GMAX, 0>(a, grid, lds, s)
        : a.p.merge == 1 ? launch_tm<GMAX, 1>(a, grid, lds, s)
                         : launch_tm<GMAX, 2>(a, grid, lds, s);
@@ -978,6 +1084,15 @@ hipError_t launch_forward_mfma(const Problem &p, hipStream_t s) {
                        (const uint4 *)p.W_x, (uint4 *)wx16, n8);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+  }
+  a.rmask = nullptr;
+  if (p.reset) {
+    uint4 *masks = (uint4 *)((char *)p.ws + forward_mfma_ws_bytes(p.B, p.T, p.D, p.nb));
+    const int n = p.B * a.ntile;
+    hipLaunchKernelGGL(reset_mask_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p.reset, masks, p.B, p.T, a.ntile);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    a.rmask = masks;
   }
   if (a.G == 1) {
     a.rec = nullptr;

@@ -122,6 +122,7 @@ hipError_t launch_cg_backward(const Problem &p, bool bf, hipStream_t s);
 bool forward_mfma_supported(const Problem &p, bool bf);
 bool forward_mfma_block(int bs);   // gate block sizes the forward kernel takes
 size_t forward_mfma_ws_bytes(int B, int T, int D, int nb);
+size_t forward_mfma_mask_bytes(int B, int T);   // appended for packed sequences (Problem.reset)
 hipError_t launch_forward_mfma(const Problem &p, hipStream_t s);
 bool forward_mfma_merge_fused(const Problem &p);   // merge as epilogue (else: a kernel of its own)
 

@@ -107,7 +107,8 @@ class DeviceProblem:
         y = self.empty_act(B, T, D)
         hT = self.empty_f32(B, D)
         st = self.empty_act(B, 3, D)
-        R.rglru_forward_packed(sh, self.params, u, reset, h0, state_in, pos0, y, hT, st, stream)
+        ws, n = self.workspace(sh, R.OP_FORWARD_PACKED)
+        R.rglru_forward_packed(sh, self.params, u, reset, h0, state_in, pos0, y, hT, st, ws, n, stream)
         return y, hT, st
 
     def backward_packed(self, u, reset, y, dy, h0=None, state_in=None, pos0=0, dhT=None,

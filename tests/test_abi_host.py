@@ -151,15 +151,20 @@ def test_backward_validation_and_workspace():
 
 def test_packed_calls_validation_and_workspace():
     s = R.make_shape(2, 8, 512, 2, R.BF16)
-    assert R.rglru_workspace_bytes(s, R.OP_FORWARD_PACKED) == 0
+    fneed = R.rglru_workspace_bytes(s, R.OP_FORWARD_PACKED)
+    assert fneed >= R.rglru_workspace_bytes(s, R.OP_FORWARD) + 2 * 16 and fneed % 256 == 0
+    assert R.rglru_workspace_bytes(R.make_shape(2, 8, 96, 3, R.F32), R.OP_FORWARD_PACKED) == 0
     need = R.rglru_workspace_bytes(s, R.OP_BACKWARD_PACKED)
     assert need >= 4 * 2 * 8 * 512 * 4 and need % 256 == 0
     with pytest.raises(R.RglruError) as e:
-        R.rglru_forward_packed(s, params(), None, FAKE, None, None, 0, FAKE, None, None)
+        R.rglru_forward_packed(s, params(), None, FAKE, None, None, 0, FAKE, None, None, FAKE, fneed)
     assert e.value.code == R.ERR_INVALID_ARG and "u" in str(e.value)
     with pytest.raises(R.RglruError) as e:
-        R.rglru_forward_packed(s, params(), FAKE, FAKE, None, None, -1, FAKE, None, None)
+        R.rglru_forward_packed(s, params(), FAKE, FAKE, None, None, -1, FAKE, None, None, FAKE, fneed)
     assert e.value.code == R.ERR_INVALID_ARG
+    with pytest.raises(R.RglruError) as e:
+        R.rglru_forward_packed(s, params(), FAKE, FAKE, None, None, 0, FAKE, None, None, FAKE, fneed - 1)
+    assert e.value.code == R.ERR_WORKSPACE
     g = R.make_param_grads(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)
     args = (s, params(), FAKE, FAKE + 1, None, None, 0, FAKE, FAKE, None, FAKE, None, g)   # the mask is bytes: any address
     with pytest.raises(R.RglruError) as e:

@@ -752,6 +752,10 @@ PACKED = [
     (2, 130, 320, 2, "bf16", 16),
     (1, 700, 1024, 2, "bf16", 100),
     (4, 2, 64, 2, "bf16", 1),      # fewer steps than the filter is wide, a boundary at most steps
+    (8, 600, 2048, 8, "bf16", 50),  # fused forward: 64 units x 4 time slices
+    (1, 1500, 256, 1, "bf16", 200), # fused forward: 16 time slices, most tiles without a boundary
+    (3, 300, 2560, 16, "bf16", 7),  # fused forward, blocks of 160 channels, a boundary in most tiles
+    (33, 70, 1024, 4, "bf16", 30),  # fused forward, one workgroup per unit
 ]
 
 
