@@ -258,13 +258,13 @@ int rglru_backward(const rglru_shape *shape, const rglru_params *params, const v
  *   every other argument: as in rglru_forward / rglru_backward; conv_width 0 is accepted.
  *   workspace  rglru_workspace_bytes(shape, RGLRU_OP_FORWARD_PACKED) bytes for the forward,
  *              rglru_workspace_bytes(shape, RGLRU_OP_BACKWARD_PACKED) bytes for the backward.
- * The forward runs on the fused matrix-core kernel of rglru_forward where that takes the shape
- * (bf16 storage, gate blocks of 128 - 256 channels; the boundaries reach it as bit masks per
- * tile of 32 steps, and tiles without a boundary run the unpacked code), with
- * rglru_workspace_status(shape, RGLRU_OP_FORWARD_PACKED, ...) as for rglru_forward; every
- * other shape, and the backward for all shapes, run on the library's general kernels (one
- * workgroup per (sequence, gate block), plain fp32 arithmetic for either storage type), where
- * no kernel waits on another.
+ * Both calls run on the fused matrix-core kernels of rglru_forward / rglru_backward where those
+ * take the shape - the forward for bf16 storage and gate blocks of 128 - 256 channels, the
+ * backward for bf16 storage and blocks of 256 channels. The boundaries reach the kernels as bit
+ * masks per tile of 32 steps (a prep kernel makes them in the workspace); rglru_workspace_status
+ * with RGLRU_OP_FORWARD_PACKED / RGLRU_OP_BACKWARD_PACKED works as for the unpacked calls. Every
+ * other shape runs on the library's general kernels (one workgroup per (sequence, gate block),
+ * plain fp32 arithmetic for either storage type), where no kernel waits on another.
  */
 int rglru_forward_packed(const rglru_shape *shape, const rglru_params *params, const void *u,
                          const uint8_t *reset, const float *h0, const void *conv_state_in,

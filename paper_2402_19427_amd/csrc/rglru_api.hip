@@ -202,8 +202,15 @@ size_t workspace_need(const rglru_shape *s, int op) {
       if (s->act_dtype == RGLRU_BF16 && forward_mfma_block(s->D / s->num_blocks) && s->T >= 1)
         return forward_mfma_ws_bytes(s->B, s->T, s->D, s->num_blocks) + forward_mfma_mask_bytes(s->B, s->T);
       return 0;
-    case RGLRU_OP_BACKWARD_PACKED:
-      return backward_generic_ws_bytes(s->B, s->T, s->D, s->num_blocks);
+    case RGLRU_OP_BACKWARD_PACKED: {   // fused kernels for blocks of 256 channels (the general kernels remain the
+                                       // fallback for loosely aligned pointers), the general kernels otherwise
+      const size_t gen = backward_generic_ws_bytes(s->B, s->T, s->D, s->num_blocks);
+      if (s->act_dtype == RGLRU_BF16 && s->D / s->num_blocks == 256 && (size_t)s->T * s->D * 4 < ((size_t)1 << 32)) {
+        const size_t fused = backward_mfma_packed_ws_bytes(s->B, s->T, s->D, s->num_blocks);
+        return fused > gen ? fused : gen;
+      }
+      return gen;
+    }
     case RGLRU_OP_CG_BACKWARD:
       return cg_backward_ws_bytes(s->B, s->T, s->D, s->num_blocks);
     case RGLRU_OP_BACKWARD_MERGE:   // dy (+ dy_lo) between the merge adjoint and the backward, then the backward's own
@@ -365,9 +372,10 @@ size_t rglru_workspace_bytes(const rglru_shape *shape, int op) {
 
 int rglru_workspace_status(const rglru_shape *shape, int op, const void *workspace, void *stream) {
   if (op != RGLRU_OP_FORWARD && op != RGLRU_OP_BACKWARD && op != RGLRU_OP_SCAN &&
-      op != RGLRU_OP_FORWARD_MERGE && op != RGLRU_OP_BACKWARD_MERGE && op != RGLRU_OP_FORWARD_PACKED)
+      op != RGLRU_OP_FORWARD_MERGE && op != RGLRU_OP_BACKWARD_MERGE && op != RGLRU_OP_FORWARD_PACKED &&
+      op != RGLRU_OP_BACKWARD_PACKED)
     return fail(RGLRU_ERR_INVALID_ARG, "op %d has no workspace status", op);
-  const bool bwd = op == RGLRU_OP_BACKWARD || op == RGLRU_OP_BACKWARD_MERGE;
+  const bool bwd = op == RGLRU_OP_BACKWARD || op == RGLRU_OP_BACKWARD_MERGE || op == RGLRU_OP_BACKWARD_PACKED;
   CHECK(check_shape(shape, op != RGLRU_OP_SCAN, true, bwd ? 1 : 0));
   const size_t need = workspace_need(shape, op);
   hipError_t e = hipStreamSynchronize((hipStream_t)stream);
@@ -387,6 +395,8 @@ int rglru_workspace_status(const rglru_shape *shape, int op, const void *workspa
     if (shape->act_dtype == RGLRU_BF16 && shape->D / shape->num_blocks == 256 &&
         (size_t)shape->T * shape->D * 4 < ((size_t)1 << 32))
       off = backward_mfma_flag_offset(shape->B, shape->T, shape->D, shape->num_blocks);
+    else if (op == RGLRU_OP_BACKWARD_PACKED)
+      return RGLRU_OK;              // packed sequences at other block sizes: the general kernels
     else if (backward_via_padding(shape))
       off = backward_padded_flag_offset(shape->B, shape->T, shape->D, shape->num_blocks);
     else if (backward_in_passes(shape) &&
@@ -678,7 +688,19 @@ int rglru_backward_packed(const rglru_shape *shape, const rglru_params *params, 
     q.g.dconv_w = q.g.dconv_b = nullptr;
   }
   q.ws = workspace; q.ws_bytes = workspace_bytes;
-  const hipError_t e = launch_backward_generic(q, shape->act_dtype == RGLRU_BF16, (hipStream_t)stream);
+  const bool bf = shape->act_dtype == RGLRU_BF16;
+  hipError_t e;
+  if (reset && backward_mfma_supported(q, bf)) {
+    e = launch_backward_mfma(q, (hipStream_t)stream);   // the fused kernels take the boundaries as bit masks
+  } else {
+    e = launch_backward_generic(q, bf, (hipStream_t)stream);
+    // where the shape would have taken the fused kernels, their status word lies inside the
+    // scratch the general kernels have just used: leave it cleared
+    if (e == hipSuccess && bf && shape->D / shape->num_blocks == 256 &&
+        (size_t)shape->T * shape->D * 4 < ((size_t)1 << 32))
+      e = launch_clear((char *)workspace + backward_mfma_flag_offset(shape->B, shape->T, shape->D, shape->num_blocks),
+                       16, (hipStream_t)stream);
+  }
   if (e != hipSuccess) return hip_fail(e, "backward launch");
   g_err[0] = 0;
   return RGLRU_OK;

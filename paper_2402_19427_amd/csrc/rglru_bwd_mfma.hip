@@ -31,6 +31,7 @@ using namespace mfma;
 namespace {
 
 typedef unsigned u32x3 __attribute__((ext_vector_type(3)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 constexpr int TS = TT + 8;                       // row stride (bf16) of the [channel][time] tiles
 constexpr int TR_BYTES = BS * TS * 2;            // one transposed tile
 // LDS of the gates kernel: x tile (high, low) | constants | dy^T | y^T | r_t of the tile |
@@ -61,6 +62,7 @@ struct BwdArgs {
   unsigned char *dxo;                     // dxd, 24 bits per value (bf16 would break du: it sums four taps of it
                                           // with cancellation)
   float *part;                            // [B*G][3][D]: sums for db_a, db_x, dLambda
+  const uint4 *rmask;                     // packed sequences: boundary bit masks per (sequence, tile), or NULL
 };
 
 // packs the low halves (sel = 0) or high halves (sel = 1) of two dwords of bf16 pairs
@@ -70,7 +72,11 @@ __device__ __forceinline__ unsigned pick_halves(unsigned lo_src, unsigned hi_src
 }
 
 // DYLO: the upstream gradient is dy + dy_lo, two bf16 tensors (16 significant bits)
-template <int GMAX, bool DYLO = false>
+// PACKED: the sequences hold several documents (BwdArgs.rmask): nothing crosses a document's
+// first step - its h_{t-1} is zero, a_t delta_t does not reach the step before it, and the
+// Conv1D takes the inputs in front of it as zeros. An instance of its own, so that the plain
+// kernel keeps its register allocation.
+template <int GMAX, bool DYLO = false, bool PACKED = false>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 bwd_gates_kernel(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -101,7 +107,7 @@ bwd_gates_kernel(BwdArgs a) {
   // stay in registers, the next NLDS K-steps of W_x in LDS, and the rest is re-read from L2
   // every tile as contiguous 1 KB fragments (the register file cannot hold everything this
   // kernel needs, and L2 is a far better spill space than scratch)
-  constexpr int NRES = GMAX == 1 ? G_NRES + 1 : G_NRES, NLDS = g_nlds(DYLO);
+  constexpr int NRES = (GMAX == 1 ? G_NRES + 1 : G_NRES) - (PACKED ? 2 : 0), NLDS = g_nlds(DYLO);   // (the masks of packed sequences take registers of their own)
   // (the products run in half precision, see w_to_f16; the streamed copy is already converted)
   f16x8 wa[16], wx[NRES];
   // fragment ks of this lane when streamed: pxs[ks * 64] (W_x in fragment order)
@@ -201,16 +207,22 @@ bwd_gates_kernel(BwdArgs a) {
     }
   };
   unsigned short *xw = xs + (8 * rg) * XS + 2 * c2;
-  // Conv1D rows of this workgroup's next tile into the x tile
-  auto conv_rows = [&]() {
+  // Conv1D rows of this workgroup's next tile into the x tile (mk: the tile's mask word; packed
+  // sequences drop the lags that reach in front of a row's document, a select per lag on a
+  // scalar condition)
+  auto conv_rows = [&](const u32x4 &mk) {
     const f32x4 w01 = cw_lds[c2], w23 = cw_lds[128 + c2], bb = cw_lds[256 + c2];
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
+      const int bit = 8 * rg + r;
+      const unsigned v1 = (!PACKED || ((mk[1] >> bit) & 1u)) ? raw[r + 2] : 0u;
+      const unsigned v2 = (!PACKED || ((mk[2] >> bit) & 1u)) ? raw[r + 1] : 0u;
+      const unsigned v3 = (!PACKED || ((mk[3] >> bit) & 1u)) ? raw[r] : 0u;
       float x0 = bb[0], x1 = bb[1];
       x0 = fmaf(w01[0], bf_lo(raw[r + 3]), x0); x1 = fmaf(w01[1], bf_hi(raw[r + 3]), x1);
-      x0 = fmaf(w01[2], bf_lo(raw[r + 2]), x0); x1 = fmaf(w01[3], bf_hi(raw[r + 2]), x1);
-      x0 = fmaf(w23[0], bf_lo(raw[r + 1]), x0); x1 = fmaf(w23[1], bf_hi(raw[r + 1]), x1);
-      x0 = fmaf(w23[2], bf_lo(raw[r]), x0);     x1 = fmaf(w23[3], bf_hi(raw[r]), x1);
+      x0 = fmaf(w01[2], bf_lo(v1), x0);         x1 = fmaf(w01[3], bf_hi(v1), x1);
+      x0 = fmaf(w23[0], bf_lo(v2), x0);         x1 = fmaf(w23[1], bf_hi(v2), x1);
+      x0 = fmaf(w23[2], bf_lo(v3), x0);         x1 = fmaf(w23[3], bf_hi(v3), x1);
       unsigned hi_pk, lo_pk;
       split_f16(x0, x1, hi_pk, lo_pk);
       *(unsigned *)(xw + r * XS) = hi_pk;
@@ -275,15 +287,40 @@ bwd_gates_kernel(BwdArgs a) {
 
   // tiles are walked from the end of the sequence: this workgroup owns ntile-1-w, -G, ...
   int tile = a.ntile - 1 - w;
+  // Mask words of packed sequences: lanes 0..3 fetch the four dwords of a tile's word two tiles
+  // ahead, as the first load of an iteration, and the word reaches the scalar registers by lane
+  // reads where the tile's rows are waited for anyway. Tiles outside the sequence read as zero.
+  const __amdgpu_buffer_rsrc_t mk_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_ptr(PACKED ? (const void *)(a.rmask + (size_t)b * a.ntile) : (const void *)p.u), 0,
+      PACKED ? (unsigned)a.ntile * 16u : 0u, 0x00020000);
+  auto mask_fetch = [&](int tl) __attribute__((always_inline)) {
+    return __builtin_amdgcn_raw_buffer_load_b32(mk_rsrc, (unsigned)(lane & 3) * 4u, (unsigned)tl * 16u, 0);
+  };
+  auto mask_word = [&](unsigned v) __attribute__((always_inline)) {
+    u32x4 m;
+    m[0] = __builtin_amdgcn_readlane(v, 0); m[1] = __builtin_amdgcn_readlane(v, 1);
+    m[2] = __builtin_amdgcn_readlane(v, 2); m[3] = __builtin_amdgcn_readlane(v, 3);
+    return m;
+  };
+  u32x4 mk0 = {0u, 0u, 0u, 0u};
+  unsigned mv_next = 0u;
+  if (PACKED && tile >= 0) {
+    mk0 = mask_word(mask_fetch(tile));
+    mv_next = mask_fetch(tile - G);
+  }
+  unsigned starts = mk0[0];   // steps of this iteration's tile that start a document
   if (tile >= 0) load_rows(tile * TT);
   __syncthreads();
-  if (tile >= 0) conv_rows();
+  if (tile >= 0) conv_rows(mk0);
   if (tile >= 0) load_dy_y(tile * TT);
   __syncthreads();
 
   for (int it = 0; tile >= 0; tile -= G, ++it) {
     const int t0 = tile * TT;
     const int next = tile - G;
+    unsigned mv_after = 0u;
+    if (PACKED) mv_after = mask_fetch(next - G);
+    const unsigned st16 = hf ? starts >> 16 : starts;   // this lane's 16 steps
 
     // ---- gate pre-activations on the matrix cores
     f32x16 accp, accq, accx;
@@ -353,6 +390,7 @@ bwd_gates_kernel(BwdArgs a) {
         const float rv = __builtin_amdgcn_rcpf(1.f + ep);
         float av = __builtin_amdgcn_exp2f(kd * rv);
         if (4 * q + e >= nvalid) av = 1.f;  // past the end: eps passes through (dy is zero there)
+        if (PACKED && ((st16 >> (4 * q + e)) & 1u)) av = 0.f;   // nothing flows out of a document's first step
         erun = av * (dyv[e] + erun);
         prun *= av;
         rq[e] = rv;
@@ -439,7 +477,8 @@ bwd_gates_kernel(BwdArgs a) {
         const float eq = __builtin_amdgcn_exp2f(-accq[4 * q + e]);
         const float iv = __builtin_amdgcn_rcpf(1.f + eq);
         const float gin = iv * (accx[4 * q + e] * LN2);   // i_t x_t
-        const float hprev = e > 0 ? yv[e - 1] : hfirst;
+        const bool fresh = PACKED && ((st16 >> (4 * q + e)) & 1u);   // a document's first step: h_{t-1} = 0
+        const float hprev = fresh ? 0.f : (e > 0 ? yv[e - 1] : hfirst);
         const float dla = (delta * av) * fmaf(-av * gin, rs, hprev);   // delta a (h_{t-1} - a g/m)
         const float dg = delta * m;
         dxv[e] = dg * iv;
@@ -449,7 +488,7 @@ bwd_gates_kernel(BwdArgs a) {
         s_lam = fmaf(dla, rv, s_lam);
         s_ba += dpv[e];                             // (unscaled at the end)
         s_bx += dqu;
-        erev = ok ? av * delta : erev;
+        erev = ok ? (fresh ? 0.f : av * delta) : erev;
       }
       // S dp, S dq (half precision): one 64-byte piece of a row per lane half and step
       {
@@ -481,8 +520,12 @@ bwd_gates_kernel(BwdArgs a) {
       }
     }
 
+    u32x4 mkn = {0u, 0u, 0u, 0u};
+    if (PACKED) mkn = mask_word(mv_next);
+    starts = mkn[0];
+    mv_next = mv_after;
     if (next >= 0) {
-      conv_rows();
+      conv_rows(mkn);
       // dy and y of the next tile: requested before the barrier, so that part of the trip to HBM
       // is over when the streamed weight fragments of the next product queue up behind it
       load_dy_y(next * TT);
@@ -530,6 +573,7 @@ struct DgradArgs {
   const unsigned char *dxo;                // dxd [B][ceil(T/4)][D][12 bytes]
   const unsigned short *wta, *wtx;         // transposed gate weights [nb][in k][out j], half precision
   float *part;                             // [B*C][5][D]: dconv_w[0..3], dconv_b partial sums
+  const uint4 *rmask;                      // packed sequences: boundary bit masks per (sequence, tile), or NULL
 };
 
 // Preparation pass of the backward: the first 128 nb blocks transpose W_a and W_x in 32 x 32
@@ -578,6 +622,9 @@ __global__ void __launch_bounds__(256) bwd_prep_kernel(PrepArgs a) {
   }
 }
 
+// PACKED: the sequences hold several documents (DgradArgs.rmask): lag k of step t counts only
+// while step t - k belongs to t's document, in du and in the tap gradients alike.
+template <bool PACKED = false>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 bwd_dgrad_kernel(DgradArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -737,6 +784,21 @@ bwd_dgrad_kernel(DgradArgs a) {
     // them done. The u tile is double-buffered so that the taps' sums of one tile may still read
     // it while the next tile is parked.
     int tile = hi < a.ntile ? hi : hi - 1;
+    // mask words of packed sequences (lag masks y, z, w of a tile's word): fetched by lanes 0..3 an
+    // iteration ahead with the other loads, read into scalar registers at the top of the next one
+    const __amdgpu_buffer_rsrc_t mk_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        uniform_ptr(PACKED ? (const void *)(a.rmask + (size_t)b * a.ntile) : (const void *)p.u), 0,
+        PACKED ? (unsigned)a.ntile * 16u : 0u, 0x00020000);
+    auto mask_fetch = [&](int tl) __attribute__((always_inline)) {
+      return __builtin_amdgcn_raw_buffer_load_b32(mk_rsrc, (unsigned)(lane & 3) * 4u, (unsigned)tl * 16u, 0);
+    };
+    unsigned mv = 0u, lnext[4] = {0u, 0u, 0u, 0u};   // word of this iteration's tile (lanes 0..3); the tile after it
+    if (PACKED) {
+      const unsigned v = mask_fetch(tile + 1);
+#pragma unroll
+      for (int k = 1; k < 4; ++k) lnext[k] = __builtin_amdgcn_readlane(v, k);
+      mv = mask_fetch(tile);
+    }
     load_a(0, tile * TT);
     if (tile > lo) load_a(1, (tile - 1) * TT);
     load_dxd(tile * TT, true);
@@ -745,6 +807,11 @@ bwd_dgrad_kernel(DgradArgs a) {
     for (int it = 0; tile >= lo; --tile, ++it) {
       const int buf = it & 1, t0 = tile * TT;
       const bool halo = tile == hi;
+      unsigned lcur[4] = {0u, ~0u, ~0u, ~0u};
+      if (PACKED) {
+#pragma unroll
+        for (int k = 1; k < 4; ++k) lcur[k] = __builtin_amdgcn_readlane(mv, k);
+      }
 
       f32x16 acc0, acc1;
 #pragma unroll
@@ -779,20 +846,46 @@ bwd_dgrad_kernel(DgradArgs a) {
       if (tile - 2 >= lo) load_a(buf, t0 - 2 * TT);
       load_dxd(t0 - TT, tile > lo);   // (nothing left to fetch after the last tile: out of range, zeros)
       load_u(t0 - TT, tile > lo);
+      if (PACKED) mv = mask_fetch(tile - 1);
+      // lag masks of the 19 steps from this lane's first: bit i = step 16 hf + i (the steps past
+      // the tile are the next tile's first three)
+      unsigned wk[4] = {0u, 0u, 0u, 0u};
+      // (the packed instance masks every tile: the selects are cheap next to this kernel's memory
+      // traffic, and a second copy of the sums for tiles without a boundary costs registers)
+      constexpr bool plain = !PACKED;
+      if (PACKED) {
+#pragma unroll
+        for (int k = 1; k < 4; ++k) wk[k] = hf ? ((lcur[k] >> 16) | (lnext[k] << 16)) : lcur[k];
+      }
       if (!halo) {
         // Conv1D adjoint towards the input; the wave's [32 steps][32 channels] results leave
         // through its staging tile as 16-byte stores
+        if (plain) {
 #pragma unroll
-        for (int r = 0; r < 16; r += 2) {
-          float v0 = cw[0] * dx[r], v1 = cw[0] * dx[r + 1];
+          for (int r = 0; r < 16; r += 2) {
+            float v0 = cw[0] * dx[r], v1 = cw[0] * dx[r + 1];
 #pragma unroll
-          for (int k = 1; k < 4; ++k) {
-            v0 = fmaf(cw[k], dx[r + k], v0);
-            v1 = fmaf(cw[k], dx[r + 1 + k], v1);
+            for (int k = 1; k < 4; ++k) {
+              v0 = fmaf(cw[k], dx[r + k], v0);
+              v1 = fmaf(cw[k], dx[r + 1 + k], v1);
+            }
+            const unsigned pk = pack_bf16(v0, v1);
+            ot_mine[r * OT] = (unsigned short)(pk & 0xffff);
+            ot_mine[(r + 1) * OT] = (unsigned short)(pk >> 16);
           }
-          const unsigned pk = pack_bf16(v0, v1);
-          ot_mine[r * OT] = (unsigned short)(pk & 0xffff);
-          ot_mine[(r + 1) * OT] = (unsigned short)(pk >> 16);
+        } else {   // x_{t+k} sees u_t only while t lies in its document
+#pragma unroll
+          for (int r = 0; r < 16; r += 2) {
+            float v0 = cw[0] * dx[r], v1 = cw[0] * dx[r + 1];
+#pragma unroll
+            for (int k = 1; k < 4; ++k) {
+              v0 = fmaf(cw[k], ((wk[k] >> (r + k)) & 1u) ? dx[r + k] : 0.f, v0);
+              v1 = fmaf(cw[k], ((wk[k] >> (r + 1 + k)) & 1u) ? dx[r + 1 + k] : 0.f, v1);
+            }
+            const unsigned pk = pack_bf16(v0, v1);
+            ot_mine[r * OT] = (unsigned short)(pk & 0xffff);
+            ot_mine[(r + 1) * OT] = (unsigned short)(pk >> 16);
+          }
         }
         store_staged_tile_s<OT, RGLRU_NT>(otile, lane, du_rsrc, du_voff, (unsigned)t0 * row_bytes, row_bytes, T - t0);
         // Conv1D adjoint towards the taps: u_{t-k} in accumulator layout by selection
@@ -804,11 +897,20 @@ bwd_dgrad_kernel(DgradArgs a) {
           const unsigned short *up = urow_base + buf * (D_U_TILE / 2) - k * XS;
           au = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(up), sel_lds[lane], au, 0, 0, 0);
           au = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(up + 16), sel_lds[64 + lane], au, 0, 0, 0);
+          if (k == 0 || plain) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) sw[k] = fmaf(dx[r], au[r], sw[k]);
+            for (int r = 0; r < 16; ++r) sw[k] = fmaf(dx[r], au[r], sw[k]);
+          } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sw[k] = fmaf(((wk[k] >> r) & 1u) ? dx[r] : 0.f, au[r], sw[k]);
+          }
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) sb += dx[r];
+      }
+      if (PACKED) {
+#pragma unroll
+        for (int k = 1; k < 4; ++k) lnext[k] = lcur[k];
       }
     }
   }
@@ -852,8 +954,12 @@ struct WgradArgs {
   const unsigned short *state_in;           // bf16 [B][3][D] ring, or NULL
   const float *conv_w, *conv_b;             // [4][D], [D] or NULL
   float *part;                              // [S][2][nb][256][256]
+  const unsigned char *nlag;                // packed sequences: [rows] largest Conv1D lag inside the row's document, or NULL
 };
 
+// PACKED: the sequences hold several documents (WgradArgs.nlag): x is rebuilt with the lags that
+// reach in front of a row's document dropped.
+template <bool PACKED = false>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 bwd_wgrad_kernel(WgradArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -924,6 +1030,7 @@ bwd_wgrad_kernel(WgradArgs a) {
     return 0u;
   };
   unsigned raw[11];   // inputs of rows r0-3 .. r0+7, r0 = first of this thread's 8 rows
+  unsigned nl0 = 0x03030303u, nl1 = 0x03030303u;   // largest lag of rows r0 .. r0+3 and r0+4 .. r0+7, a byte each
   int slow = 0;       // this thread's rows of the tile being prepared are not one plain window
   // (sequence, step) of this thread's first row in the tile the next load_tiles call fetches;
   // the calls walk consecutive tiles, so it advances without a division
@@ -942,7 +1049,6 @@ bwd_wgrad_kernel(WgradArgs a) {
       const unsigned nrows = left < TT ? (unsigned)left : (unsigned)TT;
       const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
           uniform_ptr(src + (size_t)first * D), 0, nrows * row_bytes, 0x00020000);
-      typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, t_voff, (unsigned)(16 * h) * row_bytes, RGLRU_NT);
@@ -950,6 +1056,12 @@ bwd_wgrad_kernel(WgradArgs a) {
       }
     }
     slow = !(nt_ >= 3 && nt_ + 8 <= T && r0 + 8 <= a.rows);
+    if (PACKED) {   // (no branch on `slow` around the load; r0 is a multiple of 8, and the array is
+                    // padded by a tile beyond the last row: one aligned 8-byte read)
+      const uint2 v = *(const uint2 *)(a.nlag + r0);
+      nl0 = v.x;
+      nl1 = v.y;
+    }
     if (!slow) {
       // (cached normally: the other gate's workgroup of this slice finds these rows in L2)
       const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(
@@ -973,11 +1085,13 @@ bwd_wgrad_kernel(WgradArgs a) {
     if (!slow) {
 #pragma unroll
       for (int r = 0; r < 8; ++r) {
+        const unsigned n = PACKED ? (((r < 4 ? nl0 : nl1) >> (8 * (r & 3))) & 3u) : 3u;
+        const unsigned v1 = n >= 1u ? raw[r + 2] : 0u, v2 = n >= 2u ? raw[r + 1] : 0u, v3 = n >= 3u ? raw[r] : 0u;
         float x0 = bb[0], x1 = bb[1];
         x0 = fmaf(w01[0], bf_lo(raw[r + 3]), x0); x1 = fmaf(w01[1], bf_hi(raw[r + 3]), x1);
-        x0 = fmaf(w01[2], bf_lo(raw[r + 2]), x0); x1 = fmaf(w01[3], bf_hi(raw[r + 2]), x1);
-        x0 = fmaf(w23[0], bf_lo(raw[r + 1]), x0); x1 = fmaf(w23[1], bf_hi(raw[r + 1]), x1);
-        x0 = fmaf(w23[2], bf_lo(raw[r]), x0);     x1 = fmaf(w23[3], bf_hi(raw[r]), x1);
+        x0 = fmaf(w01[2], bf_lo(v1), x0);         x1 = fmaf(w01[3], bf_hi(v1), x1);
+        x0 = fmaf(w23[0], bf_lo(v2), x0);         x1 = fmaf(w23[1], bf_hi(v2), x1);
+        x0 = fmaf(w23[2], bf_lo(v3), x0);         x1 = fmaf(w23[3], bf_hi(v3), x1);
         xa[r] = x0;
         xb[r] = x1;
       }
@@ -990,8 +1104,9 @@ bwd_wgrad_kernel(WgradArgs a) {
         if (row < a.rows) {
           const long long b = row / T;
           const int t = (int)(row - b * T);
-          const unsigned i0 = input_at(b, t), i1 = input_at(b, t - 1), i2 = input_at(b, t - 2),
-                         i3 = input_at(b, t - 3);
+          const unsigned n = PACKED ? a.nlag[row] : 3u;
+          const unsigned i0 = input_at(b, t), i1 = n >= 1u ? input_at(b, t - 1) : 0u,
+                         i2 = n >= 2u ? input_at(b, t - 2) : 0u, i3 = n >= 3u ? input_at(b, t - 3) : 0u;
           x0 = bb[0]; x1 = bb[1];
           x0 = fmaf(w01[0], bf_lo(i0), x0); x1 = fmaf(w01[1], bf_hi(i0), x1);
           x0 = fmaf(w01[2], bf_lo(i1), x0); x1 = fmaf(w01[3], bf_hi(i1), x1);
@@ -1175,9 +1290,10 @@ size_t al256(size_t n) { return (n + 255) & ~(size_t)255; }
 struct BwdPlan {
   int units, ntile, G, R, C, S;
   size_t off_dp, off_dq, off_dx, off_wta, off_wtx, off_wxf, off_sc, off_rec, off_partA, off_partC, off_partW, total;
+  size_t off_masks, off_nlag;   // packed sequences only, behind everything else
 };
 
-BwdPlan plan_backward(int B, int T, int D, int nb, int ncu) {
+BwdPlan plan_backward(int B, int T, int D, int nb, int ncu, bool packed = false) {
   BwdPlan q;
   q.units = B * nb;
   q.ntile = (T + TT - 1) / TT;
@@ -1205,6 +1321,11 @@ BwdPlan plan_backward(int B, int T, int D, int nb, int ncu) {
   q.off_partA = off; off += al256((size_t)B * q.G * 3 * D * 4);
   q.off_partC = off; off += al256((size_t)B * q.C * 5 * D * 4);
   q.off_partW = off; off += al256((size_t)q.S * 2 * nb * BS * BS * 4);
+  q.off_masks = q.off_nlag = off;
+  if (packed) {
+    q.off_masks = off; off += al256((size_t)B * q.ntile * sizeof(uint4));
+    q.off_nlag = off; off += al256((size_t)B * T + TT);   // (read in 8-byte pieces up to a tile past the end)
+  }
   q.total = off;
   return q;
 }
@@ -1223,6 +1344,10 @@ size_t backward_mfma_ws_bytes(int B, int T, int D, int nb) {
   return plan_backward(B, T, D, nb, 256).total;
 }
 
+size_t backward_mfma_packed_ws_bytes(int B, int T, int D, int nb) {
+  return plan_backward(B, T, D, nb, 256, true).total;
+}
+
 size_t backward_mfma_flag_offset(int B, int T, int D, int nb) {
   int ncu = num_cu();
   if (ncu > 256) ncu = 256;
@@ -1237,11 +1362,18 @@ static hipError_t big_lds(K kernel, int bytes) {
 hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   int ncu = num_cu();
   if (ncu > 256) ncu = 256;
-  const BwdPlan q = plan_backward(p.B, p.T, p.D, p.nb, ncu);
+  const bool packed = p.reset != nullptr;
+  const BwdPlan q = plan_backward(p.B, p.T, p.D, p.nb, ncu, packed);
   char *ws = (char *)p.ws;
   hipError_t e;
   static bool configured = false;
   if (!configured) {
+    if ((e = big_lds(bwd_gates_kernel<1, false, true>, g_lds(false))) != hipSuccess) return e;
+    if ((e = big_lds(bwd_gates_kernel<4, false, true>, g_lds(false))) != hipSuccess) return e;
+    if ((e = big_lds(bwd_gates_kernel<8, false, true>, g_lds(false))) != hipSuccess) return e;
+    if ((e = big_lds(bwd_gates_kernel<16, false, true>, g_lds(false))) != hipSuccess) return e;
+    if ((e = big_lds(bwd_dgrad_kernel<true>, D_LDS)) != hipSuccess) return e;
+    if ((e = big_lds(bwd_wgrad_kernel<true>, W_LDS)) != hipSuccess) return e;
     if ((e = big_lds(bwd_gates_kernel<1>, g_lds(false))) != hipSuccess) return e;
     if ((e = big_lds(bwd_gates_kernel<4>, g_lds(false))) != hipSuccess) return e;
     if ((e = big_lds(bwd_gates_kernel<8>, g_lds(false))) != hipSuccess) return e;
@@ -1250,8 +1382,8 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
     if ((e = big_lds(bwd_gates_kernel<4, true>, g_lds(true))) != hipSuccess) return e;
     if ((e = big_lds(bwd_gates_kernel<8, true>, g_lds(true))) != hipSuccess) return e;
     if ((e = big_lds(bwd_gates_kernel<16, true>, g_lds(true))) != hipSuccess) return e;
-    if ((e = big_lds(bwd_dgrad_kernel, D_LDS)) != hipSuccess) return e;
-    if ((e = big_lds(bwd_wgrad_kernel, W_LDS)) != hipSuccess) return e;
+    if ((e = big_lds(bwd_dgrad_kernel<false>, D_LDS)) != hipSuccess) return e;
+    if ((e = big_lds(bwd_wgrad_kernel<false>, W_LDS)) != hipSuccess) return e;
     configured = true;
   }
   unsigned short *wta = (unsigned short *)(ws + q.off_wta), *wtx = (unsigned short *)(ws + q.off_wtx);
@@ -1265,9 +1397,15 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   if ((e = launch_grad_scale(p.dy, (size_t)p.B * p.T * p.D, p.dhT, (size_t)p.B * p.D, sc, 5, s)) != hipSuccess)
     return e;
 
+  // (packed sequences: the document boundaries as bit masks per tile and as lag counts per step)
+  uint4 *masks = (uint4 *)(ws + q.off_masks);
+  unsigned char *nlag = (unsigned char *)(ws + q.off_nlag);
+  if (packed && (e = launch_reset_masks(p.reset, masks, nlag, p.B, p.T, s)) != hipSuccess) return e;
+
   // 1. gates, reverse scan, pointwise adjoints
   BwdArgs a;
   a.p = p;
+  a.rmask = packed ? masks : nullptr;
   a.G = q.G; a.ntile = q.ntile; a.R = q.R;
   a.err = (int *)(ws + q.off_rec);
   a.rec = (u64 *)(ws + q.off_rec + 256);
@@ -1296,8 +1434,17 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   }
   if ((e = hipGetLastError()) != hipSuccess) return e;
   {
-    KernelTimer kt("bwd_gates_kernel", s);
-    if (p.dy_lo) {
+    KernelTimer kt(packed ? "bwd_gates_packed_kernel" : "bwd_gates_kernel", s);
+    if (packed) {   // (the packed entry point takes dy as one tensor)
+      if (q.G == 1)
+        hipLaunchKernelGGL((bwd_gates_kernel<1, false, true>), dim3(grid), dim3(NTHR), g_lds(false), s, a);
+      else if (q.G <= 4)
+        hipLaunchKernelGGL((bwd_gates_kernel<4, false, true>), dim3(grid), dim3(NTHR), g_lds(false), s, a);
+      else if (q.G <= 8)
+        hipLaunchKernelGGL((bwd_gates_kernel<8, false, true>), dim3(grid), dim3(NTHR), g_lds(false), s, a);
+      else
+        hipLaunchKernelGGL((bwd_gates_kernel<16, false, true>), dim3(grid), dim3(NTHR), g_lds(false), s, a);
+    } else if (p.dy_lo) {
       if (q.G == 1)
         hipLaunchKernelGGL((bwd_gates_kernel<1, true>), dim3(grid), dim3(NTHR), g_lds(true), s, a);
       else if (q.G <= 4)
@@ -1325,9 +1472,13 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   dg.sc = sc;
   dg.wta = wta; dg.wtx = wtx;
   dg.part = (float *)(ws + q.off_partC);
+  dg.rmask = packed ? masks : nullptr;
   {
-    KernelTimer kt("bwd_dgrad_kernel", s);
-    hipLaunchKernelGGL(bwd_dgrad_kernel, dim3(q.units * q.C), dim3(NTHR), D_LDS, s, dg);
+    KernelTimer kt(packed ? "bwd_dgrad_packed_kernel" : "bwd_dgrad_kernel", s);
+    if (packed)
+      hipLaunchKernelGGL(bwd_dgrad_kernel<true>, dim3(q.units * q.C), dim3(NTHR), D_LDS, s, dg);
+    else
+      hipLaunchKernelGGL(bwd_dgrad_kernel<false>, dim3(q.units * q.C), dim3(NTHR), D_LDS, s, dg);
   }
   if ((e = hipGetLastError()) != hipSuccess) return e;
 
@@ -1341,9 +1492,13 @@ hipError_t launch_backward_mfma(const Problem &p, hipStream_t s) {
   wg.state_in = (const unsigned short *)p.state_in;
   wg.conv_w = p.conv_w; wg.conv_b = p.conv_b;
   wg.part = (float *)(ws + q.off_partW);
+  wg.nlag = packed ? nlag : nullptr;
   {
-    KernelTimer kt("bwd_wgrad_kernel", s);
-    hipLaunchKernelGGL(bwd_wgrad_kernel, dim3((q.S * 2 * p.nb + 15) / 16 * 16), dim3(NTHR), W_LDS, s, wg);
+    KernelTimer kt(packed ? "bwd_wgrad_packed_kernel" : "bwd_wgrad_kernel", s);
+    if (packed)
+      hipLaunchKernelGGL(bwd_wgrad_kernel<true>, dim3((q.S * 2 * p.nb + 15) / 16 * 16), dim3(NTHR), W_LDS, s, wg);
+    else
+      hipLaunchKernelGGL(bwd_wgrad_kernel<false>, dim3((q.S * 2 * p.nb + 15) / 16 * 16), dim3(NTHR), W_LDS, s, wg);
   }
   if ((e = hipGetLastError()) != hipSuccess) return e;
   // 4. all partial sums

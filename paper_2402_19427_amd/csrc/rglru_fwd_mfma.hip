@@ -88,8 +88,12 @@ typedef unsigned u32x4m __attribute__((ext_vector_type(4)));
 //   x: a document starts at this step (the recurrence takes h_{t-1} = 0)
 //   y, z, w: the Conv1D's lag 1, 2, 3 of this step stays inside the step's document (no start at
 //            steps t .. t-lag+1; inputs in front of a document count as zeros)
-__global__ void __launch_bounds__(256) reset_mask_kernel(const unsigned char *reset, uint4 *out, int B, int T,
-                                                         int ntile) {
+// Steps past the end of the sequence count as inside a document (their inputs are zero anyway),
+// so that a ragged last tile without a boundary looks like any other tile without one.
+// nlag (may be null): per step the largest lag (0..3) that stays inside the step's document,
+// [B * T] bytes, for kernels that walk the flattened rows.
+__global__ void __launch_bounds__(256) reset_mask_kernel(const unsigned char *reset, uint4 *out,
+                                                         unsigned char *nlag, int B, int T, int ntile) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i >= B * ntile) return;
   const int b = i / ntile, t0 = (i - b * ntile) * TT;
@@ -97,12 +101,16 @@ __global__ void __launch_bounds__(256) reset_mask_kernel(const unsigned char *re
   unsigned r = 0, l1 = 0, l2 = 0, l3 = 0;
   for (int k = 0; k < TT; ++k) {
     const int t = t0 + k;
-    if (t >= T) break;
+    if (t >= T) {
+      l1 |= 1u << k; l2 |= 1u << k; l3 |= 1u << k;
+      continue;
+    }
     const bool s0 = m[t] != 0, s1 = t >= 1 && m[t - 1] != 0, s2 = t >= 2 && m[t - 2] != 0;
     r |= (unsigned)s0 << k;
     l1 |= (unsigned)(!s0) << k;
     l2 |= (unsigned)(!s0 && !s1) << k;
     l3 |= (unsigned)(!s0 && !s1 && !s2) << k;
+    if (nlag) nlag[(size_t)b * T + t] = (unsigned char)(s0 ? 0 : s1 ? 1 : s2 ? 2 : 3);
   }
   out[i] = make_uint4(r, l1, l2, l3);
 }
@@ -1014,6 +1022,13 @@ size_t forward_mfma_ws_bytes(int B, int T, int D, int nb) {
   return fwd_rec_bytes(B, T, nb) + ((w + 255) & ~(size_t)255);
 }
 
+hipError_t mfma::launch_reset_masks(const unsigned char *reset, uint4 *masks, unsigned char *nlag, int B, int T,
+                                    hipStream_t s) {
+  const int ntile = (T + TT - 1) / TT, n = B * ntile;
+  hipLaunchKernelGGL(reset_mask_kernel, dim3((n + 255) / 256), dim3(256), 0, s, reset, masks, nlag, B, T, ntile);
+  return hipGetLastError();
+}
+
 // ... and, for packed sequences, by the boundary masks
 size_t forward_mfma_mask_bytes(int B, int T) {
   const size_t n = (size_t)B * ((T + TT - 1) / TT) * sizeof(uint4);
@@ -1088,9 +1103,7 @@ hipError_t launch_forward_mfma(const Problem &p, hipStream_t s) {
   a.rmask = nullptr;
   if (p.reset) {
     uint4 *masks = (uint4 *)((char *)p.ws + forward_mfma_ws_bytes(p.B, p.T, p.D, p.nb));
-    const int n = p.B * a.ntile;
-    hipLaunchKernelGGL(reset_mask_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p.reset, masks, p.B, p.T, a.ntile);
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_reset_masks(p.reset, masks, nullptr, p.B, p.T, s);
     if (e != hipSuccess) return e;
     a.rmask = masks;
   }

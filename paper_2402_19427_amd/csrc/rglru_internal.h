@@ -146,6 +146,7 @@ hipError_t launch_decode_mfma(const Problem &p, hipStream_t s);
 // MFMA backward (bf16 storage, gate blocks of 256)
 bool backward_mfma_supported(const Problem &p, bool bf);
 size_t backward_mfma_ws_bytes(int B, int T, int D, int nb);
+size_t backward_mfma_packed_ws_bytes(int B, int T, int D, int nb);   // with the boundary masks of packed sequences (Problem.reset)
 size_t backward_mfma_flag_offset(int B, int T, int D, int nb);   // byte offset of the timeout flag
 hipError_t launch_backward_mfma(const Problem &p, hipStream_t s);
 

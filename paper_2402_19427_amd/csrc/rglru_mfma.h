@@ -174,6 +174,11 @@ void set_slice_cap(int cap);                              // process-wide upper 
 // clears zero_bytes (% 16 == 0) at `zero` with a fill kernel
 //   keep_status: the region starts with a status word, which stays if it reports an expired wait
 hipError_t launch_prep(void *zero, size_t zero_bytes, hipStream_t s, bool keep_status = false);
+// packed sequences: the document boundaries reset[B][T] as one uint4 of bit masks per (sequence,
+// tile of TT steps) - x: a document starts at the step, y / z / w: lag 1 / 2 / 3 of the step's
+// Conv1D stays inside its document - and, if nlag is not null, the largest such lag per step
+hipError_t launch_reset_masks(const unsigned char *reset, uint4 *masks, unsigned char *nlag, int B, int T,
+                              hipStream_t s);
 
 }  // namespace mfma
 }  // namespace rglru

@@ -174,7 +174,7 @@ def test_packed_calls_validation_and_workspace():
         R.rglru_backward_packed(*args, None, 0)
     assert e.value.code == R.ERR_WORKSPACE
     with pytest.raises(R.RglruError) as e:
-        R.rglru_workspace_status(s, R.OP_BACKWARD_PACKED, None)
+        R.rglru_workspace_status(s, R.OP_CG_BACKWARD, None)
     assert e.value.code == R.ERR_INVALID_ARG
 
 

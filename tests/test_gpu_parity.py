@@ -756,6 +756,9 @@ PACKED = [
     (1, 1500, 256, 1, "bf16", 200), # fused forward: 16 time slices, most tiles without a boundary
     (3, 300, 2560, 16, "bf16", 7),  # fused forward, blocks of 160 channels, a boundary in most tiles
     (33, 70, 1024, 4, "bf16", 30),  # fused forward, one workgroup per unit
+    (2, 130, 512, 2, "bf16", 3),    # a boundary every few steps, ragged last tile
+    (5, 70, 256, 1, "bf16", 8),     # tiles of the flattened rows straddle sequences (weight gradients)
+    (16, 4096, 256, 1, "bf16", 300),  # long rows: 16 workgroups x 16 time slices
 ]
 
 
