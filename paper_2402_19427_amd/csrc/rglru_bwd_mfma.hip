@@ -11,10 +11,9 @@
 //        dp_t  = -c softplus(-Lambda) dla_t r_t (1 - r_t)
 //        dq_t  = delta_t m_t g_t (1 - i_t)
 //        dxd_t = delta_t m_t i_t                 (the part of dx that bypasses the gates)
-//     and writes S dp, S dq in half precision (S: the power of two that brings max |dy| into
-//     [32, 64), found by a pass over dy beforehand; the dgrad and wgrad kernels undo it), dxd (24
-//     bits: sign, exponent, 15 mantissa bits; four steps of a channel packed in 12 bytes) plus
-//     per-channel sums for db_a, db_x, dLambda.
+//     and writes S dp, S dq, S dxd in half precision (S: the power of two that brings max |dy| into
+//     [32, 64), found by a pass over dy beforehand; the dgrad and wgrad kernels undo it; four
+//     steps of a channel of dxd packed in 8 bytes) plus per-channel sums for db_a, db_x, dLambda.
 //     Time slices of one sequence exchange tile aggregates (prod a, local eps) as tagged 8-byte
 //     records; a first sweep over the tile computes a_t and the aggregate, a second sweep the
 //     adjoints once the incoming eps is known.
@@ -59,8 +58,8 @@ struct BwdArgs {
   const unsigned short *wxf;              // W_x in fragment order (bwd_prep_kernel)
   unsigned short *dpo, *dqo;              // half precision [B][T][D]: S dp, S dq
   const float *sc;                        // sc[1] = S, sc[2] = 1 / S (launch_grad_scale)
-  unsigned char *dxo;                     // dxd, 24 bits per value (bf16 would break du: it sums four taps of it
-                                          // with cancellation)
+  unsigned char *dxo;                     // S dxd, half precision, [B][ceil(T/4)][D][4 steps] (bf16 would break du:
+                                          // it sums four taps of it with cancellation)
   float *part;                            // [B*G][3][D]: sums for db_a, db_x, dLambda
   const uint4 *rmask;                     // packed sequences: boundary bit masks per (sequence, tile), or NULL
 };
@@ -175,11 +174,11 @@ bwd_gates_kernel(BwdArgs a) {
   const __amdgpu_buffer_rsrc_t u_rsrc = rsrc(p.u), y_rsrc = rsrc(p.y_in), dy_rsrc = rsrc(p.dy);
   const __amdgpu_buffer_rsrc_t dyl_rsrc = rsrc(DYLO ? p.dy_lo : p.dy);
   const __amdgpu_buffer_rsrc_t dp_rsrc = rsrc(a.dpo), dq_rsrc = rsrc(a.dqo);
-  // dxd: [group of 4 steps][channel][12 bytes], four values of 24 bits (top three bytes of fp32)
-  const unsigned grp_bytes = (unsigned)D * 12, ngrp = (unsigned)(T + 3) / 4;
+  // S dxd: [group of 4 steps][channel][8 bytes], four half-precision values
+  const unsigned grp_bytes = (unsigned)D * 8, ngrp = (unsigned)(T + 3) / 4;
   const __amdgpu_buffer_rsrc_t dx_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       uniform_ptr(a.dxo + (size_t)b * ngrp * grp_bytes), 0, ngrp * grp_bytes, 0x00020000);
-  const unsigned dx_voff = (unsigned)d * 12 + (unsigned)hf * 4 * grp_bytes;  // channel, lane half
+  const unsigned dx_voff = (unsigned)d * 8 + (unsigned)hf * 4 * grp_bytes;  // channel, lane half
   const unsigned c_voff = (unsigned)dc * 2;                                   // channel pair
   const unsigned o_voff = (unsigned)d * 2 + (unsigned)hf * 16 * row_bytes;    // channel, lane half
   const unsigned *st32 =
@@ -481,7 +480,8 @@ bwd_gates_kernel(BwdArgs a) {
         const float hprev = fresh ? 0.f : (e > 0 ? yv[e - 1] : hfirst);
         const float dla = (delta * av) * fmaf(-av * gin, rs, hprev);   // delta a (h_{t-1} - a g/m)
         const float dg = delta * m;
-        dxv[e] = dg * iv;
+        const float dxu = dg * iv;
+        dxv[e] = dxu * S;
         const float dqu = dg * gin * (1.f - iv);
         dqv[e] = dqu * S;
         dpv[e] = (kdS * dla) * fmaf(-rv, rv, rv);   // S dp
@@ -507,16 +507,14 @@ bwd_gates_kernel(BwdArgs a) {
           }
         }
       }
-      // dxd: the four steps as 24-bit values (zero past the end of the sequence), 12 bytes per
-      // lane, 384 contiguous bytes per lane half
+      // S dxd: the four steps in half precision (zero past the end of the sequence), 8 bytes per
+      // lane, 256 contiguous bytes per lane half
       if (4 * q < nvalid) {
-        const unsigned r0 = __float_as_uint(dxv[0]) + 0x80u, r1 = __float_as_uint(dxv[1]) + 0x80u;
-        const unsigned r2 = __float_as_uint(dxv[2]) + 0x80u, r3 = __float_as_uint(dxv[3]) + 0x80u;
-        u32x3 w;
-        w[0] = __builtin_amdgcn_perm(r1, r0, 0x05030201u);
-        w[1] = __builtin_amdgcn_perm(r2, r1, 0x06050302u);
-        w[2] = __builtin_amdgcn_perm(r3, r2, 0x07060503u);
-        __builtin_amdgcn_raw_buffer_store_b96(w, dx_rsrc, dx_voff, (unsigned)(t0 / 4 + q) * grp_bytes, RGLRU_NT);
+        typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+        u32x2 w;
+        w[0] = pack_f16(dxv[0], dxv[1]);
+        w[1] = pack_f16(dxv[2], dxv[3]);
+        __builtin_amdgcn_raw_buffer_store_b64(w, dx_rsrc, dx_voff, (unsigned)(t0 / 4 + q) * grp_bytes, RGLRU_NT);
       }
     }
 
@@ -570,7 +568,7 @@ struct DgradArgs {
   int C, ntile;                            // contiguous time chunks per unit, tiles per sequence
   const unsigned short *dpo, *dqo;         // half precision [B][T][D]: S dp, S dq
   const float *sc;                         // sc[2] = 1 / S
-  const unsigned char *dxo;                // dxd [B][ceil(T/4)][D][12 bytes]
+  const unsigned char *dxo;                // S dxd, half precision [B][ceil(T/4)][D][4 steps]
   const unsigned short *wta, *wtx;         // transposed gate weights [nb][in k][out j], half precision
   float *part;                             // [B*C][5][D]: dconv_w[0..3], dconv_b partial sums
   const uint4 *rmask;                      // packed sequences: boundary bit masks per (sequence, tile), or NULL
@@ -696,29 +694,25 @@ bwd_dgrad_kernel(DgradArgs a) {
       __builtin_amdgcn_raw_ptr_buffer_load_lds(dq_rsrc, (__attribute__((address_space(3))) void *)(dst + D_A_TILE / 2), 16, a_voff, so, 0, RGLRU_NT);
     }
   };
-  // dxd of this lane's run (channel d, 16 consecutive steps): four groups of four 24-bit
-  // values, 12 bytes each; groups past the end of the sequence are out of range and read as zero
-  const unsigned grp_bytes = (unsigned)D * 12, ngrp = (unsigned)(T + 3) / 4;
+  // S dxd of this lane's run (channel d, 16 consecutive steps): four groups of four half-precision
+  // values, 8 bytes each; groups past the end of the sequence are out of range and read as zero
+  const unsigned grp_bytes = (unsigned)D * 8, ngrp = (unsigned)(T + 3) / 4;
   const __amdgpu_buffer_rsrc_t dx_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       uniform_ptr(a.dxo + (size_t)b * ngrp * grp_bytes), 0, ngrp * grp_bytes, 0x00020000);
-  const unsigned dx_voff = (unsigned)d * 12 + (unsigned)hf * 4 * grp_bytes;
-  u32x3 dxw[4];
+  const unsigned dx_voff = (unsigned)d * 8 + (unsigned)hf * 4 * grp_bytes;
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  u32x2 dxw[4];
   // (no branches around these loads, see load_u below; `ok` false pushes them all out of range)
   auto load_dxd = [&](int t0, bool ok) {
     const unsigned vo = ok ? dx_voff : 0x80000000u;
     const unsigned so = ok ? (unsigned)(t0 / 4) * grp_bytes : 0u;
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-      dxw[q] = __builtin_amdgcn_raw_buffer_load_b96(dx_rsrc, vo, so + (unsigned)q * grp_bytes, RGLRU_NT);
+      dxw[q] = __builtin_amdgcn_raw_buffer_load_b64(dx_rsrc, vo, so + (unsigned)q * grp_bytes, RGLRU_NT);
   };
-  auto dxd_at = [&](int r) __attribute__((always_inline)) {   // step r of the run, back in fp32
-    const u32x3 w = dxw[r >> 2];
-    const int e = r & 3;
-    const unsigned bits = e == 0 ? __builtin_amdgcn_perm(0u, w[0], 0x0201000cu)
-                        : e == 1 ? __builtin_amdgcn_perm(w[1], w[0], 0x0504030cu)
-                        : e == 2 ? __builtin_amdgcn_perm(w[2], w[1], 0x0403020cu)
-                                 : (w[2] & 0xffffff00u);
-    return __uint_as_float(bits);
+  auto dxd_at = [&](int r) __attribute__((always_inline)) {   // S dxd at step r of the run, in fp32
+    const unsigned pair = dxw[r >> 2][(r >> 1) & 1];
+    return (r & 1) ? f16_hi(pair) : f16_lo(pair);
   };
   // u rows t0-3 .. t0+31 (35 rows), 16 bytes (8 channels) per thread: rows lr, lr+16 and
   // (for lr < 3) lr+32
@@ -833,7 +827,7 @@ bwd_dgrad_kernel(DgradArgs a) {
       }
       float dx[19];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dx[r] = fmaf(acc0[r] + acc1[r], invS, dxd_at(r));
+      for (int r = 0; r < 16; ++r) dx[r] = (acc0[r] + acc1[r] + dxd_at(r)) * invS;
       // steps 16..18 of this lane's run: the other half's first three (lower lanes) or the
       // next tile's first three (upper lanes)
       const float s0v = __shfl_xor(dx[0], 32), s1v = __shfl_xor(dx[1], 32), s2v = __shfl_xor(dx[2], 32);
@@ -1312,7 +1306,7 @@ BwdPlan plan_backward(int B, int T, int D, int nb, int ncu, bool packed = false)
   size_t off = 0;
   q.off_dp = off; off += N2;
   q.off_dq = off; off += N2;
-  q.off_dx = off; off += al256((size_t)B * ((T + 3) / 4) * D * 12);
+  q.off_dx = off; off += al256((size_t)B * ((T + 3) / 4) * D * 8);
   q.off_wta = off; off += wbytes;
   q.off_wtx = off; off += wbytes;
   q.off_wxf = off; off += wbytes;
