@@ -308,3 +308,62 @@ def test_sixteen_blocks_at_width_5632_backward_full_size():
     assert gen.rel_err(dL_h[sl], acc["dLambda"]) < TOL
     assert gen.rel_err(dcw_h[:, sl], acc["dconv_w"]) < TOL
     assert np.isfinite(du_h).all() and np.isfinite(dWa_h).all() and np.isfinite(dWx_h).all()
+
+
+@pytest.mark.parametrize("name,backward,packed", [("C4", True, False), ("C1", True, False), ("C2", False, False),
+                                                  ("C4", True, True), ("C1", True, True), ("C2", False, True)])
+def test_every_unit_gives_the_same_result_on_replicated_inputs_full_size(name, backward, packed):
+    """Sampling (sequence, gate block) pairs would miss a mis-indexed block or a bad block-id
+    remapping on a pair that is not sampled. Here every pair gets the SAME data (inputs, weights,
+    states, upstream gradient replicated over sequences and blocks): all units then have to agree
+    bit for bit with unit (0, 0) - the arithmetic of a unit does not depend on where it sits - and
+    unit (0, 0) is checked against the oracle. Gradients that sum over the batch are B times one
+    sequence's contribution in every block alike."""
+    import torch
+    import paper_2402_19427_amd.runner as rn
+    w = gen.CONFIGS[name]
+    B, T, D, nb, bs = w.B, w.T, w.D, w.nb, w.bs
+    one = gen.make_inputs(1, T, bs, 1, act=w.act, seed=w.seed + 50, h0=True, dy=True, bias=True)
+    tile_c = lambda a: np.tile(a, (1,) * (a.ndim - 1) + (nb,))         # replicate along the channel axis
+    inp = dict(one)
+    inp["W_a"], inp["W_x"] = np.repeat(one["W_a"], nb, axis=0), np.repeat(one["W_x"], nb, axis=0)
+    for k in ("b_a", "b_x", "Lambda", "conv_w", "conv_b"):
+        inp[k] = tile_c(one[k])
+    dp = rn.DeviceProblem(inp, B, T, D, nb, w.act)
+    rep = lambda a, act: rn.to_device(a, act)[:, :, None, :].expand(B, T, nb, bs).reshape(B, T, D).contiguous()
+    u = rep(one["u"], w.act)
+    h0 = rn.to_device(one["h0"], "f32")[:, None, :].expand(B, nb, bs).reshape(B, D).contiguous()
+    reset = gen.make_resets(1, T, seed=w.seed, mean_len=300) if packed else None   # the same documents in every row
+    r_dev = torch.from_numpy(np.repeat(reset, B, axis=0)).cuda() if packed else None
+    y, hT, st = dp.forward_packed(u, r_dev, h0=h0) if packed else dp.forward(u, h0=h0)
+    units = lambda t: t.reshape(B, -1, nb, bs)
+    assert bool((units(y) == units(y)[:1, :, :1]).all()), "y differs between units"
+    assert bool((units(hT) == units(hT)[:1, :, :1]).all()) and bool((units(st) == units(st)[:1, :, :1]).all())
+    q = {k: (None if v is None else np.asarray(v, np.float64)) for k, v in one.items()}
+    par = (q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"], q["conv_w"])
+    oracle.set_threads(1)
+    y_ref, hT_ref, _ = oracle.forward(q["u"], *par, conv_b=q["conv_b"], h0=q["h0"], reset=reset)
+    assert gen.rel_err(rn.to_host(y[:1, :, :bs]), y_ref) < TOL
+    assert gen.rel_err(rn.to_host(hT[:1, :bs]), hT_ref) < TOL
+    if not backward:
+        return
+    dy = rep(one["dy"], w.act)
+    dhT = rn.to_device(one["dhT"], "f32")[:, None, :].expand(B, nb, bs).reshape(B, D).contiguous()
+    g = dp.backward_packed(u, r_dev, y, dy, h0=h0, dhT=dhT) if packed else dp.backward(u, y, dy, h0=h0, dhT=dhT)
+    for k in ("du", "dh0"):
+        assert bool((units(g[k]) == units(g[k])[:1, :, :1]).all()), k
+    for k in ("dW_a", "dW_x"):
+        assert bool((g[k] == g[k][:1]).all()), k
+    for k in ("db_a", "db_x", "dLambda", "dconv_b"):
+        v = g[k].reshape(nb, bs)
+        assert bool((v == v[:1]).all()), k
+    v = g["dconv_w"].reshape(4, nb, bs)
+    assert bool((v == v[:, :1]).all())
+    ref = oracle.backward(q["u"], *par, q["dy"], conv_b=q["conv_b"], h0=q["h0"], dhT=q["dhT"], reset=reset)
+    assert gen.rel_err(rn.to_host(g["du"][:1, :, :bs]), ref["du"]) < TOL
+    assert gen.rel_err(rn.to_host(g["dh0"][:1, :bs]), ref["dh0"]) < TOL
+    assert gen.rel_err(rn.to_host(g["dW_a"][0]), B * ref["dW_a"][0]) < TOL
+    assert gen.rel_err(rn.to_host(g["dW_x"][0]), B * ref["dW_x"][0]) < TOL
+    for k in ("db_a", "db_x", "dLambda", "dconv_b"):
+        assert gen.rel_err(rn.to_host(g[k][:bs]), B * ref[k]) < TOL, k
+    assert gen.rel_err(rn.to_host(g["dconv_w"][:, :bs]), B * ref["dconv_w"]) < TOL
