@@ -811,3 +811,38 @@ def test_packed_calls_without_a_mask_are_the_plain_calls():
     g, g2 = dp.backward(u, y, dy, h0=h0), dp.backward_packed(u, None, y, dy, h0=h0)
     for k in g:
         np.testing.assert_array_equal(rn.to_host(g[k]), rn.to_host(g2[k]))
+
+
+@pytest.mark.parametrize("B,T,D,nb,act", [(2, 37, 96, 3, "f32"), (3, 300, 512, 2, "bf16"), (8, 200, 2048, 8, "bf16")])
+def test_packed_calls_without_the_conv1d(B, T, D, nb, act):
+    """conv_width = 0 together with document boundaries: only the recurrence restarts (general
+    kernels, fused kernels with and without time slices)."""
+    import torch
+    import paper_2402_19427_amd as R
+    rn = runner()
+    inp = gen.make_inputs(B, T, D, nb, act=act, seed=B + T + D + 7, h0=True, dy=True, bias=True)
+    reset = gen.make_resets(B, T, seed=D, mean_len=20)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    par = R.make_params(dp.W_a, dp.W_x, dp.b_a, dp.b_x, dp.Lambda, None, None)
+    sh = R.make_shape(B, T, D, nb, R.BF16 if act == "bf16" else R.F32, conv_width=0)
+    u, h0, r_dev = rn.to_device(inp["u"], act), rn.to_device(inp["h0"], "f32"), torch.from_numpy(reset).cuda()
+    ws, n = dp.workspace(sh, R.OP_FORWARD_PACKED)
+    y, hT = dp.empty_act(B, T, D), dp.empty_f32(B, D)
+    R.rglru_forward_packed(sh, par, u, r_dev, h0, None, 0, y, hT, None, ws, n)
+    q = f64(inp)
+    y_ref, hT_ref = oracle.rglru(q["u"], q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"], h0=q["h0"], reset=reset)
+    assert gen.rel_err(rn.to_host(y), y_ref) < TOL[act]
+    assert gen.rel_err(rn.to_host(hT), hT_ref) < TOL[act]
+    wsb, nbytes = dp.workspace(sh, R.OP_BACKWARD_PACKED)
+    g = dp.alloc_grads()
+    pg = R.make_param_grads(g["dW_a"], g["dW_x"], g["db_a"], g["db_x"], g["dLambda"], None, None)
+    du, dh0 = dp.empty_act(B, T, D), dp.empty_f32(B, D)
+    R.rglru_backward_packed(sh, par, u, r_dev, h0, None, 0, y, rn.to_device(inp["dy"], act),
+                            rn.to_device(inp["dhT"], "f32"), du, dh0, pg, wsb, nbytes)
+    ident = np.zeros((4, D)); ident[0] = 1.0
+    ref = oracle.backward(q["u"], q["W_a"], q["W_x"], q["b_a"], q["b_x"], q["Lambda"], ident, q["dy"],
+                          h0=q["h0"], dhT=q["dhT"], reset=reset)
+    for k, got in (("du", du), ("dh0", dh0)):
+        assert gen.rel_err(rn.to_host(got), ref[k]) < TOL[act], k
+    for k in ("dW_a", "dW_x", "db_a", "db_x", "dLambda"):
+        assert gen.rel_err(rn.to_host(g[k]), ref[k]) < GRAD_TOL[act], k

@@ -136,3 +136,34 @@ def test_gpu_final_state_is_affine_in_the_initial_state(shape, seed, T, alpha):
     run = lambda h: rn.to_host(dp.forward(u, h0=rn.to_device(h, "f32"))[1]).astype(np.float64)   # hT: fp32, unrounded
     mix, e1, e2 = run(a * h1 + (1 - a) * h2), run(h1), run(h2)
     assert gen.rel_err(mix, float(a) * e1 + (1 - float(a)) * e2) < 2e-5
+
+
+@pytest.mark.gpu
+@settings(**CFG)
+@given(shape=st.sampled_from(SHAPES_GPU), seed=st.integers(0, 10 ** 6), T=st.integers(1, 150), data=st.data())
+def test_gpu_packed_calls_match_the_oracle_for_any_mask(shape, seed, T, data):
+    import torch
+    rn = runner()
+    B, D, nb, act = shape
+    density = data.draw(st.sampled_from([0.02, 0.2, 0.7]))
+    rng = np.random.default_rng(seed)
+    reset = (rng.random((B, T)) < density).astype(np.uint8)
+    inp = gen.make_inputs(B, T, D, nb, act=act, seed=seed, h0=True, state=True, bias=True, dy=True)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    pos0 = seed % 5
+    u, h0 = rn.to_device(inp["u"], act), rn.to_device(inp["h0"], "f32")
+    ring = rn.to_device(gen.ring_from_chrono(inp["state"], pos0), act)
+    r_dev = torch.from_numpy(reset).cuda()
+    y, hT, s_out = dp.forward_packed(u, r_dev, h0=h0, state_in=ring, pos0=pos0)
+    q = f64(inp)
+    kw = dict(conv_b=q["conv_b"], h0=q["h0"], state_in=q["state"], reset=reset)
+    y_ref, hT_ref, st_ref = oracle.forward(q["u"], *params(q), **kw)
+    tol = 1e-5 if act == "f32" else 2e-2
+    assert gen.rel_err(rn.to_host(y), y_ref) < tol
+    assert gen.rel_err(rn.to_host(hT), hT_ref) < tol
+    np.testing.assert_array_equal(gen.chrono_from_ring(rn.to_host(s_out), pos0 + T), st_ref)
+    g = dp.backward_packed(u, r_dev, y, rn.to_device(inp["dy"], act), h0=h0, state_in=ring, pos0=pos0,
+                           dhT=rn.to_device(inp["dhT"], "f32"))
+    ref = oracle.backward(q["u"], *params(q), q["dy"], dhT=q["dhT"], **kw)
+    for k in ("du", "dh0", "dW_a", "dW_x", "db_a", "db_x", "dLambda", "dconv_w", "dconv_b"):
+        assert gen.rel_err(rn.to_host(g[k]), ref[k]) < tol, k
