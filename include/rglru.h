@@ -174,7 +174,10 @@ int rglru_scan(const rglru_shape *shape, const void *a, const void *g, const flo
  *   conv_state_in / pos0 / conv_state_out  as in rglru_conv1d.
  *   y              [B][T][D] act, written (y_t = h_t, rounded to act).
  *   hT             [B][D] f32 state after the last step (unrounded), or NULL. May alias h0.
- *   workspace      >= rglru_workspace_bytes(shape, RGLRU_OP_FORWARD) bytes.
+ *   workspace      >= rglru_workspace_bytes(shape, RGLRU_OP_FORWARD) bytes. For shapes that run on
+ *                  the general kernels (fp32 storage, block sizes no matrix-core kernel takes)
+ *                  the scratch is optional: with it the forward runs in two passes parallel
+ *                  over time, without it (NULL or too small) in one pass serial in time.
  * A sequence may be fed in pieces: passing hT and conv_state_out of one call as h0 and
  * conv_state_in of the next (with pos0 advanced by T) gives the one-shot result.
  * T == 0 copies h0 to hT and the conv state through.

@@ -110,6 +110,15 @@ int check_workspace(const void *ws, size_t have, size_t need) {
   return RGLRU_OK;
 }
 
+// the forward on the general kernels can do without scratch (one pass, serial in time): a missing
+// or short workspace is not an error there, a misaligned one is
+bool forward_on_general_kernels(const rglru_shape *s);
+int check_forward_workspace(const rglru_shape *s, const void *ws, size_t have, size_t need) {
+  if (!forward_on_general_kernels(s)) return check_workspace(ws, have, need);
+  if (ws && !aligned(ws, 256)) return fail(RGLRU_ERR_INVALID_ARG, "workspace is not 256-byte aligned");
+  return RGLRU_OK;
+}
+
 int hip_fail(hipError_t e, const char *what) {
   return fail(RGLRU_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
@@ -201,7 +210,7 @@ size_t workspace_need(const rglru_shape *s, int op) {
     case RGLRU_OP_FORWARD_PACKED:   // the fused kernel's own scratch, then the boundary masks
       if (s->act_dtype == RGLRU_BF16 && forward_mfma_block(s->D / s->num_blocks) && s->T >= 1)
         return forward_mfma_ws_bytes(s->B, s->T, s->D, s->num_blocks) + forward_mfma_mask_bytes(s->B, s->T);
-      return 0;
+      return forward_generic_ws_bytes(s->B, s->T, s->D);
     case RGLRU_OP_BACKWARD_PACKED: {   // fused kernels for blocks of 256 channels (the general kernels remain the
                                        // fallback for loosely aligned pointers), the general kernels otherwise
       const size_t gen = backward_generic_ws_bytes(s->B, s->T, s->D, s->num_blocks);
@@ -222,10 +231,19 @@ size_t workspace_need(const rglru_shape *s, int op) {
       if (s->act_dtype == RGLRU_BF16 && forward_wide_block(s->D / s->num_blocks) && s->T >= 1 &&
           s->D % 256 == 0 && (size_t)s->B * s->T * s->D * 2 < ((size_t)1 << 31))
         return forward_wide_ws_bytes(s->B, s->T, s->D, s->num_blocks);
-      return 0;
+      return forward_generic_ws_bytes(s->B, s->T, s->D);   // the general kernels, two passes
     default:
       return 0;
   }
+}
+
+bool forward_on_general_kernels(const rglru_shape *s) {
+  const bool bf = s->act_dtype == RGLRU_BF16;
+  if (bf && forward_mfma_block(s->D / s->num_blocks) && s->T >= 1) return false;
+  if (bf && forward_wide_block(s->D / s->num_blocks) && s->T >= 1 && s->D % 256 == 0 &&
+      (size_t)s->B * s->T * s->D * 2 < ((size_t)1 << 31))
+    return false;
+  return true;
 }
 
 }  // namespace
@@ -381,6 +399,9 @@ int rglru_workspace_status(const rglru_shape *shape, int op, const void *workspa
   hipError_t e = hipStreamSynchronize((hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
   if (need == 0) return RGLRU_OK;   // no time slices, no waits
+  if ((op == RGLRU_OP_FORWARD || op == RGLRU_OP_FORWARD_MERGE || op == RGLRU_OP_FORWARD_PACKED) &&
+      forward_on_general_kernels(shape))
+    return RGLRU_OK;                // the general kernels never wait on each other (their scratch is optional)
   if (!workspace) return fail(RGLRU_ERR_INVALID_ARG, "workspace is NULL");
   size_t off = 0;   // forward and scan keep the flag in the first word
   if ((op == RGLRU_OP_FORWARD || op == RGLRU_OP_FORWARD_MERGE) &&
@@ -462,7 +483,7 @@ int rglru_forward(const rglru_shape *shape, const rglru_params *params, const vo
   CHECK(check_ptr(hT, "hT", 4, false));
   CHECK(check_ptr(conv_state_in, "conv_state_in", as, false));
   CHECK(check_ptr(conv_state_out, "conv_state_out", as, false));
-  CHECK(check_workspace(workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_FORWARD)));
+  CHECK(check_forward_workspace(shape, workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_FORWARD)));
 
   Problem q;
   memset(&q, 0, sizeof(q));
@@ -493,7 +514,7 @@ int rglru_forward_packed(const rglru_shape *shape, const rglru_params *params, c
   CHECK(check_ptr(hT, "hT", 4, false));
   CHECK(check_ptr(conv_state_in, "conv_state_in", as, false));
   CHECK(check_ptr(conv_state_out, "conv_state_out", as, false));
-  CHECK(check_workspace(workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_FORWARD_PACKED)));
+  CHECK(check_forward_workspace(shape, workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_FORWARD_PACKED)));
 
   Problem q;
   memset(&q, 0, sizeof(q));
@@ -725,7 +746,7 @@ int rglru_forward_merge(const rglru_shape *shape, const rglru_params *params, co
   CHECK(check_ptr(hT, "hT", 4, false));
   CHECK(check_ptr(conv_state_in, "conv_state_in", as, false));
   CHECK(check_ptr(conv_state_out, "conv_state_out", as, false));
-  CHECK(check_workspace(workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_FORWARD_MERGE)));
+  CHECK(check_forward_workspace(shape, workspace, workspace_bytes, workspace_need(shape, RGLRU_OP_FORWARD_MERGE)));
   if (shape->T > 0 && (out == y || out == branch || out == u))
     return fail(RGLRU_ERR_INVALID_ARG, "out must not alias y, branch or u");
 

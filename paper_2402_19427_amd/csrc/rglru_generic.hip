@@ -12,22 +12,22 @@ namespace rglru {
 // largest dynamic LDS any generic kernel asks for: two [GT][bs] tiles (dgrad)
 size_t generic_lds_bytes(int bs) { return (size_t)(2 * GT) * bs * sizeof(float); }
 
-// p[tt], q[tt] = b + W[g][j][:] . xs[tt][:] for the GT rows of an LDS tile xs[GT][bs]
-template <typename AT>
+// p[tt], q[tt] = b + W[g][j][:] . xs[tt][:] for the ROWS rows of an LDS tile xs[ROWS][bs]
+template <typename AT, int ROWS = GT>
 __device__ __forceinline__ void gate_rows(const Problem &p, int g, int j, const float *xs,
                                           float *pa, float *qa) {
   const int bs = p.bs, d = g * bs + j;
   const AT *wa = (const AT *)p.W_a + ((size_t)g * bs + j) * bs;
   const AT *wx = (const AT *)p.W_x + ((size_t)g * bs + j) * bs;
 #pragma unroll
-  for (int tt = 0; tt < GT; ++tt) {
+  for (int tt = 0; tt < ROWS; ++tt) {
     pa[tt] = p.b_a[d];
     qa[tt] = p.b_x[d];
   }
   for (int k = 0; k < bs; ++k) {
     const float a = ldf(wa, k), x = ldf(wx, k);
 #pragma unroll
-    for (int tt = 0; tt < GT; ++tt) {
+    for (int tt = 0; tt < ROWS; ++tt) {
       const float v = xs[tt * bs + k];
       pa[tt] = fmaf(a, v, pa[tt]);
       qa[tt] = fmaf(x, v, qa[tt]);
@@ -114,6 +114,70 @@ __global__ void __launch_bounds__(NTHREADS) forward_kernel(Problem p) {
   __syncthreads();
   if (p.hT)
     for (int j = tid; j < bs; j += NTHREADS) p.hT[(size_t)b * p.D + g * bs + j] = hc[j];
+}
+
+// The same forward in two passes, parallel over time, for callers that bring scratch memory:
+// (1) one workgroup per (gate block, sequence, tile of TG steps) forms the scan's coefficients
+//     a_t (zero at a document's first step) and b_t = sqrt(1 - a_t^2) i_t x_t for a chunk of the
+//     time axis; (2) one thread per (sequence, channel) runs eq. (4) over the chunk. The chunks
+//     follow each other on the stream, the state travels in `hstate`.
+constexpr int TG = 16;
+template <typename AT>
+__global__ void __launch_bounds__(NTHREADS) fwd_coeff_kernel(Problem p, int t_lo, int t_hi, float *A, float *Bv) {
+  extern __shared__ float smem[];
+  const int g = blockIdx.x, b = blockIdx.y, t0 = t_lo + blockIdx.z * TG, bs = p.bs, tid = threadIdx.x;
+  const int nt = min(TG, t_hi - t0), tc = t_hi - t_lo;
+  float *xs = smem;
+  for (int idx = tid; idx < TG * bs; idx += NTHREADS) {
+    const int tt = idx / bs, j = idx - tt * bs;
+    xs[idx] = tt < nt ? conv_at<AT>(p, b, t0 + tt, g * bs + j) : 0.f;
+  }
+  __syncthreads();
+  for (int j = tid; j < bs; j += NTHREADS) {
+    const int d = g * bs + j;
+    float pa[TG], qa[TG];
+    gate_rows<AT, TG>(p, g, j, xs, pa, qa);
+    const float neg_cs = -p.c * softplus_f(-p.Lambda[d]);
+#pragma unroll
+    for (int tt = 0; tt < TG; ++tt) {
+      if (tt < nt) {
+        const Gates gt = gate_math(pa[tt], qa[tt], neg_cs);
+        const size_t o = ((size_t)b * tc + (t0 - t_lo) + tt) * p.D + d;
+        A[o] = starts_document(p, b, t0 + tt) ? 0.f : gt.a;
+        Bv[o] = gt.m * (gt.i * xs[tt * bs + j]);
+      }
+    }
+  }
+}
+template <typename AT>
+__global__ void __launch_bounds__(NTHREADS) fwd_scan_kernel(Problem p, int t_lo, int t_hi, const float *A,
+                                                            const float *Bv, const float *h_in, float *h_out) {
+  const size_t n = (size_t)p.B * p.D, idx = (size_t)blockIdx.x * NTHREADS + threadIdx.x;
+  if (idx >= n) return;
+  const int b = (int)(idx / p.D), d = (int)(idx - (size_t)b * p.D), tc = t_hi - t_lo;
+  float h = h_in ? h_in[idx] : 0.f;
+  const float *a = A + (size_t)b * tc * p.D + d, *bv = Bv + (size_t)b * tc * p.D + d;
+  AT *y = (AT *)p.y + ((size_t)b * p.T + t_lo) * p.D + d;
+  // (the loads do not depend on the state: 32 steps of them are in flight at a time)
+  int t = 0;
+  for (; t + 32 <= tc; t += 32) {
+    float av[32], bb[32];
+#pragma unroll
+    for (int k = 0; k < 32; ++k) {
+      av[k] = a[(size_t)(t + k) * p.D];
+      bb[k] = bv[(size_t)(t + k) * p.D];
+    }
+#pragma unroll
+    for (int k = 0; k < 32; ++k) {
+      h = fmaf(av[k], h, bb[k]);   // eq. (4)
+      stf(y, (size_t)(t + k) * p.D, h);
+    }
+  }
+  for (; t < tc; ++t) {
+    h = fmaf(a[(size_t)t * p.D], h, bv[(size_t)t * p.D]);
+    stf(y, (size_t)t * p.D, h);
+  }
+  if (h_out) h_out[idx] = h;
 }
 
 // ---------------------------------------------------------------------------- decode
@@ -448,7 +512,46 @@ hipError_t launch_state_update(const Problem &p, bool bf, hipStream_t s) {
   return hipGetLastError();
 }
 
+// scratch of the two-pass forward: a 256-byte cell (left alone: the fused kernels keep their status
+// word there), the state between chunks, a_t and b_t of one chunk of steps (at most 4 MB each)
+static int fwd_chunk_steps(int B, int T, int D) {
+  long long tc = ((long long)4 << 20) / ((long long)4 * B * D);
+  tc = tc / TG * TG;
+  if (tc < TG) tc = TG;
+  return (int)(tc < T ? tc : T);
+}
+size_t forward_generic_ws_bytes(int B, int T, int D) {
+  if (T < 1) return 0;
+  const size_t chunk = align256((size_t)4 * B * D * fwd_chunk_steps(B, T, D));
+  return 256 + align256((size_t)4 * B * D) + 2 * chunk;
+}
+
+template <typename AT>
+static hipError_t forward_two_pass(const Problem &p, hipStream_t s) {
+  const int tcmax = fwd_chunk_steps(p.B, p.T, p.D);
+  const size_t chunk = align256((size_t)4 * p.B * p.D * tcmax), lds = (size_t)TG * p.bs * sizeof(float);
+  float *hstate = (float *)((char *)p.ws + 256);
+  float *A = (float *)((char *)p.ws + 256 + align256((size_t)4 * p.B * p.D)), *Bv = (float *)((char *)A + chunk);
+  hipError_t e = allow_lds(fwd_coeff_kernel<AT>, lds);
+  if (e != hipSuccess) return e;
+  const int sblocks = (int)(((size_t)p.B * p.D + NTHREADS - 1) / NTHREADS);
+  for (int t_lo = 0; t_lo < p.T; t_lo += tcmax) {
+    const int t_hi = t_lo + tcmax < p.T ? t_lo + tcmax : p.T, ntile = (t_hi - t_lo + TG - 1) / TG;
+    if (ntile > 65535) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(fwd_coeff_kernel<AT>, dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds, s, p, t_lo, t_hi, A, Bv);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const bool last = t_hi == p.T;
+    hipLaunchKernelGGL(fwd_scan_kernel<AT>, dim3(sblocks), dim3(NTHREADS), 0, s, p, t_lo, t_hi, A, Bv,
+                       t_lo == 0 ? p.h0 : hstate, last ? p.hT : hstate);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
 hipError_t launch_forward_generic(const Problem &p, bool bf, hipStream_t s) {
+  // with enough scratch and more than one tile of steps: the two-pass version, parallel over time
+  if (p.ws && p.T > GT && p.ws_bytes >= forward_generic_ws_bytes(p.B, p.T, p.D) && ((uintptr_t)p.ws % 256) == 0)
+    return bf ? forward_two_pass<bf16>(p, s) : forward_two_pass<float>(p, s);
   const size_t lds = generic_lds_bytes(p.bs);
   hipError_t e = bf ? allow_lds(forward_kernel<bf16>, lds) : allow_lds(forward_kernel<float>, lds);
   if (e != hipSuccess) return e;

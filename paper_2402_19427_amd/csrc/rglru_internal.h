@@ -100,7 +100,8 @@ struct KernelTimer {
 // Launchers. Each returns hipSuccess or the launch error. `bf` selects bf16 act+weights.
 hipError_t launch_conv1d_generic(const Problem &p, bool bf, void *x_out, hipStream_t s);
 hipError_t launch_state_update(const Problem &p, bool bf, hipStream_t s);
-hipError_t launch_forward_generic(const Problem &p, bool bf, hipStream_t s);
+hipError_t launch_forward_generic(const Problem &p, bool bf, hipStream_t s);   // (two passes, parallel over time, if p.ws holds forward_generic_ws_bytes)
+size_t forward_generic_ws_bytes(int B, int T, int D);
 hipError_t launch_decode_generic(const Problem &p, bool bf, hipStream_t s);
 hipError_t launch_backward_generic(const Problem &p, bool bf, hipStream_t s);
 size_t backward_generic_ws_bytes(int B, int T, int D, int nb);
