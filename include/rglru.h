@@ -87,6 +87,7 @@ extern "C" {
 #define RGLRU_OP_FORWARD_PACKED 7
 #define RGLRU_OP_BACKWARD_PACKED 8
 #define RGLRU_OP_CG_BACKWARD 9
+#define RGLRU_OP_CG_FORWARD 10
 
 typedef struct rglru_shape {
   int32_t B;          /* sequences                                  (>= 1)                 */
@@ -326,13 +327,15 @@ typedef struct rglru_cg_param_grads {
  * returns dtheta; it takes no y: the gradient of the decay multiplies the state's adjoint by
  * conj(h~_{t-1}), which needs more than the 8 bits of a bf16 y, so the backward recomputes the
  * states in fp32 into its workspace). They run on shape-generic kernels (fp32 arithmetic for either storage
- * type, one workgroup per (sequence, gate block)); no kernel waits on another. The forward and
- * the decode step need no workspace, the backward needs
- * rglru_workspace_bytes(shape, RGLRU_OP_CG_BACKWARD) bytes. hs may be at most 1024.
+ * type); no kernel waits on another. The forward's workspace is optional (NULL, or
+ * rglru_workspace_bytes(shape, RGLRU_OP_CG_FORWARD) bytes: with it the forward runs in two passes
+ * parallel over time, without it in one pass, a workgroup per (sequence, gate block)); the decode
+ * step needs none; the backward needs rglru_workspace_bytes(shape, RGLRU_OP_CG_BACKWARD) bytes.
+ * hs may be at most 1024.
  */
 int rglru_cg_forward(const rglru_shape *shape, const rglru_cg_params *params, const void *u,
                      const float *h0, const void *conv_state_in, int64_t pos0, void *y, float *hT,
-                     void *conv_state_out, void *stream);
+                     void *conv_state_out, void *workspace, size_t workspace_bytes, void *stream);
 int rglru_cg_decode_step(const rglru_shape *shape, const rglru_cg_params *params, const void *u_t,
                          float *h, void *conv_state, int64_t pos, void *y_t, void *stream);
 int rglru_cg_backward(const rglru_shape *shape, const rglru_cg_params *params, const void *u,

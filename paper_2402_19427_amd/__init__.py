@@ -10,7 +10,7 @@ import importlib
 
 _EXPORTS = (
     "BF16", "F32", "OK", "ERR_HIP", "ERR_TIMEOUT", "rglru_workspace_status", "rglru_set_max_time_slices", "ERR_INVALID_ARG", "ERR_UNSUPPORTED", "ERR_WORKSPACE",
-    "OP_CG_BACKWARD", "CgParams", "CgParamGrads", "make_cg_params", "make_cg_param_grads",
+    "OP_CG_BACKWARD", "OP_CG_FORWARD", "CgParams", "CgParamGrads", "make_cg_params", "make_cg_param_grads",
     "rglru_cg_forward", "rglru_cg_decode_step", "rglru_cg_backward",
     "OP_FORWARD_PACKED", "OP_BACKWARD_PACKED", "rglru_forward_packed", "rglru_backward_packed",
     "OP_BACKWARD", "OP_BACKWARD_MERGE", "OP_FORWARD_MERGE", "MERGE_GELU_TANH", "MERGE_SEPARATE", "rglru_forward_merge", "rglru_decode_step_merge",

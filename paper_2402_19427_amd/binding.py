@@ -15,7 +15,7 @@ F32, BF16 = 0, 1
 OP_CONV1D, OP_FORWARD, OP_DECODE, OP_BACKWARD, OP_SCAN = 0, 1, 2, 3, 4
 OP_FORWARD_MERGE, OP_BACKWARD_MERGE = 5, 6
 OP_FORWARD_PACKED, OP_BACKWARD_PACKED = 7, 8
-OP_CG_BACKWARD = 9
+OP_CG_BACKWARD, OP_CG_FORWARD = 9, 10
 MERGE_GELU_TANH, MERGE_SEPARATE = 1, 2
 SCAN_LOG_A, SCAN_NO_INPUT_SCALE, SCAN_ADJOINT = 1, 2, 4
 STATIC_SCRATCH_BYTES = 16 << 20
@@ -77,7 +77,7 @@ def _load():
     lib.rglru_backward_packed.argtypes = [sp, pp, vp, vp, vp, vp, i64, vp, vp, vp, vp, vp, gp, vp, sz, vp]
     lib.rglru_backward_packed.restype = ctypes.c_int
     cp, cgp = ctypes.POINTER(CgParams), ctypes.POINTER(CgParamGrads)
-    lib.rglru_cg_forward.argtypes = [sp, cp, vp, vp, vp, i64, vp, vp, vp, vp]
+    lib.rglru_cg_forward.argtypes = [sp, cp, vp, vp, vp, i64, vp, vp, vp, vp, sz, vp]
     lib.rglru_cg_decode_step.argtypes = [sp, cp, vp, vp, vp, i64, vp, vp]
     lib.rglru_cg_backward.argtypes = [sp, cp, vp, vp, vp, i64, vp, vp, vp, vp, cgp, vp, sz, vp]
     for f in (lib.rglru_cg_forward, lib.rglru_cg_decode_step, lib.rglru_cg_backward):
@@ -245,9 +245,11 @@ def rglru_backward_packed(shape, params, u, reset, h0, conv_state_in, pos0, y, d
                                       workspace_bytes, _stream(stream)))
 
 
-def rglru_cg_forward(shape, params, u, h0, conv_state_in, pos0, y, hT, conv_state_out, stream=None):
+def rglru_cg_forward(shape, params, u, h0, conv_state_in, pos0, y, hT, conv_state_out, workspace=None,
+                     workspace_bytes=0, stream=None):
     _check(_lib.rglru_cg_forward(_ref(shape), _ref(params), _addr(u), _addr(h0), _addr(conv_state_in),
-                                 pos0, _addr(y), _addr(hT), _addr(conv_state_out), _stream(stream)))
+                                 pos0, _addr(y), _addr(hT), _addr(conv_state_out), _addr(workspace),
+                                 workspace_bytes, _stream(stream)))
 
 
 def rglru_cg_decode_step(shape, params, u_t, h, conv_state, pos, y_t, stream=None):

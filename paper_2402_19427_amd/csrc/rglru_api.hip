@@ -222,6 +222,8 @@ size_t workspace_need(const rglru_shape *s, int op) {
     }
     case RGLRU_OP_CG_BACKWARD:
       return cg_backward_ws_bytes(s->B, s->T, s->D, s->num_blocks);
+    case RGLRU_OP_CG_FORWARD:   // optional: the two-pass forward of the general kernels
+      return forward_generic_ws_bytes(s->B, s->T, s->D);
     case RGLRU_OP_BACKWARD_MERGE:   // dy (+ dy_lo) between the merge adjoint and the backward, then the backward's own
       return merge_dy_bytes(s) + workspace_need(s, RGLRU_OP_BACKWARD);
     case RGLRU_OP_FORWARD_MERGE:
@@ -375,14 +377,14 @@ int rglru_set_max_time_slices(int max_slices) {
 }
 
 size_t rglru_workspace_bytes(const rglru_shape *shape, int op) {
-  if (op < RGLRU_OP_CONV1D || op > RGLRU_OP_CG_BACKWARD) return 0;
+  if (op < RGLRU_OP_CONV1D || op > RGLRU_OP_CG_FORWARD) return 0;
   char keep[sizeof(g_err)];
   memcpy(keep, g_err, sizeof(g_err));
   const bool blocks = op != RGLRU_OP_CONV1D && op != RGLRU_OP_SCAN;
   const bool bwd = op == RGLRU_OP_BACKWARD || op == RGLRU_OP_BACKWARD_MERGE || op == RGLRU_OP_BACKWARD_PACKED ||
                    op == RGLRU_OP_CG_BACKWARD;
   int rc = check_shape(shape, blocks, op != RGLRU_OP_DECODE, bwd ? 1 : 0);
-  if (rc == RGLRU_OK && op == RGLRU_OP_CG_BACKWARD) rc = check_cg_shape(shape);
+  if (rc == RGLRU_OK && (op == RGLRU_OP_CG_BACKWARD || op == RGLRU_OP_CG_FORWARD)) rc = check_cg_shape(shape);
   memcpy(g_err, keep, sizeof(g_err));  // a size query does not disturb the error string
   if (rc != RGLRU_OK) return 0;
   return workspace_need(shape, op);
@@ -857,9 +859,10 @@ int rglru_backward_merge(const rglru_shape *shape, const rglru_params *params, c
 
 int rglru_cg_forward(const rglru_shape *shape, const rglru_cg_params *params, const void *u,
                      const float *h0, const void *conv_state_in, int64_t pos0, void *y, float *hT,
-                     void *conv_state_out, void *stream) {
+                     void *conv_state_out, void *workspace, size_t workspace_bytes, void *stream) {
   CHECK(check_shape(shape, true, true, 0));
   CHECK(check_cg_shape(shape));
+  if (workspace && !aligned(workspace, 256)) return fail(RGLRU_ERR_INVALID_ARG, "workspace is not 256-byte aligned");
   CHECK(check_cg_params(shape, params));
   const size_t as = act_size(shape);
   if (pos0 < 0) return fail(RGLRU_ERR_INVALID_ARG, "pos0 must be >= 0");
@@ -875,6 +878,7 @@ int rglru_cg_forward(const rglru_shape *shape, const rglru_cg_params *params, co
   q.pos0 = pos0; q.u = u; q.h0 = h0; q.state_in = conv_state_in;
   q.y = y; q.hT = hT; q.state_out = conv_state_out;
   if (shape->conv_width == 0) q.state_in = q.state_out = nullptr;
+  q.ws = workspace; q.ws_bytes = workspace ? workspace_bytes : 0;
   const bool bf = shape->act_dtype == RGLRU_BF16;
   hipError_t e = launch_cg_forward(q, bf, (hipStream_t)stream);
   // the new ring state is written after the last read of the incoming one (they may alias)

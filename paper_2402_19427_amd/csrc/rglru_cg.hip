@@ -47,31 +47,31 @@ __device__ __forceinline__ CGates cg_gate_math(float p, float q, float neg_cs, f
 }
 
 // the x tile of gate block g: xs[tt][k] for the GT steps from t0 (zero past the sequence's end)
-template <typename AT>
+template <typename AT, int ROWS = GT>
 __device__ __forceinline__ void cg_load_tile(const Problem &p, int g, int b, int t0, int nt, float *xs) {
   const int hs = p.bs, H = p.D / 2;
-  for (int idx = threadIdx.x; idx < GT * 2 * hs; idx += NTHREADS) {
+  for (int idx = threadIdx.x; idx < ROWS * 2 * hs; idx += NTHREADS) {
     const int tt = idx / (2 * hs), k = idx - tt * 2 * hs;
     xs[idx] = tt < nt ? conv_at<AT>(p, b, t0 + tt, cg_channel(g, hs, H, k)) : 0.f;
   }
 }
 
 // pre-activations of output j of block g for the GT rows of the tile: b + W[g][j][:] . xs[tt][:]
-template <typename AT>
+template <typename AT, int ROWS = GT>
 __device__ __forceinline__ void cg_gate_rows(const Problem &p, int g, int j, const float *xs, float *pa,
                                              float *qa) {
   const int hs = p.bs, nin = 2 * hs, h = g * hs + j;
   const AT *wa = (const AT *)p.W_a + (size_t)h * nin;
   const AT *wx = (const AT *)p.W_x + (size_t)h * nin;
 #pragma unroll
-  for (int tt = 0; tt < GT; ++tt) {
+  for (int tt = 0; tt < ROWS; ++tt) {
     pa[tt] = p.b_a[h];
     qa[tt] = p.b_x[h];
   }
   for (int k = 0; k < nin; ++k) {
     const float a = ldf(wa, k), x = ldf(wx, k);
 #pragma unroll
-    for (int tt = 0; tt < GT; ++tt) {
+    for (int tt = 0; tt < ROWS; ++tt) {
       const float v = xs[tt * nin + k];
       pa[tt] = fmaf(a, v, pa[tt]);
       qa[tt] = fmaf(x, v, qa[tt]);
@@ -125,6 +125,79 @@ __global__ void __launch_bounds__(NTHREADS) cg_forward_kernel(Problem p) {
       p.hT[(size_t)b * p.D + g * hs + j] = hc[j];
       p.hT[(size_t)b * p.D + H + g * hs + j] = hc[hs + j];
     }
+}
+
+// The forward in two passes, parallel over time, where scratch is at hand: (1) a workgroup per
+// (gate block, sequence, 16 steps) writes the scan's coefficients a~_t and b~_t = sqrt(1 - |a~_t|^2)
+// i_t x~_t for a chunk of steps as (re, im) pairs [B][steps][H]; (2) a thread per (sequence,
+// complex channel) runs the recurrence over the chunk. OT: storage type of y.
+constexpr int CTG = 16;
+template <typename AT>
+__global__ void __launch_bounds__(NTHREADS) cg_coeff_kernel(Problem p, int t_lo, int t_hi, float2 *A, float2 *Bv) {
+  extern __shared__ float smem[];
+  const int g = blockIdx.x, b = blockIdx.y, t0 = t_lo + blockIdx.z * CTG, hs = p.bs, H = p.D / 2;
+  const int nt = min(CTG, t_hi - t0), tc = t_hi - t_lo;
+  float *xs = smem;
+  cg_load_tile<AT, CTG>(p, g, b, t0, nt, xs);
+  __syncthreads();
+  for (int j = threadIdx.x; j < hs; j += NTHREADS) {
+    const int h = g * hs + j;
+    float pa[CTG], qa[CTG];
+    cg_gate_rows<AT, CTG>(p, g, j, xs, pa, qa);
+    const float neg_cs = -p.c * softplus_f(-p.Lambda[h]), c_theta = p.c * p.theta[h];
+#pragma unroll
+    for (int tt = 0; tt < CTG; ++tt) {
+      if (tt < nt) {
+        const CGates gt = cg_gate_math(pa[tt], qa[tt], neg_cs, c_theta);
+        const float gain = gt.m * gt.i;
+        const size_t o = ((size_t)b * tc + (t0 - t_lo) + tt) * H + h;
+        A[o] = make_float2(gt.ar, gt.ai);
+        Bv[o] = make_float2(gain * xs[tt * 2 * hs + j], gain * xs[tt * 2 * hs + hs + j]);
+      }
+    }
+  }
+}
+template <typename OT>
+__global__ void __launch_bounds__(NTHREADS) cg_scan_kernel(Problem p, int t_lo, int t_hi, const float2 *A,
+                                                           const float2 *Bv, const float *h_in, float *h_out) {
+  const int H = p.D / 2;
+  const size_t n = (size_t)p.B * H, idx = (size_t)blockIdx.x * NTHREADS + threadIdx.x;
+  if (idx >= n) return;
+  const int b = (int)(idx / H), h = (int)(idx - (size_t)b * H), tc = t_hi - t_lo;
+  float hr = h_in ? h_in[(size_t)b * p.D + h] : 0.f, hi = h_in ? h_in[(size_t)b * p.D + H + h] : 0.f;
+  const float2 *a = A + (size_t)b * tc * H + h, *bv = Bv + (size_t)b * tc * H + h;
+  OT *y = (OT *)p.y + ((size_t)b * p.T + t_lo) * p.D + h;
+  int t = 0;
+  for (; t + 16 <= tc; t += 16) {   // (the loads do not depend on the state: 16 steps of them in flight)
+    float2 av[16], bb[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      av[k] = a[(size_t)(t + k) * H];
+      bb[k] = bv[(size_t)(t + k) * H];
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const float nr = fmaf(av[k].x, hr, fmaf(-av[k].y, hi, bb[k].x));
+      const float ni = fmaf(av[k].x, hi, fmaf(av[k].y, hr, bb[k].y));
+      hr = nr;
+      hi = ni;
+      stf(y, (size_t)(t + k) * p.D, hr);
+      stf(y, (size_t)(t + k) * p.D + H, hi);
+    }
+  }
+  for (; t < tc; ++t) {
+    const float2 av = a[(size_t)t * H], bb = bv[(size_t)t * H];
+    const float nr = fmaf(av.x, hr, fmaf(-av.y, hi, bb.x));
+    const float ni = fmaf(av.x, hi, fmaf(av.y, hr, bb.y));
+    hr = nr;
+    hi = ni;
+    stf(y, (size_t)t * p.D, hr);
+    stf(y, (size_t)t * p.D + H, hi);
+  }
+  if (h_out) {
+    h_out[(size_t)b * p.D + h] = hr;
+    h_out[(size_t)b * p.D + H + h] = hi;
+  }
 }
 
 // ---------------------------------------------------------------------------- decode
@@ -373,6 +446,28 @@ hipError_t allow_lds(K kernel, size_t bytes) {
   return hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
+// the forward over steps [0, T) in chunks of at most `tcmax` steps: coefficients into A / Bv, then the
+// recurrence; `hstate` carries the state between chunks; y of storage type OT
+template <typename AT, typename OT>
+hipError_t cg_forward_two_pass(const Problem &p, int tcmax, float2 *A, float2 *Bv, float *hstate, hipStream_t s) {
+  const int hs = p.bs, H = p.D / 2;
+  const size_t lds = (size_t)CTG * 2 * hs * sizeof(float);
+  hipError_t e = allow_lds(cg_coeff_kernel<AT>, lds);
+  if (e != hipSuccess) return e;
+  const int sblocks = (int)(((size_t)p.B * H + NTHREADS - 1) / NTHREADS);
+  for (int t_lo = 0; t_lo < p.T; t_lo += tcmax) {
+    const int t_hi = t_lo + tcmax < p.T ? t_lo + tcmax : p.T, ntile = (t_hi - t_lo + CTG - 1) / CTG;
+    if (ntile > 65535) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(cg_coeff_kernel<AT>, dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds, s, p, t_lo, t_hi, A, Bv);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const bool last = t_hi == p.T;
+    hipLaunchKernelGGL(cg_scan_kernel<OT>, dim3(sblocks), dim3(NTHREADS), 0, s, p, t_lo, t_hi, A, Bv,
+                       t_lo == 0 ? p.h0 : hstate, last ? p.hT : hstate);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
 template <typename AT>
 hipError_t cg_backward_t(const Problem &p, hipStream_t s) {
   const BwdWs w = carve_bwd_ws(p.ws, p.B, p.T, p.D);
@@ -383,14 +478,11 @@ hipError_t cg_backward_t(const Problem &p, hipStream_t s) {
   const int ntile = (p.T + GT - 1) / GT;
   if (ntile > 65535 || p.B > 65535) return hipErrorInvalidConfiguration;
   float *hs32 = (float *)((char *)p.ws + backward_generic_ws_bytes(p.B, p.T, p.D, p.nb));
-  {
+  {   // (the dp and dq arrays, not yet in use, hold the scan's coefficients of the whole sequence)
     Problem f = p;
     f.y = hs32;
     f.hT = nullptr;
-    const size_t ldsf = (size_t)(GT * 2 * hs + 2 * hs) * sizeof(float);
-    if ((e = allow_lds(cg_forward_kernel<AT, float>, ldsf)) != hipSuccess) return e;
-    hipLaunchKernelGGL((cg_forward_kernel<AT, float>), dim3(p.nb, p.B), dim3(NTHREADS), ldsf, s, f);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = cg_forward_two_pass<AT, float>(f, p.T, (float2 *)w.dp, (float2 *)w.dq, nullptr, s)) != hipSuccess) return e;
   }
   hipLaunchKernelGGL(cg_bwd_pointwise_kernel<AT>, dim3(p.nb, p.B), dim3(NTHREADS), lds1, s, p, w, hs32);
   if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -415,6 +507,20 @@ size_t cg_backward_ws_bytes(int B, int T, int D, int nb) {
 }
 
 hipError_t launch_cg_forward(const Problem &p, bool bf, hipStream_t s) {
+  // with the optional scratch (the real layer's layout: a 256-byte cell, the state between chunks,
+  // two coefficient arrays for a chunk of steps) and more than one tile of steps: two passes
+  if (p.ws && p.T > GT && ((uintptr_t)p.ws % 256) == 0 && p.ws_bytes >= forward_generic_ws_bytes(p.B, p.T, p.D)) {
+    const size_t state = ((size_t)4 * p.B * p.D + 255) & ~(size_t)255;
+    const size_t chunk = (p.ws_bytes - 256 - state) / 2 & ~(size_t)255;
+    int tcmax = (int)(chunk / ((size_t)4 * p.B * p.D)) / CTG * CTG;
+    if (tcmax > p.T) tcmax = p.T;
+    if (tcmax >= CTG || tcmax == p.T) {
+      float *hstate = (float *)((char *)p.ws + 256);
+      float2 *A = (float2 *)((char *)p.ws + 256 + state), *Bv = (float2 *)((char *)A + chunk);
+      return bf ? cg_forward_two_pass<bf16, bf16>(p, tcmax, A, Bv, hstate, s)
+                : cg_forward_two_pass<float, float>(p, tcmax, A, Bv, hstate, s);
+    }
+  }
   const size_t lds = (size_t)(GT * 2 * p.bs + 2 * p.bs) * sizeof(float);
   hipError_t e = bf ? allow_lds(cg_forward_kernel<bf16>, lds) : allow_lds(cg_forward_kernel<float>, lds);
   if (e != hipSuccess) return e;

@@ -513,9 +513,9 @@ hipError_t launch_state_update(const Problem &p, bool bf, hipStream_t s) {
 }
 
 // scratch of the two-pass forward: a 256-byte cell (left alone: the fused kernels keep their status
-// word there), the state between chunks, a_t and b_t of one chunk of steps (at most 4 MB each)
+// word there), the state between chunks, a_t and b_t of one chunk of steps (at most 64 MB each)
 static int fwd_chunk_steps(int B, int T, int D) {
-  long long tc = ((long long)4 << 20) / ((long long)4 * B * D);
+  long long tc = ((long long)64 << 20) / ((long long)4 * B * D);
   tc = tc / TG * TG;
   if (tc < TG) tc = TG;
   return (int)(tc < T ? tc : T);

@@ -226,12 +226,16 @@ class CgDeviceProblem:
         return R.make_shape(self.B if B is None else B, self.T if T is None else T, self.D, self.nb,
                             self.dt, c=self.c, conv_width=4 if self.conv else 0)
 
-    def forward(self, u, h0=None, state_in=None, pos0=0, stream=None):
+    def forward(self, u, h0=None, state_in=None, pos0=0, stream=None, scratch=True):
+        """scratch: bring the optional workspace (two passes parallel over time) or not (one pass)."""
         B, T, D = u.shape
         y = torch.empty(B, T, D, dtype=self.tdtype, device=self.device)
         hT = torch.empty(B, D, dtype=torch.float32, device=self.device)
         st = torch.empty(B, 3, D, dtype=self.tdtype, device=self.device) if self.conv else None
-        R.rglru_cg_forward(self.shape(T=T, B=B), self.params, u, h0, state_in, pos0, y, hT, st, stream)
+        sh = self.shape(T=T, B=B)
+        n = R.rglru_workspace_bytes(sh, R.OP_CG_FORWARD) if scratch else 0
+        ws = torch.empty(n, dtype=torch.uint8, device=self.device) if n else None
+        R.rglru_cg_forward(sh, self.params, u, h0, state_in, pos0, y, hT, st, ws, n, stream)
         return y, hT, st
 
     def decode_step(self, u_t, h, conv_state, pos, stream=None):

@@ -188,12 +188,12 @@ def test_cg_calls_validation_and_workspace():
     for bad, what in ((R.make_shape(2, 8, 63, 1, R.F32), "even"), (R.make_shape(2, 8, 64, 3, R.F32), "multiple"),
                       (R.make_shape(2, 8, 8192, 1, R.BF16), "exceeds")):
         with pytest.raises(R.RglruError) as e:
-            R.rglru_cg_forward(bad, cg, FAKE, None, None, 0, FAKE, None, None)
+            R.rglru_cg_forward(bad, cg, FAKE, None, None, 0, FAKE, None, None, None, 0)
         assert what in str(e.value)
         assert R.rglru_workspace_bytes(bad, R.OP_CG_BACKWARD) == 0
     no_theta = R.make_cg_params(FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE)
     with pytest.raises(R.RglruError) as e:
-        R.rglru_cg_forward(s, no_theta, FAKE, None, None, 0, FAKE, None, None)
+        R.rglru_cg_forward(s, no_theta, FAKE, None, None, 0, FAKE, None, None, None, 0)
     assert e.value.code == R.ERR_INVALID_ARG and "theta" in str(e.value)
     with pytest.raises(R.RglruError) as e:
         R.rglru_cg_decode_step(s, cg, FAKE, None, FAKE, 0, FAKE)
@@ -346,4 +346,4 @@ def test_workspace_sizes_for_narrower_gate_blocks():
     # scratch, capped (a chunk of the time axis at a time), and optional
     for sh in (R.make_shape(8, 2048, 2560, 16, R.F32), R.make_shape(8, 2048, 2560, 64, R.BF16)):   # (bs 40)
         n = R.rglru_workspace_bytes(sh, R.OP_FORWARD)
-        assert 0 < n <= 256 + 8 * 2560 * 4 + 2 * (4 << 20) + 1024 and n % 256 == 0
+        assert 0 < n <= 256 + 8 * 2560 * 4 + 2 * (64 << 20) + 1024 and n % 256 == 0

@@ -45,6 +45,10 @@ def test_cg_forward_and_backward_match_oracle(B, T, D, nb, act, conv):
     u, h0 = rn.to_device(inp["u"], act), rn.to_device(inp["h0"], "f32")
     ring = rn.to_device(gen.ring_from_chrono(inp["state"], pos0), act) if conv else None
     y, hT, st = dp.forward(u, h0=h0, state_in=ring, pos0=pos0)
+    # the same call without the optional scratch (one pass instead of two): the same arithmetic per step
+    y1, hT1, _ = dp.forward(u, h0=h0, state_in=ring, pos0=pos0, scratch=False)
+    assert gen.rel_err(rn.to_host(y1), rn.to_host(y)) < (2e-6 if act == "f32" else 1e-2)
+    assert gen.rel_err(rn.to_host(hT1), rn.to_host(hT)) < 2e-6
     q = f64(inp)
     kw = dict(conv_w=q["conv_w"], conv_b=q["conv_b"], state_in=q["state"]) if conv else {}
     y_ref, hT_ref, st_ref = oracle.cg_forward(q["u"], *params(q), h0=q["h0"], **kw)
