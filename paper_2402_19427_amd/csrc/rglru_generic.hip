@@ -241,84 +241,99 @@ size_t backward_generic_ws_bytes(int B, int T, int D, int nb) {
   return 4 * align256(N * 4) + align256((size_t)B * 3 * D * 4) + align256(nchunk * 5 * D * 4);
 }
 
-// Pass 1: one workgroup per (gate block, sequence), walking the sequence backwards in tiles:
-// recompute x and the gates, run delta_t = dy_t + a_{t+1} delta_{t+1}, form the pointwise
-// adjoints, and store x, dp, dq and the direct part of dx for the later contractions.
+// Pass 1a, parallel over time: one workgroup per (gate block, sequence, tile of TG steps) recomputes
+// the Conv1D and the gate pre-activations and parks x, p, q (fp32) where the later passes expect
+// x, dp, dq.
 template <typename AT>
-__global__ void __launch_bounds__(NTHREADS) bwd_pointwise_kernel(Problem p, BwdWs w) {
+__global__ void __launch_bounds__(NTHREADS) bwd_preact_kernel(Problem p, BwdWs w) {
   extern __shared__ float smem[];
-  const int g = blockIdx.x, b = blockIdx.y, bs = p.bs, tid = threadIdx.x;
-  float *xs = smem;                 // [GT][bs]
-  float *carry = smem + GT * bs;    // [bs]  a_{t+1} * delta_{t+1}
-  float *sums = carry + bs;         // [3][bs] running db_a, db_x, dLambda of this sequence
-  float *comps = sums + 3 * bs;     // [3][bs] their compensation terms
-  for (int j = tid; j < bs; j += NTHREADS) {
-    carry[j] = p.dhT ? p.dhT[(size_t)b * p.D + g * bs + j] : 0.f;
-    sums[j] = sums[bs + j] = sums[2 * bs + j] = 0.f;
-    comps[j] = comps[bs + j] = comps[2 * bs + j] = 0.f;
-  }
-  const int ntile = (p.T + GT - 1) / GT;
-  for (int tile = ntile - 1; tile >= 0; --tile) {
-    const int t0 = tile * GT, nt = min(GT, p.T - t0);
-    __syncthreads();
-    for (int idx = tid; idx < GT * bs; idx += NTHREADS) {
-      const int tt = idx / bs, j = idx - tt * bs;
-      xs[idx] = tt < nt ? conv_at<AT>(p, b, t0 + tt, g * bs + j) : 0.f;
-    }
-    __syncthreads();
-    for (int j = tid; j < bs; j += NTHREADS) {
-      const int d = g * bs + j;
-      float pa[GT], qa[GT];
-      gate_rows<AT>(p, g, j, xs, pa, qa);
-      const float neg_cs = -p.c * softplus_f(-p.Lambda[d]);
-      // 1 - sigmoid(Lambda) = sigmoid(-Lambda), evaluated without cancellation
-      const float lam_scale = p.c * sigmoid_f(-p.Lambda[d]);
-      float cy = carry[j], s_ba = 0.f, s_bx = 0.f, s_lam = 0.f;
-#pragma unroll
-      for (int tt = GT - 1; tt >= 0; --tt) {
-        if (tt < nt) {
-          const int t = t0 + tt;
-          const size_t o = ((size_t)b * p.T + t) * p.D + d;
-          const Gates gt = gate_math(pa[tt], qa[tt], neg_cs);
-          const float x = xs[tt * bs + j];
-          const float delta = ldf((const AT *)p.dy, o) + (p.dy_lo ? ldf((const AT *)p.dy_lo, o) : 0.f) + cy;
-          const bool fresh = starts_document(p, b, t);   // h_{t-1} := 0, nothing flows further back
-          const float hprev = fresh ? 0.f
-                              : t > 0 ? ldf((const AT *)p.y_in, o - p.D)
-                                      : (p.h0 ? p.h0[(size_t)b * p.D + d] : 0.f);
-          const float gin = gt.i * x;
-          // d m / d a = -a / m; the term vanishes with the gate in the limit m -> 0
-          const float corr = gt.m > 0.f ? gt.a * gin / gt.m : 0.f;
-          const float dla = delta * gt.a * (hprev - corr);
-          const float dg = delta * gt.m;
-          const float di = dg * x;
-          const float dr = neg_cs * dla;
-          const float dpv = dr * gt.r * gt.rc;
-          const float dqv = di * gt.i * gt.ic;
-          s_lam = fmaf(dla * gt.r, lam_scale, s_lam);
-          s_ba += dpv;
-          s_bx += dqv;
-          w.x[o] = x;
-          w.dp[o] = dpv;
-          w.dq[o] = dqv;
-          w.dx[o] = dg * gt.i;
-          cy = fresh ? 0.f : gt.a * delta;
-        }
-      }
-      carry[j] = cy;
-      comp_add(sums[j], comps[j], s_ba);
-      comp_add(sums[bs + j], comps[bs + j], s_bx);
-      comp_add(sums[2 * bs + j], comps[2 * bs + j], s_lam);
-    }
+  const int g = blockIdx.x, b = blockIdx.y, t0 = blockIdx.z * TG, bs = p.bs, tid = threadIdx.x;
+  const int nt = min(TG, p.T - t0);
+  float *xs = smem;
+  for (int idx = tid; idx < TG * bs; idx += NTHREADS) {
+    const int tt = idx / bs, j = idx - tt * bs;
+    xs[idx] = tt < nt ? conv_at<AT>(p, b, t0 + tt, g * bs + j) : 0.f;
   }
   __syncthreads();
   for (int j = tid; j < bs; j += NTHREADS) {
     const int d = g * bs + j;
-    if (p.dh0) p.dh0[(size_t)b * p.D + d] = carry[j];
-    w.partA[((size_t)b * 3 + 0) * p.D + d] = sums[j];
-    w.partA[((size_t)b * 3 + 1) * p.D + d] = sums[bs + j];
-    w.partA[((size_t)b * 3 + 2) * p.D + d] = sums[2 * bs + j];
+    float pa[TG], qa[TG];
+    gate_rows<AT, TG>(p, g, j, xs, pa, qa);
+#pragma unroll
+    for (int tt = 0; tt < TG; ++tt) {
+      if (tt < nt) {
+        const size_t o = ((size_t)b * p.T + t0 + tt) * p.D + d;
+        w.x[o] = xs[tt * bs + j];
+        w.dp[o] = pa[tt];
+        w.dq[o] = qa[tt];
+      }
+    }
   }
+}
+
+// Pass 1b: one thread per (sequence, channel) walks the sequence backwards: gates from the parked
+// pre-activations, delta_t = dy_t + a_{t+1} delta_{t+1}, the pointwise adjoints; dp, dq replace
+// the pre-activations in place, the direct part of dx goes to its array, and the per-sequence
+// sums for db_a, db_x, dLambda are kept with compensation (eight steps as plain sums at a time).
+template <typename AT>
+__global__ void __launch_bounds__(NTHREADS) bwd_chain_kernel(Problem p, BwdWs w) {
+  const size_t n = (size_t)p.B * p.D, idx = (size_t)blockIdx.x * NTHREADS + threadIdx.x;
+  if (idx >= n) return;
+  const int b = (int)(idx / p.D), d = (int)(idx - (size_t)b * p.D);
+  const float neg_cs = -p.c * softplus_f(-p.Lambda[d]);
+  const float lam_scale = p.c * sigmoid_f(-p.Lambda[d]);   // 1 - sigmoid(Lambda) without cancellation
+  float cy = p.dhT ? p.dhT[idx] : 0.f;
+  float sum[3] = {0.f, 0.f, 0.f}, comp[3] = {0.f, 0.f, 0.f};
+  const size_t base = (size_t)b * p.T * p.D + d;
+  for (int t1 = p.T; t1 > 0; t1 -= 8) {   // steps t1-1 down to max(t1-8, 0)
+    const int t_lo = t1 > 8 ? t1 - 8 : 0, cnt = t1 - t_lo;
+    float pv[8], qv[8], xv[8], dyv[8], hp[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {   // the loads of a group do not depend on the chain: all in flight at once
+      if (k < cnt) {
+        const int t = t1 - 1 - k;
+        const size_t o = base + (size_t)t * p.D;
+        pv[k] = w.dp[o];
+        qv[k] = w.dq[o];
+        xv[k] = w.x[o];
+        dyv[k] = ldf((const AT *)p.dy, o) + (p.dy_lo ? ldf((const AT *)p.dy_lo, o) : 0.f);
+        hp[k] = t > 0 ? ldf((const AT *)p.y_in, o - p.D) : (p.h0 ? p.h0[idx] : 0.f);
+      }
+    }
+    float s_ba = 0.f, s_bx = 0.f, s_lam = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      if (k < cnt) {
+        const int t = t1 - 1 - k;
+        const size_t o = base + (size_t)t * p.D;
+        const bool fresh = starts_document(p, b, t);   // h_{t-1} := 0, nothing flows further back
+        const Gates gt = gate_math(pv[k], qv[k], neg_cs);
+        const float delta = dyv[k] + cy;
+        const float hprev = fresh ? 0.f : hp[k];
+        const float gin = gt.i * xv[k];
+        // d m / d a = -a / m; the term vanishes with the gate in the limit m -> 0
+        const float corr = gt.m > 0.f ? gt.a * gin / gt.m : 0.f;
+        const float dla = delta * gt.a * (hprev - corr);
+        const float dg = delta * gt.m;
+        const float dpv = neg_cs * dla * gt.r * gt.rc;
+        const float dqv = dg * xv[k] * gt.i * gt.ic;
+        s_lam = fmaf(dla * gt.r, lam_scale, s_lam);
+        s_ba += dpv;
+        s_bx += dqv;
+        w.dp[o] = dpv;
+        w.dq[o] = dqv;
+        w.dx[o] = dg * gt.i;
+        cy = fresh ? 0.f : gt.a * delta;
+      }
+    }
+    comp_add(sum[0], comp[0], s_ba);
+    comp_add(sum[1], comp[1], s_bx);
+    comp_add(sum[2], comp[2], s_lam);
+  }
+  if (p.dh0) p.dh0[idx] = cy;
+  w.partA[((size_t)b * 3 + 0) * p.D + d] = sum[0];
+  w.partA[((size_t)b * 3 + 1) * p.D + d] = sum[1];
+  w.partA[((size_t)b * 3 + 2) * p.D + d] = sum[2];
 }
 
 // Pass 2: dx[t][k] += sum_j W_a[g][j][k] dp[t][j] + W_x[g][j][k] dq[t][j]
@@ -580,7 +595,7 @@ static hipError_t backward_generic_t(const Problem &p, hipStream_t s, bool with_
                                      bool with_dgrad = true, bool with_wgrad = true, bool with_du = true) {
   const BwdWs w = carve_bwd_ws(p.ws, p.B, p.T, p.D);
   const size_t lds = generic_lds_bytes(p.bs);
-  hipError_t e = allow_lds(bwd_pointwise_kernel<AT>, lds);
+  hipError_t e = allow_lds(bwd_preact_kernel<AT>, (size_t)TG * p.bs * sizeof(float));
   if (e != hipSuccess) return e;
   e = allow_lds(bwd_dgrad_kernel<AT>, lds);
   if (e != hipSuccess) return e;
@@ -588,7 +603,13 @@ static hipError_t backward_generic_t(const Problem &p, hipStream_t s, bool with_
   const int dblocks = (p.D + NTHREADS - 1) / NTHREADS;
 
   if (with_pointwise) {
-    hipLaunchKernelGGL(bwd_pointwise_kernel<AT>, dim3(p.nb, p.B), dim3(NTHREADS), lds, s, p, w);
+    const int nt16 = (p.T + TG - 1) / TG;
+    if (nt16 > 65535 || p.B > 65535) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(bwd_preact_kernel<AT>, dim3(p.nb, p.B, nt16), dim3(NTHREADS), (size_t)TG * p.bs * sizeof(float), s,
+                       p, w);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(bwd_chain_kernel<AT>, dim3((unsigned)(((size_t)p.B * p.D + NTHREADS - 1) / NTHREADS)),
+                       dim3(NTHREADS), 0, s, p, w);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   const RowOuts gate_outs = {{p.g.db_a, p.g.db_x, p.g.dLambda, nullptr, nullptr}};
