@@ -131,9 +131,12 @@ __global__ void __launch_bounds__(NTHREADS) cg_forward_kernel(Problem p) {
 // (gate block, sequence, 16 steps) writes the scan's coefficients a~_t and b~_t = sqrt(1 - |a~_t|^2)
 // i_t x~_t for a chunk of steps as (re, im) pairs [B][steps][H]; (2) a thread per (sequence,
 // complex channel) runs the recurrence over the chunk. OT: storage type of y.
+// KEEP (the backward's recomputation): x goes to `xk` [B][T][D] and the gate pre-activations to
+// `pq` ([B*T][H] of p, then [B*T][H] of q) as well.
 constexpr int CTG = 16;
-template <typename AT>
-__global__ void __launch_bounds__(NTHREADS) cg_coeff_kernel(Problem p, int t_lo, int t_hi, float2 *A, float2 *Bv) {
+template <typename AT, bool KEEP = false>
+__global__ void __launch_bounds__(NTHREADS) cg_coeff_kernel(Problem p, int t_lo, int t_hi, float2 *A, float2 *Bv,
+                                                            float *xk = nullptr, float *pq = nullptr) {
   extern __shared__ float smem[];
   const int g = blockIdx.x, b = blockIdx.y, t0 = t_lo + blockIdx.z * CTG, hs = p.bs, H = p.D / 2;
   const int nt = min(CTG, t_hi - t0), tc = t_hi - t_lo;
@@ -153,6 +156,13 @@ __global__ void __launch_bounds__(NTHREADS) cg_coeff_kernel(Problem p, int t_lo,
         const size_t o = ((size_t)b * tc + (t0 - t_lo) + tt) * H + h;
         A[o] = make_float2(gt.ar, gt.ai);
         Bv[o] = make_float2(gain * xs[tt * 2 * hs + j], gain * xs[tt * 2 * hs + hs + j]);
+        if (KEEP) {
+          const size_t row = (size_t)b * p.T + t0 + tt;
+          xk[row * p.D + h] = xs[tt * 2 * hs + j];
+          xk[row * p.D + H + h] = xs[tt * 2 * hs + hs + j];
+          pq[row * H + h] = pa[tt];
+          pq[((size_t)p.B * p.T + row) * H + h] = qa[tt];
+        }
       }
     }
   }
@@ -260,99 +270,90 @@ __global__ void __launch_bounds__(NTHREADS) cg_decode_kernel(Problem p) {
 // Pass 0 is the forward kernel once more, writing the states h~_t in fp32 into the workspace
 // (`hs32`): the gradient of the decay multiplies delta~_t by conj(h~_{t-1}), and with the
 // phases in play the 8 bits of a bf16 y would leave dW_a some 3e-2 off.
-// Pass 1: one workgroup per (gate block, sequence), backwards in time. The adjoint of the state
-// is complex, delta~_t = dy~_t + conj(a~_{t+1}) delta~_{t+1} (a complex number standing for the
-// pair of derivatives with respect to the real and the imaginary part). Stores x, the gate
-// adjoints dp, dq ([B*T][H]) and the direct part of dx for the later contractions.
+// Pass 1: one thread per (sequence, complex channel) walks backwards in time on what pass 0 parked
+// (x, the pre-activations, the states). The adjoint of the state is complex, delta~_t = dy~_t +
+// conj(a~_{t+1}) delta~_{t+1} (a complex number standing for the pair of derivatives with respect
+// to the real and the imaginary part). Writes the gate adjoints dp, dq ([B*T][H]), the direct
+// part of dx, and per-sequence sums for db_a, db_x, dLambda, dtheta (compensated, four steps as
+// plain sums at a time). The loads of four steps are in flight at once.
 template <typename AT>
-__global__ void __launch_bounds__(NTHREADS) cg_bwd_pointwise_kernel(Problem p, BwdWs w, const float *hs32) {
-  extern __shared__ float smem[];
-  const int g = blockIdx.x, b = blockIdx.y, hs = p.bs, H = p.D / 2, tid = threadIdx.x;
-  float *xs = smem;                    // [GT][2 hs]
-  float *carry = smem + GT * 2 * hs;   // [2][hs]  conj(a~_{t+1}) delta~_{t+1}
-  float *sums = carry + 2 * hs;        // [4][hs]  running db_a, db_x, dLambda, dtheta of this sequence
-  float *comps = sums + 4 * hs;        // [4][hs]  their compensation terms
-  for (int j = tid; j < hs; j += NTHREADS) {
-    carry[j] = p.dhT ? p.dhT[(size_t)b * p.D + g * hs + j] : 0.f;
-    carry[hs + j] = p.dhT ? p.dhT[(size_t)b * p.D + H + g * hs + j] : 0.f;
-    for (int q = 0; q < 4; ++q) sums[q * hs + j] = comps[q * hs + j] = 0.f;
-  }
-  const int ntile = (p.T + GT - 1) / GT;
-  for (int tile = ntile - 1; tile >= 0; --tile) {
-    const int t0 = tile * GT, nt = min(GT, p.T - t0);
-    __syncthreads();
-    cg_load_tile<AT>(p, g, b, t0, nt, xs);
-    __syncthreads();
-    for (int j = tid; j < hs; j += NTHREADS) {
-      const int h = g * hs + j;
-      float pa[GT], qa[GT];
-      cg_gate_rows<AT>(p, g, j, xs, pa, qa);
-      const float theta = p.theta[h];
-      const float log_sig = -softplus_f(-p.Lambda[h]);         // log sigmoid(Lambda)
-      const float neg_cs = p.c * log_sig, c_theta = p.c * theta;
-      const float lam_scale = p.c * sigmoid_f(-p.Lambda[h]);   // c d log sigmoid(Lambda) / d Lambda
-      float cr = carry[j], ci = carry[hs + j];
-      float s_ba = 0.f, s_bx = 0.f, s_lam = 0.f, s_th = 0.f;
+__global__ void __launch_bounds__(NTHREADS) cg_bwd_chain_kernel(Problem p, BwdWs w, const float *hs32, const float *pq) {
+  const int H = p.D / 2;
+  const size_t n = (size_t)p.B * H, idx = (size_t)blockIdx.x * NTHREADS + threadIdx.x;
+  if (idx >= n) return;
+  const int b = (int)(idx / H), h = (int)(idx - (size_t)b * H);
+  const float theta = p.theta[h];
+  const float log_sig = -softplus_f(-p.Lambda[h]);         // log sigmoid(Lambda)
+  const float neg_cs = p.c * log_sig, c_theta = p.c * theta;
+  const float lam_scale = p.c * sigmoid_f(-p.Lambda[h]);   // c d log sigmoid(Lambda) / d Lambda
+  float cr = p.dhT ? p.dhT[(size_t)b * p.D + h] : 0.f, ci = p.dhT ? p.dhT[(size_t)b * p.D + H + h] : 0.f;
+  float sum[4] = {0.f, 0.f, 0.f, 0.f}, comp[4] = {0.f, 0.f, 0.f, 0.f};
+  const size_t rows = (size_t)p.B * p.T;
+  for (int t1 = p.T; t1 > 0; t1 -= 4) {   // steps t1-1 down to max(t1-4, 0)
+    const int t_lo = t1 > 4 ? t1 - 4 : 0, cnt = t1 - t_lo;
+    float pv[4], qv[4], xr[4], xi[4], yr[4], yi[4], pr[4], pi[4];
 #pragma unroll
-      for (int tt = GT - 1; tt >= 0; --tt) {
-        if (tt < nt) {
-          const int t = t0 + tt;
-          const size_t o = ((size_t)b * p.T + t) * p.D;
-          const CGates gt = cg_gate_math(pa[tt], qa[tt], neg_cs, c_theta);
-          const float xr = xs[tt * 2 * hs + j], xi = xs[tt * 2 * hs + hs + j];
-          const float dr_ = ldf((const AT *)p.dy, o + h) + cr, di_ = ldf((const AT *)p.dy, o + H + h) + ci;
-          float pr, pi;   // h~_{t-1}
-          if (t > 0) {
-            pr = hs32[o - p.D + h];
-            pi = hs32[o - p.D + H + h];
-          } else {
-            pr = p.h0 ? p.h0[(size_t)b * p.D + h] : 0.f;
-            pi = p.h0 ? p.h0[(size_t)b * p.D + H + h] : 0.f;
-          }
-          // G = delta~ conj(h~_{t-1}) = (dL/dRe a~_t, dL/dIm a~_t)
-          const float Gr = fmaf(dr_, pr, di_ * pi), Gi = fmaf(di_, pr, -dr_ * pi);
-          const float s = fmaf(dr_, xr, di_ * xi);   // dL/d(m_t i_t)
-          // a~_t = exp(lm + i ph): d/d lm = a~_t, d/d ph = i a~_t;  m_t = sqrt(1 - e^{2 lm})
-          float dlm = fmaf(Gr, gt.ar, Gi * gt.ai);
-          const float dph = fmaf(Gi, gt.ar, -Gr * gt.ai);
-          if (gt.m > 0.f) dlm -= s * gt.i * gt.mod2 / gt.m;
-          const float dgate_r = p.c * fmaf(dlm, log_sig, dph * theta);
-          const float dpv = dgate_r * gt.r * gt.rc;
-          const float dqv = s * gt.m * gt.i * gt.ic;
-          s_lam = fmaf(dlm * gt.r, lam_scale, s_lam);
-          s_th = fmaf(dph * gt.r, p.c, s_th);
-          s_ba += dpv;
-          s_bx += dqv;
-          const size_t oh = ((size_t)b * p.T + t) * H + h;
-          w.dp[oh] = dpv;
-          w.dq[oh] = dqv;
-          w.x[o + h] = xr;
-          w.x[o + H + h] = xi;
-          const float gain = gt.m * gt.i;
-          w.dx[o + h] = dr_ * gain;
-          w.dx[o + H + h] = di_ * gain;
-          // conj(a~_t) delta~_t
-          cr = fmaf(gt.ar, dr_, gt.ai * di_);
-          ci = fmaf(gt.ar, di_, -gt.ai * dr_);
+    for (int k = 0; k < 4; ++k) {
+      if (k < cnt) {
+        const int t = t1 - 1 - k;
+        const size_t row = (size_t)b * p.T + t, o = row * p.D;
+        pv[k] = pq[row * H + h];
+        qv[k] = pq[(rows + row) * H + h];
+        xr[k] = w.x[o + h];
+        xi[k] = w.x[o + H + h];
+        yr[k] = ldf((const AT *)p.dy, o + h);
+        yi[k] = ldf((const AT *)p.dy, o + H + h);
+        if (t > 0) {
+          pr[k] = hs32[o - p.D + h];
+          pi[k] = hs32[o - p.D + H + h];
+        } else {
+          pr[k] = p.h0 ? p.h0[(size_t)b * p.D + h] : 0.f;
+          pi[k] = p.h0 ? p.h0[(size_t)b * p.D + H + h] : 0.f;
         }
       }
-      carry[j] = cr;
-      carry[hs + j] = ci;
-      comp_add(sums[j], comps[j], s_ba);
-      comp_add(sums[hs + j], comps[hs + j], s_bx);
-      comp_add(sums[2 * hs + j], comps[2 * hs + j], s_lam);
-      comp_add(sums[3 * hs + j], comps[3 * hs + j], s_th);
     }
-  }
-  __syncthreads();
-  for (int j = tid; j < hs; j += NTHREADS) {
-    const int h = g * hs + j;
-    if (p.dh0) {
-      p.dh0[(size_t)b * p.D + h] = carry[j];
-      p.dh0[(size_t)b * p.D + H + h] = carry[hs + j];
+    float s_ba = 0.f, s_bx = 0.f, s_lam = 0.f, s_th = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (k < cnt) {
+        const int t = t1 - 1 - k;
+        const size_t row = (size_t)b * p.T + t, o = row * p.D;
+        const CGates gt = cg_gate_math(pv[k], qv[k], neg_cs, c_theta);
+        const float dr_ = yr[k] + cr, di_ = yi[k] + ci;
+        // G = delta~ conj(h~_{t-1}) = (dL/dRe a~_t, dL/dIm a~_t)
+        const float Gr = fmaf(dr_, pr[k], di_ * pi[k]), Gi = fmaf(di_, pr[k], -dr_ * pi[k]);
+        const float s = fmaf(dr_, xr[k], di_ * xi[k]);   // dL/d(m_t i_t)
+        // a~_t = exp(lm + i ph): d/d lm = a~_t, d/d ph = i a~_t;  m_t = sqrt(1 - e^{2 lm})
+        float dlm = fmaf(Gr, gt.ar, Gi * gt.ai);
+        const float dph = fmaf(Gi, gt.ar, -Gr * gt.ai);
+        if (gt.m > 0.f) dlm -= s * gt.i * gt.mod2 / gt.m;
+        const float dgate_r = p.c * fmaf(dlm, log_sig, dph * theta);
+        const float dpv = dgate_r * gt.r * gt.rc;
+        const float dqv = s * gt.m * gt.i * gt.ic;
+        s_lam = fmaf(dlm * gt.r, lam_scale, s_lam);
+        s_th = fmaf(dph * gt.r, p.c, s_th);
+        s_ba += dpv;
+        s_bx += dqv;
+        w.dp[row * H + h] = dpv;
+        w.dq[row * H + h] = dqv;
+        const float gain = gt.m * gt.i;
+        w.dx[o + h] = dr_ * gain;
+        w.dx[o + H + h] = di_ * gain;
+        // conj(a~_t) delta~_t
+        cr = fmaf(gt.ar, dr_, gt.ai * di_);
+        ci = fmaf(gt.ar, di_, -gt.ai * dr_);
+      }
     }
-    for (int q = 0; q < 4; ++q) w.partA[((size_t)b * 4 + q) * H + h] = sums[q * hs + j];
+    comp_add(sum[0], comp[0], s_ba);
+    comp_add(sum[1], comp[1], s_bx);
+    comp_add(sum[2], comp[2], s_lam);
+    comp_add(sum[3], comp[3], s_th);
   }
+  if (p.dh0) {
+    p.dh0[(size_t)b * p.D + h] = cr;
+    p.dh0[(size_t)b * p.D + H + h] = ci;
+  }
+  for (int q = 0; q < 4; ++q) w.partA[((size_t)b * 4 + q) * H + h] = sum[q];
 }
 
 // Pass 2: dx[t][chan(k)] += sum_j W_a[g][j][k] dp[t][j] + W_x[g][j][k] dq[t][j]
@@ -448,17 +449,19 @@ hipError_t allow_lds(K kernel, size_t bytes) {
 
 // the forward over steps [0, T) in chunks of at most `tcmax` steps: coefficients into A / Bv, then the
 // recurrence; `hstate` carries the state between chunks; y of storage type OT
-template <typename AT, typename OT>
-hipError_t cg_forward_two_pass(const Problem &p, int tcmax, float2 *A, float2 *Bv, float *hstate, hipStream_t s) {
+template <typename AT, typename OT, bool KEEP = false>
+hipError_t cg_forward_two_pass(const Problem &p, int tcmax, float2 *A, float2 *Bv, float *hstate, hipStream_t s,
+                               float *xk = nullptr, float *pq = nullptr) {
   const int hs = p.bs, H = p.D / 2;
   const size_t lds = (size_t)CTG * 2 * hs * sizeof(float);
-  hipError_t e = allow_lds(cg_coeff_kernel<AT>, lds);
+  hipError_t e = allow_lds(cg_coeff_kernel<AT, KEEP>, lds);
   if (e != hipSuccess) return e;
   const int sblocks = (int)(((size_t)p.B * H + NTHREADS - 1) / NTHREADS);
   for (int t_lo = 0; t_lo < p.T; t_lo += tcmax) {
     const int t_hi = t_lo + tcmax < p.T ? t_lo + tcmax : p.T, ntile = (t_hi - t_lo + CTG - 1) / CTG;
     if (ntile > 65535) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL(cg_coeff_kernel<AT>, dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds, s, p, t_lo, t_hi, A, Bv);
+    hipLaunchKernelGGL((cg_coeff_kernel<AT, KEEP>), dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds, s, p, t_lo, t_hi, A, Bv,
+                       xk, pq);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     const bool last = t_hi == p.T;
     hipLaunchKernelGGL(cg_scan_kernel<OT>, dim3(sblocks), dim3(NTHREADS), 0, s, p, t_lo, t_hi, A, Bv,
@@ -472,22 +475,27 @@ template <typename AT>
 hipError_t cg_backward_t(const Problem &p, hipStream_t s) {
   const BwdWs w = carve_bwd_ws(p.ws, p.B, p.T, p.D);
   const int hs = p.bs, H = p.D / 2;
-  const size_t lds1 = (size_t)(GT * 2 * hs + 10 * hs) * sizeof(float), lds2 = (size_t)(2 * GT * hs) * sizeof(float);
-  hipError_t e = allow_lds(cg_bwd_pointwise_kernel<AT>, lds1);
-  if (e != hipSuccess) return e;
+  const size_t lds2 = (size_t)(2 * GT * hs) * sizeof(float);
+  hipError_t e;
   const int ntile = (p.T + GT - 1) / GT;
   if (ntile > 65535 || p.B > 65535) return hipErrorInvalidConfiguration;
+  const size_t nbytes = ((size_t)p.B * p.T * p.D * sizeof(float) + 255) & ~(size_t)255;
   float *hs32 = (float *)((char *)p.ws + backward_generic_ws_bytes(p.B, p.T, p.D, p.nb));
-  {   // (the dp and dq arrays, not yet in use, hold the scan's coefficients of the whole sequence)
+  float *pq = (float *)((char *)hs32 + nbytes);
+  {   // pass 0: the forward once more, in two passes (the dp and dq arrays, not yet in use, hold the scan's
+      // coefficients of the whole sequence); it parks x and the pre-activations for pass 1
     Problem f = p;
     f.y = hs32;
     f.hT = nullptr;
-    if ((e = cg_forward_two_pass<AT, float>(f, p.T, (float2 *)w.dp, (float2 *)w.dq, nullptr, s)) != hipSuccess) return e;
+    if ((e = cg_forward_two_pass<AT, float, true>(f, p.T, (float2 *)w.dp, (float2 *)w.dq, nullptr, s, w.x, pq)) != hipSuccess)
+      return e;
   }
-  hipLaunchKernelGGL(cg_bwd_pointwise_kernel<AT>, dim3(p.nb, p.B), dim3(NTHREADS), lds1, s, p, w, hs32);
+  hipLaunchKernelGGL(cg_bwd_chain_kernel<AT>, dim3((unsigned)(((size_t)p.B * H + NTHREADS - 1) / NTHREADS)),
+                     dim3(NTHREADS), 0, s, p, w, hs32, pq);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const RowOuts outs = {{p.g.db_a, p.g.db_x, p.g.dLambda, p.dtheta, nullptr}};
   if ((e = launch_reduce_parts(w.partA, p.B, 4, H, outs, s)) != hipSuccess) return e;
+  if ((e = allow_lds(cg_bwd_dgrad_kernel<AT>, lds2)) != hipSuccess) return e;
   hipLaunchKernelGGL(cg_bwd_dgrad_kernel<AT>, dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds2, s, p, w);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const int tj = (hs + 31) / 32, tk = (2 * hs + 31) / 32;
@@ -501,9 +509,9 @@ hipError_t cg_backward_t(const Problem &p, hipStream_t s) {
 
 }  // namespace
 
-size_t cg_backward_ws_bytes(int B, int T, int D, int nb) {
+size_t cg_backward_ws_bytes(int B, int T, int D, int nb) {   // ... + the recomputed states + the parked pre-activations
   const size_t n = (size_t)B * T * D * sizeof(float);
-  return backward_generic_ws_bytes(B, T, D, nb) + ((n + 255) & ~(size_t)255);
+  return backward_generic_ws_bytes(B, T, D, nb) + 2 * ((n + 255) & ~(size_t)255);
 }
 
 hipError_t launch_cg_forward(const Problem &p, bool bf, hipStream_t s) {
