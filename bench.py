@@ -39,6 +39,9 @@ def algorithmic_costs(B, T, D, nb, B_dec):
     return {
         # u in, y out, weights, hT and conv state out
         "fwd_mfma_kernel": dict(bytes=4 * N + w_bytes + vec + 10 * B * D, flops=gemm),
+        # the aggregate pass of a single long prompt's forward (contiguous windows in two passes;
+        # the forward proper then is a launch of fwd_mfma_kernel): u in, weights
+        "fwd_agg_mfma_kernel": dict(bytes=2 * N + w_bytes + vec, flops=gemm),
         # u_t, 3 ring slots read + 1 written, h read + written, y_t, weights
         "decode_mfma_kernel": dict(bytes=(2 + 6 + 2 + 4 + 4 + 2) * B_dec * D + w_bytes + vec,
                                    flops=4 * bs * B_dec * D),

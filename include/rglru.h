@@ -436,7 +436,8 @@ int rglru_workspace_status(const rglru_shape *shape, int op, const void *workspa
 
 /*
  * Upper bound on the number of time slices a sequence is cut into (process-wide; 0 = automatic,
- * the default). With 1 no kernel ever waits on another workgroup: every (sequence, gate block)
+ * the default; it also bounds the contiguous windows that the forward of a single long prompt is
+ * run in, which exchange nothing while they run and cannot time out). With 1 no kernel ever waits on another workgroup: every (sequence, gate block)
  * pair is walked by a single workgroup, slower for few long sequences but independent of all
  * workgroups of a launch being resident at once. This is the setting to retry with after
  * rglru_workspace_status has reported RGLRU_ERR_TIMEOUT (e.g. when another process occupies part

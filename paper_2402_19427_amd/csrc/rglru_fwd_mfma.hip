@@ -45,6 +45,11 @@ struct FwdArgs {
   const unsigned short *wx16;   // W_x in half precision, same layout (fwd_prep_kernel)
   const uint4 *rmask;           // packed sequences: per (sequence, tile) bit masks of the document
                                 // boundaries (reset_mask_kernel), or NULL
+  // Contiguous time slices (G == 1 only): S > 1 cuts every sequence into S windows of Ts steps
+  // (the last one shorter), each a workgroup's own; h0, state_in (and hT, aprod of the
+  // aggregate pass) are then [B*S] arrays with one entry per window.
+  int S, Ts;
+  float *aprod;                 // aggregate pass: [B*S][D] product of a_t over the window
 };
 
 // eqs. (1)-(3) with base-2 exponentials; pp, qq, xx carry a factor log2(e).
@@ -117,6 +122,58 @@ __global__ void __launch_bounds__(256) reset_mask_kernel(const unsigned char *re
 
 constexpr int FWD_MAX_SLICES = 16;
 
+// Contiguous time slices ("windows") of a sequence, first helper: the Conv1D ring each window
+// starts from - the caller's ring for a sequence's first window (zeros without one), the three
+// inputs in front of it for every other window, in the slots their positions select.
+struct WinArgs {
+  const unsigned short *u, *state_in;
+  unsigned short *rings;   // [B*S][3][D]
+  int B, S, Ts, T, D;
+  long long pos0;
+};
+__global__ void __launch_bounds__(256) window_ring_kernel(WinArgs a) {
+  const int D2 = a.D / 2;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)a.B * a.S * 3 * D2) return;
+  const int c = (int)(i % D2), slot = (int)((i / D2) % 3);
+  const int bw = (int)(i / ((size_t)3 * D2)), seq = bw / a.S, win = bw - seq * a.S;
+  unsigned v = 0;
+  if (win == 0) {
+    if (a.state_in) v = ((const unsigned *)a.state_in)[((size_t)seq * 3 + slot) * D2 + c];
+  } else {
+    const long long pw = a.pos0 + (long long)win * a.Ts;   // position of the window's first step
+    for (int k = 1; k <= 3; ++k)
+      if (ring_slot(pw - k) == slot)
+        v = ((const unsigned *)a.u)[((size_t)seq * a.T + (size_t)win * a.Ts - k) * D2 + c];
+  }
+  ((unsigned *)a.rings)[i] = v;
+}
+// Second helper: the state every window starts from, out of the windows' aggregates
+// (h_end = A h_in + H for a window with decay product A and zero-state end value H; eq. (4)).
+__global__ void __launch_bounds__(256) window_chain_kernel(const float *h0, const float *A, const float *H,
+                                                           float *hin, int B, int S, int D) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)B * D) return;
+  const int seq = (int)(i / D), d = (int)(i - (size_t)seq * D);
+  float h = h0 ? h0[i] : 0.f;
+  for (int w0 = 0; w0 < S; w0 += 8) {   // eight windows' aggregates in flight ahead of the chain
+    float av[8], hv[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const size_t k = ((size_t)seq * S + (w0 + e < S ? w0 + e : S - 1)) * D + d;
+      av[e] = A[k];
+      hv[e] = H[k];
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (w0 + e < S) {
+        hin[((size_t)seq * S + w0 + e) * D + d] = h;
+        h = fmaf(av[e], h, hv[e]);
+      }
+    }
+  }
+}
+
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 // eight values of y (bf16 pairs) times GeLU of eight values of the block's other branch
@@ -139,7 +196,9 @@ __device__ __forceinline__ u32x4 merge8(const u32x4 yv, const u32x4 bv) {
 // missing channels write x = 0), their loads of u read nothing and their stores are dropped.
 // PACKED: the sequences hold several documents (FwdArgs.rmask); a variant of its own, so that
 // the plain kernel keeps its register allocation
-template <int GMAX, int MERGE, bool PAD, bool PACKED = false>
+// AGG: aggregate pass over contiguous time slices: nothing of y is formed or written, every
+// window leaves its end state for a zero incoming state (hT) and the product of its a_t (aprod)
+template <int GMAX, int MERGE, bool PAD, bool PACKED = false, bool AGG = false>
 __global__ void __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(2, 2)))
 fwd_mfma_kernel(FwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -160,8 +219,23 @@ fwd_mfma_kernel(FwdArgs a) {
     bid = (bid & 7) * per + (bid >> 3);
   }
   const int unit = bid / G, w = bid - unit * G;
+  // b: entry of the per-sequence arrays (h0, states); with contiguous time slices that is the
+  // window, which covers rows row0 .. row0 + T - 1 of the [B*T] rows and starts at position pos0
   const int b = unit / p.nb, g = unit - b * p.nb;
-  const int D = p.D, T = p.T;
+  const int D = p.D;
+  int T = p.T, ntile = a.ntile, win = 0, nwin = 1, ob = b;   // ob: entry of the final states
+  size_t row0 = (size_t)b * p.T;
+  long long pos0 = p.pos0;
+  if (GMAX == 1 && !PACKED && a.S > 1) {
+    const int seq = b / a.S;
+    nwin = a.S;
+    ob = seq;
+    win = b - seq * a.S;
+    row0 = (size_t)seq * p.T + (size_t)win * a.Ts;
+    T = p.T - win * a.Ts < a.Ts ? p.T - win * a.Ts : a.Ts;
+    ntile = (T + TT - 1) / TT;
+    pos0 += (long long)win * a.Ts;
+  }
   const int ch = wv * 32 + j;  // channel inside the block owned by this lane
   constexpr unsigned OOB = 0x80000000u;   // buffer offset past every range: loads give 0, stores are dropped
   const int bs = PAD ? p.bs : BS;         // channels of a gate block in memory
@@ -183,7 +257,8 @@ fwd_mfma_kernel(FwdArgs a) {
   constexpr int NRES_P = GMAX == 1 ? 11 : (GMAX == 4 ? 2 : (GMAX == 8 ? 0 : 2));
   constexpr int NRES_U = !PAD ? NRES_M : (MERGE == 0 ? NRES_P : (NRES_P >= 2 ? NRES_P - 2 : 0));
   // (the masks of packed sequences take registers of their own)
-  constexpr int NRES = !PACKED ? NRES_U : (NRES_U >= 1 ? NRES_U - 1 : 0);
+  // (the aggregate pass stages no outputs)
+  constexpr int NRES = AGG ? (PAD ? 11 : 14) : !PACKED ? NRES_U : (NRES_U >= 1 ? NRES_U - 1 : 0);
   constexpr int PF = 2;   // streamed fragments in flight (deeper rings measured no better)
   f16x8 wa[16], wx[NRES > 0 ? NRES : 1];   // (half precision, see w_to_f16)
   const f16x8 *pxs = (const f16x8 *)(a.wx16 + ((size_t)g * bs + chc) * bs + hf * 8);
@@ -242,14 +317,14 @@ fwd_mfma_kernel(FwdArgs a) {
   const unsigned seq_bytes = (unsigned)((size_t)T * D * 2);
   const unsigned row_bytes = (unsigned)D * 2;
   const __amdgpu_buffer_rsrc_t u_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      uniform_ptr((const unsigned short *)p.u + (size_t)b * T * D), 0, seq_bytes, 0x00020000);
+      uniform_ptr((const unsigned short *)p.u + row0 * D), 0, seq_bytes, 0x00020000);
   // (a y that is not asked for gets an empty range: its stores are dropped)
   const __amdgpu_buffer_rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      uniform_ptr((unsigned short *)p.y + (size_t)b * T * D), 0, p.y ? seq_bytes : 0u, 0x00020000);
+      uniform_ptr((unsigned short *)p.y + row0 * D), 0, p.y ? seq_bytes : 0u, 0x00020000);
   const __amdgpu_buffer_rsrc_t br_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      uniform_ptr((const unsigned short *)(MERGE ? p.branch : p.u) + (size_t)b * T * D), 0, seq_bytes, 0x00020000);
+      uniform_ptr((const unsigned short *)(MERGE ? p.branch : p.u) + row0 * D), 0, seq_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t out_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      uniform_ptr((unsigned short *)(MERGE ? p.out : p.y) + (size_t)b * T * D), 0, seq_bytes, 0x00020000);
+      uniform_ptr((unsigned short *)(MERGE ? p.out : p.y) + row0 * D), 0, seq_bytes, 0x00020000);
   const unsigned u_voff = pair_ok ? (unsigned)dc * 2 : OOB;
   const unsigned *st32 = (p.state_in && pair_ok)
       ? (const unsigned *)((const unsigned short *)p.state_in + (size_t)b * 3 * D + dc) : nullptr;
@@ -269,7 +344,7 @@ fwd_mfma_kernel(FwdArgs a) {
         if (t >= 0) {
           if (t < T) v = __builtin_amdgcn_raw_buffer_load_b32(u_rsrc, u_voff, (unsigned)t * row_bytes, 0);
         } else if (st32) {
-          v = st32[(size_t)ring_slot(p.pos0 + t) * (D / 2)];
+          v = st32[(size_t)ring_slot(pos0 + t) * (D / 2)];
         }
         raw[n] = v;
       }
@@ -289,7 +364,7 @@ fwd_mfma_kernel(FwdArgs a) {
   // skips the loads of a tile that does not exist measured 3-4 % faster)
   auto next_rows = [&](int next) __attribute__((always_inline)) {
     if (MERGE == 0) {
-      if (next < a.ntile) load_rows(next * TT);
+      if (next < ntile) load_rows(next * TT);
     } else {
       load_rows_inner(next * TT);
     }
@@ -330,6 +405,7 @@ fwd_mfma_kernel(FwdArgs a) {
 
   u64 *ring = GMAX > 1 ? a.rec + (size_t)unit * a.R * 2 * BS + ch : nullptr;
   float carry = p.h0 ? p.h0[(size_t)b * D + d] : 0.f;  // state after this workgroup's previous tile
+  float aprod = 1.f;                                    // (aggregate pass) product of a_t so far
   // (a workspace that still reports an expired wait of an earlier call: no waiting, NaN throughout)
   int spins = (GMAX > 1 && expired_before(a.err)) ? SPIN_LIMIT : 0;
 
@@ -492,8 +568,10 @@ fwd_mfma_kernel(FwdArgs a) {
           aq[e] = av;
           bq[e] = bv;
         }
-        hold_mine[q * 64] = aq;
-        hold_mine[(q + 4) * 64] = bq;
+        if (!AGG) {
+          hold_mine[q * 64] = aq;
+          hold_mine[(q + 4) * 64] = bq;
+        }
       }
     } else {
       const int nvalid = T - t0 - hf * 16;
@@ -517,8 +595,10 @@ fwd_mfma_kernel(FwdArgs a) {
           aq[e] = av;
           bq[e] = bv;
         }
-        hold_mine[q * 64] = aq;
-        hold_mine[(q + 4) * 64] = bq;
+        if (!AGG) {
+          hold_mine[q * 64] = aq;
+          hold_mine[(q + 4) * 64] = bq;
+        }
       }
     }
     // combine the two lane halves: lower half = steps 0..15, upper = 16..31
@@ -534,6 +614,9 @@ fwd_mfma_kernel(FwdArgs a) {
       // publish the aggregate: lower half writes A, upper half writes H
       publish(ring + (size_t)(tl % a.R) * 2 * BS + hf * BS, hf ? hH_t : hA_t, (unsigned)(tl + 1));
       held = tl;
+    } else if (AGG) {   // only the window's aggregate is wanted
+      carry = fmaf(hA_t, carry, hH_t);
+      aprod *= hA_t;
     } else {
       resolve(tl);
     }
@@ -547,7 +630,7 @@ fwd_mfma_kernel(FwdArgs a) {
   const bool late = wv < NWAVE / 2;
 
   int tile = w;
-  if (tile < a.ntile) load_rows(tile * TT);
+  if (tile < ntile) load_rows(tile * TT);
   __syncthreads();  // the constants parked in LDS are visible to every wave
   // Mask words of packed sequences: lanes 0..3 of a wave fetch the four dwords of a tile's word two
   // tiles ahead, as the first load of an iteration (a load consumed any sooner would make its
@@ -571,7 +654,7 @@ fwd_mfma_kernel(FwdArgs a) {
     mk0 = mask_word(mask_fetch(tile));
     mv_next = mask_fetch(tile + G);
   }
-  if (tile < a.ntile) conv_rows(0, tile, mk0);
+  if (tile < ntile) conv_rows(0, tile, mk0);
   unsigned st_cur = mk0[0], st_prev = 0u;   // starts of this iteration's tile and of the one before
   __syncthreads();
 
@@ -580,7 +663,7 @@ fwd_mfma_kernel(FwdArgs a) {
   auto run = [&](auto late_c) __attribute__((always_inline)) {
     constexpr bool LATE = decltype(late_c)::value;
     int it = 0;
-    for (; tile < a.ntile; tile += G, ++it) {
+    for (; tile < ntile; tile += G, ++it) {
       const int buf = it & 1;
       const int next = tile + G;
       u32x4m mkn = {0u, 0u, 0u, 0u};
@@ -602,7 +685,7 @@ fwd_mfma_kernel(FwdArgs a) {
       // next tile of this workgroup into the other LDS buffer
       // (the word of the next tile is read where the tile's rows are waited for anyway)
       if (PACKED) mkn = mask_word(mv_next);
-      if (next < a.ntile) conv_rows(buf ^ 1, next, mkn);
+      if (next < ntile) conv_rows(buf ^ 1, next, mkn);
       st_prev = st_cur;
       st_cur = mkn[0];
       mv_next = mv_after;
@@ -627,22 +710,27 @@ fwd_mfma_kernel(FwdArgs a) {
   }
 
   // the workgroup that ran the last tile owns the final states
-  if ((a.ntile - 1) % G == w) {
-    if (p.hT && hf == 0 && ch_ok) p.hT[(size_t)b * D + d] = carry;
+  if (AGG) {
+    if (hf == 0 && ch_ok) {
+      p.hT[(size_t)b * D + d] = carry;
+      a.aprod[(size_t)b * D + d] = aprod;
+    }
+  } else if ((ntile - 1) % G == w && win == nwin - 1) {   // (of contiguous windows, the sequence's last)
+    if (p.hT && hf == 0 && ch_ok) p.hT[(size_t)ob * D + d] = carry;
     if (p.state_out && tid < 128 && pair_ok) {
       // ring slots of the last three inputs; older slots are carried over (Appendix F state)
-      unsigned *so32 = (unsigned *)((unsigned short *)p.state_out + (size_t)b * 3 * D + dc);
-      const long long end = p.pos0 + T;
+      unsigned *so32 = (unsigned *)((unsigned short *)p.state_out + (size_t)ob * 3 * D + dc);
+      const long long end = pos0 + T;
 #pragma unroll
       for (int slot = 0; slot < 3; ++slot) {
         const long long npos = end - 1 - ring_slot(end - 1 - slot);
         unsigned v = 0;
-        if (npos >= p.pos0)
-          v = __builtin_amdgcn_raw_buffer_load_b32(u_rsrc, u_voff, (unsigned)(npos - p.pos0) * row_bytes, 0);
+        if (npos >= pos0)
+          v = __builtin_amdgcn_raw_buffer_load_b32(u_rsrc, u_voff, (unsigned)(npos - pos0) * row_bytes, 0);
         else if (st32)
           v = st32[(size_t)slot * (D / 2)];
         if (PACKED) {   // an input in front of the last document's first step is not part of its history
-          const long long first = npos - p.pos0 + 1;   // (at least T - 2)
+          const long long first = npos - pos0 + 1;   // (at least T - 2)
           for (int t = first > 0 ? (int)first : 0; t < T; ++t)
             if (p.reset[(size_t)b * T + t]) v = 0;
         }
@@ -987,9 +1075,12 @@ bool forward_mfma_supported(const Problem &p, bool bf) {
 // Whether the merge runs as the forward kernel's epilogue. With more than 8 time slices per
 // sequence the kernel has no registers left for it (every W_x fragment is then re-read per
 // tile) and the merge as a streaming kernel of its own measured faster.
+static int contiguous_windows(int units, int ntile, int ncu, bool packed, int *tiles_per);
 bool forward_mfma_merge_fused(const Problem &p) {
   int ncu = num_cu();
   if (ncu > 256) ncu = 256;
+  // (contiguous windows run the kernel of unsliced sequences, which has the epilogue)
+  if (contiguous_windows(p.B * p.nb, (p.T + TT - 1) / TT, ncu, p.reset != nullptr, nullptr)) return true;
   return pick_slices(p.B * p.nb, (p.T + TT - 1) / TT, ncu, FWD_MAX_SLICES) <= 8;
 }
 
@@ -1008,18 +1099,52 @@ int mfma::pick_slices(int units, int ntile, int ncu, int cap) {
   return G;
 }
 
-// Workspace: one record ring per unit when the sequence is sliced in time. Sized for the
-// worst case of 256 compute units so that it does not depend on the device.
-static size_t fwd_rec_bytes(int B, int T, int nb) {   // status word + record rings, 256-byte granules
+// Long sequences of very few units (a single prompt: B * nb of 12 or less) are cut into
+// contiguous windows instead, as many as there are compute units, and run in two passes - the
+// windows' aggregates (decay product, end state from zero) first, then, once a short chain has
+// turned them into every window's incoming state, the forward proper. That doubles the
+// arithmetic but nothing is exchanged between running workgroups. Interleaved slices read G - 1
+// records per tile and stop at 16 slices (7.2 us per workgroup and tile there, against 3.5 + 4.3 us
+// for the two passes of a window's tile on a full chip), so the two passes win where they put
+// 21 or more compute units on a sequence's block instead of 16 and the sequence is long enough to
+// pay for three more launches (measured: B = 1, T = 32768, 10 blocks 467 -> 344 us; 16 or 20
+// units: 5-8 % slower, left to the interleaved scheme). Returns the number of windows, or 0.
+constexpr int WIN_MAX_UNITS = 12, WIN_MIN_TILES = 384;
+static int contiguous_windows(int units, int ntile, int ncu, bool packed, int *tiles_per) {
+  if (packed || units > WIN_MAX_UNITS || ntile < WIN_MIN_TILES) return 0;
+  int S = ncu / units;
+  if (S > ntile / 4) S = ntile / 4;
+  const int user = g_slice_cap.load();
+  if (user > 0 && S > user) S = user;
+  if (S < 2) return 0;
+  const int per = (ntile + S - 1) / S;
+  S = (ntile + per - 1) / per;    // no empty window
+  if (tiles_per) *tiles_per = per;
+  return S >= 2 ? S : 0;
+}
+static size_t al256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+// Workspace: one record ring per unit when the sequence is sliced in time, or the windows'
+// rings, incoming states and aggregates. Sized for the worst case of 256 compute units so that
+// it does not depend on the device.
+static size_t fwd_rec_bytes(int B, int T, int D, int nb) {   // status word + the above, 256-byte granules
   const int units = B * nb, ntile = (T + TT - 1) / TT;
   const int G = pick_slices(units, ntile, 256, FWD_MAX_SLICES);
   const size_t R = 8 * (size_t)G;
-  return 256 + (G == 1 ? 0 : (size_t)units * R * 2 * BS * sizeof(u64));
+  size_t n = G == 1 ? 0 : (size_t)units * R * 2 * BS * sizeof(u64);
+  // (whatever the user's cap on the slices is when the size is asked for: the largest count)
+  int S = 256 / units;
+  if (S > ntile / 4) S = ntile / 4;
+  if (units <= WIN_MAX_UNITS && ntile >= WIN_MIN_TILES && S >= 2) {
+    const size_t w = al256((size_t)B * S * 3 * D * 2) + 3 * al256((size_t)B * S * D * 4);
+    if (w > n) n = w;
+  }
+  return 256 + n;
 }
 // ... followed by W_x in half precision
 size_t forward_mfma_ws_bytes(int B, int T, int D, int nb) {
   const size_t w = (size_t)D * (D / nb) * 2;
-  return fwd_rec_bytes(B, T, nb) + ((w + 255) & ~(size_t)255);
+  return fwd_rec_bytes(B, T, D, nb) + ((w + 255) & ~(size_t)255);
 }
 
 hipError_t mfma::launch_reset_masks(const unsigned char *reset, uint4 *masks, unsigned char *nlag, int B, int T,
@@ -1062,6 +1187,19 @@ static hipError_t launch_packed_tp(const FwdArgs &a, int grid, size_t lds, hipSt
   hipLaunchKernelGGL((fwd_mfma_kernel<GMAX, 0, PAD, true>), dim3(grid), dim3(NTHR), lds, s, a);
   return hipGetLastError();
 }
+template <bool PAD>
+static hipError_t launch_agg_tp(const FwdArgs &a, int grid, size_t lds, hipStream_t s) {
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void *)fwd_mfma_kernel<1, 0, PAD, false, true>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, FWD_LDS);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  KernelTimer kt("fwd_agg_mfma_kernel", s);
+  hipLaunchKernelGGL((fwd_mfma_kernel<1, 0, PAD, false, true>), dim3(grid), dim3(NTHR), lds, s, a);
+  return hipGetLastError();
+}
 template <int GMAX, int MERGE>
 static hipError_t launch_tm(const FwdArgs &a, int grid, size_t lds, hipStream_t s) {
   return a.p.bs == BS ? launch_tmp<GMAX, MERGE, false>(a, grid, lds, s)
@@ -1083,12 +1221,17 @@ hipError_t launch_forward_mfma(const Problem &p, hipStream_t s) {
   a.ntile = (p.T + TT - 1) / TT;
   int ncu = num_cu();
   if (ncu > 256) ncu = 256;  // the workspace is sized for at most 256 resident workgroups
-  a.G = pick_slices(units, a.ntile, ncu, FWD_MAX_SLICES);
+  int tiles_per = 0;
+  const int S = contiguous_windows(units, a.ntile, ncu, p.reset != nullptr, &tiles_per);
+  a.S = 1;
+  a.Ts = p.T;
+  a.aprod = nullptr;
+  a.G = S ? 1 : pick_slices(units, a.ntile, ncu, FWD_MAX_SLICES);
   a.R = 8 * a.G;
   const int grid = units * a.G;
   a.swizzle = (a.G > 1 && grid % 8 == 0) ? 1 : 0;
   // workspace: status word, record rings (sized for 256 compute units), W_x in half precision
-  unsigned short *wx16 = (unsigned short *)((char *)p.ws + fwd_rec_bytes(p.B, p.T, p.nb));
+  unsigned short *wx16 = (unsigned short *)((char *)p.ws + fwd_rec_bytes(p.B, p.T, p.D, p.nb));
   a.wx16 = wx16;
   const size_t n8 = (size_t)p.D * p.bs / 8;
   const size_t n16 = (a.G == 1 ? 256 : 256 + (size_t)units * a.R * 2 * BS * sizeof(u64)) / 16;
@@ -1106,6 +1249,51 @@ hipError_t launch_forward_mfma(const Problem &p, hipStream_t s) {
     hipError_t e = launch_reset_masks(p.reset, masks, nullptr, p.B, p.T, s);
     if (e != hipSuccess) return e;
     a.rmask = masks;
+  }
+  if (S) {   // contiguous windows in two passes (contiguous_windows)
+    a.rec = nullptr;
+    a.err = nullptr;
+    a.S = S;
+    a.Ts = tiles_per * TT;
+    const size_t nw = (size_t)p.B * S;
+    char *at = (char *)p.ws + 256;
+    unsigned short *rings = (unsigned short *)at;
+    at += al256(nw * 3 * p.D * 2);
+    float *hin = (float *)at;
+    at += al256(nw * p.D * 4);
+    float *Hs = (float *)at;
+    at += al256(nw * p.D * 4);
+    float *As = (float *)at;
+    WinArgs wa;
+    wa.u = (const unsigned short *)p.u;
+    wa.state_in = (const unsigned short *)p.state_in;
+    wa.rings = rings;
+    wa.B = p.B; wa.S = S; wa.Ts = a.Ts; wa.T = p.T; wa.D = p.D;
+    wa.pos0 = p.pos0;
+    hipError_t e;
+    {
+      KernelTimer kt("window_ring_kernel", s);
+      const size_t n = nw * 3 * (p.D / 2);
+      hipLaunchKernelGGL(window_ring_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, wa);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    FwdArgs g = a;   // pass 1: aggregates of every window
+    g.p.y = nullptr; g.p.out = nullptr; g.p.branch = nullptr; g.p.merge = 0;
+    g.p.h0 = nullptr; g.p.state_in = rings; g.p.state_out = nullptr;
+    g.p.hT = Hs;
+    g.aprod = As;
+    e = p.bs == BS ? launch_agg_tp<false>(g, units * S, FWD_LDS, s) : launch_agg_tp<true>(g, units * S, FWD_LDS, s);
+    if (e != hipSuccess) return e;
+    {
+      KernelTimer kt("window_chain_kernel", s);
+      const size_t n = (size_t)p.B * p.D;
+      hipLaunchKernelGGL(window_chain_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                         (const float *)p.h0, (const float *)As, (const float *)Hs, hin, p.B, S, p.D);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    a.p.h0 = hin;        // pass 2: the forward proper, every window from its own state
+    a.p.state_in = rings;
+    return launch_t<1>(a, units * S, FWD_LDS, s);
   }
   if (a.G == 1) {
     a.rec = nullptr;

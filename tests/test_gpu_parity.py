@@ -60,6 +60,8 @@ SHAPES = [
     (1, 1500, 256, 1, "bf16"),   # MFMA path, one unit in 16 time slices
     (33, 70, 1024, 4, "bf16"),   # MFMA path, 132 units: one workgroup per unit, no slicing
     (8, 600, 2048, 8, "bf16"),   # MFMA path, 64 units x 4 slices, record ring wraps (19 tiles > 16)
+    (1, 12400, 512, 2, "bf16"),  # MFMA path, few units and a long sequence: contiguous windows in two passes, ragged end
+    (2, 12320, 320, 2, "bf16"),  # the same with narrower blocks in the padded tile, two sequences
 ]
 
 
@@ -523,6 +525,7 @@ MERGE_SHAPES = [
     (33, 70, 1024, 4, "bf16"),   # MFMA path, one workgroup per unit
     (8, 600, 2048, 8, "bf16"),   # MFMA path, time slices
     (1, 1500, 256, 1, "bf16"),   # MFMA path, 16 time slices: the merge runs as a kernel of its own
+    (1, 12500, 256, 1, "bf16"),  # MFMA path, contiguous windows in two passes, merge as epilogue of the second
     (3, 300, 2560, 16, "bf16"),  # bs = 160 in the padded tile, merge as epilogue
     (2, 100, 2816, 8, "bf16"),   # bs = 352: separate passes, then the merge kernel
 ]
@@ -644,6 +647,7 @@ def test_decode_steps_with_merge_match_oracle(B, D, nb, act, tanh_form):
 @pytest.mark.parametrize("B,T,D,nb,act", [(2, 37, 96, 3, "f32"),      # generic kernels
                                           (2, 130, 512, 2, "bf16"),   # fused kernels
                                           (1, 1100, 256, 1, "bf16"),  # fused, 16 time slices
+                                          (1, 12300, 256, 1, "bf16"), # fused, contiguous windows in two passes
                                           (2, 70, 320, 2, "bf16"),    # padded tile
                                           (1, 75, 1024, 2, "bf16")])  # passes of the wide blocks
 def test_conv_width_zero_is_the_rglru_layer_alone(B, T, D, nb, act):
