@@ -267,98 +267,151 @@ __global__ void __launch_bounds__(NTHREADS) cg_decode_kernel(Problem p) {
 }
 
 // --------------------------------------------------------------------------- backward
-// Pass 0 is the forward kernel once more, writing the states h~_t in fp32 into the workspace
-// (`hs32`): the gradient of the decay multiplies delta~_t by conj(h~_{t-1}), and with the
-// phases in play the 8 bits of a bf16 y would leave dW_a some 3e-2 off.
-// Pass 1: one thread per (sequence, complex channel) walks backwards in time on what pass 0 parked
-// (x, the pre-activations, the states). The adjoint of the state is complex, delta~_t = dy~_t +
-// conj(a~_{t+1}) delta~_{t+1} (a complex number standing for the pair of derivatives with respect
-// to the real and the imaginary part). Writes the gate adjoints dp, dq ([B*T][H]), the direct
-// part of dx, and per-sequence sums for db_a, db_x, dLambda, dtheta (compensated, four steps as
-// plain sums at a time). The loads of four steps are in flight at once.
+// Pass 0 is the forward once more (two passes, parallel over time), writing the states h~_t in
+// fp32 into the workspace (`hs32`): the gradient of the decay multiplies delta~_t by
+// conj(h~_{t-1}), and with the phases in play the 8 bits of a bf16 y would leave dW_a some 3e-2
+// off. It parks x, the pre-activations and the coefficients a~_t as well.
+// Pass 1a: the adjoint of the state is complex, delta~_t = dy~_t + conj(a~_{t+1}) delta~_{t+1} (a
+// complex number standing for the pair of derivatives with respect to the real and the imaginary
+// part): a linear recurrence backwards in time over the parked a~_t, one thread per (sequence,
+// complex channel) with the loads of 16 steps in flight; delta~_t goes where pass 0 had the
+// b~_t. Nothing else is serial in time.
 template <typename AT>
-__global__ void __launch_bounds__(NTHREADS) cg_bwd_chain_kernel(Problem p, BwdWs w, const float *hs32, const float *pq) {
+__global__ void __launch_bounds__(NTHREADS) cg_adj_scan_kernel(Problem p, const float2 *A, float2 *delta) {
   const int H = p.D / 2;
   const size_t n = (size_t)p.B * H, idx = (size_t)blockIdx.x * NTHREADS + threadIdx.x;
   if (idx >= n) return;
   const int b = (int)(idx / H), h = (int)(idx - (size_t)b * H);
-  const float theta = p.theta[h];
-  const float log_sig = -softplus_f(-p.Lambda[h]);         // log sigmoid(Lambda)
-  const float neg_cs = p.c * log_sig, c_theta = p.c * theta;
-  const float lam_scale = p.c * sigmoid_f(-p.Lambda[h]);   // c d log sigmoid(Lambda) / d Lambda
   float cr = p.dhT ? p.dhT[(size_t)b * p.D + h] : 0.f, ci = p.dhT ? p.dhT[(size_t)b * p.D + H + h] : 0.f;
-  float sum[4] = {0.f, 0.f, 0.f, 0.f}, comp[4] = {0.f, 0.f, 0.f, 0.f};
-  const size_t rows = (size_t)p.B * p.T;
-  for (int t1 = p.T; t1 > 0; t1 -= 4) {   // steps t1-1 down to max(t1-4, 0)
-    const int t_lo = t1 > 4 ? t1 - 4 : 0, cnt = t1 - t_lo;
-    float pv[4], qv[4], xr[4], xi[4], yr[4], yi[4], pr[4], pi[4];
+  const float2 *a = A + (size_t)b * p.T * H + h;
+  float2 *dl = delta + (size_t)b * p.T * H + h;
+  const AT *dy = (const AT *)p.dy + (size_t)b * p.T * p.D + h;
+  int t = p.T;
+  for (; t >= 16; t -= 16) {   // steps t-1 down to t-16
+    float2 av[16];
+    float yr[16], yi[16];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      if (k < cnt) {
-        const int t = t1 - 1 - k;
-        const size_t row = (size_t)b * p.T + t, o = row * p.D;
-        pv[k] = pq[row * H + h];
-        qv[k] = pq[(rows + row) * H + h];
-        xr[k] = w.x[o + h];
-        xi[k] = w.x[o + H + h];
-        yr[k] = ldf((const AT *)p.dy, o + h);
-        yi[k] = ldf((const AT *)p.dy, o + H + h);
-        if (t > 0) {
-          pr[k] = hs32[o - p.D + h];
-          pi[k] = hs32[o - p.D + H + h];
-        } else {
-          pr[k] = p.h0 ? p.h0[(size_t)b * p.D + h] : 0.f;
-          pi[k] = p.h0 ? p.h0[(size_t)b * p.D + H + h] : 0.f;
-        }
-      }
+    for (int k = 0; k < 16; ++k) {
+      const size_t tt = (size_t)(t - 1 - k);
+      av[k] = a[tt * H];
+      yr[k] = ldf(dy, tt * p.D);
+      yi[k] = ldf(dy, tt * p.D + H);
     }
-    float s_ba = 0.f, s_bx = 0.f, s_lam = 0.f, s_th = 0.f;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      if (k < cnt) {
-        const int t = t1 - 1 - k;
-        const size_t row = (size_t)b * p.T + t, o = row * p.D;
-        const CGates gt = cg_gate_math(pv[k], qv[k], neg_cs, c_theta);
-        const float dr_ = yr[k] + cr, di_ = yi[k] + ci;
-        // G = delta~ conj(h~_{t-1}) = (dL/dRe a~_t, dL/dIm a~_t)
-        const float Gr = fmaf(dr_, pr[k], di_ * pi[k]), Gi = fmaf(di_, pr[k], -dr_ * pi[k]);
-        const float s = fmaf(dr_, xr[k], di_ * xi[k]);   // dL/d(m_t i_t)
-        // a~_t = exp(lm + i ph): d/d lm = a~_t, d/d ph = i a~_t;  m_t = sqrt(1 - e^{2 lm})
-        float dlm = fmaf(Gr, gt.ar, Gi * gt.ai);
-        const float dph = fmaf(Gi, gt.ar, -Gr * gt.ai);
-        if (gt.m > 0.f) dlm -= s * gt.i * gt.mod2 / gt.m;
-        const float dgate_r = p.c * fmaf(dlm, log_sig, dph * theta);
-        const float dpv = dgate_r * gt.r * gt.rc;
-        const float dqv = s * gt.m * gt.i * gt.ic;
-        s_lam = fmaf(dlm * gt.r, lam_scale, s_lam);
-        s_th = fmaf(dph * gt.r, p.c, s_th);
-        s_ba += dpv;
-        s_bx += dqv;
-        w.dp[row * H + h] = dpv;
-        w.dq[row * H + h] = dqv;
-        const float gain = gt.m * gt.i;
-        w.dx[o + h] = dr_ * gain;
-        w.dx[o + H + h] = di_ * gain;
-        // conj(a~_t) delta~_t
-        cr = fmaf(gt.ar, dr_, gt.ai * di_);
-        ci = fmaf(gt.ar, di_, -gt.ai * dr_);
-      }
+    for (int k = 0; k < 16; ++k) {
+      const float dr_ = yr[k] + cr, di_ = yi[k] + ci;
+      dl[(size_t)(t - 1 - k) * H] = make_float2(dr_, di_);
+      cr = fmaf(av[k].x, dr_, av[k].y * di_);    // conj(a~_t) delta~_t
+      ci = fmaf(av[k].x, di_, -av[k].y * dr_);
     }
-    comp_add(sum[0], comp[0], s_ba);
-    comp_add(sum[1], comp[1], s_bx);
-    comp_add(sum[2], comp[2], s_lam);
-    comp_add(sum[3], comp[3], s_th);
+  }
+  for (; t > 0; --t) {
+    const size_t tt = (size_t)(t - 1);
+    const float2 av = a[tt * H];
+    const float dr_ = ldf(dy, tt * p.D) + cr, di_ = ldf(dy, tt * p.D + H) + ci;
+    dl[tt * H] = make_float2(dr_, di_);
+    cr = fmaf(av.x, dr_, av.y * di_);
+    ci = fmaf(av.x, di_, -av.y * dr_);
   }
   if (p.dh0) {
     p.dh0[(size_t)b * p.D + h] = cr;
     p.dh0[(size_t)b * p.D + H + h] = ci;
   }
-  for (int q = 0; q < 4; ++q) w.partA[((size_t)b * 4 + q) * H + h] = sum[q];
 }
 
-// Pass 2: dx[t][chan(k)] += sum_j W_a[g][j][k] dp[t][j] + W_x[g][j][k] dq[t][j]
+// Pass 1b, parallel over time: a thread takes PCH consecutive steps of one complex channel and
+// forms, from delta~_t and what pass 0 parked, the gate adjoints (dp, dq) - written as a pair over
+// the a~_t it has just read - and the direct part of dx; a workgroup is 64 channels x 4 such runs,
+// whose sums for db_a, db_x, dLambda, dtheta it adds up in a fixed order into one row of `parts`
+// ([B * gridDim.z][4][H]; four steps as plain sums at a time, compensated beyond).
+constexpr int PCH = 64;
 template <typename AT>
-__global__ void __launch_bounds__(NTHREADS) cg_bwd_dgrad_kernel(Problem p, BwdWs w) {
+__global__ void __launch_bounds__(NTHREADS) cg_bwd_point_kernel(Problem p, BwdWs w, const float *hs32, const float *pq,
+                                                                float2 *adpq, const float2 *delta, float *parts) {
+  __shared__ float red[4][4][64];
+  const int H = p.D / 2, hl = threadIdx.x & 63, cq = threadIdx.x >> 6;
+  const int h = blockIdx.x * 64 + hl, b = blockIdx.y;
+  const int t_lo = (blockIdx.z * 4 + cq) * PCH, t_hi = min(p.T, t_lo + PCH);
+  float sum[4] = {0.f, 0.f, 0.f, 0.f}, comp[4] = {0.f, 0.f, 0.f, 0.f};
+  if (h < H && t_lo < t_hi) {
+    const float theta = p.theta[h];
+    const float log_sig = -softplus_f(-p.Lambda[h]);         // log sigmoid(Lambda)
+    const float neg_cs = p.c * log_sig;
+    const float lam_scale = p.c * sigmoid_f(-p.Lambda[h]);   // c d log sigmoid(Lambda) / d Lambda
+    const size_t rows = (size_t)p.B * p.T;
+    for (int t0 = t_lo; t0 < t_hi; t0 += 4) {
+      const int cnt = min(4, t_hi - t0);
+      float pv[4], qv[4], xr[4], xi[4], pr[4], pi[4];
+      float2 av[4], dv[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (k < cnt) {
+          const int t = t0 + k;
+          const size_t row = (size_t)b * p.T + t, o = row * p.D;
+          pv[k] = pq[row * H + h];
+          qv[k] = pq[(rows + row) * H + h];
+          xr[k] = w.x[o + h];
+          xi[k] = w.x[o + H + h];
+          av[k] = adpq[row * H + h];
+          dv[k] = delta[row * H + h];
+          if (t > 0) {
+            pr[k] = hs32[o - p.D + h];
+            pi[k] = hs32[o - p.D + H + h];
+          } else {
+            pr[k] = p.h0 ? p.h0[(size_t)b * p.D + h] : 0.f;
+            pi[k] = p.h0 ? p.h0[(size_t)b * p.D + H + h] : 0.f;
+          }
+        }
+      }
+      float s_ba = 0.f, s_bx = 0.f, s_lam = 0.f, s_th = 0.f;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (k < cnt) {
+          const size_t row = (size_t)b * p.T + t0 + k, o = row * p.D;
+          const float r = sigmoid_f(pv[k]), rc = sigmoid_f(-pv[k]), gi = sigmoid_f(qv[k]), ic = sigmoid_f(-qv[k]);
+          const float lm2 = 2.f * neg_cs * r;              // log |a~_t|^2 <= 0
+          const float mod2 = expf(lm2), m = sqrtf(-expm1f(lm2));
+          const float dr_ = dv[k].x, di_ = dv[k].y, ar = av[k].x, ai = av[k].y;
+          // G = delta~ conj(h~_{t-1}) = (dL/dRe a~_t, dL/dIm a~_t)
+          const float Gr = fmaf(dr_, pr[k], di_ * pi[k]), Gi = fmaf(di_, pr[k], -dr_ * pi[k]);
+          const float s = fmaf(dr_, xr[k], di_ * xi[k]);   // dL/d(m_t i_t)
+          // a~_t = exp(lm + i ph): d/d lm = a~_t, d/d ph = i a~_t;  m_t = sqrt(1 - e^{2 lm})
+          float dlm = fmaf(Gr, ar, Gi * ai);
+          const float dph = fmaf(Gi, ar, -Gr * ai);
+          if (m > 0.f) dlm -= s * gi * mod2 / m;
+          const float dgate_r = p.c * fmaf(dlm, log_sig, dph * theta);
+          const float dpv = dgate_r * r * rc;
+          const float dqv = s * m * gi * ic;
+          s_lam = fmaf(dlm * r, lam_scale, s_lam);
+          s_th = fmaf(dph * r, p.c, s_th);
+          s_ba += dpv;
+          s_bx += dqv;
+          adpq[row * H + h] = make_float2(dpv, dqv);
+          const float gain = m * gi;
+          w.dx[o + h] = dr_ * gain;
+          w.dx[o + H + h] = di_ * gain;
+        }
+      }
+      comp_add(sum[0], comp[0], s_ba);
+      comp_add(sum[1], comp[1], s_bx);
+      comp_add(sum[2], comp[2], s_lam);
+      comp_add(sum[3], comp[3], s_th);
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) red[cq][q][hl] = sum[q];
+  __syncthreads();
+  if (cq == 0 && h < H) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      parts[(((size_t)b * gridDim.z + blockIdx.z) * 4 + q) * H + h] =
+          ((red[0][q][hl] + red[1][q][hl]) + red[2][q][hl]) + red[3][q][hl];
+  }
+}
+
+// Pass 2: dx[t][chan(k)] += sum_j W_a[g][j][k] dp[t][j] + W_x[g][j][k] dq[t][j]   (dpq: the (dp, dq) pairs [B*T][H])
+template <typename AT>
+__global__ void __launch_bounds__(NTHREADS) cg_bwd_dgrad_kernel(Problem p, BwdWs w, const float2 *dpq) {
   extern __shared__ float smem[];
   const int g = blockIdx.x, b = blockIdx.y, t0 = blockIdx.z * GT, hs = p.bs, H = p.D / 2, tid = threadIdx.x;
   const int nt = min(GT, p.T - t0), nin = 2 * hs;
@@ -366,8 +419,9 @@ __global__ void __launch_bounds__(NTHREADS) cg_bwd_dgrad_kernel(Problem p, BwdWs
   for (int idx = tid; idx < GT * hs; idx += NTHREADS) {
     const int tt = idx / hs, j = idx - tt * hs;
     const size_t o = ((size_t)b * p.T + t0 + tt) * H + g * hs + j;
-    dps[idx] = tt < nt ? w.dp[o] : 0.f;
-    dqs[idx] = tt < nt ? w.dq[o] : 0.f;
+    const float2 v = tt < nt ? dpq[o] : make_float2(0.f, 0.f);
+    dps[idx] = v.x;
+    dqs[idx] = v.y;
   }
   __syncthreads();
   const AT *Wa = (const AT *)p.W_a + (size_t)g * hs * nin;
@@ -392,7 +446,7 @@ __global__ void __launch_bounds__(NTHREADS) cg_bwd_dgrad_kernel(Problem p, BwdWs
 // Pass 4: dW_a[g][j][k] = sum_{b,t} dp[b,t,j] x[b,t,chan(k)], dW_x likewise with dq. One
 // workgroup per 32x32 output tile of one block, 16x16 threads with 2x2 outputs each, rows
 // streamed through LDS 32 at a time; the chunks of 32 rows are added up with compensation.
-__global__ void __launch_bounds__(NTHREADS) cg_bwd_wgrad_kernel(Problem p, BwdWs w) {
+__global__ void __launch_bounds__(NTHREADS) cg_bwd_wgrad_kernel(Problem p, BwdWs w, const float2 *dpq) {
   __shared__ float xs[32][33], ps[32][33], qs[32][33];
   const int g = blockIdx.x, j0 = blockIdx.y * 32, k0 = blockIdx.z * 32, hs = p.bs, H = p.D / 2, nin = 2 * hs;
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
@@ -406,8 +460,9 @@ __global__ void __launch_bounds__(NTHREADS) cg_bwd_wgrad_kernel(Problem p, BwdWs
       const size_t row = r0 + rr;
       const bool okr = row < rows;
       xs[rr][cc] = (okr && k0 + cc < nin) ? w.x[row * p.D + cg_channel(g, hs, H, k0 + cc)] : 0.f;
-      ps[rr][cc] = (okr && j0 + cc < hs) ? w.dp[row * H + g * hs + j0 + cc] : 0.f;
-      qs[rr][cc] = (okr && j0 + cc < hs) ? w.dq[row * H + g * hs + j0 + cc] : 0.f;
+      const float2 v = (okr && j0 + cc < hs) ? dpq[row * H + g * hs + j0 + cc] : make_float2(0.f, 0.f);
+      ps[rr][cc] = v.x;
+      qs[rr][cc] = v.y;
     }
     __syncthreads();
     float la[2][2] = {{0.f, 0.f}, {0.f, 0.f}}, lx[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
@@ -471,6 +526,9 @@ hipError_t cg_forward_two_pass(const Problem &p, int tcmax, float2 *A, float2 *B
   return hipSuccess;
 }
 
+// rows of partial sums per sequence that pass 1b leaves: one per 4 runs of PCH steps
+static int cg_point_rows(int T) { return ((T + PCH - 1) / PCH + 3) / 4; }
+
 template <typename AT>
 hipError_t cg_backward_t(const Problem &p, hipStream_t s) {
   const BwdWs w = carve_bwd_ws(p.ws, p.B, p.T, p.D);
@@ -482,6 +540,8 @@ hipError_t cg_backward_t(const Problem &p, hipStream_t s) {
   const size_t nbytes = ((size_t)p.B * p.T * p.D * sizeof(float) + 255) & ~(size_t)255;
   float *hs32 = (float *)((char *)p.ws + backward_generic_ws_bytes(p.B, p.T, p.D, p.nb));
   float *pq = (float *)((char *)hs32 + nbytes);
+  float *parts = (float *)((char *)pq + nbytes);
+  float2 *adpq = (float2 *)w.dp, *delta = (float2 *)w.dq;   // a~_t, then (dp, dq); b~_t, then delta~_t
   {   // pass 0: the forward once more, in two passes (the dp and dq arrays, not yet in use, hold the scan's
       // coefficients of the whole sequence); it parks x and the pre-activations for pass 1
     Problem f = p;
@@ -490,16 +550,20 @@ hipError_t cg_backward_t(const Problem &p, hipStream_t s) {
     if ((e = cg_forward_two_pass<AT, float, true>(f, p.T, (float2 *)w.dp, (float2 *)w.dq, nullptr, s, w.x, pq)) != hipSuccess)
       return e;
   }
-  hipLaunchKernelGGL(cg_bwd_chain_kernel<AT>, dim3((unsigned)(((size_t)p.B * H + NTHREADS - 1) / NTHREADS)),
-                     dim3(NTHREADS), 0, s, p, w, hs32, pq);
+  hipLaunchKernelGGL(cg_adj_scan_kernel<AT>, dim3((unsigned)(((size_t)p.B * H + NTHREADS - 1) / NTHREADS)),
+                     dim3(NTHREADS), 0, s, p, adpq, delta);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  const int nz = cg_point_rows(p.T);
+  hipLaunchKernelGGL(cg_bwd_point_kernel<AT>, dim3((H + 63) / 64, p.B, nz), dim3(NTHREADS), 0, s, p, w, hs32, pq,
+                     adpq, delta, parts);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const RowOuts outs = {{p.g.db_a, p.g.db_x, p.g.dLambda, p.dtheta, nullptr}};
-  if ((e = launch_reduce_parts(w.partA, p.B, 4, H, outs, s)) != hipSuccess) return e;
+  if ((e = launch_reduce_parts(parts, p.B * nz, 4, H, outs, s)) != hipSuccess) return e;
   if ((e = allow_lds(cg_bwd_dgrad_kernel<AT>, lds2)) != hipSuccess) return e;
-  hipLaunchKernelGGL(cg_bwd_dgrad_kernel<AT>, dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds2, s, p, w);
+  hipLaunchKernelGGL(cg_bwd_dgrad_kernel<AT>, dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds2, s, p, w, adpq);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const int tj = (hs + 31) / 32, tk = (2 * hs + 31) / 32;
-  hipLaunchKernelGGL(cg_bwd_wgrad_kernel, dim3(p.nb, tj, tk), dim3(NTHREADS), 0, s, p, w);
+  hipLaunchKernelGGL(cg_bwd_wgrad_kernel, dim3(p.nb, tj, tk), dim3(NTHREADS), 0, s, p, w, adpq);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   // the Conv1D's adjoint is the real layer's: du from dx, tap and bias gradients
   Problem q = p;
@@ -509,9 +573,11 @@ hipError_t cg_backward_t(const Problem &p, hipStream_t s) {
 
 }  // namespace
 
-size_t cg_backward_ws_bytes(int B, int T, int D, int nb) {   // ... + the recomputed states + the parked pre-activations
+size_t cg_backward_ws_bytes(int B, int T, int D, int nb) {   // ... + the recomputed states, the parked
+                                                             // pre-activations and the partial sums of pass 1b
   const size_t n = (size_t)B * T * D * sizeof(float);
-  return backward_generic_ws_bytes(B, T, D, nb) + 2 * ((n + 255) & ~(size_t)255);
+  const size_t parts = (size_t)B * cg_point_rows(T) * 4 * (D / 2) * sizeof(float);
+  return backward_generic_ws_bytes(B, T, D, nb) + 2 * ((n + 255) & ~(size_t)255) + ((parts + 255) & ~(size_t)255);
 }
 
 hipError_t launch_cg_forward(const Problem &p, bool bf, hipStream_t s) {
