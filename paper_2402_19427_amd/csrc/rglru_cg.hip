@@ -12,6 +12,7 @@
 // math), built like the real layer's general kernels: one workgroup per (gate block, sequence)
 // walks the sequence in tiles of GT steps. In Problem, bs = hs and D is the real width.
 #include "rglru_generic.h"
+#include "rglru_mfma.h"
 
 namespace rglru {
 
@@ -166,6 +167,77 @@ __global__ void __launch_bounds__(NTHREADS) cg_coeff_kernel(Problem p, int t_lo,
       }
     }
   }
+}
+// The same pass with the gate products on the matrix cores (bf16 storage, hs a multiple of 16):
+// a workgroup of four waves takes 32 steps of one (gate block, sequence); the x tile sits in LDS
+// in fp32 (for b~_t and the parked copy) and in half precision (the products' row operand, 11
+// significant bits; the bf16 weights convert to half precision exactly from 6.1e-5 up); a wave
+// owns 32 complex channels at a time and multiplies the tile by those channels' rows of W_a and
+// of W_x, fetched as 16-byte fragments straight from the matrices (v_mfma_f32_32x32x16_f16), so
+// that a lane ends up with both pre-activations of one channel for 16 steps.
+constexpr int MT = 32;   // steps per tile of the matrix-core passes
+// row of the x tile that lane column j feeds, so that accumulator register r of lane half hf is step 16 hf + r
+__device__ __forceinline__ int mfma_arow(int j) { return ((j >> 2) & 1) * 16 + (j >> 3) * 4 + (j & 3); }
+template <bool KEEP = false>
+__global__ void __launch_bounds__(NTHREADS) cg_coeff_mfma_kernel(Problem p, int t_lo, int t_hi, float2 *A, float2 *Bv,
+                                                                 float *xk = nullptr, float *pq = nullptr) {
+  extern __shared__ float smem[];
+  const int g = blockIdx.x, b = blockIdx.y, t0 = t_lo + blockIdx.z * MT, hs = p.bs, H = p.D / 2, nin = 2 * hs;
+  const int nt = min(MT, t_hi - t0), tc = t_hi - t_lo, xsh = nin + 8;
+  float *xf = smem;                                    // [MT][nin] fp32
+  _Float16 *xh = (_Float16 *)(smem + MT * nin);        // [MT][nin + 8] half precision
+  for (int idx = threadIdx.x; idx < MT * nin; idx += NTHREADS) {
+    const int tt = idx / nin, k = idx - tt * nin;
+    const float v = tt < nt ? conv_at<bf16>(p, b, t0 + tt, cg_channel(g, hs, H, k)) : 0.f;
+    xf[idx] = v;
+    xh[tt * xsh + k] = (_Float16)v;
+  }
+  __syncthreads();
+  const int lane = threadIdx.x & 63, hf = lane >> 5, j = lane & 31, wv = threadIdx.x >> 6;
+  const _Float16 *arow = xh + mfma_arow(j) * xsh + hf * 8;
+  for (int cb = wv; cb * 32 < hs; cb += NTHREADS / 64) {
+    const int jj = cb * 32 + j;
+    const bool ok = jj < hs;
+    const int h = g * hs + (ok ? jj : hs - 1);
+    const mfma::bf16x8 *wa = (const mfma::bf16x8 *)((const unsigned short *)p.W_a + (size_t)h * nin + hf * 8);
+    const mfma::bf16x8 *wx = (const mfma::bf16x8 *)((const unsigned short *)p.W_x + (size_t)h * nin + hf * 8);
+    mfma::f32x16 accp, accq;
+    const float bp = p.b_a[h], bq = p.b_x[h];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      accp[r] = bp;
+      accq[r] = bq;
+    }
+    for (int ks = 0; ks < nin / 16; ++ks) {
+      const mfma::f16x8 a = *(const mfma::f16x8 *)(arow + ks * 16);
+      accp = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, mfma::w_to_f16(wa[ks * 2]), accp, 0, 0, 0);
+      accq = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, mfma::w_to_f16(wx[ks * 2]), accq, 0, 0, 0);
+    }
+    if (!ok) continue;
+    const float neg_cs = -p.c * softplus_f(-p.Lambda[h]), c_theta = p.c * p.theta[h];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int tt = hf * 16 + r;
+      if (tt < nt) {
+        const CGates gt = cg_gate_math(accp[r], accq[r], neg_cs, c_theta);
+        const float gain = gt.m * gt.i, xr = xf[tt * nin + jj], xi = xf[tt * nin + hs + jj];
+        const size_t o = ((size_t)b * tc + (t0 - t_lo) + tt) * H + h;
+        A[o] = make_float2(gt.ar, gt.ai);
+        Bv[o] = make_float2(gain * xr, gain * xi);
+        if (KEEP) {
+          const size_t row = (size_t)b * p.T + t0 + tt;
+          xk[row * p.D + h] = xr;
+          xk[row * p.D + H + h] = xi;
+          pq[row * H + h] = accp[r];
+          pq[((size_t)p.B * p.T + row) * H + h] = accq[r];
+        }
+      }
+    }
+  }
+}
+// whether the matrix-core passes take this problem (bf16 storage is the caller's to check)
+static bool cg_mfma_ok(const Problem &p) {
+  return p.bs % 16 == 0 && p.bs <= 256 && ((uintptr_t)p.W_a % 16) == 0 && ((uintptr_t)p.W_x % 16) == 0;
 }
 template <typename OT>
 __global__ void __launch_bounds__(NTHREADS) cg_scan_kernel(Problem p, int t_lo, int t_hi, const float2 *A,
@@ -508,15 +580,20 @@ template <typename AT, typename OT, bool KEEP = false>
 hipError_t cg_forward_two_pass(const Problem &p, int tcmax, float2 *A, float2 *Bv, float *hstate, hipStream_t s,
                                float *xk = nullptr, float *pq = nullptr) {
   const int hs = p.bs, H = p.D / 2;
-  const size_t lds = (size_t)CTG * 2 * hs * sizeof(float);
-  hipError_t e = allow_lds(cg_coeff_kernel<AT, KEEP>, lds);
+  const bool on_mfma = sizeof(AT) == 2 && cg_mfma_ok(p);
+  const size_t lds = on_mfma ? (size_t)MT * 2 * hs * 4 + (size_t)MT * (2 * hs + 8) * 2 : (size_t)CTG * 2 * hs * sizeof(float);
+  hipError_t e = on_mfma ? allow_lds(cg_coeff_mfma_kernel<KEEP>, lds) : allow_lds(cg_coeff_kernel<AT, KEEP>, lds);
   if (e != hipSuccess) return e;
-  const int sblocks = (int)(((size_t)p.B * H + NTHREADS - 1) / NTHREADS);
+  const int sblocks = (int)(((size_t)p.B * H + NTHREADS - 1) / NTHREADS), steps = on_mfma ? MT : CTG;
   for (int t_lo = 0; t_lo < p.T; t_lo += tcmax) {
-    const int t_hi = t_lo + tcmax < p.T ? t_lo + tcmax : p.T, ntile = (t_hi - t_lo + CTG - 1) / CTG;
+    const int t_hi = t_lo + tcmax < p.T ? t_lo + tcmax : p.T, ntile = (t_hi - t_lo + steps - 1) / steps;
     if (ntile > 65535) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((cg_coeff_kernel<AT, KEEP>), dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds, s, p, t_lo, t_hi, A, Bv,
-                       xk, pq);
+    if (on_mfma)
+      hipLaunchKernelGGL((cg_coeff_mfma_kernel<KEEP>), dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds, s, p, t_lo, t_hi, A,
+                         Bv, xk, pq);
+    else
+      hipLaunchKernelGGL((cg_coeff_kernel<AT, KEEP>), dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds, s, p, t_lo, t_hi, A,
+                         Bv, xk, pq);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     const bool last = t_hi == p.T;
     hipLaunchKernelGGL(cg_scan_kernel<OT>, dim3(sblocks), dim3(NTHREADS), 0, s, p, t_lo, t_hi, A, Bv,

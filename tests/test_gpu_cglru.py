@@ -17,6 +17,8 @@ SHAPES = [
     (3, 5, 40, 5, "f32"),        # hs = 4, fewer steps than a tile
     (1, 1, 16, 1, "f32"),        # one step, one dense block
     (2, 130, 512, 2, "bf16"),    # hs = 128
+    (2, 100, 640, 2, "bf16"),    # hs = 160: ten column blocks of the matrix-core passes
+    (3, 70, 192, 2, "bf16"),     # hs = 48: a partial column block
     (1, 300, 1024, 1, "bf16"),   # hs = 512: more outputs than threads
     (4, 20, 24, 12, "bf16"),     # hs = 1: per-channel gates
 ]
@@ -45,10 +47,11 @@ def test_cg_forward_and_backward_match_oracle(B, T, D, nb, act, conv):
     u, h0 = rn.to_device(inp["u"], act), rn.to_device(inp["h0"], "f32")
     ring = rn.to_device(gen.ring_from_chrono(inp["state"], pos0), act) if conv else None
     y, hT, st = dp.forward(u, h0=h0, state_in=ring, pos0=pos0)
-    # the same call without the optional scratch (one pass instead of two): the same arithmetic per step
+    # the same call without the optional scratch (one pass instead of two)
     y1, hT1, _ = dp.forward(u, h0=h0, state_in=ring, pos0=pos0, scratch=False)
     assert gen.rel_err(rn.to_host(y1), rn.to_host(y)) < (2e-6 if act == "f32" else 1e-2)
-    assert gen.rel_err(rn.to_host(hT1), rn.to_host(hT)) < 2e-6
+    # (bf16 storage: the two-pass form takes x_t in half precision into its gate products)
+    assert gen.rel_err(rn.to_host(hT1), rn.to_host(hT)) < (2e-6 if act == "f32" else 1e-2)
     q = f64(inp)
     kw = dict(conv_w=q["conv_w"], conv_b=q["conv_b"], state_in=q["state"]) if conv else {}
     y_ref, hT_ref, st_ref = oracle.cg_forward(q["u"], *params(q), h0=q["h0"], **kw)
@@ -100,6 +103,8 @@ def test_cg_forward_in_pieces_equals_one_shot():
         y, h, state = dp.forward(u[:, pos:pos + T1].contiguous(), h0=h, state_in=state, pos0=pos)
         ys.append(rn.to_host(y))
         pos += T1
-    np.testing.assert_array_equal(np.concatenate(ys, axis=1), rn.to_host(y_all))
-    np.testing.assert_array_equal(rn.to_host(h), rn.to_host(hT_all))
+    # (short pieces run in one pass with fp32 gate products, long ones on the matrix cores with
+    # x_t in half precision: equal up to that rounding, a bf16 step of y here and there)
+    assert gen.rel_err(np.concatenate(ys, axis=1), rn.to_host(y_all)) < 1e-2
+    assert gen.rel_err(rn.to_host(h), rn.to_host(hT_all)) < 1e-2
     np.testing.assert_array_equal(rn.to_host(state), rn.to_host(st_all))
