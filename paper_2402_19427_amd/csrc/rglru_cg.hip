@@ -568,6 +568,146 @@ __global__ void __launch_bounds__(NTHREADS) cg_bwd_wgrad_kernel(Problem p, BwdWs
     }
 }
 
+// The same contraction on the matrix cores (bf16 storage, hs a multiple of 16 up to 128). Time
+// is the contraction index, so both operands are staged transposed - [output j][step] for the
+// (dp, dq) pairs, [input k][step] for x - each as a bf16 high part + low part (16 significant
+// bits at the full fp32 exponent range: gradients may be arbitrarily small or large), and a
+// product is hi*hi + hi*lo + lo*hi. A workgroup of eight waves accumulates one gate block's
+// [2 hs][2 hs] gradient (rows: W_a's outputs, then W_x's) over a slice of the B*T rows, 32 rows at a
+// time: wave w owns output rows 32 w .. 32 w + 31 against every column block. The next 32 rows are
+// fetched into registers while the products run. The slices' partial sums ([S][nb][2 hs][2 hs])
+// are added up in a fixed order by cg_wgrad_reduce_kernel.
+constexpr int WRS = MT + 8;   // row stride of the transposed tiles (bf16 elements)
+__global__ void __launch_bounds__(512) cg_wgrad_mfma_kernel(Problem p, BwdWs w, const float2 *dpq, float *part,
+                                                            int rows_per) {
+  extern __shared__ __attribute__((aligned(16))) unsigned short wsm[];
+  const int g = blockIdx.x, sl = blockIdx.y, hs = p.bs, H = p.D / 2, nin = 2 * hs, ncb = nin / 32;
+  unsigned short *d_hi = wsm, *d_lo = wsm + nin * WRS, *x_hi = wsm + 2 * nin * WRS, *x_lo = wsm + 3 * nin * WRS;
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, j = lane & 31, wv = tid >> 6;
+  const size_t rows = (size_t)p.B * p.T;
+  const size_t r_lo = (size_t)sl * rows_per, r_hi = r_lo + rows_per < rows ? r_lo + rows_per : rows;
+  // a thread stages 8 consecutive rows of one output's (dp, dq) and 16 consecutive rows of one
+  // input's x: eight (sixteen) steps of a channel are one (two) 16-byte pieces of a transposed row
+  const int jc = tid & 127, rg = tid >> 7;    // (dp, dq): complex channel jc of the block, rows 8 rg ..
+  const int kx = tid & 255, rg2 = tid >> 8;   // x: input kx of the block, rows 16 rg2 ..
+  const bool d_ok = jc < hs, x_ok = kx < nin;
+  const float2 *dsrc = dpq + (size_t)g * hs + (d_ok ? jc : 0);
+  const float *xsrc = w.x + cg_channel(g, hs, H, x_ok ? kx : 0);
+  float2 dv[8];
+  float xv[16];
+  auto fetch = [&](size_t r0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const size_t row = r0 + 8 * rg + i;
+      dv[i] = (d_ok && row < r_hi) ? dsrc[row * H] : make_float2(0.f, 0.f);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const size_t row = r0 + 16 * rg2 + i;
+      xv[i] = (x_ok && row < r_hi) ? xsrc[row * p.D] : 0.f;
+    }
+  };
+  typedef unsigned u32x4w __attribute__((ext_vector_type(4)));
+  auto park = [&]() __attribute__((always_inline)) {
+    if (d_ok) {
+      u32x4w ph, pl, qh, ql;   // dp: high, low; dq: high, low
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        unsigned hi, lo;
+        mfma::split_bf16(dv[2 * i].x, dv[2 * i + 1].x, hi, lo);
+        ph[i] = hi;
+        pl[i] = lo;
+        mfma::split_bf16(dv[2 * i].y, dv[2 * i + 1].y, hi, lo);
+        qh[i] = hi;
+        ql[i] = lo;
+      }
+      *(u32x4w *)(d_hi + jc * WRS + 8 * rg) = ph;
+      *(u32x4w *)(d_lo + jc * WRS + 8 * rg) = pl;
+      *(u32x4w *)(d_hi + (hs + jc) * WRS + 8 * rg) = qh;
+      *(u32x4w *)(d_lo + (hs + jc) * WRS + 8 * rg) = ql;
+    }
+    if (x_ok) {
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        u32x4w xh4, xl4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          unsigned hi, lo;
+          mfma::split_bf16(xv[8 * half + 2 * i], xv[8 * half + 2 * i + 1], hi, lo);
+          xh4[i] = hi;
+          xl4[i] = lo;
+        }
+        *(u32x4w *)(x_hi + kx * WRS + 16 * rg2 + 8 * half) = xh4;
+        *(u32x4w *)(x_lo + kx * WRS + 16 * rg2 + 8 * half) = xl4;
+      }
+    }
+  };
+  mfma::f32x16 acc[8];
+#pragma unroll
+  for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
+  const bool active = wv * 32 < nin;
+  if (r_lo < r_hi) fetch(r_lo);
+  for (size_t r0 = r_lo; r0 < r_hi; r0 += MT) {
+    __syncthreads();   // the previous tile's products are done with the buffers
+    park();
+    __syncthreads();
+    if (r0 + MT < r_hi) fetch(r0 + MT);
+    if (active) {
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int off = (wv * 32 + j) * WRS + 16 * q + 8 * hf;
+        const mfma::bf16x8 a_hi = *(const mfma::bf16x8 *)(d_hi + off), a_lo = *(const mfma::bf16x8 *)(d_lo + off);
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb) {
+          if (cb < ncb) {
+            const int bo = (cb * 32 + j) * WRS + 16 * q + 8 * hf;
+            const mfma::bf16x8 b_hi = *(const mfma::bf16x8 *)(x_hi + bo), b_lo = *(const mfma::bf16x8 *)(x_lo + bo);
+            acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, b_hi, acc[cb], 0, 0, 0);
+            acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, b_lo, acc[cb], 0, 0, 0);
+            acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, b_hi, acc[cb], 0, 0, 0);
+          }
+          if (cb & 1) __builtin_amdgcn_sched_barrier(0);   // (two column blocks' fragments in flight, not all eight)
+        }
+      }
+    }
+  }
+  if (active) {
+    float *out = part + ((size_t)sl * p.nb + g) * nin * nin;
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb) {
+      if (cb < ncb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = wv * 32 + 8 * (r >> 2) + 4 * hf + (r & 3), col = cb * 32 + j;
+          out[(size_t)row * nin + col] = acc[cb][r];
+        }
+      }
+    }
+  }
+}
+// dW_a[g][j][k], dW_x[g][j][k] from the S partial [2 hs][2 hs] sums of every block, in a fixed order
+__global__ void __launch_bounds__(NTHREADS) cg_wgrad_reduce_kernel(Problem p, const float *part, int S) {
+  const int hs = p.bs, nin = 2 * hs;
+  const size_t per = (size_t)p.nb * nin * nin, i = (size_t)blockIdx.x * NTHREADS + threadIdx.x;
+  if (i >= per) return;
+  float sum = 0.f, comp = 0.f;
+  for (int s = 0; s < S; ++s) comp_add(sum, comp, part[(size_t)s * per + i]);
+  const int g = (int)(i / ((size_t)nin * nin)), rem = (int)(i - (size_t)g * nin * nin), jj = rem / nin, k = rem - jj * nin;
+  float *dst = jj < hs ? p.g.dW_a : p.g.dW_x;
+  dst[((size_t)g * hs + (jj < hs ? jj : jj - hs)) * nin + k] = sum;
+}
+static bool cg_wgrad_mfma_ok(int hs) { return hs % 16 == 0 && hs <= 128; }
+// slices of the B*T rows that the matrix-core wgrad pass runs in: enough workgroups for the chip,
+// no slice shorter than 256 rows
+static int cg_wgrad_slices(size_t rows, int nb) {
+  int S = (256 + nb - 1) / nb;
+  const size_t most = (rows + 255) / 256;
+  if ((size_t)S > most) S = (int)most;
+  return S < 1 ? 1 : S;
+}
+
 template <typename K>
 hipError_t allow_lds(K kernel, size_t bytes) {
   if (bytes <= 48 * 1024) return hipSuccess;
@@ -639,9 +779,24 @@ hipError_t cg_backward_t(const Problem &p, hipStream_t s) {
   if ((e = allow_lds(cg_bwd_dgrad_kernel<AT>, lds2)) != hipSuccess) return e;
   hipLaunchKernelGGL(cg_bwd_dgrad_kernel<AT>, dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds2, s, p, w, adpq);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  const int tj = (hs + 31) / 32, tk = (2 * hs + 31) / 32;
-  hipLaunchKernelGGL(cg_bwd_wgrad_kernel, dim3(p.nb, tj, tk), dim3(NTHREADS), 0, s, p, w, adpq);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (sizeof(AT) == 2 && cg_wgrad_mfma_ok(hs)) {
+    const size_t rows = (size_t)p.B * p.T;
+    const int S = cg_wgrad_slices(rows, p.nb), nin = 2 * hs;
+    const int rows_per = (int)(((rows + S - 1) / S + MT - 1) / MT * MT);
+    float *wpart = (float *)((char *)parts + align256((size_t)p.B * nz * 4 * H * sizeof(float)));
+    const size_t ldsw = (size_t)4 * nin * WRS * 2;
+    if ((e = allow_lds(cg_wgrad_mfma_kernel, ldsw)) != hipSuccess) return e;
+    hipLaunchKernelGGL(cg_wgrad_mfma_kernel, dim3(p.nb, S), dim3(512), ldsw, s, p, w, adpq, wpart, rows_per);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const size_t per = (size_t)p.nb * nin * nin;
+    hipLaunchKernelGGL(cg_wgrad_reduce_kernel, dim3((unsigned)((per + NTHREADS - 1) / NTHREADS)), dim3(NTHREADS), 0, s, p,
+                       wpart, S);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  } else {
+    const int tj = (hs + 31) / 32, tk = (2 * hs + 31) / 32;
+    hipLaunchKernelGGL(cg_bwd_wgrad_kernel, dim3(p.nb, tj, tk), dim3(NTHREADS), 0, s, p, w, adpq);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   // the Conv1D's adjoint is the real layer's: du from dx, tap and bias gradients
   Problem q = p;
   q.g.db_a = q.g.db_x = q.g.dLambda = nullptr;
@@ -654,7 +809,11 @@ size_t cg_backward_ws_bytes(int B, int T, int D, int nb) {   // ... + the recomp
                                                              // pre-activations and the partial sums of pass 1b
   const size_t n = (size_t)B * T * D * sizeof(float);
   const size_t parts = (size_t)B * cg_point_rows(T) * 4 * (D / 2) * sizeof(float);
-  return backward_generic_ws_bytes(B, T, D, nb) + 2 * ((n + 255) & ~(size_t)255) + ((parts + 255) & ~(size_t)255);
+  const int hs = D / 2 / nb;
+  // (the matrix-core wgrad pass's partial sums, whatever the storage type turns out to be)
+  const size_t wpart = cg_wgrad_mfma_ok(hs) ? (size_t)cg_wgrad_slices((size_t)B * T, nb) * nb * 4 * hs * hs * sizeof(float) : 0;
+  return backward_generic_ws_bytes(B, T, D, nb) + 2 * ((n + 255) & ~(size_t)255) + ((parts + 255) & ~(size_t)255) +
+         ((wpart + 255) & ~(size_t)255);
 }
 
 hipError_t launch_cg_forward(const Problem &p, bool bf, hipStream_t s) {
