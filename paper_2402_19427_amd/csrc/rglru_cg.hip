@@ -186,11 +186,24 @@ __global__ void __launch_bounds__(NTHREADS) cg_coeff_mfma_kernel(Problem p, int 
   const int nt = min(MT, t_hi - t0), tc = t_hi - t_lo, xsh = nin + 8;
   float *xf = smem;                                    // [MT][nin] fp32
   _Float16 *xh = (_Float16 *)(smem + MT * nin);        // [MT][nin + 8] half precision
-  for (int idx = threadIdx.x; idx < MT * nin; idx += NTHREADS) {
-    const int tt = idx / nin, k = idx - tt * nin;
-    const float v = tt < nt ? conv_at<bf16>(p, b, t0 + tt, cg_channel(g, hs, H, k)) : 0.f;
-    xf[idx] = v;
-    xh[tt * xsh + k] = (_Float16)v;
+  for (int k = threadIdx.x; k < nin; k += NTHREADS) {   // a thread walks one input column down the tile's steps
+    const int d = cg_channel(g, hs, H, k);
+    const bool conv = p.conv_w != nullptr;
+    const float w0 = conv ? p.conv_w[d] : 1.f, w1 = conv ? p.conv_w[(size_t)p.D + d] : 0.f;
+    const float w2 = conv ? p.conv_w[(size_t)2 * p.D + d] : 0.f, w3 = conv ? p.conv_w[(size_t)3 * p.D + d] : 0.f;
+    const float cb = (conv && p.conv_b) ? p.conv_b[d] : 0.f;
+    float u1 = conv ? input_at<bf16>(p, b, t0 - 1, d) : 0.f, u2 = conv ? input_at<bf16>(p, b, t0 - 2, d) : 0.f;
+    float u3 = conv ? input_at<bf16>(p, b, t0 - 3, d) : 0.f;
+#pragma unroll 8
+    for (int tt = 0; tt < MT; ++tt) {
+      const float u0 = tt < nt ? input_at<bf16>(p, b, t0 + tt, d) : 0.f;
+      const float v = tt < nt ? fmaf(w0, u0, fmaf(w1, u1, fmaf(w2, u2, fmaf(w3, u3, cb)))) : 0.f;
+      xf[tt * nin + k] = v;
+      xh[tt * xsh + k] = (_Float16)v;
+      u3 = u2;
+      u2 = u1;
+      u1 = u0;
+    }
   }
   __syncthreads();
   const int lane = threadIdx.x & 63, hf = lane >> 5, j = lane & 31, wv = threadIdx.x >> 6;
@@ -214,22 +227,34 @@ __global__ void __launch_bounds__(NTHREADS) cg_coeff_mfma_kernel(Problem p, int 
       accq = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, mfma::w_to_f16(wx[ks * 2]), accq, 0, 0, 0);
     }
     if (!ok) continue;
-    const float neg_cs = -p.c * softplus_f(-p.Lambda[h]), c_theta = p.c * p.theta[h];
+    // (base-2 exponentials and the hardware's sine / cosine of an angle in revolutions)
+    const float l2cs = -p.c * softplus_f(-p.Lambda[h]) * mfma::LOG2E, rev = p.c * p.theta[h] * 0.15915494309189535f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int tt = hf * 16 + r;
       if (tt < nt) {
-        const CGates gt = cg_gate_math(accp[r], accq[r], neg_cs, c_theta);
-        const float gain = gt.m * gt.i, xr = xf[tt * nin + jj], xi = xf[tt * nin + hs + jj];
+        const float gr = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-accp[r] * mfma::LOG2E));
+        const float gi = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-accq[r] * mfma::LOG2E));
+        const float l2 = l2cs * gr, mod = __builtin_amdgcn_exp2f(l2);   // |a~_t| and its base-2 logarithm
+        const float ar = mod * __builtin_amdgcn_cosf(rev * gr), ai = mod * __builtin_amdgcn_sinf(rev * gr);
+        const float gain = __builtin_amdgcn_sqrtf(mfma::one_minus_sq(mod, l2)) * gi;
+        const float xr = xf[tt * nin + jj], xi = xf[tt * nin + hs + jj];
         const size_t o = ((size_t)b * tc + (t0 - t_lo) + tt) * H + h;
-        A[o] = make_float2(gt.ar, gt.ai);
+        A[o] = make_float2(ar, ai);
         Bv[o] = make_float2(gain * xr, gain * xi);
-        if (KEEP) {
-          const size_t row = (size_t)b * p.T + t0 + tt;
-          xk[row * p.D + h] = xr;
-          xk[row * p.D + H + h] = xi;
-          pq[row * H + h] = accp[r];
-          pq[((size_t)p.B * p.T + row) * H + h] = accq[r];
+      }
+    }
+    if (KEEP) {   // (a loop of its own: fused with the one above it took 300 registers)
+      const size_t row0 = (size_t)b * p.T + t0 + hf * 16;
+      float *xo = xk + row0 * p.D + h, *po = pq + row0 * H + h, *qo = po + (size_t)p.B * p.T * H;
+      const float *xr = xf + (hf * 16) * nin + jj;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        if (hf * 16 + r < nt) {
+          xo[(size_t)r * p.D] = xr[r * nin];
+          xo[(size_t)r * p.D + H] = xr[r * nin + hs];
+          po[(size_t)r * H] = accp[r];
+          qo[(size_t)r * H] = accq[r];
         }
       }
     }
