@@ -540,6 +540,60 @@ __global__ void __launch_bounds__(NTHREADS) cg_bwd_dgrad_kernel(Problem p, BwdWs
   }
 }
 
+// Pass 2 on the matrix cores (bf16 storage, hs a multiple of 16 up to 256). The contraction runs
+// over a block's 2 hs gate outputs (dp against W_a, dq against W_x), so the weights are needed
+// transposed: cg_wt_kernel writes wt[g][k][jj] = W_a[g][jj][k] for jj < hs, W_x[g][jj - hs][k] beyond
+// (bf16, exact) into the workspace. A workgroup of four waves takes 32 steps of one (gate block,
+// sequence): the (dp, dq) tile in LDS as bf16 high + low parts (16 significant bits at the full
+// fp32 exponent range), a wave owns 32 of the 2 hs inputs at a time and adds its products to dx.
+__global__ void __launch_bounds__(NTHREADS) cg_wt_kernel(Problem p, unsigned short *wt) {
+  const int hs = p.bs, nin = 2 * hs;
+  const size_t n = (size_t)p.nb * nin * nin, i = (size_t)blockIdx.x * NTHREADS + threadIdx.x;
+  if (i >= n) return;
+  const int g = (int)(i / ((size_t)nin * nin)), rem = (int)(i - (size_t)g * nin * nin), k = rem / nin, jj = rem - k * nin;
+  const unsigned short *src = (const unsigned short *)(jj < hs ? p.W_a : p.W_x);
+  wt[i] = src[((size_t)g * hs + (jj < hs ? jj : jj - hs)) * nin + k];
+}
+__global__ void __launch_bounds__(NTHREADS) cg_dgrad_mfma_kernel(Problem p, BwdWs w, const float2 *dpq,
+                                                                 const unsigned short *wt) {
+  extern __shared__ __attribute__((aligned(16))) unsigned short dsm[];
+  const int g = blockIdx.x, b = blockIdx.y, t0 = blockIdx.z * MT, hs = p.bs, H = p.D / 2, nin = 2 * hs;
+  const int nt = min(MT, p.T - t0), xs = nin + 8;
+  unsigned short *a_hi = dsm, *a_lo = dsm + MT * xs;   // [MT][nin + 8] each: dp of the hs outputs, then dq
+  for (int jc = threadIdx.x; jc < hs; jc += NTHREADS) {   // a thread walks one output column down the tile
+    const float2 *src = dpq + ((size_t)b * p.T + t0) * H + (size_t)g * hs + jc;
+#pragma unroll 8
+    for (int tt = 0; tt < MT; ++tt) {
+      const float2 v = tt < nt ? src[(size_t)tt * H] : make_float2(0.f, 0.f);
+      unsigned hi, lo;
+      mfma::split_bf16(v.x, v.y, hi, lo);
+      a_hi[tt * xs + jc] = (unsigned short)(hi & 0xffff);
+      a_hi[tt * xs + hs + jc] = (unsigned short)(hi >> 16);
+      a_lo[tt * xs + jc] = (unsigned short)(lo & 0xffff);
+      a_lo[tt * xs + hs + jc] = (unsigned short)(lo >> 16);
+    }
+  }
+  __syncthreads();
+  const int lane = threadIdx.x & 63, hf = lane >> 5, j = lane & 31, wv = threadIdx.x >> 6;
+  const int aoff = mfma_arow(j) * xs + hf * 8;
+  for (int cb = wv; cb * 32 < nin; cb += NTHREADS / 64) {
+    const int k = cb * 32 + j;   // (nin is a multiple of 32)
+    const mfma::bf16x8 *wk = (const mfma::bf16x8 *)(wt + ((size_t)g * nin + k) * nin + hf * 8);
+    mfma::f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    for (int ks = 0; ks < nin / 16; ++ks) {
+      const mfma::bf16x8 bw = wk[ks * 2];
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const mfma::bf16x8 *)(a_hi + aoff + ks * 16), bw, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const mfma::bf16x8 *)(a_lo + aoff + ks * 16), bw, acc, 0, 0, 0);
+    }
+    float *dst = w.dx + ((size_t)b * p.T + t0 + hf * 16) * p.D + cg_channel(g, hs, H, k);
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (hf * 16 + r < nt) dst[(size_t)r * p.D] += acc[r];
+  }
+}
+
 // Pass 4: dW_a[g][j][k] = sum_{b,t} dp[b,t,j] x[b,t,chan(k)], dW_x likewise with dq. One
 // workgroup per 32x32 output tile of one block, 16x16 threads with 2x2 outputs each, rows
 // streamed through LDS 32 at a time; the chunks of 32 rows are added up with compensation.
@@ -732,6 +786,12 @@ static int cg_wgrad_slices(size_t rows, int nb) {
   if ((size_t)S > most) S = (int)most;
   return S < 1 ? 1 : S;
 }
+// workspace of the matrix-core passes behind the partial sums of pass 1b: the wgrad pass's partial
+// sums, then the transposed weights of the dgrad pass (sized whatever the storage type turns out to be)
+static size_t cg_wgrad_part_bytes(size_t rows, int nb, int hs) {
+  return cg_wgrad_mfma_ok(hs) ? align256((size_t)cg_wgrad_slices(rows, nb) * nb * 4 * hs * hs * sizeof(float)) : 0;
+}
+static size_t cg_wt_bytes(int nb, int hs) { return (hs % 16 == 0 && hs <= 256) ? align256((size_t)nb * 4 * hs * hs * 2) : 0; }
 
 template <typename K>
 hipError_t allow_lds(K kernel, size_t bytes) {
@@ -801,14 +861,25 @@ hipError_t cg_backward_t(const Problem &p, hipStream_t s) {
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const RowOuts outs = {{p.g.db_a, p.g.db_x, p.g.dLambda, p.dtheta, nullptr}};
   if ((e = launch_reduce_parts(parts, p.B * nz, 4, H, outs, s)) != hipSuccess) return e;
-  if ((e = allow_lds(cg_bwd_dgrad_kernel<AT>, lds2)) != hipSuccess) return e;
-  hipLaunchKernelGGL(cg_bwd_dgrad_kernel<AT>, dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds2, s, p, w, adpq);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  float *wpart = (float *)((char *)parts + align256((size_t)p.B * nz * 4 * H * sizeof(float)));
+  if (sizeof(AT) == 2 && cg_mfma_ok(p)) {
+    const int nin = 2 * hs, mtile = (p.T + MT - 1) / MT;
+    unsigned short *wt = (unsigned short *)((char *)wpart + cg_wgrad_part_bytes((size_t)p.B * p.T, p.nb, hs));
+    const size_t nw = (size_t)p.nb * nin * nin, ldsd = (size_t)2 * MT * (nin + 8) * 2;
+    hipLaunchKernelGGL(cg_wt_kernel, dim3((unsigned)((nw + NTHREADS - 1) / NTHREADS)), dim3(NTHREADS), 0, s, p, wt);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = allow_lds(cg_dgrad_mfma_kernel, ldsd)) != hipSuccess) return e;
+    hipLaunchKernelGGL(cg_dgrad_mfma_kernel, dim3(p.nb, p.B, mtile), dim3(NTHREADS), ldsd, s, p, w, adpq, wt);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  } else {
+    if ((e = allow_lds(cg_bwd_dgrad_kernel<AT>, lds2)) != hipSuccess) return e;
+    hipLaunchKernelGGL(cg_bwd_dgrad_kernel<AT>, dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds2, s, p, w, adpq);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   if (sizeof(AT) == 2 && cg_wgrad_mfma_ok(hs)) {
     const size_t rows = (size_t)p.B * p.T;
     const int S = cg_wgrad_slices(rows, p.nb), nin = 2 * hs;
     const int rows_per = (int)(((rows + S - 1) / S + MT - 1) / MT * MT);
-    float *wpart = (float *)((char *)parts + align256((size_t)p.B * nz * 4 * H * sizeof(float)));
     const size_t ldsw = (size_t)4 * nin * WRS * 2;
     if ((e = allow_lds(cg_wgrad_mfma_kernel, ldsw)) != hipSuccess) return e;
     hipLaunchKernelGGL(cg_wgrad_mfma_kernel, dim3(p.nb, S), dim3(512), ldsw, s, p, w, adpq, wpart, rows_per);
@@ -835,10 +906,8 @@ size_t cg_backward_ws_bytes(int B, int T, int D, int nb) {   // ... + the recomp
   const size_t n = (size_t)B * T * D * sizeof(float);
   const size_t parts = (size_t)B * cg_point_rows(T) * 4 * (D / 2) * sizeof(float);
   const int hs = D / 2 / nb;
-  // (the matrix-core wgrad pass's partial sums, whatever the storage type turns out to be)
-  const size_t wpart = cg_wgrad_mfma_ok(hs) ? (size_t)cg_wgrad_slices((size_t)B * T, nb) * nb * 4 * hs * hs * sizeof(float) : 0;
   return backward_generic_ws_bytes(B, T, D, nb) + 2 * ((n + 255) & ~(size_t)255) + ((parts + 255) & ~(size_t)255) +
-         ((wpart + 255) & ~(size_t)255);
+         cg_wgrad_part_bytes((size_t)B * T, nb, hs) + cg_wt_bytes(nb, hs);
 }
 
 hipError_t launch_cg_forward(const Problem &p, bool bf, hipStream_t s) {
