@@ -170,8 +170,10 @@ __global__ void __launch_bounds__(NTHREADS) cg_coeff_kernel(Problem p, int t_lo,
 }
 // The same pass with the gate products on the matrix cores (bf16 storage, hs a multiple of 16):
 // a workgroup of four waves takes 32 steps of one (gate block, sequence); the x tile sits in LDS
-// in fp32 (for b~_t and the parked copy) and in half precision (the products' row operand, 11
-// significant bits; the bf16 weights convert to half precision exactly from 6.1e-5 up); a wave
+// in fp32 (for b~_t and the parked copy) and as a half-precision high part + low part (the
+// products' row operand, two products per fragment: with the high part alone, 11 significant bits,
+// the phase errors of a~_t added up over 2048 steps to 3e-2 in dW_a and du at width 2560; the
+// bf16 weights convert to half precision exactly from 6.1e-5 up); a wave
 // owns 32 complex channels at a time and multiplies the tile by those channels' rows of W_a and
 // of W_x, fetched as 16-byte fragments straight from the matrices (v_mfma_f32_32x32x16_f16), so
 // that a lane ends up with both pre-activations of one channel for 16 steps.
@@ -185,7 +187,8 @@ __global__ void __launch_bounds__(NTHREADS) cg_coeff_mfma_kernel(Problem p, int 
   const int g = blockIdx.x, b = blockIdx.y, t0 = t_lo + blockIdx.z * MT, hs = p.bs, H = p.D / 2, nin = 2 * hs;
   const int nt = min(MT, t_hi - t0), tc = t_hi - t_lo, xsh = nin + 8;
   float *xf = smem;                                    // [MT][nin] fp32
-  _Float16 *xh = (_Float16 *)(smem + MT * nin);        // [MT][nin + 8] half precision
+  _Float16 *xh = (_Float16 *)(smem + MT * nin);        // [MT][nin + 8] half precision, high part
+  _Float16 *xl = xh + MT * xsh;                        // ... and low part (x = high + low to 22 bits)
   for (int k = threadIdx.x; k < nin; k += NTHREADS) {   // a thread walks one input column down the tile's steps
     const int d = cg_channel(g, hs, H, k);
     const bool conv = p.conv_w != nullptr;
@@ -199,7 +202,9 @@ __global__ void __launch_bounds__(NTHREADS) cg_coeff_mfma_kernel(Problem p, int 
       const float u0 = tt < nt ? input_at<bf16>(p, b, t0 + tt, d) : 0.f;
       const float v = tt < nt ? fmaf(w0, u0, fmaf(w1, u1, fmaf(w2, u2, fmaf(w3, u3, cb)))) : 0.f;
       xf[tt * nin + k] = v;
-      xh[tt * xsh + k] = (_Float16)v;
+      const _Float16 vh = (_Float16)v;
+      xh[tt * xsh + k] = vh;
+      xl[tt * xsh + k] = (_Float16)(v - (float)vh);
       u3 = u2;
       u2 = u1;
       u1 = u0;
@@ -222,9 +227,12 @@ __global__ void __launch_bounds__(NTHREADS) cg_coeff_mfma_kernel(Problem p, int 
       accq[r] = bq;
     }
     for (int ks = 0; ks < nin / 16; ++ks) {
-      const mfma::f16x8 a = *(const mfma::f16x8 *)(arow + ks * 16);
-      accp = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, mfma::w_to_f16(wa[ks * 2]), accp, 0, 0, 0);
-      accq = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, mfma::w_to_f16(wx[ks * 2]), accq, 0, 0, 0);
+      const mfma::f16x8 a = *(const mfma::f16x8 *)(arow + ks * 16), al = *(const mfma::f16x8 *)(arow + MT * xsh + ks * 16);
+      const mfma::f16x8 fa = mfma::w_to_f16(wa[ks * 2]), fx = mfma::w_to_f16(wx[ks * 2]);
+      accp = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, fa, accp, 0, 0, 0);
+      accq = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, fx, accq, 0, 0, 0);
+      accp = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, fa, accp, 0, 0, 0);
+      accq = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, fx, accq, 0, 0, 0);
     }
     if (!ok) continue;
     // (base-2 exponentials and the hardware's sine / cosine of an angle in revolutions)
@@ -806,7 +814,7 @@ hipError_t cg_forward_two_pass(const Problem &p, int tcmax, float2 *A, float2 *B
                                float *xk = nullptr, float *pq = nullptr) {
   const int hs = p.bs, H = p.D / 2;
   const bool on_mfma = sizeof(AT) == 2 && cg_mfma_ok(p);
-  const size_t lds = on_mfma ? (size_t)MT * 2 * hs * 4 + (size_t)MT * (2 * hs + 8) * 2 : (size_t)CTG * 2 * hs * sizeof(float);
+  const size_t lds = on_mfma ? (size_t)MT * 2 * hs * 4 + (size_t)2 * MT * (2 * hs + 8) * 2 : (size_t)CTG * 2 * hs * sizeof(float);
   hipError_t e = on_mfma ? allow_lds(cg_coeff_mfma_kernel<KEEP>, lds) : allow_lds(cg_coeff_kernel<AT, KEEP>, lds);
   if (e != hipSuccess) return e;
   const int sblocks = (int)(((size_t)p.B * H + NTHREADS - 1) / NTHREADS), steps = on_mfma ? MT : CTG;

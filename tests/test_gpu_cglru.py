@@ -108,3 +108,25 @@ def test_cg_forward_in_pieces_equals_one_shot():
     assert gen.rel_err(np.concatenate(ys, axis=1), rn.to_host(y_all)) < 1e-2
     assert gen.rel_err(rn.to_host(h), rn.to_host(hT_all)) < 1e-2
     np.testing.assert_array_equal(rn.to_host(state), rn.to_host(st_all))
+
+
+def test_cg_at_the_paper_s_block_shape_full_width():
+    """The complex-gated layer at width 2560 in 10 blocks (hs = 128, the [128][256] gate matrices the
+    matrix-core passes are built for), 2048 steps: forward and every gradient against the oracle."""
+    rn = runner()
+    B, T, D, nb, act = 2, 2048, 2560, 10, "bf16"
+    inp = gen.make_cg_inputs(B, T, D, nb, act=act, seed=11, h0=True, bias=True, dy=True)
+    dp = rn.CgDeviceProblem(inp, B, T, D, nb, act)
+    u, h0 = rn.to_device(inp["u"], act), rn.to_device(inp["h0"], "f32")
+    y, hT, _ = dp.forward(u, h0=h0)
+    g = dp.backward(u, rn.to_device(inp["dy"], act), h0=h0, dhT=rn.to_device(inp["dhT"], "f32"))
+    q = f64(inp)
+    kw = dict(conv_w=q["conv_w"], conv_b=q["conv_b"])
+    y_ref, hT_ref, _ = oracle.cg_forward(q["u"], *params(q), h0=q["h0"], **kw)
+    assert gen.rel_err(rn.to_host(y), y_ref) < TOL[act]
+    assert gen.rel_err(rn.to_host(hT), hT_ref) < TOL[act]
+    ref = oracle.cg_backward(q["u"], *params(q), q["dy"], h0=q["h0"], dhT=q["dhT"], **kw)
+    errs = {k: gen.rel_err(rn.to_host(g[k]), ref[k]) for k in ref}
+    print("errors:", {k: float("%.3g" % v) for k, v in errs.items()})
+    for k in ref:
+        assert errs[k] < TOL[act], (k, errs)
