@@ -1,6 +1,6 @@
 """Per-workload timing report of the Conv1D -> RG-LRU path on one MI355X.
 
-    python -m paper_2402_19427_amd.workloads [--configs C0,C1,C2,C3,C4,SCAN,MERGE,NB16] [--json]
+    python -m paper_2402_19427_amd.workloads [--configs C0,C1,C2,C3,C4,SCAN,MERGE,NB16,CG] [--json]
 
 For each of the five synthetic workloads it times the calls that workload is about (forward;
 forward and backward for the training shape; the single-token decode step for the decode shape,
@@ -331,9 +331,71 @@ def run_merge_workload(dev, out, names=("C1", "C2", "C3", "C4"), steps=1000):
         torch.cuda.empty_cache()
 
 
+def run_cg_workload(dev, out, sizes=((8, 2048, 2560, 10), (16, 4096, 4096, 16)), steps=200):
+    """The complex-gated variant (Appendix B), bf16 storage: forward (with its optional scratch) and
+    backward at C1's and C4's sizes, a decode step at batch 256. Algorithmic bytes: u in, y out
+    (backward: u, dy in, du out - this backward takes no y), the [hs][2 hs] gate matrices; gate FLOPs
+    2 (D / nb) per element forward, three times that backward."""
+    sp = torch.cuda.current_stream().cuda_stream
+    for (B, T, D, nb) in sizes:
+        inp = gen.make_cg_inputs(1, 8, D, nb, act="bf16", seed=3)       # parameters only
+        cg = rn.CgDeviceProblem(inp, B, T, D, nb, "bf16", device=dev)
+        sh = cg.shape()
+        H, hs = D // 2, D // 2 // nb
+        draws = rn.SeededDraws(300 + D, dev)
+        u, dy = draws.normal(B, T, D, act="bf16"), draws.normal(B, T, D, act="bf16")
+        y = torch.empty_like(u)
+        hT = torch.empty(B, D, dtype=torch.float32, device=dev)
+        st = torch.empty(B, 3, D, dtype=torch.bfloat16, device=dev)
+        n_f = R.rglru_workspace_bytes(sh, R.OP_CG_FORWARD)
+        ws_f = torch.empty(max(n_f, 256), dtype=torch.uint8, device=dev)
+        n_b = R.rglru_workspace_bytes(sh, R.OP_CG_BACKWARD)
+        ws_b = torch.empty(max(n_b, 256), dtype=torch.uint8, device=dev)
+        f32 = lambda *shape: torch.empty(*shape, dtype=torch.float32, device=dev)
+        g = [f32(nb, hs, 2 * hs), f32(nb, hs, 2 * hs), f32(H), f32(H), f32(H), f32(H), f32(4, D), f32(D)]
+        pg = R.make_cg_param_grads(*g)
+        du, dh0 = torch.empty_like(u), f32(B, D)
+        size = "B%d T%d D%d nb%d" % (B, T, D, nb)
+        N, wcg, vec = B * T * D, 2 * nb * hs * 2 * hs * 2, 9 * H * 4 + 5 * D * 4
+        fwd_bytes = 4 * N + wcg + vec + 10 * B * D
+        bwd_bytes = 6 * N + wcg + vec + 2 * nb * hs * 2 * hs * 4
+        fwd_flops = 2 * (D // nb) * N
+
+        def fwd(i):
+            R.rglru_cg_forward(sh, cg.params, u, None, None, 0, y, hT, st, ws_f, n_f, sp)
+
+        def bwd(i):
+            R.rglru_cg_backward(sh, cg.params, u, None, None, 0, dy, None, du, dh0, pg, ws_b, n_b, sp)
+
+        iters = 30 if B * T * D < (1 << 27) else 10
+        ms = time_calls(fwd, 1, iters, 3)
+        out.append(row("CG", "forward, " + size, "1 buffer set", ms, B * T, fwd_bytes, fwd_flops))
+        ms = time_calls(bwd, 1, iters, 2)
+        out.append(row("CG", "backward, " + size, "1 buffer set", ms, B * T, bwd_bytes, 3 * fwd_flops))
+        del ws_f, ws_b, u, dy, y, du
+        torch.cuda.empty_cache()
+    B, D, nb = 256, 2560, 10
+    inp = gen.make_cg_inputs(1, 8, D, nb, act="bf16", seed=3)
+    cg = rn.CgDeviceProblem(inp, B, 1, D, nb, "bf16", device=dev)
+    draws = rn.SeededDraws(77, dev)
+    u_t, h = draws.normal(B, D, act="bf16"), draws.normal(B, D)
+    ring = draws.normal(B, 3, D, act="bf16")
+    y_t = torch.empty_like(u_t)
+    sh = cg.shape(T=1, B=B)
+    pos = [3]
+
+    def step(i):
+        R.rglru_cg_decode_step(sh, cg.params, u_t, h, ring, pos[0], y_t, sp)
+        pos[0] += 1
+
+    ms = time_calls(step, 1, steps, 10)
+    out.append(row("CG", "decode step, B%d D%d nb%d, per launch" % (B, D, nb), "hot: 1 buffer set", ms, B,
+                   alg_bytes("decode", B, 1, D, nb, 2) - 2 * nb * (D // nb) * (D // nb), 2 * (D // nb) * B * D))
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--configs", default="C0,C1,C2,C3,C4,SCAN,MERGE,NB16")
+    ap.add_argument("--configs", default="C0,C1,C2,C3,C4,SCAN,MERGE,NB16,CG")
     ap.add_argument("--scan-lengths", default="1024,4096,16384,65536")
     ap.add_argument("--json", action="store_true", help="print one JSON object per row instead of the table")
     args = ap.parse_args()
@@ -347,6 +409,8 @@ def main():
             run_scan_workload(dev, out, tuple(int(x) for x in args.scan_lengths.split(",")))
         elif name == "MERGE":
             run_merge_workload(dev, out)
+        elif name == "CG":
+            run_cg_workload(dev, out)
         elif name == "NB16":
             c1 = gen.CONFIGS["C1"]
             run_sequence_workload(dataclasses.replace(c1, name="NB16", nb=16, kind="train"), dev, out)
