@@ -117,6 +117,44 @@ def test_forward_in_pieces_equals_one_shot_and_states_may_alias(act, D, nb):
     np.testing.assert_array_equal(gen.chrono_from_ring(rn.to_host(state), T), st_ref)
 
 
+def test_a_long_prompt_in_windows_equals_the_capped_call_and_carries_states_in_place():
+    """A single long sequence runs as contiguous windows in two passes. The same call with the
+    time slices capped at one (a single workgroup per unit walks the sequence) must agree to
+    rounding; the call continues from a carried state and Conv1D ring, which may be given in place."""
+    import paper_2402_19427_amd as R
+    rn = runner()
+    B, T, D, nb, act = 1, 12700, 512, 2, "bf16"
+    inp = gen.make_inputs(B, T, D, nb, act=act, seed=31, h0=True, state=True, bias=True)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    u = rn.to_device(inp["u"], act)
+    pos0 = 4
+    ring = rn.to_device(gen.ring_from_chrono(inp["state"], pos0), act)
+    h0 = rn.to_device(inp["h0"], "f32")
+    y, hT, st = dp.forward(u, h0=h0, state_in=ring, pos0=pos0)
+    R.rglru_set_max_time_slices(1)
+    try:
+        y1, hT1, st1 = dp.forward(u, h0=h0, state_in=ring, pos0=pos0)
+    finally:
+        R.rglru_set_max_time_slices(0)
+    assert gen.rel_err(rn.to_host(y), rn.to_host(y1)) < 1e-2      # (bf16 steps of y here and there)
+    assert gen.rel_err(rn.to_host(hT), rn.to_host(hT1)) < 1e-5
+    assert torch_equal(st, st1)
+    # states in place
+    sh = dp.shape()
+    ws, n = dp.workspace(sh, R.OP_FORWARD)
+    h_io, ring_io, y2 = h0.clone(), ring.clone(), dp.empty_act(B, T, D)
+    R.rglru_forward(sh, dp.params, u, h_io, ring_io, pos0, y2, h_io, ring_io, ws, n)
+    assert torch_equal(h_io, hT) and torch_equal(ring_io, st) and torch_equal(y2, y)
+    y_ref, hT_ref, st_ref = oracle_forward(inp, h0=inp["h0"], state=inp["state"])
+    assert gen.rel_err(rn.to_host(y), y_ref) < TOL[act]
+    assert gen.rel_err(rn.to_host(hT), hT_ref) < TOL[act]
+
+
+def torch_equal(a, b):
+    import torch
+    return bool(torch.equal(a, b))
+
+
 def test_forward_zero_length_passes_states_through():
     rn = runner()
     B, D, nb = 2, 32, 2
