@@ -405,6 +405,41 @@ def test_whole_step_replays_as_a_hip_graph():
             assert torch.equal(v, eager[k]), (rep, k)
 
 
+def test_long_prompt_forward_replays_as_a_hip_graph():
+    """The windows of a single long prompt (ring pass, aggregate pass, chain, forward proper) captured
+    into a HIP graph: every replay gives the bits of the eager run, whatever the workspace held."""
+    import torch
+    import paper_2402_19427_amd as R
+    rn = runner()
+    B, T, D, nb, act = 1, 12500, 256, 1, "bf16"
+    inp = gen.make_inputs(B, T, D, nb, act=act, seed=23, h0=True)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    u, h0 = rn.to_device(inp["u"], act), rn.to_device(inp["h0"], "f32")
+    sh = dp.shape()
+    ws, n = dp.workspace(sh, R.OP_FORWARD)
+    y, hT, st = dp.empty_act(B, T, D), dp.empty_f32(B, D), dp.empty_act(B, 3, D)
+    outs = dict(y=y, hT=hT, st=st)
+
+    def step(stream):
+        R.rglru_forward(sh, dp.params, u, h0, None, 0, y, hT, st, ws, n, stream)
+
+    step(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    eager = {k: v.clone() for k, v in outs.items()}
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(torch.cuda.current_stream().cuda_stream)
+    for rep in range(3):
+        for v in outs.values():
+            v.fill_(7.0)
+        ws.fill_(rep + 1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, v in outs.items():
+            assert torch.equal(v, eager[k]), (rep, k)
+
+
 @pytest.mark.parametrize("D,nb", [(2560, 16),     # 160-channel blocks: padded tile, backward on the widened copy
                                   (1024, 2)])      # 512-channel blocks: forward and decode as separate kernels
 def test_merge_step_replays_as_a_hip_graph(D, nb):
