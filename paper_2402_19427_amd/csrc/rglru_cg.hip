@@ -272,6 +272,172 @@ __global__ void __launch_bounds__(NTHREADS) cg_coeff_mfma_kernel(Problem p, int 
 static bool cg_mfma_ok(const Problem &p) {
   return p.bs % 16 == 0 && p.bs <= 256 && ((uintptr_t)p.W_a % 16) == 0 && ((uintptr_t)p.W_x % 16) == 0;
 }
+// Fused forward (bf16 storage, hs = 32, 64, 96 or 128; needs no scratch): one workgroup of four
+// waves per (gate block, sequence) walks the sequence in tiles of 32 steps and never parks the scan's
+// coefficients. Per tile: the thread of input column k turns 32 prefetched inputs into Conv1D
+// outputs (its last three inputs stay in registers from tile to tile); the gate products as in
+// cg_coeff_mfma_kernel, a wave owning 32 complex channels; then every lane has a~_t, b~_t of one
+// channel for 16 consecutive steps and runs the complex recurrence twice - from zero for its run's
+// aggregate (product of a~_t, end state), which the two lane halves exchange, then from the true
+// incoming state, writing y. The state stays in registers between tiles.
+// (A variant that also parks what the backward wants - x, the pre-activations, a~_t, fp32 states -
+// ran out of registers and measured slower than the two passes; the backward recomputes with those.)
+__global__ void __launch_bounds__(NTHREADS) cg_fused_kernel(Problem p) {
+  extern __shared__ float smem[];
+  const int g = blockIdx.x, b = blockIdx.y, hs = p.bs, H = p.D / 2, nin = 2 * hs, xsh = nin + 8;
+  float *xf = smem;
+  _Float16 *xh = (_Float16 *)(smem + MT * nin), *xl = xh + MT * xsh;
+  const int T = p.T, ntile = (T + MT - 1) / MT;
+  // ---- this thread's input column
+  const int k = threadIdx.x;
+  const bool col = k < nin, conv = p.conv_w != nullptr;
+  const int dcol = cg_channel(g, hs, H, col ? k : 0);
+  const float w0 = conv ? p.conv_w[dcol] : 1.f, w1 = conv ? p.conv_w[(size_t)p.D + dcol] : 0.f;
+  const float w2 = conv ? p.conv_w[(size_t)2 * p.D + dcol] : 0.f, w3 = conv ? p.conv_w[(size_t)3 * p.D + dcol] : 0.f;
+  const float cbias = (conv && p.conv_b) ? p.conv_b[dcol] : 0.f;
+  float u1 = (conv && col) ? input_at<bf16>(p, b, -1, dcol) : 0.f, u2 = (conv && col) ? input_at<bf16>(p, b, -2, dcol) : 0.f;
+  float u3 = (conv && col) ? input_at<bf16>(p, b, -3, dcol) : 0.f;
+  const bf16 *ucol = (const bf16 *)p.u + (size_t)b * T * p.D + dcol;
+  float un[MT];
+  auto fetch = [&](int t0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int tt = 0; tt < MT; ++tt) {   // (no load under a condition: the compiler would wait for each on the spot;
+                                        // steps past the end re-read the last row and are dropped by the Conv1D below)
+      const int t = t0 + tt < T ? t0 + tt : T - 1;
+      un[tt] = ldf(ucol, (size_t)t * p.D);
+    }
+  };
+  // ---- this lane's complex channel
+  const int lane = threadIdx.x & 63, hf = lane >> 5, j = lane & 31, wv = threadIdx.x >> 6;
+  const bool active = wv * 32 < hs;
+  const int jj = wv * 32 + j, h = g * hs + (active ? jj : 0);
+  const _Float16 *arow = xh + mfma_arow(j) * xsh + hf * 8;
+  // this channel's rows of W_a and W_x stay in registers for the whole sequence (a wave runs alone
+  // on its SIMD here, so it has the whole register file, and nothing would hide the latency of
+  // fetching them per tile)
+  const int nks = nin / 16;
+  constexpr int RES = 16;   // K-steps of the weights kept in registers (all: 0 / 8 / 12 measured 50 / 18 / 10 % slower)
+  mfma::f16x8 wra[RES > 0 ? RES : 1], wrx[RES > 0 ? RES : 1];
+  const mfma::bf16x8 *wa = (const mfma::bf16x8 *)((const unsigned short *)p.W_a + (size_t)h * nin + hf * 8);
+  const mfma::bf16x8 *wx = (const mfma::bf16x8 *)((const unsigned short *)p.W_x + (size_t)h * nin + hf * 8);
+#pragma unroll
+  for (int ks = 0; ks < RES; ++ks) {
+    wra[ks] = mfma::w_to_f16(wa[(ks < nks ? ks : 0) * 2]);
+    wrx[ks] = mfma::w_to_f16(wx[(ks < nks ? ks : 0) * 2]);
+  }
+  const float bp = p.b_a[h], bq = p.b_x[h];
+  const float l2cs = -p.c * softplus_f(-p.Lambda[h]) * mfma::LOG2E, rev = p.c * p.theta[h] * 0.15915494309189535f;
+  float sr = p.h0 ? p.h0[(size_t)b * p.D + h] : 0.f, si = p.h0 ? p.h0[(size_t)b * p.D + H + h] : 0.f;   // state entering the tile
+
+  if (ntile > 0) fetch(0);
+  for (int tile = 0; tile < ntile; ++tile) {
+    const int t0 = tile * MT, nt = min(MT, T - t0);
+    if (col) {
+#pragma unroll
+      for (int tt = 0; tt < MT; ++tt) {
+        const float u0 = un[tt];
+        const float v = tt < nt ? fmaf(w0, u0, fmaf(w1, u1, fmaf(w2, u2, fmaf(w3, u3, cbias)))) : 0.f;
+        xf[tt * nin + k] = v;
+        const _Float16 vh = (_Float16)v;
+        xh[tt * xsh + k] = vh;
+        xl[tt * xsh + k] = (_Float16)(v - (float)vh);
+        u3 = u2;
+        u2 = u1;
+        u1 = u0;
+      }
+    }
+    __syncthreads();
+    if (tile + 1 < ntile) fetch(t0 + MT);   // lands during the products and the recurrence
+    if (active) {
+      mfma::f32x16 accp, accq;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        accp[r] = bp;
+        accq[r] = bq;
+      }
+      // (the K-steps that are not resident: all fragments of the tile requested up front)
+      mfma::bf16x8 sa[RES < 16 ? 16 - RES : 1], sx[RES < 16 ? 16 - RES : 1];
+#pragma unroll
+      for (int ks = RES; ks < 16; ++ks) {
+        sa[ks - RES] = wa[(ks < nks ? ks : 0) * 2];
+        sx[ks - RES] = wx[(ks < nks ? ks : 0) * 2];
+      }
+#pragma unroll
+      for (int ks = 0; ks < 16; ++ks) {
+        if (ks < nks) {
+          const mfma::f16x8 a = *(const mfma::f16x8 *)(arow + ks * 16), al = *(const mfma::f16x8 *)(arow + MT * xsh + ks * 16);
+          const mfma::f16x8 fa = ks < RES ? wra[ks < RES ? ks : 0] : mfma::w_to_f16(sa[ks >= RES ? ks - RES : 0]);
+          const mfma::f16x8 fx = ks < RES ? wrx[ks < RES ? ks : 0] : mfma::w_to_f16(sx[ks >= RES ? ks - RES : 0]);
+          accp = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, fa, accp, 0, 0, 0);
+          accq = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, fx, accq, 0, 0, 0);
+          accp = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, fa, accp, 0, 0, 0);
+          accq = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, fx, accq, 0, 0, 0);
+        }
+      }
+      // gates, coefficients of this lane's 16 steps, and their aggregate from a zero state
+      // (kept in registers between the two runs: parked in LDS instead they cost 10 % more time than
+      // the spills they avoid)
+      float car[16], cai[16], cbr[16], cbi[16];
+      float Pr = 1.f, Pi = 0.f, Hr = 0.f, Hi = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int tt = hf * 16 + r;
+        const float gr = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-accp[r] * mfma::LOG2E));
+        const float gi = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-accq[r] * mfma::LOG2E));
+        const float l2 = l2cs * gr, mod = __builtin_amdgcn_exp2f(l2);
+        float ar = mod * __builtin_amdgcn_cosf(rev * gr), ai = mod * __builtin_amdgcn_sinf(rev * gr);
+        const float gain = __builtin_amdgcn_sqrtf(mfma::one_minus_sq(mod, l2)) * gi;
+        float br = gain * xf[tt * nin + jj], bi = gain * xf[tt * nin + hs + jj];
+        if (tt >= nt) {   // past the end of the sequence: the state passes through
+          ar = 1.f; ai = 0.f; br = 0.f; bi = 0.f;
+        }
+        car[r] = ar; cai[r] = ai; cbr[r] = br; cbi[r] = bi;
+        const float nHr = fmaf(ar, Hr, fmaf(-ai, Hi, br)), nHi = fmaf(ar, Hi, fmaf(ai, Hr, bi));
+        const float nPr = fmaf(ar, Pr, -ai * Pi), nPi = fmaf(ar, Pi, ai * Pr);
+        Hr = nHr; Hi = nHi; Pr = nPr; Pi = nPi;
+      }
+      // lane halves: lower = steps 0..15, upper = 16..31
+      const float oPr = __shfl_xor(Pr, 32), oPi = __shfl_xor(Pi, 32), oHr = __shfl_xor(Hr, 32), oHi = __shfl_xor(Hi, 32);
+      const float Plr = hf ? oPr : Pr, Pli = hf ? oPi : Pi, Hlr = hf ? oHr : Hr, Hli = hf ? oHi : Hi;   // lower half's
+      const float Pur = hf ? Pr : oPr, Pui = hf ? Pi : oPi, Hur = hf ? Hr : oHr, Hui = hf ? Hi : oHi;   // upper half's
+      // state after the lower half's steps, then after the tile
+      const float mr = fmaf(Plr, sr, fmaf(-Pli, si, Hlr)), mi = fmaf(Plr, si, fmaf(Pli, sr, Hli));
+      const float er = fmaf(Pur, mr, fmaf(-Pui, mi, Hur)), ei = fmaf(Pur, mi, fmaf(Pui, mr, Hui));
+      float hr = hf ? mr : sr, hi = hf ? mi : si;   // state entering this lane's run
+      bf16 *yo = (bf16 *)p.y + ((size_t)b * T + t0 + hf * 16) * p.D + h;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float nr = fmaf(car[r], hr, fmaf(-cai[r], hi, cbr[r])), ni = fmaf(car[r], hi, fmaf(cai[r], hr, cbi[r]));
+        hr = nr;
+        hi = ni;
+        if (hf * 16 + r < nt && jj < hs) {
+          stf(yo, (size_t)r * p.D, hr);
+          stf(yo, (size_t)r * p.D + H, hi);
+        }
+      }
+      sr = er;
+      si = ei;
+    }
+    __syncthreads();   // the tile is consumed before the next Conv1D outputs overwrite it
+  }
+  if (p.hT && active && hf == 0 && jj < hs) {
+    p.hT[(size_t)b * p.D + h] = sr;
+    p.hT[(size_t)b * p.D + H + h] = si;
+  }
+}
+// whether the fused forward takes this problem (bf16 storage is the caller's to check)
+static bool cg_fused_ok(const Problem &p) {
+  return p.bs % 32 == 0 && p.bs <= 128 && ((uintptr_t)p.W_a % 16) == 0 && ((uintptr_t)p.W_x % 16) == 0 && p.B <= 65535;
+}
+static hipError_t launch_cg_fused(const Problem &p, hipStream_t s) {
+  const size_t lds = (size_t)MT * 2 * p.bs * 4 + (size_t)2 * MT * (2 * p.bs + 8) * 2;
+  if (lds > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void *)cg_fused_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(cg_fused_kernel, dim3(p.nb, p.B), dim3(NTHREADS), lds, s, p);
+  return hipGetLastError();
+}
 template <typename OT>
 __global__ void __launch_bounds__(NTHREADS) cg_scan_kernel(Problem p, int t_lo, int t_hi, const float2 *A,
                                                            const float2 *Bv, const float *h_in, float *h_out) {
@@ -919,6 +1085,7 @@ size_t cg_backward_ws_bytes(int B, int T, int D, int nb) {   // ... + the recomp
 }
 
 hipError_t launch_cg_forward(const Problem &p, bool bf, hipStream_t s) {
+  if (bf && cg_fused_ok(p)) return launch_cg_fused(p, s);
   // with the optional scratch (the real layer's layout: a 256-byte cell, the state between chunks,
   // two coefficient arrays for a chunk of steps) and more than one tile of steps: two passes
   if (p.ws && p.T > GT && ((uintptr_t)p.ws % 256) == 0 && p.ws_bytes >= forward_generic_ws_bytes(p.B, p.T, p.D)) {
