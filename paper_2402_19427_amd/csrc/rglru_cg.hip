@@ -197,9 +197,15 @@ __global__ void __launch_bounds__(NTHREADS) cg_coeff_mfma_kernel(Problem p, int 
     const float cb = (conv && p.conv_b) ? p.conv_b[d] : 0.f;
     float u1 = conv ? input_at<bf16>(p, b, t0 - 1, d) : 0.f, u2 = conv ? input_at<bf16>(p, b, t0 - 2, d) : 0.f;
     float u3 = conv ? input_at<bf16>(p, b, t0 - 3, d) : 0.f;
-#pragma unroll 8
+    // (no load under a condition - the compiler waits for such a load on the spot: steps past the
+    // end re-read the last row and are dropped below)
+    const bf16 *ucol = (const bf16 *)p.u + (size_t)b * p.T * p.D + d;
+    float un[MT];
+#pragma unroll
+    for (int tt = 0; tt < MT; ++tt) un[tt] = ldf(ucol, (size_t)(t0 + tt < p.T ? t0 + tt : p.T - 1) * p.D);
+#pragma unroll
     for (int tt = 0; tt < MT; ++tt) {
-      const float u0 = tt < nt ? input_at<bf16>(p, b, t0 + tt, d) : 0.f;
+      const float u0 = un[tt];
       const float v = tt < nt ? fmaf(w0, u0, fmaf(w1, u1, fmaf(w2, u2, fmaf(w3, u3, cb)))) : 0.f;
       xf[tt * nin + k] = v;
       const _Float16 vh = (_Float16)v;
@@ -614,25 +620,25 @@ __global__ void __launch_bounds__(NTHREADS) cg_bwd_point_kernel(Problem p, BwdWs
       const int cnt = min(4, t_hi - t0);
       float pv[4], qv[4], xr[4], xi[4], pr[4], pi[4];
       float2 av[4], dv[4];
+      // (no load under a condition - the compiler would wait for each on the spot: steps past the
+      // run re-read its last step, step 0 reads the state of step 0 in place of the one before it
+      // and takes h0 afterwards)
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
-        if (k < cnt) {
-          const int t = t0 + k;
-          const size_t row = (size_t)b * p.T + t, o = row * p.D;
-          pv[k] = pq[row * H + h];
-          qv[k] = pq[(rows + row) * H + h];
-          xr[k] = w.x[o + h];
-          xi[k] = w.x[o + H + h];
-          av[k] = adpq[row * H + h];
-          dv[k] = delta[row * H + h];
-          if (t > 0) {
-            pr[k] = hs32[o - p.D + h];
-            pi[k] = hs32[o - p.D + H + h];
-          } else {
-            pr[k] = p.h0 ? p.h0[(size_t)b * p.D + h] : 0.f;
-            pi[k] = p.h0 ? p.h0[(size_t)b * p.D + H + h] : 0.f;
-          }
-        }
+        const int t = k < cnt ? t0 + k : t_hi - 1;
+        const size_t row = (size_t)b * p.T + t, o = row * p.D, op = t > 0 ? o - p.D : o;
+        pv[k] = pq[row * H + h];
+        qv[k] = pq[(rows + row) * H + h];
+        xr[k] = w.x[o + h];
+        xi[k] = w.x[o + H + h];
+        av[k] = adpq[row * H + h];
+        dv[k] = delta[row * H + h];
+        pr[k] = hs32[op + h];
+        pi[k] = hs32[op + H + h];
+      }
+      if (t0 == 0) {
+        pr[0] = p.h0 ? p.h0[(size_t)b * p.D + h] : 0.f;
+        pi[0] = p.h0 ? p.h0[(size_t)b * p.D + H + h] : 0.f;
       }
       float s_ba = 0.f, s_bx = 0.f, s_lam = 0.f, s_th = 0.f;
 #pragma unroll
