@@ -744,7 +744,8 @@ __global__ void __launch_bounds__(NTHREADS) cg_dgrad_mfma_kernel(Problem p, BwdW
     const float2 *src = dpq + ((size_t)b * p.T + t0) * H + (size_t)g * hs + jc;
 #pragma unroll 8
     for (int tt = 0; tt < MT; ++tt) {
-      const float2 v = tt < nt ? src[(size_t)tt * H] : make_float2(0.f, 0.f);
+      float2 v = src[(size_t)(tt < nt ? tt : nt - 1) * H];   // (no load under a condition)
+      if (tt >= nt) v = make_float2(0.f, 0.f);
       unsigned hi, lo;
       mfma::split_bf16(v.x, v.y, hi, lo);
       a_hi[tt * xs + jc] = (unsigned short)(hi & 0xffff);
@@ -857,13 +858,15 @@ __global__ void __launch_bounds__(512) cg_wgrad_mfma_kernel(Problem p, BwdWs w, 
   auto fetch = [&](size_t r0) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const size_t row = r0 + 8 * rg + i;
-      dv[i] = (d_ok && row < r_hi) ? dsrc[row * H] : make_float2(0.f, 0.f);
+      const size_t row = r0 + 8 * rg + i;   // (no load under a condition: rows past the slice re-read its last row)
+      dv[i] = dsrc[(row < r_hi ? row : r_hi - 1) * H];
+      if (!d_ok || row >= r_hi) dv[i] = make_float2(0.f, 0.f);
     }
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const size_t row = r0 + 16 * rg2 + i;
-      xv[i] = (x_ok && row < r_hi) ? xsrc[row * p.D] : 0.f;
+      xv[i] = xsrc[(row < r_hi ? row : r_hi - 1) * p.D];
+      if (!x_ok || row >= r_hi) xv[i] = 0.f;
     }
   };
   typedef unsigned u32x4w __attribute__((ext_vector_type(4)));

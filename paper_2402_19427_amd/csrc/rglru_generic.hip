@@ -288,17 +288,26 @@ __global__ void __launch_bounds__(NTHREADS) bwd_chain_kernel(Problem p, BwdWs w)
   for (int t1 = p.T; t1 > 0; t1 -= 8) {   // steps t1-1 down to max(t1-8, 0)
     const int t_lo = t1 > 8 ? t1 - 8 : 0, cnt = t1 - t_lo;
     float pv[8], qv[8], xv[8], dyv[8], hp[8];
+    // the loads of a group do not depend on the chain: all in flight at once. (No load under a
+    // condition - the compiler waits for such a load on the spot: steps in front of the sequence
+    // re-read step 0, step 0 reads its own y in place of the one before and takes h0 afterwards.)
+    const AT *dyl = (const AT *)(p.dy_lo ? p.dy_lo : p.dy);
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {   // the loads of a group do not depend on the chain: all in flight at once
-      if (k < cnt) {
-        const int t = t1 - 1 - k;
-        const size_t o = base + (size_t)t * p.D;
-        pv[k] = w.dp[o];
-        qv[k] = w.dq[o];
-        xv[k] = w.x[o];
-        dyv[k] = ldf((const AT *)p.dy, o) + (p.dy_lo ? ldf((const AT *)p.dy_lo, o) : 0.f);
-        hp[k] = t > 0 ? ldf((const AT *)p.y_in, o - p.D) : (p.h0 ? p.h0[idx] : 0.f);
-      }
+    for (int k = 0; k < 8; ++k) {
+      const int t = k < cnt ? t1 - 1 - k : t_lo;
+      const size_t o = base + (size_t)t * p.D;
+      pv[k] = w.dp[o];
+      qv[k] = w.dq[o];
+      xv[k] = w.x[o];
+      const float lo = ldf(dyl, o);
+      dyv[k] = ldf((const AT *)p.dy, o) + (p.dy_lo ? lo : 0.f);
+      hp[k] = ldf((const AT *)p.y_in, t > 0 ? o - p.D : o);
+    }
+    if (t_lo == 0) {
+      const float h0v = p.h0 ? p.h0[idx] : 0.f;
+#pragma unroll
+      for (int k = 0; k < 8; ++k)   // (a dynamic index would put the array in scratch memory)
+        if (k == cnt - 1) hp[k] = h0v;
     }
     float s_ba = 0.f, s_bx = 0.f, s_lam = 0.f;
 #pragma unroll
