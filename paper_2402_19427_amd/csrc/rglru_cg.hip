@@ -69,7 +69,22 @@ __device__ __forceinline__ void cg_gate_rows(const Problem &p, int g, int j, con
     pa[tt] = p.b_a[h];
     qa[tt] = p.b_x[h];
   }
-  for (int k = 0; k < nin; ++k) {
+  int k = 0;
+  // four inputs at a time where the rows allow it (the same products in the same order)
+  if ((nin & 3) == 0 && (((uintptr_t)p.W_a | (uintptr_t)p.W_x) & 15) == 0) {
+    for (; k < nin; k += 4) {
+      float a4[4], x4[4];
+      ldf4(wa, k, a4);
+      ldf4(wx, k, x4);
+#pragma unroll
+      for (int tt = 0; tt < ROWS; ++tt) {
+        const float4 v = *(const float4 *)(xs + tt * nin + k);
+        pa[tt] = fmaf(a4[3], v.w, fmaf(a4[2], v.z, fmaf(a4[1], v.y, fmaf(a4[0], v.x, pa[tt]))));
+        qa[tt] = fmaf(x4[3], v.w, fmaf(x4[2], v.z, fmaf(x4[1], v.y, fmaf(x4[0], v.x, qa[tt]))));
+      }
+    }
+  }
+  for (; k < nin; ++k) {
     const float a = ldf(wa, k), x = ldf(wx, k);
 #pragma unroll
     for (int tt = 0; tt < ROWS; ++tt) {
@@ -84,7 +99,7 @@ __device__ __forceinline__ void cg_gate_rows(const Problem &p, int g, int j, con
 // OT: storage type of y (the backward recomputes the states into an fp32 array)
 template <typename AT, typename OT = AT>
 __global__ void __launch_bounds__(NTHREADS) cg_forward_kernel(Problem p) {
-  extern __shared__ float smem[];
+  extern __shared__ __attribute__((aligned(16))) float smem[];
   const int g = blockIdx.x, b = blockIdx.y, hs = p.bs, H = p.D / 2, tid = threadIdx.x;
   float *xs = smem, *hc = smem + GT * 2 * hs;   // state: [hs] real parts, [hs] imaginary parts
   for (int j = tid; j < hs; j += NTHREADS) {
@@ -138,7 +153,7 @@ constexpr int CTG = 16;
 template <typename AT, bool KEEP = false>
 __global__ void __launch_bounds__(NTHREADS) cg_coeff_kernel(Problem p, int t_lo, int t_hi, float2 *A, float2 *Bv,
                                                             float *xk = nullptr, float *pq = nullptr) {
-  extern __shared__ float smem[];
+  extern __shared__ __attribute__((aligned(16))) float smem[];
   const int g = blockIdx.x, b = blockIdx.y, t0 = t_lo + blockIdx.z * CTG, hs = p.bs, H = p.D / 2;
   const int nt = min(CTG, t_hi - t0), tc = t_hi - t_lo;
   float *xs = smem;
@@ -183,7 +198,7 @@ __device__ __forceinline__ int mfma_arow(int j) { return ((j >> 2) & 1) * 16 + (
 template <bool KEEP = false>
 __global__ void __launch_bounds__(NTHREADS) cg_coeff_mfma_kernel(Problem p, int t_lo, int t_hi, float2 *A, float2 *Bv,
                                                                  float *xk = nullptr, float *pq = nullptr) {
-  extern __shared__ float smem[];
+  extern __shared__ __attribute__((aligned(16))) float smem[];
   const int g = blockIdx.x, b = blockIdx.y, t0 = t_lo + blockIdx.z * MT, hs = p.bs, H = p.D / 2, nin = 2 * hs;
   const int nt = min(MT, t_hi - t0), tc = t_hi - t_lo, xsh = nin + 8;
   float *xf = smem;                                    // [MT][nin] fp32
@@ -289,7 +304,7 @@ static bool cg_mfma_ok(const Problem &p) {
 // (A variant that also parks what the backward wants - x, the pre-activations, a~_t, fp32 states -
 // ran out of registers and measured slower than the two passes; the backward recomputes with those.)
 __global__ void __launch_bounds__(NTHREADS) cg_fused_kernel(Problem p) {
-  extern __shared__ float smem[];
+  extern __shared__ __attribute__((aligned(16))) float smem[];
   const int g = blockIdx.x, b = blockIdx.y, hs = p.bs, H = p.D / 2, nin = 2 * hs, xsh = nin + 8;
   float *xf = smem;
   _Float16 *xh = (_Float16 *)(smem + MT * nin), *xl = xh + MT * xsh;
@@ -492,7 +507,7 @@ __global__ void __launch_bounds__(NTHREADS) cg_scan_kernel(Problem p, int t_lo, 
 // of the new token is written by the workgroup that owns the channels, after all its reads.
 template <typename AT>
 __global__ void __launch_bounds__(NTHREADS) cg_decode_kernel(Problem p) {
-  extern __shared__ float smem[];
+  extern __shared__ __attribute__((aligned(16))) float smem[];
   const int g = blockIdx.x, b0 = blockIdx.y * GT, hs = p.bs, H = p.D / 2, tid = threadIdx.x;
   const int nbat = min(GT, p.B - b0);
   float *xs = smem;
@@ -689,7 +704,7 @@ __global__ void __launch_bounds__(NTHREADS) cg_bwd_point_kernel(Problem p, BwdWs
 // Pass 2: dx[t][chan(k)] += sum_j W_a[g][j][k] dp[t][j] + W_x[g][j][k] dq[t][j]   (dpq: the (dp, dq) pairs [B*T][H])
 template <typename AT>
 __global__ void __launch_bounds__(NTHREADS) cg_bwd_dgrad_kernel(Problem p, BwdWs w, const float2 *dpq) {
-  extern __shared__ float smem[];
+  extern __shared__ __attribute__((aligned(16))) float smem[];
   const int g = blockIdx.x, b = blockIdx.y, t0 = blockIdx.z * GT, hs = p.bs, H = p.D / 2, tid = threadIdx.x;
   const int nt = min(GT, p.T - t0), nin = 2 * hs;
   float *dps = smem, *dqs = smem + GT * hs;   // [GT][hs] each

@@ -24,7 +24,23 @@ __device__ __forceinline__ void gate_rows(const Problem &p, int g, int j, const 
     pa[tt] = p.b_a[d];
     qa[tt] = p.b_x[d];
   }
-  for (int k = 0; k < bs; ++k) {
+  int k = 0;
+  // four inputs at a time where the rows allow it: one 16-byte LDS read per row and four inputs,
+  // the weights as one vector load (the same products in the same order as one by one)
+  if ((bs & 3) == 0 && (((uintptr_t)p.W_a | (uintptr_t)p.W_x) & 15) == 0) {
+    for (; k < bs; k += 4) {
+      float a4[4], x4[4];
+      ldf4(wa, k, a4);
+      ldf4(wx, k, x4);
+#pragma unroll
+      for (int tt = 0; tt < ROWS; ++tt) {
+        const float4 v = *(const float4 *)(xs + tt * bs + k);
+        pa[tt] = fmaf(a4[3], v.w, fmaf(a4[2], v.z, fmaf(a4[1], v.y, fmaf(a4[0], v.x, pa[tt]))));
+        qa[tt] = fmaf(x4[3], v.w, fmaf(x4[2], v.z, fmaf(x4[1], v.y, fmaf(x4[0], v.x, qa[tt]))));
+      }
+    }
+  }
+  for (; k < bs; ++k) {
     const float a = ldf(wa, k), x = ldf(wx, k);
 #pragma unroll
     for (int tt = 0; tt < ROWS; ++tt) {
@@ -80,7 +96,7 @@ __global__ void __launch_bounds__(NTHREADS) state_update_kernel(Problem p) {
 // kept per channel in LDS.
 template <typename AT>
 __global__ void __launch_bounds__(NTHREADS) forward_kernel(Problem p) {
-  extern __shared__ float smem[];
+  extern __shared__ __attribute__((aligned(16))) float smem[];
   const int g = blockIdx.x, b = blockIdx.y, bs = p.bs, tid = threadIdx.x;
   float *xs = smem, *hc = smem + GT * bs;
   for (int j = tid; j < bs; j += NTHREADS)
@@ -124,7 +140,7 @@ __global__ void __launch_bounds__(NTHREADS) forward_kernel(Problem p) {
 constexpr int TG = 16;
 template <typename AT>
 __global__ void __launch_bounds__(NTHREADS) fwd_coeff_kernel(Problem p, int t_lo, int t_hi, float *A, float *Bv) {
-  extern __shared__ float smem[];
+  extern __shared__ __attribute__((aligned(16))) float smem[];
   const int g = blockIdx.x, b = blockIdx.y, t0 = t_lo + blockIdx.z * TG, bs = p.bs, tid = threadIdx.x;
   const int nt = min(TG, t_hi - t0), tc = t_hi - t_lo;
   float *xs = smem;
@@ -186,7 +202,7 @@ __global__ void __launch_bounds__(NTHREADS) fwd_scan_kernel(Problem p, int t_lo,
 // all of its reads of the state.
 template <typename AT>
 __global__ void __launch_bounds__(NTHREADS) decode_kernel(Problem p) {
-  extern __shared__ float smem[];
+  extern __shared__ __attribute__((aligned(16))) float smem[];
   const int g = blockIdx.x, b0 = blockIdx.y * GT, bs = p.bs, tid = threadIdx.x;
   const int nbat = min(GT, p.B - b0);
   float *xs = smem;
@@ -246,7 +262,7 @@ size_t backward_generic_ws_bytes(int B, int T, int D, int nb) {
 // x, dp, dq.
 template <typename AT>
 __global__ void __launch_bounds__(NTHREADS) bwd_preact_kernel(Problem p, BwdWs w) {
-  extern __shared__ float smem[];
+  extern __shared__ __attribute__((aligned(16))) float smem[];
   const int g = blockIdx.x, b = blockIdx.y, t0 = blockIdx.z * TG, bs = p.bs, tid = threadIdx.x;
   const int nt = min(TG, p.T - t0);
   float *xs = smem;
@@ -348,7 +364,7 @@ __global__ void __launch_bounds__(NTHREADS) bwd_chain_kernel(Problem p, BwdWs w)
 // Pass 2: dx[t][k] += sum_j W_a[g][j][k] dp[t][j] + W_x[g][j][k] dq[t][j]
 template <typename AT>
 __global__ void __launch_bounds__(NTHREADS) bwd_dgrad_kernel(Problem p, BwdWs w) {
-  extern __shared__ float smem[];
+  extern __shared__ __attribute__((aligned(16))) float smem[];
   const int g = blockIdx.x, b = blockIdx.y, t0 = blockIdx.z * GT, bs = p.bs, tid = threadIdx.x;
   const int nt = min(GT, p.T - t0);
   float *dps = smem, *dqs = smem + GT * bs;  // [GT][bs] each

@@ -24,6 +24,16 @@ __device__ __forceinline__ unsigned short f32_to_bf16_bits(float f) {
   u += 0x7fffu + ((u >> 16) & 1u);
   return (unsigned short)(u >> 16);
 }
+// four consecutive elements from a 16-byte (fp32) / 8-byte (bf16) aligned position
+__device__ __forceinline__ void ldf4(const float *p, size_t i, float (&o)[4]) {
+  const float4 v = *(const float4 *)(p + i);
+  o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+}
+__device__ __forceinline__ void ldf4(const bf16 *p, size_t i, float (&o)[4]) {
+  const uint2 v = *(const uint2 *)(p + i);
+  o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
+  o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
+}
 __device__ __forceinline__ void stf(float *p, size_t i, float v) { p[i] = v; }
 __device__ __forceinline__ void stf(bf16 *p, size_t i, float v) { p[i].v = f32_to_bf16_bits(v); }
 
