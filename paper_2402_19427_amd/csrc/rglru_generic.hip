@@ -362,13 +362,14 @@ __global__ void __launch_bounds__(NTHREADS) bwd_chain_kernel(Problem p, BwdWs w)
 }
 
 // Pass 2: dx[t][k] += sum_j W_a[g][j][k] dp[t][j] + W_x[g][j][k] dq[t][j]
-template <typename AT>
+template <typename AT, int ROWS>
 __global__ void __launch_bounds__(NTHREADS) bwd_dgrad_kernel(Problem p, BwdWs w) {
+  constexpr int TR = ROWS;   // steps per workgroup: 16, or 8 for blocks whose two tiles of 16 would not fit LDS
   extern __shared__ __attribute__((aligned(16))) float smem[];
-  const int g = blockIdx.x, b = blockIdx.y, t0 = blockIdx.z * GT, bs = p.bs, tid = threadIdx.x;
-  const int nt = min(GT, p.T - t0);
-  float *dps = smem, *dqs = smem + GT * bs;  // [GT][bs] each
-  for (int idx = tid; idx < GT * bs; idx += NTHREADS) {
+  const int g = blockIdx.x, b = blockIdx.y, t0 = blockIdx.z * TR, bs = p.bs, tid = threadIdx.x;
+  const int nt = min(TR, p.T - t0);
+  float *dps = smem, *dqs = smem + TR * bs;  // [TR][bs] each
+  for (int idx = tid; idx < TR * bs; idx += NTHREADS) {
     const int tt = idx / bs, j = idx - tt * bs;
     const size_t o = ((size_t)b * p.T + t0 + tt) * p.D + g * bs + j;
     dps[idx] = tt < nt ? w.dp[o] : 0.f;
@@ -378,18 +379,41 @@ __global__ void __launch_bounds__(NTHREADS) bwd_dgrad_kernel(Problem p, BwdWs w)
   const AT *Wa = (const AT *)p.W_a + (size_t)g * bs * bs;
   const AT *Wx = (const AT *)p.W_x + (size_t)g * bs * bs;
   for (int k = tid; k < bs; k += NTHREADS) {
-    float acc[GT];
+    float acc[TR];
 #pragma unroll
-    for (int tt = 0; tt < GT; ++tt)
+    for (int tt = 0; tt < TR; ++tt)
       acc[tt] = tt < nt ? w.dx[((size_t)b * p.T + t0 + tt) * p.D + g * bs + k] : 0.f;
-    for (int j = 0; j < bs; ++j) {
+    int j = 0;
+    // four gate outputs at a time where the rows allow it: one 16-byte LDS read per row and array
+    // (the same products in the same order as one by one)
+    if ((bs & 3) == 0) {
+      for (; j < bs; j += 4) {
+        float wa[4], wx[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          wa[e] = ldf(Wa, (size_t)(j + e) * bs + k);
+          wx[e] = ldf(Wx, (size_t)(j + e) * bs + k);
+        }
+#pragma unroll
+        for (int tt = 0; tt < TR; ++tt) {
+          const float4 dp4 = *(const float4 *)(dps + tt * bs + j), dq4 = *(const float4 *)(dqs + tt * bs + j);
+          float a = acc[tt];
+          a = fmaf(wa[0], dp4.x, fmaf(wx[0], dq4.x, a));
+          a = fmaf(wa[1], dp4.y, fmaf(wx[1], dq4.y, a));
+          a = fmaf(wa[2], dp4.z, fmaf(wx[2], dq4.z, a));
+          a = fmaf(wa[3], dp4.w, fmaf(wx[3], dq4.w, a));
+          acc[tt] = a;
+        }
+      }
+    }
+    for (; j < bs; ++j) {
       const float wa = ldf(Wa, (size_t)j * bs + k), wx = ldf(Wx, (size_t)j * bs + k);
 #pragma unroll
-      for (int tt = 0; tt < GT; ++tt)
+      for (int tt = 0; tt < TR; ++tt)
         acc[tt] = fmaf(wa, dps[tt * bs + j], fmaf(wx, dqs[tt * bs + j], acc[tt]));
     }
 #pragma unroll
-    for (int tt = 0; tt < GT; ++tt)
+    for (int tt = 0; tt < TR; ++tt)
       if (tt < nt) w.dx[((size_t)b * p.T + t0 + tt) * p.D + g * bs + k] = acc[tt];
   }
 }
@@ -622,7 +646,9 @@ static hipError_t backward_generic_t(const Problem &p, hipStream_t s, bool with_
   const size_t lds = generic_lds_bytes(p.bs);
   hipError_t e = allow_lds(bwd_preact_kernel<AT>, (size_t)TG * p.bs * sizeof(float));
   if (e != hipSuccess) return e;
-  e = allow_lds(bwd_dgrad_kernel<AT>, lds);
+  const int dg_rows = p.bs <= 1024 ? TG : GT;
+  const size_t lds_dg = (size_t)2 * dg_rows * p.bs * sizeof(float);
+  e = dg_rows == TG ? allow_lds(bwd_dgrad_kernel<AT, TG>, lds_dg) : allow_lds(bwd_dgrad_kernel<AT, GT>, lds_dg);
   if (e != hipSuccess) return e;
   const size_t n = (size_t)p.B * p.T * p.D;
   const int dblocks = (p.D + NTHREADS - 1) / NTHREADS;
@@ -642,10 +668,13 @@ static hipError_t backward_generic_t(const Problem &p, hipStream_t s, bool with_
                      p.D, gate_outs);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   // dgrad: time tiles in gridDim.z (<= 65535), sequences in y
-  const int ntile = (p.T + GT - 1) / GT;
+  const int ntile = (p.T + dg_rows - 1) / dg_rows;
   if (ntile > 65535 || p.B > 65535) return hipErrorInvalidConfiguration;
   if (with_dgrad) {
-    hipLaunchKernelGGL(bwd_dgrad_kernel<AT>, dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds, s, p, w);
+    if (dg_rows == TG)
+      hipLaunchKernelGGL((bwd_dgrad_kernel<AT, TG>), dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds_dg, s, p, w);
+    else
+      hipLaunchKernelGGL((bwd_dgrad_kernel<AT, GT>), dim3(p.nb, p.B, ntile), dim3(NTHREADS), lds_dg, s, p, w);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (with_du) {
