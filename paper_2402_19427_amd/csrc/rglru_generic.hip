@@ -483,58 +483,85 @@ __global__ void __launch_bounds__(NTHREADS) reduce_parts_kernel(const float *par
   out.p[r][d] = s;
 }
 
-// Pass 4: dW_a[g][j][k] = sum_{b,t} dp[b,t,j] x[b,t,k], dW_x likewise with dq. One workgroup
-// per 32x32 output tile of one block, 16x16 threads with 2x2 outputs each, rows streamed
-// through LDS 32 at a time.
-__global__ void __launch_bounds__(NTHREADS) bwd_wgrad_kernel(Problem p, BwdWs w) {
-  __shared__ float xs[32][33], ps[32][33], qs[32][33];
-  const int g = blockIdx.x, j0 = blockIdx.y * 32, k0 = blockIdx.z * 32, bs = p.bs;
+// Pass 4: dW_a[g][j][k] = sum_{b,t} dp[b,t,j] x[b,t,k], dW_x likewise with dq. One workgroup per
+// 64x64 output tile of one block and slice of the B*T rows, 16x16 threads with 4x4 outputs each
+// (12 LDS reads per 32 products), rows streamed through LDS 32 at a time; the chunks of 32 rows
+// are added up with compensation. With one slice the sums go straight to dW; otherwise to
+// part[slice][gate][nb][bs][bs], which wgrad_reduce_kernel adds up in a fixed order.
+__global__ void __launch_bounds__(NTHREADS) bwd_wgrad_kernel(Problem p, BwdWs w, float *part, int rows_per, int tiles) {
+  __shared__ float xs[32][65], ps[32][65], qs[32][65];
+  const int g = blockIdx.x, j0 = (blockIdx.y / tiles) * 64, k0 = (blockIdx.y % tiles) * 64, bs = p.bs;
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-  float aa[2][2] = {{0.f, 0.f}, {0.f, 0.f}}, ax[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
-  float ca[2][2] = {{0.f, 0.f}, {0.f, 0.f}}, cx[2][2] = {{0.f, 0.f}, {0.f, 0.f}};   // compensation terms
+  float aa[4][4], ax[4][4], ca[4][4], cx[4][4];   // sums and their compensation terms
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) aa[a][c] = ax[a][c] = ca[a][c] = cx[a][c] = 0.f;
   const size_t rows = (size_t)p.B * p.T;
-  for (size_t r0 = 0; r0 < rows; r0 += 32) {
+  const size_t r_lo = (size_t)blockIdx.z * rows_per, r_hi = r_lo + rows_per < rows ? r_lo + rows_per : rows;
+  for (size_t r0 = r_lo; r0 < r_hi; r0 += 32) {
     __syncthreads();
-    for (int idx = threadIdx.x; idx < 32 * 32; idx += NTHREADS) {
-      const int rr = idx >> 5, cc = idx & 31;
+    for (int idx = threadIdx.x; idx < 32 * 64; idx += NTHREADS) {
+      const int rr = idx >> 6, cc = idx & 63;
       const size_t row = r0 + rr;
-      const bool okr = row < rows;
+      const bool okr = row < r_hi;
       const size_t base = row * p.D + (size_t)g * bs;
       xs[rr][cc] = (okr && k0 + cc < bs) ? w.x[base + k0 + cc] : 0.f;
       ps[rr][cc] = (okr && j0 + cc < bs) ? w.dp[base + j0 + cc] : 0.f;
       qs[rr][cc] = (okr && j0 + cc < bs) ? w.dq[base + j0 + cc] : 0.f;
     }
     __syncthreads();
-    // the 32 rows of the chunk as plain sums, the chunks added up with compensation
-    float la[2][2] = {{0.f, 0.f}, {0.f, 0.f}}, lx[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
-#pragma unroll 8
+    float la[4][4], lx[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) la[a][c] = lx[a][c] = 0.f;
+#pragma unroll 4
     for (int rr = 0; rr < 32; ++rr) {
-      const float x0 = xs[rr][tx], x1 = xs[rr][tx + 16];
-      const float p0 = ps[rr][ty], p1 = ps[rr][ty + 16];
-      const float q0 = qs[rr][ty], q1 = qs[rr][ty + 16];
-      la[0][0] = fmaf(p0, x0, la[0][0]); la[0][1] = fmaf(p0, x1, la[0][1]);
-      la[1][0] = fmaf(p1, x0, la[1][0]); la[1][1] = fmaf(p1, x1, la[1][1]);
-      lx[0][0] = fmaf(q0, x0, lx[0][0]); lx[0][1] = fmaf(q0, x1, lx[0][1]);
-      lx[1][0] = fmaf(q1, x0, lx[1][0]); lx[1][1] = fmaf(q1, x1, lx[1][1]);
+      float xv[4], pv[4], qv[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        xv[e] = xs[rr][tx + 16 * e];
+        pv[e] = ps[rr][ty + 16 * e];
+        qv[e] = qs[rr][ty + 16 * e];
+      }
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          la[a][c] = fmaf(pv[a], xv[c], la[a][c]);
+          lx[a][c] = fmaf(qv[a], xv[c], lx[a][c]);
+        }
     }
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < 4; ++a)
 #pragma unroll
-      for (int c = 0; c < 2; ++c) {
+      for (int c = 0; c < 4; ++c) {
         comp_add(aa[a][c], ca[a][c], la[a][c]);
         comp_add(ax[a][c], cx[a][c], lx[a][c]);
       }
   }
+  const size_t per_gate = (size_t)p.nb * bs * bs;
+  float *oa = part ? part + (size_t)blockIdx.z * 2 * per_gate : p.g.dW_a;
+  float *ox = part ? oa + per_gate : p.g.dW_x;
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < 4; ++a)
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
+    for (int c = 0; c < 4; ++c) {
       const int j = j0 + ty + 16 * a, k = k0 + tx + 16 * c;
       if (j < bs && k < bs) {
-        p.g.dW_a[((size_t)g * bs + j) * bs + k] = aa[a][c];
-        p.g.dW_x[((size_t)g * bs + j) * bs + k] = ax[a][c];
+        oa[((size_t)g * bs + j) * bs + k] = aa[a][c];
+        ox[((size_t)g * bs + j) * bs + k] = ax[a][c];
       }
     }
+}
+__global__ void __launch_bounds__(NTHREADS) wgrad_reduce_kernel(Problem p, const float *part, int S) {
+  const size_t per_gate = (size_t)p.nb * p.bs * p.bs, i = (size_t)blockIdx.x * NTHREADS + threadIdx.x;
+  if (i >= 2 * per_gate) return;
+  float sum = 0.f, comp = 0.f;
+  for (int s = 0; s < S; ++s) comp_add(sum, comp, part[(size_t)s * 2 * per_gate + i]);
+  if (i < per_gate) p.g.dW_a[i] = sum;
+  else p.g.dW_x[i - per_gate] = sum;
 }
 
 // ------------------------------------------------------------------------- launchers
@@ -692,9 +719,27 @@ static hipError_t backward_generic_t(const Problem &p, hipStream_t s, bool with_
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (!with_wgrad) return hipSuccess;
-  const int tiles = (p.bs + 31) / 32;
-  hipLaunchKernelGGL(bwd_wgrad_kernel, dim3(p.nb, tiles, tiles), dim3(NTHREADS), 0, s, p, w);
-  return hipGetLastError();
+  // slices of the rows: enough workgroups for the chip, none shorter than 128 rows; their partial
+  // sums go where dx was (every reader of dx has run by now) as far as that array reaches
+  const int tiles = (p.bs + 63) / 64;
+  const size_t rows = (size_t)p.B * p.T, wg1 = (size_t)p.nb * tiles * tiles;
+  size_t S = (1024 + wg1 - 1) / wg1;
+  if (S > rows / 128) S = rows / 128;
+  if (S > n / (2 * (size_t)p.D * p.bs)) S = n / (2 * (size_t)p.D * p.bs);   // S partial copies of dW_a, dW_x in n floats
+  if (S < 1) S = 1;
+  if (S > 65535 || (size_t)tiles * tiles > 65535) return hipErrorInvalidConfiguration;
+  const int rows_per = (int)(((rows + S - 1) / S + 31) / 32 * 32);
+  float *part = S > 1 ? w.dx : nullptr;
+  hipLaunchKernelGGL(bwd_wgrad_kernel, dim3(p.nb, tiles * tiles, (unsigned)S), dim3(NTHREADS), 0, s, p, w, part, rows_per,
+                     tiles);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (S > 1) {
+    const size_t cnt = 2 * (size_t)p.nb * p.bs * p.bs;
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((cnt + NTHREADS - 1) / NTHREADS)), dim3(NTHREADS), 0, s, p,
+                       (const float *)part, (int)S);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_backward_generic(const Problem &p, bool bf, hipStream_t s) {
