@@ -28,6 +28,7 @@ __device__ __forceinline__ void gate_rows(const Problem &p, int g, int j, const 
   // four inputs at a time where the rows allow it: one 16-byte LDS read per row and four inputs,
   // the weights as one vector load (the same products in the same order as one by one)
   if ((bs & 3) == 0 && (((uintptr_t)p.W_a | (uintptr_t)p.W_x) & 15) == 0) {
+#pragma unroll 4   // (the loads of four steps in flight)
     for (; k < bs; k += 4) {
       float a4[4], x4[4];
       ldf4(wa, k, a4);
