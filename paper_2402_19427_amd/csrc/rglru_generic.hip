@@ -706,8 +706,12 @@ static hipError_t backward_generic_t(const Problem &p, hipStream_t s, bool with_
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (with_du) {
-    hipLaunchKernelGGL(bwd_conv_input_kernel<AT>, dim3(grid_1d(n)), dim3(NTHREADS), 0, s, p, w);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (conv_adjoint_rows_applies(p, sizeof(AT) == 2)) {   // 4 channels x 8 steps per thread, vector accesses
+      if ((e = launch_conv_adjoint_rows(p, w.dx, s)) != hipSuccess) return e;
+    } else {
+      hipLaunchKernelGGL(bwd_conv_input_kernel<AT>, dim3(grid_1d(n)), dim3(NTHREADS), 0, s, p, w);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
   }
   if (p.g.dconv_w) {   // (absent without a Conv1D)
     if (w.nchunk > 65535) return hipErrorInvalidConfiguration;

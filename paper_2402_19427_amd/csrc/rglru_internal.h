@@ -119,6 +119,9 @@ size_t backward_generic_ws_bytes(int B, int T, int D, int nb);
 hipError_t launch_backward_generic_tail(const Problem &p, bool bf, hipStream_t s, bool with_dgrad = true,
                                         bool with_wgrad = true, bool with_du = true);
 void backward_generic_arrays(const Problem &p, float **x, float **dp, float **dq, float **dx, float **partA);
+// du from an fp32 dx [B][T][D] by a streaming kernel (bf16 storage, no document boundaries, aligned)
+bool conv_adjoint_rows_applies(const Problem &p, bool bf);
+hipError_t launch_conv_adjoint_rows(const Problem &p, const float *dx, hipStream_t s);
 size_t generic_lds_bytes(int bs);
 
 // Complex-gated variant (Appendix B): D real channels as D / 2 complex ones, Problem.bs = complex

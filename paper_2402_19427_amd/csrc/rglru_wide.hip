@@ -782,9 +782,10 @@ __global__ void __launch_bounds__(256) conv_adjoint_rows_kernel(ConvAdjArgs a) {
   }
   const float *dx = a.dx + (size_t)b * T * D + d0;
 #pragma unroll
-  for (int n = 0; n < CR + 3; ++n) {
+  for (int n = 0; n < CR + 3; ++n) {   // (no load under a condition: rows past the end re-read the last row)
     const int t = t0 + n;
-    in[n] = t < T ? *(const f32x4 *)(dx + (size_t)t * D) : f32x4{0.f, 0.f, 0.f, 0.f};
+    in[n] = *(const f32x4 *)(dx + (size_t)(t < T ? t : T - 1) * D);
+    if (t >= T) in[n] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 #pragma unroll
   for (int r = 0; r < CR; ++r) {
@@ -800,6 +801,22 @@ __global__ void __launch_bounds__(256) conv_adjoint_rows_kernel(ConvAdjArgs a) {
     *(uint2 *)(a.du + ((size_t)b * T + t0 + r) * D + d0) = o;
   }
 }
+}  // namespace
+// du from the fp32 dx with the streaming kernel above: bf16 storage, rows that hold one document each,
+// a width that is a multiple of 4 and 8-byte / 16-byte aligned du / taps; false if it does not apply
+bool conv_adjoint_rows_applies(const Problem &p, bool bf) {
+  return bf && !p.reset && p.D % 4 == 0 && p.T >= 1 && (uintptr_t)p.du % 8 == 0 && (uintptr_t)p.conv_w % 16 == 0;
+}
+hipError_t launch_conv_adjoint_rows(const Problem &p, const float *dx, hipStream_t s) {
+  KernelTimer kt("conv_adjoint_rows_kernel", s);
+  ConvAdjArgs ca;
+  ca.dx = dx; ca.conv_w = p.conv_w; ca.du = (unsigned short *)p.du;
+  ca.B = p.B; ca.T = p.T; ca.D = p.D;
+  const size_t total = (size_t)p.B * ((p.T + CR - 1) / CR) * (p.D / 4);
+  hipLaunchKernelGGL(conv_adjoint_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, ca);
+  return hipGetLastError();
+}
+namespace {
 
 // bf16 -> half precision, n elements (gate weights: the products run on the f16 form of the MFMA
 // with x in half precision; exact for weights from 6.1e-5 up to 65504, smaller ones round with
@@ -1280,19 +1297,8 @@ hipError_t launch_backward_wide(const Problem &p_in, hipStream_t s) {
     hipLaunchKernelGGL(gates_wide_kernel<MODE_WGRAD>, dim3(wg.ntiles, p.nb * wg.nob), dim3(NTHR), W_LDS, s, wg);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  const bool own_du = ((uintptr_t)p.du % 8 == 0);
-  if (own_du) {
-    KernelTimer kt("conv_adjoint_rows_kernel", s);
-    ConvAdjArgs ca;
-    float *gx, *gdp, *gdq, *gdx, *gpartA;
-    backward_generic_arrays(p, &gx, &gdp, &gdq, &gdx, &gpartA);
-    ca.dx = gdx; ca.conv_w = p.conv_w; ca.du = (unsigned short *)p.du;
-    ca.B = p.B; ca.T = p.T; ca.D = p.D;
-    const size_t total = (size_t)p.B * ((p.T + CR - 1) / CR) * (p.D / 4);
-    hipLaunchKernelGGL(conv_adjoint_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, ca);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-  }
-  if ((e = launch_backward_generic_tail(p, true, s, false, !mfma_wgrad, !own_du)) != hipSuccess) return e;
+  // (du: the tail takes the streaming kernel below where it applies)
+  if ((e = launch_backward_generic_tail(p, true, s, false, !mfma_wgrad, true)) != hipSuccess) return e;
   {
     KernelTimer kt("grad_scale_kernels", s);
     hipLaunchKernelGGL(scale_bf16_kernel, dim3(stream_grid(N)), dim3(256), 0, s, (const unsigned short *)p.du,
