@@ -19,6 +19,8 @@ SHAPES = [
     (2, 130, 512, 2, "bf16"),    # hs = 128
     (2, 100, 640, 2, "bf16"),    # hs = 160: ten column blocks of the matrix-core passes
     (3, 70, 192, 2, "bf16"),     # hs = 48: a partial column block
+    (2, 70, 384, 2, "bf16"),     # hs = 96: the fused forward with one of its four waves idle
+    (1, 200, 256, 2, "bf16"),    # hs = 64: ... with two
     (1, 300, 1024, 1, "bf16"),   # hs = 512: more outputs than threads
     (4, 20, 24, 12, "bf16"),     # hs = 1: per-channel gates
 ]
