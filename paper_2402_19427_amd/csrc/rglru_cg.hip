@@ -302,9 +302,11 @@ static bool cg_mfma_ok(const Problem &p) {
 // channel for 16 consecutive steps and runs the complex recurrence twice - from zero for its run's
 // aggregate (product of a~_t, end state), which the two lane halves exchange, then from the true
 // incoming state, writing y. The state stays in registers between tiles.
-// (A variant that also parks what the backward wants - x, the pre-activations, a~_t, fp32 states -
-// ran out of registers and measured slower than the two passes; the backward recomputes with those.)
-__global__ void __launch_bounds__(NTHREADS) cg_fused_kernel(Problem p) {
+// KEEP (the backward's recomputation): y is the fp32 state array, and x, the pre-activations and
+// a~_t are parked as cg_coeff_mfma_kernel<true> parks them - each stored where it is produced, so
+// that nothing more stays live.
+template <typename OT, bool KEEP>
+__global__ void __launch_bounds__(NTHREADS) cg_fused_kernel(Problem p, float *xk, float *pq, float2 *A) {
   extern __shared__ __attribute__((aligned(16))) float smem[];
   const int g = blockIdx.x, b = blockIdx.y, hs = p.bs, H = p.D / 2, nin = 2 * hs, xsh = nin + 8;
   float *xf = smem;
@@ -351,6 +353,21 @@ __global__ void __launch_bounds__(NTHREADS) cg_fused_kernel(Problem p) {
   const float l2cs = -p.c * softplus_f(-p.Lambda[h]) * mfma::LOG2E, rev = p.c * p.theta[h] * 0.15915494309189535f;
   float sr = p.h0 ? p.h0[(size_t)b * p.D + h] : 0.f, si = p.h0 ? p.h0[(size_t)b * p.D + H + h] : 0.f;   // state entering the tile
 
+  // parked arrays of this sequence as buffers (KEEP): per-lane offset = (first step of the lane's run, channel)
+  const unsigned seq_elems = (unsigned)T * (unsigned)H;
+  const __amdgpu_buffer_rsrc_t p_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      mfma::uniform_ptr(KEEP ? (void *)(pq + (size_t)b * seq_elems) : (void *)p.y), 0, KEEP ? seq_elems * 4u : 0u, 0x00020000);
+  const __amdgpu_buffer_rsrc_t q_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      mfma::uniform_ptr(KEEP ? (void *)(pq + ((size_t)p.B + b) * seq_elems) : (void *)p.y), 0, KEEP ? seq_elems * 4u : 0u, 0x00020000);
+  const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      mfma::uniform_ptr(KEEP ? (void *)(A + (size_t)b * seq_elems) : (void *)p.y), 0, KEEP ? seq_elems * 8u : 0u, 0x00020000);
+  const unsigned k_voff = ((unsigned)(hf * 16) * (unsigned)H + (unsigned)h) * 4u;
+  const unsigned row_elems = (unsigned)T * (unsigned)p.D;
+  const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      mfma::uniform_ptr(KEEP ? (void *)(xk + (size_t)b * row_elems) : (void *)p.y), 0, KEEP ? row_elems * 4u : 0u, 0x00020000);
+  const __amdgpu_buffer_rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      mfma::uniform_ptr((OT *)p.y + (size_t)b * row_elems), 0, row_elems * (unsigned)sizeof(OT), 0x00020000);
+  const unsigned y_voff = ((unsigned)(hf * 16) * (unsigned)p.D + (unsigned)h) * (unsigned)sizeof(OT);
   if (ntile > 0) fetch(0);
   for (int tile = 0; tile < ntile; ++tile) {
     const int t0 = tile * MT, nt = min(MT, T - t0);
@@ -363,6 +380,8 @@ __global__ void __launch_bounds__(NTHREADS) cg_fused_kernel(Problem p) {
         const _Float16 vh = (_Float16)v;
         xh[tt * xsh + k] = vh;
         xl[tt * xsh + k] = (_Float16)(v - (float)vh);
+        if (KEEP && tt < nt)
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), x_rsrc, (unsigned)dcol * 4u, (unsigned)(t0 + tt) * (unsigned)p.D * 4u, 0);
         u3 = u2;
         u2 = u1;
         u1 = u0;
@@ -404,6 +423,10 @@ __global__ void __launch_bounds__(NTHREADS) cg_fused_kernel(Problem p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int tt = hf * 16 + r;
+        if (KEEP && tt < nt) {   // (scalar row offsets: no address registers per step)
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(accp[r]), p_rsrc, k_voff, (unsigned)(t0 + r) * (unsigned)H * 4u, 0);
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(accq[r]), q_rsrc, k_voff, (unsigned)(t0 + r) * (unsigned)H * 4u, 0);
+        }
         const float gr = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-accp[r] * mfma::LOG2E));
         const float gi = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-accq[r] * mfma::LOG2E));
         const float l2 = l2cs * gr, mod = __builtin_amdgcn_exp2f(l2);
@@ -412,6 +435,10 @@ __global__ void __launch_bounds__(NTHREADS) cg_fused_kernel(Problem p) {
         float br = gain * xf[tt * nin + jj], bi = gain * xf[tt * nin + hs + jj];
         if (tt >= nt) {   // past the end of the sequence: the state passes through
           ar = 1.f; ai = 0.f; br = 0.f; bi = 0.f;
+        } else if (KEEP) {
+          typedef unsigned u32x2k __attribute__((ext_vector_type(2)));
+          const u32x2k av = {__float_as_uint(ar), __float_as_uint(ai)};
+          __builtin_amdgcn_raw_buffer_store_b64(av, a_rsrc, 2 * k_voff, (unsigned)(t0 + r) * (unsigned)H * 8u, 0);
         }
         car[r] = ar; cai[r] = ai; cbr[r] = br; cbi[r] = bi;
         const float nHr = fmaf(ar, Hr, fmaf(-ai, Hi, br)), nHi = fmaf(ar, Hi, fmaf(ai, Hr, bi));
@@ -426,15 +453,20 @@ __global__ void __launch_bounds__(NTHREADS) cg_fused_kernel(Problem p) {
       const float mr = fmaf(Plr, sr, fmaf(-Pli, si, Hlr)), mi = fmaf(Plr, si, fmaf(Pli, sr, Hli));
       const float er = fmaf(Pur, mr, fmaf(-Pui, mi, Hur)), ei = fmaf(Pur, mi, fmaf(Pui, mr, Hui));
       float hr = hf ? mr : sr, hi = hf ? mi : si;   // state entering this lane's run
-      bf16 *yo = (bf16 *)p.y + ((size_t)b * T + t0 + hf * 16) * p.D + h;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const float nr = fmaf(car[r], hr, fmaf(-cai[r], hi, cbr[r])), ni = fmaf(car[r], hi, fmaf(cai[r], hr, cbi[r]));
         hr = nr;
         hi = ni;
         if (hf * 16 + r < nt && jj < hs) {
-          stf(yo, (size_t)r * p.D, hr);
-          stf(yo, (size_t)r * p.D + H, hi);
+          const unsigned so = (unsigned)(t0 + r) * (unsigned)p.D * (unsigned)sizeof(OT);
+          if (sizeof(OT) == 4) {
+            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hr), y_rsrc, y_voff, so, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hi), y_rsrc, y_voff + (unsigned)H * 4u, so, 0);
+          } else {
+            __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16_bits(hr), y_rsrc, y_voff, so, 0);
+            __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16_bits(hi), y_rsrc, y_voff + (unsigned)H * 2u, so, 0);
+          }
         }
       }
       sr = er;
@@ -451,13 +483,14 @@ __global__ void __launch_bounds__(NTHREADS) cg_fused_kernel(Problem p) {
 static bool cg_fused_ok(const Problem &p) {
   return p.bs % 32 == 0 && p.bs <= 128 && ((uintptr_t)p.W_a % 16) == 0 && ((uintptr_t)p.W_x % 16) == 0 && p.B <= 65535;
 }
-static hipError_t launch_cg_fused(const Problem &p, hipStream_t s) {
+template <typename OT, bool KEEP>
+static hipError_t launch_cg_fused(const Problem &p, float *xk, float *pq, float2 *A, hipStream_t s) {
   const size_t lds = (size_t)MT * 2 * p.bs * 4 + (size_t)2 * MT * (2 * p.bs + 8) * 2;
   if (lds > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void *)cg_fused_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = hipFuncSetAttribute((const void *)cg_fused_kernel<OT, KEEP>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(cg_fused_kernel, dim3(p.nb, p.B), dim3(NTHREADS), lds, s, p);
+  hipLaunchKernelGGL((cg_fused_kernel<OT, KEEP>), dim3(p.nb, p.B), dim3(NTHREADS), lds, s, p, xk, pq, A);
   return hipGetLastError();
 }
 template <typename OT>
@@ -1048,8 +1081,14 @@ hipError_t cg_backward_t(const Problem &p, hipStream_t s) {
     Problem f = p;
     f.y = hs32;
     f.hT = nullptr;
-    if ((e = cg_forward_two_pass<AT, float, true>(f, p.T, (float2 *)w.dp, (float2 *)w.dq, nullptr, s, w.x, pq)) != hipSuccess)
-      return e;
+    // (with enough (gate block, sequence) pairs for the chip the fused kernel does it in one pass:
+    // 6.9 -> 6.15 ms for the whole backward at 256 pairs; at 80 pairs the two passes, which are
+    // parallel over time, are 2 % ahead. It parks a~_t but no b~_t: nothing reads them.)
+    if (sizeof(AT) == 2 && cg_fused_ok(p) && p.B * p.nb >= 160)
+      e = launch_cg_fused<float, true>(f, w.x, pq, (float2 *)w.dp, s);
+    else
+      e = cg_forward_two_pass<AT, float, true>(f, p.T, (float2 *)w.dp, (float2 *)w.dq, nullptr, s, w.x, pq);
+    if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(cg_adj_scan_kernel<AT>, dim3((unsigned)(((size_t)p.B * H + NTHREADS - 1) / NTHREADS)),
                      dim3(NTHREADS), 0, s, p, adpq, delta);
@@ -1110,7 +1149,7 @@ size_t cg_backward_ws_bytes(int B, int T, int D, int nb) {   // ... + the recomp
 }
 
 hipError_t launch_cg_forward(const Problem &p, bool bf, hipStream_t s) {
-  if (bf && cg_fused_ok(p)) return launch_cg_fused(p, s);
+  if (bf && cg_fused_ok(p)) return launch_cg_fused<bf16, false>(p, nullptr, nullptr, nullptr, s);
   // with the optional scratch (the real layer's layout: a 256-byte cell, the state between chunks,
   // two coefficient arrays for a chunk of steps) and more than one tile of steps: two passes
   if (p.ws && p.T > GT && ((uintptr_t)p.ws % 256) == 0 && p.ws_bytes >= forward_generic_ws_bytes(p.B, p.T, p.D)) {

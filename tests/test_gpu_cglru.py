@@ -21,6 +21,7 @@ SHAPES = [
     (3, 70, 192, 2, "bf16"),     # hs = 48: a partial column block
     (2, 70, 384, 2, "bf16"),     # hs = 96: the fused forward with one of its four waves idle
     (1, 200, 256, 2, "bf16"),    # hs = 64: ... with two
+    (40, 45, 512, 4, "bf16"),    # 160 (gate block, sequence) pairs: the backward recomputes with the fused kernel
     (1, 300, 1024, 1, "bf16"),   # hs = 512: more outputs than threads
     (4, 20, 24, 12, "bf16"),     # hs = 1: per-channel gates
 ]
