@@ -429,6 +429,7 @@ bwd_gates_kernel(BwdArgs a) {
               __builtin_amdgcn_s_sleep(2);
               rec[i] = peek(slot);
             }
+            if (spins < SPIN_LIMIT) spins = 0;   // the limit is per wait; an expired wait stays expired
             const float mine = __uint_as_float((unsigned)rec[i]), other = __shfl_xor(mine, 32);
             e_in = fmaf(hf ? other : mine, e_in, hf ? mine : other);
           }

@@ -245,6 +245,7 @@ scan_tiled_kernel(ScanArgs a) {
           __builtin_amdgcn_s_sleep(1);
           rec[s] = peek(slot);
         }
+        if (spins < SPIN_LIMIT) spins = 0;   // the limit is per wait; an expired wait stays expired
         const float mine = __uint_as_float((unsigned)rec[s]), other = __shfl_xor(mine, 32);
         h = fmaf(hf ? other : mine, h, hf ? mine : other);
       }
