@@ -287,6 +287,7 @@ BWD_SHAPES = [
     (1, 1, 256, 1, "bf16"),       # MFMA path, single step
     (2, 31, 256, 1, "bf16"),      # MFMA path, one partial tile
     (1, 700, 256, 1, "bf16"),     # MFMA path, one unit in 16 time slices
+    (1, 13000, 256, 1, "bf16"),   # ... over a long sequence: 26 rounds of the slices, the record rings wrap (forward: windows)
     (33, 70, 1024, 4, "bf16"),    # MFMA path, 132 units, no slicing
     (8, 300, 2048, 8, "bf16"),    # MFMA path, 64 units x 4 slices
 ]
