@@ -56,6 +56,26 @@ def test_c2_long_sequence_forward_full_size():
     run_forward_full("C2", [(0, 0), (0, 9)])
 
 
+def test_long_prompt_with_sixteen_blocks_forward_in_interleaved_slices():
+    """One sequence of 16384 steps at width 4096 with 16 gate blocks: more units than the windows of
+    a single prompt take, so all 256 compute units run it as 16 interleaved time slices per unit,
+    32 rounds of them. Two of the blocks against the oracle, every output finite."""
+    import paper_2402_19427_amd.runner as rn
+    B, T, D, nb, act = 1, 16384, 4096, 16, "bf16"
+    inp = gen.make_inputs(B, T, D, nb, act=act, seed=41, h0=True)
+    dp = rn.DeviceProblem(inp, B, T, D, nb, act)
+    y, hT, st = dp.forward(rn.to_device(inp["u"], act), h0=rn.to_device(inp["h0"], "f32"))
+    y_h, hT_h = rn.to_host(y), rn.to_host(hT)
+    oracle.set_threads(1)
+    for g in (0, 11):
+        sl, par = block_params(inp, g, D // nb)
+        y_ref, hT_ref, _ = oracle.forward(np.asarray(inp["u"][:, :, sl], np.float64), *par,
+                                          h0=np.asarray(inp["h0"][:, sl], np.float64))
+        assert gen.rel_err(y_h[:, :, sl], y_ref) < TOL, g
+        assert gen.rel_err(hT_h[:, sl], hT_ref) < TOL, g
+    assert np.isfinite(y_h).all() and np.isfinite(hT_h).all()
+
+
 def run_train_full(name, g, y_rows, decode=False):
     """forward (+ one decode step continuing it) + backward at the workload's full size; every
     sequence of gate block g goes through the oracle (parameter gradients sum over the batch)."""
